@@ -1,0 +1,165 @@
+"""ctypes front end of the CPU oracle (moc_oracle.cpp, moc_bruteforce.cpp,
+moc_exhaustive.cpp).
+
+TEST INFRASTRUCTURE ONLY.  Imported by tests/, by the smoke check and by the
+CPU-baseline leg of the benchmark; never by the product path, and it imports
+nothing of the HIP library.  The oracle evaluates Eq. (1)-(8) of Section 2.1
+of the paper (arXiv 2304.14463) exactly as defined; see moc_oracle.cpp for
+the readings taken and the pins.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SOURCES = ["moc_oracle.cpp", "moc_bruteforce.cpp", "moc_exhaustive.cpp"]
+_LIB_PATH = os.path.join(_HERE, "liboracle.so")
+_lib = None
+
+FIELDS = ("peak", "duration", "violations", "feasible", "v_form", "v_first", "v_order", "v_start", "v_prec")
+
+
+def build(force: bool = True) -> str:
+    """Compile the oracle with g++ (host only)."""
+    srcs = [os.path.join(_HERE, s) for s in _SOURCES]
+    if not force and os.path.exists(_LIB_PATH) and all(
+            os.path.getmtime(_LIB_PATH) >= os.path.getmtime(s) for s in srcs):
+        return _LIB_PATH
+    cmd = ["g++", "-O2", "-std=c++17", "-shared", "-fPIC", "-pthread", "-Wall", "-o", _LIB_PATH] + srcs
+    subprocess.run(cmd, check=True)
+    return _LIB_PATH
+
+
+def _p(arr, ctype):
+    return arr.ctypes.data_as(ctypes.POINTER(ctype))
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build(force=False)
+        _lib = ctypes.CDLL(_LIB_PATH)
+        _lib.orc_result_fields.restype = ctypes.c_int
+        _lib.bf_enumerate.restype = ctypes.c_int64
+        _lib.bf_simulate.restype = ctypes.c_int
+        assert _lib.orc_result_fields() == len(FIELDS)
+    return _lib
+
+
+def _graph_args(g):
+    in_ptr = np.ascontiguousarray(g.in_ptr, dtype=np.int32)
+    in_idx = np.ascontiguousarray(g.in_idx, dtype=np.int32)
+    size = np.ascontiguousarray(g.size, dtype=np.int32)
+    dur = np.ascontiguousarray(g.dur, dtype=np.int32)
+    keep = (in_ptr, in_idx, size, dur)
+    args = (ctypes.c_int32(g.n), _p(in_ptr, ctypes.c_int32), _p(in_idx, ctypes.c_int32),
+            _p(size, ctypes.c_int32), _p(dur, ctypes.c_int32))
+    return keep, args
+
+
+def _cand(x, dtype, K):
+    x = np.ascontiguousarray(x, dtype=dtype)
+    return x.reshape(-1, K)
+
+
+def evaluate(g, budget, C, starts, ends, active, T=None):
+    """Evaluate candidates [B][n*C]; returns int64 [B][9], columns = FIELDS."""
+    K = g.n * C
+    T = K if T is None else T
+    s, e, a = _cand(starts, np.int32, K), _cand(ends, np.int32, K), _cand(active, np.uint8, K)
+    B = s.shape[0]
+    out = np.zeros((B, len(FIELDS)), dtype=np.int64)
+    keep, ga = _graph_args(g)
+    lib().orc_eval(*ga, ctypes.c_int64(budget), ctypes.c_int32(C), ctypes.c_int32(T), ctypes.c_int64(B),
+                   _p(s, ctypes.c_int32), _p(e, ctypes.c_int32), _p(a, ctypes.c_uint8), _p(out, ctypes.c_int64))
+    return out
+
+
+def profile(g, budget, C, starts, ends, active, T=None):
+    """One candidate: (result row, memory in use at every position)."""
+    K = g.n * C
+    T = K if T is None else T
+    s, e, a = _cand(starts, np.int32, K), _cand(ends, np.int32, K), _cand(active, np.uint8, K)
+    assert s.shape[0] == 1
+    out = np.zeros(len(FIELDS), dtype=np.int64)
+    prof = np.zeros(T, dtype=np.int64)
+    keep, ga = _graph_args(g)
+    lib().orc_profile(*ga, ctypes.c_int64(budget), ctypes.c_int32(C), ctypes.c_int32(T),
+                      _p(s, ctypes.c_int32), _p(e, ctypes.c_int32), _p(a, ctypes.c_uint8),
+                      _p(out, ctypes.c_int64), _p(prof, ctypes.c_int64))
+    return out, prof
+
+
+def neighbours(g, budget, C, starts, ends, active, R, moves=None, T=None):
+    """Scores of single-field moves of one candidate by full re-evaluation.
+
+    Returns (scores int64 [count][2] = (violations, peak) or (-1,-1),
+    best = (move, violations, peak)); `moves` = None scores all n*C*4R moves.
+    """
+    K = g.n * C
+    T = K if T is None else T
+    s, e, a = _cand(starts, np.int32, K), _cand(ends, np.int32, K), _cand(active, np.uint8, K)
+    assert s.shape[0] == 1
+    if moves is None:
+        n_moves, mv, count = 0, None, K * 4 * R
+    else:
+        mv = np.ascontiguousarray(moves, dtype=np.int64)
+        n_moves = count = mv.shape[0]
+    scores = np.zeros((count, 2), dtype=np.int64)
+    best = np.zeros(3, dtype=np.int64)
+    keep, ga = _graph_args(g)
+    lib().orc_neighbours(*ga, ctypes.c_int64(budget), ctypes.c_int32(C), ctypes.c_int32(T),
+                         _p(s, ctypes.c_int32), _p(e, ctypes.c_int32), _p(a, ctypes.c_uint8),
+                         ctypes.c_int32(R), ctypes.c_int64(n_moves),
+                         _p(mv, ctypes.c_int64) if mv is not None else None,
+                         _p(scores, ctypes.c_int64), _p(best, ctypes.c_int64))
+    return scores, tuple(int(x) for x in best)
+
+
+def simulate_sequence(g, seq):
+    """Independent liveness simulation of a rematerialisation sequence.
+    Returns (valid, peak, duration)."""
+    sq = np.ascontiguousarray(seq, dtype=np.int32)
+    peak = ctypes.c_int64(0)
+    dur = ctypes.c_int64(0)
+    keep, ga = _graph_args(g)
+    ok = lib().bf_simulate(*ga, ctypes.c_int32(sq.shape[0]), _p(sq, ctypes.c_int32),
+                           ctypes.byref(peak), ctypes.byref(dur))
+    return bool(ok), peak.value, dur.value
+
+
+def enumerate_sequences(g, C, max_extra, cap=2_000_000):
+    """All valid sequences with <= C occurrences per node and <= max_extra
+    recomputations, with simulated peak/duration and canonical candidates."""
+    K = g.n * C
+    seq_len = np.zeros(cap, dtype=np.int32)
+    seqs = np.zeros((cap, K), dtype=np.int32)
+    peak = np.zeros(cap, dtype=np.int64)
+    dur = np.zeros(cap, dtype=np.int64)
+    s = np.zeros((cap, K), dtype=np.int32)
+    e = np.zeros((cap, K), dtype=np.int32)
+    a = np.zeros((cap, K), dtype=np.uint8)
+    keep, ga = _graph_args(g)
+    cnt = lib().bf_enumerate(*ga, ctypes.c_int32(C), ctypes.c_int32(max_extra), ctypes.c_int64(cap),
+                             _p(seq_len, ctypes.c_int32), _p(seqs, ctypes.c_int32), _p(peak, ctypes.c_int64),
+                             _p(dur, ctypes.c_int64), _p(s, ctypes.c_int32), _p(e, ctypes.c_int32),
+                             _p(a, ctypes.c_uint8))
+    if cnt > cap:
+        raise RuntimeError(f"{cnt} sequences exceed cap {cap}")
+    return dict(count=int(cnt), seq_len=seq_len[:cnt], seqs=seqs[:cnt], peak=peak[:cnt], duration=dur[:cnt],
+                starts=s[:cnt], ends=e[:cnt], active=a[:cnt])
+
+
+def exhaustive_c2(g, n_threads=8):
+    """Every C=2 assignment on a DAG with n <= 4 (see moc_exhaustive.cpp).
+    Returns (counts = evaluated, violation-free, failed checks; min_peak[mask])."""
+    assert g.n <= 4
+    counts = np.zeros(3, dtype=np.int64)
+    min_peak = np.zeros(1 << g.n, dtype=np.int64)
+    keep, ga = _graph_args(g)
+    lib().orc_exhaustive_c2(*ga, ctypes.c_int32(n_threads), _p(counts, ctypes.c_int64), _p(min_peak, ctypes.c_int64))
+    return counts, min_peak

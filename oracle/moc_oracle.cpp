@@ -1,0 +1,218 @@
+// CPU oracle for the batched candidate evaluator.  TEST INFRASTRUCTURE ONLY:
+// it is what the HIP library is checked against, it is never on the product
+// path, and it shares no code with the HIP sources.
+//
+// It evaluates the retention-interval model of Moccasin (arXiv 2304.14463,
+// Section 2.1, Eq. (1)-(8)) on a given assignment of the variables
+// (a, s, e) -- the plain definitions written out, single-threaded, int64.
+//
+// Notation: node v in [0,n), copy i in [0,C), copy index k = v*C + i,
+// positions (the paper's event domain D, Eq. (8) and the display after it,
+// shifted to 0-based) t in [0,T).  T is an explicit argument so that the
+// worked example of Section 2 (drawn on 10 events for 4 nodes x 2 copies)
+// can be evaluated as printed; the HIP library always uses T = n*C.
+//
+// Readings taken where the paper leaves a choice (all listed in the design
+// notes): an inactive copy is ignored by every constraint (Section 2.1, first
+// paragraph); intervals are closed, [s, e] (Eq. (4)); precedence is Eq. (5)
+// literally, s_u + 1 <= s_v <= e_u; "all starts different" (Eq. (6) and the
+// sentence after Eq. (8) on it) covers all live copies, same node included;
+// an active copy with s > e or a position outside [0,T) is malformed: it is
+// one violation of Eq. (2)/(8), is skipped by everything else, and still
+// counts in the objective (Eq. (1) depends on a only).
+//
+// Parity pins (tests/test_oracle_*.py): the worked example's printed values,
+// hand-counted single-violation cases, closed forms, exhaustive enumeration
+// of rematerialisation sequences on tiny DAGs against an independent liveness
+// simulation (moc_bruteforce.cpp), the no-remat liveness invariant.  The
+// neighbourhood scorer is pinned by definition (full re-evaluation through
+// the pinned evaluator); the move set itself is this library's, not the
+// paper's.
+#include <cstdint>
+#include <cstring>
+#include <vector>
+
+namespace {
+
+struct Problem {
+  int32_t n;
+  const int32_t* in_ptr;  // [n+1] predecessors of v: in_idx[in_ptr[v] .. in_ptr[v+1])
+  const int32_t* in_idx;  // [m]
+  const int32_t* size;    // [n]  m_v
+  const int32_t* dur;     // [n]  w_v
+  int64_t budget;         // M
+  int32_t C;
+  int32_t T;
+};
+
+// fields of one result row (int64 each)
+enum { R_PEAK, R_DURATION, R_VIOLATIONS, R_FEASIBLE, R_FORM, R_FIRST, R_ORDER, R_START, R_PREC, R_FIELDS };
+
+struct Scratch {
+  std::vector<char> live;
+  std::vector<int64_t> profile;
+  std::vector<int32_t> cnt;
+};
+
+// Eq. (2) and the domain of Eq. (8): an active copy is usable iff 0 <= s <= e <= T-1.
+inline bool well_formed(const Problem& p, int32_t s, int32_t e, uint8_t a) {
+  return a != 0 && 0 <= s && s <= e && e <= p.T - 1;
+}
+
+void evaluate(const Problem& p, const int32_t* s, const int32_t* e, const uint8_t* a, Scratch& w,
+              int64_t* out, int64_t* profile_out) {
+  const int K = p.n * p.C;
+  w.live.assign(K, 0);
+  int64_t v_form = 0, v_first = 0, v_order = 0, v_start = 0, v_prec = 0, duration = 0;
+
+  for (int k = 0; k < K; ++k) {
+    w.live[k] = well_formed(p, s[k], e[k], a[k]);
+    if (a[k] != 0 && !w.live[k]) ++v_form;          // Eq. (2), Eq. (8)
+    if (a[k] != 0) duration += p.dur[k / p.C];      // Eq. (1)
+  }
+  for (int v = 0; v < p.n; ++v)
+    if (a[v * p.C] == 0) ++v_first;                 // Eq. (7)
+
+  // Eq. (3): a live copy must end no later than the next live copy of its node starts.
+  for (int v = 0; v < p.n; ++v)
+    for (int i = 0; i < p.C; ++i) {
+      if (!w.live[v * p.C + i]) continue;
+      for (int j = i + 1; j < p.C; ++j)
+        if (w.live[v * p.C + j]) {
+          if (e[v * p.C + i] > s[v * p.C + j]) ++v_order;
+          break;
+        }
+    }
+
+  // Eq. (6): compute events do not coincide.
+  w.cnt.assign(p.T > 0 ? p.T : 0, 0);
+  for (int k = 0; k < K; ++k)
+    if (w.live[k]) ++w.cnt[s[k]];
+  for (int t = 0; t < p.T; ++t)
+    if (w.cnt[t] > 1) v_start += w.cnt[t] - 1;
+
+  // Eq. (5): every input of every live copy is covered by a live copy of the producer.
+  for (int v = 0; v < p.n; ++v)
+    for (int q = p.in_ptr[v]; q < p.in_ptr[v + 1]; ++q) {
+      const int u = p.in_idx[q];
+      for (int i = 0; i < p.C; ++i) {
+        if (!w.live[v * p.C + i]) continue;
+        const int64_t sv = s[v * p.C + i];
+        bool covered = false;
+        for (int j = 0; j < p.C; ++j) {
+          const int ku = u * p.C + j;
+          if (w.live[ku] && (int64_t)s[ku] + 1 <= sv && sv <= (int64_t)e[ku]) covered = true;
+        }
+        if (!covered) ++v_prec;
+      }
+    }
+
+  // Eq. (4): memory in use at every position, closed intervals; peak = max over positions.
+  w.profile.assign(p.T > 0 ? p.T : 0, 0);
+  for (int k = 0; k < K; ++k)
+    if (w.live[k])
+      for (int t = s[k]; t <= e[k]; ++t) w.profile[t] += p.size[k / p.C];
+  int64_t peak = 0;
+  for (int t = 0; t < p.T; ++t)
+    if (w.profile[t] > peak) peak = w.profile[t];
+  if (profile_out)
+    for (int t = 0; t < p.T; ++t) profile_out[t] = w.profile[t];
+
+  const int64_t violations = v_form + v_first + v_order + v_start + v_prec;
+  out[R_PEAK] = peak;
+  out[R_DURATION] = duration;
+  out[R_VIOLATIONS] = violations;
+  out[R_FEASIBLE] = (violations == 0 && peak <= p.budget) ? 1 : 0;
+  out[R_FORM] = v_form;
+  out[R_FIRST] = v_first;
+  out[R_ORDER] = v_order;
+  out[R_START] = v_start;
+  out[R_PREC] = v_prec;
+}
+
+}  // namespace
+
+extern "C" {
+
+int orc_result_fields() { return R_FIELDS; }
+
+// Evaluate B candidates; starts/ends/active are [B][n*C]; out is [B][R_FIELDS] int64.
+void orc_eval(int32_t n, const int32_t* in_ptr, const int32_t* in_idx, const int32_t* size,
+              const int32_t* dur, int64_t budget, int32_t C, int32_t T, int64_t B,
+              const int32_t* starts, const int32_t* ends, const uint8_t* active, int64_t* out) {
+  Problem p{n, in_ptr, in_idx, size, dur, budget, C, T};
+  Scratch w;
+  const int64_t K = (int64_t)n * C;
+  for (int64_t b = 0; b < B; ++b)
+    evaluate(p, starts + b * K, ends + b * K, active + b * K, w, out + b * R_FIELDS, nullptr);
+}
+
+// One candidate; also returns the memory profile (Eq. (4) left-hand side) per position.
+void orc_profile(int32_t n, const int32_t* in_ptr, const int32_t* in_idx, const int32_t* size,
+                 const int32_t* dur, int64_t budget, int32_t C, int32_t T, const int32_t* starts,
+                 const int32_t* ends, const uint8_t* active, int64_t* out, int64_t* profile) {
+  Problem p{n, in_ptr, in_idx, size, dur, budget, C, T};
+  Scratch w;
+  evaluate(p, starts, ends, active, w, out, profile);
+}
+
+// Neighbourhood of one candidate by full re-evaluation.  Move index
+// q = ((k*2 + field)*2R + d), field 0 = start, 1 = end, delta = d-R for d < R,
+// d-R+1 otherwise (so delta runs -R..-1, +1..+R).  A move is not applicable if
+// the copy is inactive or the moved field would leave [0,T): score (-1,-1).
+// Otherwise the score is (violations, peak) of the candidate with that one
+// field changed.  n_moves == 0: score every move, moves == NULL; else score
+// only the listed move indices.  scores is [count][2] int64.
+// best (may be NULL) receives {move, violations, peak} of the applicable move
+// that minimises (violations, max(peak, M), peak, q) lexicographically -- the
+// Phase-1 objective of Section 2.4 as tie-break after the violation count --
+// over the moves scored by this call; move = -1 if none was applicable.
+void orc_neighbours(int32_t n, const int32_t* in_ptr, const int32_t* in_idx, const int32_t* size,
+                    const int32_t* dur, int64_t budget, int32_t C, int32_t T, const int32_t* starts,
+                    const int32_t* ends, const uint8_t* active, int32_t R, int64_t n_moves,
+                    const int64_t* moves, int64_t* scores, int64_t* best) {
+  Problem p{n, in_ptr, in_idx, size, dur, budget, C, T};
+  Scratch w;
+  const int K = n * C;
+  std::vector<int32_t> s(starts, starts + K), e(ends, ends + K);
+  const int64_t total = (int64_t)K * 4 * R;
+  const int64_t count = n_moves ? n_moves : total;
+  int64_t best_move = -1, best_v = 0, best_peak = 0;
+  int64_t res[R_FIELDS];
+  for (int64_t idx = 0; idx < count; ++idx) {
+    const int64_t q = n_moves ? moves[idx] : idx;
+    const int d = (int)(q % (2 * R));
+    const int field = (int)((q / (2 * R)) % 2);
+    const int k = (int)(q / (4 * R));
+    const int delta = d < R ? d - R : d - R + 1;
+    int32_t& var = field == 0 ? s[k] : e[k];
+    const int64_t moved = (int64_t)var + delta;
+    if (active[k] == 0 || moved < 0 || moved >= T) {
+      scores[2 * idx] = -1;
+      scores[2 * idx + 1] = -1;
+      continue;
+    }
+    const int32_t keep = var;
+    var = (int32_t)moved;
+    evaluate(p, s.data(), e.data(), active, w, res, nullptr);
+    var = keep;
+    scores[2 * idx] = res[R_VIOLATIONS];
+    scores[2 * idx + 1] = res[R_PEAK];
+    const int64_t key_mem = res[R_PEAK] > budget ? res[R_PEAK] : budget;
+    const int64_t best_mem = best_peak > budget ? best_peak : budget;
+    if (best_move < 0 || res[R_VIOLATIONS] < best_v ||
+        (res[R_VIOLATIONS] == best_v &&
+         (key_mem < best_mem || (key_mem == best_mem && res[R_PEAK] < best_peak)))) {
+      // moves are visited in increasing q within a call that scores all of them,
+      // so strict improvement keeps the smallest q among equals
+      best_move = q; best_v = res[R_VIOLATIONS]; best_peak = res[R_PEAK];
+    }
+  }
+  if (best) {
+    best[0] = best_move;
+    best[1] = best_move < 0 ? 0 : best_v;
+    best[2] = best_move < 0 ? 0 : best_peak;
+  }
+}
+
+}  // extern "C"
