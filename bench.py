@@ -1,0 +1,159 @@
+#!/usr/bin/env python3
+"""Benchmark of the batched candidate evaluator on one MI355X.
+
+A step is one pass of the whole hot path (moc_eval_batch: load, structural
+checks, start collisions, memory profile, peak, precedence, objective, store)
+over one resident batch of synthetic candidates.  Default workload: the
+n=5000, C=3, B=262144 configuration (35.4 GB of candidates resident in HBM);
+the n=442 configuration is timed as well and reported under "also".
+
+Prints ONE JSON line.  `value` is candidates evaluated per second with inputs
+resident in HBM; `roofline` prices the evaluation kernel against the 8 TB/s
+HBM peak using its algorithmic bytes (9*T + 24 per candidate); `cpu_baseline`
+times the CPU oracle on a bounded sample of the same candidates.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", type=int, default=4, choices=[0, 1, 2, 3, 4])
+    ap.add_argument("--batch", type=int, default=None, help="override the workload's batch size")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-also", action="store_true", help="skip the secondary (n=442) measurement")
+    return ap.parse_args()
+
+
+def time_eval(moc, gh, cand, steps, warmup):
+    """Returns (ms per step over the whole timed region, mean kernel ms from per-launch events)."""
+    import torch
+    ds, de, da = cand
+    B = ds.shape[0]
+    out = torch.empty((B, moc.RESULT_DTYPE.itemsize), dtype=torch.uint8, device=ds.device)
+    stream = torch.cuda.current_stream()
+    for _ in range(warmup):
+        moc.moc_eval_batch(gh, ds, de, da, out=out, stream=stream)
+    torch.cuda.synchronize()
+    begins = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+    finishes = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+    t0 = time.perf_counter()
+    for i in range(steps):
+        begins[i].record(stream)
+        moc.moc_eval_batch(gh, ds, de, da, out=out, stream=stream)
+        finishes[i].record(stream)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    kernel_ms = [b.elapsed_time(f) for b, f in zip(begins, finishes)]
+    return wall_ms / steps, sum(kernel_ms) / len(kernel_ms), min(kernel_ms), out
+
+
+def measure(moc, cfg, steps, warmup, batch=None):
+    import torch
+    from paper_2304_14463_amd.inputs import DeviceWorkload, make_workload
+    w = make_workload(cfg, batch)
+    g = w.graph
+    gh = moc.moc_graph_upload(g.n, g.in_ptr, g.in_idx, g.size, g.dur, w.budget, w.C)
+    cand = DeviceWorkload(w).candidates()
+    torch.cuda.synchronize()
+    ms_step, ms_kernel, ms_kernel_min, out = time_eval(moc, gh, cand, steps, warmup)
+    res = moc.results_to_numpy(out)
+    bytes_per_cand = 9 * w.T + 24
+    info = {
+        "workload": w.name, "n": w.n, "m": w.m, "C": w.C, "T": w.T, "B": w.B,
+        "budget_pct_of_no_remat_peak": w.pct, "bytes_per_candidate": bytes_per_cand,
+        "frac_violation_free": float((res["violations"] == 0).mean()),
+        "frac_feasible": float(res["feasible"].mean()),
+    }
+    gbs = w.B * bytes_per_cand / (ms_kernel * 1e-3) / 1e9
+    return w, gh, cand, res, info, ms_step, ms_kernel, ms_kernel_min, gbs
+
+
+def cpu_baseline(w, cand, res, target_seconds=15.0):
+    """Times oracle.evaluate (single thread, as it stands) on the first candidates of the batch."""
+    import numpy as np
+    import oracle
+    ds, de, da = cand
+    probe = 8
+    s, e, a = ds[:probe].cpu().numpy(), de[:probe].cpu().numpy(), da[:probe].cpu().numpy()
+    t0 = time.perf_counter()
+    oracle.evaluate(w.graph, w.budget, w.C, s, e, a)
+    per = max((time.perf_counter() - t0) / probe, 1e-7)
+    count = int(max(probe, min(w.B, target_seconds / per)))
+    s, e, a = ds[:count].cpu().numpy(), de[:count].cpu().numpy(), da[:count].cpu().numpy()
+    t0 = time.perf_counter()
+    ref = oracle.evaluate(w.graph, w.budget, w.C, s, e, a)
+    dt = time.perf_counter() - t0
+    ok = all((res[name][:count].astype(np.int64) == ref[:, i]).all()
+             for i, name in enumerate(("peak", "duration", "violations", "feasible")))
+    # same function on all host cores (disjoint candidate ranges, one thread each)
+    cores = min(os.cpu_count() or 1, 16)
+    cuts = np.linspace(0, count, cores + 1).astype(int)
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(cores) as ex:
+        list(ex.map(lambda i: oracle.evaluate(w.graph, w.budget, w.C, s[cuts[i]:cuts[i + 1]],
+                                              e[cuts[i]:cuts[i + 1]], a[cuts[i]:cuts[i + 1]]), range(cores)))
+    dt_all = time.perf_counter() - t0
+    return ({"value": count / dt, "unit": "candidates/s", "cores": 1, "kind": "oracle",
+             "sample": f"first {count} candidates of the batch, single-threaded oracle.evaluate",
+             "matches_gpu": bool(ok)},
+            {"value": count / dt_all, "unit": "candidates/s", "cores": cores, "kind": "oracle",
+             "sample": f"same {count} candidates split over {cores} host threads"})
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (candidates shard trivially by batch; "
+                 "no multi-GPU path is built). Use --gpus 1.")
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; the evaluator has no CPU fallback.")
+    from paper_2304_14463_amd import moccasin as moc
+    moc.lib()
+
+    w, gh, cand, res, info, ms_step, ms_kernel, ms_kernel_min, gbs = measure(
+        moc, args.workload, args.steps, args.warmup, args.batch)
+    line = {
+        "metric": "candidate schedules evaluated/sec",
+        "value": w.B / (ms_step * 1e-3),
+        "unit": "candidates/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int32", "data": "synthetic",
+        "config": info,
+        "roofline": {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": gbs / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "eval_batch_kernel", "kernel_ms_avg": ms_kernel, "kernel_ms_min": ms_kernel_min,
+                     "algorithmic_bytes_per_launch": w.B * info["bytes_per_candidate"]},
+    }
+    if not args.no_cpu_baseline:
+        one, allc = cpu_baseline(w, cand, res)
+        line["cpu_baseline"] = one
+        line["cpu_baseline_all_cores"] = allc
+    del cand
+    gh.free()
+    torch.cuda.empty_cache()
+    if not args.no_also and args.workload != 1:
+        w2, gh2, cand2, res2, info2, ms2, msk2, mskmin2, gbs2 = measure(moc, 1, max(args.steps, 50), args.warmup)
+        line["also"] = {"config": info2, "value": w2.B / (ms2 * 1e-3), "unit": "candidates/s", "ms_per_step": ms2,
+                        "kernel_ms_avg": msk2, "kernel_ms_min": mskmin2, "achieved_GBs": gbs2,
+                        "frac_of_hbm_peak": gbs2 / HBM_PEAK_GBS}
+        gh2.free()
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,161 @@
+/*
+ * moccasin.h -- C ABI of libmoccasin_hip.so: batched evaluation of candidate
+ * assignments to the retention-interval model of Moccasin (arXiv 2304.14463)
+ * on one AMD MI355X (gfx950).
+ *
+ * Model (paper, Section 2 and Section 2.1).  A compute DAG G = (V, E) has n
+ * nodes; node v has a duration w_v and an output size m_v; the memory budget
+ * is M.  Every node may be computed up to C times; copy i of node v is a
+ * retention interval with variables a (active flag), s (start = the event at
+ * which v is computed) and e (end = last event at which its output is kept).
+ * A candidate is one assignment to all n*C copies.
+ *
+ * Conventions of this library
+ *   - copy index k = v*C + i (the copies of a node are adjacent), T = n*C;
+ *   - positions are 0-based: the paper's event t in D = {1..sum C_v} (the
+ *     display after Eq. (8)) is position t-1 in [0, T);
+ *   - a batch of B candidates is three row-major [B][T] arrays: int32 starts,
+ *     int32 ends, uint8 active (non-zero = active);
+ *   - a copy is "live" iff it is active and 0 <= s <= e <= T-1.  An inactive
+ *     copy is ignored by every constraint (Section 2.1, first paragraph).  An
+ *     active copy that is not live is counted once as a violation of
+ *     Eq. (2)/(8), is ignored by Eq. (3)-(6), and still counts in Eq. (1).
+ *
+ * What is computed per candidate (moc_result)
+ *   duration   = sum over active copies of w_v                       Eq. (1)
+ *   peak       = max over positions t of the summed m_v of the live
+ *                copies with s <= t <= e (closed intervals)           Eq. (4)
+ *   violations = number of violated constraint instances:
+ *                  active copies that are not live                    Eq. (2), (8)
+ *                + nodes whose copy 0 is inactive                     Eq. (7)
+ *                + live copies that end after the next live copy of
+ *                  the same node starts                               Eq. (3)
+ *                + sum over positions of (live starts there - 1)+     Eq. (6)
+ *                + pairs (edge (u,v), live copy i of v) for which no
+ *                  live copy j of u has s_u^j + 1 <= s_v^i <= e_u^j   Eq. (5)
+ *   feasible   = (violations == 0 && peak <= M)
+ * The budget never adds to `violations`; its slack is peak - M.
+ *
+ * Memory and ownership.  Graph arrays are HOST pointers, read during
+ * moc_graph_upload only.  Candidate and result arrays are DEVICE pointers
+ * owned by the caller and must stay valid until the work queued on the stream
+ * has finished.  Evaluation calls allocate nothing and are asynchronous on
+ * the given HIP stream.  The device that was current at upload must be
+ * current at every later call with that graph.
+ *
+ * Errors.  Every function that returns int returns MOC_OK (0) or a negative
+ * code; nothing is queued on the stream when an error is returned.  Contents
+ * of a candidate are never an error: bad values are violations.
+ */
+#ifndef MOCCASIN_H
+#define MOCCASIN_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MOC_OK          0
+#define MOC_EINVAL    (-1)  /* bad argument: null pointer, size out of range, index out of range, misaligned */
+#define MOC_EOVERFLOW (-2)  /* C * sum(size) or C * sum(dur) >= 2^31, or T too large for the LDS layout */
+#define MOC_ENOMEM    (-3)  /* host or device allocation failed */
+#define MOC_EHIP      (-4)  /* a HIP runtime call failed; see moc_last_hip_error() */
+#define MOC_EDEVICE   (-5)  /* the graph's device is not the current device */
+
+/* Largest T = n*C an uploaded graph may have (the per-candidate working set
+ * -- memory-delta array, packed intervals, start bitmap -- lives in the
+ * 160 KB LDS of one compute unit). */
+#define MOC_MAX_T 19455
+
+typedef struct moc_graph moc_graph; /* opaque; owns device copies of the graph */
+
+typedef struct {
+  int64_t peak;       /* Eq. (4) left-hand side, maximised over positions */
+  int64_t duration;   /* Eq. (1) */
+  int32_t violations; /* violated instances of Eq. (2),(3),(5),(6),(7),(8) */
+  int32_t feasible;   /* 1 iff violations == 0 and peak <= M */
+} moc_result;         /* 24 bytes */
+
+typedef struct {
+  int32_t violations; /* -1 if the move is not applicable */
+  int32_t peak;       /* -1 if the move is not applicable */
+} moc_move_score;
+
+typedef struct {
+  int32_t move;       /* index of the best move, -1 if no move is applicable */
+  int32_t violations; /* 0 when move == -1 */
+  int64_t peak;       /* 0 when move == -1 */
+} moc_best_move;
+
+/*
+ * Upload a problem instance (Section 1, problem statement; Section 2.1: w_v and
+ * m_v are known).
+ *   n        number of nodes, >= 1
+ *   in_ptr   host, [n+1], CSR offsets by in-edges: the predecessors u of v
+ *            (edges (u,v) in E) are in_idx[in_ptr[v] .. in_ptr[v+1]); in_ptr[0] = 0,
+ *            non-decreasing
+ *   in_idx   host, [m = in_ptr[n]], each in [0, n)
+ *   size     host, [n], m_v >= 0
+ *   dur      host, [n], w_v >= 0
+ *   budget   M
+ *   C        copies per node (the paper's C_v, uniform), >= 1
+ *   out      receives the handle; release with moc_graph_free
+ * Acyclicity is not required and not checked (evaluation is defined on any
+ * digraph).  Duplicate in-edges are kept and counted as separate instances.
+ * Errors: MOC_EINVAL, MOC_EOVERFLOW (sums, or n*C > MOC_MAX_T), MOC_ENOMEM, MOC_EHIP.
+ */
+int moc_graph_upload(int32_t n, const int32_t* in_ptr, const int32_t* in_idx, const int32_t* size,
+                     const int32_t* dur, int64_t budget, int32_t C, moc_graph** out);
+
+/* Sizes of an uploaded graph; any output pointer may be NULL. */
+int moc_graph_info(const moc_graph* g, int32_t* n, int32_t* m, int32_t* C, int32_t* T);
+
+/*
+ * Evaluate B candidates (Eq. (1)-(8) as listed above).
+ *   starts, ends   device, int32 [B][T]
+ *   active         device, uint8 [B][T]
+ *   out            device, moc_result [B], 8-byte aligned
+ *   hip_stream     a hipStream_t (NULL = the default stream)
+ * starts/ends must be 4-byte aligned; when starts and ends are 16-byte aligned
+ * and active is 4-byte aligned the rows are read with 16-byte loads, otherwise
+ * element by element (same results).  B == 0 is a no-op.
+ * Errors: MOC_EINVAL, MOC_EDEVICE, MOC_EHIP.
+ */
+int moc_eval_batch(const moc_graph* g, int64_t B, const int32_t* starts, const int32_t* ends,
+                   const uint8_t* active, moc_result* out, void* hip_stream);
+
+/*
+ * Score every single-field move of B base candidates.  Not part of the paper:
+ * it is the neighbourhood a local search over the variables of Section 2.1
+ * would scan.  Move index q = ((k*2 + field)*2R + d): copy k, field 0 = start,
+ * 1 = end, displacement delta = d-R for d < R and d-R+1 otherwise (delta runs
+ * over -R..-1, +1..+R).  A move is not applicable when copy k is inactive or
+ * the moved field would leave [0, T): its score is (-1, -1).  Otherwise its
+ * score is the (violations, peak) that moc_eval_batch returns for the
+ * candidate with that one field changed; the duration does not change.
+ *   R           radius, 1 <= R <= 32
+ *   out_moves   device, moc_move_score [B][T*4R], or NULL
+ *   out_best    device, moc_best_move [B], or NULL: the applicable move that
+ *               minimises (violations, max(peak, M), peak, q) lexicographically
+ *               (max(peak, M) is the Phase-1 objective of Section 2.4)
+ * At least one of out_moves / out_best must be given.
+ * Errors: MOC_EINVAL, MOC_EDEVICE, MOC_EOVERFLOW (T too large for this call), MOC_EHIP.
+ */
+int moc_eval_neighbours(const moc_graph* g, int64_t B, const int32_t* starts, const int32_t* ends,
+                        const uint8_t* active, int32_t R, moc_move_score* out_moves,
+                        moc_best_move* out_best, void* hip_stream);
+
+/* Release a graph (synchronises its device first).  NULL is a no-op. */
+void moc_graph_free(moc_graph* g);
+
+/* Static description of an error code. */
+const char* moc_strerror(int code);
+
+/* hipError_t value of the last failed HIP call on this thread (0 if none). */
+int moc_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOCCASIN_H */

@@ -1,0 +1,53 @@
+"""Builds the HIP shared libraries in-tree with hipcc for gfx950.
+
+  paper_2304_14463_amd/libmoccasin_hip.so          the C-ABI evaluator (include/moccasin.h)
+  paper_2304_14463_amd/inputs/libmoc_inputs_hip.so device twin of the candidate generator
+
+hipcc cross-compiles without a GPU.  Run as `python -m paper_2304_14463_amd.build`.
+"""
+from __future__ import annotations
+
+import glob
+import os
+import subprocess
+import sys
+
+PKG = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(PKG)
+LIB = os.path.join(PKG, "libmoccasin_hip.so")
+INPUTS_LIB = os.path.join(PKG, "inputs", "libmoc_inputs_hip.so")
+
+HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
+               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+               "-Wall", "-Wno-unused-result"]
+
+
+def _hipcc(out, sources, extra=()):
+    cmd = ["hipcc", *HIPCC_FLAGS, *extra, "-o", out, *sources]
+    proc = subprocess.run(cmd, capture_output=True, text=True)
+    noise = "packed-fp32-ops' is not a recognized feature"
+    err = "\n".join(l for l in proc.stderr.splitlines() if noise not in l)
+    if proc.returncode != 0:
+        raise RuntimeError(f"hipcc failed ({' '.join(cmd)}):\n{err}")
+    if err.strip():
+        sys.stderr.write(err + "\n")
+    return out
+
+
+def build_library():
+    srcs = sorted(glob.glob(os.path.join(PKG, "csrc", "*.hip")))
+    return _hipcc(LIB, srcs, ["-I", os.path.join(ROOT, "include"), "-I", os.path.join(PKG, "csrc")])
+
+
+def build_inputs():
+    srcs = sorted(glob.glob(os.path.join(PKG, "inputs", "csrc", "*.hip")))
+    return _hipcc(INPUTS_LIB, srcs)
+
+
+def build_all():
+    return [build_library(), build_inputs()]
+
+
+if __name__ == "__main__":
+    for path in build_all():
+        print("built", path)

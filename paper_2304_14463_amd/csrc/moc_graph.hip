@@ -1,0 +1,167 @@
+// moc_graph_upload / moc_graph_free / error reporting: host-side validation
+// and preprocessing of the problem instance (paper, Section 1 problem
+// statement and Section 2.1: DAG, durations w_v, sizes m_v, budget M, C).
+//
+// The kernels walk precedence constraints (Eq. (5)) node by node, one lane
+// per consumer node.  To keep the 64 lanes of a wavefront on equal trip
+// counts, nodes are sorted by in-degree and their predecessor lists stored as
+// sliced ELL: 64 nodes per slice, slice width = largest in-degree in the
+// slice, column-major so that edge j of the 64 nodes is one contiguous
+// 128-byte read.
+#include <algorithm>
+#include <cstring>
+#include <new>
+#include <numeric>
+#include <vector>
+
+#include "moc_internal.h"
+
+static thread_local int g_last_hip_error = 0;
+
+int moc_set_hip_error(hipError_t e) {
+  g_last_hip_error = (int)e;
+  return MOC_EHIP;
+}
+
+template <typename T>
+static int upload(moc_graph* g, const std::vector<T>& host, const T** dev) {
+  void* p = nullptr;
+  const size_t bytes = std::max<size_t>(host.size(), 1) * sizeof(T);
+  hipError_t e = hipMalloc(&p, bytes);
+  if (e == hipErrorOutOfMemory) return MOC_ENOMEM;
+  if (e != hipSuccess) return moc_set_hip_error(e);
+  g->allocs[g->n_allocs++] = p;
+  if (!host.empty()) MOC_HIP(hipMemcpy(p, host.data(), host.size() * sizeof(T), hipMemcpyHostToDevice));
+  *dev = (const T*)p;
+  return MOC_OK;
+}
+
+extern "C" {
+
+int moc_graph_upload(int32_t n, const int32_t* in_ptr, const int32_t* in_idx, const int32_t* size,
+                     const int32_t* dur, int64_t budget, int32_t C, moc_graph** out) {
+  if (!out) return MOC_EINVAL;
+  *out = nullptr;
+  if (n < 1 || C < 1 || !in_ptr || !size || !dur) return MOC_EINVAL;
+  if ((int64_t)n * C > MOC_MAX_T) return MOC_EOVERFLOW;
+  if (in_ptr[0] != 0) return MOC_EINVAL;
+  for (int v = 0; v < n; ++v)
+    if (in_ptr[v + 1] < in_ptr[v]) return MOC_EINVAL;
+  const int32_t m = in_ptr[n];
+  if (m > 0 && !in_idx) return MOC_EINVAL;
+  for (int q = 0; q < m; ++q)
+    if (in_idx[q] < 0 || in_idx[q] >= n) return MOC_EINVAL;
+  int64_t sum_size = 0, sum_dur = 0;
+  for (int v = 0; v < n; ++v) {
+    if (size[v] < 0 || dur[v] < 0) return MOC_EINVAL;
+    sum_size += size[v];
+    sum_dur += dur[v];
+  }
+  // The memory profile and the objective are accumulated in int32 on the device.
+  if (sum_size * C >= (int64_t)1 << 31 || sum_dur * C >= (int64_t)1 << 31) return MOC_EOVERFLOW;
+
+  try {
+    const int T = n * C;
+    std::vector<int2> size_dur(n);
+    for (int v = 0; v < n; ++v) size_dur[v] = make_int2(size[v], dur[v]);
+
+    // nodes by in-degree, largest first (stable: ties keep id order)
+    std::vector<int> order(n);
+    std::iota(order.begin(), order.end(), 0);
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) {
+      return in_ptr[a + 1] - in_ptr[a] > in_ptr[b + 1] - in_ptr[b];
+    });
+    const int n_slices = (n + kWave - 1) / kWave;
+    std::vector<uint32_t> slot_info((size_t)n_slices * kWave, MOC_DEAD);
+    std::vector<int32_t> ell_ptr(n_slices + 1, 0);
+    for (int sl = 0; sl < n_slices; ++sl) {
+      const int v0 = order[sl * kWave];
+      ell_ptr[sl + 1] = ell_ptr[sl] + (in_ptr[v0 + 1] - in_ptr[v0]) * kWave;
+    }
+    std::vector<uint16_t> ell_pred(ell_ptr[n_slices], 0);
+    for (int p = 0; p < n; ++p) {
+      const int v = order[p], deg = in_ptr[v + 1] - in_ptr[v];
+      if (deg > 0xFFFF) return MOC_EOVERFLOW;
+      slot_info[p] = (uint32_t)(v * C) | ((uint32_t)deg << 16);
+      const int sl = p / kWave, lane = p % kWave;
+      for (int j = 0; j < deg; ++j)
+        ell_pred[ell_ptr[sl] + j * kWave + lane] = (uint16_t)(in_idx[in_ptr[v] + j] * C);
+    }
+
+    // out-edge CSR (consumers of every node), used by the neighbourhood kernel
+    std::vector<int32_t> out_ptr(n + 1, 0), out_idx(m);
+    for (int q = 0; q < m; ++q) ++out_ptr[in_idx[q] + 1];
+    for (int v = 0; v < n; ++v) out_ptr[v + 1] += out_ptr[v];
+    {
+      std::vector<int32_t> fill(out_ptr.begin(), out_ptr.end() - 1);
+      for (int v = 0; v < n; ++v)
+        for (int q = in_ptr[v]; q < in_ptr[v + 1]; ++q) out_idx[fill[in_idx[q]]++] = v;
+    }
+    std::vector<int32_t> in_ptr_v(in_ptr, in_ptr + n + 1), in_idx_v(in_idx, in_idx + m);
+
+    moc_graph* g = new moc_graph();
+    std::memset(g, 0, sizeof(*g));
+    int rc = MOC_OK;
+    hipError_t e = hipGetDevice(&g->device);
+    hipDeviceProp_t prop;
+    if (e == hipSuccess) e = hipGetDeviceProperties(&prop, g->device);
+    if (e != hipSuccess) {
+      delete g;
+      return moc_set_hip_error(e);
+    }
+    g->num_cu = prop.multiProcessorCount;
+    g->max_lds = (int)prop.sharedMemPerBlock;
+    GraphView& w = g->view;
+    w.budget = budget; w.n = n; w.m = m; w.C = C; w.T = T; w.n_slices = n_slices;
+    if (rc == MOC_OK) rc = upload(g, size_dur, &w.size_dur);
+    if (rc == MOC_OK) rc = upload(g, slot_info, &w.slot_info);
+    if (rc == MOC_OK) rc = upload(g, ell_pred, &w.ell_pred);
+    if (rc == MOC_OK) rc = upload(g, ell_ptr, &w.ell_ptr);
+    if (rc == MOC_OK) rc = upload(g, in_ptr_v, &w.in_ptr);
+    if (rc == MOC_OK) rc = upload(g, in_idx_v, &w.in_idx);
+    if (rc == MOC_OK) rc = upload(g, out_ptr, &w.out_ptr);
+    if (rc == MOC_OK) rc = upload(g, out_idx, &w.out_idx);
+    if (rc != MOC_OK) {
+      for (int i = 0; i < g->n_allocs; ++i) (void)hipFree(g->allocs[i]);
+      delete g;
+      return rc;
+    }
+    *out = g;
+    return MOC_OK;
+  } catch (const std::bad_alloc&) {
+    return MOC_ENOMEM;
+  }
+}
+
+int moc_graph_info(const moc_graph* g, int32_t* n, int32_t* m, int32_t* C, int32_t* T) {
+  if (!g) return MOC_EINVAL;
+  if (n) *n = g->view.n;
+  if (m) *m = g->view.m;
+  if (C) *C = g->view.C;
+  if (T) *T = g->view.T;
+  return MOC_OK;
+}
+
+void moc_graph_free(moc_graph* g) {
+  if (!g) return;
+  int cur = -1;
+  if (hipGetDevice(&cur) == hipSuccess && cur == g->device) (void)hipDeviceSynchronize();
+  for (int i = 0; i < g->n_allocs; ++i) (void)hipFree(g->allocs[i]);
+  delete g;
+}
+
+const char* moc_strerror(int code) {
+  switch (code) {
+    case MOC_OK: return "ok";
+    case MOC_EINVAL: return "invalid argument";
+    case MOC_EOVERFLOW: return "size limit exceeded (int32 sums or T too large for LDS)";
+    case MOC_ENOMEM: return "out of memory";
+    case MOC_EHIP: return "HIP runtime error (see moc_last_hip_error)";
+    case MOC_EDEVICE: return "graph was uploaded on a different device than the current one";
+    default: return "unknown error";
+  }
+}
+
+int moc_last_hip_error(void) { return g_last_hip_error; }
+
+}  // extern "C"

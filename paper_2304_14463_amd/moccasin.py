@@ -1,0 +1,158 @@
+"""Python binding of libmoccasin_hip.so (C ABI in include/moccasin.h).
+
+Argument marshalling only: every step of the evaluation runs in the HIP
+kernels of the library.  Tensors are torch tensors on the GPU (torch is used
+for device memory and streams); graph arrays are host numpy arrays.  There is
+no CPU fallback: a missing library or GPU raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libmoccasin_hip.so")
+_lib = None
+
+MOC_MAX_T = 19455
+
+# numpy views of the result structs of include/moccasin.h
+RESULT_DTYPE = np.dtype([("peak", "<i8"), ("duration", "<i8"), ("violations", "<i4"), ("feasible", "<i4")])
+MOVE_SCORE_DTYPE = np.dtype([("violations", "<i4"), ("peak", "<i4")])
+BEST_MOVE_DTYPE = np.dtype([("move", "<i4"), ("violations", "<i4"), ("peak", "<i8")])
+
+EXPORTS = ("moc_graph_upload", "moc_graph_info", "moc_eval_batch", "moc_eval_neighbours",
+           "moc_graph_free", "moc_strerror", "moc_last_hip_error")
+
+
+class MoccasinError(RuntimeError):
+    def __init__(self, code, where):
+        self.code = code
+        msg = lib().moc_strerror(code).decode()
+        hip = lib().moc_last_hip_error() if code == -4 else 0
+        super().__init__(f"{where}: {msg} (code {code}" + (f", hipError {hip})" if hip else ")"))
+
+
+def lib():
+    """Load the shared library (build it first with `python -m paper_2304_14463_amd.build`)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} is not built; run python -m paper_2304_14463_amd.build")
+        L = ctypes.CDLL(LIB_PATH)
+        P, I32, I64, VP = ctypes.POINTER, ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p
+        L.moc_graph_upload.argtypes = [I32, VP, VP, VP, VP, I64, I32, P(VP)]
+        L.moc_graph_upload.restype = ctypes.c_int
+        L.moc_graph_info.argtypes = [VP, P(I32), P(I32), P(I32), P(I32)]
+        L.moc_graph_info.restype = ctypes.c_int
+        L.moc_eval_batch.argtypes = [VP, I64, VP, VP, VP, VP, VP]
+        L.moc_eval_batch.restype = ctypes.c_int
+        if hasattr(L, "moc_eval_neighbours"):
+            L.moc_eval_neighbours.argtypes = [VP, I64, VP, VP, VP, I32, VP, VP, VP]
+            L.moc_eval_neighbours.restype = ctypes.c_int
+        L.moc_graph_free.argtypes = [VP]
+        L.moc_graph_free.restype = None
+        L.moc_strerror.argtypes = [ctypes.c_int]
+        L.moc_strerror.restype = ctypes.c_char_p
+        L.moc_last_hip_error.argtypes = []
+        L.moc_last_hip_error.restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def _check(code, where):
+    if code != 0:
+        raise MoccasinError(code, where)
+
+
+def _host(arr, n):
+    a = np.ascontiguousarray(arr, dtype=np.int32).reshape(-1)
+    if a.shape[0] != n:
+        raise ValueError(f"expected {n} int32 values, got {a.shape[0]}")
+    return a
+
+
+def _stream_handle(stream):
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+class Graph:
+    """Handle of an uploaded problem instance (moc_graph_upload / moc_graph_free)."""
+
+    def __init__(self, handle, n, m, C):
+        self._h = handle
+        self.n, self.m, self.C, self.T = n, m, C, n * C
+
+    def free(self):
+        if self._h is not None:
+            lib().moc_graph_free(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def moc_graph_upload(n, in_ptr, in_idx, size, dur, budget, C) -> Graph:
+    in_ptr = _host(in_ptr, n + 1)
+    m = int(in_ptr[-1])
+    in_idx = _host(in_idx, len(np.asarray(in_idx).reshape(-1)))
+    size, dur = _host(size, n), _host(dur, n)
+    h = ctypes.c_void_p()
+    code = lib().moc_graph_upload(n, in_ptr.ctypes.data, in_idx.ctypes.data if in_idx.size else None,
+                                  size.ctypes.data, dur.ctypes.data, int(budget), int(C), ctypes.byref(h))
+    _check(code, "moc_graph_upload")
+    return Graph(h, n, m, int(C))
+
+
+def _cand_ptrs(g, B, starts, ends, active):
+    import torch
+    for t, dt in ((starts, torch.int32), (ends, torch.int32), (active, torch.uint8)):
+        if not t.is_cuda or t.dtype != dt or not t.is_contiguous() or t.numel() != B * g.T:
+            raise ValueError("candidate arrays must be contiguous CUDA tensors [B][T]: int32, int32, uint8")
+    return ctypes.c_void_p(starts.data_ptr()), ctypes.c_void_p(ends.data_ptr()), ctypes.c_void_p(active.data_ptr())
+
+
+def moc_eval_batch(g: Graph, starts, ends, active, out=None, stream=None):
+    """Evaluate B candidates; returns a uint8 CUDA tensor [B][24] holding moc_result records
+    (see results_to_numpy).  Asynchronous on `stream` (default: torch's current stream)."""
+    import torch
+    B = starts.numel() // g.T if g.T else 0
+    ps, pe, pa = _cand_ptrs(g, B, starts, ends, active)
+    if out is None:
+        out = torch.empty((B, RESULT_DTYPE.itemsize), dtype=torch.uint8, device=starts.device)
+    code = lib().moc_eval_batch(g._h, B, ps, pe, pa, ctypes.c_void_p(out.data_ptr()), _stream_handle(stream))
+    _check(code, "moc_eval_batch")
+    return out
+
+
+def moc_eval_neighbours(g: Graph, starts, ends, active, R, want_moves=True, want_best=True, out_moves=None,
+                        out_best=None, stream=None):
+    """Score all single-field moves of B candidates.  Returns (moves, best): uint8 CUDA tensors
+    [B][T*4R][8] (moc_move_score) and [B][16] (moc_best_move), or None where not requested."""
+    import torch
+    B = starts.numel() // g.T if g.T else 0
+    ps, pe, pa = _cand_ptrs(g, B, starts, ends, active)
+    if want_moves and out_moves is None:
+        out_moves = torch.empty((B, g.T * 4 * R, MOVE_SCORE_DTYPE.itemsize), dtype=torch.uint8, device=starts.device)
+    if want_best and out_best is None:
+        out_best = torch.empty((B, BEST_MOVE_DTYPE.itemsize), dtype=torch.uint8, device=starts.device)
+    code = lib().moc_eval_neighbours(
+        g._h, B, ps, pe, pa, int(R),
+        ctypes.c_void_p(out_moves.data_ptr()) if out_moves is not None else None,
+        ctypes.c_void_p(out_best.data_ptr()) if out_best is not None else None, _stream_handle(stream))
+    _check(code, "moc_eval_neighbours")
+    return out_moves, out_best
+
+
+def results_to_numpy(out, dtype=RESULT_DTYPE):
+    """Copy a record tensor to the host (synchronises) and view it as a structured array."""
+    host = out.cpu().numpy()
+    return host.reshape(-1).view(dtype).reshape(host.shape[:-1])

@@ -1,0 +1,188 @@
+"""GPU parity of moc_eval_batch against the CPU oracle: bit-exact on every
+field, through the C ABI (ctypes binding), on the five synthetic workloads and
+on edge-case shapes."""
+import numpy as np
+import pytest
+
+from helpers import F, assert_results_equal, oracle_eval_parallel, upload
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def moc():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2304_14463_amd import moccasin
+    moccasin.lib()
+    return moccasin
+
+
+def to_dev(*arrs):
+    import torch
+    return [torch.from_numpy(np.ascontiguousarray(x)).cuda() for x in arrs]
+
+
+def run_eval(moc, gh, s, e, a):
+    ds, de, da = to_dev(s, e, a)
+    return moc.results_to_numpy(moc.moc_eval_batch(gh, ds, de, da))
+
+
+# ---------------------------------------------------------------- the device generator emits the host's bits
+@pytest.mark.parametrize("cfg", [0, 1, 2, 3, 4])
+def test_device_generator_matches_host(workloads, cfg):
+    import torch
+    from paper_2304_14463_amd.inputs import DeviceWorkload
+    w = workloads(cfg)
+    dw = DeviceWorkload(w)
+    count = min(w.B, 2048 if cfg < 4 else 256)
+    for b0 in (0, w.B // 2 - count // 2, w.B - count):
+        s, e, a = w.candidates(b0, count)
+        ds, de, da = dw.candidates(b0, count)
+        torch.cuda.synchronize()
+        assert (ds.cpu().numpy() == s).all() and (de.cpu().numpy() == e).all() and (da.cpu().numpy() == a).all()
+
+
+# ---------------------------------------------------------------- full workloads
+@pytest.mark.parametrize("cfg", [0, 1, 2, 3])
+def test_eval_parity_full_batch(moc, workloads, cfg):
+    """Configs 0-3 at their full batch size, every candidate compared."""
+    import torch
+    from paper_2304_14463_amd.inputs import DeviceWorkload
+    w = workloads(cfg)
+    gh = upload(moc, w)
+    ds, de, da = DeviceWorkload(w).candidates()
+    gpu = moc.results_to_numpy(moc.moc_eval_batch(gh, ds, de, da))
+    s, e, a = ds.cpu().numpy(), de.cpu().numpy(), da.cpu().numpy()
+    ref = oracle_eval_parallel(w.graph, w.budget, w.C, s, e, a)
+    assert_results_equal(gpu, ref, f"cfg {cfg}")
+    assert (ref[:, F["violations"]] == 0).any() and (ref[:, F["violations"]] > 0).any()
+    # same batch under a budget that splits the violation-free candidates
+    clean = ref[:, F["violations"]] == 0
+    mid = int(np.median(ref[clean, F["peak"]]))
+    gh2 = upload(moc, w, budget=mid)
+    gpu2 = moc.results_to_numpy(moc.moc_eval_batch(gh2, ds, de, da))
+    want = (clean & (ref[:, F["peak"]] <= mid)).astype(np.int64)
+    assert (gpu2["feasible"] == want).all() and 0 < want.sum() < len(want)
+    # determinism: a second launch returns the same bytes
+    again = moc.results_to_numpy(moc.moc_eval_batch(gh, ds, de, da))
+    assert gpu.tobytes() == again.tobytes()
+    gh.free(); gh2.free()
+    torch.cuda.synchronize()
+
+
+def test_eval_parity_largest_workload_sampled(moc, workloads):
+    """Config 4 (n=5000, C=3, T=15000): the GPU evaluates chunks of the full
+    262144-candidate batch in the launch configuration the benchmark times;
+    the oracle checks sampled candidates of every chunk."""
+    import torch
+    from paper_2304_14463_amd.inputs import DeviceWorkload
+    w = workloads(4)
+    gh = upload(moc, w)
+    dw = DeviceWorkload(w)
+    chunk = 32768
+    rng = np.random.default_rng(4)
+    for b0 in range(0, w.B, chunk):
+        ds, de, da = dw.candidates(b0, chunk)
+        gpu = moc.results_to_numpy(moc.moc_eval_batch(gh, ds, de, da))
+        pick = np.sort(np.concatenate([[0, chunk - 1], rng.choice(chunk - 2, 30, replace=False) + 1]))
+        idx = torch.from_numpy(pick).cuda()
+        s, e, a = ds[idx].cpu().numpy(), de[idx].cpu().numpy(), da[idx].cpu().numpy()
+        ref = oracle_eval_parallel(w.graph, w.budget, w.C, s, e, a)
+        assert_results_equal(gpu[pick], ref, f"cfg 4 chunk at {b0}")
+        # properties that hold for every candidate of the chunk
+        assert (gpu["duration"] >= int(w.graph.dur.sum())).all()
+        assert (gpu["feasible"] == ((gpu["violations"] == 0) & (gpu["peak"] <= w.budget))).all()
+        assert (gpu["peak"] > 0).all() and (gpu["peak"] <= w.C * int(w.graph.size.sum())).all()
+        del ds, de, da
+    gh.free()
+
+
+# ---------------------------------------------------------------- edge cases
+def random_candidates(rng, B, n, C, T, wild):
+    """Uniformly random (mostly broken) candidates; `wild` adds out-of-domain values."""
+    lo, hi = (-3, T + 3) if wild else (0, T)
+    s = rng.integers(lo, hi, size=(B, n * C)).astype(np.int32)
+    e = rng.integers(lo, hi, size=(B, n * C)).astype(np.int32)
+    swap = (rng.random((B, n * C)) < 0.7) & (s > e)
+    s, e = np.where(swap, e, s).astype(np.int32), np.where(swap, s, e).astype(np.int32)
+    a = (rng.random((B, n * C)) < 0.6).astype(np.uint8) * rng.integers(1, 256, size=(B, n * C)).astype(np.uint8)
+    return s, e, a
+
+
+@pytest.mark.parametrize("n,C", [(1, 1), (1, 3), (2, 2), (7, 1), (13, 3), (21, 5), (64, 2), (65, 3), (100, 7),
+                                 (341, 3), (513, 2), (1025, 1), (1031, 2), (1537, 4), (2049, 3), (3000, 6)])
+def test_eval_ragged_shapes_random_candidates(moc, n, C):
+    """Shapes around every tile boundary (wave of 64 nodes, 4 copies per lane, workgroup
+    sizes, rows whose byte length is not a multiple of 16) with random DAGs and random,
+    mostly infeasible candidates including out-of-domain positions and a > 1."""
+    from paper_2304_14463_amd.inputs import graph_from_edges
+    rng = np.random.default_rng(n * 131 + C)
+    edges = set()
+    for v in range(1, n):
+        for u in rng.integers(0, v, size=rng.integers(0, 4)):
+            edges.add((int(u), v))
+    if n > 40:   # one node with a very high in-degree, one with a very high out-degree
+        edges |= {(u, n - 1) for u in range(0, n - 1, 2)} | {(0, v) for v in range(1, n, 3)}
+    g = graph_from_edges(n, sorted(edges), rng.integers(0, 1000, n), rng.integers(0, 50, n))
+    T = n * C
+    B = 37
+    s, e, a = random_candidates(rng, B, n, C, T, wild=True)
+    # a few structured rows: everything active on [0,T-1]; all ends equal; only first copies
+    s[0], e[0], a[0] = 0, T - 1, 1
+    e[1] = T - 1
+    a[2].reshape(n, C)[:, 1:] = 0
+    a[2].reshape(n, C)[:, 0] = 1
+    budget = int(g.size.sum()) // 2
+    gh = moc.moc_graph_upload(n, g.in_ptr, g.in_idx, g.size, g.dur, budget, C)
+    import oracle
+    ref = oracle.evaluate(g, budget, C, s, e, a)
+    assert_results_equal(run_eval(moc, gh, s, e, a), ref, f"n={n} C={C}")
+    # unaligned views of the same rows (element-wise load path)
+    import torch
+    pad_s = torch.zeros(B * T + 1, dtype=torch.int32, device="cuda")
+    pad_e = torch.zeros(B * T + 1, dtype=torch.int32, device="cuda")
+    pad_a = torch.zeros(B * T + 1, dtype=torch.uint8, device="cuda")
+    pad_s[1:] = torch.from_numpy(s.reshape(-1)).cuda()
+    pad_e[1:] = torch.from_numpy(e.reshape(-1)).cuda()
+    pad_a[1:] = torch.from_numpy(a.reshape(-1)).cuda()
+    out = moc.moc_eval_batch(gh, pad_s[1:], pad_e[1:], pad_a[1:])
+    assert_results_equal(moc.results_to_numpy(out), ref, f"n={n} C={C} unaligned")
+    gh.free()
+
+
+def test_eval_empty_batch_and_single_candidate(moc, workloads):
+    import torch
+    w = workloads(0)
+    gh = upload(moc, w)
+    empty = [torch.empty((0, w.T), dtype=dt, device="cuda") for dt in (torch.int32, torch.int32, torch.uint8)]
+    out = moc.moc_eval_batch(gh, *empty)
+    assert out.shape[0] == 0
+    s, e, a = w.base()
+    got = run_eval(moc, gh, s[None], e[None], a[None])
+    assert (got["violations"][0], got["peak"][0], got["duration"][0], got["feasible"][0]) == \
+        (0, w.no_remat_peak, int(w.graph.dur.sum()), 0)
+    gh.free()
+
+
+def test_eval_maximum_size(moc):
+    """T at the library's limit (the LDS working set of one candidate fills a compute unit)."""
+    import oracle
+    from paper_2304_14463_amd.inputs import graph_from_edges
+    n, C = moc.MOC_MAX_T, 1
+    rng = np.random.default_rng(7)
+    edges = [(int(rng.integers(max(0, v - 50), v)), v) for v in range(1, n)]
+    g = graph_from_edges(n, edges, rng.integers(1, 100, n), rng.integers(1, 9, n))
+    gh = moc.moc_graph_upload(n, g.in_ptr, g.in_idx, g.size, g.dur, 10**6, C)
+    s = np.tile(np.arange(n, dtype=np.int32), (3, 1))
+    e = np.minimum(s + rng.integers(0, 60, size=s.shape), n - 1).astype(np.int32)
+    a = np.ones_like(s, dtype=np.uint8)
+    s[1, 100] = s[1, 99]; e[2, 5000] = n   # one collision, one malformed copy
+    ref = oracle.evaluate(g, 10**6, C, s, e, a)
+    assert_results_equal(run_eval(moc, gh, s, e, a), ref, "T = MOC_MAX_T")
+    gh.free()
+    # one more copy per node does not fit
+    with pytest.raises(moc.MoccasinError) as err:
+        moc.moc_graph_upload(n + 1, np.zeros(n + 2, np.int32), np.zeros(0, np.int32), np.ones(n + 1, np.int32),
+                             np.ones(n + 1, np.int32), 1, 1)
+    assert err.value.code == -2
