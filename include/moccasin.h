@@ -63,9 +63,11 @@ extern "C" {
 #define MOC_EHIP      (-4)  /* a HIP runtime call failed; see moc_last_hip_error() */
 #define MOC_EDEVICE   (-5)  /* the graph's device is not the current device */
 
-/* Largest T = n*C an uploaded graph may have (the per-candidate working set
- * -- memory-delta array, packed intervals, start bitmap -- lives in the
- * 160 KB LDS of one compute unit). */
+/* Largest T = n*C an uploaded graph may have: the per-candidate working set
+ * (memory-delta array, packed intervals, start bitmap, queue of extra copies)
+ * lives in the 160 KB LDS of one compute unit.  The queue of extra copies
+ * lowers the bound to 16755 for C = 3 and 16384 for C = 4.  moc_graph_upload
+ * returns MOC_EOVERFLOW for a graph that does not fit. */
 #define MOC_MAX_T 19455
 
 typedef struct moc_graph moc_graph; /* opaque; owns device copies of the graph */

@@ -2,308 +2,473 @@
 // of the paper's Section 2.1) with its whole working set in LDS.
 //
 // Per candidate:
-//   phase 1 (per copy)  the rows of starts/ends/active are streamed with 16-byte
-//            loads, four consecutive copies per lane.  Each copy is classified
-//            (active / live), counted for Eq. (2),(7),(8) and Eq. (1), staged in
-//            LDS as one packed word s | e << 16, and -- if live -- scattered into
-//            the memory-delta array (+m_v at s, -m_v at e+1: closed intervals of
-//            Eq. (4)) and into a bitmap of occupied start positions (Eq. (6)).
-//   phase 2 (a) each thread reduces a contiguous chunk of the delta array to
+//   phase 1  one lane per node, nodes in id order.  The lane holds the C copies
+//            of its node in registers (they were requested from HBM while the
+//            previous candidate was still being reduced), classifies them
+//            (active / live), counts Eq. (2),(7),(8) and Eq. (3), adds the node's
+//            share of Eq. (1), stages each copy in LDS as one packed word
+//            s | e << 16, and scatters every live copy into the memory-delta
+//            array (+m_v at s, -m_v at e+1: the closed intervals of Eq. (4)) and
+//            into a bitmap of occupied start positions (Eq. (6)).  Live copies
+//            i >= 1 are rare; they are queued for phase 2d.
+//   phase 2  (a) each thread reduces a contiguous chunk of the delta array to
 //            (sum, max prefix); chunks combine associatively in position order,
 //            which yields the peak of Eq. (4) without materialising the profile;
 //            (b) popcount of the bitmap: distinct start positions, so that
 //            sum_t max(0, cnt_t - 1) = live copies - distinct starts;
-//            (c) one lane per node (in-degree-sorted slices): Eq. (3) among the
-//            node's own copies and Eq. (5) against the staged copies of every
-//            predecessor.
-// Predicates are counted with wave ballots + scalar popcounts, so violation
-// counters live in scalar registers.  All arithmetic is integer: results do not
-// depend on the order in which lanes or workgroups run.
+//            (c) one lane per edge (u,v): Eq. (5) for copy 0 of v against the staged
+//            copies of u.  The edge list is the same for every candidate and is
+//            read in independent batches, so no lane waits on a chain of loads;
+//            (d) Eq. (5) for the queued copies i >= 1, one lane per copy.
+// All arithmetic is integer: results do not depend on the order in which
+// lanes or workgroups run.
 #include "moc_internal.h"
 
 namespace {
 
 constexpr int kRedStride = 8;  // ints per wave in the cross-wave exchange area
+constexpr int kMaxIters = 8;   // nodes per lane the register-resident kernel is built for
 
 struct LdsLayout {
   int chunk;       // delta entries per thread (odd: conflict-free strided reads)
   int delta_len;   // NT * chunk >= T + 1
-  int packed_len;  // >= T + 6, multiple of 4
+  int packed_len;  // >= T, multiple of 4
   int occ_words;   // ceil(T / 32)
+  int queue_cap;   // 16-bit entries per wave: extra copies of the nodes the wave owns (even)
   int bytes;
 };
 
-LdsLayout lds_layout(int T, int nt) {
+LdsLayout lds_layout(int n, int C, int nt, bool with_queue) {
+  const int T = n * C;
   LdsLayout l;
   l.chunk = ((T + 1 + nt - 1) / nt) | 1;
   l.delta_len = nt * l.chunk;
-  l.packed_len = (T + 6 + 3) & ~3;
+  l.packed_len = (T + 3) & ~3;
   l.occ_words = (T + 31) / 32;
-  l.bytes = 4 * (l.delta_len + l.packed_len + l.occ_words + (nt / kWave) * kRedStride);
+  l.queue_cap = with_queue ? kWave * ((n + nt - 1) / nt) * (C - 1) : 0;
+  l.bytes = 4 * (l.delta_len + l.packed_len + l.occ_words + (nt / kWave) * (kRedStride + l.queue_cap / 2));
   return l;
 }
 
-__device__ __forceinline__ int wave_count(bool pred) { return __popcll(__ballot(pred)); }
+struct Lds {
+  int32_t* delta;
+  uint32_t* packed;
+  uint32_t* occ;
+  int32_t* red;
+  uint16_t* queue;   // [waves][queue_cap]
+};
 
-// Four consecutive elements starting at flat index idx.  Elements outside
-// [lo, hi) are returned as 0 on the guarded path; on the vector path the
-// caller masks them.
-template <bool VEC>
-__device__ __forceinline__ void load4(const int32_t* __restrict__ starts, const int32_t* __restrict__ ends,
-                                      const uint8_t* __restrict__ active, int64_t idx, int64_t lo, int64_t hi,
-                                      int64_t total, int (&s)[4], int (&e)[4], uint32_t& a4) {
-  if (VEC && idx + 3 < total) {
-    const int4 sv = *reinterpret_cast<const int4*>(starts + idx);
-    const int4 ev = *reinterpret_cast<const int4*>(ends + idx);
-    a4 = *reinterpret_cast<const uint32_t*>(active + idx);
-    s[0] = sv.x; s[1] = sv.y; s[2] = sv.z; s[3] = sv.w;
-    e[0] = ev.x; e[1] = ev.y; e[2] = ev.z; e[3] = ev.w;
-  } else {
-    a4 = 0;
+__device__ __forceinline__ Lds carve(uint32_t* base, const LdsLayout& lay, int nw) {
+  Lds l;
+  l.delta = reinterpret_cast<int32_t*>(base);
+  l.packed = base + lay.delta_len;
+  l.occ = l.packed + lay.packed_len;
+  l.red = reinterpret_cast<int32_t*>(l.occ + lay.occ_words);
+  l.queue = reinterpret_cast<uint16_t*>(l.red + nw * kRedStride);
+  return l;
+}
+
+template <int CTRL>
+__device__ __forceinline__ int dpp_move(int v) {
+  return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xF, 0xF, true);
+}
+
+// Sum over the 64 lanes, returned in every lane (wave-uniform).
+__device__ __forceinline__ int wave_sum(int v) {
+  v += dpp_move<0xB1>(v);    // quad_perm [1,0,3,2]
+  v += dpp_move<0x4E>(v);    // quad_perm [2,3,0,1]
+  v += dpp_move<0x141>(v);   // row_half_mirror
+  v += dpp_move<0x140>(v);   // row_mirror: every lane of a row of 16 holds the row's sum
+  return __builtin_amdgcn_readlane(v, 0) + __builtin_amdgcn_readlane(v, 16) + __builtin_amdgcn_readlane(v, 32) +
+         __builtin_amdgcn_readlane(v, 48);
+}
+
+__device__ __forceinline__ bool is_live(uint32_t packed) { return (packed & 0xFFFFu) != 0xFFFFu; }
+
+// Eq. (5) for one consumer start x (xs = x << 16) against one staged provider copy:
+// s_u + 1 <= x  and  x <= e_u.  A copy that is not live has s = 0xFFFF and fails.
+__device__ __forceinline__ bool covers(uint32_t pu, uint32_t x, uint32_t xs) { return (pu & 0xFFFFu) < x && pu >= xs; }
+
+// ------------------------------------------------------------------ phase 2 pieces shared by both kernels
+template <int NT>
+__device__ __forceinline__ void reduce_delta(const Lds& L, const LdsLayout& lay, int tid, int lane, int& S, int& P) {
+  S = 0;
+  P = 0;
+  int32_t* d = L.delta + tid * lay.chunk;
+#pragma unroll 5
+  for (int j = 0; j < lay.chunk; ++j) {
+    const int x = d[j];
+    d[j] = 0;
+    S += x;
+    P = max(P, S);
+  }
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      const int64_t i = idx + c;
-      const bool in = i >= lo && i < hi;
-      s[c] = in ? starts[i] : 0;
-      e[c] = in ? ends[i] : 0;
-      a4 |= (in ? (uint32_t)active[i] : 0u) << (8 * c);
+  for (int off = 1; off < kWave; off <<= 1) {   // ordered combine: lane l absorbs lanes l+off..
+    const int S2 = __shfl_down(S, off), P2 = __shfl_down(P, off);
+    if (lane + off < kWave) {
+      P = max(P, S + P2);
+      S += S2;
     }
   }
 }
 
-template <int NT, int CT, bool VEC>
+template <int NT>
+__device__ __forceinline__ int count_distinct_starts(const Lds& L, const LdsLayout& lay, int tid) {
+  int distinct = 0;
+  for (int w = tid; w < lay.occ_words; w += NT) {
+    distinct += __popc(L.occ[w]);
+    L.occ[w] = 0;
+  }
+  return distinct;
+}
+
+// Eq. (5) for copy 0 of every consumer, one lane per edge.  edge_pair[e] = u*C | v*C << 16.
+template <int NT, int CT>
+__device__ __forceinline__ int check_edges(const Lds& L, const GraphView& g, int tid) {
+  int viol = 0;
+  const int C = CT ? CT : g.C;
+#pragma unroll 4
+  for (int e = tid; e < g.m; e += NT) {
+    const uint32_t pair = g.edge_pair[e];
+    const uint32_t pv = L.packed[pair >> 16];
+    const uint32_t x = pv & 0xFFFFu, xs = x << 16;
+    const int ub = (int)(pair & 0xFFFFu);
+    bool cov = false;
+    if constexpr (CT > 0) {
+#pragma unroll
+      for (int q = 0; q < CT; ++q) cov = cov || covers(L.packed[ub + q], x, xs);
+    } else {
+      for (int q = 0; q < C; ++q) cov = cov || covers(L.packed[ub + q], x, xs);
+    }
+    viol += (is_live(pv) && !cov) ? 1 : 0;
+  }
+  return viol;
+}
+
+// Cross-wave combine.  Every wave leaves its partial results in LDS; after the
+// barrier the lanes of wave 0 pick up one wave each and reduce in registers.
+template <int NT>
+__device__ __forceinline__ void finish(const Lds& L, const GraphView& g, int tid, int lane, int wave, int S, int P,
+                                       int viol, int nlive, int distinct, int dur, moc_result* __restrict__ out,
+                                       int64_t b) {
+  constexpr int NW = NT / kWave;
+  viol = wave_sum(viol);
+  nlive = wave_sum(nlive);
+  distinct = wave_sum(distinct);
+  dur = wave_sum(dur);
+  if constexpr (NW > 1) {
+    if (lane == 0) {
+      int32_t* r = L.red + wave * kRedStride;
+      r[0] = S; r[1] = P; r[2] = viol + nlive - distinct; r[3] = dur;
+    }
+    __syncthreads();
+    if (wave != 0) return;
+    const bool has = lane < NW;
+    const int32_t* r = L.red + (has ? lane : 0) * kRedStride;
+    S = has ? r[0] : 0;
+    P = has ? r[1] : 0;
+    viol = wave_sum(has ? r[2] : 0);
+    dur = wave_sum(has ? r[3] : 0);
+#pragma unroll
+    for (int off = 1; off < NW; off <<= 1) {
+      const int S2 = __shfl_down(S, off), P2 = __shfl_down(P, off);
+      P = max(P, S + P2);   // lanes >= NW hold (0, 0), the identity
+      S += S2;
+    }
+  } else {
+    viol += nlive - distinct;   // Eq. (6): live copies minus distinct start positions
+    __syncthreads();
+  }
+  if (tid == 0) {
+    moc_result res;
+    res.peak = P;
+    res.duration = dur;
+    res.violations = viol;
+    res.feasible = (viol == 0 && (int64_t)P <= g.budget) ? 1 : 0;
+    out[b] = res;
+  }
+}
+
+// ------------------------------------------------------------------ register-resident kernel
+template <int CT>
+struct NodeIn {
+  int s[CT], e[CT];
+  uint32_t a;   // CT flag bytes, byte i = a of copy i (bytes above CT are not used)
+};
+
+struct __attribute__((packed, aligned(4))) Int3 { int x, y, z; };
+
+template <int CT>
+__device__ __forceinline__ void load_node(const int32_t* __restrict__ starts, const int32_t* __restrict__ ends,
+                                          const uint8_t* __restrict__ active, int64_t off, int64_t total,
+                                          NodeIn<CT>& r) {
+  if constexpr (CT == 1) {
+    r.s[0] = starts[off]; r.e[0] = ends[off]; r.a = active[off];
+  } else if constexpr (CT == 2) {
+    const int2 sv = *reinterpret_cast<const int2*>(starts + off);
+    const int2 ev = *reinterpret_cast<const int2*>(ends + off);
+    r.s[0] = sv.x; r.s[1] = sv.y; r.e[0] = ev.x; r.e[1] = ev.y;
+    r.a = *reinterpret_cast<const uint16_t*>(active + off);
+  } else if constexpr (CT == 3) {
+    const Int3 sv = *reinterpret_cast<const Int3*>(starts + off);
+    const Int3 ev = *reinterpret_cast<const Int3*>(ends + off);
+    r.s[0] = sv.x; r.s[1] = sv.y; r.s[2] = sv.z; r.e[0] = ev.x; r.e[1] = ev.y; r.e[2] = ev.z;
+    // one (unaligned) 4-byte read covers the 3 flags; the last node of the batch reads
+    // the 4 bytes that end with the array and shifts
+    const int64_t at = off < total - 4 ? off : total - 4;
+    uint32_t w;
+    __builtin_memcpy(&w, active + at, 4);
+    r.a = w >> (8 * (int)(off - at));
+  } else {
+    const int4 sv = *reinterpret_cast<const int4*>(starts + off);
+    const int4 ev = *reinterpret_cast<const int4*>(ends + off);
+    r.s[0] = sv.x; r.s[1] = sv.y; r.s[2] = sv.z; r.s[3] = sv.w;
+    r.e[0] = ev.x; r.e[1] = ev.y; r.e[2] = ev.z; r.e[3] = ev.w;
+    r.a = *reinterpret_cast<const uint32_t*>(active + off);
+  }
+}
+
+template <int NT, int CT, int ITERS>
 __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, const int32_t* __restrict__ starts,
                                                         const int32_t* __restrict__ ends,
                                                         const uint8_t* __restrict__ active,
                                                         moc_result* __restrict__ out, LdsLayout lay) {
   constexpr int NW = NT / kWave;
-  extern __shared__ uint32_t lds[];
-  int32_t* delta = reinterpret_cast<int32_t*>(lds);
-  uint32_t* packed = lds + lay.delta_len;
-  uint32_t* occ = packed + lay.packed_len;
-  int32_t* red = reinterpret_cast<int32_t*>(occ + lay.occ_words);
-
+  extern __shared__ uint32_t lds_raw[];
+  const Lds L = carve(lds_raw, lay, NW);
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
-  const int T = g.T;
-  const int C = CT ? CT : g.C;
+  const int T = g.T, n = g.n;
   const int64_t total = B * (int64_t)T;
 
-  for (int i = tid; i < lay.delta_len; i += NT) delta[i] = 0;
-  for (int i = tid; i < lay.occ_words; i += NT) occ[i] = 0;
+  for (int i = tid; i < lay.delta_len; i += NT) L.delta[i] = 0;
+  for (int i = tid; i < lay.occ_words; i += NT) L.occ[i] = 0;
+
+  // the nodes of this lane never change: keep m_v, w_v in registers
+  int2 sd[ITERS];
+#pragma unroll
+  for (int it = 0; it < ITERS; ++it) {
+    const int v = it * NT + tid;
+    sd[it] = v < n ? g.size_dur[v] : make_int2(0, 0);
+  }
+  NodeIn<CT> in[ITERS];
+  auto request = [&](int64_t b) {
+    const int64_t row = b * T;
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+      const int v = it * NT + tid;
+      if (v < n) load_node<CT>(starts, ends, active, row + (int64_t)v * CT, total, in[it]);
+    }
+  };
+  if ((int64_t)blockIdx.x < B) request(blockIdx.x);
+  __syncthreads();
+
+  uint16_t* my_queue = L.queue + wave * lay.queue_cap;   // extra copies of this wave's nodes
+  for (int64_t b = blockIdx.x; b < B; b += gridDim.x) {
+    int viol = 0, nlive = 0, dur = 0;   // per lane
+    int nq = 0;                         // wave-uniform: entries in my_queue
+
+    // ---------------- phase 1: per node, copies in registers
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+      const int v = it * NT + tid;
+      const bool isn = v < n;
+      if (it * NT + wave * kWave >= n) break;   // whole wave past the last node
+      const NodeIn<CT>& r = in[it];
+      bool act[CT], live[CT];
+      uint32_t pk[CT];
+      int nact = 0;
+#pragma unroll
+      for (int i = 0; i < CT; ++i) {
+        act[i] = isn && ((r.a >> (8 * i)) & 0xFFu) != 0;
+        const bool well = (uint32_t)r.s[i] <= (uint32_t)r.e[i] && (uint32_t)r.e[i] < (uint32_t)T;   // Eq. (2), (8)
+        live[i] = act[i] && well;
+        viol += (act[i] && !well) ? 1 : 0;
+        nact += act[i] ? 1 : 0;
+        nlive += live[i] ? 1 : 0;
+        pk[i] = live[i] ? ((uint32_t)r.s[i] | ((uint32_t)r.e[i] << 16)) : MOC_DEAD;
+      }
+      viol += (isn && !act[0]) ? 1 : 0;   // Eq. (7)
+      dur += nact * sd[it].y;              // Eq. (1)
+#pragma unroll
+      for (int i = 0; i + 1 < CT; ++i) {   // Eq. (3): against the next live copy
+        bool seen = false, late = false;
+#pragma unroll
+        for (int j = i + 1; j < CT; ++j) {
+          late = late || (!seen && live[j] && r.e[i] > r.s[j]);
+          seen = seen || live[j];
+        }
+        viol += (live[i] && late) ? 1 : 0;
+      }
+#pragma unroll
+      for (int i = 0; i < CT; ++i) {
+        if (isn) L.packed[v * CT + i] = pk[i];
+        if (live[i]) {
+          atomicAdd(&L.delta[r.s[i]], sd[it].x);          // Eq. (4): allocated at s ...
+          atomicAdd(&L.delta[r.e[i] + 1], -sd[it].x);     // ... released after e
+          atomicOr(&L.occ[r.s[i] >> 5], 1u << (r.s[i] & 31));   // Eq. (6)
+        }
+        if (i >= 1) {   // queue the rare live extra copies for phase 2d
+          const uint64_t mask = __ballot(live[i]);
+          if (mask != 0) {
+            const int rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0));
+            if (live[i]) my_queue[nq + rank] = (uint16_t)(v * CT + i);
+            nq += (int)__popcll(mask);
+          }
+        }
+      }
+    }
+    // the registers are free again: request the next candidate of this workgroup; it
+    // arrives while phase 2 runs
+    if (b + gridDim.x < B) request(b + gridDim.x);
+    __syncthreads();
+
+    // ---------------- phase 2
+    int S, P;
+    reduce_delta<NT>(L, lay, tid, lane, S, P);
+    const int distinct = count_distinct_starts<NT>(L, lay, tid);
+    viol += check_edges<NT, CT>(L, g, tid);
+    // (d) Eq. (5), queued copies i >= 1 of this wave's nodes; one lane per copy, plain CSR
+    if constexpr (CT > 1) {
+      for (int q = lane; q < nq; q += kWave) {
+        const int k = my_queue[q];
+        const int v = k / CT;
+        const uint32_t pv = L.packed[k];
+        const uint32_t x = pv & 0xFFFFu, xs = x << 16;
+        for (int ed = g.in_ptr[v]; ed < g.in_ptr[v + 1]; ++ed) {
+          const int ub = g.in_idx[ed] * CT;
+          bool cov = false;
+#pragma unroll
+          for (int j = 0; j < CT; ++j) cov = cov || covers(L.packed[ub + j], x, xs);
+          viol += cov ? 0 : 1;
+        }
+      }
+    }
+    finish<NT>(L, g, tid, lane, wave, S, P, viol, nlive, distinct, dur, out, b);
+  }
+}
+
+// ------------------------------------------------------------------ general kernel: any C, any n, any alignment
+template <int NT>
+__global__ __launch_bounds__(NT) void eval_batch_general_kernel(GraphView g, int64_t B,
+                                                                const int32_t* __restrict__ starts,
+                                                                const int32_t* __restrict__ ends,
+                                                                const uint8_t* __restrict__ active,
+                                                                moc_result* __restrict__ out, LdsLayout lay) {
+  constexpr int NW = NT / kWave;
+  extern __shared__ uint32_t lds_raw[];
+  const Lds L = carve(lds_raw, lay, NW);
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  const int T = g.T, n = g.n, C = g.C;
+
+  for (int i = tid; i < lay.delta_len; i += NT) L.delta[i] = 0;
+  for (int i = tid; i < lay.occ_words; i += NT) L.occ[i] = 0;
   __syncthreads();
 
   for (int64_t b = blockIdx.x; b < B; b += gridDim.x) {
     const int64_t row = b * T;
-    const int head = VEC ? (int)(row & 3) : 0;   // copies of the previous row sharing the first 16 bytes
-    const int64_t base = row - head;
-    const int nslots = (head + T + 3) >> 2;
-    const int iters = (nslots + NT - 1) / NT;
-
-    int viol = 0, nlive = 0;   // wave-uniform counters
-    int dur = 0;               // per lane
-
-    // ---------------- phase 1: per copy
-    for (int it = 0; it < iters; ++it) {
-      const int slot = it * NT + tid;
-      const bool ok = slot < nslots;
-      int s[4] = {0, 0, 0, 0}, e[4] = {0, 0, 0, 0};
-      uint32_t a4 = 0;
-      if (ok) load4<VEC>(starts, ends, active, base + 4 * (int64_t)slot, row, row + T, total, s, e, a4);
-      uint32_t pk[4];
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const int kk = 4 * slot + c - head;                       // copy index within the row
-        const bool valid = ok && (unsigned)kk < (unsigned)T;
-        const uint32_t a = (a4 >> (8 * c)) & 0xFFu;
-        const bool act = valid && a != 0;
-        const bool well = (uint32_t)s[c] <= (uint32_t)e[c] && (uint32_t)e[c] < (uint32_t)T;   // Eq. (2), (8)
+    int viol = 0, nlive = 0, dur = 0;
+    // phase 1: per node, copies read one by one
+    for (int v = tid; v < n; v += NT) {
+      const int2 sd = g.size_dur[v];
+      int prev_end = -1;   // end of the latest live copy seen so far (Eq. (3))
+      for (int i = 0; i < C; ++i) {
+        const int64_t at = row + (int64_t)v * C + i;
+        const int s = starts[at], e = ends[at];
+        const bool act = active[at] != 0;
+        const bool well = (uint32_t)s <= (uint32_t)e && (uint32_t)e < (uint32_t)T;
         const bool live = act && well;
-        const int v = (int)((unsigned)kk / (unsigned)C);
-        const bool first_off = valid && a == 0 && kk == v * C;   // Eq. (7)
-        viol += wave_count((act && !well) || first_off);
-        nlive += wave_count(live);
-        int2 sd = make_int2(0, 0);
-        if (act) sd = g.size_dur[v];
-        dur += sd.y;                                              // Eq. (1)
-        pk[c] = live ? ((uint32_t)s[c] | ((uint32_t)e[c] << 16)) : MOC_DEAD;
+        viol += (act && !well) ? 1 : 0;
+        if (i == 0) viol += act ? 0 : 1;
+        dur += act ? sd.y : 0;
+        L.packed[v * C + i] = live ? ((uint32_t)s | ((uint32_t)e << 16)) : MOC_DEAD;
         if (live) {
-          atomicAdd(&delta[s[c]], sd.x);                          // Eq. (4): allocated at s ...
-          atomicAdd(&delta[e[c] + 1], -sd.x);                     // ... released after e
-          atomicOr(&occ[s[c] >> 5], 1u << (s[c] & 31));           // Eq. (6)
+          nlive += 1;
+          viol += prev_end > s ? 1 : 0;
+          prev_end = e;
+          atomicAdd(&L.delta[s], sd.x);
+          atomicAdd(&L.delta[e + 1], -sd.x);
+          atomicOr(&L.occ[s >> 5], 1u << (s & 31));
         }
       }
-      if (ok) *reinterpret_cast<uint4*>(&packed[4 * slot]) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
     }
     __syncthreads();
 
-    // ---------------- phase 2a: (sum, max prefix) of this thread's chunk, then of the wave
-    int S = 0, P = 0;
-    {
-      int32_t* d = delta + tid * lay.chunk;
-      for (int j = 0; j < lay.chunk; ++j) {
-        const int x = d[j];
-        d[j] = 0;
-        S += x;
-        P = max(P, S);
+    int S, P;
+    reduce_delta<NT>(L, lay, tid, lane, S, P);
+    const int distinct = count_distinct_starts<NT>(L, lay, tid);
+    viol += check_edges<NT, 0>(L, g, tid);
+    for (int i = 1; i < C; ++i)   // Eq. (5) for the copies i >= 1 of every consumer
+      for (int e = tid; e < g.m; e += NT) {
+        const uint32_t pair = g.edge_pair[e];
+        const uint32_t pv = L.packed[(pair >> 16) + i];
+        const uint32_t x = pv & 0xFFFFu, xs = x << 16;
+        bool cov = false;
+        for (int q = 0; q < C; ++q) cov = cov || covers(L.packed[(pair & 0xFFFFu) + q], x, xs);
+        viol += (is_live(pv) && !cov) ? 1 : 0;
       }
-    }
-#pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) {
-      const int S2 = __shfl_down(S, off), P2 = __shfl_down(P, off);
-      if (lane + off < kWave) {
-        P = max(P, S + P2);
-        S += S2;
-      }
-    }
-
-    // ---------------- phase 2b: distinct start positions
-    int distinct = 0;
-    for (int w = tid; w < lay.occ_words; w += NT) {
-      distinct += __popc(occ[w]);
-      occ[w] = 0;
-    }
-
-    // ---------------- phase 2c: per node, Eq. (3) and Eq. (5)
-    for (int sl = wave; sl < g.n_slices; sl += NW) {
-      const int p = sl * kWave + lane;
-      const uint32_t info = g.slot_info[p];
-      const bool is_node = p < g.n;
-      const int kbase = head + (int)(info & 0xFFFFu);
-      const int deg = (int)(info >> 16);
-      const int e0 = g.ell_ptr[sl];
-      const int width = (g.ell_ptr[sl + 1] - e0) / kWave;
-      if constexpr (CT > 0) {
-        uint32_t pv[CT], x[CT], xs[CT];
-        bool lv[CT];
-#pragma unroll
-        for (int i = 0; i < CT; ++i) {
-          pv[i] = is_node ? packed[kbase + i] : MOC_DEAD;
-          lv[i] = pv[i] != MOC_DEAD;
-          x[i] = pv[i] & 0xFFFFu;   // start of the consumer copy
-          xs[i] = x[i] << 16;
-        }
-#pragma unroll
-        for (int i = 0; i + 1 < CT; ++i) {   // Eq. (3): against the next live copy
-          bool seen = false, late = false;
-#pragma unroll
-          for (int j = i + 1; j < CT; ++j) {
-            late = late || (!seen && lv[j] && (pv[i] >> 16) > x[j]);
-            seen = seen || lv[j];
-          }
-          viol += wave_count(lv[i] && late);
-        }
-        for (int j = 0; j < width; ++j) {
-          const int ub = head + (int)g.ell_pred[e0 + j * kWave + lane];
-          const bool has = j < deg;
-          uint32_t pu[CT];
-#pragma unroll
-          for (int q = 0; q < CT; ++q) pu[q] = packed[ub + q];
-#pragma unroll
-          for (int i = 0; i < CT; ++i) {
-            bool cov = false;   // Eq. (5): s_u + 1 <= s_v  and  s_v <= e_u
-#pragma unroll
-            for (int q = 0; q < CT; ++q) cov = cov || ((pu[q] & 0xFFFFu) < x[i] && pu[q] >= xs[i]);
-            viol += wave_count(has && lv[i] && !cov);
-          }
-        }
-      } else {
-        for (int i = 0; i < C; ++i) {
-          const uint32_t pvi = is_node ? packed[kbase + i] : MOC_DEAD;
-          const bool lvi = pvi != MOC_DEAD;
-          const uint32_t xi = pvi & 0xFFFFu, xsi = xi << 16;
-          bool seen = false, late = false;
-          for (int j = i + 1; j < C; ++j) {
-            const uint32_t pvj = is_node ? packed[kbase + j] : MOC_DEAD;
-            const bool lvj = pvj != MOC_DEAD;
-            late = late || (!seen && lvj && (pvi >> 16) > (pvj & 0xFFFFu));
-            seen = seen || lvj;
-          }
-          viol += wave_count(lvi && late);
-          for (int j = 0; j < width; ++j) {
-            const int ub = head + (int)g.ell_pred[e0 + j * kWave + lane];
-            bool cov = false;
-            for (int q = 0; q < C; ++q) {
-              const uint32_t pu = packed[ub + q];
-              cov = cov || ((pu & 0xFFFFu) < xi && pu >= xsi);
-            }
-            viol += wave_count(j < deg && lvi && !cov);
-          }
-        }
-      }
-    }
-
-    // ---------------- combine
-#pragma unroll
-    for (int off = kWave / 2; off > 0; off >>= 1) {
-      dur += __shfl_xor(dur, off);
-      distinct += __shfl_xor(distinct, off);
-    }
-    if (lane == 0) {
-      int32_t* r = red + wave * kRedStride;
-      r[0] = S; r[1] = P; r[2] = viol; r[3] = nlive; r[4] = distinct; r[5] = dur;
-    }
-    __syncthreads();
-    if (tid == 0) {
-      int Sa = 0, Pa = 0, va = 0, la = 0, da = 0, ua = 0;
-      for (int w = 0; w < NW; ++w) {
-        const int32_t* r = red + w * kRedStride;
-        Pa = max(Pa, Sa + r[1]);
-        Sa += r[0];
-        va += r[2]; la += r[3]; da += r[4]; ua += r[5];
-      }
-      va += la - da;   // Eq. (6): live copies minus distinct start positions
-      moc_result res;
-      res.peak = Pa;
-      res.duration = ua;
-      res.violations = va;
-      res.feasible = (va == 0 && (int64_t)Pa <= g.budget) ? 1 : 0;
-      out[b] = res;
-    }
+    finish<NT>(L, g, tid, lane, wave, S, P, viol, nlive, distinct, dur, out, b);
   }
 }
 
-template <int NT, int CT, bool VEC>
-int launch(const moc_graph* g, int64_t B, const int32_t* starts, const int32_t* ends, const uint8_t* active,
-           moc_result* out, hipStream_t stream) {
-  const LdsLayout lay = lds_layout(g->view.T, NT);
+// ------------------------------------------------------------------ host side
+template <typename K>
+int launch_kernel(K kern, int nt, const moc_graph* g, const LdsLayout& lay, int64_t B, const int32_t* starts,
+                  const int32_t* ends, const uint8_t* active, moc_result* out, hipStream_t stream) {
   if (lay.bytes > g->max_lds) return MOC_EOVERFLOW;
-  auto kern = eval_batch_kernel<NT, CT, VEC>;
   MOC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                               lay.bytes));
   int per_cu = 0;
-  MOC_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, NT, lay.bytes));
+  MOC_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, nt, lay.bytes));
   if (per_cu < 1) per_cu = 1;
   const int64_t resident = (int64_t)per_cu * g->num_cu;
   const unsigned grid = (unsigned)(B < resident ? B : resident);
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(NT), lay.bytes, stream, g->view, B, starts, ends, active, out, lay);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(nt), lay.bytes, stream, g->view, B, starts, ends, active, out, lay);
   MOC_HIP(hipGetLastError());
   return MOC_OK;
 }
 
-template <int NT, bool VEC>
-int launch_c(const moc_graph* g, int64_t B, const int32_t* s, const int32_t* e, const uint8_t* a, moc_result* out,
-             hipStream_t st) {
-  switch (g->view.C) {
-    case 1: return launch<NT, 1, VEC>(g, B, s, e, a, out, st);
-    case 2: return launch<NT, 2, VEC>(g, B, s, e, a, out, st);
-    case 3: return launch<NT, 3, VEC>(g, B, s, e, a, out, st);
-    case 4: return launch<NT, 4, VEC>(g, B, s, e, a, out, st);
-    default: return launch<NT, 0, VEC>(g, B, s, e, a, out, st);
+template <int NT, int CT, int IT = kMaxIters>
+int launch_iters(int iters, const moc_graph* g, const LdsLayout& lay, int64_t B, const int32_t* s, const int32_t* e,
+                 const uint8_t* a, moc_result* out, hipStream_t st) {
+  if constexpr (IT == 0) {
+    return MOC_EINVAL;
+  } else {
+    if (iters == IT) return launch_kernel(eval_batch_kernel<NT, CT, IT>, NT, g, lay, B, s, e, a, out, st);
+    return launch_iters<NT, CT, IT - 1>(iters, g, lay, B, s, e, a, out, st);
   }
 }
 
-template <bool VEC>
+template <int NT>
 int launch_nt(const moc_graph* g, int64_t B, const int32_t* s, const int32_t* e, const uint8_t* a, moc_result* out,
-              hipStream_t st) {
-  // Workgroup size by row length: one wave per candidate while a row is a few
-  // vector loads per lane, a full 1024-thread workgroup for the longest rows.
-  const int T = g->view.T;
-  if (T <= 1024) return launch_c<64, VEC>(g, B, s, e, a, out, st);
-  if (T <= 6144) return launch_c<256, VEC>(g, B, s, e, a, out, st);
-  return launch_c<1024, VEC>(g, B, s, e, a, out, st);
+              hipStream_t st, bool fast_ok) {
+  const int n = g->view.n, C = g->view.C;
+  const int iters = (n + NT - 1) / NT;
+  if (fast_ok && iters <= kMaxIters) {
+    const LdsLayout lay = lds_layout(n, C, NT, true);
+    switch (C) {
+      case 1: return launch_iters<NT, 1>(iters, g, lay, B, s, e, a, out, st);
+      case 2: return launch_iters<NT, 2>(iters, g, lay, B, s, e, a, out, st);
+      case 3: return launch_iters<NT, 3>(iters, g, lay, B, s, e, a, out, st);
+      case 4: return launch_iters<NT, 4>(iters, g, lay, B, s, e, a, out, st);
+      default: break;
+    }
+  }
+  return launch_kernel(eval_batch_general_kernel<NT>, NT, g, lds_layout(n, C, NT, false), B, s, e, a, out, st);
+}
+
+int block_threads(int n) {
+  // Workgroup size by node count: one wave per candidate for small graphs, a full
+  // 1024-thread workgroup (one per compute unit) for the largest.
+  return n <= kMaxIters * 64 ? 64 : n <= kMaxIters * 256 ? 256 : 1024;
 }
 
 }  // namespace
+
+int moc_eval_lds_bytes(int n, int C) {
+  const int nt = block_threads(n);
+  const bool queue = C <= 4 && (n + nt - 1) / nt <= kMaxIters;
+  return lds_layout(n, C, nt, queue).bytes;
+}
 
 extern "C" int moc_eval_batch(const moc_graph* g, int64_t B, const int32_t* starts, const int32_t* ends,
                               const uint8_t* active, moc_result* out, void* hip_stream) {
@@ -314,8 +479,17 @@ extern "C" int moc_eval_batch(const moc_graph* g, int64_t B, const int32_t* star
   int dev = -1;
   MOC_HIP(hipGetDevice(&dev));
   if (dev != g->device) return MOC_EDEVICE;
-  const bool vec = ((((uintptr_t)starts | (uintptr_t)ends) & 15) == 0) && (((uintptr_t)active & 3) == 0);
+  const int n = g->view.n, C = g->view.C;
+  // The register-resident kernel reads the C copies of a node as one vector: rows must be
+  // aligned to the vector (they are when the base pointers are, since a row is n vectors).
+  const uintptr_t se = (uintptr_t)starts | (uintptr_t)ends;
+  bool fast_ok = C <= 4 && B * (int64_t)n * C >= 4;
+  if (C == 2) fast_ok = fast_ok && (se & 7) == 0 && ((uintptr_t)active & 1) == 0;
+  if (C == 4) fast_ok = fast_ok && (se & 15) == 0 && ((uintptr_t)active & 3) == 0;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  return vec ? launch_nt<true>(g, B, starts, ends, active, out, st)
-             : launch_nt<false>(g, B, starts, ends, active, out, st);
+  switch (block_threads(n)) {
+    case 64: return launch_nt<64>(g, B, starts, ends, active, out, st, fast_ok);
+    case 256: return launch_nt<256>(g, B, starts, ends, active, out, st, fast_ok);
+    default: return launch_nt<1024>(g, B, starts, ends, active, out, st, fast_ok);
+  }
 }

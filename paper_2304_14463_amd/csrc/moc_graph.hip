@@ -2,16 +2,13 @@
 // and preprocessing of the problem instance (paper, Section 1 problem
 // statement and Section 2.1: DAG, durations w_v, sizes m_v, budget M, C).
 //
-// The kernels walk precedence constraints (Eq. (5)) node by node, one lane
-// per consumer node.  To keep the 64 lanes of a wavefront on equal trip
-// counts, nodes are sorted by in-degree and their predecessor lists stored as
-// sliced ELL: 64 nodes per slice, slice width = largest in-degree in the
-// slice, column-major so that edge j of the 64 nodes is one contiguous
-// 128-byte read.
+// The evaluation kernel checks precedence constraints (Eq. (5)) one lane per
+// edge, so the edges are also stored as a flat list of packed (u*C, v*C)
+// pairs in consumer order; the neighbourhood kernel walks the in- and
+// out-edge CSR of single nodes.
 #include <algorithm>
 #include <cstring>
 #include <new>
-#include <numeric>
 #include <vector>
 
 #include "moc_internal.h"
@@ -65,28 +62,10 @@ int moc_graph_upload(int32_t n, const int32_t* in_ptr, const int32_t* in_idx, co
     std::vector<int2> size_dur(n);
     for (int v = 0; v < n; ++v) size_dur[v] = make_int2(size[v], dur[v]);
 
-    // nodes by in-degree, largest first (stable: ties keep id order)
-    std::vector<int> order(n);
-    std::iota(order.begin(), order.end(), 0);
-    std::stable_sort(order.begin(), order.end(), [&](int a, int b) {
-      return in_ptr[a + 1] - in_ptr[a] > in_ptr[b + 1] - in_ptr[b];
-    });
-    const int n_slices = (n + kWave - 1) / kWave;
-    std::vector<uint32_t> slot_info((size_t)n_slices * kWave, MOC_DEAD);
-    std::vector<int32_t> ell_ptr(n_slices + 1, 0);
-    for (int sl = 0; sl < n_slices; ++sl) {
-      const int v0 = order[sl * kWave];
-      ell_ptr[sl + 1] = ell_ptr[sl] + (in_ptr[v0 + 1] - in_ptr[v0]) * kWave;
-    }
-    std::vector<uint16_t> ell_pred(ell_ptr[n_slices], 0);
-    for (int p = 0; p < n; ++p) {
-      const int v = order[p], deg = in_ptr[v + 1] - in_ptr[v];
-      if (deg > 0xFFFF) return MOC_EOVERFLOW;
-      slot_info[p] = (uint32_t)(v * C) | ((uint32_t)deg << 16);
-      const int sl = p / kWave, lane = p % kWave;
-      for (int j = 0; j < deg; ++j)
-        ell_pred[ell_ptr[sl] + j * kWave + lane] = (uint16_t)(in_idx[in_ptr[v] + j] * C);
-    }
+    std::vector<uint32_t> edge_pair(m);
+    for (int v = 0; v < n; ++v)
+      for (int q = in_ptr[v]; q < in_ptr[v + 1]; ++q)
+        edge_pair[q] = (uint32_t)(in_idx[q] * C) | ((uint32_t)(v * C) << 16);
 
     // out-edge CSR (consumers of every node), used by the neighbourhood kernel
     std::vector<int32_t> out_ptr(n + 1, 0), out_idx(m);
@@ -111,12 +90,14 @@ int moc_graph_upload(int32_t n, const int32_t* in_ptr, const int32_t* in_idx, co
     }
     g->num_cu = prop.multiProcessorCount;
     g->max_lds = (int)prop.sharedMemPerBlock;
+    if (moc_eval_lds_bytes(n, C) > g->max_lds) {
+      delete g;
+      return MOC_EOVERFLOW;
+    }
     GraphView& w = g->view;
-    w.budget = budget; w.n = n; w.m = m; w.C = C; w.T = T; w.n_slices = n_slices;
+    w.budget = budget; w.n = n; w.m = m; w.C = C; w.T = T;
     if (rc == MOC_OK) rc = upload(g, size_dur, &w.size_dur);
-    if (rc == MOC_OK) rc = upload(g, slot_info, &w.slot_info);
-    if (rc == MOC_OK) rc = upload(g, ell_pred, &w.ell_pred);
-    if (rc == MOC_OK) rc = upload(g, ell_ptr, &w.ell_ptr);
+    if (rc == MOC_OK) rc = upload(g, edge_pair, &w.edge_pair);
     if (rc == MOC_OK) rc = upload(g, in_ptr_v, &w.in_ptr);
     if (rc == MOC_OK) rc = upload(g, in_idx_v, &w.in_idx);
     if (rc == MOC_OK) rc = upload(g, out_ptr, &w.out_ptr);

@@ -15,15 +15,13 @@ constexpr int kWave = 64;  // CDNA wavefront
 // Device-side view of an uploaded graph, passed to kernels by value.
 struct GraphView {
   const int2* size_dur;        // [n] {m_v, w_v}
-  const uint32_t* slot_info;   // [n_slices*64] (v*C) | in-degree << 16, nodes sorted by in-degree (desc)
-  const uint16_t* ell_pred;    // sliced ELL: slice sl, edge j, lane l at ell_ptr[sl] + j*64 + l -> u*C
-  const int32_t* ell_ptr;      // [n_slices+1]
+  const uint32_t* edge_pair;   // [m] edge (u,v) as u*C | v*C << 16, ordered by v
   const int32_t* in_ptr;       // [n+1] plain CSR by in-edges
   const int32_t* in_idx;       // [m]
   const int32_t* out_ptr;      // [n+1] CSR by out-edges
   const int32_t* out_idx;      // [m]
   int64_t budget;
-  int32_t n, m, C, T, n_slices;
+  int32_t n, m, C, T;
 };
 
 struct moc_graph {
@@ -34,6 +32,9 @@ struct moc_graph {
   void* allocs[8];   // device allocations backing `view`
   int n_allocs;
 };
+
+// LDS bytes one workgroup of the evaluation kernel needs for a graph of n nodes, C copies.
+int moc_eval_lds_bytes(int n, int C);
 
 int moc_set_hip_error(hipError_t e);  // records e, returns MOC_EHIP
 
