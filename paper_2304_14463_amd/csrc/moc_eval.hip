@@ -3,23 +3,26 @@
 //
 // Per candidate:
 //   phase 1  one lane per node, nodes in id order.  The lane holds the C copies
-//            of its node in registers (they were requested from HBM while the
-//            previous candidate was still being reduced), classifies them
-//            (active / live), counts Eq. (2),(7),(8) and Eq. (3), adds the node's
-//            share of Eq. (1), stages each copy in LDS as one packed word
-//            s | e << 16, and scatters every live copy into the memory-delta
-//            array (+m_v at s, -m_v at e+1: the closed intervals of Eq. (4)) and
-//            into a bitmap of occupied start positions (Eq. (6)).  Live copies
-//            i >= 1 are rare; they are queued for phase 2d.
+//            of its node in registers (requested from HBM while the previous
+//            candidate was being reduced), classifies them (active / live),
+//            counts Eq. (2),(7),(8) and Eq. (3), adds the node's share of
+//            Eq. (1), stages each copy in LDS as one packed word s | e << 16, and
+//            scatters every live copy into the memory-delta array (+m_v at s,
+//            -m_v at e+1: the closed intervals of Eq. (4)) and into a bitmap of
+//            occupied start positions (Eq. (6)).  A node with a live copy i >= 1
+//            (rare) sets its bit in a second bitmap.
 //   phase 2  (a) each thread reduces a contiguous chunk of the delta array to
 //            (sum, max prefix); chunks combine associatively in position order,
 //            which yields the peak of Eq. (4) without materialising the profile;
-//            (b) popcount of the bitmap: distinct start positions, so that
+//            (b) popcount of the start bitmap: distinct start positions, so that
 //            sum_t max(0, cnt_t - 1) = live copies - distinct starts;
 //            (c) one lane per edge (u,v): Eq. (5) for copy 0 of v against the staged
-//            copies of u.  The edge list is the same for every candidate and is
-//            read in independent batches, so no lane waits on a chain of loads;
-//            (d) Eq. (5) for the queued copies i >= 1, one lane per copy.
+//            copies of u, and for the copies i >= 1 of v where its bit is set.
+//            The edges of a lane never change, so they stay in registers.
+//            Phase 2 touches no global memory; the loads of the workgroup's next
+//            candidate are issued in slices between its steps, so that HBM
+//            streams while the LDS work runs and no wave stalls on a full
+//            memory queue.
 // All arithmetic is integer: results do not depend on the order in which
 // lanes or workgroups run.
 #include "moc_internal.h"
@@ -27,26 +30,27 @@
 namespace {
 
 constexpr int kRedStride = 8;  // ints per wave in the cross-wave exchange area
-constexpr int kMaxIters = 8;   // nodes per lane the register-resident kernel is built for
+constexpr int kMaxIters = 6;   // nodes per lane the register-resident kernel is built for
+constexpr int kEdgesPerNode = 3;   // edges per lane = kEdgesPerNode * nodes per lane
 
 struct LdsLayout {
   int chunk;       // delta entries per thread (odd: conflict-free strided reads)
   int delta_len;   // NT * chunk >= T + 1
   int packed_len;  // >= T, multiple of 4
   int occ_words;   // ceil(T / 32)
-  int queue_cap;   // 16-bit entries per wave: extra copies of the nodes the wave owns (even)
+  int sec_words;   // ceil((T + 1) / 32), two such bitmaps (by candidate parity); 0 in the general kernel
   int bytes;
 };
 
-LdsLayout lds_layout(int n, int C, int nt, bool with_queue) {
+LdsLayout lds_layout(int n, int C, int nt, bool fast) {
   const int T = n * C;
   LdsLayout l;
   l.chunk = ((T + 1 + nt - 1) / nt) | 1;
   l.delta_len = nt * l.chunk;
-  l.packed_len = (T + 3) & ~3;
+  l.packed_len = (T + 4 + 3) & ~3;   // entries T.. stay "not live": target of padding edges
   l.occ_words = (T + 31) / 32;
-  l.queue_cap = with_queue ? kWave * ((n + nt - 1) / nt) * (C - 1) : 0;
-  l.bytes = 4 * (l.delta_len + l.packed_len + l.occ_words + (nt / kWave) * (kRedStride + l.queue_cap / 2));
+  l.sec_words = fast ? (T + 1 + 31) / 32 : 0;
+  l.bytes = 4 * (l.delta_len + l.packed_len + l.occ_words + 2 * l.sec_words + (nt / kWave) * kRedStride);
   return l;
 }
 
@@ -54,8 +58,8 @@ struct Lds {
   int32_t* delta;
   uint32_t* packed;
   uint32_t* occ;
+  uint32_t* sec;     // [2][sec_words]
   int32_t* red;
-  uint16_t* queue;   // [waves][queue_cap]
 };
 
 __device__ __forceinline__ Lds carve(uint32_t* base, const LdsLayout& lay, int nw) {
@@ -63,8 +67,8 @@ __device__ __forceinline__ Lds carve(uint32_t* base, const LdsLayout& lay, int n
   l.delta = reinterpret_cast<int32_t*>(base);
   l.packed = base + lay.delta_len;
   l.occ = l.packed + lay.packed_len;
-  l.red = reinterpret_cast<int32_t*>(l.occ + lay.occ_words);
-  l.queue = reinterpret_cast<uint16_t*>(l.red + nw * kRedStride);
+  l.sec = l.occ + lay.occ_words;
+  l.red = reinterpret_cast<int32_t*>(l.sec + 2 * lay.sec_words);
   return l;
 }
 
@@ -198,34 +202,70 @@ struct NodeIn {
 
 struct __attribute__((packed, aligned(4))) Int3 { int x, y, z; };
 
+// Loads the C copies of one node.  s_row/e_row/a_row point at the candidate's row (uniform
+// over the workgroup, so they live in scalar registers) and `off` = v*C is the lane's
+// 32-bit element offset; `a_last` = largest byte offset at which 4 flag bytes can be read.
 template <int CT>
-__device__ __forceinline__ void load_node(const int32_t* __restrict__ starts, const int32_t* __restrict__ ends,
-                                          const uint8_t* __restrict__ active, int64_t off, int64_t total,
+__device__ __forceinline__ void load_node(const int32_t* __restrict__ s_row, const int32_t* __restrict__ e_row,
+                                          const uint8_t* __restrict__ a_row, uint32_t off, uint32_t a_last,
                                           NodeIn<CT>& r) {
   if constexpr (CT == 1) {
-    r.s[0] = starts[off]; r.e[0] = ends[off]; r.a = active[off];
+    r.s[0] = s_row[off]; r.e[0] = e_row[off]; r.a = a_row[off];
   } else if constexpr (CT == 2) {
-    const int2 sv = *reinterpret_cast<const int2*>(starts + off);
-    const int2 ev = *reinterpret_cast<const int2*>(ends + off);
+    const int2 sv = *reinterpret_cast<const int2*>(s_row + off);
+    const int2 ev = *reinterpret_cast<const int2*>(e_row + off);
     r.s[0] = sv.x; r.s[1] = sv.y; r.e[0] = ev.x; r.e[1] = ev.y;
-    r.a = *reinterpret_cast<const uint16_t*>(active + off);
+    r.a = *reinterpret_cast<const uint16_t*>(a_row + off);
   } else if constexpr (CT == 3) {
-    const Int3 sv = *reinterpret_cast<const Int3*>(starts + off);
-    const Int3 ev = *reinterpret_cast<const Int3*>(ends + off);
+    const Int3 sv = *reinterpret_cast<const Int3*>(s_row + off);
+    const Int3 ev = *reinterpret_cast<const Int3*>(e_row + off);
     r.s[0] = sv.x; r.s[1] = sv.y; r.s[2] = sv.z; r.e[0] = ev.x; r.e[1] = ev.y; r.e[2] = ev.z;
     // one (unaligned) 4-byte read covers the 3 flags; the last node of the batch reads
     // the 4 bytes that end with the array and shifts
-    const int64_t at = off < total - 4 ? off : total - 4;
+    const uint32_t at = off < a_last ? off : a_last;
     uint32_t w;
-    __builtin_memcpy(&w, active + at, 4);
-    r.a = w >> (8 * (int)(off - at));
+    __builtin_memcpy(&w, a_row + at, 4);
+    r.a = w >> (8 * (off - at));
   } else {
-    const int4 sv = *reinterpret_cast<const int4*>(starts + off);
-    const int4 ev = *reinterpret_cast<const int4*>(ends + off);
+    const int4 sv = *reinterpret_cast<const int4*>(s_row + off);
+    const int4 ev = *reinterpret_cast<const int4*>(e_row + off);
     r.s[0] = sv.x; r.s[1] = sv.y; r.s[2] = sv.z; r.s[3] = sv.w;
     r.e[0] = ev.x; r.e[1] = ev.y; r.e[2] = ev.z; r.e[3] = ev.w;
-    r.a = *reinterpret_cast<const uint32_t*>(active + off);
+    r.a = *reinterpret_cast<const uint32_t*>(a_row + off);
   }
+}
+
+// Eq. (5) for one edge held in a register: copy 0 of the consumer always, its copies
+// i >= 1 only if the consumer's bit in `sec` is set.  Returns the violated instances.
+template <int CT>
+__device__ __forceinline__ int check_edge(const Lds& L, const uint32_t* __restrict__ sec, uint32_t pair) {
+  // The pair is the same for every candidate.  Hide that from the optimiser: otherwise it
+  // keeps every address derived from it in a register of its own for the whole kernel.
+  asm volatile("" : "+v"(pair));
+  const int kd = (int)(pair >> 16), ub = (int)(pair & 0xFFFFu);
+  const uint32_t pv = L.packed[kd];
+  uint32_t pu[CT];
+#pragma unroll
+  for (int q = 0; q < CT; ++q) pu[q] = L.packed[ub + q];
+  const uint32_t x = pv & 0xFFFFu, xs = x << 16;
+  bool cov = false;
+#pragma unroll
+  for (int q = 0; q < CT; ++q) cov = cov || covers(pu[q], x, xs);
+  int viol = (is_live(pv) && !cov) ? 1 : 0;
+  if constexpr (CT > 1) {
+    if ((sec[kd >> 5] >> (kd & 31)) & 1u) {
+#pragma unroll
+      for (int i = 1; i < CT; ++i) {
+        const uint32_t pi = L.packed[kd + i];
+        const uint32_t xi = pi & 0xFFFFu, xsi = xi << 16;
+        bool covi = false;
+#pragma unroll
+        for (int q = 0; q < CT; ++q) covi = covi || covers(pu[q], xi, xsi);
+        viol += (is_live(pi) && !covi) ? 1 : 0;
+      }
+    }
+  }
+  return viol;
 }
 
 template <int NT, int CT, int ITERS>
@@ -234,6 +274,7 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
                                                         const uint8_t* __restrict__ active,
                                                         moc_result* __restrict__ out, LdsLayout lay) {
   constexpr int NW = NT / kWave;
+  constexpr int EPT = kEdgesPerNode * ITERS;
   extern __shared__ uint32_t lds_raw[];
   const Lds L = carve(lds_raw, lay, NW);
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
@@ -241,36 +282,45 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
   const int64_t total = B * (int64_t)T;
 
   for (int i = tid; i < lay.delta_len; i += NT) L.delta[i] = 0;
-  for (int i = tid; i < lay.occ_words; i += NT) L.occ[i] = 0;
+  for (int i = tid; i < lay.occ_words + 2 * lay.sec_words; i += NT) L.occ[i] = 0;
+  for (int i = T + tid; i < lay.packed_len; i += NT) L.packed[i] = MOC_DEAD;
 
-  // the nodes of this lane never change: keep m_v, w_v in registers
+  // what a lane owns never changes: m_v, w_v of its nodes and its edges stay in registers
   int2 sd[ITERS];
 #pragma unroll
   for (int it = 0; it < ITERS; ++it) {
     const int v = it * NT + tid;
     sd[it] = v < n ? g.size_dur[v] : make_int2(0, 0);
   }
-  NodeIn<CT> in[ITERS];
-  auto request = [&](int64_t b) {
-    const int64_t row = b * T;
+  uint32_t edge[EPT];
 #pragma unroll
-    for (int it = 0; it < ITERS; ++it) {
-      const int v = it * NT + tid;
-      if (v < n) load_node<CT>(starts, ends, active, row + (int64_t)v * CT, total, in[it]);
-    }
+  for (int j = 0; j < EPT; ++j) {
+    const int e = j * NT + tid;
+    edge[j] = e < g.m ? g.edge_pair[e] : (uint32_t)T << 16;   // padding: consumer entry T is never live
+  }
+  NodeIn<CT> in[ITERS];
+  auto request = [&](int it, int64_t row) {   // loads of node slot `it` of the candidate at `row`
+    const int v = it * NT + tid;
+    const int64_t left = total - row - 4;      // >= 0: the kernel is not used for T < 4
+    const uint32_t a_last = left < 0x7FFFFFFF ? (uint32_t)left : 0x7FFFFFFFu;
+    if (v < n) load_node<CT>(starts + row, ends + row, active + row, (uint32_t)v * CT, a_last, in[it]);
   };
-  if ((int64_t)blockIdx.x < B) request(blockIdx.x);
+  if ((int64_t)blockIdx.x < B) {
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) request(it, (int64_t)blockIdx.x * T);
+  }
   __syncthreads();
 
-  uint16_t* my_queue = L.queue + wave * lay.queue_cap;   // extra copies of this wave's nodes
-  for (int64_t b = blockIdx.x; b < B; b += gridDim.x) {
+  int parity = 0;
+  for (int64_t b = blockIdx.x; b < B; b += gridDim.x, parity ^= 1) {
     int viol = 0, nlive = 0, dur = 0;   // per lane
-    int nq = 0;                         // wave-uniform: entries in my_queue
+    uint32_t* sec = L.sec + parity * lay.sec_words;
 
     // ---------------- phase 1: per node, copies in registers
 #pragma unroll
     for (int it = 0; it < ITERS; ++it) {
-      const int v = it * NT + tid;
+      int v = it * NT + tid;
+      asm volatile("" : "+v"(v));               // as in check_edge: keep derived addresses out of registers
       const bool isn = v < n;
       if (it * NT + wave * kWave >= n) break;   // whole wave past the last node
       const NodeIn<CT>& r = in[it];
@@ -299,6 +349,7 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
         }
         viol += (live[i] && late) ? 1 : 0;
       }
+      bool extra = false;
 #pragma unroll
       for (int i = 0; i < CT; ++i) {
         if (isn) L.packed[v * CT + i] = pk[i];
@@ -307,41 +358,28 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
           atomicAdd(&L.delta[r.e[i] + 1], -sd[it].x);     // ... released after e
           atomicOr(&L.occ[r.s[i] >> 5], 1u << (r.s[i] & 31));   // Eq. (6)
         }
-        if (i >= 1) {   // queue the rare live extra copies for phase 2d
-          const uint64_t mask = __ballot(live[i]);
-          if (mask != 0) {
-            const int rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0));
-            if (live[i]) my_queue[nq + rank] = (uint16_t)(v * CT + i);
-            nq += (int)__popcll(mask);
-          }
-        }
+        if (i >= 1) extra = extra || live[i];
       }
+      if (extra) atomicOr(&sec[(v * CT) >> 5], 1u << ((v * CT) & 31));
     }
-    // the registers are free again: request the next candidate of this workgroup; it
-    // arrives while phase 2 runs
-    if (b + gridDim.x < B) request(b + gridDim.x);
     __syncthreads();
 
-    // ---------------- phase 2
+    // ---------------- phase 2 (LDS only), with the next candidate's loads issued in slices
+    const bool more = b + gridDim.x < B;
+    const int64_t next_row = (b + gridDim.x) * T;
+    if (more) request(0, next_row);
+    __builtin_amdgcn_sched_barrier(0);
     int S, P;
     reduce_delta<NT>(L, lay, tid, lane, S, P);
     const int distinct = count_distinct_starts<NT>(L, lay, tid);
-    viol += check_edges<NT, CT>(L, g, tid);
-    // (d) Eq. (5), queued copies i >= 1 of this wave's nodes; one lane per copy, plain CSR
-    if constexpr (CT > 1) {
-      for (int q = lane; q < nq; q += kWave) {
-        const int k = my_queue[q];
-        const int v = k / CT;
-        const uint32_t pv = L.packed[k];
-        const uint32_t x = pv & 0xFFFFu, xs = x << 16;
-        for (int ed = g.in_ptr[v]; ed < g.in_ptr[v + 1]; ++ed) {
-          const int ub = g.in_idx[ed] * CT;
-          bool cov = false;
+    for (int w = tid; w < lay.sec_words; w += NT) L.sec[(parity ^ 1) * lay.sec_words + w] = 0;
 #pragma unroll
-          for (int j = 0; j < CT; ++j) cov = cov || covers(L.packed[ub + j], x, xs);
-          viol += cov ? 0 : 1;
-        }
-      }
+    for (int it = 0; it < ITERS; ++it) {
+      __builtin_amdgcn_sched_barrier(0);
+      if (it > 0 && more) request(it, next_row);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int j = it * kEdgesPerNode; j < (it + 1) * kEdgesPerNode; ++j) viol += check_edge<CT>(L, sec, edge[j]);
     }
     finish<NT>(L, g, tid, lane, wave, S, P, viol, nlive, distinct, dur, out, b);
   }
@@ -438,11 +476,26 @@ int launch_iters(int iters, const moc_graph* g, const LdsLayout& lay, int64_t B,
   }
 }
 
+// Node slots per lane the register-resident kernel needs with nt threads: enough for the
+// nodes (one per slot) and for the edges (kEdgesPerNode per slot).
+int slots_per_lane(int n, int m, int nt) {
+  const int by_nodes = (n + nt - 1) / nt, by_edges = (m + kEdgesPerNode * nt - 1) / (kEdgesPerNode * nt);
+  return by_nodes > by_edges ? by_nodes : by_edges;
+}
+
+// Workgroup size: the smallest that leaves at most 5 node slots per lane (one wave per
+// candidate for small graphs, up to a full 1024-thread workgroup per compute unit).
+int block_threads(int n, int m) {
+  for (int nt = 64; nt < 1024; nt *= 2)
+    if (slots_per_lane(n, m, nt) <= 5) return nt;
+  return 1024;
+}
+
 template <int NT>
 int launch_nt(const moc_graph* g, int64_t B, const int32_t* s, const int32_t* e, const uint8_t* a, moc_result* out,
               hipStream_t st, bool fast_ok) {
-  const int n = g->view.n, C = g->view.C;
-  const int iters = (n + NT - 1) / NT;
+  const int n = g->view.n, m = g->view.m, C = g->view.C;
+  const int iters = slots_per_lane(n, m, NT);
   if (fast_ok && iters <= kMaxIters) {
     const LdsLayout lay = lds_layout(n, C, NT, true);
     switch (C) {
@@ -456,18 +509,12 @@ int launch_nt(const moc_graph* g, int64_t B, const int32_t* s, const int32_t* e,
   return launch_kernel(eval_batch_general_kernel<NT>, NT, g, lds_layout(n, C, NT, false), B, s, e, a, out, st);
 }
 
-int block_threads(int n) {
-  // Workgroup size by node count: one wave per candidate for small graphs, a full
-  // 1024-thread workgroup (one per compute unit) for the largest.
-  return n <= kMaxIters * 64 ? 64 : n <= kMaxIters * 256 ? 256 : 1024;
-}
-
 }  // namespace
 
-int moc_eval_lds_bytes(int n, int C) {
-  const int nt = block_threads(n);
-  const bool queue = C <= 4 && (n + nt - 1) / nt <= kMaxIters;
-  return lds_layout(n, C, nt, queue).bytes;
+int moc_eval_lds_bytes(int n, int m, int C) {
+  const int nt = block_threads(n, m);
+  const bool fast = C <= 4 && slots_per_lane(n, m, nt) <= kMaxIters;
+  return lds_layout(n, C, nt, fast).bytes;
 }
 
 extern "C" int moc_eval_batch(const moc_graph* g, int64_t B, const int32_t* starts, const int32_t* ends,
@@ -483,13 +530,15 @@ extern "C" int moc_eval_batch(const moc_graph* g, int64_t B, const int32_t* star
   // The register-resident kernel reads the C copies of a node as one vector: rows must be
   // aligned to the vector (they are when the base pointers are, since a row is n vectors).
   const uintptr_t se = (uintptr_t)starts | (uintptr_t)ends;
-  bool fast_ok = C <= 4 && B * (int64_t)n * C >= 4;
+  bool fast_ok = C <= 4 && n * C >= 4;
   if (C == 2) fast_ok = fast_ok && (se & 7) == 0 && ((uintptr_t)active & 1) == 0;
   if (C == 4) fast_ok = fast_ok && (se & 15) == 0 && ((uintptr_t)active & 3) == 0;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  switch (block_threads(n)) {
+  switch (block_threads(n, g->view.m)) {
     case 64: return launch_nt<64>(g, B, starts, ends, active, out, st, fast_ok);
+    case 128: return launch_nt<128>(g, B, starts, ends, active, out, st, fast_ok);
     case 256: return launch_nt<256>(g, B, starts, ends, active, out, st, fast_ok);
+    case 512: return launch_nt<512>(g, B, starts, ends, active, out, st, fast_ok);
     default: return launch_nt<1024>(g, B, starts, ends, active, out, st, fast_ok);
   }
 }

@@ -33,8 +33,8 @@ struct moc_graph {
   int n_allocs;
 };
 
-// LDS bytes one workgroup of the evaluation kernel needs for a graph of n nodes, C copies.
-int moc_eval_lds_bytes(int n, int C);
+// LDS bytes one workgroup of the evaluation kernel needs for a graph of n nodes, m edges, C copies.
+int moc_eval_lds_bytes(int n, int m, int C);
 
 int moc_set_hip_error(hipError_t e);  // records e, returns MOC_EHIP
 
