@@ -1,56 +1,78 @@
 // moc_eval_batch: one workgroup evaluates one candidate at a time (Eq. (1)-(8)
 // of the paper's Section 2.1) with its whole working set in LDS.
 //
-// Per candidate:
+// Per candidate (register-resident kernel, C <= 4):
 //   phase 1  one lane per node, nodes in id order.  The lane holds the C copies
 //            of its node in registers (requested from HBM while the previous
 //            candidate was being reduced), classifies them (active / live),
 //            counts Eq. (2),(7),(8) and Eq. (3), adds the node's share of
-//            Eq. (1), stages each copy in LDS as one packed word s | e << 16, and
-//            scatters every live copy into the memory-delta array (+m_v at s,
-//            -m_v at e+1: the closed intervals of Eq. (4)) and into a bitmap of
-//            occupied start positions (Eq. (6)).  A node with a live copy i >= 1
-//            (rare) sets its bit in a second bitmap.
-//   phase 2  (a) each thread reduces a contiguous chunk of the delta array to
+//            Eq. (1), stages the node in LDS as one record of packed words
+//            s | e << 16 (one wide store), and scatters every live copy into the
+//            memory-delta array (+m_v at s, -m_v at e+1: the closed intervals of
+//            Eq. (4)) and into a bitmap of occupied start positions (Eq. (6)).
+//   phase 2  (a) the delta array is cut into chunks of 32 positions; a thread reads
+//            its chunk with 16-byte LDS loads, zeroes it, and reduces it to
 //            (sum, max prefix); chunks combine associatively in position order,
 //            which yields the peak of Eq. (4) without materialising the profile;
 //            (b) popcount of the start bitmap: distinct start positions, so that
 //            sum_t max(0, cnt_t - 1) = live copies - distinct starts;
-//            (c) one lane per edge (u,v): Eq. (5) for copy 0 of v against the staged
-//            copies of u, and for the copies i >= 1 of v where its bit is set.
-//            The edges of a lane never change, so they stay in registers.
+//            (c) one lane per edge (u,v): the records of u and v are fetched with
+//            one wide LDS load each and every live copy of v is tested against
+//            the copies of u (Eq. (5)).  The edges of a lane never change, so
+//            they stay in registers.
 //            Phase 2 touches no global memory; the loads of the workgroup's next
 //            candidate are issued in slices between its steps, so that HBM
 //            streams while the LDS work runs and no wave stalls on a full
 //            memory queue.
+// LDS costs that shaped this (measured on gfx950, per compute unit): a 64-lane
+// 4-byte access to random addresses takes about 7 clocks, read, write or atomic
+// alike; 8-byte random costs the same, 16-byte random 12.5; conflict-free
+// 4-byte 2.8 and 16-byte 4.5.  Hence records and chunks are sized for wide
+// accesses and nothing is read twice.
 // All arithmetic is integer: results do not depend on the order in which
 // lanes or workgroups run.
 #include "moc_internal.h"
 
 namespace {
 
-constexpr int kRedStride = 8;  // ints per wave in the cross-wave exchange area
-constexpr int kMaxIters = 6;   // nodes per lane the register-resident kernel is built for
+constexpr int kRedStride = 8;      // ints per wave in the cross-wave exchange area
+constexpr int kMaxIters = 6;       // nodes per lane the register-resident kernel is built for
 constexpr int kEdgesPerNode = 3;   // edges per lane = kEdgesPerNode * nodes per lane
+constexpr int kChunk = 32;         // delta positions per chunk ...
+constexpr int kChunkStride = 36;   // ... stored 36 words apart: 16 lanes x 16 bytes hit 64 distinct banks
 
+// ------------------------------------------------------------------ LDS layouts
 struct LdsLayout {
-  int chunk;       // delta entries per thread (odd: conflict-free strided reads)
-  int delta_len;   // NT * chunk >= T + 1
-  int packed_len;  // >= T, multiple of 4
+  int chunk;       // general kernel: delta entries per thread (odd: conflict-free strided reads)
+  int n_chunks;    // register-resident kernel: chunks of kChunk positions
+  int delta_len;   // words
+  int packed_len;  // words
   int occ_words;   // ceil(T / 32)
-  int sec_words;   // ceil((T + 1) / 32), two such bitmaps (by candidate parity); 0 in the general kernel
   int bytes;
 };
 
-LdsLayout lds_layout(int n, int C, int nt, bool fast) {
+// register-resident kernel: delta in padded chunks, one record of `ns` words per node (+1 dummy node)
+LdsLayout fast_layout(int n, int C, int nt) {
+  const int T = n * C, ns = moc_node_stride(C);
+  LdsLayout l;
+  l.chunk = 0;
+  l.n_chunks = (T + 1 + kChunk - 1) / kChunk;
+  l.delta_len = l.n_chunks * kChunkStride;
+  l.packed_len = ((n + 1) * ns + 3) & ~3;
+  l.occ_words = (T + 31) / 32;
+  l.bytes = 4 * (l.delta_len + l.packed_len + l.occ_words + (nt / kWave) * kRedStride);
+  return l;
+}
+
+LdsLayout general_layout(int n, int C, int nt) {
   const int T = n * C;
   LdsLayout l;
   l.chunk = ((T + 1 + nt - 1) / nt) | 1;
+  l.n_chunks = 0;
   l.delta_len = nt * l.chunk;
-  l.packed_len = (T + 4 + 3) & ~3;   // entries T.. stay "not live": target of padding edges
+  l.packed_len = (T + 3) & ~3;
   l.occ_words = (T + 31) / 32;
-  l.sec_words = fast ? (T + 1 + 31) / 32 : 0;
-  l.bytes = 4 * (l.delta_len + l.packed_len + l.occ_words + 2 * l.sec_words + (nt / kWave) * kRedStride);
+  l.bytes = 4 * (l.delta_len + l.packed_len + l.occ_words + (nt / kWave) * kRedStride);
   return l;
 }
 
@@ -58,20 +80,19 @@ struct Lds {
   int32_t* delta;
   uint32_t* packed;
   uint32_t* occ;
-  uint32_t* sec;     // [2][sec_words]
   int32_t* red;
 };
 
-__device__ __forceinline__ Lds carve(uint32_t* base, const LdsLayout& lay, int nw) {
+__device__ __forceinline__ Lds carve(uint32_t* base, const LdsLayout& lay) {
   Lds l;
   l.delta = reinterpret_cast<int32_t*>(base);
   l.packed = base + lay.delta_len;
   l.occ = l.packed + lay.packed_len;
-  l.sec = l.occ + lay.occ_words;
-  l.red = reinterpret_cast<int32_t*>(l.sec + 2 * lay.sec_words);
+  l.red = reinterpret_cast<int32_t*>(l.occ + lay.occ_words);
   return l;
 }
 
+// ------------------------------------------------------------------ wave helpers
 template <int CTRL>
 __device__ __forceinline__ int dpp_move(int v) {
   return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xF, 0xF, true);
@@ -87,27 +108,10 @@ __device__ __forceinline__ int wave_sum(int v) {
          __builtin_amdgcn_readlane(v, 48);
 }
 
-__device__ __forceinline__ bool is_live(uint32_t packed) { return (packed & 0xFFFFu) != 0xFFFFu; }
-
-// Eq. (5) for one consumer start x (xs = x << 16) against one staged provider copy:
-// s_u + 1 <= x  and  x <= e_u.  A copy that is not live has s = 0xFFFF and fails.
-__device__ __forceinline__ bool covers(uint32_t pu, uint32_t x, uint32_t xs) { return (pu & 0xFFFFu) < x && pu >= xs; }
-
-// ------------------------------------------------------------------ phase 2 pieces shared by both kernels
-template <int NT>
-__device__ __forceinline__ void reduce_delta(const Lds& L, const LdsLayout& lay, int tid, int lane, int& S, int& P) {
-  S = 0;
-  P = 0;
-  int32_t* d = L.delta + tid * lay.chunk;
-#pragma unroll 5
-  for (int j = 0; j < lay.chunk; ++j) {
-    const int x = d[j];
-    d[j] = 0;
-    S += x;
-    P = max(P, S);
-  }
+// (sum, max prefix) of consecutive segments, one per lane, combined in lane order into lane 0.
+__device__ __forceinline__ void wave_combine_ordered(int lane, int& S, int& P) {
 #pragma unroll
-  for (int off = 1; off < kWave; off <<= 1) {   // ordered combine: lane l absorbs lanes l+off..
+  for (int off = 1; off < kWave; off <<= 1) {   // lane l absorbs lanes l+off .. l+2*off-1
     const int S2 = __shfl_down(S, off), P2 = __shfl_down(P, off);
     if (lane + off < kWave) {
       P = max(P, S + P2);
@@ -115,6 +119,12 @@ __device__ __forceinline__ void reduce_delta(const Lds& L, const LdsLayout& lay,
     }
   }
 }
+
+__device__ __forceinline__ bool is_live(uint32_t packed) { return (packed & 0xFFFFu) != 0xFFFFu; }
+
+// Eq. (5) for one consumer start x (xs = x << 16) against one staged provider copy:
+// s_u + 1 <= x  and  x <= e_u.  A copy that is not live has s = 0xFFFF and fails.
+__device__ __forceinline__ bool covers(uint32_t pu, uint32_t x, uint32_t xs) { return (pu & 0xFFFFu) < x && pu >= xs; }
 
 template <int NT>
 __device__ __forceinline__ int count_distinct_starts(const Lds& L, const LdsLayout& lay, int tid) {
@@ -124,29 +134,6 @@ __device__ __forceinline__ int count_distinct_starts(const Lds& L, const LdsLayo
     L.occ[w] = 0;
   }
   return distinct;
-}
-
-// Eq. (5) for copy 0 of every consumer, one lane per edge.  edge_pair[e] = u*C | v*C << 16.
-template <int NT, int CT>
-__device__ __forceinline__ int check_edges(const Lds& L, const GraphView& g, int tid) {
-  int viol = 0;
-  const int C = CT ? CT : g.C;
-#pragma unroll 4
-  for (int e = tid; e < g.m; e += NT) {
-    const uint32_t pair = g.edge_pair[e];
-    const uint32_t pv = L.packed[pair >> 16];
-    const uint32_t x = pv & 0xFFFFu, xs = x << 16;
-    const int ub = (int)(pair & 0xFFFFu);
-    bool cov = false;
-    if constexpr (CT > 0) {
-#pragma unroll
-      for (int q = 0; q < CT; ++q) cov = cov || covers(L.packed[ub + q], x, xs);
-    } else {
-      for (int q = 0; q < C; ++q) cov = cov || covers(L.packed[ub + q], x, xs);
-    }
-    viol += (is_live(pv) && !cov) ? 1 : 0;
-  }
-  return viol;
 }
 
 // Cross-wave combine.  Every wave leaves its partial results in LDS; after the
@@ -197,7 +184,8 @@ __device__ __forceinline__ void finish(const Lds& L, const GraphView& g, int tid
 template <int CT>
 struct NodeIn {
   int s[CT], e[CT];
-  uint32_t a;   // CT flag bytes, byte i = a of copy i (bytes above CT are not used)
+  uint32_t a;   // CT flag bytes, byte i = a of copy i (bytes above CT are not used); for CT == 3 they
+                // start at byte (off - min(off, a_last)), see load_node
 };
 
 struct __attribute__((packed, aligned(4))) Int3 { int x, y, z; };
@@ -225,7 +213,7 @@ __device__ __forceinline__ void load_node(const int32_t* __restrict__ s_row, con
     const uint32_t at = off < a_last ? off : a_last;
     uint32_t w;
     __builtin_memcpy(&w, a_row + at, 4);
-    r.a = w >> (8 * (off - at));
+    r.a = w;   // the consumer shifts by 8 * (off - at): nothing here may wait for the load
   } else {
     const int4 sv = *reinterpret_cast<const int4*>(s_row + off);
     const int4 ev = *reinterpret_cast<const int4*>(e_row + off);
@@ -235,35 +223,56 @@ __device__ __forceinline__ void load_node(const int32_t* __restrict__ s_row, con
   }
 }
 
-// Eq. (5) for one edge held in a register: copy 0 of the consumer always, its copies
-// i >= 1 only if the consumer's bit in `sec` is set.  Returns the violated instances.
+// The record of a node: CT packed words, stored/fetched with one LDS access of NS words.
 template <int CT>
-__device__ __forceinline__ int check_edge(const Lds& L, const uint32_t* __restrict__ sec, uint32_t pair) {
+struct Record {
+  uint32_t w[CT];
+};
+
+template <int CT>
+__device__ __forceinline__ void store_record(uint32_t* at, const Record<CT>& r) {
+  if constexpr (CT == 1) at[0] = r.w[0];
+  else if constexpr (CT == 2) *reinterpret_cast<uint2*>(at) = make_uint2(r.w[0], r.w[1]);
+  else if constexpr (CT == 3) *reinterpret_cast<uint4*>(at) = make_uint4(r.w[0], r.w[1], r.w[2], MOC_DEAD);
+  else *reinterpret_cast<uint4*>(at) = make_uint4(r.w[0], r.w[1], r.w[2], r.w[3]);
+}
+
+template <int CT>
+__device__ __forceinline__ Record<CT> fetch_record(const uint32_t* at) {
+  Record<CT> r;
+  if constexpr (CT == 1) {
+    r.w[0] = at[0];
+  } else if constexpr (CT == 2) {
+    const uint2 v = *reinterpret_cast<const uint2*>(at);
+    r.w[0] = v.x; r.w[1] = v.y;
+  } else {
+    const uint4 v = *reinterpret_cast<const uint4*>(at);
+    r.w[0] = v.x; r.w[1] = v.y; r.w[2] = v.z;
+    if constexpr (CT == 4) r.w[3] = v.w;
+  }
+  return r;
+}
+
+// position t of the delta array -> word index (chunks of 32 words, 36 apart)
+__device__ __forceinline__ int delta_at(int t) { return t + ((t >> 5) << 2); }
+
+// Eq. (5) for one edge held in a register, pair = u*NS | v*NS << 16: every live copy of
+// the consumer v against the copies of the provider u.  Returns the violated instances.
+template <int CT>
+__device__ __forceinline__ int check_edge(const Lds& L, uint32_t pair) {
   // The pair is the same for every candidate.  Hide that from the optimiser: otherwise it
   // keeps every address derived from it in a register of its own for the whole kernel.
   asm volatile("" : "+v"(pair));
-  const int kd = (int)(pair >> 16), ub = (int)(pair & 0xFFFFu);
-  const uint32_t pv = L.packed[kd];
-  uint32_t pu[CT];
+  const Record<CT> pv = fetch_record<CT>(L.packed + (pair >> 16));
+  const Record<CT> pu = fetch_record<CT>(L.packed + (pair & 0xFFFFu));
+  int viol = 0;
 #pragma unroll
-  for (int q = 0; q < CT; ++q) pu[q] = L.packed[ub + q];
-  const uint32_t x = pv & 0xFFFFu, xs = x << 16;
-  bool cov = false;
+  for (int i = 0; i < CT; ++i) {
+    const uint32_t x = pv.w[i] & 0xFFFFu, xs = x << 16;
+    bool cov = false;
 #pragma unroll
-  for (int q = 0; q < CT; ++q) cov = cov || covers(pu[q], x, xs);
-  int viol = (is_live(pv) && !cov) ? 1 : 0;
-  if constexpr (CT > 1) {
-    if ((sec[kd >> 5] >> (kd & 31)) & 1u) {
-#pragma unroll
-      for (int i = 1; i < CT; ++i) {
-        const uint32_t pi = L.packed[kd + i];
-        const uint32_t xi = pi & 0xFFFFu, xsi = xi << 16;
-        bool covi = false;
-#pragma unroll
-        for (int q = 0; q < CT; ++q) covi = covi || covers(pu[q], xi, xsi);
-        viol += (is_live(pi) && !covi) ? 1 : 0;
-      }
-    }
+    for (int q = 0; q < CT; ++q) cov = cov || covers(pu.w[q], x, xs);
+    viol += (is_live(pv.w[i]) && !cov) ? 1 : 0;
   }
   return viol;
 }
@@ -273,37 +282,45 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
                                                         const int32_t* __restrict__ ends,
                                                         const uint8_t* __restrict__ active,
                                                         moc_result* __restrict__ out, LdsLayout lay) {
-  constexpr int NW = NT / kWave;
   constexpr int EPT = kEdgesPerNode * ITERS;
+  constexpr int NS = CT == 3 ? 4 : CT;
   extern __shared__ uint32_t lds_raw[];
-  const Lds L = carve(lds_raw, lay, NW);
+  const Lds L = carve(lds_raw, lay);
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
   const int T = g.T, n = g.n;
   const int64_t total = B * (int64_t)T;
 
   for (int i = tid; i < lay.delta_len; i += NT) L.delta[i] = 0;
-  for (int i = tid; i < lay.occ_words + 2 * lay.sec_words; i += NT) L.occ[i] = 0;
-  for (int i = T + tid; i < lay.packed_len; i += NT) L.packed[i] = MOC_DEAD;
+  for (int i = tid; i < lay.occ_words; i += NT) L.occ[i] = 0;
+  for (int i = tid; i < lay.packed_len; i += NT) L.packed[i] = MOC_DEAD;   // incl. the dummy node n
 
-  // what a lane owns never changes: m_v, w_v of its nodes and its edges stay in registers
-  int2 sd[ITERS];
-#pragma unroll
-  for (int it = 0; it < ITERS; ++it) {
-    const int v = it * NT + tid;
-    sd[it] = v < n ? g.size_dur[v] : make_int2(0, 0);
-  }
+  // what a lane owns never changes: its edges stay in registers
   uint32_t edge[EPT];
 #pragma unroll
   for (int j = 0; j < EPT; ++j) {
     const int e = j * NT + tid;
-    edge[j] = e < g.m ? g.edge_pair[e] : (uint32_t)T << 16;   // padding: consumer entry T is never live
+    edge[j] = e < g.m ? g.edge_pair[e] : (uint32_t)(n * NS) << 16;   // padding: the dummy node is never live
   }
   NodeIn<CT> in[ITERS];
-  auto request = [&](int it, int64_t row) {   // loads of node slot `it` of the candidate at `row`
-    const int v = it * NT + tid;
+  // m_v, w_v of the lane's nodes: re-read (from L2) at the start of each phase 1, behind the
+  // candidate's own loads, rather than held in registers through phase 2 where registers are scarce
+  int2 sd[ITERS];
+  auto request_size_dur = [&]() {
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+      int v = it * NT + tid;
+      asm volatile("" : "+v"(v));
+      sd[it] = v < n ? g.size_dur[v] : make_int2(0, 0);
+    }
+  };
+  auto flags_last = [&](int64_t row) {         // largest byte offset in the row at which 4 flag bytes exist
     const int64_t left = total - row - 4;      // >= 0: the kernel is not used for T < 4
-    const uint32_t a_last = left < 0x7FFFFFFF ? (uint32_t)left : 0x7FFFFFFFu;
-    if (v < n) load_node<CT>(starts + row, ends + row, active + row, (uint32_t)v * CT, a_last, in[it]);
+    return left < 0x7FFFFFFF ? (uint32_t)left : 0x7FFFFFFFu;
+  };
+  auto request = [&](int it, int64_t row) {   // loads of node slot `it` of the candidate at `row`
+    int v = it * NT + tid;
+    asm volatile("" : "+v"(v));                // keep the per-slot offsets and guards out of registers
+    if (v < n) load_node<CT>(starts + row, ends + row, active + row, (uint32_t)v * CT, flags_last(row), in[it]);
   };
   if ((int64_t)blockIdx.x < B) {
 #pragma unroll
@@ -311,12 +328,11 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
   }
   __syncthreads();
 
-  int parity = 0;
-  for (int64_t b = blockIdx.x; b < B; b += gridDim.x, parity ^= 1) {
+  for (int64_t b = blockIdx.x; b < B; b += gridDim.x) {
     int viol = 0, nlive = 0, dur = 0;   // per lane
-    uint32_t* sec = L.sec + parity * lay.sec_words;
 
     // ---------------- phase 1: per node, copies in registers
+    request_size_dur();
 #pragma unroll
     for (int it = 0; it < ITERS; ++it) {
       int v = it * NT + tid;
@@ -324,18 +340,23 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
       const bool isn = v < n;
       if (it * NT + wave * kWave >= n) break;   // whole wave past the last node
       const NodeIn<CT>& r = in[it];
+      uint32_t flags = r.a;
+      if constexpr (CT == 3) {
+        const uint32_t off = (uint32_t)v * CT, a_last = flags_last(b * T);
+        flags >>= 8 * (off - (off < a_last ? off : a_last));
+      }
       bool act[CT], live[CT];
-      uint32_t pk[CT];
+      Record<CT> rec;
       int nact = 0;
 #pragma unroll
       for (int i = 0; i < CT; ++i) {
-        act[i] = isn && ((r.a >> (8 * i)) & 0xFFu) != 0;
+        act[i] = isn && ((flags >> (8 * i)) & 0xFFu) != 0;
         const bool well = (uint32_t)r.s[i] <= (uint32_t)r.e[i] && (uint32_t)r.e[i] < (uint32_t)T;   // Eq. (2), (8)
         live[i] = act[i] && well;
         viol += (act[i] && !well) ? 1 : 0;
         nact += act[i] ? 1 : 0;
         nlive += live[i] ? 1 : 0;
-        pk[i] = live[i] ? ((uint32_t)r.s[i] | ((uint32_t)r.e[i] << 16)) : MOC_DEAD;
+        rec.w[i] = live[i] ? ((uint32_t)r.s[i] | ((uint32_t)r.e[i] << 16)) : MOC_DEAD;
       }
       viol += (isn && !act[0]) ? 1 : 0;   // Eq. (7)
       dur += nact * sd[it].y;              // Eq. (1)
@@ -349,19 +370,20 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
         }
         viol += (live[i] && late) ? 1 : 0;
       }
-      bool extra = false;
+      if (isn) store_record<CT>(L.packed + v * NS, rec);
 #pragma unroll
       for (int i = 0; i < CT; ++i) {
-        if (isn) L.packed[v * CT + i] = pk[i];
         if (live[i]) {
-          atomicAdd(&L.delta[r.s[i]], sd[it].x);          // Eq. (4): allocated at s ...
-          atomicAdd(&L.delta[r.e[i] + 1], -sd[it].x);     // ... released after e
-          atomicOr(&L.occ[r.s[i] >> 5], 1u << (r.s[i] & 31));   // Eq. (6)
+          atomicAdd(&L.delta[delta_at(r.s[i])], sd[it].x);          // Eq. (4): allocated at s ...
+          atomicSub(&L.delta[delta_at(r.e[i] + 1)], sd[it].x);      // ... released after e
+          atomicOr(&L.occ[r.s[i] >> 5], 1u << (r.s[i] & 31));       // Eq. (6)
         }
-        if (i >= 1) extra = extra || live[i];
       }
-      if (extra) atomicOr(&sec[(v * CT) >> 5], 1u << ((v * CT) & 31));
     }
+    // every load issued so far has been consumed or is waited for here, so that phase 2 starts
+    // with no load outstanding and none of its register writes has to wait for one
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) asm volatile("" ::"v"(sd[it].x), "v"(sd[it].y));
     __syncthreads();
 
     // ---------------- phase 2 (LDS only), with the next candidate's loads issued in slices
@@ -369,17 +391,38 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
     const int64_t next_row = (b + gridDim.x) * T;
     if (more) request(0, next_row);
     __builtin_amdgcn_sched_barrier(0);
-    int S, P;
-    reduce_delta<NT>(L, lay, tid, lane, S, P);
+    // (a) one chunk of 32 delta positions per thread
+    int S = 0, P = 0;
+    if (wave * kWave < lay.n_chunks) {
+      if (tid < lay.n_chunks) {
+        int4* d = reinterpret_cast<int4*>(L.delta + tid * kChunkStride);
+#pragma unroll
+        for (int h = 0; h < kChunk / 8; ++h) {   // 8 positions at a time keeps the register count down
+          const int4 x0 = d[2 * h], x1 = d[2 * h + 1];
+          d[2 * h] = make_int4(0, 0, 0, 0);
+          d[2 * h + 1] = make_int4(0, 0, 0, 0);
+          S += x0.x; P = max(P, S);
+          S += x0.y; P = max(P, S);
+          S += x0.z; P = max(P, S);
+          S += x0.w; P = max(P, S);
+          S += x1.x; P = max(P, S);
+          S += x1.y; P = max(P, S);
+          S += x1.z; P = max(P, S);
+          S += x1.w; P = max(P, S);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+      wave_combine_ordered(lane, S, P);
+    }
     const int distinct = count_distinct_starts<NT>(L, lay, tid);
-    for (int w = tid; w < lay.sec_words; w += NT) L.sec[(parity ^ 1) * lay.sec_words + w] = 0;
+    // (c) edges, three per slice of the prefetch
 #pragma unroll
     for (int it = 0; it < ITERS; ++it) {
       __builtin_amdgcn_sched_barrier(0);
       if (it > 0 && more) request(it, next_row);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int j = it * kEdgesPerNode; j < (it + 1) * kEdgesPerNode; ++j) viol += check_edge<CT>(L, sec, edge[j]);
+      for (int j = it * kEdgesPerNode; j < (it + 1) * kEdgesPerNode; ++j) viol += check_edge<CT>(L, edge[j]);
     }
     finish<NT>(L, g, tid, lane, wave, S, P, viol, nlive, distinct, dur, out, b);
   }
@@ -392,9 +435,8 @@ __global__ __launch_bounds__(NT) void eval_batch_general_kernel(GraphView g, int
                                                                 const int32_t* __restrict__ ends,
                                                                 const uint8_t* __restrict__ active,
                                                                 moc_result* __restrict__ out, LdsLayout lay) {
-  constexpr int NW = NT / kWave;
   extern __shared__ uint32_t lds_raw[];
-  const Lds L = carve(lds_raw, lay, NW);
+  const Lds L = carve(lds_raw, lay);
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
   const int T = g.T, n = g.n, C = g.C;
 
@@ -431,19 +473,32 @@ __global__ __launch_bounds__(NT) void eval_batch_general_kernel(GraphView g, int
     }
     __syncthreads();
 
-    int S, P;
-    reduce_delta<NT>(L, lay, tid, lane, S, P);
+    // phase 2a: contiguous odd-length chunk per thread
+    int S = 0, P = 0;
+    {
+      int32_t* d = L.delta + tid * lay.chunk;
+#pragma unroll 5
+      for (int j = 0; j < lay.chunk; ++j) {
+        const int x = d[j];
+        d[j] = 0;
+        S += x;
+        P = max(P, S);
+      }
+    }
+    wave_combine_ordered(lane, S, P);
     const int distinct = count_distinct_starts<NT>(L, lay, tid);
-    viol += check_edges<NT, 0>(L, g, tid);
-    for (int i = 1; i < C; ++i)   // Eq. (5) for the copies i >= 1 of every consumer
-      for (int e = tid; e < g.m; e += NT) {
-        const uint32_t pair = g.edge_pair[e];
-        const uint32_t pv = L.packed[(pair >> 16) + i];
+    // Eq. (5): one lane per edge, every live copy of the consumer; edge_pair_c = u*C | v*C << 16
+    for (int e = tid; e < g.m; e += NT) {
+      const uint32_t pair = g.edge_pair_c[e];
+      const int kd = (int)(pair >> 16), ub = (int)(pair & 0xFFFFu);
+      for (int i = 0; i < C; ++i) {
+        const uint32_t pv = L.packed[kd + i];
         const uint32_t x = pv & 0xFFFFu, xs = x << 16;
         bool cov = false;
-        for (int q = 0; q < C; ++q) cov = cov || covers(L.packed[(pair & 0xFFFFu) + q], x, xs);
+        for (int q = 0; q < C; ++q) cov = cov || covers(L.packed[ub + q], x, xs);
         viol += (is_live(pv) && !cov) ? 1 : 0;
       }
+    }
     finish<NT>(L, g, tid, lane, wave, S, P, viol, nlive, distinct, dur, out, b);
   }
 }
@@ -491,30 +546,40 @@ int block_threads(int n, int m) {
   return 1024;
 }
 
+// The register-resident kernel applies when C <= 4, a lane's nodes and edges fit its
+// registers, and every thread has at most one delta chunk.
+bool fast_shape(int n, int m, int C, int nt) {
+  return C <= 4 && n * C >= 4 && slots_per_lane(n, m, nt) <= kMaxIters && (n * C + kChunk) / kChunk <= nt &&
+         (n + 1) * moc_node_stride(C) <= 0xFFFF;
+}
+
 template <int NT>
 int launch_nt(const moc_graph* g, int64_t B, const int32_t* s, const int32_t* e, const uint8_t* a, moc_result* out,
-              hipStream_t st, bool fast_ok) {
+              hipStream_t st, bool aligned) {
   const int n = g->view.n, m = g->view.m, C = g->view.C;
-  const int iters = slots_per_lane(n, m, NT);
-  if (fast_ok && iters <= kMaxIters) {
-    const LdsLayout lay = lds_layout(n, C, NT, true);
+  if (aligned && fast_shape(n, m, C, NT)) {
+    const LdsLayout lay = fast_layout(n, C, NT);
+    const int iters = slots_per_lane(n, m, NT);
     switch (C) {
       case 1: return launch_iters<NT, 1>(iters, g, lay, B, s, e, a, out, st);
       case 2: return launch_iters<NT, 2>(iters, g, lay, B, s, e, a, out, st);
       case 3: return launch_iters<NT, 3>(iters, g, lay, B, s, e, a, out, st);
-      case 4: return launch_iters<NT, 4>(iters, g, lay, B, s, e, a, out, st);
-      default: break;
+      default: return launch_iters<NT, 4>(iters, g, lay, B, s, e, a, out, st);
     }
   }
-  return launch_kernel(eval_batch_general_kernel<NT>, NT, g, lds_layout(n, C, NT, false), B, s, e, a, out, st);
+  return launch_kernel(eval_batch_general_kernel<NT>, NT, g, general_layout(n, C, NT), B, s, e, a, out, st);
 }
 
 }  // namespace
 
+int moc_node_stride(int C) { return C == 3 ? 4 : C; }
+
 int moc_eval_lds_bytes(int n, int m, int C) {
   const int nt = block_threads(n, m);
-  const bool fast = C <= 4 && slots_per_lane(n, m, nt) <= kMaxIters;
-  return lds_layout(n, C, nt, fast).bytes;
+  const int general = general_layout(n, C, nt).bytes;
+  if (!fast_shape(n, m, C, nt)) return general;
+  const int fast = fast_layout(n, C, nt).bytes;   // misaligned candidate arrays fall back to the general kernel
+  return fast > general ? fast : general;
 }
 
 extern "C" int moc_eval_batch(const moc_graph* g, int64_t B, const int32_t* starts, const int32_t* ends,
@@ -530,15 +595,15 @@ extern "C" int moc_eval_batch(const moc_graph* g, int64_t B, const int32_t* star
   // The register-resident kernel reads the C copies of a node as one vector: rows must be
   // aligned to the vector (they are when the base pointers are, since a row is n vectors).
   const uintptr_t se = (uintptr_t)starts | (uintptr_t)ends;
-  bool fast_ok = C <= 4 && n * C >= 4;
-  if (C == 2) fast_ok = fast_ok && (se & 7) == 0 && ((uintptr_t)active & 1) == 0;
-  if (C == 4) fast_ok = fast_ok && (se & 15) == 0 && ((uintptr_t)active & 3) == 0;
+  bool aligned = true;
+  if (C == 2) aligned = (se & 7) == 0 && ((uintptr_t)active & 1) == 0;
+  if (C == 4) aligned = (se & 15) == 0 && ((uintptr_t)active & 3) == 0;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   switch (block_threads(n, g->view.m)) {
-    case 64: return launch_nt<64>(g, B, starts, ends, active, out, st, fast_ok);
-    case 128: return launch_nt<128>(g, B, starts, ends, active, out, st, fast_ok);
-    case 256: return launch_nt<256>(g, B, starts, ends, active, out, st, fast_ok);
-    case 512: return launch_nt<512>(g, B, starts, ends, active, out, st, fast_ok);
-    default: return launch_nt<1024>(g, B, starts, ends, active, out, st, fast_ok);
+    case 64: return launch_nt<64>(g, B, starts, ends, active, out, st, aligned);
+    case 128: return launch_nt<128>(g, B, starts, ends, active, out, st, aligned);
+    case 256: return launch_nt<256>(g, B, starts, ends, active, out, st, aligned);
+    case 512: return launch_nt<512>(g, B, starts, ends, active, out, st, aligned);
+    default: return launch_nt<1024>(g, B, starts, ends, active, out, st, aligned);
   }
 }

@@ -62,10 +62,14 @@ int moc_graph_upload(int32_t n, const int32_t* in_ptr, const int32_t* in_idx, co
     std::vector<int2> size_dur(n);
     for (int v = 0; v < n; ++v) size_dur[v] = make_int2(size[v], dur[v]);
 
-    std::vector<uint32_t> edge_pair(m);
+    const int ns = moc_node_stride(C);
+    const bool wide_ok = (int64_t)(n + 1) * ns <= 0xFFFF;   // else only the kernel for any C runs
+    std::vector<uint32_t> edge_pair(m), edge_pair_c(m);
     for (int v = 0; v < n; ++v)
-      for (int q = in_ptr[v]; q < in_ptr[v + 1]; ++q)
-        edge_pair[q] = (uint32_t)(in_idx[q] * C) | ((uint32_t)(v * C) << 16);
+      for (int q = in_ptr[v]; q < in_ptr[v + 1]; ++q) {
+        edge_pair_c[q] = (uint32_t)(in_idx[q] * C) | ((uint32_t)(v * C) << 16);
+        edge_pair[q] = wide_ok ? (uint32_t)(in_idx[q] * ns) | ((uint32_t)(v * ns) << 16) : 0u;
+      }
 
     // out-edge CSR (consumers of every node), used by the neighbourhood kernel
     std::vector<int32_t> out_ptr(n + 1, 0), out_idx(m);
@@ -98,6 +102,7 @@ int moc_graph_upload(int32_t n, const int32_t* in_ptr, const int32_t* in_idx, co
     w.budget = budget; w.n = n; w.m = m; w.C = C; w.T = T;
     if (rc == MOC_OK) rc = upload(g, size_dur, &w.size_dur);
     if (rc == MOC_OK) rc = upload(g, edge_pair, &w.edge_pair);
+    if (rc == MOC_OK) rc = upload(g, edge_pair_c, &w.edge_pair_c);
     if (rc == MOC_OK) rc = upload(g, in_ptr_v, &w.in_ptr);
     if (rc == MOC_OK) rc = upload(g, in_idx_v, &w.in_idx);
     if (rc == MOC_OK) rc = upload(g, out_ptr, &w.out_ptr);

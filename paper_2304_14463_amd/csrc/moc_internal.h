@@ -15,7 +15,8 @@ constexpr int kWave = 64;  // CDNA wavefront
 // Device-side view of an uploaded graph, passed to kernels by value.
 struct GraphView {
   const int2* size_dur;        // [n] {m_v, w_v}
-  const uint32_t* edge_pair;   // [m] edge (u,v) as u*C | v*C << 16, ordered by v
+  const uint32_t* edge_pair;   // [m] edge (u,v) as u*NS | v*NS << 16, ordered by v; NS = moc_node_stride(C)
+  const uint32_t* edge_pair_c; // [m] the same with stride C (kernel for any C)
   const int32_t* in_ptr;       // [n+1] plain CSR by in-edges
   const int32_t* in_idx;       // [m]
   const int32_t* out_ptr;      // [n+1] CSR by out-edges
@@ -32,6 +33,9 @@ struct moc_graph {
   void* allocs[8];   // device allocations backing `view`
   int n_allocs;
 };
+
+// Words per node record in LDS: C rounded up to 1, 2 or 4 so that a record is one wide access.
+int moc_node_stride(int C);
 
 // LDS bytes one workgroup of the evaluation kernel needs for a graph of n nodes, m edges, C copies.
 int moc_eval_lds_bytes(int n, int m, int C);
