@@ -192,34 +192,42 @@ struct __attribute__((packed, aligned(4))) Int3 { int x, y, z; };
 
 // Loads the C copies of one node.  s_row/e_row/a_row point at the candidate's row (uniform
 // over the workgroup, so they live in scalar registers) and `off` = v*C is the lane's
-// 32-bit element offset; `a_last` = largest byte offset at which 4 flag bytes can be read.
+// element offset, turned into 32-bit byte offsets so that the loads take the scalar base +
+// 32-bit lane offset form; `a_last` = largest byte offset at which 4 flag bytes can be read.
+template <typename V>
+__device__ __forceinline__ V load_at(const void* base, uint32_t byte_off) {
+  return *reinterpret_cast<const V*>(static_cast<const char*>(base) + byte_off);
+}
+
 template <int CT>
 __device__ __forceinline__ void load_node(const int32_t* __restrict__ s_row, const int32_t* __restrict__ e_row,
                                           const uint8_t* __restrict__ a_row, uint32_t off, uint32_t a_last,
                                           NodeIn<CT>& r) {
+  const uint32_t boff = off * 4u;   // T <= 19455: no overflow
   if constexpr (CT == 1) {
-    r.s[0] = s_row[off]; r.e[0] = e_row[off]; r.a = a_row[off];
+    r.s[0] = load_at<int>(s_row, boff); r.e[0] = load_at<int>(e_row, boff); r.a = load_at<uint8_t>(a_row, off);
   } else if constexpr (CT == 2) {
-    const int2 sv = *reinterpret_cast<const int2*>(s_row + off);
-    const int2 ev = *reinterpret_cast<const int2*>(e_row + off);
+    const int2 sv = load_at<int2>(s_row, boff);
+    const int2 ev = load_at<int2>(e_row, boff);
     r.s[0] = sv.x; r.s[1] = sv.y; r.e[0] = ev.x; r.e[1] = ev.y;
-    r.a = *reinterpret_cast<const uint16_t*>(a_row + off);
+    r.a = load_at<uint16_t>(a_row, off);
   } else if constexpr (CT == 3) {
-    const Int3 sv = *reinterpret_cast<const Int3*>(s_row + off);
-    const Int3 ev = *reinterpret_cast<const Int3*>(e_row + off);
+    const Int3 sv = load_at<Int3>(s_row, boff);
+    const Int3 ev = load_at<Int3>(e_row, boff);
     r.s[0] = sv.x; r.s[1] = sv.y; r.s[2] = sv.z; r.e[0] = ev.x; r.e[1] = ev.y; r.e[2] = ev.z;
     // one (unaligned) 4-byte read covers the 3 flags; the last node of the batch reads
-    // the 4 bytes that end with the array and shifts
+    // the 4 bytes that end with the array and the consumer shifts by 8 * (off - at):
+    // nothing here may wait for the load
     const uint32_t at = off < a_last ? off : a_last;
     uint32_t w;
     __builtin_memcpy(&w, a_row + at, 4);
-    r.a = w;   // the consumer shifts by 8 * (off - at): nothing here may wait for the load
+    r.a = w;
   } else {
-    const int4 sv = *reinterpret_cast<const int4*>(s_row + off);
-    const int4 ev = *reinterpret_cast<const int4*>(e_row + off);
+    const int4 sv = load_at<int4>(s_row, boff);
+    const int4 ev = load_at<int4>(e_row, boff);
     r.s[0] = sv.x; r.s[1] = sv.y; r.s[2] = sv.z; r.s[3] = sv.w;
     r.e[0] = ev.x; r.e[1] = ev.y; r.e[2] = ev.z; r.e[3] = ev.w;
-    r.a = *reinterpret_cast<const uint32_t*>(a_row + off);
+    r.a = load_at<uint32_t>(a_row, off);
   }
 }
 
@@ -284,6 +292,7 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
                                                         moc_result* __restrict__ out, LdsLayout lay) {
   constexpr int EPT = kEdgesPerNode * ITERS;
   constexpr int NS = CT == 3 ? 4 : CT;
+  constexpr int kEarly = ITERS * 2 / 5;   // node slots re-requested during phase 1
   extern __shared__ uint32_t lds_raw[];
   const Lds L = carve(lds_raw, lay);
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
@@ -308,28 +317,33 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
   auto request_size_dur = [&]() {
 #pragma unroll
     for (int it = 0; it < ITERS; ++it) {
-      int v = it * NT + tid;
+      int v = min(it * NT + tid, n - 1);       // lanes past the last node re-read it; their results are masked
       asm volatile("" : "+v"(v));
-      sd[it] = v < n ? g.size_dur[v] : make_int2(0, 0);
+      sd[it] = load_at<int2>(g.size_dur, (uint32_t)v * 8u);
     }
   };
   auto flags_last = [&](int64_t row) {         // largest byte offset in the row at which 4 flag bytes exist
     const int64_t left = total - row - 4;      // >= 0: the kernel is not used for T < 4
     return left < 0x7FFFFFFF ? (uint32_t)left : 0x7FFFFFFFu;
   };
-  auto request = [&](int it, int64_t row) {   // loads of node slot `it` of the candidate at `row`
-    int v = it * NT + tid;
-    asm volatile("" : "+v"(v));                // keep the per-slot offsets and guards out of registers
-    if (v < n) load_node<CT>(starts + row, ends + row, active + row, (uint32_t)v * CT, flags_last(row), in[it]);
+  // Loads of node slot `it` of the candidate at `row`.  Issued unconditionally (lanes past the
+  // last node re-read it) so that the count of loads in flight is the same on every path.
+  auto request = [&](int it, int64_t row) {
+    int v = min(it * NT + tid, n - 1);
+    asm volatile("" : "+v"(v));                // keep the per-slot offsets out of registers
+    load_node<CT>(starts + row, ends + row, active + row, (uint32_t)v * CT, flags_last(row), in[it]);
   };
-  if ((int64_t)blockIdx.x < B) {
 #pragma unroll
-    for (int it = 0; it < ITERS; ++it) request(it, (int64_t)blockIdx.x * T);
-  }
+  for (int it = 0; it < ITERS; ++it) request(it, (int64_t)blockIdx.x * T);   // grid <= B
   __syncthreads();
 
   for (int64_t b = blockIdx.x; b < B; b += gridDim.x) {
     int viol = 0, nlive = 0, dur = 0;   // per lane
+    // The workgroup's next candidate; the last one re-reads itself so that the loads below
+    // need no condition.  Slot `it` is requested as soon as phase 1 has consumed the
+    // registers of slot `it` (the first kEarly slots) or between the steps of phase 2 (the
+    // rest): HBM streams through both phases and no wave queues all its loads at once.
+    const int64_t next_row = (b + gridDim.x < B ? b + gridDim.x : b) * T;
 
     // ---------------- phase 1: per node, copies in registers
     request_size_dur();
@@ -338,58 +352,58 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
       int v = it * NT + tid;
       asm volatile("" : "+v"(v));               // as in check_edge: keep derived addresses out of registers
       const bool isn = v < n;
-      if (it * NT + wave * kWave >= n) break;   // whole wave past the last node
-      const NodeIn<CT>& r = in[it];
-      uint32_t flags = r.a;
-      if constexpr (CT == 3) {
-        const uint32_t off = (uint32_t)v * CT, a_last = flags_last(b * T);
-        flags >>= 8 * (off - (off < a_last ? off : a_last));
-      }
-      bool act[CT], live[CT];
-      Record<CT> rec;
-      int nact = 0;
-#pragma unroll
-      for (int i = 0; i < CT; ++i) {
-        act[i] = isn && ((flags >> (8 * i)) & 0xFFu) != 0;
-        const bool well = (uint32_t)r.s[i] <= (uint32_t)r.e[i] && (uint32_t)r.e[i] < (uint32_t)T;   // Eq. (2), (8)
-        live[i] = act[i] && well;
-        viol += (act[i] && !well) ? 1 : 0;
-        nact += act[i] ? 1 : 0;
-        nlive += live[i] ? 1 : 0;
-        rec.w[i] = live[i] ? ((uint32_t)r.s[i] | ((uint32_t)r.e[i] << 16)) : MOC_DEAD;
-      }
-      viol += (isn && !act[0]) ? 1 : 0;   // Eq. (7)
-      dur += nact * sd[it].y;              // Eq. (1)
-#pragma unroll
-      for (int i = 0; i + 1 < CT; ++i) {   // Eq. (3): against the next live copy
-        bool seen = false, late = false;
-#pragma unroll
-        for (int j = i + 1; j < CT; ++j) {
-          late = late || (!seen && live[j] && r.e[i] > r.s[j]);
-          seen = seen || live[j];
+      // m_v, w_v of this slot have arrived on every path from here on (its loads were issued
+      // before anything that is still in flight)
+      asm volatile("" ::"v"(sd[it].x), "v"(sd[it].y));
+      if (it * NT + wave * kWave < n) {   // else: whole wave past the last node
+        const NodeIn<CT>& r = in[it];
+        uint32_t flags = r.a;
+        if constexpr (CT == 3) {
+          const uint32_t off = (uint32_t)v * CT, a_last = flags_last(b * T);
+          flags >>= 8 * (off - (off < a_last ? off : a_last));
         }
-        viol += (live[i] && late) ? 1 : 0;
-      }
-      if (isn) store_record<CT>(L.packed + v * NS, rec);
+        bool act[CT], live[CT];
+        Record<CT> rec;
+        int nact = 0;
 #pragma unroll
-      for (int i = 0; i < CT; ++i) {
-        if (live[i]) {
-          atomicAdd(&L.delta[delta_at(r.s[i])], sd[it].x);          // Eq. (4): allocated at s ...
-          atomicSub(&L.delta[delta_at(r.e[i] + 1)], sd[it].x);      // ... released after e
-          atomicOr(&L.occ[r.s[i] >> 5], 1u << (r.s[i] & 31));       // Eq. (6)
+        for (int i = 0; i < CT; ++i) {
+          act[i] = isn && ((flags >> (8 * i)) & 0xFFu) != 0;
+          const bool well = (uint32_t)r.s[i] <= (uint32_t)r.e[i] && (uint32_t)r.e[i] < (uint32_t)T;   // Eq. (2), (8)
+          live[i] = act[i] && well;
+          viol += (act[i] && !well) ? 1 : 0;
+          nact += act[i] ? 1 : 0;
+          nlive += live[i] ? 1 : 0;
+          rec.w[i] = live[i] ? ((uint32_t)r.s[i] | ((uint32_t)r.e[i] << 16)) : MOC_DEAD;
+        }
+        viol += (isn && !act[0]) ? 1 : 0;   // Eq. (7)
+        dur += nact * sd[it].y;              // Eq. (1)
+#pragma unroll
+        for (int i = 0; i + 1 < CT; ++i) {   // Eq. (3): against the next live copy
+          bool seen = false, late = false;
+#pragma unroll
+          for (int j = i + 1; j < CT; ++j) {
+            late = late || (!seen && live[j] && r.e[i] > r.s[j]);
+            seen = seen || live[j];
+          }
+          viol += (live[i] && late) ? 1 : 0;
+        }
+        if (isn) store_record<CT>(L.packed + v * NS, rec);
+#pragma unroll
+        for (int i = 0; i < CT; ++i) {
+          if (live[i]) {
+            atomicAdd(&L.delta[delta_at(r.s[i])], sd[it].x);          // Eq. (4): allocated at s ...
+            atomicSub(&L.delta[delta_at(r.e[i] + 1)], sd[it].x);      // ... released after e
+            atomicOr(&L.occ[r.s[i] >> 5], 1u << (r.s[i] & 31));       // Eq. (6)
+          }
         }
       }
+      if (it < kEarly) request(it, next_row);
+      __builtin_amdgcn_sched_barrier(0);   // one node slot at a time: interleaving them costs registers
     }
-    // every load issued so far has been consumed or is waited for here, so that phase 2 starts
-    // with no load outstanding and none of its register writes has to wait for one
-#pragma unroll
-    for (int it = 0; it < ITERS; ++it) asm volatile("" ::"v"(sd[it].x), "v"(sd[it].y));
     __syncthreads();
 
     // ---------------- phase 2 (LDS only), with the next candidate's loads issued in slices
-    const bool more = b + gridDim.x < B;
-    const int64_t next_row = (b + gridDim.x) * T;
-    if (more) request(0, next_row);
+    if (kEarly < ITERS) request(kEarly, next_row);
     __builtin_amdgcn_sched_barrier(0);
     // (a) one chunk of 32 delta positions per thread
     int S = 0, P = 0;
@@ -419,7 +433,7 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
 #pragma unroll
     for (int it = 0; it < ITERS; ++it) {
       __builtin_amdgcn_sched_barrier(0);
-      if (it > 0 && more) request(it, next_row);
+      if (it > 0 && kEarly + it < ITERS) request(kEarly + it, next_row);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int j = it * kEdgesPerNode; j < (it + 1) * kEdgesPerNode; ++j) viol += check_edge<CT>(L, edge[j]);
