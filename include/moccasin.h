@@ -64,9 +64,9 @@ extern "C" {
 #define MOC_EDEVICE   (-5)  /* the graph's device is not the current device */
 
 /* Largest T = n*C an uploaded graph may have: the per-candidate working set
- * (memory-delta array, packed intervals, start bitmap, queue of extra copies)
- * lives in the 160 KB LDS of one compute unit.  The queue of extra copies
- * lowers the bound to 16755 for C = 3 and 16384 for C = 4.  moc_graph_upload
+ * (memory-delta array, one record of packed intervals per node, start bitmap)
+ * lives in the 160 KB LDS of one compute unit.  With C = 3 a node record is
+ * padded to 4 words, which lowers the bound to 16383.  moc_graph_upload
  * returns MOC_EOVERFLOW for a graph that does not fit. */
 #define MOC_MAX_T 19455
 
@@ -119,9 +119,10 @@ int moc_graph_info(const moc_graph* g, int32_t* n, int32_t* m, int32_t* C, int32
  *   active         device, uint8 [B][T]
  *   out            device, moc_result [B], 8-byte aligned
  *   hip_stream     a hipStream_t (NULL = the default stream)
- * starts/ends must be 4-byte aligned; when starts and ends are 16-byte aligned
- * and active is 4-byte aligned the rows are read with 16-byte loads, otherwise
- * element by element (same results).  B == 0 is a no-op.
+ * starts/ends must be 4-byte aligned.  The C copies of a node are read as one
+ * vector when the arrays allow it (C = 2: starts/ends 8-byte and active 2-byte
+ * aligned; C = 4: 16-byte and 4-byte), otherwise element by element (slower,
+ * same results).  B == 0 is a no-op.
  * Errors: MOC_EINVAL, MOC_EDEVICE, MOC_EHIP.
  */
 int moc_eval_batch(const moc_graph* g, int64_t B, const int32_t* starts, const int32_t* ends,
@@ -141,7 +142,9 @@ int moc_eval_batch(const moc_graph* g, int64_t B, const int32_t* starts, const i
  *   out_best    device, moc_best_move [B], or NULL: the applicable move that
  *               minimises (violations, max(peak, M), peak, q) lexicographically
  *               (max(peak, M) is the Phase-1 objective of Section 2.4)
- * At least one of out_moves / out_best must be given.
+ * At least one of out_moves / out_best must be given; both 8-byte aligned.
+ * This call keeps five T-word arrays in LDS: T <= about 8100.  A graph with an
+ * edge (v,v) is not accepted.
  * Errors: MOC_EINVAL, MOC_EDEVICE, MOC_EOVERFLOW (T too large for this call), MOC_EHIP.
  */
 int moc_eval_neighbours(const moc_graph* g, int64_t B, const int32_t* starts, const int32_t* ends,

@@ -92,6 +92,9 @@ int moc_graph_upload(int32_t n, const int32_t* in_ptr, const int32_t* in_idx, co
       delete g;
       return moc_set_hip_error(e);
     }
+    for (int v = 0; v < n; ++v)
+      for (int q = in_ptr[v]; q < in_ptr[v + 1]; ++q)
+        if (in_idx[q] == v) g->has_self_loop = 1;
     g->num_cu = prop.multiProcessorCount;
     g->max_lds = (int)prop.sharedMemPerBlock;
     if (moc_eval_lds_bytes(n, m, C) > g->max_lds) {

@@ -29,6 +29,7 @@ struct moc_graph {
   int device;
   int num_cu;
   int max_lds;       // bytes of LDS one workgroup may use
+  int has_self_loop; // an edge (v,v) exists: the neighbourhood kernel does not take such graphs
   GraphView view;    // device pointers
   void* allocs[8];   // device allocations backing `view`
   int n_allocs;

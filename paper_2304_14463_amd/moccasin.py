@@ -49,9 +49,8 @@ def lib():
         L.moc_graph_info.restype = ctypes.c_int
         L.moc_eval_batch.argtypes = [VP, I64, VP, VP, VP, VP, VP]
         L.moc_eval_batch.restype = ctypes.c_int
-        if hasattr(L, "moc_eval_neighbours"):
-            L.moc_eval_neighbours.argtypes = [VP, I64, VP, VP, VP, I32, VP, VP, VP]
-            L.moc_eval_neighbours.restype = ctypes.c_int
+        L.moc_eval_neighbours.argtypes = [VP, I64, VP, VP, VP, I32, VP, VP, VP]
+        L.moc_eval_neighbours.restype = ctypes.c_int
         L.moc_graph_free.argtypes = [VP]
         L.moc_graph_free.restype = None
         L.moc_strerror.argtypes = [ctypes.c_int]

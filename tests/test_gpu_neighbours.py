@@ -1,0 +1,172 @@
+"""GPU parity of moc_eval_neighbours: every move score equals the oracle's full
+re-evaluation of the moved candidate, bit-exact; the best move follows the
+documented ordering."""
+import numpy as np
+import pytest
+
+import oracle
+from helpers import F, upload
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def moc():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2304_14463_amd import moccasin
+    moccasin.lib()
+    return moccasin
+
+
+def to_dev(*arrs):
+    import torch
+    return [torch.from_numpy(np.ascontiguousarray(x)).cuda() for x in arrs]
+
+
+def gpu_neighbours(moc, gh, s, e, a, R, moves=True, best=True):
+    ds, de, da = to_dev(s, e, a)
+    om, ob = moc.moc_eval_neighbours(gh, ds, de, da, R, want_moves=moves, want_best=best)
+    om = moc.results_to_numpy(om, moc.MOVE_SCORE_DTYPE) if om is not None else None
+    ob = moc.results_to_numpy(ob, moc.BEST_MOVE_DTYPE) if ob is not None else None
+    return om, ob
+
+
+def random_candidates(rng, B, K, T, wild):
+    lo, hi = (-3, T + 3) if wild else (0, T)
+    s = rng.integers(lo, hi, size=(B, K)).astype(np.int32)
+    e = rng.integers(lo, hi, size=(B, K)).astype(np.int32)
+    swap = (rng.random((B, K)) < 0.8) & (s > e)
+    s, e = np.where(swap, e, s).astype(np.int32), np.where(swap, s, e).astype(np.int32)
+    a = (rng.random((B, K)) < 0.7).astype(np.uint8)
+    return s, e, a
+
+
+@pytest.mark.parametrize("n,C,R", [(1, 1, 1), (2, 2, 2), (5, 1, 3), (9, 2, 8), (12, 3, 4), (17, 2, 8), (30, 4, 2),
+                                   (40, 3, 8), (64, 2, 5)])
+def test_neighbours_full_table_small_graphs(moc, n, C, R):
+    from paper_2304_14463_amd.inputs import graph_from_edges
+    rng = np.random.default_rng(1000 * n + 10 * C + R)
+    edges = set()
+    for v in range(1, n):
+        for u in rng.integers(0, v, size=rng.integers(0, 4)):
+            edges.add((int(u), v))
+    g = graph_from_edges(n, sorted(edges), rng.integers(0, 50, n), rng.integers(1, 9, n))
+    T = n * C
+    budget = int(g.size.sum()) // 2
+    B = 6
+    s, e, a = random_candidates(rng, B, T, T, wild=True)
+    # one orderly candidate: a topological order with every copy 0 kept to the end
+    s[0] = 0; e[0] = 0; a[0] = 0
+    for v in range(n):
+        s[0, v * C], e[0, v * C], a[0, v * C] = v, T - 1, 1
+    gh = moc.moc_graph_upload(n, g.in_ptr, g.in_idx, g.size, g.dur, budget, C)
+    om, ob = gpu_neighbours(moc, gh, s, e, a, R)
+    for b in range(B):
+        scores, best = oracle.neighbours(g, budget, C, s[b], e[b], a[b], R)
+        assert (om[b]["violations"].astype(np.int64) == scores[:, 0]).all(), (n, C, R, b)
+        assert (om[b]["peak"].astype(np.int64) == scores[:, 1]).all(), (n, C, R, b)
+        assert (int(ob[b]["move"]), int(ob[b]["violations"]), int(ob[b]["peak"])) == best, (n, C, R, b)
+    # each output alone
+    om2, _ = gpu_neighbours(moc, gh, s, e, a, R, best=False)
+    _, ob2 = gpu_neighbours(moc, gh, s, e, a, R, moves=False)
+    assert om2.tobytes() == om.tobytes() and ob2.tobytes() == ob.tobytes()
+    gh.free()
+
+
+def test_neighbours_smallest_workload_all_moves(moc, workloads):
+    w = workloads(0)
+    gh = upload(moc, w)
+    s1, e1, a1 = w.candidates(0, 4)
+    s2, e2, a2 = w.candidates(w.B - 4, 4)
+    s, e, a = np.vstack([s1, s2]), np.vstack([e1, e2]), np.vstack([a1, a2])
+    om, ob = gpu_neighbours(moc, gh, s, e, a, 8)
+    for b in range(8):
+        scores, best = oracle.neighbours(w.graph, w.budget, w.C, s[b], e[b], a[b], 8)
+        assert (om[b]["violations"].astype(np.int64) == scores[:, 0]).all()
+        assert (om[b]["peak"].astype(np.int64) == scores[:, 1]).all()
+        assert (int(ob[b]["move"]), int(ob[b]["violations"]), int(ob[b]["peak"])) == best
+    gh.free()
+
+
+def test_neighbours_workload_sampled(moc, workloads):
+    """n=2000, C=2, R=8 at the full batch of 8192 bases (1.05e9 moves): the oracle
+    re-evaluates sampled moves; the best move is checked against the GPU's own
+    table for every base, and a sample of moves is applied and re-evaluated with
+    moc_eval_batch."""
+    import torch
+    from paper_2304_14463_amd.inputs import DeviceWorkload
+    w = workloads(3)
+    R = w.R
+    gh = upload(moc, w)
+    ds, de, da = DeviceWorkload(w).candidates()
+    om_t, ob_t = moc.moc_eval_neighbours(gh, ds, de, da, R)
+    torch.cuda.synchronize()
+    n_moves = w.T * 4 * R
+    rng = np.random.default_rng(3)
+    for b in (0, 1, w.B // 2, w.B - 1):
+        s, e, a = ds[b].cpu().numpy(), de[b].cpu().numpy(), da[b].cpu().numpy()
+        row = moc.results_to_numpy(om_t[b], moc.MOVE_SCORE_DTYPE)
+        pick = np.sort(rng.choice(n_moves, 1200, replace=False))
+        scores, _ = oracle.neighbours(w.graph, w.budget, w.C, s, e, a, R, moves=pick)
+        assert (row["violations"][pick].astype(np.int64) == scores[:, 0]).all(), b
+        assert (row["peak"][pick].astype(np.int64) == scores[:, 1]).all(), b
+        assert (scores[:, 0] >= 0).sum() > 300
+    # best = lexicographic minimum of (violations, max(peak, M), peak, move) over the applicable moves
+    ob = moc.results_to_numpy(ob_t, moc.BEST_MOVE_DTYPE)
+    for b0 in range(0, w.B, 1024):
+        rows = moc.results_to_numpy(om_t[b0:b0 + 8], moc.MOVE_SCORE_DTYPE)
+        for j in range(8):
+            v, p = rows[j]["violations"].astype(np.int64), rows[j]["peak"].astype(np.int64)
+            ok = v >= 0
+            key = np.lexsort((np.arange(n_moves)[ok], p[ok], np.maximum(p[ok], w.budget), v[ok]))
+            q = int(np.arange(n_moves)[ok][key[0]])
+            assert (int(ob[b0 + j]["move"]), int(ob[b0 + j]["violations"]), int(ob[b0 + j]["peak"])) == (q, v[q], p[q])
+    # apply sampled moves and evaluate them as candidates
+    b = 5
+    row = moc.results_to_numpy(om_t[b], moc.MOVE_SCORE_DTYPE)
+    pick = np.flatnonzero(row["violations"] >= 0)
+    pick = pick[rng.choice(pick.size, 512, replace=False)]
+    s = ds[b].cpu().numpy()[None].repeat(512, 0)
+    e = de[b].cpu().numpy()[None].repeat(512, 0)
+    a = da[b].cpu().numpy()[None].repeat(512, 0)
+    for j, q in enumerate(pick):
+        d, field, k = q % (2 * R), (q // (2 * R)) % 2, q // (4 * R)
+        delta = d - R if d < R else d - R + 1
+        (s if field == 0 else e)[j, k] += delta
+    ms, me, ma = to_dev(s, e, a)
+    res = moc.results_to_numpy(moc.moc_eval_batch(gh, ms, me, ma))
+    assert (res["violations"] == row["violations"][pick]).all() and (res["peak"] == row["peak"][pick]).all()
+    gh.free()
+
+
+def test_neighbours_argument_errors(moc, workloads):
+    import torch
+    from paper_2304_14463_amd.inputs import graph_from_edges
+    w = workloads(0)
+    gh = upload(moc, w)
+    s, e, a = to_dev(*w.candidates(0, 2))
+    for R in (0, 33):
+        with pytest.raises(moc.MoccasinError) as err:
+            moc.moc_eval_neighbours(gh, s, e, a, R)
+        assert err.value.code == -1
+    with pytest.raises(moc.MoccasinError):
+        moc.moc_eval_neighbours(gh, s, e, a, 4, want_moves=False, want_best=False)
+    gh.free()
+    # five T-word arrays do not fit the LDS for T = 9000
+    n = 9000
+    g = graph_from_edges(n, [(i, i + 1) for i in range(n - 1)], np.ones(n), np.ones(n))
+    gh = moc.moc_graph_upload(n, g.in_ptr, g.in_idx, g.size, g.dur, 10, 1)
+    z = torch.zeros((1, n), dtype=torch.int32, device="cuda")
+    with pytest.raises(moc.MoccasinError) as err:
+        moc.moc_eval_neighbours(gh, z, z, torch.zeros((1, n), dtype=torch.uint8, device="cuda"), 2)
+    assert err.value.code == -2
+    gh.free()
+    # self loops are refused by this call only
+    g = graph_from_edges(3, [(0, 1), (1, 1)], [1, 1, 1], [1, 1, 1])
+    gh = moc.moc_graph_upload(3, g.in_ptr, g.in_idx, g.size, g.dur, 10, 1)
+    z = torch.zeros((1, 3), dtype=torch.int32, device="cuda")
+    with pytest.raises(moc.MoccasinError) as err:
+        moc.moc_eval_neighbours(gh, z, z, torch.ones((1, 3), dtype=torch.uint8, device="cuda"), 2)
+    assert err.value.code == -1
+    gh.free()
