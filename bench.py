@@ -33,6 +33,9 @@ def parse():
     ap.add_argument("--batch", type=int, default=None, help="override the workload's batch size")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-also", action="store_true", help="skip the secondary (n=442) measurement")
+    ap.add_argument("--no-neighbours", action="store_true", help="skip the neighbourhood (n=2000) measurement")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run one 1 GiB device copy first (reference dispatch for the HBM byte counters)")
     return ap.parse_args()
 
 
@@ -80,6 +83,34 @@ def measure(moc, cfg, steps, warmup, batch=None):
     return w, gh, cand, res, info, ms_step, ms_kernel, ms_kernel_min, gbs
 
 
+def measure_neighbours(moc, steps, warmup):
+    """moc_eval_neighbours on the n=2000, C=2, R=8 workload: all 128000 moves of 8192 bases."""
+    import torch
+    from paper_2304_14463_amd.inputs import DeviceWorkload, make_workload
+    w = make_workload(3)
+    g = w.graph
+    gh = moc.moc_graph_upload(g.n, g.in_ptr, g.in_idx, g.size, g.dur, w.budget, w.C)
+    ds, de, da = DeviceWorkload(w).candidates()
+    n_moves = w.T * 4 * w.R
+    out = {}
+    for mode, (wm, wb) in (("full_table", (True, True)), ("best_only", (False, True))):
+        om, ob = moc.moc_eval_neighbours(gh, ds, de, da, w.R, want_moves=wm, want_best=wb)
+        for _ in range(warmup):
+            moc.moc_eval_neighbours(gh, ds, de, da, w.R, want_moves=wm, want_best=wb, out_moves=om, out_best=ob)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            moc.moc_eval_neighbours(gh, ds, de, da, w.R, want_moves=wm, want_best=wb, out_moves=om, out_best=ob)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / steps
+        out[mode] = {"ms_per_step": ms, "moves_per_s": w.B * n_moves / (ms * 1e-3),
+                     "bytes_written": (w.B * n_moves * 8 if wm else 0) + w.B * 16}
+        del om, ob
+    gh.free()
+    return {"workload": w.name, "n": w.n, "m": w.m, "C": w.C, "T": w.T, "B": w.B, "R": w.R,
+            "moves_per_candidate": n_moves, **out}
+
+
 def cpu_baseline(w, cand, res, target_seconds=15.0):
     """Times oracle.evaluate (single thread, as it stands) on the first candidates of the batch."""
     import numpy as np
@@ -122,6 +153,13 @@ def main():
         sys.exit("bench.py: no GPU visible; the evaluator has no CPU fallback.")
     from paper_2304_14463_amd import moccasin as moc
     moc.lib()
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
 
     w, gh, cand, res, info, ms_step, ms_kernel, ms_kernel_min, gbs = measure(
         moc, args.workload, args.steps, args.warmup, args.batch)
@@ -152,6 +190,9 @@ def main():
                         "kernel_ms_avg": msk2, "kernel_ms_min": mskmin2, "achieved_GBs": gbs2,
                         "frac_of_hbm_peak": gbs2 / HBM_PEAK_GBS}
         gh2.free()
+    if not args.no_neighbours:
+        torch.cuda.empty_cache()
+        line["neighbours"] = measure_neighbours(moc, max(3, args.steps // 4), 1)
     print(json.dumps(line))
 
 
