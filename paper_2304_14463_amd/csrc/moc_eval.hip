@@ -124,7 +124,7 @@ __device__ __forceinline__ bool is_live(uint32_t packed) { return (packed & 0xFF
 
 // Eq. (5) for one consumer start x (xs = x << 16) against one staged provider copy:
 // s_u + 1 <= x  and  x <= e_u.  A copy that is not live has s = 0xFFFF and fails.
-__device__ __forceinline__ bool covers(uint32_t pu, uint32_t x, uint32_t xs) { return (pu & 0xFFFFu) < x && pu >= xs; }
+__device__ __forceinline__ bool covers(uint32_t pu, uint32_t x, uint32_t xs) { return ((pu & 0xFFFFu) < x) & (pu >= xs); }
 
 template <int NT>
 __device__ __forceinline__ int count_distinct_starts(const Lds& L, const LdsLayout& lay, int tid) {
@@ -138,13 +138,16 @@ __device__ __forceinline__ int count_distinct_starts(const Lds& L, const LdsLayo
 
 // Cross-wave combine.  Every wave leaves its partial results in LDS; after the
 // barrier the lanes of wave 0 pick up one wave each and reduce in registers.
-template <int NT>
+// WAVE_TOTALS: viol and nlive are already sums over the wave (counted with ballots).
+template <int NT, bool WAVE_TOTALS = false>
 __device__ __forceinline__ void finish(const Lds& L, const GraphView& g, int tid, int lane, int wave, int S, int P,
                                        int viol, int nlive, int distinct, int dur, moc_result* __restrict__ out,
                                        int64_t b) {
   constexpr int NW = NT / kWave;
-  viol = wave_sum(viol);
-  nlive = wave_sum(nlive);
+  if constexpr (!WAVE_TOTALS) {
+    viol = wave_sum(viol);
+    nlive = wave_sum(nlive);
+  }
   distinct = wave_sum(distinct);
   dur = wave_sum(dur);
   if constexpr (NW > 1) {
@@ -262,27 +265,102 @@ __device__ __forceinline__ Record<CT> fetch_record(const uint32_t* at) {
 }
 
 // position t of the delta array -> word index (chunks of 32 words, 36 apart)
-__device__ __forceinline__ int delta_at(int t) { return t + ((t >> 5) << 2); }
+__device__ __forceinline__ int delta_at(int t) { return (int)((uint32_t)t + (((uint32_t)t >> 5) << 2)); }
+
+// Lane masks.  A predicate over the wave is one 64-bit scalar: a vector compare writes it
+// directly, the scalar unit combines and counts them, and nothing per lane is spent on
+// booleans.  The compares that pick a 16-bit half or a byte of their operand are written out
+// (sub-dword operand selects) since the compiler would first extract the field into a register.
+// Lanes that are switched off read as 0.  Use in wave-uniform control flow only.
+using lanemask = uint64_t;
+#define MOC_MASK_CMP(name, text, breg)                                             \
+  __device__ __forceinline__ lanemask name(uint32_t a, uint32_t b) {               \
+    lanemask m;                                                                    \
+    asm(text : "=s"(m) : "v"(a), breg(b));                                         \
+    return m;                                                                      \
+  }
+MOC_MASK_CMP(u_le, "v_cmp_le_u32_e64 %0, %1, %2", "v")
+MOC_MASK_CMP(i_gt, "v_cmp_gt_i32_e64 %0, %1, %2", "v")
+// b the same in every lane (a scalar register)
+MOC_MASK_CMP(u_lt_k, "v_cmp_lt_u32_e64 %0, %1, %2", "s")
+MOC_MASK_CMP(byte0_ne_k, "v_cmp_ne_u32_sdwa %0, %1, %2 src0_sel:BYTE_0 src1_sel:DWORD", "s")
+MOC_MASK_CMP(byte1_ne_k, "v_cmp_ne_u32_sdwa %0, %1, %2 src0_sel:BYTE_1 src1_sel:DWORD", "s")
+MOC_MASK_CMP(byte2_ne_k, "v_cmp_ne_u32_sdwa %0, %1, %2 src0_sel:BYTE_2 src1_sel:DWORD", "s")
+MOC_MASK_CMP(byte3_ne_k, "v_cmp_ne_u32_sdwa %0, %1, %2 src0_sel:BYTE_3 src1_sel:DWORD", "s")
+#undef MOC_MASK_CMP
+__device__ __forceinline__ lanemask byte_ne_k(uint32_t a, int i, uint32_t b) {
+  return i == 0 ? byte0_ne_k(a, b) : i == 1 ? byte1_ne_k(a, b) : i == 2 ? byte2_ne_k(a, b) : byte3_ne_k(a, b);
+}
+// per lane: m ? yes : no
+__device__ __forceinline__ uint32_t pick(lanemask m, uint32_t yes, uint32_t no) {
+  uint32_t r;
+  asm("v_cndmask_b32_e64 %0, %1, %2, %3" : "=v"(r) : "v"(no), "v"(yes), "s"(m));
+  return r;
+}
+// per lane: m ? yes : 0
+__device__ __forceinline__ uint32_t pick(lanemask m, uint32_t yes) {
+  uint32_t r;
+  asm("v_cndmask_b32_e64 %0, 0, %1, %2" : "=v"(r) : "v"(yes), "s"(m));
+  return r;
+}
+__device__ __forceinline__ int count(lanemask m) { return __builtin_popcountll(m); }
+// true in exactly the lanes of m: `if (lanes(m))` runs its body with those lanes switched on
+__device__ __forceinline__ bool lanes(lanemask m) { return __builtin_amdgcn_inverse_ballot_w64(m); }
+
+// Eq. (5) for one copy of the consumer, packed as s | e << 16 in pv, against the CT copies of
+// the provider in pu: adds to viol the number of lanes in which the copy is live and no copy of
+// the provider has s_u + 1 <= s_v <= e_u (a dead copy has s = 0xFFFF and covers nothing).
+// One block of instructions that ends in the count, so that three masks exist at a time
+// however the surrounding code is scheduled: the masks of many edges in flight at once do not
+// fit the scalar registers.
+#define MOC_COVER_FIRST(U)                                                        \
+  "v_cmp_lt_u32_sdwa %1, " U ", %5 src0_sel:WORD_0 src1_sel:WORD_0\n\t"           \
+  "v_cmp_ge_u32_sdwa %2, " U ", %5 src0_sel:WORD_1 src1_sel:WORD_0\n\t"           \
+  "s_and_b64 %1, %1, %2\n\t"
+#define MOC_COVER_NEXT(U)                                                         \
+  "v_cmp_lt_u32_sdwa %2, " U ", %5 src0_sel:WORD_0 src1_sel:WORD_0\n\t"           \
+  "v_cmp_ge_u32_sdwa %3, " U ", %5 src0_sel:WORD_1 src1_sel:WORD_0\n\t"           \
+  "s_and_b64 %2, %2, %3\n\t"                                                      \
+  "s_or_b64 %1, %1, %2\n\t"
+#define MOC_COVER_LAST                                                            \
+  "v_cmp_ne_u32_sdwa %2, %5, %6 src0_sel:WORD_0 src1_sel:DWORD\n\t"               \
+  "s_andn2_b64 %1, %2, %1\n\t"                                                    \
+  "s_bcnt1_i32_b64 %4, %1\n\t"                                                    \
+  "s_add_i32 %0, %0, %4"
+#define MOC_COVER_REGS "+s"(viol), "=&s"(t1), "=&s"(t2), "=&s"(t3), "=&s"(c) : "v"(pv), "s"(dead)
+template <int CT>
+__device__ __forceinline__ void count_live_uncovered(int& viol, const Record<CT>& pu, uint32_t pv) {
+  lanemask t1, t2, t3;
+  int c;
+  const uint32_t dead = MOC_DEAD;
+  if constexpr (CT == 1)
+    asm(MOC_COVER_FIRST("%7") MOC_COVER_LAST : MOC_COVER_REGS, "v"(pu.w[0]) : "scc");
+  else if constexpr (CT == 2)
+    asm(MOC_COVER_FIRST("%7") MOC_COVER_NEXT("%8") MOC_COVER_LAST : MOC_COVER_REGS, "v"(pu.w[0]), "v"(pu.w[1]) : "scc");
+  else if constexpr (CT == 3)
+    asm(MOC_COVER_FIRST("%7") MOC_COVER_NEXT("%8") MOC_COVER_NEXT("%9") MOC_COVER_LAST
+        : MOC_COVER_REGS, "v"(pu.w[0]), "v"(pu.w[1]), "v"(pu.w[2]) : "scc");
+  else
+    asm(MOC_COVER_FIRST("%7") MOC_COVER_NEXT("%8") MOC_COVER_NEXT("%9") MOC_COVER_NEXT("%10") MOC_COVER_LAST
+        : MOC_COVER_REGS, "v"(pu.w[0]), "v"(pu.w[1]), "v"(pu.w[2]), "v"(pu.w[3]) : "scc");
+}
+#undef MOC_COVER_FIRST
+#undef MOC_COVER_NEXT
+#undef MOC_COVER_LAST
+#undef MOC_COVER_REGS
 
 // Eq. (5) for one edge held in a register, pair = u*NS | v*NS << 16: every live copy of
-// the consumer v against the copies of the provider u.  Returns the violated instances.
+// the consumer v against the copies of the provider u.  Adds the violated instances over the
+// whole wave to viol (wave-uniform).
 template <int CT>
-__device__ __forceinline__ int check_edge(const Lds& L, uint32_t pair) {
+__device__ __forceinline__ void check_edge(int& viol, const Lds& L, uint32_t pair) {
   // The pair is the same for every candidate.  Hide that from the optimiser: otherwise it
   // keeps every address derived from it in a register of its own for the whole kernel.
   asm volatile("" : "+v"(pair));
   const Record<CT> pv = fetch_record<CT>(L.packed + (pair >> 16));
   const Record<CT> pu = fetch_record<CT>(L.packed + (pair & 0xFFFFu));
-  int viol = 0;
 #pragma unroll
-  for (int i = 0; i < CT; ++i) {
-    const uint32_t x = pv.w[i] & 0xFFFFu, xs = x << 16;
-    bool cov = false;
-#pragma unroll
-    for (int q = 0; q < CT; ++q) cov = cov || covers(pu.w[q], x, xs);
-    viol += (is_live(pv.w[i]) && !cov) ? 1 : 0;
-  }
-  return viol;
+  for (int i = 0; i < CT; ++i) count_live_uncovered<CT>(viol, pu, pv.w[i]);
 }
 
 template <int NT, int CT, int ITERS>
@@ -295,7 +373,8 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
   constexpr int kEarly = ITERS * 2 / 5;   // node slots re-requested during phase 1
   extern __shared__ uint32_t lds_raw[];
   const Lds L = carve(lds_raw, lay);
-  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  const int tid = threadIdx.x, lane = tid & (kWave - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);   // the same in every lane: say so
   const int T = g.T, n = g.n;
   const int64_t total = B * (int64_t)T;
 
@@ -338,7 +417,8 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
   __syncthreads();
 
   for (int64_t b = blockIdx.x; b < B; b += gridDim.x) {
-    int viol = 0, nlive = 0, dur = 0;   // per lane
+    int viol = 0, nlive = 0;   // per wave (wave-uniform, counted with ballots)
+    int dur = 0;               // per lane
     // The workgroup's next candidate; the last one re-reads itself so that the loads below
     // need no condition.  Slot `it` is requested as soon as phase 1 has consumed the
     // registers of slot `it` (the first kEarly slots) or between the steps of phase 2 (the
@@ -351,7 +431,6 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
     for (int it = 0; it < ITERS; ++it) {
       int v = it * NT + tid;
       asm volatile("" : "+v"(v));               // as in check_edge: keep derived addresses out of registers
-      const bool isn = v < n;
       // m_v, w_v of this slot have arrived on every path from here on (its loads were issued
       // before anything that is still in flight)
       asm volatile("" ::"v"(sd[it].x), "v"(sd[it].y));
@@ -362,35 +441,35 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
           const uint32_t off = (uint32_t)v * CT, a_last = flags_last(b * T);
           flags >>= 8 * (off - (off < a_last ? off : a_last));
         }
-        bool act[CT], live[CT];
+        // Eq. (2), (7), (8), (3) on lane masks; Eq. (1) per lane
+        const lanemask isn = u_lt_k((uint32_t)v, (uint32_t)n);
+        lanemask act[CT], live[CT];
         Record<CT> rec;
-        int nact = 0;
 #pragma unroll
         for (int i = 0; i < CT; ++i) {
-          act[i] = isn && ((flags >> (8 * i)) & 0xFFu) != 0;
-          const bool well = (uint32_t)r.s[i] <= (uint32_t)r.e[i] && (uint32_t)r.e[i] < (uint32_t)T;   // Eq. (2), (8)
-          live[i] = act[i] && well;
-          viol += (act[i] && !well) ? 1 : 0;
-          nact += act[i] ? 1 : 0;
-          nlive += live[i] ? 1 : 0;
-          rec.w[i] = live[i] ? ((uint32_t)r.s[i] | ((uint32_t)r.e[i] << 16)) : MOC_DEAD;
+          act[i] = byte_ne_k(flags, i, 0u) & isn;
+          const lanemask well = u_le((uint32_t)r.s[i], (uint32_t)r.e[i]) & u_lt_k((uint32_t)r.e[i], (uint32_t)T);
+          live[i] = act[i] & well;
+          viol += count(act[i] & ~well);
+          nlive += count(live[i]);
+          dur += (int)pick(act[i], (uint32_t)sd[it].y);
+          rec.w[i] = pick(live[i], (uint32_t)r.s[i] | ((uint32_t)r.e[i] << 16), MOC_DEAD);
         }
-        viol += (isn && !act[0]) ? 1 : 0;   // Eq. (7)
-        dur += nact * sd[it].y;              // Eq. (1)
+        viol += count(isn & ~act[0]);
 #pragma unroll
         for (int i = 0; i + 1 < CT; ++i) {   // Eq. (3): against the next live copy
-          bool seen = false, late = false;
+          lanemask seen = 0, late = 0;
 #pragma unroll
           for (int j = i + 1; j < CT; ++j) {
-            late = late || (!seen && live[j] && r.e[i] > r.s[j]);
-            seen = seen || live[j];
+            late |= ~seen & live[j] & i_gt((uint32_t)r.e[i], (uint32_t)r.s[j]);
+            seen |= live[j];
           }
-          viol += (live[i] && late) ? 1 : 0;
+          viol += count(live[i] & late);
         }
-        if (isn) store_record<CT>(L.packed + v * NS, rec);
+        if (lanes(isn)) store_record<CT>(L.packed + v * NS, rec);
 #pragma unroll
         for (int i = 0; i < CT; ++i) {
-          if (live[i]) {
+          if (lanes(live[i])) {
             atomicAdd(&L.delta[delta_at(r.s[i])], sd[it].x);          // Eq. (4): allocated at s ...
             atomicSub(&L.delta[delta_at(r.e[i] + 1)], sd[it].x);      // ... released after e
             atomicOr(&L.occ[r.s[i] >> 5], 1u << (r.s[i] & 31));       // Eq. (6)
@@ -436,9 +515,9 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
       if (it > 0 && kEarly + it < ITERS) request(kEarly + it, next_row);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int j = it * kEdgesPerNode; j < (it + 1) * kEdgesPerNode; ++j) viol += check_edge<CT>(L, edge[j]);
+      for (int j = it * kEdgesPerNode; j < (it + 1) * kEdgesPerNode; ++j) check_edge<CT>(viol, L, edge[j]);
     }
-    finish<NT>(L, g, tid, lane, wave, S, P, viol, nlive, distinct, dur, out, b);
+    finish<NT, true>(L, g, tid, lane, wave, S, P, viol, nlive, distinct, dur, out, b);
   }
 }
 
