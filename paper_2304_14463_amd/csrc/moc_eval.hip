@@ -40,27 +40,50 @@ constexpr int kMaxIters = 6;       // nodes per lane the register-resident kerne
 constexpr int kEdgesPerNode = 3;   // edges per lane = kEdgesPerNode * nodes per lane
 constexpr int kChunk = 32;         // delta positions per chunk ...
 constexpr int kChunkStride = 36;   // ... stored 36 words apart: 16 lanes x 16 bytes hit 64 distinct banks
+constexpr int kQueueCap = 192;     // C >= 3: edges a wave sets aside before it has to work them off
 
 // ------------------------------------------------------------------ LDS layouts
+// Word offsets of the arrays inside the dynamic LDS segment, and their sizes in words.
 struct LdsLayout {
+  int packed_off, rest_off, delta_off, occ_off, red_off, queue_off;
   int chunk;       // general kernel: delta entries per thread (odd: conflict-free strided reads)
   int n_chunks;    // register-resident kernel: chunks of kChunk positions
-  int delta_len;   // words
-  int packed_len;  // words
+  int delta_len;
+  int packed_len;  // node records (register-resident kernel, C >= 3: first copies, then the rest)
   int occ_words;   // ceil(T / 32)
+  int qcap;        // register-resident kernel, C >= 3: entries per wave in the queue of edges set aside
   int bytes;
 };
 
-// register-resident kernel: delta in padded chunks, one record of `ns` words per node (+1 dummy node)
-LdsLayout fast_layout(int n, int C, int nt) {
-  const int T = n * C, ns = moc_node_stride(C);
+constexpr int round4(int x) { return (x + 3) & ~3; }
+
+// Register-resident kernel.  Node records first, at LDS address 0: with C <= 2 one record of
+// C words per node; with C >= 3 the first copy of every node (1 word), then the other copies
+// of every node (2 words for C = 3, 4 for C = 4).  One dummy node n that is never live ends
+// each array.  Then the delta array in padded chunks, the start bitmap, the cross-wave
+// exchange area and (C >= 3) a queue per wave, shrunk to fit when LDS is short.
+LdsLayout fast_layout(int n, int C, int nt, int max_lds) {
+  const int T = n * C, nw = nt / kWave;
   LdsLayout l;
   l.chunk = 0;
   l.n_chunks = (T + 1 + kChunk - 1) / kChunk;
   l.delta_len = l.n_chunks * kChunkStride;
-  l.packed_len = ((n + 1) * ns + 3) & ~3;
+  const int first_len = round4((n + 1) * moc_node_stride(C));
+  const int rest_len = C >= 3 ? round4((n + 1) * (C == 3 ? 2 : 4)) : 0;
+  l.packed_len = first_len + rest_len;
   l.occ_words = (T + 31) / 32;
-  l.bytes = 4 * (l.delta_len + l.packed_len + l.occ_words + (nt / kWave) * kRedStride);
+  l.packed_off = 0;
+  l.rest_off = first_len;
+  l.delta_off = l.packed_len;
+  l.occ_off = l.delta_off + l.delta_len;
+  l.red_off = l.occ_off + l.occ_words;
+  l.queue_off = l.red_off + nw * kRedStride;
+  l.qcap = C >= 3 ? kQueueCap : 0;
+  l.bytes = 4 * (l.queue_off + nw * l.qcap);
+  while (l.bytes > max_lds && l.qcap > kWave) {
+    l.qcap -= kWave;
+    l.bytes = 4 * (l.queue_off + nw * l.qcap);
+  }
   return l;
 }
 
@@ -70,25 +93,36 @@ LdsLayout general_layout(int n, int C, int nt) {
   l.chunk = ((T + 1 + nt - 1) / nt) | 1;
   l.n_chunks = 0;
   l.delta_len = nt * l.chunk;
-  l.packed_len = (T + 3) & ~3;
+  l.packed_len = round4(T);
   l.occ_words = (T + 31) / 32;
-  l.bytes = 4 * (l.delta_len + l.packed_len + l.occ_words + (nt / kWave) * kRedStride);
+  l.delta_off = 0;
+  l.packed_off = l.delta_len;
+  l.rest_off = l.packed_off;
+  l.occ_off = l.packed_off + l.packed_len;
+  l.red_off = l.occ_off + l.occ_words;
+  l.queue_off = l.red_off + (nt / kWave) * kRedStride;
+  l.qcap = 0;
+  l.bytes = 4 * l.queue_off;
   return l;
 }
 
 struct Lds {
   int32_t* delta;
   uint32_t* packed;
+  uint32_t* rest;
   uint32_t* occ;
   int32_t* red;
+  uint32_t* queue;
 };
 
 __device__ __forceinline__ Lds carve(uint32_t* base, const LdsLayout& lay) {
   Lds l;
-  l.delta = reinterpret_cast<int32_t*>(base);
-  l.packed = base + lay.delta_len;
-  l.occ = l.packed + lay.packed_len;
-  l.red = reinterpret_cast<int32_t*>(l.occ + lay.occ_words);
+  l.delta = reinterpret_cast<int32_t*>(base + lay.delta_off);
+  l.packed = base + lay.packed_off;
+  l.rest = base + lay.rest_off;
+  l.occ = base + lay.occ_off;
+  l.red = reinterpret_cast<int32_t*>(base + lay.red_off);
+  l.queue = base + lay.queue_off;
   return l;
 }
 
@@ -234,38 +268,49 @@ __device__ __forceinline__ void load_node(const int32_t* __restrict__ s_row, con
   }
 }
 
-// The record of a node: CT packed words, stored/fetched with one LDS access of NS words.
+// ------------------------------------------------------------------ LDS by byte address
+// The dynamic LDS segment starts at address 0 (the kernels declare no static LDS, which the
+// host verifies before the first launch) and the node records are its first array: the LDS
+// address of a record is its word index times 4 and needs no base register.
+typedef __attribute__((address_space(3))) uint32_t lds_u32;
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef __attribute__((address_space(3))) u32x2 lds_u32x2;
+__device__ __forceinline__ uint32_t lds_read(uint32_t addr) { return *(const lds_u32*)(uintptr_t)addr; }
+__device__ __forceinline__ uint2 lds_read2(uint32_t addr) {
+  const u32x2 v = *(const lds_u32x2*)(uintptr_t)addr;
+  return make_uint2(v.x, v.y);
+}
+
+// 4 * (low / high half of p): the LDS address of the record whose word index is packed in p.
+// Written out so that the half is picked by the shift itself, and kept where it is used: the
+// operand never changes, and the optimiser would otherwise hold every such address in a
+// register of its own for the whole kernel.
+__device__ __forceinline__ uint32_t addr_lo16(uint32_t p) {
+  uint32_t r;
+  asm volatile("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_0"
+               : "=v"(r) : "s"(2u), "v"(p));
+  return r;
+}
+__device__ __forceinline__ uint32_t addr_hi16(uint32_t p) {
+  uint32_t r;
+  asm volatile("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_1"
+               : "=v"(r) : "s"(2u), "v"(p));
+  return r;
+}
+
+// The copies of a node as packed words s | e << 16 (MOC_DEAD if not live).
 template <int CT>
 struct Record {
   uint32_t w[CT];
 };
 
-template <int CT>
-__device__ __forceinline__ void store_record(uint32_t* at, const Record<CT>& r) {
-  if constexpr (CT == 1) at[0] = r.w[0];
-  else if constexpr (CT == 2) *reinterpret_cast<uint2*>(at) = make_uint2(r.w[0], r.w[1]);
-  else if constexpr (CT == 3) *reinterpret_cast<uint4*>(at) = make_uint4(r.w[0], r.w[1], r.w[2], MOC_DEAD);
-  else *reinterpret_cast<uint4*>(at) = make_uint4(r.w[0], r.w[1], r.w[2], r.w[3]);
+// position t of the delta array -> word index (chunks of 32 words, 36 apart).  The index is
+// made opaque so that it is formed in two instructions and scaled by the addressing one.
+__device__ __forceinline__ int delta_at(int t) {
+  int idx = (int)((uint32_t)t + (((uint32_t)t >> 5) << 2));
+  asm("" : "+v"(idx));
+  return idx;
 }
-
-template <int CT>
-__device__ __forceinline__ Record<CT> fetch_record(const uint32_t* at) {
-  Record<CT> r;
-  if constexpr (CT == 1) {
-    r.w[0] = at[0];
-  } else if constexpr (CT == 2) {
-    const uint2 v = *reinterpret_cast<const uint2*>(at);
-    r.w[0] = v.x; r.w[1] = v.y;
-  } else {
-    const uint4 v = *reinterpret_cast<const uint4*>(at);
-    r.w[0] = v.x; r.w[1] = v.y; r.w[2] = v.z;
-    if constexpr (CT == 4) r.w[3] = v.w;
-  }
-  return r;
-}
-
-// position t of the delta array -> word index (chunks of 32 words, 36 apart)
-__device__ __forceinline__ int delta_at(int t) { return (int)((uint32_t)t + (((uint32_t)t >> 5) << 2)); }
 
 // Lane masks.  A predicate over the wave is one 64-bit scalar: a vector compare writes it
 // directly, the scalar unit combines and counts them, and nothing per lane is spent on
@@ -306,6 +351,10 @@ __device__ __forceinline__ uint32_t pick(lanemask m, uint32_t yes) {
 __device__ __forceinline__ int count(lanemask m) { return __builtin_popcountll(m); }
 // true in exactly the lanes of m: `if (lanes(m))` runs its body with those lanes switched on
 __device__ __forceinline__ bool lanes(lanemask m) { return __builtin_amdgcn_inverse_ballot_w64(m); }
+// number of lanes of m below the calling lane, plus base
+__device__ __forceinline__ uint32_t rank_in(lanemask m, uint32_t base) {
+  return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, base));
+}
 
 // Eq. (5) for one copy of the consumer, packed as s | e << 16 in pv, against the CT copies of
 // the provider in pu: adds to viol the number of lanes in which the copy is live and no copy of
@@ -349,18 +398,73 @@ __device__ __forceinline__ void count_live_uncovered(int& viol, const Record<CT>
 #undef MOC_COVER_LAST
 #undef MOC_COVER_REGS
 
-// Eq. (5) for one edge held in a register, pair = u*NS | v*NS << 16: every live copy of
-// the consumer v against the copies of the provider u.  Adds the violated instances over the
-// whole wave to viol (wave-uniform).
+// Eq. (5), C <= 2, for one edge held in a register as pair = u*C | v*C << 16 (word indices of
+// the two records): every live copy of the consumer v against the copies of the provider u.
+// Adds the violated instances over the whole wave to viol (wave-uniform).
 template <int CT>
-__device__ __forceinline__ void check_edge(int& viol, const Lds& L, uint32_t pair) {
-  // The pair is the same for every candidate.  Hide that from the optimiser: otherwise it
-  // keeps every address derived from it in a register of its own for the whole kernel.
-  asm volatile("" : "+v"(pair));
-  const Record<CT> pv = fetch_record<CT>(L.packed + (pair >> 16));
-  const Record<CT> pu = fetch_record<CT>(L.packed + (pair & 0xFFFFu));
+__device__ __forceinline__ void check_edge(int& viol, uint32_t pair) {
+  Record<CT> pv, pu;
+  if constexpr (CT == 1) {
+    pv.w[0] = lds_read(addr_hi16(pair));
+    pu.w[0] = lds_read(addr_lo16(pair));
+  } else {
+    const uint2 rv = lds_read2(addr_hi16(pair)), ru = lds_read2(addr_lo16(pair));
+    pv.w[0] = rv.x; pv.w[1] = rv.y; pu.w[0] = ru.x; pu.w[1] = ru.y;
+  }
 #pragma unroll
   for (int i = 0; i < CT; ++i) count_live_uncovered<CT>(viol, pu, pv.w[i]);
+}
+
+// Eq. (5), C >= 3, first pass over an edge pair = u | v << 16: only the first copies of the
+// two nodes are fetched (pu, pv: one word each; bit 31 says that the node has other live
+// copies).  Where neither node has other live copies the instance is settled here and counted
+// into viol; the lanes where one has are returned, their edges go to the wave's queue.
+__device__ __forceinline__ lanemask check_first_copies(int& viol, uint32_t pu, uint32_t pv) {
+  lanemask t1, t2, more;
+  int c;
+  const uint32_t dead = MOC_DEAD;
+  asm("v_cmp_lt_u32_sdwa %1, %5, %6 src0_sel:WORD_0 src1_sel:WORD_0\n\t"
+      "v_cmp_ge_u32_sdwa %2, %5, %6 src0_sel:WORD_1 src1_sel:WORD_0\n\t"
+      "s_and_b64 %1, %1, %2\n\t"   // covered by the first copy of u (void where bit 31 of pu is set)
+      "v_cmp_ne_u32_sdwa %2, %6, %7 src0_sel:WORD_0 src1_sel:DWORD\n\t"
+      "s_andn2_b64 %1, %2, %1\n\t"   // first copy of v live and not covered
+      "v_cmp_gt_i32_e64 %3, 0, %5\n\t"
+      "v_cmp_gt_i32_e64 %2, 0, %6\n\t"
+      "s_or_b64 %3, %3, %2\n\t"      // one of the nodes has other live copies
+      "s_andn2_b64 %1, %1, %3\n\t"
+      "s_bcnt1_i32_b64 %4, %1\n\t"
+      "s_add_i32 %0, %0, %4"
+      : "+s"(viol), "=&s"(t1), "=&s"(t2), "=&s"(more), "=&s"(c)
+      : "v"(pu), "v"(pv), "s"(dead)
+      : "scc");
+  return more;
+}
+
+// Eq. (5), C >= 3, second pass: the full test (every live copy of v against every copy of u)
+// for the `count` edges in the wave's queue, 64 at a time.
+template <int CT>
+__device__ __forceinline__ void drain_queue(int& viol, const Lds& L, const uint32_t* queue, int count, int lane,
+                                            uint32_t dummy_pair) {
+  constexpr int RS = CT == 3 ? 2 : 4;
+  for (int base = 0; base < count; base += kWave) {
+    const int idx = base + lane;   // inside the queue: its capacity is a multiple of 64
+    const uint32_t pair = pick(u_lt_k((uint32_t)idx, (uint32_t)count), queue[idx], dummy_pair);
+    const uint32_t v = pair >> 16, u = pair & 0xFFFFu;
+    Record<CT> pv, pu;
+    pv.w[0] = L.packed[v];
+    pu.w[0] = L.packed[u] & 0x7FFFFFFFu;   // only the provider's end is read from the high half
+    if constexpr (CT == 3) {
+      const uint2 rv = *reinterpret_cast<const uint2*>(L.rest + v * RS);
+      const uint2 ru = *reinterpret_cast<const uint2*>(L.rest + u * RS);
+      pv.w[1] = rv.x; pv.w[2] = rv.y; pu.w[1] = ru.x; pu.w[2] = ru.y;
+    } else {
+      const uint4 rv = *reinterpret_cast<const uint4*>(L.rest + v * RS);
+      const uint4 ru = *reinterpret_cast<const uint4*>(L.rest + u * RS);
+      pv.w[1] = rv.x; pv.w[2] = rv.y; pv.w[3] = rv.z; pu.w[1] = ru.x; pu.w[2] = ru.y; pu.w[3] = ru.z;
+    }
+#pragma unroll
+    for (int i = 0; i < CT; ++i) count_live_uncovered<CT>(viol, pu, pv.w[i]);
+  }
 }
 
 template <int NT, int CT, int ITERS>
@@ -369,25 +473,29 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
                                                         const uint8_t* __restrict__ active,
                                                         moc_result* __restrict__ out, LdsLayout lay) {
   constexpr int EPT = kEdgesPerNode * ITERS;
-  constexpr int NS = CT == 3 ? 4 : CT;
-  constexpr int kEarly = ITERS * 2 / 5;   // node slots re-requested during phase 1
+  constexpr bool kSplit = CT >= 3;          // first copies and other copies in separate arrays
+  constexpr int NS = kSplit ? 1 : CT;       // words per node in the first array
+  constexpr int RS = CT == 3 ? 2 : 4;       // kSplit: words per node in the second
+  constexpr int kEarly = ITERS * 2 / 5;     // node slots re-requested during phase 1
   extern __shared__ uint32_t lds_raw[];
   const Lds L = carve(lds_raw, lay);
   const int tid = threadIdx.x, lane = tid & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);   // the same in every lane: say so
   const int T = g.T, n = g.n;
   const int64_t total = B * (int64_t)T;
+  uint32_t* const queue = L.queue + wave * lay.qcap;   // kSplit: this wave's edges set aside
+  const uint32_t dummy_pair = (uint32_t)(n * NS) | (uint32_t)(n * NS) << 16;   // the dummy node is never live
 
   for (int i = tid; i < lay.delta_len; i += NT) L.delta[i] = 0;
   for (int i = tid; i < lay.occ_words; i += NT) L.occ[i] = 0;
-  for (int i = tid; i < lay.packed_len; i += NT) L.packed[i] = MOC_DEAD;   // incl. the dummy node n
+  for (int i = tid; i < lay.packed_len; i += NT) L.packed[i] = MOC_DEAD;   // both record arrays, incl. the dummy node
 
   // what a lane owns never changes: its edges stay in registers
   uint32_t edge[EPT];
 #pragma unroll
   for (int j = 0; j < EPT; ++j) {
     const int e = j * NT + tid;
-    edge[j] = e < g.m ? g.edge_pair[e] : (uint32_t)(n * NS) << 16;   // padding: the dummy node is never live
+    edge[j] = e < g.m ? g.edge_pair[e] : dummy_pair;
   }
   NodeIn<CT> in[ITERS];
   // m_v, w_v of the lane's nodes: re-read (from L2) at the start of each phase 1, behind the
@@ -412,12 +520,19 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
     asm volatile("" : "+v"(v));                // keep the per-slot offsets out of registers
     load_node<CT>(starts + row, ends + row, active + row, (uint32_t)v * CT, flags_last(row), in[it]);
   };
+  // Eq. (4), (6): one live copy [s, e] of a node of size m_v into the delta array (+m_v at s,
+  // -m_v after e) and the bitmap of start positions
+  auto scatter = [&](int s, int e, int size) {
+    atomicAdd(&L.delta[delta_at(s)], size);
+    atomicSub(&L.delta[delta_at(e + 1)], size);
+    atomicOr(&L.occ[s >> 5], 1u << (s & 31));
+  };
 #pragma unroll
   for (int it = 0; it < ITERS; ++it) request(it, (int64_t)blockIdx.x * T);   // grid <= B
   __syncthreads();
 
   for (int64_t b = blockIdx.x; b < B; b += gridDim.x) {
-    int viol = 0, nlive = 0;   // per wave (wave-uniform, counted with ballots)
+    int viol = 0, nlive = 0;   // per wave (the same in every lane, counted on lane masks)
     int dur = 0;               // per lane
     // The workgroup's next candidate; the last one re-reads itself so that the loads below
     // need no condition.  Slot `it` is requested as soon as phase 1 has consumed the
@@ -430,7 +545,7 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
 #pragma unroll
     for (int it = 0; it < ITERS; ++it) {
       int v = it * NT + tid;
-      asm volatile("" : "+v"(v));               // as in check_edge: keep derived addresses out of registers
+      asm volatile("" : "+v"(v));               // as for the edges: keep derived addresses out of registers
       // m_v, w_v of this slot have arrived on every path from here on (its loads were issued
       // before anything that is still in flight)
       asm volatile("" ::"v"(sd[it].x), "v"(sd[it].y));
@@ -466,13 +581,45 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
           }
           viol += count(live[i] & late);
         }
-        if (lanes(isn)) store_record<CT>(L.packed + v * NS, rec);
+        lanemask others = 0;   // lanes whose node has a live copy besides the first
 #pragma unroll
-        for (int i = 0; i < CT; ++i) {
-          if (lanes(live[i])) {
-            atomicAdd(&L.delta[delta_at(r.s[i])], sd[it].x);          // Eq. (4): allocated at s ...
-            atomicSub(&L.delta[delta_at(r.e[i] + 1)], sd[it].x);      // ... released after e
-            atomicOr(&L.occ[r.s[i] >> 5], 1u << (r.s[i] & 31));       // Eq. (6)
+        for (int i = 1; i < CT; ++i) others |= live[i];
+        if (lanes(isn)) {
+          if constexpr (CT == 1) {
+            L.packed[v] = rec.w[0];
+          } else if constexpr (CT == 2) {
+            *reinterpret_cast<uint2*>(L.packed + v * 2) = make_uint2(rec.w[0], rec.w[1]);
+          } else {
+            L.packed[v] = rec.w[0] | pick(others, 0x80000000u);
+            if constexpr (CT == 3) *reinterpret_cast<uint2*>(L.rest + v * RS) = make_uint2(rec.w[1], rec.w[2]);
+            else *reinterpret_cast<uint4*>(L.rest + v * RS) = make_uint4(rec.w[1], rec.w[2], rec.w[3], MOC_DEAD);
+          }
+        }
+        if (lanes(live[0])) scatter(r.s[0], r.e[0], sd[it].x);
+        // The other copies are rarely live: in round k every lane brings the k-th of its
+        // live ones, so that a wave runs as many rounds as its busiest node has such copies
+        // rather than one per copy.
+        lanemask left[CT];
+#pragma unroll
+        for (int i = 1; i < CT; ++i) left[i] = live[i];
+#pragma unroll
+        for (int round = 1; round < CT; ++round) {
+          if (others == 0) break;
+          int sx = r.s[CT - 1], ex = r.e[CT - 1];
+#pragma unroll
+          for (int i = CT - 2; i >= round; --i) {   // the first of the lane's copies that are left
+            sx = (int)pick(left[i], (uint32_t)r.s[i], (uint32_t)sx);
+            ex = (int)pick(left[i], (uint32_t)r.e[i], (uint32_t)ex);
+          }
+          if (lanes(others)) scatter(sx, ex, sd[it].x);
+          lanemask before = 0;
+          others = 0;
+#pragma unroll
+          for (int i = round; i < CT; ++i) {
+            const lanemask taken = left[i] & ~before;
+            before |= left[i];
+            left[i] &= ~taken;
+            others |= left[i];
           }
         }
       }
@@ -509,14 +656,31 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
     }
     const int distinct = count_distinct_starts<NT>(L, lay, tid);
     // (c) edges, three per slice of the prefetch
+    int queued = 0;
 #pragma unroll
     for (int it = 0; it < ITERS; ++it) {
       __builtin_amdgcn_sched_barrier(0);
       if (it > 0 && kEarly + it < ITERS) request(kEarly + it, next_row);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int j = it * kEdgesPerNode; j < (it + 1) * kEdgesPerNode; ++j) check_edge<CT>(viol, L, edge[j]);
+      for (int j = it * kEdgesPerNode; j < (it + 1) * kEdgesPerNode; ++j) {
+        if constexpr (!kSplit) {
+          check_edge<CT>(viol, edge[j]);
+        } else {
+          if (queued > lay.qcap - kWave) {   // the next 64 might not fit: work the queue off first
+            drain_queue<CT>(viol, L, queue, queued, lane, dummy_pair);
+            queued = 0;
+          }
+          const uint32_t pv = lds_read(addr_hi16(edge[j])), pu = lds_read(addr_lo16(edge[j]));
+          const lanemask more = check_first_copies(viol, pu, pv);
+          if (more != 0) {
+            if (lanes(more)) queue[rank_in(more, (uint32_t)queued)] = edge[j];
+            queued += count(more);
+          }
+        }
+      }
     }
+    if constexpr (kSplit) drain_queue<CT>(viol, L, queue, queued, lane, dummy_pair);
     finish<NT, true>(L, g, tid, lane, wave, S, P, viol, nlive, distinct, dur, out, b);
   }
 }
@@ -601,6 +765,15 @@ template <typename K>
 int launch_kernel(K kern, int nt, const moc_graph* g, const LdsLayout& lay, int64_t B, const int32_t* starts,
                   const int32_t* ends, const uint8_t* active, moc_result* out, hipStream_t stream) {
   if (lay.bytes > g->max_lds) return MOC_EOVERFLOW;
+  // The kernels address the node records from LDS address 0: nothing may be placed before the
+  // dynamic segment.  Checked once per kernel.
+  static bool checked = false;   // one per instantiation, i.e. per kernel
+  if (!checked) {
+    hipFuncAttributes attr;
+    MOC_HIP(hipFuncGetAttributes(&attr, reinterpret_cast<const void*>(kern)));
+    if (attr.sharedSizeBytes != 0) return MOC_EINVAL;
+    checked = true;
+  }
   MOC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                               lay.bytes));
   int per_cu = 0;
@@ -651,7 +824,7 @@ int launch_nt(const moc_graph* g, int64_t B, const int32_t* s, const int32_t* e,
               hipStream_t st, bool aligned) {
   const int n = g->view.n, m = g->view.m, C = g->view.C;
   if (aligned && fast_shape(n, m, C, NT)) {
-    const LdsLayout lay = fast_layout(n, C, NT);
+    const LdsLayout lay = fast_layout(n, C, NT, g->max_lds);
     const int iters = slots_per_lane(n, m, NT);
     switch (C) {
       case 1: return launch_iters<NT, 1>(iters, g, lay, B, s, e, a, out, st);
@@ -665,13 +838,13 @@ int launch_nt(const moc_graph* g, int64_t B, const int32_t* s, const int32_t* e,
 
 }  // namespace
 
-int moc_node_stride(int C) { return C == 3 ? 4 : C; }
+int moc_node_stride(int C) { return C == 2 ? 2 : 1; }
 
-int moc_eval_lds_bytes(int n, int m, int C) {
+int moc_eval_lds_bytes(int n, int m, int C, int max_lds) {
   const int nt = block_threads(n, m);
   const int general = general_layout(n, C, nt).bytes;
   if (!fast_shape(n, m, C, nt)) return general;
-  const int fast = fast_layout(n, C, nt).bytes;   // misaligned candidate arrays fall back to the general kernel
+  const int fast = fast_layout(n, C, nt, max_lds).bytes;   // misaligned candidate arrays fall back to the general kernel
   return fast > general ? fast : general;
 }
 

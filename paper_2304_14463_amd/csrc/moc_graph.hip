@@ -97,7 +97,7 @@ int moc_graph_upload(int32_t n, const int32_t* in_ptr, const int32_t* in_idx, co
         if (in_idx[q] == v) g->has_self_loop = 1;
     g->num_cu = prop.multiProcessorCount;
     g->max_lds = (int)prop.sharedMemPerBlock;
-    if (moc_eval_lds_bytes(n, m, C) > g->max_lds) {
+    if (moc_eval_lds_bytes(n, m, C, g->max_lds) > g->max_lds) {
       delete g;
       return MOC_EOVERFLOW;
     }

@@ -35,11 +35,14 @@ struct moc_graph {
   int n_allocs;
 };
 
-// Words per node record in LDS: C rounded up to 1, 2 or 4 so that a record is one wide access.
+// Unit of the node indices in GraphView::edge_pair = words per node in the first record array
+// of the register-resident kernel: C for C <= 2 (all copies of a node in one record), 1 for
+// C >= 3 (first copies only; the other copies are kept in a second array).
 int moc_node_stride(int C);
 
-// LDS bytes one workgroup of the evaluation kernel needs for a graph of n nodes, m edges, C copies.
-int moc_eval_lds_bytes(int n, int m, int C);
+// LDS bytes one workgroup of the evaluation kernel needs for a graph of n nodes, m edges, C copies
+// when max_lds bytes are available (optional buffers shrink to fit).
+int moc_eval_lds_bytes(int n, int m, int C, int max_lds);
 
 int moc_set_hip_error(hipError_t e);  // records e, returns MOC_EHIP
 
