@@ -19,6 +19,9 @@ INPUTS_LIB = os.path.join(PKG, "inputs", "libmoc_inputs_hip.so")
 
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+               # a one-lane atomic is to stay one instruction whose result is waited for where it
+               # is used: the evaluator draws its next candidate index that way, far ahead
+               "-mllvm", "-amdgpu-atomic-optimizer-strategy=None",
                "-Wall", "-Wno-unused-result"]
 
 

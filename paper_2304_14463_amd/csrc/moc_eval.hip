@@ -31,15 +31,19 @@
 // accesses and nothing is read twice.
 // All arithmetic is integer: results do not depend on the order in which
 // lanes or workgroups run.
+#include <type_traits>
+
 #include "moc_internal.h"
 
 namespace {
 
-constexpr int kRedStride = 8;      // ints per wave in the cross-wave exchange area
+constexpr int kRedStride = 8;      // ints per wave in the cross-wave exchange area (4 in use)
+constexpr int kRedPass = 4;        // word of that area through which thread 0 passes a value to all
 constexpr int kMaxIters = 6;       // nodes per lane the register-resident kernel is built for
 constexpr int kEdgesPerNode = 3;   // edges per lane = kEdgesPerNode * nodes per lane
 constexpr int kChunk = 32;         // delta positions per chunk ...
 constexpr int kChunkStride = 36;   // ... stored 36 words apart: 16 lanes x 16 bytes hit 64 distinct banks
+constexpr int64_t kMaxLaunch = (int64_t)1 << 31;   // candidates per launch
 constexpr int kQueueCap = 192;     // C >= 3: edges a wave sets aside before it has to work them off
 
 // ------------------------------------------------------------------ LDS layouts
@@ -173,11 +177,14 @@ __device__ __forceinline__ int count_distinct_starts(const Lds& L, const LdsLayo
 // Cross-wave combine.  Every wave leaves its partial results in LDS; after the
 // barrier the lanes of wave 0 pick up one wave each and reduce in registers.
 // WAVE_TOTALS: viol and nlive are already sums over the wave (counted with ballots).
+// `pass` (thread 0's value) travels through the same barrier: every thread gets it back in
+// `passed`.  The kernel hands the workgroup's next candidate index around this way.
 template <int NT, bool WAVE_TOTALS = false>
 __device__ __forceinline__ void finish(const Lds& L, const GraphView& g, int tid, int lane, int wave, int S, int P,
                                        int viol, int nlive, int distinct, int dur, moc_result* __restrict__ out,
-                                       int64_t b) {
+                                       int64_t b, uint32_t pass = 0, uint32_t* passed = nullptr) {
   constexpr int NW = NT / kWave;
+  if (passed && tid == 0) L.red[kRedPass] = (int32_t)pass;
   if constexpr (!WAVE_TOTALS) {
     viol = wave_sum(viol);
     nlive = wave_sum(nlive);
@@ -190,6 +197,7 @@ __device__ __forceinline__ void finish(const Lds& L, const GraphView& g, int tid
       r[0] = S; r[1] = P; r[2] = viol + nlive - distinct; r[3] = dur;
     }
     __syncthreads();
+    if (passed) *passed = (uint32_t)L.red[kRedPass];
     if (wave != 0) return;
     const bool has = lane < NW;
     const int32_t* r = L.red + (has ? lane : 0) * kRedStride;
@@ -206,6 +214,7 @@ __device__ __forceinline__ void finish(const Lds& L, const GraphView& g, int tid
   } else {
     viol += nlive - distinct;   // Eq. (6): live copies minus distinct start positions
     __syncthreads();
+    if (passed) *passed = (uint32_t)L.red[kRedPass];
   }
   if (tid == 0) {
     moc_result res;
@@ -221,8 +230,12 @@ __device__ __forceinline__ void finish(const Lds& L, const GraphView& g, int tid
 template <int CT>
 struct NodeIn {
   int s[CT], e[CT];
-  uint32_t a;   // CT flag bytes, byte i = a of copy i (bytes above CT are not used); for CT == 3 they
-                // start at byte (off - min(off, a_last)), see load_node
+  // CT flag bytes, byte i = a of copy i (bytes above CT are not used); for CT == 3 they start at
+  // byte (off - min(off, a_last)), see load_node.  For CT <= 2 a 16-bit value that is never
+  // widened: it goes into the byte compares as it is, so that no conversion instruction sits
+  // between the load and its first use (the compiler places such a conversion, and with it
+  // the wait for the load, at the end of the iteration that issued the load).
+  typename std::conditional<CT <= 2, uint16_t, uint32_t>::type a;
 };
 
 struct __attribute__((packed, aligned(4))) Int3 { int x, y, z; };
@@ -242,7 +255,7 @@ __device__ __forceinline__ void load_node(const int32_t* __restrict__ s_row, con
                                           NodeIn<CT>& r) {
   const uint32_t boff = off * 4u;   // T <= 19455: no overflow
   if constexpr (CT == 1) {
-    r.s[0] = load_at<int>(s_row, boff); r.e[0] = load_at<int>(e_row, boff); r.a = load_at<uint8_t>(a_row, off);
+    r.s[0] = load_at<int>(s_row, boff); r.e[0] = load_at<int>(e_row, boff); r.a = load_at<uint8_t>(a_row, off);   // widened to 16 bits by the load itself
   } else if constexpr (CT == 2) {
     const int2 sv = load_at<int2>(s_row, boff);
     const int2 ev = load_at<int2>(e_row, boff);
@@ -328,12 +341,21 @@ MOC_MASK_CMP(u_le, "v_cmp_le_u32_e64 %0, %1, %2", "v")
 MOC_MASK_CMP(i_gt, "v_cmp_gt_i32_e64 %0, %1, %2", "v")
 // b the same in every lane (a scalar register)
 MOC_MASK_CMP(u_lt_k, "v_cmp_lt_u32_e64 %0, %1, %2", "s")
-MOC_MASK_CMP(byte0_ne_k, "v_cmp_ne_u32_sdwa %0, %1, %2 src0_sel:BYTE_0 src1_sel:DWORD", "s")
-MOC_MASK_CMP(byte1_ne_k, "v_cmp_ne_u32_sdwa %0, %1, %2 src0_sel:BYTE_1 src1_sel:DWORD", "s")
-MOC_MASK_CMP(byte2_ne_k, "v_cmp_ne_u32_sdwa %0, %1, %2 src0_sel:BYTE_2 src1_sel:DWORD", "s")
-MOC_MASK_CMP(byte3_ne_k, "v_cmp_ne_u32_sdwa %0, %1, %2 src0_sel:BYTE_3 src1_sel:DWORD", "s")
 #undef MOC_MASK_CMP
-__device__ __forceinline__ lanemask byte_ne_k(uint32_t a, int i, uint32_t b) {
+#define MOC_BYTE_CMP(name, sel)                                                                   \
+  template <typename F>                                                                           \
+  __device__ __forceinline__ lanemask name(F a, uint32_t b) {                                     \
+    lanemask m;                                                                                   \
+    asm("v_cmp_ne_u32_sdwa %0, %1, %2 src0_sel:" sel " src1_sel:DWORD" : "=s"(m) : "v"(a), "s"(b)); \
+    return m;                                                                                     \
+  }
+MOC_BYTE_CMP(byte0_ne_k, "BYTE_0")
+MOC_BYTE_CMP(byte1_ne_k, "BYTE_1")
+MOC_BYTE_CMP(byte2_ne_k, "BYTE_2")
+MOC_BYTE_CMP(byte3_ne_k, "BYTE_3")
+#undef MOC_BYTE_CMP
+template <typename F>
+__device__ __forceinline__ lanemask byte_ne_k(F a, int i, uint32_t b) {
   return i == 0 ? byte0_ne_k(a, b) : i == 1 ? byte1_ne_k(a, b) : i == 2 ? byte2_ne_k(a, b) : byte3_ne_k(a, b);
 }
 // per lane: m ? yes : no
@@ -471,7 +493,8 @@ template <int NT, int CT, int ITERS>
 __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, const int32_t* __restrict__ starts,
                                                         const int32_t* __restrict__ ends,
                                                         const uint8_t* __restrict__ active,
-                                                        moc_result* __restrict__ out, LdsLayout lay) {
+                                                        moc_result* __restrict__ out, LdsLayout lay,
+                                                        uint32_t* __restrict__ ticket, int groups) {
   constexpr int EPT = kEdgesPerNode * ITERS;
   constexpr bool kSplit = CT >= 3;          // first copies and other copies in separate arrays
   constexpr int NS = kSplit ? 1 : CT;       // words per node in the first array
@@ -483,6 +506,10 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
   const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);   // the same in every lane: say so
   const int T = g.T, n = g.n;
   const int64_t total = B * (int64_t)T;
+  const uint32_t group = groups ? blockIdx.x % (uint32_t)groups : 0u;
+  uint32_t* const counter = ticket + (size_t)group * kTicketStride;
+  uint32_t first_draw = 0;   // thread 0: the first two candidates of this workgroup, asked for before anything else
+  if (tid == 0 && groups != 0) first_draw = atomicAdd(counter, 2u);
   uint32_t* const queue = L.queue + wave * lay.qcap;   // kSplit: this wave's edges set aside
   const uint32_t dummy_pair = (uint32_t)(n * NS) | (uint32_t)(n * NS) << 16;   // the dummy node is never live
 
@@ -527,31 +554,55 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
     atomicSub(&L.delta[delta_at(e + 1)], size);
     atomicOr(&L.occ[s >> 5], 1u << (s & 31));
   };
+  request_size_dur();
+  // Candidates are handed out dynamically, so that compute units that hold fewer or faster
+  // workgroups take more of the batch, and a workgroup that starts late finds nothing left
+  // and goes.  They are dealt into `groups` interleaved sequences, group r = {r + groups * t};
+  // a workgroup belongs to group blockIdx.x % groups and draws t from the group's counter
+  // (many counters: one would be drawn from faster than a single address serves).  It starts
+  // with two draws; then the draw for the candidate after next is made at the top of an
+  // iteration and collected at its end: its latency never shows, and the next candidate is
+  // known early enough to prefetch it.  A workgroup thus holds two candidates beyond the one
+  // it works on, which is too many when the batch has only a few per workgroup: then
+  // (groups == 0) the split is fixed, workgroup w takes w, w + grid, ...  32 bits are enough
+  // for t: the host launches at most 2^31 candidates at a time.
+  const auto dealt = [&](uint32_t t) {
+    return groups ? (int64_t)group + (int64_t)groups * t : (int64_t)blockIdx.x + (int64_t)gridDim.x * t;
+  };
+  if (groups == 0) {
 #pragma unroll
-  for (int it = 0; it < ITERS; ++it) request(it, (int64_t)blockIdx.x * T);   // grid <= B
+    for (int it = 0; it < ITERS; ++it) request(it, (int64_t)blockIdx.x * T);   // the grid is not larger than the batch
+  }
+  if (tid == 0) L.red[kRedPass] = (int32_t)first_draw;
   __syncthreads();
+  uint32_t next = (uint32_t)__builtin_amdgcn_readfirstlane(L.red[kRedPass]);
+  int64_t b = dealt(next);
+  ++next;
+  if (groups != 0 && b < B) {
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) request(it, b * T);
+  }
+  uint32_t drawn = 0;   // thread 0
 
-  for (int64_t b = blockIdx.x; b < B; b += gridDim.x) {
+  while (b < B) {
     int viol = 0, nlive = 0;   // per wave (the same in every lane, counted on lane masks)
     int dur = 0;               // per lane
+    if (tid == 0) drawn = groups ? atomicAdd(counter, 1u) : next + 1;
     // The workgroup's next candidate; the last one re-reads itself so that the loads below
     // need no condition.  Slot `it` is requested as soon as phase 1 has consumed the
     // registers of slot `it` (the first kEarly slots) or between the steps of phase 2 (the
     // rest): HBM streams through both phases and no wave queues all its loads at once.
-    const int64_t next_row = (b + gridDim.x < B ? b + gridDim.x : b) * T;
+    const int64_t b_next = dealt(next);
+    const int64_t next_row = (b_next < B ? b_next : b) * T;
 
     // ---------------- phase 1: per node, copies in registers
-    request_size_dur();
 #pragma unroll
     for (int it = 0; it < ITERS; ++it) {
       int v = it * NT + tid;
       asm volatile("" : "+v"(v));               // as for the edges: keep derived addresses out of registers
-      // m_v, w_v of this slot have arrived on every path from here on (its loads were issued
-      // before anything that is still in flight)
-      asm volatile("" ::"v"(sd[it].x), "v"(sd[it].y));
       if (it * NT + wave * kWave < n) {   // else: whole wave past the last node
         const NodeIn<CT>& r = in[it];
-        uint32_t flags = r.a;
+        auto flags = r.a;
         if constexpr (CT == 3) {
           const uint32_t off = (uint32_t)v * CT, a_last = flags_last(b * T);
           flags >>= 8 * (off - (off < a_last ? off : a_last));
@@ -681,7 +732,19 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
       }
     }
     if constexpr (kSplit) drain_queue<CT>(viol, L, queue, queued, lane, dummy_pair);
-    finish<NT, true>(L, g, tid, lane, wave, S, P, viol, nlive, distinct, dur, out, b);
+    uint32_t after_next;
+    finish<NT, true>(L, g, tid, lane, wave, S, P, viol, nlive, distinct, dur, out, b, drawn, &after_next);
+    b = b_next;
+    next = (uint32_t)__builtin_amdgcn_readfirstlane(after_next);
+  }
+  // The last workgroup to leave puts the counters back to zero for the next launch.  No fence
+  // is needed: a workgroup has received the results of all its draws before it signs off, and
+  // all accesses to the counters are atomic operations, which meet in one place.
+  if (tid == 0 && groups != 0) {
+    uint32_t* const left = ticket + (size_t)groups * kTicketStride;
+    if (atomicAdd(left, 1u) == gridDim.x - 1) {
+      for (int r = 0; r <= groups; ++r) atomicExch(&ticket[(size_t)r * kTicketStride], 0u);
+    }
   }
 }
 
@@ -691,7 +754,8 @@ __global__ __launch_bounds__(NT) void eval_batch_general_kernel(GraphView g, int
                                                                 const int32_t* __restrict__ starts,
                                                                 const int32_t* __restrict__ ends,
                                                                 const uint8_t* __restrict__ active,
-                                                                moc_result* __restrict__ out, LdsLayout lay) {
+                                                                moc_result* __restrict__ out, LdsLayout lay,
+                                                                uint32_t* __restrict__ /*ticket*/, int /*groups*/) {
   extern __shared__ uint32_t lds_raw[];
   const Lds L = carve(lds_raw, lay);
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
@@ -781,7 +845,13 @@ int launch_kernel(K kern, int nt, const moc_graph* g, const LdsLayout& lay, int6
   if (per_cu < 1) per_cu = 1;
   const int64_t resident = (int64_t)per_cu * g->num_cu;
   const unsigned grid = (unsigned)(B < resident ? B : resident);
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(nt), lay.bytes, stream, g->view, B, starts, ends, active, out, lay);
+  // One set of counters per launch in flight (see moc_graph::tickets); about 16 workgroups share a
+  // counter.  A batch of fewer than 8 candidates per workgroup is split statically (groups = 0).
+  uint32_t* ticket = g->tickets + (size_t)(g->launch_seq.fetch_add(1u) % kTicketSlots) * kTicketSlotWords;
+  int groups = grid / 16 < 1 ? 1 : grid / 16 > kTicketGroups ? kTicketGroups : (int)(grid / 16);
+  if (B < (int64_t)8 * grid) groups = 0;
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(nt), lay.bytes, stream, g->view, B, starts, ends, active, out, lay,
+                     ticket, groups);
   MOC_HIP(hipGetLastError());
   return MOC_OK;
 }
@@ -865,11 +935,23 @@ extern "C" int moc_eval_batch(const moc_graph* g, int64_t B, const int32_t* star
   if (C == 2) aligned = (se & 7) == 0 && ((uintptr_t)active & 1) == 0;
   if (C == 4) aligned = (se & 15) == 0 && ((uintptr_t)active & 3) == 0;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  switch (block_threads(n, g->view.m)) {
-    case 64: return launch_nt<64>(g, B, starts, ends, active, out, st, aligned);
-    case 128: return launch_nt<128>(g, B, starts, ends, active, out, st, aligned);
-    case 256: return launch_nt<256>(g, B, starts, ends, active, out, st, aligned);
-    case 512: return launch_nt<512>(g, B, starts, ends, active, out, st, aligned);
-    default: return launch_nt<1024>(g, B, starts, ends, active, out, st, aligned);
+  const int nt = block_threads(n, g->view.m);
+  // The kernels count candidates handed out in 32 bits: longer batches go in several launches.
+  const int64_t T = g->view.T;
+  for (int64_t at = 0; at < B; at += kMaxLaunch) {
+    const int64_t count = B - at < kMaxLaunch ? B - at : kMaxLaunch;
+    const int32_t* s = starts + at * T;
+    const int32_t* e = ends + at * T;
+    const uint8_t* a = active + at * T;
+    int rc;
+    switch (nt) {
+      case 64: rc = launch_nt<64>(g, count, s, e, a, out + at, st, aligned); break;
+      case 128: rc = launch_nt<128>(g, count, s, e, a, out + at, st, aligned); break;
+      case 256: rc = launch_nt<256>(g, count, s, e, a, out + at, st, aligned); break;
+      case 512: rc = launch_nt<512>(g, count, s, e, a, out + at, st, aligned); break;
+      default: rc = launch_nt<1024>(g, count, s, e, a, out + at, st, aligned); break;
+    }
+    if (rc != MOC_OK) return rc;
   }
+  return MOC_OK;
 }

@@ -82,8 +82,7 @@ int moc_graph_upload(int32_t n, const int32_t* in_ptr, const int32_t* in_idx, co
     }
     std::vector<int32_t> in_ptr_v(in_ptr, in_ptr + n + 1), in_idx_v(in_idx, in_idx + m);
 
-    moc_graph* g = new moc_graph();
-    std::memset(g, 0, sizeof(*g));
+    moc_graph* g = new moc_graph();   // all members zero
     int rc = MOC_OK;
     hipError_t e = hipGetDevice(&g->device);
     hipDeviceProp_t prop;
@@ -110,6 +109,12 @@ int moc_graph_upload(int32_t n, const int32_t* in_ptr, const int32_t* in_idx, co
     if (rc == MOC_OK) rc = upload(g, in_idx_v, &w.in_idx);
     if (rc == MOC_OK) rc = upload(g, out_ptr, &w.out_ptr);
     if (rc == MOC_OK) rc = upload(g, out_idx, &w.out_idx);
+    if (rc == MOC_OK) {
+      const std::vector<uint32_t> zeros((size_t)kTicketSlots * kTicketSlotWords, 0u);
+      const uint32_t* dev = nullptr;
+      rc = upload(g, zeros, &dev);
+      g->tickets = const_cast<uint32_t*>(dev);
+    }
     if (rc != MOC_OK) {
       for (int i = 0; i < g->n_allocs; ++i) (void)hipFree(g->allocs[i]);
       delete g;

@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "moccasin.h"
 
 // A copy that is not live is staged as s = 0xFFFF, e = 0: no position x
@@ -31,9 +33,21 @@ struct moc_graph {
   int max_lds;       // bytes of LDS one workgroup may use
   int has_self_loop; // an edge (v,v) exists: the neighbourhood kernel does not take such graphs
   GraphView view;    // device pointers
-  void* allocs[8];   // device allocations backing `view`
+  void* allocs[8];   // device allocations backing `view`, and `tickets`
   int n_allocs;
+  // Work counters of the evaluation kernel: kTicketSlots sets of kTicketGroups + 1 counters,
+  // each counter on a 64-byte line of its own, all zero between launches (a launch leaves its
+  // set at zero when it ends).  Launches take the sets in turn, so that launches running at
+  // the same time on different streams do not share one unless more than kTicketSlots are
+  // in flight.
+  uint32_t* tickets;
+  mutable std::atomic<uint32_t> launch_seq;
 };
+
+constexpr int kTicketSlots = 16;
+constexpr int kTicketGroups = 64;  // counters a launch draws candidates from (+1: workgroups that have left)
+constexpr int kTicketStride = 16;  // words from one counter to the next
+constexpr int kTicketSlotWords = (kTicketGroups + 1) * kTicketStride;
 
 // Unit of the node indices in GraphView::edge_pair = words per node in the first record array
 // of the register-resident kernel: C for C <= 2 (all copies of a node in one record), 1 for

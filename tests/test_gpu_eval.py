@@ -153,6 +153,40 @@ def test_eval_ragged_shapes_random_candidates(moc, n, C):
     gh.free()
 
 
+
+@pytest.mark.parametrize("n,C,B", [(96, 3, 40000), (200, 2, 50000), (96, 3, 3000)])
+def test_eval_many_launches_one_graph(moc, n, C, B):
+    """Launches share the graph's work counters, which every launch must leave at zero: 40
+    launches of the same batch in a row, alternating between two streams, all return the bytes
+    of the first, which match the oracle.  The long batches are handed out dynamically, the
+    short one is split statically."""
+    import torch
+    import oracle
+    from paper_2304_14463_amd.inputs import graph_from_edges
+    rng = np.random.default_rng(n * 7 + C)
+    edges = sorted({(int(u), v) for v in range(1, n) for u in rng.integers(0, v, size=3)})
+    g = graph_from_edges(n, edges, rng.integers(1, 100, n), rng.integers(1, 9, n))
+    T = n * C
+    s, e, a = random_candidates(rng, B, n, C, T, wild=False)
+    a.reshape(B, n, C)[:, :, 0] = 1
+    a.reshape(B, n, C)[:, :, 1:] *= (rng.random((B, n, C - 1)) < 0.1)
+    gh = moc.moc_graph_upload(n, g.in_ptr, g.in_idx, g.size, g.dur, int(g.size.sum()) // 3, C)
+    ds, de, da = to_dev(s, e, a)
+    first = moc.results_to_numpy(moc.moc_eval_batch(gh, ds, de, da))
+    assert_results_equal(first, oracle_eval_parallel(g, int(g.size.sum()) // 3, C, s, e, a), f"n={n} C={C}")
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for st in streams:
+        st.wait_stream(torch.cuda.current_stream())
+    outs = []
+    for i in range(40):
+        with torch.cuda.stream(streams[i % 2]):
+            outs.append(moc.moc_eval_batch(gh, ds, de, da, stream=streams[i % 2]))
+    torch.cuda.synchronize()
+    for i, out in enumerate(outs):
+        assert moc.results_to_numpy(out).tobytes() == first.tobytes(), f"launch {i} differs"
+    gh.free()
+
+
 def test_eval_empty_batch_and_single_candidate(moc, workloads):
     import torch
     w = workloads(0)
