@@ -44,7 +44,7 @@ constexpr int kEdgesPerNode = 3;   // edges per lane = kEdgesPerNode * nodes per
 constexpr int kChunk = 32;         // delta positions per chunk ...
 constexpr int kChunkStride = 36;   // ... stored 36 words apart: 16 lanes x 16 bytes hit 64 distinct banks
 constexpr int64_t kMaxLaunch = (int64_t)1 << 31;   // candidates per launch
-constexpr int kQueueCap = 192;     // C >= 3: edges a wave sets aside before it has to work them off
+constexpr int kQueueCap = 320;     // C >= 3: edges a wave sets aside before it has to work them off
 
 // ------------------------------------------------------------------ LDS layouts
 // Word offsets of the arrays inside the dynamic LDS segment, and their sizes in words.
@@ -84,7 +84,7 @@ LdsLayout fast_layout(int n, int C, int nt, int max_lds) {
   l.queue_off = l.red_off + nw * kRedStride;
   l.qcap = C >= 3 ? kQueueCap : 0;
   l.bytes = 4 * (l.queue_off + nw * l.qcap);
-  while (l.bytes > max_lds && l.qcap > kWave) {
+  while (l.bytes > max_lds && l.qcap > kEdgesPerNode * kWave) {   // a slice of edges must fit
     l.qcap -= kWave;
     l.bytes = 4 * (l.queue_off + nw * l.qcap);
   }
@@ -230,12 +230,13 @@ __device__ __forceinline__ void finish(const Lds& L, const GraphView& g, int tid
 template <int CT>
 struct NodeIn {
   int s[CT], e[CT];
-  // CT flag bytes, byte i = a of copy i (bytes above CT are not used); for CT == 3 they start at
-  // byte (off - min(off, a_last)), see load_node.  For CT <= 2 a 16-bit value that is never
-  // widened: it goes into the byte compares as it is, so that no conversion instruction sits
-  // between the load and its first use (the compiler places such a conversion, and with it
-  // the wait for the load, at the end of the iteration that issued the load).
-  typename std::conditional<CT <= 2, uint16_t, uint32_t>::type a;
+  // The flag bytes, byte i = a of copy i.  C <= 2: one 16-bit value; C = 3: a 16-bit value and
+  // the third byte in a2; C = 4: one 32-bit value.  The 16-bit values are never widened: they
+  // go into the byte compares as they are, so that no conversion instruction sits between
+  // the load and its first use (the compiler places such a conversion, and with it the wait
+  // for the load, at the end of the iteration that issued the load).
+  typename std::conditional<CT <= 3, uint16_t, uint32_t>::type a;
+  uint16_t a2;
 };
 
 struct __attribute__((packed, aligned(4))) Int3 { int x, y, z; };
@@ -243,7 +244,7 @@ struct __attribute__((packed, aligned(4))) Int3 { int x, y, z; };
 // Loads the C copies of one node.  s_row/e_row/a_row point at the candidate's row (uniform
 // over the workgroup, so they live in scalar registers) and `off` = v*C is the lane's
 // element offset, turned into 32-bit byte offsets so that the loads take the scalar base +
-// 32-bit lane offset form; `a_last` = largest byte offset at which 4 flag bytes can be read.
+// 32-bit lane offset form.
 template <typename V>
 __device__ __forceinline__ V load_at(const void* base, uint32_t byte_off) {
   return *reinterpret_cast<const V*>(static_cast<const char*>(base) + byte_off);
@@ -251,8 +252,7 @@ __device__ __forceinline__ V load_at(const void* base, uint32_t byte_off) {
 
 template <int CT>
 __device__ __forceinline__ void load_node(const int32_t* __restrict__ s_row, const int32_t* __restrict__ e_row,
-                                          const uint8_t* __restrict__ a_row, uint32_t off, uint32_t a_last,
-                                          NodeIn<CT>& r) {
+                                          const uint8_t* __restrict__ a_row, uint32_t off, NodeIn<CT>& r) {
   const uint32_t boff = off * 4u;   // T <= 19455: no overflow
   if constexpr (CT == 1) {
     r.s[0] = load_at<int>(s_row, boff); r.e[0] = load_at<int>(e_row, boff); r.a = load_at<uint8_t>(a_row, off);   // widened to 16 bits by the load itself
@@ -265,13 +265,8 @@ __device__ __forceinline__ void load_node(const int32_t* __restrict__ s_row, con
     const Int3 sv = load_at<Int3>(s_row, boff);
     const Int3 ev = load_at<Int3>(e_row, boff);
     r.s[0] = sv.x; r.s[1] = sv.y; r.s[2] = sv.z; r.e[0] = ev.x; r.e[1] = ev.y; r.e[2] = ev.z;
-    // one (unaligned) 4-byte read covers the 3 flags; the last node of the batch reads
-    // the 4 bytes that end with the array and the consumer shifts by 8 * (off - at):
-    // nothing here may wait for the load
-    const uint32_t at = off < a_last ? off : a_last;
-    uint32_t w;
-    __builtin_memcpy(&w, a_row + at, 4);
-    r.a = w;
+    r.a = load_at<uint16_t>(a_row, off);            // flags of copies 0 and 1 (any alignment)
+    r.a2 = load_at<uint8_t>(a_row, off + 2);        // flag of copy 2, widened to 16 bits by the load itself
   } else {
     const int4 sv = load_at<int4>(s_row, boff);
     const int4 ev = load_at<int4>(e_row, boff);
@@ -317,11 +312,11 @@ struct Record {
   uint32_t w[CT];
 };
 
-// position t of the delta array -> word index (chunks of 32 words, 36 apart).  The index is
-// made opaque so that it is formed in two instructions and scaled by the addressing one.
+// position t of the delta array -> word index t + 4 * (t / 32) (chunks of 32 words, 36 apart),
+// in the two instructions it takes
 __device__ __forceinline__ int delta_at(int t) {
-  int idx = (int)((uint32_t)t + (((uint32_t)t >> 5) << 2));
-  asm("" : "+v"(idx));
+  int idx;
+  asm("v_lshrrev_b32 %0, 5, %1\n\tv_lshl_add_u32 %0, %0, 2, %1" : "=&v"(idx) : "v"(t));
   return idx;
 }
 
@@ -420,12 +415,10 @@ __device__ __forceinline__ void count_live_uncovered(int& viol, const Record<CT>
 #undef MOC_COVER_LAST
 #undef MOC_COVER_REGS
 
-// Eq. (5), C <= 2, for one edge held in a register as pair = u*C | v*C << 16 (word indices of
-// the two records): every live copy of the consumer v against the copies of the provider u.
-// Adds the violated instances over the whole wave to viol (wave-uniform).
+// C <= 2: the records of the two nodes of an edge held in a register as pair = u*C | v*C << 16
+// (word indices of the records)
 template <int CT>
-__device__ __forceinline__ void check_edge(int& viol, uint32_t pair) {
-  Record<CT> pv, pu;
+__device__ __forceinline__ void fetch_edge(uint32_t pair, Record<CT>& pv, Record<CT>& pu) {
   if constexpr (CT == 1) {
     pv.w[0] = lds_read(addr_hi16(pair));
     pu.w[0] = lds_read(addr_lo16(pair));
@@ -433,8 +426,6 @@ __device__ __forceinline__ void check_edge(int& viol, uint32_t pair) {
     const uint2 rv = lds_read2(addr_hi16(pair)), ru = lds_read2(addr_lo16(pair));
     pv.w[0] = rv.x; pv.w[1] = rv.y; pu.w[0] = ru.x; pu.w[1] = ru.y;
   }
-#pragma unroll
-  for (int i = 0; i < CT; ++i) count_live_uncovered<CT>(viol, pu, pv.w[i]);
 }
 
 // Eq. (5), C >= 3, first pass over an edge pair = u | v << 16: only the first copies of the
@@ -505,7 +496,6 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
   const int tid = threadIdx.x, lane = tid & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);   // the same in every lane: say so
   const int T = g.T, n = g.n;
-  const int64_t total = B * (int64_t)T;
   const uint32_t group = groups ? blockIdx.x % (uint32_t)groups : 0u;
   uint32_t* const counter = ticket + (size_t)group * kTicketStride;
   uint32_t first_draw = 0;   // thread 0: the first two candidates of this workgroup, asked for before anything else
@@ -536,16 +526,12 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
       sd[it] = load_at<int2>(g.size_dur, (uint32_t)v * 8u);
     }
   };
-  auto flags_last = [&](int64_t row) {         // largest byte offset in the row at which 4 flag bytes exist
-    const int64_t left = total - row - 4;      // >= 0: the kernel is not used for T < 4
-    return left < 0x7FFFFFFF ? (uint32_t)left : 0x7FFFFFFFu;
-  };
   // Loads of node slot `it` of the candidate at `row`.  Issued unconditionally (lanes past the
   // last node re-read it) so that the count of loads in flight is the same on every path.
   auto request = [&](int it, int64_t row) {
     int v = min(it * NT + tid, n - 1);
     asm volatile("" : "+v"(v));                // keep the per-slot offsets out of registers
-    load_node<CT>(starts + row, ends + row, active + row, (uint32_t)v * CT, flags_last(row), in[it]);
+    load_node<CT>(starts + row, ends + row, active + row, (uint32_t)v * CT, in[it]);
   };
   // Eq. (4), (6): one live copy [s, e] of a node of size m_v into the delta array (+m_v at s,
   // -m_v after e) and the bitmap of start positions
@@ -585,7 +571,7 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
   uint32_t drawn = 0;   // thread 0
 
   while (b < B) {
-    int viol = 0, nlive = 0;   // per wave (the same in every lane, counted on lane masks)
+    int viol = 0;              // per wave (the same in every lane, counted on lane masks)
     int dur = 0;               // per lane
     if (tid == 0) drawn = groups ? atomicAdd(counter, 1u) : next + 1;
     // The workgroup's next candidate; the last one re-reads itself so that the loads below
@@ -602,22 +588,20 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
       asm volatile("" : "+v"(v));               // as for the edges: keep derived addresses out of registers
       if (it * NT + wave * kWave < n) {   // else: whole wave past the last node
         const NodeIn<CT>& r = in[it];
-        auto flags = r.a;
-        if constexpr (CT == 3) {
-          const uint32_t off = (uint32_t)v * CT, a_last = flags_last(b * T);
-          flags >>= 8 * (off - (off < a_last ? off : a_last));
-        }
         // Eq. (2), (7), (8), (3) on lane masks; Eq. (1) per lane
         const lanemask isn = u_lt_k((uint32_t)v, (uint32_t)n);
         lanemask act[CT], live[CT];
         Record<CT> rec;
 #pragma unroll
         for (int i = 0; i < CT; ++i) {
-          act[i] = byte_ne_k(flags, i, 0u) & isn;
+          if constexpr (CT == 3) act[i] = (i < 2 ? byte_ne_k(r.a, i, 0u) : byte_ne_k(r.a2, 0, 0u)) & isn;
+          else act[i] = byte_ne_k(r.a, i, 0u) & isn;
           const lanemask well = u_le((uint32_t)r.s[i], (uint32_t)r.e[i]) & u_lt_k((uint32_t)r.e[i], (uint32_t)T);
           live[i] = act[i] & well;
-          viol += count(act[i] & ~well);
-          nlive += count(live[i]);
+          // an active copy is either ill-formed, one violation of Eq. (2)/(8), or live, one
+          // more start for Eq. (6) (the distinct start positions are taken off at the end):
+          // both end up in the same sum
+          viol += count(act[i]);
           dur += (int)pick(act[i], (uint32_t)sd[it].y);
           rec.w[i] = pick(live[i], (uint32_t)r.s[i] | ((uint32_t)r.e[i] << 16), MOC_DEAD);
         }
@@ -713,27 +697,39 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
       __builtin_amdgcn_sched_barrier(0);
       if (it > 0 && kEarly + it < ITERS) request(kEarly + it, next_row);
       __builtin_amdgcn_sched_barrier(0);
+      // the records of the slice's edges are asked for together and looked at afterwards: one
+      // LDS latency per slice, not one per edge
+      if constexpr (!kSplit) {
+        Record<CT> pv[kEdgesPerNode], pu[kEdgesPerNode];
 #pragma unroll
-      for (int j = it * kEdgesPerNode; j < (it + 1) * kEdgesPerNode; ++j) {
-        if constexpr (!kSplit) {
-          check_edge<CT>(viol, edge[j]);
-        } else {
-          if (queued > lay.qcap - kWave) {   // the next 64 might not fit: work the queue off first
-            drain_queue<CT>(viol, L, queue, queued, lane, dummy_pair);
-            queued = 0;
-          }
-          const uint32_t pv = lds_read(addr_hi16(edge[j])), pu = lds_read(addr_lo16(edge[j]));
-          const lanemask more = check_first_copies(viol, pu, pv);
-          if (more != 0) {
-            if (lanes(more)) queue[rank_in(more, (uint32_t)queued)] = edge[j];
-            queued += count(more);
-          }
+        for (int j = 0; j < kEdgesPerNode; ++j) fetch_edge<CT>(edge[it * kEdgesPerNode + j], pv[j], pu[j]);
+#pragma unroll
+        for (int j = 0; j < kEdgesPerNode; ++j) {
+#pragma unroll
+          for (int i = 0; i < CT; ++i) count_live_uncovered<CT>(viol, pu[j], pv[j].w[i]);
+        }
+      } else {
+        if (queued > lay.qcap - kEdgesPerNode * kWave) {   // the slice might not fit: work the queue off first
+          drain_queue<CT>(viol, L, queue, queued, lane, dummy_pair);
+          queued = 0;
+        }
+        uint32_t pv[kEdgesPerNode], pu[kEdgesPerNode];
+#pragma unroll
+        for (int j = 0; j < kEdgesPerNode; ++j) {
+          pv[j] = lds_read(addr_hi16(edge[it * kEdgesPerNode + j]));
+          pu[j] = lds_read(addr_lo16(edge[it * kEdgesPerNode + j]));
+        }
+#pragma unroll
+        for (int j = 0; j < kEdgesPerNode; ++j) {
+          const lanemask more = check_first_copies(viol, pu[j], pv[j]);
+          if (lanes(more)) queue[rank_in(more, (uint32_t)queued)] = edge[it * kEdgesPerNode + j];
+          queued += count(more);
         }
       }
     }
     if constexpr (kSplit) drain_queue<CT>(viol, L, queue, queued, lane, dummy_pair);
     uint32_t after_next;
-    finish<NT, true>(L, g, tid, lane, wave, S, P, viol, nlive, distinct, dur, out, b, drawn, &after_next);
+    finish<NT, true>(L, g, tid, lane, wave, S, P, viol, 0, distinct, dur, out, b, drawn, &after_next);
     b = b_next;
     next = (uint32_t)__builtin_amdgcn_readfirstlane(after_next);
   }
