@@ -512,7 +512,7 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
 #pragma unroll
   for (int j = 0; j < EPT; ++j) {
     const int e = j * NT + tid;
-    edge[j] = e < g.m ? g.edge_pair[e] : dummy_pair;
+    edge[j] = g.edge_pair[e];   // the list is padded with dummy edges to EPT * NT entries
   }
   NodeIn<CT> in[ITERS];
   // m_v, w_v of the lane's nodes: re-read (from L2) at the start of each phase 1, behind the
@@ -905,6 +905,12 @@ int launch_nt(const moc_graph* g, int64_t B, const int32_t* s, const int32_t* e,
 }  // namespace
 
 int moc_node_stride(int C) { return C == 2 ? 2 : 1; }
+
+bool moc_eval_shape(int n, int m, int C, int* nt, int* edges_per_lane) {
+  *nt = block_threads(n, m);
+  *edges_per_lane = kEdgesPerNode * slots_per_lane(n, m, *nt);
+  return fast_shape(n, m, C, *nt);
+}
 
 int moc_eval_lds_bytes(int n, int m, int C, int max_lds) {
   const int nt = block_threads(n, m);

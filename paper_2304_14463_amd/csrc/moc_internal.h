@@ -17,8 +17,9 @@ constexpr int kWave = 64;  // CDNA wavefront
 // Device-side view of an uploaded graph, passed to kernels by value.
 struct GraphView {
   const int2* size_dur;        // [n] {m_v, w_v}
-  const uint32_t* edge_pair;   // [m] edge (u,v) as u*NS | v*NS << 16, ordered by v; NS = moc_node_stride(C)
-  const uint32_t* edge_pair_c; // [m] the same with stride C (kernel for any C)
+  const uint32_t* edge_pair;   // edges (u,v) as u*NS | v*NS << 16, NS = moc_node_stride(C), in the order and
+                               // with the padding the register-resident kernel reads them (see moc_place_edges)
+  const uint32_t* edge_pair_c; // [m] edges as u*C | v*C << 16, ordered by v (kernel for any C)
   const int32_t* in_ptr;       // [n+1] plain CSR by in-edges
   const int32_t* in_idx;       // [m]
   const int32_t* out_ptr;      // [n+1] CSR by out-edges
@@ -57,6 +58,10 @@ int moc_node_stride(int C);
 // LDS bytes one workgroup of the evaluation kernel needs for a graph of n nodes, m edges, C copies
 // when max_lds bytes are available (optional buffers shrink to fit).
 int moc_eval_lds_bytes(int n, int m, int C, int max_lds);
+
+// Workgroup size and edges per lane of the register-resident evaluation kernel for this
+// graph; false if the graph does not take that kernel.
+bool moc_eval_shape(int n, int m, int C, int* nt, int* edges_per_lane);
 
 int moc_set_hip_error(hipError_t e);  // records e, returns MOC_EHIP
 
