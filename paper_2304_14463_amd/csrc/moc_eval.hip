@@ -571,7 +571,7 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
   uint32_t drawn = 0;   // thread 0
 
   while (b < B) {
-    int viol = 0;              // per wave (the same in every lane, counted on lane masks)
+    int viol = wave == 0 ? n : 0;   // per wave (the same in every lane, counted on lane masks); see phase 1
     int dur = 0;               // per lane
     if (tid == 0) drawn = groups ? atomicAdd(counter, 1u) : next + 1;
     // The workgroup's next candidate; the last one re-reads itself so that the loads below
@@ -600,12 +600,12 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
           live[i] = act[i] & well;
           // an active copy is either ill-formed, one violation of Eq. (2)/(8), or live, one
           // more start for Eq. (6) (the distinct start positions are taken off at the end):
-          // both end up in the same sum
-          viol += count(act[i]);
+          // both end up in the same sum.  The first copy adds one in every case, for when
+          // it is not active Eq. (7) is violated: that makes n, which the sum starts from.
+          if (i > 0) viol += count(act[i]);
           dur += (int)pick(act[i], (uint32_t)sd[it].y);
           rec.w[i] = pick(live[i], (uint32_t)r.s[i] | ((uint32_t)r.e[i] << 16), MOC_DEAD);
         }
-        viol += count(isn & ~act[0]);
 #pragma unroll
         for (int i = 0; i + 1 < CT; ++i) {   // Eq. (3): against the next live copy
           lanemask seen = 0, late = 0;
