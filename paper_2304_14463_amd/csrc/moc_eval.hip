@@ -63,8 +63,9 @@ constexpr int round4(int x) { return (x + 3) & ~3; }
 
 // Register-resident kernel.  Node records first, at LDS address 0: with C <= 2 one record of
 // C words per node; with C >= 3 the first copy of every node (1 word), then the other copies
-// of every node (2 words for C = 3, 4 for C = 4).  One dummy node n that is never live ends
-// each array.  Then the delta array in padded chunks, the start bitmap, the cross-wave
+// of every node (2 words for C = 3, 4 for C = 4).  Dummy nodes end the arrays: C <= 2 one
+// node n that is never live; C >= 3 a consumer n and a provider n + 1 that form a satisfied
+// edge, and a node n + 2 that is never live.  Then the delta array in padded chunks, the start bitmap, the cross-wave
 // exchange area and (C >= 3) a queue per wave, shrunk to fit when LDS is short.
 LdsLayout fast_layout(int n, int C, int nt, int max_lds) {
   const int T = n * C, nw = nt / kWave;
@@ -72,8 +73,8 @@ LdsLayout fast_layout(int n, int C, int nt, int max_lds) {
   l.chunk = 0;
   l.n_chunks = (T + 1 + kChunk - 1) / kChunk;
   l.delta_len = l.n_chunks * kChunkStride;
-  const int first_len = round4((n + 1) * moc_node_stride(C));
-  const int rest_len = C >= 3 ? round4((n + 1) * (C == 3 ? 2 : 4)) : 0;
+  const int first_len = round4((n + (C >= 3 ? 3 : 1)) * moc_node_stride(C));
+  const int rest_len = C >= 3 ? round4((n + 3) * (C == 3 ? 2 : 4)) : 0;
   l.packed_len = first_len + rest_len;
   l.occ_words = (T + 31) / 32;
   l.packed_off = 0;
@@ -391,24 +392,23 @@ __device__ __forceinline__ uint32_t rank_in(lanemask m, uint32_t base) {
 #define MOC_COVER_LAST                                                            \
   "v_cmp_ne_u32_sdwa %2, %5, %6 src0_sel:WORD_0 src1_sel:DWORD\n\t"               \
   "s_andn2_b64 %1, %2, %1\n\t"                                                    \
-  "s_bcnt1_i32_b64 %4, %1\n\t"                                                    \
-  "s_add_i32 %0, %0, %4"
-#define MOC_COVER_REGS "+s"(viol), "=&s"(t1), "=&s"(t2), "=&s"(t3), "=&s"(c) : "v"(pv), "s"(dead)
+  "v_addc_co_u32 %0, vcc, 0, %0, %1"
+#define MOC_COVER_REGS "+v"(viol), "=&s"(t1), "=&s"(t2), "=&s"(t3), "=&s"(c) : "v"(pv), "s"(dead)
 template <int CT>
 __device__ __forceinline__ void count_live_uncovered(int& viol, const Record<CT>& pu, uint32_t pv) {
   lanemask t1, t2, t3;
   int c;
   const uint32_t dead = MOC_DEAD;
   if constexpr (CT == 1)
-    asm(MOC_COVER_FIRST("%7") MOC_COVER_LAST : MOC_COVER_REGS, "v"(pu.w[0]) : "scc");
+    asm(MOC_COVER_FIRST("%7") MOC_COVER_LAST : MOC_COVER_REGS, "v"(pu.w[0]) : "scc", "vcc");
   else if constexpr (CT == 2)
-    asm(MOC_COVER_FIRST("%7") MOC_COVER_NEXT("%8") MOC_COVER_LAST : MOC_COVER_REGS, "v"(pu.w[0]), "v"(pu.w[1]) : "scc");
+    asm(MOC_COVER_FIRST("%7") MOC_COVER_NEXT("%8") MOC_COVER_LAST : MOC_COVER_REGS, "v"(pu.w[0]), "v"(pu.w[1]) : "scc", "vcc");
   else if constexpr (CT == 3)
     asm(MOC_COVER_FIRST("%7") MOC_COVER_NEXT("%8") MOC_COVER_NEXT("%9") MOC_COVER_LAST
-        : MOC_COVER_REGS, "v"(pu.w[0]), "v"(pu.w[1]), "v"(pu.w[2]) : "scc");
+        : MOC_COVER_REGS, "v"(pu.w[0]), "v"(pu.w[1]), "v"(pu.w[2]) : "scc", "vcc");
   else
     asm(MOC_COVER_FIRST("%7") MOC_COVER_NEXT("%8") MOC_COVER_NEXT("%9") MOC_COVER_NEXT("%10") MOC_COVER_LAST
-        : MOC_COVER_REGS, "v"(pu.w[0]), "v"(pu.w[1]), "v"(pu.w[2]), "v"(pu.w[3]) : "scc");
+        : MOC_COVER_REGS, "v"(pu.w[0]), "v"(pu.w[1]), "v"(pu.w[2]), "v"(pu.w[3]) : "scc", "vcc");
 }
 #undef MOC_COVER_FIRST
 #undef MOC_COVER_NEXT
@@ -428,28 +428,25 @@ __device__ __forceinline__ void fetch_edge(uint32_t pair, Record<CT>& pv, Record
   }
 }
 
-// Eq. (5), C >= 3, first pass over an edge pair = u | v << 16: only the first copies of the
-// two nodes are fetched (pu, pv: one word each; bit 31 says that the node has other live
-// copies).  Where neither node has other live copies the instance is settled here and counted
-// into viol; the lanes where one has are returned, their edges go to the wave's queue.
+// Eq. (5), C >= 3, first pass over an edge pair = u | v << 16: only the first words of the
+// two nodes are fetched (pu, pv).  Bit 31 of a first word says that the node needs the full
+// test: it has other live copies, or its first copy is not live.  Where neither word has it,
+// the instance is settled here and counted (per lane) into viol; the lanes where one has are
+// returned, their edges go to the wave's queue.
 __device__ __forceinline__ lanemask check_first_copies(int& viol, uint32_t pu, uint32_t pv) {
   lanemask t1, t2, more;
-  int c;
-  const uint32_t dead = MOC_DEAD;
-  asm("v_cmp_lt_u32_sdwa %1, %5, %6 src0_sel:WORD_0 src1_sel:WORD_0\n\t"
-      "v_cmp_ge_u32_sdwa %2, %5, %6 src0_sel:WORD_1 src1_sel:WORD_0\n\t"
-      "s_and_b64 %1, %1, %2\n\t"   // covered by the first copy of u (void where bit 31 of pu is set)
-      "v_cmp_ne_u32_sdwa %2, %6, %7 src0_sel:WORD_0 src1_sel:DWORD\n\t"
-      "s_andn2_b64 %1, %2, %1\n\t"   // first copy of v live and not covered
-      "v_cmp_gt_i32_e64 %3, 0, %5\n\t"
-      "v_cmp_gt_i32_e64 %2, 0, %6\n\t"
-      "s_or_b64 %3, %3, %2\n\t"      // one of the nodes has other live copies
-      "s_andn2_b64 %1, %1, %3\n\t"
-      "s_bcnt1_i32_b64 %4, %1\n\t"
-      "s_add_i32 %0, %0, %4"
-      : "+s"(viol), "=&s"(t1), "=&s"(t2), "=&s"(more), "=&s"(c)
-      : "v"(pu), "v"(pv), "s"(dead)
-      : "scc");
+  asm("v_cmp_lt_u32_sdwa %1, %4, %5 src0_sel:WORD_0 src1_sel:WORD_0\n\t"
+      "v_cmp_ge_u32_sdwa %2, %4, %5 src0_sel:WORD_1 src1_sel:WORD_0\n\t"
+      "s_and_b64 %1, %1, %2\n\t"   // covered by the first copy of u
+      "v_cmp_gt_i32_e64 %3, 0, %4\n\t"
+      "v_cmp_gt_i32_e64 %2, 0, %5\n\t"
+      "s_or_b64 %3, %3, %2\n\t"      // one of the nodes needs the full test
+      "s_or_b64 %1, %1, %3\n\t"
+      "s_andn2_b64 %1, exec, %1\n\t"
+      "v_addc_co_u32 %0, vcc, 0, %0, %1"
+      : "+v"(viol), "=&s"(t1), "=&s"(t2), "=&s"(more)
+      : "v"(pu), "v"(pv)
+      : "scc", "vcc");
   return more;
 }
 
@@ -501,11 +498,19 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
   uint32_t first_draw = 0;   // thread 0: the first two candidates of this workgroup, asked for before anything else
   if (tid == 0 && groups != 0) first_draw = atomicAdd(counter, 2u);
   uint32_t* const queue = L.queue + wave * lay.qcap;   // kSplit: this wave's edges set aside
-  const uint32_t dummy_pair = (uint32_t)(n * NS) | (uint32_t)(n * NS) << 16;   // the dummy node is never live
+  // the pair of a node that is never live with itself: what idle lanes of the second pass look at
+  const uint32_t dummy_pair = kSplit ? (uint32_t)(n + 2) * 0x10001u : (uint32_t)(n * NS) * 0x10001u;
 
   for (int i = tid; i < lay.delta_len; i += NT) L.delta[i] = 0;
   for (int i = tid; i < lay.occ_words; i += NT) L.occ[i] = 0;
-  for (int i = tid; i < lay.packed_len; i += NT) L.packed[i] = MOC_DEAD;   // both record arrays, incl. the dummy node
+  for (int i = tid; i < lay.packed_len; i += NT) L.packed[i] = MOC_DEAD;   // both record arrays, incl. the dummy nodes
+  if constexpr (kSplit) {
+    __syncthreads();
+    if (tid == 0) {   // the padding of the edge list is the edge (n + 1, n): start 1 inside [0, 0x7FFF]
+      L.packed[n] = 1u;
+      L.packed[n + 1] = 0x7FFF0000u;
+    }
+  }
 
   // what a lane owns never changes: its edges stay in registers
   uint32_t edge[EPT];
@@ -625,7 +630,8 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
           } else if constexpr (CT == 2) {
             *reinterpret_cast<uint2*>(L.packed + v * 2) = make_uint2(rec.w[0], rec.w[1]);
           } else {
-            L.packed[v] = rec.w[0] | pick(others, 0x80000000u);
+            // bit 31: the edges of this node take the full test (other live copies, or no live first copy)
+            L.packed[v] = rec.w[0] | pick(others | (isn & ~live[0]), 0x80000000u);
             if constexpr (CT == 3) *reinterpret_cast<uint2*>(L.rest + v * RS) = make_uint2(rec.w[1], rec.w[2]);
             else *reinterpret_cast<uint4*>(L.rest + v * RS) = make_uint4(rec.w[1], rec.w[2], rec.w[3], MOC_DEAD);
           }
@@ -690,8 +696,8 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
       wave_combine_ordered(lane, S, P);
     }
     const int distinct = count_distinct_starts<NT>(L, lay, tid);
-    // (c) edges, three per slice of the prefetch
-    int queued = 0;
+    // (c) edges, three per slice of the prefetch; their violations are counted per lane
+    int queued = 0, eviol = 0;
 #pragma unroll
     for (int it = 0; it < ITERS; ++it) {
       __builtin_amdgcn_sched_barrier(0);
@@ -706,11 +712,11 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
 #pragma unroll
         for (int j = 0; j < kEdgesPerNode; ++j) {
 #pragma unroll
-          for (int i = 0; i < CT; ++i) count_live_uncovered<CT>(viol, pu[j], pv[j].w[i]);
+          for (int i = 0; i < CT; ++i) count_live_uncovered<CT>(eviol, pu[j], pv[j].w[i]);
         }
       } else {
         if (queued > lay.qcap - kEdgesPerNode * kWave) {   // the slice might not fit: work the queue off first
-          drain_queue<CT>(viol, L, queue, queued, lane, dummy_pair);
+          drain_queue<CT>(eviol, L, queue, queued, lane, dummy_pair);
           queued = 0;
         }
         uint32_t pv[kEdgesPerNode], pu[kEdgesPerNode];
@@ -721,15 +727,15 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
         }
 #pragma unroll
         for (int j = 0; j < kEdgesPerNode; ++j) {
-          const lanemask more = check_first_copies(viol, pu[j], pv[j]);
+          const lanemask more = check_first_copies(eviol, pu[j], pv[j]);
           if (lanes(more)) queue[rank_in(more, (uint32_t)queued)] = edge[it * kEdgesPerNode + j];
           queued += count(more);
         }
       }
     }
-    if constexpr (kSplit) drain_queue<CT>(viol, L, queue, queued, lane, dummy_pair);
+    if constexpr (kSplit) drain_queue<CT>(eviol, L, queue, queued, lane, dummy_pair);
     uint32_t after_next;
-    finish<NT, true>(L, g, tid, lane, wave, S, P, viol, 0, distinct, dur, out, b, drawn, &after_next);
+    finish<NT, true>(L, g, tid, lane, wave, S, P, viol, 0, distinct - eviol, dur, out, b, drawn, &after_next);
     b = b_next;
     next = (uint32_t)__builtin_amdgcn_readfirstlane(after_next);
   }
@@ -882,7 +888,7 @@ int block_threads(int n, int m) {
 // registers, and every thread has at most one delta chunk.
 bool fast_shape(int n, int m, int C, int nt) {
   return C <= 4 && n * C >= 4 && slots_per_lane(n, m, nt) <= kMaxIters && (n * C + kChunk) / kChunk <= nt &&
-         (n + 1) * moc_node_stride(C) <= 0xFFFF;
+         (n + 3) * moc_node_stride(C) <= 0xFFFF;
 }
 
 template <int NT>

@@ -29,14 +29,15 @@ int moc_set_hip_error(hipError_t e) {
 // distinct banks and so do the consumers: such a read costs 2.8 clocks per wave instead of
 // the 7.3 of arbitrary indices.  Greedy: a group takes, bank of u by bank of u (fullest row
 // first), an edge whose bank of v is still free; what does not fit that way while spare
-// entries remain is left for later groups.  Entries without an edge hold the dummy node n,
-// which is never live.
+// entries remain is left for later groups.  Entries without an edge hold a dummy that never
+// counts (see the kernel's LDS layout).
 static std::vector<uint32_t> place_edges(int n, int C, const int32_t* in_ptr, const int32_t* in_idx, int nt,
                                          int edges_per_lane) {
   const int ns = moc_node_stride(C);
   const int banks = ns == 2 ? 16 : 32;   // also the lanes LDS serves at a time
   const size_t slots = (size_t)nt * edges_per_lane;
-  const uint32_t dummy = (uint32_t)(n * ns) | ((uint32_t)(n * ns) << 16);
+  // padding: C <= 2 the node n, which is never live; C >= 3 the satisfied edge (n + 1, n)
+  const uint32_t dummy = C >= 3 ? (uint32_t)(n + 1) | ((uint32_t)n << 16) : (uint32_t)(n * ns) | ((uint32_t)(n * ns) << 16);
   std::vector<uint32_t> out(slots, dummy);
   std::vector<std::vector<uint32_t>> bucket((size_t)banks * banks);   // [bank of u][bank of v] -> pairs
   std::vector<int> row(banks, 0);
