@@ -23,6 +23,36 @@ from concurrent.futures import ThreadPoolExecutor
 
 HBM_PEAK_GBS = 8000.0
 
+# HBM traffic of the evaluation kernel on the default workload, from rocprofv3 counter runs
+# (profiles/eval_batch_kernel_n5000_C3_B262144.md): KiB per dispatch and the factors that the same
+# counters need to reproduce a 1 GiB device copy.  Valid for the kernel sources they were taken with.
+TRAFFIC = {"workload": 4, "B": 262144, "fetch_kib": 17326700.0, "fetch_scale": 2.0, "write_kib": 20496.5,
+           "write_scale": 1.0, "sources_sha256": "de2403dfa18f778bc9ffa6b63b5d13de2c3e34ace91c06d4a0bbebd5dd70a23f"}
+KERNEL_SOURCES = ("moc_eval.hip", "moc_graph.hip", "moc_internal.h")
+
+
+def kernel_sources_sha256():
+    import hashlib
+    h = hashlib.sha256()
+    base = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2304_14463_amd", "csrc")
+    for name in KERNEL_SOURCES:
+        with open(os.path.join(base, name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
+def measured_traffic(cfg, B):
+    """HBM bytes per launch from the committed counter runs, or None when they do not apply
+    (another workload, or the kernel has changed since they were taken)."""
+    if cfg != TRAFFIC["workload"] or B != TRAFFIC["B"]:
+        return None
+    try:
+        if kernel_sources_sha256() != TRAFFIC["sources_sha256"]:
+            return None
+    except OSError:
+        return None
+    return (TRAFFIC["fetch_kib"] * TRAFFIC["fetch_scale"] + TRAFFIC["write_kib"] * TRAFFIC["write_scale"]) * 1024.0
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -173,7 +203,7 @@ def main():
         "dtype": "int32", "data": "synthetic",
         "config": info,
         "roofline": {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": gbs / HBM_PEAK_GBS, "traffic": None,
+                     "frac": gbs / HBM_PEAK_GBS, "traffic": measured_traffic(args.workload, w.B),
                      "kernel": "eval_batch_kernel", "kernel_ms_avg": ms_kernel, "kernel_ms_min": ms_kernel_min,
                      "algorithmic_bytes_per_launch": w.B * info["bytes_per_candidate"]},
     }

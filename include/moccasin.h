@@ -43,6 +43,13 @@
  * the given HIP stream.  The device that was current at upload must be
  * current at every later call with that graph.
  *
+ * Concurrency.  A graph handle may be used from several host threads and
+ * streams at once.  The handle owns 16 sets of device-side work counters,
+ * which moc_eval_batch launches take in turn and leave at zero: at most 16
+ * moc_eval_batch launches on one handle may be in flight on the device at the
+ * same time (launches on one stream follow each other and count as one).
+ * A launch that is aborted (device reset) leaves the handle unusable.
+ *
  * Errors.  Every function that returns int returns MOC_OK (0) or a negative
  * code; nothing is queued on the stream when an error is returned.  Contents
  * of a candidate are never an error: bad values are violations.
@@ -65,9 +72,10 @@ extern "C" {
 
 /* Largest T = n*C an uploaded graph may have: the per-candidate working set
  * (memory-delta array, one record of packed intervals per node, start bitmap)
- * lives in the 160 KB LDS of one compute unit.  With C = 3 a node record is
- * padded to 4 words, which lowers the bound to 16383.  moc_graph_upload
- * returns MOC_EOVERFLOW for a graph that does not fit. */
+ * lives in the 160 KB LDS of one compute unit.  The bound is reached with
+ * C = 1; with more copies per node the records take more room (about 17500
+ * for C = 3, 15600 for C = 4).  moc_graph_upload returns MOC_EOVERFLOW for a
+ * graph that does not fit. */
 #define MOC_MAX_T 19455
 
 typedef struct moc_graph moc_graph; /* opaque; owns device copies of the graph */

@@ -4,31 +4,45 @@
 // Per candidate (register-resident kernel, C <= 4):
 //   phase 1  one lane per node, nodes in id order.  The lane holds the C copies
 //            of its node in registers (requested from HBM while the previous
-//            candidate was being reduced), classifies them (active / live),
+//            candidate was being worked on), classifies them (active / live),
 //            counts Eq. (2),(7),(8) and Eq. (3), adds the node's share of
-//            Eq. (1), stages the node in LDS as one record of packed words
-//            s | e << 16 (one wide store), and scatters every live copy into the
-//            memory-delta array (+m_v at s, -m_v at e+1: the closed intervals of
-//            Eq. (4)) and into a bitmap of occupied start positions (Eq. (6)).
+//            Eq. (1), stages the node in LDS as packed words s | e << 16, and
+//            scatters every live copy into the memory-delta array (+m_v at s,
+//            -m_v at e+1: the closed intervals of Eq. (4)) and into a bitmap of
+//            occupied start positions (Eq. (6)).
 //   phase 2  (a) the delta array is cut into chunks of 32 positions; a thread reads
 //            its chunk with 16-byte LDS loads, zeroes it, and reduces it to
 //            (sum, max prefix); chunks combine associatively in position order,
 //            which yields the peak of Eq. (4) without materialising the profile;
 //            (b) popcount of the start bitmap: distinct start positions, so that
 //            sum_t max(0, cnt_t - 1) = live copies - distinct starts;
-//            (c) one lane per edge (u,v): the records of u and v are fetched with
-//            one wide LDS load each and every live copy of v is tested against
-//            the copies of u (Eq. (5)).  The edges of a lane never change, so
-//            they stay in registers.
+//            (c) one lane per edge (u,v), Eq. (5).  The edges of a lane never
+//            change, so they stay in registers.  C <= 2: the records of u and v
+//            are fetched whole and every live copy of v is tested against the
+//            copies of u.  C >= 3: copies beyond the first are rarely live, so
+//            the first copies are kept in an array of their own (one word per
+//            node, one bit of it saying "this node needs the full test") and an
+//            edge is settled on two 4-byte reads unless one of its nodes says
+//            otherwise; those edges go to a queue per wave and take the full
+//            test afterwards, 64 per instruction.
 //            Phase 2 touches no global memory; the loads of the workgroup's next
 //            candidate are issued in slices between its steps, so that HBM
-//            streams while the LDS work runs and no wave stalls on a full
-//            memory queue.
-// LDS costs that shaped this (measured on gfx950, per compute unit): a 64-lane
-// 4-byte access to random addresses takes about 7 clocks, read, write or atomic
-// alike; 8-byte random costs the same, 16-byte random 12.5; conflict-free
-// 4-byte 2.8 and 16-byte 4.5.  Hence records and chunks are sized for wide
-// accesses and nothing is read twice.
+//            streams while the LDS work runs.
+// Predicates are lane masks: a vector compare writes a 64-bit scalar, the scalar
+// unit combines the masks, counts come from popcounts or an add-with-carry per
+// lane.  Which candidate a workgroup takes next is drawn from a counter, an
+// iteration ahead (see the kernel).
+// What shaped this, measured on gfx950.  A wave issues an instruction every 8
+// clocks at best, whatever the other waves do, and with one 1024-thread
+// workgroup per compute unit (the LDS working set of a large graph allows no
+// more) only 4 waves share a SIMD: the time of a candidate is the number of
+// instructions a wave executes for it, of any kind, plus what it waits at the
+// two barriers.  LDS, per compute unit: a 64-lane 4-byte access to random
+// addresses takes about 7 clocks, read, write or atomic alike; 8-byte random
+// costs the same, 16-byte random 12.5; with the 32 lanes that LDS serves at a
+// time in distinct banks 2.8 (4.4 for 8 bytes and 16 lanes).  Hence records and
+// chunks are sized for wide accesses, nothing is read twice, and the edge list
+// is laid out for distinct banks at upload.
 // All arithmetic is integer: results do not depend on the order in which
 // lanes or workgroups run.
 #include <type_traits>

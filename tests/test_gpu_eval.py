@@ -222,3 +222,51 @@ def test_eval_maximum_size(moc):
         moc.moc_graph_upload(n + 1, np.zeros(n + 2, np.int32), np.zeros(0, np.int32), np.ones(n + 1, np.int32),
                              np.ones(n + 1, np.int32), 1, 1)
     assert err.value.code == -2
+
+
+@pytest.mark.parametrize("C", [2, 3, 4])
+def test_eval_largest_graph_per_copy_count(moc, C):
+    """The largest n that moc_graph_upload accepts for C copies (the LDS working set decides;
+    the optional buffers of the kernel are at their smallest there), with candidates in which
+    many nodes have several live copies and some have none."""
+    import oracle
+    from paper_2304_14463_amd.inputs import graph_from_edges
+    rng = np.random.default_rng(100 + C)
+
+    def make(n):
+        edges = sorted({(int(u), v) for v in range(1, n) for u in rng.integers(max(0, v - 40), v, size=2)})
+        return graph_from_edges(n, edges, rng.integers(1, 100, n), rng.integers(1, 9, n))
+
+    def accepted(n):
+        g = make(n)
+        try:
+            moc.moc_graph_upload(n, g.in_ptr, g.in_idx, g.size, g.dur, 10**6, C).free()
+            return True
+        except moc.MoccasinError as err:
+            assert err.code == -2
+            return False
+
+    lo, hi = 1000, moc.MOC_MAX_T // C + 1   # accepted(lo), not accepted(hi)
+    assert accepted(lo)
+    if accepted(hi - 1):
+        lo = hi - 1
+    while hi - lo > 1 and lo < hi - 1:
+        mid = (lo + hi) // 2
+        if accepted(mid):
+            lo = mid
+        else:
+            hi = mid
+    n = lo
+    assert n * C > 9000, f"unexpectedly small limit: n = {n}"
+    g = make(n)
+    T = n * C
+    B = 6
+    s, e, a = random_candidates(rng, B, n, C, T, wild=True)
+    a.reshape(B, n, C)[:3, :, 0] = 1                        # rows 0-2: every first copy active
+    a.reshape(B, n, C)[:2, :, 1:] *= (rng.random((2, n, C - 1)) < 0.05)   # rows 0-1: few other copies
+    s[0].reshape(n, C)[:, 0] = np.arange(n) * C             # row 0: first copies well-formed
+    e[0].reshape(n, C)[:, 0] = np.minimum(np.arange(n) * C + rng.integers(0, 90, n), T - 1)
+    gh = moc.moc_graph_upload(n, g.in_ptr, g.in_idx, g.size, g.dur, int(g.size.sum()) // 4, C)
+    ref = oracle.evaluate(g, int(g.size.sum()) // 4, C, s, e, a)
+    assert_results_equal(run_eval(moc, gh, s, e, a), ref, f"largest n={n} for C={C}")
+    gh.free()
