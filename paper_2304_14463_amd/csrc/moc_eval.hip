@@ -843,22 +843,28 @@ __global__ __launch_bounds__(NT) void eval_batch_general_kernel(GraphView g, int
 // ------------------------------------------------------------------ host side
 template <typename K>
 int launch_kernel(K kern, int nt, const moc_graph* g, const LdsLayout& lay, int64_t B, const int32_t* starts,
-                  const int32_t* ends, const uint8_t* active, moc_result* out, hipStream_t stream) {
+                  const int32_t* ends, const uint8_t* active, moc_result* out, hipStream_t stream, int which) {
   if (lay.bytes > g->max_lds) return MOC_EOVERFLOW;
-  // The kernels address the node records from LDS address 0: nothing may be placed before the
-  // dynamic segment.  Checked once per kernel.
-  static bool checked = false;   // one per instantiation, i.e. per kernel
-  if (!checked) {
+  // Once per kernel and device: nothing may be placed before the dynamic LDS segment (the
+  // kernels address the node records from LDS address 0), and the kernel may use all the LDS
+  // a workgroup can have.
+  static std::atomic<uint64_t> prepared{0};   // one per instantiation, i.e. per kernel; bit = device
+  const uint64_t dev_bit = (uint64_t)1 << (g->device & 63);
+  if (!(prepared.load(std::memory_order_acquire) & dev_bit)) {
     hipFuncAttributes attr;
     MOC_HIP(hipFuncGetAttributes(&attr, reinterpret_cast<const void*>(kern)));
     if (attr.sharedSizeBytes != 0) return MOC_EINVAL;
-    checked = true;
+    MOC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                g->max_lds));
+    prepared.fetch_or(dev_bit, std::memory_order_release);
   }
-  MOC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                              lay.bytes));
-  int per_cu = 0;
-  MOC_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, nt, lay.bytes));
-  if (per_cu < 1) per_cu = 1;
+  // Workgroups of this kernel and graph that a compute unit holds: asked once per handle.
+  int per_cu = g->per_cu[which].load(std::memory_order_relaxed);
+  if (per_cu == 0) {
+    MOC_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, nt, lay.bytes));
+    if (per_cu < 1) per_cu = 1;
+    g->per_cu[which].store(per_cu, std::memory_order_relaxed);
+  }
   const int64_t resident = (int64_t)per_cu * g->num_cu;
   const unsigned grid = (unsigned)(B < resident ? B : resident);
   // One set of counters per launch in flight (see moc_graph::tickets); about 16 workgroups share a
@@ -878,7 +884,7 @@ int launch_iters(int iters, const moc_graph* g, const LdsLayout& lay, int64_t B,
   if constexpr (IT == 0) {
     return MOC_EINVAL;
   } else {
-    if (iters == IT) return launch_kernel(eval_batch_kernel<NT, CT, IT>, NT, g, lay, B, s, e, a, out, st);
+    if (iters == IT) return launch_kernel(eval_batch_kernel<NT, CT, IT>, NT, g, lay, B, s, e, a, out, st, 0);
     return launch_iters<NT, CT, IT - 1>(iters, g, lay, B, s, e, a, out, st);
   }
 }
@@ -919,7 +925,7 @@ int launch_nt(const moc_graph* g, int64_t B, const int32_t* s, const int32_t* e,
       default: return launch_iters<NT, 4>(iters, g, lay, B, s, e, a, out, st);
     }
   }
-  return launch_kernel(eval_batch_general_kernel<NT>, NT, g, general_layout(n, C, NT), B, s, e, a, out, st);
+  return launch_kernel(eval_batch_general_kernel<NT>, NT, g, general_layout(n, C, NT), B, s, e, a, out, st, 1);
 }
 
 }  // namespace

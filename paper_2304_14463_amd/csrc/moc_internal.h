@@ -43,6 +43,9 @@ struct moc_graph {
   // in flight.
   uint32_t* tickets;
   mutable std::atomic<uint32_t> launch_seq;
+  // workgroups per compute unit of the evaluation kernel this graph takes (0: not asked yet);
+  // [0] the register-resident kernel, [1] the kernel for any C
+  mutable std::atomic<int> per_cu[2];
 };
 
 constexpr int kTicketSlots = 16;
