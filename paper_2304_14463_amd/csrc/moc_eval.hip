@@ -70,6 +70,7 @@ struct LdsLayout {
   int packed_len;  // node records (register-resident kernel, C >= 3: first copies, then the rest)
   int occ_words;   // ceil(T / 32)
   int qcap;        // register-resident kernel, C >= 3: entries per wave in the queue of edges set aside
+  int edge_slices; // register-resident kernel: slices of kEdgesPerNode edges per lane that hold edges
   int bytes;
 };
 
@@ -81,7 +82,7 @@ constexpr int round4(int x) { return (x + 3) & ~3; }
 // node n that is never live; C >= 3 a consumer n and a provider n + 1 that form a satisfied
 // edge, and a node n + 2 that is never live.  Then the delta array in padded chunks, the start bitmap, the cross-wave
 // exchange area and (C >= 3) a queue per wave, shrunk to fit when LDS is short.
-LdsLayout fast_layout(int n, int C, int nt, int max_lds) {
+LdsLayout fast_layout(int n, int m, int C, int nt, int max_lds) {
   const int T = n * C, nw = nt / kWave;
   LdsLayout l;
   l.chunk = 0;
@@ -97,6 +98,7 @@ LdsLayout fast_layout(int n, int C, int nt, int max_lds) {
   l.occ_off = l.delta_off + l.delta_len;
   l.red_off = l.occ_off + l.occ_words;
   l.queue_off = l.red_off + nw * kRedStride;
+  l.edge_slices = (m + kEdgesPerNode * nt - 1) / (kEdgesPerNode * nt);
   l.qcap = C >= 3 ? kQueueCap : 0;
   l.bytes = 4 * (l.queue_off + nw * l.qcap);
   while (l.bytes > max_lds && l.qcap > kEdgesPerNode * kWave) {   // a slice of edges must fit
@@ -121,6 +123,7 @@ LdsLayout general_layout(int n, int C, int nt) {
   l.red_off = l.occ_off + l.occ_words;
   l.queue_off = l.red_off + (nt / kWave) * kRedStride;
   l.qcap = 0;
+  l.edge_slices = 0;
   l.bytes = 4 * l.queue_off;
   return l;
 }
@@ -717,6 +720,7 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
       __builtin_amdgcn_sched_barrier(0);
       if (it > 0 && kEarly + it < ITERS) request(kEarly + it, next_row);
       __builtin_amdgcn_sched_barrier(0);
+      if (it >= lay.edge_slices) continue;   // the edge list fills the first slices; the others hold padding only
       // the records of the slice's edges are asked for together and looked at afterwards: one
       // LDS latency per slice, not one per edge
       if constexpr (!kSplit) {
@@ -916,7 +920,7 @@ int launch_nt(const moc_graph* g, int64_t B, const int32_t* s, const int32_t* e,
               hipStream_t st, bool aligned) {
   const int n = g->view.n, m = g->view.m, C = g->view.C;
   if (aligned && fast_shape(n, m, C, NT)) {
-    const LdsLayout lay = fast_layout(n, C, NT, g->max_lds);
+    const LdsLayout lay = fast_layout(n, m, C, NT, g->max_lds);
     const int iters = slots_per_lane(n, m, NT);
     switch (C) {
       case 1: return launch_iters<NT, 1>(iters, g, lay, B, s, e, a, out, st);
@@ -932,9 +936,10 @@ int launch_nt(const moc_graph* g, int64_t B, const int32_t* s, const int32_t* e,
 
 int moc_node_stride(int C) { return C == 2 ? 2 : 1; }
 
-bool moc_eval_shape(int n, int m, int C, int* nt, int* edges_per_lane) {
+bool moc_eval_shape(int n, int m, int C, int* nt, int* edges_per_lane, int* edges_per_lane_used) {
   *nt = block_threads(n, m);
   *edges_per_lane = kEdgesPerNode * slots_per_lane(n, m, *nt);
+  *edges_per_lane_used = kEdgesPerNode * ((m + kEdgesPerNode * *nt - 1) / (kEdgesPerNode * *nt));
   return fast_shape(n, m, C, *nt);
 }
 
@@ -942,7 +947,7 @@ int moc_eval_lds_bytes(int n, int m, int C, int max_lds) {
   const int nt = block_threads(n, m);
   const int general = general_layout(n, C, nt).bytes;
   if (!fast_shape(n, m, C, nt)) return general;
-  const int fast = fast_layout(n, C, nt, max_lds).bytes;   // misaligned candidate arrays fall back to the general kernel
+  const int fast = fast_layout(n, m, C, nt, max_lds).bytes;   // misaligned candidate arrays fall back to the general kernel
   return fast > general ? fast : general;
 }
 

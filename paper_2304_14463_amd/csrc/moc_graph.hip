@@ -32,13 +32,13 @@ int moc_set_hip_error(hipError_t e) {
 // entries remain is left for later groups.  Entries without an edge hold a dummy that never
 // counts (see the kernel's LDS layout).
 static std::vector<uint32_t> place_edges(int n, int C, const int32_t* in_ptr, const int32_t* in_idx, int nt,
-                                         int edges_per_lane) {
+                                         int edges_per_lane, int edges_per_lane_used) {
   const int ns = moc_node_stride(C);
   const int banks = ns == 2 ? 16 : 32;   // also the lanes LDS serves at a time
-  const size_t slots = (size_t)nt * edges_per_lane;
+  const size_t slots = (size_t)nt * edges_per_lane_used;   // the kernel skips the entries beyond
   // padding: C <= 2 the node n, which is never live; C >= 3 the satisfied edge (n + 1, n)
   const uint32_t dummy = C >= 3 ? (uint32_t)(n + 1) | ((uint32_t)n << 16) : (uint32_t)(n * ns) | ((uint32_t)(n * ns) << 16);
-  std::vector<uint32_t> out(slots, dummy);
+  std::vector<uint32_t> out((size_t)nt * edges_per_lane, dummy);
   std::vector<std::vector<uint32_t>> bucket((size_t)banks * banks);   // [bank of u][bank of v] -> pairs
   std::vector<int> row(banks, 0);
   size_t left = 0;
@@ -142,9 +142,10 @@ int moc_graph_upload(int32_t n, const int32_t* in_ptr, const int32_t* in_idx, co
     for (int v = 0; v < n; ++v)
       for (int q = in_ptr[v]; q < in_ptr[v + 1]; ++q)
         edge_pair_c[q] = (uint32_t)(in_idx[q] * C) | ((uint32_t)(v * C) << 16);
-    int nt = 0, edges_per_lane = 0;
+    int nt = 0, edges_per_lane = 0, edges_per_lane_used = 0;
     std::vector<uint32_t> edge_pair;
-    if (moc_eval_shape(n, m, C, &nt, &edges_per_lane)) edge_pair = place_edges(n, C, in_ptr, in_idx, nt, edges_per_lane);
+    if (moc_eval_shape(n, m, C, &nt, &edges_per_lane, &edges_per_lane_used))
+      edge_pair = place_edges(n, C, in_ptr, in_idx, nt, edges_per_lane, edges_per_lane_used);
 
     // out-edge CSR (consumers of every node), used by the neighbourhood kernel
     std::vector<int32_t> out_ptr(n + 1, 0), out_idx(m);

@@ -63,8 +63,9 @@ int moc_node_stride(int C);
 int moc_eval_lds_bytes(int n, int m, int C, int max_lds);
 
 // Workgroup size and edges per lane of the register-resident evaluation kernel for this
-// graph; false if the graph does not take that kernel.
-bool moc_eval_shape(int n, int m, int C, int* nt, int* edges_per_lane);
+// graph (the list holds edges_per_lane entries per lane, of which the first
+// edges_per_lane_used are looked at); false if the graph does not take that kernel.
+bool moc_eval_shape(int n, int m, int C, int* nt, int* edges_per_lane, int* edges_per_lane_used);
 
 int moc_set_hip_error(hipError_t e);  // records e, returns MOC_EHIP
 
