@@ -20,8 +20,12 @@
 // and peak' = max(prefix max before, suffix max after, shifted profile inside)
 // over the changed positions (at most R of them unless the copy was outside
 // the domain before the move).
-// Pass 1 stores f(old copy) per copy; pass 2 runs one lane per move, so that
-// the 8-byte scores of a candidate are written as one contiguous stream.
+// Pass 1 stores f(old copy) per copy.  Pass 2 runs one lane per (copy, field):
+// the lane walks the edges of its node once per 16 displacements and scores
+// them side by side (what does not depend on the displacement is computed
+// once), then writes its 2R scores, 16R contiguous bytes.  A wave takes 64
+// consecutive nodes with the same copy index and field.  The adjacency lists
+// are kept in LDS when they fit beside the five T-word arrays.
 #include "moc_internal.h"
 
 namespace {
@@ -32,17 +36,34 @@ constexpr int kNW = kNT / kWave;
 struct NbLayout {
   int T_pad;      // T rounded up to 4
   int bit_words;  // ceil(T / 32)
+  int adj_off;    // word offset of the graph's adjacency lists in LDS, 0 if they stay in global memory
   int bytes;
 };
 
-NbLayout nb_layout(int T) {
+NbLayout nb_layout(int T, int n, int m, int max_lds) {
   NbLayout l;
   l.T_pad = (T + 3) & ~3;
   l.bit_words = (T + 31) / 32;
   // profile, prefix max, suffix max, packed, f(old) + two bitmaps + scratch
-  l.bytes = 4 * (5 * l.T_pad + 2 * l.bit_words + 8 * kNW + 16);
+  const int words = 5 * l.T_pad + 2 * l.bit_words + 8 * kNW + 16;
+  l.adj_off = 0;
+  l.bytes = 4 * words;
+  // the CSR lists both ways, if there is room: every move walks the edges of its node
+  const int with_adj = 4 * (words + 2 * (n + 1) + 2 * m);
+  if (with_adj <= max_lds) {
+    l.adj_off = words;
+    l.bytes = with_adj;
+  }
   return l;
 }
+
+// The graph's adjacency, by in-edges and by out-edges (CSR), in LDS or in global memory.
+struct Adj {
+  const int32_t* in_ptr;
+  const int32_t* in_idx;
+  const int32_t* out_ptr;
+  const int32_t* out_idx;
+};
 
 struct NbLds {
   int32_t* profile;
@@ -99,9 +120,8 @@ __device__ void block_scan(const int32_t* src, int32_t* dst, int T, int32_t* scr
 //   order : Eq. (3) among the live copies of v
 //   cons  : in-edges of v not covered at the start of copy i
 //   prov  : (out-edge (v,w), live copy of w) pairs not covered by any live copy of v
-__device__ int node_part(const GraphView& g, const uint32_t* __restrict__ packed, int v, int i, bool active,
-                         bool live, int s, int e) {
-  const int C = g.C;
+__device__ __forceinline__ int node_part(const Adj& g, int C, const uint32_t* __restrict__ packed, int v, int i,
+                                         bool active, bool live, int s, int e) {
   const uint32_t mine = pack_copy(live, s, e);
   int count = (active && !live) ? 1 : 0;
   // Eq. (3): each live copy against the next live copy
@@ -138,6 +158,38 @@ __device__ int node_part(const GraphView& g, const uint32_t* __restrict__ packed
   return count;
 }
 
+constexpr int kDisp = 16;   // displacements a lane scores at a time
+
+// One move of a copy, from scratch: (violations, peak) of the candidate with that one field
+// at `moved`.  The general form; the kernel uses it for copies that are ill-formed before
+// the move, where the changed positions are a whole interval.
+__device__ __forceinline__ void score_move(const Adj& g, int C, int sz, const NbLds& L, int T, int v, int i,
+                                           int field, int s, int e, int moved, int base_viol, int base_peak,
+                                           moc_move_score& sc) {
+  const int k = v * C + i;
+  const int s2 = field == 0 ? moved : s, e2 = field == 0 ? e : moved;
+  const bool live_old = live_of(L.packed[k]);
+  const bool live_new = (uint32_t)s2 <= (uint32_t)e2 && (uint32_t)e2 < (uint32_t)T;
+  int vv = base_viol - L.fold[k] + node_part(g, C, L.packed, v, i, true, live_new, s2, e2);
+  if (live_old && bit_at(L.occ2, s)) --vv;
+  if (live_new) vv += (live_old && s2 == s) ? (bit_at(L.occ2, s) ? 1 : 0) : (bit_at(L.occ1, s2) ? 1 : 0);
+  // peak: positions lost (sign -1) or gained (sign +1)
+  int pk = base_peak;
+  if (live_old || live_new) {
+    int lo = 0, hi = -1, sign = 0;
+    if (live_old && live_new) {
+      if (field == 0) { lo = min(s, s2); hi = max(s, s2) - 1; sign = s2 < s ? 1 : -1; }
+      else { lo = min(e, e2) + 1; hi = max(e, e2); sign = e2 > e ? 1 : -1; }
+    } else if (live_old) { lo = s; hi = e; sign = -1; }
+    else { lo = s2; hi = e2; sign = 1; }
+    int inside = 0;
+    for (int t = lo; t <= hi; ++t) inside = max(inside, L.profile[t] + sign * sz);
+    pk = max(inside, max(lo > 0 ? L.pmax[lo - 1] : 0, hi + 1 < T ? L.smax[hi + 1] : 0));
+  }
+  sc.violations = vv;
+  sc.peak = pk;
+}
+
 struct Best {
   int viol, peak, move;   // move < 0: none
 };
@@ -152,6 +204,7 @@ __device__ __forceinline__ bool better(const Best& a, const Best& b, int64_t bud
   return a.move < b.move;
 }
 
+template <bool ADJ_LDS>
 __global__ __launch_bounds__(kNT) void neighbours_kernel(GraphView g, int64_t B, const int32_t* __restrict__ starts,
                                                          const int32_t* __restrict__ ends,
                                                          const uint8_t* __restrict__ active, int R,
@@ -170,6 +223,14 @@ __global__ __launch_bounds__(kNT) void neighbours_kernel(GraphView g, int64_t B,
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
   const int T = g.T, C = g.C;
   const int moves_per_cand = T * 4 * R;
+  Adj A{g.in_ptr, g.in_idx, g.out_ptr, g.out_idx};
+  if constexpr (ADJ_LDS) {   // the adjacency lists are read by every move: keep them in LDS
+    int32_t* a = reinterpret_cast<int32_t*>(nb_raw) + lay.adj_off;
+    for (int x = tid; x <= g.n; x += kNT) { a[x] = g.in_ptr[x]; a[g.n + 1 + g.m + x] = g.out_ptr[x]; }
+    for (int x = tid; x < g.m; x += kNT) { a[g.n + 1 + x] = g.in_idx[x]; a[2 * (g.n + 1) + g.m + x] = g.out_idx[x]; }
+    A = Adj{a, a + g.n + 1, a + g.n + 1 + g.m, a + 2 * (g.n + 1) + g.m};
+    __syncthreads();
+  }
 
   for (int64_t b = blockIdx.x; b < B; b += gridDim.x) {
     const int64_t row = b * T;
@@ -207,7 +268,7 @@ __global__ __launch_bounds__(kNT) void neighbours_kernel(GraphView g, int64_t B,
       const int s = starts[row + k], e = ends[row + k];
       const bool act = active[row + k] != 0;
       const bool live = live_of(L.packed[k]);
-      L.fold[k] = act ? node_part(g, L.packed, v, i, act, live, s, e) : 0;
+      L.fold[k] = act ? node_part(A, C, L.packed, v, i, act, live, s, e) : 0;
       // base count: each instance once -- form, the order pair that copy k opens, its inputs
       viol += (act && !live) ? 1 : 0;
       if (live) {
@@ -218,8 +279,8 @@ __global__ __launch_bounds__(kNT) void neighbours_kernel(GraphView g, int64_t B,
             break;
           }
         }
-        for (int q = g.in_ptr[v]; q < g.in_ptr[v + 1]; ++q) {
-          const int u = g.in_idx[q];
+        for (int q = A.in_ptr[v]; q < A.in_ptr[v + 1]; ++q) {
+          const int u = A.in_idx[q];
           bool cov = false;
           for (int j = 0; j < C; ++j) cov = cov || covers1(L.packed[u * C + j], (uint32_t)s);
           viol += cov ? 0 : 1;
@@ -233,50 +294,181 @@ __global__ __launch_bounds__(kNT) void neighbours_kernel(GraphView g, int64_t B,
     const int base_viol = L.scratch[8 * kNW];
     const int base_peak = L.pmax[T - 1];
 
-    // ---- pass 2: one lane per move
+    // ---- pass 2: one lane per (copy, field); it scores the 2R displacements of that field.
+    // A wave takes 64 consecutive nodes, one copy index and one field at a time: the field and
+    // the copy index are the same in all its lanes, and a copy index that is rarely active
+    // costs the wave next to nothing.
     Best best{0, 0, -1};
-    for (int q = tid; q < moves_per_cand; q += kNT) {
-      const int d = q % (2 * R);
-      const int pf = q / (2 * R);
-      const int field = pf & 1, k = pf >> 1;
-      const int delta = d < R ? d - R : d - R + 1;
+    const int two_r = 2 * R;
+    const int node_blocks = (g.n + kWave - 1) / kWave;
+    for (int blk = wave; blk < node_blocks * C * 2; blk += kNW) {
+      const int field = blk & 1, i = (blk >> 1) % C, v = ((blk >> 1) / C) * kWave + lane;
+      if (v >= g.n) continue;
+      const int k = v * C + i, pf = 2 * k + field;
       const int s = starts[row + k], e = ends[row + k];
       const bool act = active[row + k] != 0;
-      const int moved = (field == 0 ? s : e) + delta;
-      int sc_v = -1, sc_p = -1;
-      if (act && moved >= 0 && moved < T) {
-        const int v = k / C, i = k - v * C;
-        const int s2 = field == 0 ? moved : s, e2 = field == 0 ? e : moved;
-        const bool live_old = live_of(L.packed[k]);
-        const bool live_new = (uint32_t)s2 <= (uint32_t)e2 && (uint32_t)e2 < (uint32_t)T;
-        // violations
-        int vv = base_viol - L.fold[k] + node_part(g, L.packed, v, i, true, live_new, s2, e2);
-        if (live_old && bit_at(L.occ2, s)) --vv;
-        if (live_new) vv += (live_old && s2 == s) ? (bit_at(L.occ2, s) ? 1 : 0) : (bit_at(L.occ1, s2) ? 1 : 0);
-        // peak: positions lost (sign -1) or gained (sign +1)
-        int pk = base_peak;
-        if (live_old || live_new) {
-          const int sz = g.size_dur[v].x;
-          int lo = 0, hi = -1, sign = 0;
-          if (live_old && live_new) {
-            if (field == 0) { lo = min(s, s2); hi = max(s, s2) - 1; sign = s2 < s ? 1 : -1; }
-            else { lo = min(e, e2) + 1; hi = max(e, e2); sign = e2 > e ? 1 : -1; }
-          } else if (live_old) { lo = s; hi = e; sign = -1; }
-          else { lo = s2; hi = e2; sign = 1; }
-          int inside = 0;
-          for (int t = lo; t <= hi; ++t) inside = max(inside, L.profile[t] + sign * sz);
-          pk = max(inside, max(lo > 0 ? L.pmax[lo - 1] : 0, hi + 1 < T ? L.smax[hi + 1] : 0));
+      const uint32_t mine = L.packed[k];
+      const int sz = g.size_dur[v].x;
+      moc_move_score* const dst = out_moves ? out_moves + (b * (int64_t)moves_per_cand + (int64_t)pf * two_r) : nullptr;
+      if (!act || !live_of(mine)) {
+        // not applicable, or a copy that is ill-formed now (rare): move by move
+        for (int d = 0; d < two_r; ++d) {
+          const int delta = d < R ? d - R : d - R + 1;
+          const int moved = (field == 0 ? s : e) + delta;
+          moc_move_score sc{-1, -1};
+          if (act && moved >= 0 && moved < T) {
+            score_move(A, C, sz, L, T, v, i, field, s, e, moved, base_viol, base_peak, sc);
+            const Best cand{sc.violations, sc.peak, pf * two_r + d};
+            if (better(cand, best, g.budget)) best = cand;
+          }
+          if (dst) dst[d] = sc;
         }
-        sc_v = vv;
-        sc_p = pk;
-        const Best cand{vv, pk, q};
-        if (better(cand, best, g.budget)) best = cand;
+        continue;
       }
-      if (out_moves) {
-        moc_move_score sc;
-        sc.violations = sc_v;
-        sc.peak = sc_p;
-        out_moves[b * (int64_t)moves_per_cand + q] = sc;
+      // ---- copy k is live: what does not depend on the displacement
+      // Eq. (3): the live neighbours of copy i among the copies of v, and the violations
+      // between other consecutive live copies
+      int prev_end = -1, next_start = 0x7FFFFFFF, order_others = 0;
+      {
+        int pe = -1;
+        bool have = false;
+        for (int j = 0; j < i; ++j) {
+          const uint32_t p = L.packed[v * C + j];
+          if (!live_of(p)) continue;
+          if (have && pe > (int)(p & 0xFFFFu)) ++order_others;
+          pe = (int)(p >> 16);
+          have = true;
+        }
+        if (have) prev_end = pe;
+        have = false;
+        for (int j = i + 1; j < C; ++j) {
+          const uint32_t p = L.packed[v * C + j];
+          if (!live_of(p)) continue;
+          if (!have) next_start = (int)(p & 0xFFFFu);
+          else if (pe > (int)(p & 0xFFFFu)) ++order_others;
+          pe = (int)(p >> 16);
+          have = true;
+        }
+      }
+      const int order_without = (prev_end >= 0 && next_start != 0x7FFFFFFF && prev_end > next_start) ? 1 : 0;
+      const int start_twice = bit_at(L.occ2, s) ? 1 : 0;
+      const int fixed = base_viol - L.fold[k] + order_others - start_twice;
+      const int in_lo = A.in_ptr[v], in_hi = A.in_ptr[v + 1], out_lo = A.out_ptr[v], out_hi = A.out_ptr[v + 1];
+      int lost_all = -1;   // peak inside [s, e] without this copy: computed when first needed
+      for (int d0 = 0; d0 < two_r; d0 += kDisp) {
+        int vv[kDisp], pk[kDisp];
+        // ---- violations
+#pragma unroll
+        for (int dd = 0; dd < kDisp; ++dd) {
+          const int d = d0 + dd, delta = d < R ? d - R : d - R + 1;
+          const int s2 = field == 0 ? s + delta : s, e2 = field == 0 ? e : e + delta;
+          const bool live_new = s2 >= 0 && s2 <= e2 && e2 < T;
+          int c = fixed;
+          if (live_new) {
+            c += (prev_end > s2 ? 1 : 0) + (e2 > next_start ? 1 : 0);                  // Eq. (3) around the moved copy
+            c += s2 == s ? start_twice : (bit_at(L.occ1, s2) ? 1 : 0);               // Eq. (6)
+          } else {
+            c += 1 + order_without;                                                   // Eq. (2)/(8); Eq. (3) across the gap
+          }
+          vv[dd] = c;
+        }
+        // Eq. (5), the copy as consumer: every in-edge whose provider does not cover the start
+        if (field == 1) {
+          int uncovered = 0;
+          for (int q = in_lo; q < in_hi; ++q) {
+            const int u = A.in_idx[q];
+            bool cov = false;
+            for (int j = 0; j < C; ++j) cov = cov || covers1(L.packed[u * C + j], (uint32_t)s);
+            uncovered += cov ? 0 : 1;
+          }
+#pragma unroll
+          for (int dd = 0; dd < kDisp; ++dd) {
+            const int d = d0 + dd, delta = d < R ? d - R : d - R + 1;
+            const int e2 = e + delta;
+            vv[dd] += (s <= e2 && e2 < T) ? uncovered : 0;
+          }
+        } else {
+          for (int q = in_lo; q < in_hi; ++q) {
+            const int u = A.in_idx[q];
+            uint32_t covered = 0;   // bit dd: some copy of u covers the start moved by displacement dd
+            for (int j = 0; j < C; ++j) {
+              const uint32_t pu = L.packed[u * C + j];
+#pragma unroll
+              for (int dd = 0; dd < kDisp; ++dd) {
+                const int d = d0 + dd, delta = d < R ? d - R : d - R + 1;
+                const int s2 = s + delta;
+                covered |= (s2 >= 0 && covers1(pu, (uint32_t)s2)) ? 1u << dd : 0u;
+              }
+            }
+#pragma unroll
+            for (int dd = 0; dd < kDisp; ++dd) {
+              const int d = d0 + dd, delta = d < R ? d - R : d - R + 1;
+              const int s2 = s + delta;
+              vv[dd] += (s2 >= 0 && s2 <= e && !(covered >> dd & 1u)) ? 1 : 0;
+            }
+          }
+        }
+        // Eq. (5), node v as provider: every live copy of every consumer
+        for (int q = out_lo; q < out_hi; ++q) {
+          const int w = A.out_idx[q];
+          for (int jw = 0; jw < C; ++jw) {
+            const uint32_t pw = L.packed[w * C + jw];
+            if (!live_of(pw)) continue;
+            const uint32_t x = pw & 0xFFFFu;
+            bool cov_other = false;
+            for (int j = 0; j < C; ++j) cov_other = cov_other || (j != i && covers1(L.packed[v * C + j], x));
+            if (cov_other) continue;
+#pragma unroll
+            for (int dd = 0; dd < kDisp; ++dd) {
+              const int d = d0 + dd, delta = d < R ? d - R : d - R + 1;
+              const int s2 = field == 0 ? s + delta : s, e2 = field == 0 ? e : e + delta;
+              const bool live_new = s2 >= 0 && s2 <= e2 && e2 < T;
+              vv[dd] += (live_new && s2 < (int)x && (int)x <= e2) ? 0 : 1;
+            }
+          }
+        }
+        // ---- peak: the profile changes on the positions between the old and the new value of the field
+#pragma unroll
+        for (int dd = 0; dd < kDisp; ++dd) {
+          const int d = d0 + dd, delta = d < R ? d - R : d - R + 1;
+          const int s2 = field == 0 ? s + delta : s, e2 = field == 0 ? e : e + delta;
+          const bool in_dom = (field == 0 ? s2 : e2) >= 0 && (field == 0 ? s2 : e2) < T;
+          const bool live_new = s2 >= 0 && s2 <= e2 && e2 < T;
+          int p = base_peak;
+          if (in_dom) {
+            if (live_new) {
+              int lo, hi, sign;
+              if (field == 0) { lo = min(s, s2); hi = max(s, s2) - 1; sign = s2 < s ? 1 : -1; }
+              else { lo = min(e, e2) + 1; hi = max(e, e2); sign = e2 > e ? 1 : -1; }
+              int inside = 0;
+              for (int t = lo; t <= hi; ++t) inside = max(inside, L.profile[t] + sign * sz);
+              p = max(inside, max(lo > 0 ? L.pmax[lo - 1] : 0, hi + 1 < T ? L.smax[hi + 1] : 0));
+            } else {
+              if (lost_all < 0) {
+                lost_all = 0;
+                for (int t = s; t <= e; ++t) lost_all = max(lost_all, L.profile[t] - sz);
+              }
+              p = max(lost_all, max(s > 0 ? L.pmax[s - 1] : 0, e + 1 < T ? L.smax[e + 1] : 0));
+            }
+          }
+          pk[dd] = p;
+        }
+        // ---- results of this group of displacements
+#pragma unroll
+        for (int dd = 0; dd < kDisp; ++dd) {
+          const int d = d0 + dd;
+          if (d >= two_r) continue;
+          const int delta = d < R ? d - R : d - R + 1;
+          const int moved = (field == 0 ? s : e) + delta;
+          moc_move_score sc{-1, -1};
+          if (moved >= 0 && moved < T) {
+            sc.violations = vv[dd];
+            sc.peak = pk[dd];
+            const Best cand{vv[dd], pk[dd], pf * two_r + d};
+            if (better(cand, best, g.budget)) best = cand;
+          }
+          if (dst) dst[d] = sc;
+        }
       }
     }
 
@@ -328,18 +520,19 @@ extern "C" int moc_eval_neighbours(const moc_graph* g, int64_t B, const int32_t*
   MOC_HIP(hipGetDevice(&dev));
   if (dev != g->device) return MOC_EDEVICE;
   if (g->has_self_loop) return MOC_EINVAL;
-  const NbLayout lay = nb_layout(g->view.T);
+  const NbLayout lay = nb_layout(g->view.T, g->view.n, g->view.m, g->max_lds);
   if (lay.bytes > g->max_lds) return MOC_EOVERFLOW;
   if ((int64_t)g->view.T * 4 * R > 0x7FFFFFFF) return MOC_EOVERFLOW;
-  MOC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(neighbours_kernel),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, lay.bytes));
+  auto kern = lay.adj_off ? neighbours_kernel<true> : neighbours_kernel<false>;
+  MOC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              lay.bytes));
   int per_cu = 0;
-  MOC_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, neighbours_kernel, kNT, lay.bytes));
+  MOC_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, kNT, lay.bytes));
   if (per_cu < 1) per_cu = 1;
   const int64_t resident = (int64_t)per_cu * g->num_cu;
   const unsigned grid = (unsigned)(B < resident ? B : resident);
-  hipLaunchKernelGGL(neighbours_kernel, dim3(grid), dim3(kNT), lay.bytes, static_cast<hipStream_t>(hip_stream),
-                     g->view, B, starts, ends, active, R, out_moves, out_best, lay);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(kNT), lay.bytes, static_cast<hipStream_t>(hip_stream), g->view, B,
+                     starts, ends, active, R, out_moves, out_best, lay);
   MOC_HIP(hipGetLastError());
   return MOC_OK;
 }
