@@ -504,7 +504,7 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
   constexpr bool kSplit = CT >= 3;          // first copies and other copies in separate arrays
   constexpr int NS = kSplit ? 1 : CT;       // words per node in the first array
   constexpr int RS = CT == 3 ? 2 : 4;       // kSplit: words per node in the second
-  constexpr int kEarly = ITERS * 2 / 5;     // node slots re-requested during phase 1
+  constexpr int kEarly = ITERS * 3 / 5;     // node slots re-requested during phase 1
   extern __shared__ uint32_t lds_raw[];
   const Lds L = carve(lds_raw, lay);
   const int tid = threadIdx.x, lane = tid & (kWave - 1);
