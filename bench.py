@@ -58,7 +58,7 @@ def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", type=int, default=4, choices=[0, 1, 2, 3, 4])
     ap.add_argument("--batch", type=int, default=None, help="override the workload's batch size")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -79,6 +79,16 @@ def time_eval(moc, gh, cand, steps, warmup):
     for _ in range(warmup):
         moc.moc_eval_batch(gh, ds, de, da, out=out, stream=stream)
     torch.cuda.synchronize()
+    # launches of well under a millisecond: keep the device busy for a while first, so that the
+    # timed steps do not run while its clocks are still coming up
+    t0 = time.perf_counter()
+    moc.moc_eval_batch(gh, ds, de, da, out=out, stream=stream)
+    torch.cuda.synchronize()
+    one = max(time.perf_counter() - t0, 1e-6)
+    if one < 2e-3:
+        for _ in range(int(0.1 / one)):
+            moc.moc_eval_batch(gh, ds, de, da, out=out, stream=stream)
+        torch.cuda.synchronize()
     begins = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
     finishes = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
     t0 = time.perf_counter()
