@@ -682,7 +682,6 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
         }
       }
       if (it < kEarly) request(it, next_row);
-      __builtin_amdgcn_sched_barrier(0);   // one node slot at a time: interleaving them costs registers
     }
     __syncthreads();
 
