@@ -26,8 +26,8 @@ HBM_PEAK_GBS = 8000.0
 # HBM traffic of the evaluation kernel on the default workload, from rocprofv3 counter runs
 # (profiles/eval_batch_kernel_n5000_C3_B262144.md): KiB per dispatch and the factors that the same
 # counters need to reproduce a 1 GiB device copy.  Valid for the kernel sources they were taken with.
-TRAFFIC = {"workload": 4, "B": 262144, "fetch_kib": 17326700.0, "fetch_scale": 2.0, "write_kib": 20496.5,
-           "write_scale": 1.0, "sources_sha256": "de2403dfa18f778bc9ffa6b63b5d13de2c3e34ace91c06d4a0bbebd5dd70a23f"}
+TRAFFIC = {"workload": 4, "B": 262144, "fetch_kib": 17327700.0, "fetch_scale": 2.0, "write_kib": 20496.5,
+           "write_scale": 1.0, "sources_sha256": "75d0f43e003acddc7ee6008ca86f308c722d1b1d610ec6db45c7a0ee41992a30"}
 KERNEL_SOURCES = ("moc_eval.hip", "moc_graph.hip", "moc_internal.h")
 
 
