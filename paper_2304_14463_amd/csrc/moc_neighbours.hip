@@ -20,12 +20,12 @@
 // and peak' = max(prefix max before, suffix max after, shifted profile inside)
 // over the changed positions (at most R of them unless the copy was outside
 // the domain before the move).
-// Pass 1 stores f(old copy) per copy.  Pass 2 runs one lane per (copy, field):
-// the lane walks the edges of its node once per 16 displacements and scores
-// them side by side (what does not depend on the displacement is computed
-// once), then writes its 2R scores, 16R contiguous bytes.  A wave takes 64
-// consecutive nodes with the same copy index and field.  The adjacency lists
-// are kept in LDS when they fit beside the five T-word arrays.
+// Pass 1 stores f(old copy) per copy and lists the active copies.  Pass 2 runs
+// one lane per move of an active copy: 64 consecutive moves of the list per
+// wave, so the lanes of one copy walk the same edges together, inactive copies
+// cost nothing, and a wave writes its scores as whole 128-byte lines.  A third
+// pass fills the scores of the inactive copies (not applicable).  The adjacency
+// lists are kept in LDS when they fit beside the five T-word arrays.
 #include "moc_internal.h"
 
 namespace {
@@ -70,7 +70,8 @@ struct NbLds {
   int32_t* pmax;
   int32_t* smax;
   uint32_t* packed;
-  int32_t* fold;
+  uint16_t* fold;   // [2k]: f(old copy k), below 2^15 for any T this call accepts
+  uint16_t* list;   // [2j]: j-th entry of the copy lists (the other half of the same words)
   uint32_t* occ1;
   uint32_t* occ2;
   int32_t* scratch;   // 8 * kNW + 16
@@ -158,8 +159,6 @@ __device__ __forceinline__ int node_part(const Adj& g, int C, const uint32_t* __
   return count;
 }
 
-constexpr int kDisp = 16;   // displacements a lane scores at a time
-
 // One move of a copy, from scratch: (violations, peak) of the candidate with that one field
 // at `moved`.  The general form; the kernel uses it for copies that are ill-formed before
 // the move, where the changed positions are a whole interval.
@@ -170,7 +169,7 @@ __device__ __forceinline__ void score_move(const Adj& g, int C, int sz, const Nb
   const int s2 = field == 0 ? moved : s, e2 = field == 0 ? e : moved;
   const bool live_old = live_of(L.packed[k]);
   const bool live_new = (uint32_t)s2 <= (uint32_t)e2 && (uint32_t)e2 < (uint32_t)T;
-  int vv = base_viol - L.fold[k] + node_part(g, C, L.packed, v, i, true, live_new, s2, e2);
+  int vv = base_viol - (int)L.fold[2 * k] + node_part(g, C, L.packed, v, i, true, live_new, s2, e2);
   if (live_old && bit_at(L.occ2, s)) --vv;
   if (live_new) vv += (live_old && s2 == s) ? (bit_at(L.occ2, s) ? 1 : 0) : (bit_at(L.occ1, s2) ? 1 : 0);
   // peak: positions lost (sign -1) or gained (sign +1)
@@ -190,6 +189,75 @@ __device__ __forceinline__ void score_move(const Adj& g, int C, int sz, const Nb
   sc.peak = pk;
 }
 
+
+// One move of a live copy (v, i): field moved to `moved`, a position in [0, T).
+// `mine` is the copy before the move, `fixed` the base violation count without
+// f(old copy).  The changed positions of the profile are at most R: the move is
+// by at most R, and when it leaves the copy ill formed the copy was shorter than that.
+template <int CT>
+__device__ __forceinline__ void score_live(const Adj& A, int C, int sz, const NbLds& L, int T, int R, int v, int i,
+                                           int field, int moved, uint32_t mine, int fixed, moc_move_score& sc) {
+  const int s = (int)(mine & 0xFFFFu), e = (int)(mine >> 16);
+  const int s2 = field == 0 ? moved : s, e2 = field == 0 ? e : moved;
+  const bool live_new = s2 <= e2;
+  const uint32_t moved_copy = pack_copy(live_new, s2, e2);
+  const uint32_t* const row = L.packed + v * C;
+  uint32_t cv[CT > 0 ? CT : 1];   // the copies of v after the move
+  if constexpr (CT > 0) {
+#pragma unroll
+    for (int j = 0; j < CT; ++j) cv[j] = j == i ? moved_copy : row[j];
+  }
+  auto copy_of_v = [&](int j) -> uint32_t {
+    if constexpr (CT > 0) return cv[j];
+    else return j == i ? moved_copy : row[j];
+  };
+  int count = live_new ? 0 : 1;   // Eq. (2)/(8)
+  // Eq. (3): each live copy of v against the next live one
+  int prev_end = -1;
+  for (int j = 0; j < C; ++j) {
+    const uint32_t p = copy_of_v(j);
+    if (!live_of(p)) continue;
+    count += prev_end > (int)(p & 0xFFFFu) ? 1 : 0;
+    prev_end = (int)(p >> 16);
+  }
+  // Eq. (6): the old start leaves, the new one arrives
+  const int start_twice = bit_at(L.occ2, s) ? 1 : 0;
+  count -= start_twice;
+  if (live_new) {
+    count += s2 == s ? start_twice : (bit_at(L.occ1, s2) ? 1 : 0);
+    // Eq. (5), the copy as consumer: in-edges whose provider does not cover the start
+    for (int q = A.in_ptr[v], q1 = A.in_ptr[v + 1]; q < q1; ++q) {
+      const uint32_t* const pu = L.packed + A.in_idx[q] * C;
+      bool cov = false;
+      for (int j = 0; j < C; ++j) cov = cov || covers1(pu[j], (uint32_t)s2);
+      count += cov ? 0 : 1;
+    }
+  }
+  // Eq. (5), node v as provider: every live copy of every consumer
+  for (int q = A.out_ptr[v], q1 = A.out_ptr[v + 1]; q < q1; ++q) {
+    const uint32_t* const pw = L.packed + A.out_idx[q] * C;
+    for (int jw = 0; jw < C; ++jw) {
+      const uint32_t x = pw[jw] & 0xFFFFu;
+      if (x == 0xFFFFu) continue;
+      bool cov = false;
+      for (int j = 0; j < C; ++j) cov = cov || covers1(copy_of_v(j), x);
+      count += cov ? 0 : 1;
+    }
+  }
+  sc.violations = fixed + count;
+  // Eq. (4): positions gained (sign +1) or lost (sign -1)
+  int lo, hi;
+  bool gain;
+  if (!live_new) { lo = s; hi = e; gain = false; }
+  else if (field == 0) { lo = min(s, s2); hi = max(s, s2) - 1; gain = s2 < s; }
+  else { lo = min(e, e2) + 1; hi = max(e, e2); gain = e2 > e; }
+  int top = 0;
+  for (int j = 0; j < R; ++j) top = max(top, L.profile[min(lo + j, hi)]);
+  const int inside = top + (gain ? sz : -sz);
+  const int outside = max(lo > 0 ? L.pmax[lo - 1] : 0, hi + 1 < T ? L.smax[hi + 1] : 0);
+  sc.peak = max(max(inside, 0), outside);
+}
+
 struct Best {
   int viol, peak, move;   // move < 0: none
 };
@@ -204,7 +272,7 @@ __device__ __forceinline__ bool better(const Best& a, const Best& b, int64_t bud
   return a.move < b.move;
 }
 
-template <bool ADJ_LDS>
+template <bool ADJ_LDS, int CT>
 __global__ __launch_bounds__(kNT) void neighbours_kernel(GraphView g, int64_t B, const int32_t* __restrict__ starts,
                                                          const int32_t* __restrict__ ends,
                                                          const uint8_t* __restrict__ active, int R,
@@ -216,13 +284,23 @@ __global__ __launch_bounds__(kNT) void neighbours_kernel(GraphView g, int64_t B,
   L.pmax = L.profile + lay.T_pad;
   L.smax = L.pmax + lay.T_pad;
   L.packed = reinterpret_cast<uint32_t*>(L.smax + lay.T_pad);
-  L.fold = reinterpret_cast<int32_t*>(L.packed + lay.T_pad);
-  L.occ1 = reinterpret_cast<uint32_t*>(L.fold + lay.T_pad);
+  L.fold = reinterpret_cast<uint16_t*>(L.packed + lay.T_pad);
+  L.list = L.fold + 1;
+  L.occ1 = reinterpret_cast<uint32_t*>(L.fold + 2 * lay.T_pad);
   L.occ2 = L.occ1 + lay.bit_words;
   L.scratch = reinterpret_cast<int32_t*>(L.occ2 + lay.bit_words);
-  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
-  const int T = g.T, C = g.C;
-  const int moves_per_cand = T * 4 * R;
+  const int tid = threadIdx.x, lane = tid & (kWave - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+  const int T = g.T, C = CT ? CT : g.C;
+  const uint32_t c_magic = 0xFFFFFFFFu / (uint32_t)C + 1u;   // k / C = umulhi(k, c_magic) for C > 1, k < 2^16
+  const int two_r = 2 * R, four_r = 4 * R;
+  const int moves_per_cand = T * four_r;
+  // lane -> move: a wave scores 64 / 4R copies at a time (4R <= 64), or one copy in two pieces
+  const int per_wave = four_r <= kWave ? kWave / four_r : 1;
+  const int pieces = four_r <= kWave ? 1 : 2;
+  const int sub = four_r <= kWave ? lane / four_r : 0;
+  const int rem = four_r <= kWave ? lane - sub * four_r : lane;
+  int32_t* const counts = L.scratch + 8 * kNW;   // [0] base violations, [1] active copies, [2] inactive copies
   Adj A{g.in_ptr, g.in_idx, g.out_ptr, g.out_idx};
   if constexpr (ADJ_LDS) {   // the adjacency lists are read by every move: keep them in LDS
     int32_t* a = reinterpret_cast<int32_t*>(nb_raw) + lay.adj_off;
@@ -237,14 +315,14 @@ __global__ __launch_bounds__(kNT) void neighbours_kernel(GraphView g, int64_t B,
     // ---- base candidate: stage copies, scatter deltas, mark starts
     for (int t = tid; t < T; t += kNT) L.profile[t] = 0;
     for (int w = tid; w < 2 * lay.bit_words; w += kNT) L.occ1[w] = 0;
-    if (tid < 4) L.scratch[8 * kNW + tid] = 0;
+    if (tid < 4) counts[tid] = 0;
     __syncthreads();
     int viol = 0, nlive = 0;
     for (int k = tid; k < T; k += kNT) {
       const int s = starts[row + k], e = ends[row + k];
       const bool act = active[row + k] != 0;
       const bool live = act && (uint32_t)s <= (uint32_t)e && (uint32_t)e < (uint32_t)T;
-      const int v = k / C;
+      const int v = C == 1 ? k : (int)__umulhi((uint32_t)k, c_magic);
       L.packed[k] = pack_copy(live, s, e);
       if (k == v * C && !act) ++viol;   // Eq. (7)
       if (live) {
@@ -262,216 +340,98 @@ __global__ __launch_bounds__(kNT) void neighbours_kernel(GraphView g, int64_t B,
     block_scan<MaxOp, false>(L.profile, L.pmax, T, L.scratch, tid);
     block_scan<MaxOp, true>(L.profile, L.smax, T, L.scratch, tid);
 
-    // ---- pass 1: f(old copy) per copy; base violation count
-    for (int k = tid; k < T; k += kNT) {
-      const int v = k / C, i = k - v * C;
-      const int s = starts[row + k], e = ends[row + k];
-      const bool act = active[row + k] != 0;
-      const bool live = live_of(L.packed[k]);
-      L.fold[k] = act ? node_part(A, C, L.packed, v, i, act, live, s, e) : 0;
-      // base count: each instance once -- form, the order pair that copy k opens, its inputs
-      viol += (act && !live) ? 1 : 0;
-      if (live) {
-        for (int j = i + 1; j < C; ++j) {
-          const uint32_t p = L.packed[v * C + j];
-          if (live_of(p)) {
-            viol += e > (int)(p & 0xFFFFu) ? 1 : 0;
-            break;
+    // ---- pass 1: f(old copy) per copy; base violation count; the lists of active copies
+    // (from the front of `list`) and of inactive ones (from the back)
+    for (int k0 = wave * kWave; k0 < T; k0 += kNT) {
+      const int k = k0 + lane;
+      bool act = false;
+      if (k < T) {
+        const int v = C == 1 ? k : (int)__umulhi((uint32_t)k, c_magic), i = k - v * C;
+        const int s = starts[row + k], e = ends[row + k];
+        act = active[row + k] != 0;
+        const bool live = live_of(L.packed[k]);
+        L.fold[2 * k] = (uint16_t)(act ? node_part(A, C, L.packed, v, i, act, live, s, e) : 0);
+        // base count: each instance once -- form, the order pair that copy k opens, its inputs
+        viol += (act && !live) ? 1 : 0;
+        if (live) {
+          for (int j = i + 1; j < C; ++j) {
+            const uint32_t p = L.packed[v * C + j];
+            if (live_of(p)) {
+              viol += e > (int)(p & 0xFFFFu) ? 1 : 0;
+              break;
+            }
           }
-        }
-        for (int q = A.in_ptr[v]; q < A.in_ptr[v + 1]; ++q) {
-          const int u = A.in_idx[q];
-          bool cov = false;
-          for (int j = 0; j < C; ++j) cov = cov || covers1(L.packed[u * C + j], (uint32_t)s);
-          viol += cov ? 0 : 1;
-        }
-      }
-    }
-    int distinct = 0;
-    for (int w = tid; w < lay.bit_words; w += kNT) distinct += __popc(L.occ1[w]);
-    atomicAdd(&L.scratch[8 * kNW], viol + nlive - distinct);   // Eq. (6): live copies - distinct starts
-    __syncthreads();
-    const int base_viol = L.scratch[8 * kNW];
-    const int base_peak = L.pmax[T - 1];
-
-    // ---- pass 2: one lane per (copy, field); it scores the 2R displacements of that field.
-    // A wave takes 64 consecutive nodes, one copy index and one field at a time: the field and
-    // the copy index are the same in all its lanes, and a copy index that is rarely active
-    // costs the wave next to nothing.
-    Best best{0, 0, -1};
-    const int two_r = 2 * R;
-    const int node_blocks = (g.n + kWave - 1) / kWave;
-    for (int blk = wave; blk < node_blocks * C * 2; blk += kNW) {
-      const int field = blk & 1, i = (blk >> 1) % C, v = ((blk >> 1) / C) * kWave + lane;
-      if (v >= g.n) continue;
-      const int k = v * C + i, pf = 2 * k + field;
-      const int s = starts[row + k], e = ends[row + k];
-      const bool act = active[row + k] != 0;
-      const uint32_t mine = L.packed[k];
-      const int sz = g.size_dur[v].x;
-      moc_move_score* const dst = out_moves ? out_moves + (b * (int64_t)moves_per_cand + (int64_t)pf * two_r) : nullptr;
-      if (!act || !live_of(mine)) {
-        // not applicable, or a copy that is ill-formed now (rare): move by move
-        for (int d = 0; d < two_r; ++d) {
-          const int delta = d < R ? d - R : d - R + 1;
-          const int moved = (field == 0 ? s : e) + delta;
-          moc_move_score sc{-1, -1};
-          if (act && moved >= 0 && moved < T) {
-            score_move(A, C, sz, L, T, v, i, field, s, e, moved, base_viol, base_peak, sc);
-            const Best cand{sc.violations, sc.peak, pf * two_r + d};
-            if (better(cand, best, g.budget)) best = cand;
-          }
-          if (dst) dst[d] = sc;
-        }
-        continue;
-      }
-      // ---- copy k is live: what does not depend on the displacement
-      // Eq. (3): the live neighbours of copy i among the copies of v, and the violations
-      // between other consecutive live copies
-      int prev_end = -1, next_start = 0x7FFFFFFF, order_others = 0;
-      {
-        int pe = -1;
-        bool have = false;
-        for (int j = 0; j < i; ++j) {
-          const uint32_t p = L.packed[v * C + j];
-          if (!live_of(p)) continue;
-          if (have && pe > (int)(p & 0xFFFFu)) ++order_others;
-          pe = (int)(p >> 16);
-          have = true;
-        }
-        if (have) prev_end = pe;
-        have = false;
-        for (int j = i + 1; j < C; ++j) {
-          const uint32_t p = L.packed[v * C + j];
-          if (!live_of(p)) continue;
-          if (!have) next_start = (int)(p & 0xFFFFu);
-          else if (pe > (int)(p & 0xFFFFu)) ++order_others;
-          pe = (int)(p >> 16);
-          have = true;
-        }
-      }
-      const int order_without = (prev_end >= 0 && next_start != 0x7FFFFFFF && prev_end > next_start) ? 1 : 0;
-      const int start_twice = bit_at(L.occ2, s) ? 1 : 0;
-      const int fixed = base_viol - L.fold[k] + order_others - start_twice;
-      const int in_lo = A.in_ptr[v], in_hi = A.in_ptr[v + 1], out_lo = A.out_ptr[v], out_hi = A.out_ptr[v + 1];
-      int lost_all = -1;   // peak inside [s, e] without this copy: computed when first needed
-      for (int d0 = 0; d0 < two_r; d0 += kDisp) {
-        int vv[kDisp], pk[kDisp];
-        // ---- violations
-#pragma unroll
-        for (int dd = 0; dd < kDisp; ++dd) {
-          const int d = d0 + dd, delta = d < R ? d - R : d - R + 1;
-          const int s2 = field == 0 ? s + delta : s, e2 = field == 0 ? e : e + delta;
-          const bool live_new = s2 >= 0 && s2 <= e2 && e2 < T;
-          int c = fixed;
-          if (live_new) {
-            c += (prev_end > s2 ? 1 : 0) + (e2 > next_start ? 1 : 0);                  // Eq. (3) around the moved copy
-            c += s2 == s ? start_twice : (bit_at(L.occ1, s2) ? 1 : 0);               // Eq. (6)
-          } else {
-            c += 1 + order_without;                                                   // Eq. (2)/(8); Eq. (3) across the gap
-          }
-          vv[dd] = c;
-        }
-        // Eq. (5), the copy as consumer: every in-edge whose provider does not cover the start
-        if (field == 1) {
-          int uncovered = 0;
-          for (int q = in_lo; q < in_hi; ++q) {
+          for (int q = A.in_ptr[v]; q < A.in_ptr[v + 1]; ++q) {
             const int u = A.in_idx[q];
             bool cov = false;
             for (int j = 0; j < C; ++j) cov = cov || covers1(L.packed[u * C + j], (uint32_t)s);
-            uncovered += cov ? 0 : 1;
+            viol += cov ? 0 : 1;
           }
-#pragma unroll
-          for (int dd = 0; dd < kDisp; ++dd) {
-            const int d = d0 + dd, delta = d < R ? d - R : d - R + 1;
-            const int e2 = e + delta;
-            vv[dd] += (s <= e2 && e2 < T) ? uncovered : 0;
-          }
-        } else {
-          for (int q = in_lo; q < in_hi; ++q) {
-            const int u = A.in_idx[q];
-            uint32_t covered = 0;   // bit dd: some copy of u covers the start moved by displacement dd
-            for (int j = 0; j < C; ++j) {
-              const uint32_t pu = L.packed[u * C + j];
-#pragma unroll
-              for (int dd = 0; dd < kDisp; ++dd) {
-                const int d = d0 + dd, delta = d < R ? d - R : d - R + 1;
-                const int s2 = s + delta;
-                covered |= (s2 >= 0 && covers1(pu, (uint32_t)s2)) ? 1u << dd : 0u;
-              }
-            }
-#pragma unroll
-            for (int dd = 0; dd < kDisp; ++dd) {
-              const int d = d0 + dd, delta = d < R ? d - R : d - R + 1;
-              const int s2 = s + delta;
-              vv[dd] += (s2 >= 0 && s2 <= e && !(covered >> dd & 1u)) ? 1 : 0;
-            }
-          }
-        }
-        // Eq. (5), node v as provider: every live copy of every consumer
-        for (int q = out_lo; q < out_hi; ++q) {
-          const int w = A.out_idx[q];
-          for (int jw = 0; jw < C; ++jw) {
-            const uint32_t pw = L.packed[w * C + jw];
-            if (!live_of(pw)) continue;
-            const uint32_t x = pw & 0xFFFFu;
-            bool cov_other = false;
-            for (int j = 0; j < C; ++j) cov_other = cov_other || (j != i && covers1(L.packed[v * C + j], x));
-            if (cov_other) continue;
-#pragma unroll
-            for (int dd = 0; dd < kDisp; ++dd) {
-              const int d = d0 + dd, delta = d < R ? d - R : d - R + 1;
-              const int s2 = field == 0 ? s + delta : s, e2 = field == 0 ? e : e + delta;
-              const bool live_new = s2 >= 0 && s2 <= e2 && e2 < T;
-              vv[dd] += (live_new && s2 < (int)x && (int)x <= e2) ? 0 : 1;
-            }
-          }
-        }
-        // ---- peak: the profile changes on the positions between the old and the new value of the field
-#pragma unroll
-        for (int dd = 0; dd < kDisp; ++dd) {
-          const int d = d0 + dd, delta = d < R ? d - R : d - R + 1;
-          const int s2 = field == 0 ? s + delta : s, e2 = field == 0 ? e : e + delta;
-          const bool in_dom = (field == 0 ? s2 : e2) >= 0 && (field == 0 ? s2 : e2) < T;
-          const bool live_new = s2 >= 0 && s2 <= e2 && e2 < T;
-          int p = base_peak;
-          if (in_dom) {
-            if (live_new) {
-              int lo, hi, sign;
-              if (field == 0) { lo = min(s, s2); hi = max(s, s2) - 1; sign = s2 < s ? 1 : -1; }
-              else { lo = min(e, e2) + 1; hi = max(e, e2); sign = e2 > e ? 1 : -1; }
-              int inside = 0;
-              for (int t = lo; t <= hi; ++t) inside = max(inside, L.profile[t] + sign * sz);
-              p = max(inside, max(lo > 0 ? L.pmax[lo - 1] : 0, hi + 1 < T ? L.smax[hi + 1] : 0));
-            } else {
-              if (lost_all < 0) {
-                lost_all = 0;
-                for (int t = s; t <= e; ++t) lost_all = max(lost_all, L.profile[t] - sz);
-              }
-              p = max(lost_all, max(s > 0 ? L.pmax[s - 1] : 0, e + 1 < T ? L.smax[e + 1] : 0));
-            }
-          }
-          pk[dd] = p;
-        }
-        // ---- results of this group of displacements
-#pragma unroll
-        for (int dd = 0; dd < kDisp; ++dd) {
-          const int d = d0 + dd;
-          if (d >= two_r) continue;
-          const int delta = d < R ? d - R : d - R + 1;
-          const int moved = (field == 0 ? s : e) + delta;
-          moc_move_score sc{-1, -1};
-          if (moved >= 0 && moved < T) {
-            sc.violations = vv[dd];
-            sc.peak = pk[dd];
-            const Best cand{vv[dd], pk[dd], pf * two_r + d};
-            if (better(cand, best, g.budget)) best = cand;
-          }
-          if (dst) dst[d] = sc;
         }
       }
+      const uint64_t am = __ballot(act), im = __ballot(k < T && !act);
+      int abase = 0, ibase = 0;
+      if (lane == 0) {
+        abase = atomicAdd(&counts[1], __popcll(am));
+        ibase = atomicAdd(&counts[2], __popcll(im));
+      }
+      abase = __shfl(abase, 0);
+      ibase = __shfl(ibase, 0);
+      const uint64_t below = ((uint64_t)1 << lane) - 1;
+      if (act) L.list[2 * (abase + __popcll(am & below))] = (uint16_t)k;
+      else if (k < T) L.list[2 * (T - 1 - ibase - __popcll(im & below))] = (uint16_t)k;
     }
+    int distinct = 0;
+    for (int w = tid; w < lay.bit_words; w += kNT) distinct += __popc(L.occ1[w]);
+    atomicAdd(&counts[0], viol + nlive - distinct);   // Eq. (6): live copies - distinct starts
+    __syncthreads();
+    const int base_viol = counts[0], n_active = counts[1];
+    const int base_peak = L.pmax[T - 1];
 
+    // ---- pass 2: one lane per move of an active copy
+    Best best{0, 0, -1};
+    const int groups = (n_active + per_wave - 1) / per_wave;
+    for (int it = wave; it < groups * pieces; it += kNW) {
+      const int grp = pieces == 1 ? it : it >> 1;
+      const int in_copy = pieces == 1 ? rem : rem + (it & 1) * kWave;   // field * 2R + d
+      const int entry = grp * per_wave + sub;
+      if (sub >= per_wave || entry >= n_active || in_copy >= four_r) continue;
+      const int k = L.list[2 * entry];
+      const int v = C == 1 ? k : (int)__umulhi((uint32_t)k, c_magic), i = k - v * C;
+      const int field = in_copy >= two_r ? 1 : 0, d = in_copy - field * two_r;
+      const int delta = d < R ? d - R : d - R + 1;
+      const int q = k * four_r + in_copy;
+      const uint32_t mine = L.packed[k];
+      const int sz = g.size_dur[v].x;
+      moc_move_score sc{-1, -1};
+      if (live_of(mine)) {
+        const int moved = (int)(field == 0 ? mine & 0xFFFFu : mine >> 16) + delta;
+        if (moved >= 0 && moved < T)
+          score_live<CT>(A, C, sz, L, T, R, v, i, field, moved, mine, base_viol - (int)L.fold[2 * k], sc);
+      } else {   // active and ill formed (rare): from scratch
+        const int s = starts[row + k], e = ends[row + k];
+        const int moved = (field == 0 ? s : e) + delta;
+        if (moved >= 0 && moved < T) score_move(A, C, sz, L, T, v, i, field, s, e, moved, base_viol, base_peak, sc);
+      }
+      if (sc.violations >= 0) {
+        const Best cand{sc.violations, sc.peak, q};
+        if (better(cand, best, g.budget)) best = cand;
+      }
+      if (out_moves) out_moves[b * (int64_t)moves_per_cand + q] = sc;
+    }
+    // ---- the moves of inactive copies are not applicable
+    if (out_moves) {
+      const int n_inactive = T - n_active;
+      const int fill_groups = (n_inactive + per_wave - 1) / per_wave;
+      for (int it = wave; it < fill_groups * pieces; it += kNW) {
+        const int grp = pieces == 1 ? it : it >> 1;
+        const int in_copy = pieces == 1 ? rem : rem + (it & 1) * kWave;
+        const int entry = grp * per_wave + sub;
+        if (sub >= per_wave || entry >= n_inactive || in_copy >= four_r) continue;
+        const int k = L.list[2 * (n_active + entry)];
+        out_moves[b * (int64_t)moves_per_cand + k * four_r + in_copy] = moc_move_score{-1, -1};
+      }
+    }
     // ---- best move of the candidate
     if (out_best) {
 #pragma unroll
@@ -505,6 +465,23 @@ __global__ __launch_bounds__(kNT) void neighbours_kernel(GraphView g, int64_t B,
   }
 }
 
+
+using NbKernel = void (*)(GraphView, int64_t, const int32_t*, const int32_t*, const uint8_t*, int, moc_move_score*,
+                          moc_best_move*, NbLayout);
+
+template <bool ADJ_LDS>
+NbKernel pick_copies(int C) {
+  switch (C) {
+    case 1: return neighbours_kernel<ADJ_LDS, 1>;
+    case 2: return neighbours_kernel<ADJ_LDS, 2>;
+    case 3: return neighbours_kernel<ADJ_LDS, 3>;
+    case 4: return neighbours_kernel<ADJ_LDS, 4>;
+    default: return neighbours_kernel<ADJ_LDS, 0>;   // C read at run time
+  }
+}
+
+NbKernel pick_kernel(bool adj_lds, int C) { return adj_lds ? pick_copies<true>(C) : pick_copies<false>(C); }
+
 }  // namespace
 
 extern "C" int moc_eval_neighbours(const moc_graph* g, int64_t B, const int32_t* starts, const int32_t* ends,
@@ -523,7 +500,7 @@ extern "C" int moc_eval_neighbours(const moc_graph* g, int64_t B, const int32_t*
   const NbLayout lay = nb_layout(g->view.T, g->view.n, g->view.m, g->max_lds);
   if (lay.bytes > g->max_lds) return MOC_EOVERFLOW;
   if ((int64_t)g->view.T * 4 * R > 0x7FFFFFFF) return MOC_EOVERFLOW;
-  auto kern = lay.adj_off ? neighbours_kernel<true> : neighbours_kernel<false>;
+  auto kern = pick_kernel(lay.adj_off != 0, g->view.C);
   MOC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                               lay.bytes));
   int per_cu = 0;

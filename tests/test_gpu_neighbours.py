@@ -43,7 +43,8 @@ def random_candidates(rng, B, K, T, wild):
 
 
 @pytest.mark.parametrize("n,C,R", [(1, 1, 1), (2, 2, 2), (5, 1, 3), (9, 2, 8), (12, 3, 4), (17, 2, 8), (30, 4, 2),
-                                   (40, 3, 8), (64, 2, 5)])
+                                   (40, 3, 8), (64, 2, 5), (20, 2, 17), (10, 1, 32), (24, 5, 8), (70, 1, 16),
+                                   (33, 4, 9)])
 def test_neighbours_full_table_small_graphs(moc, n, C, R):
     from paper_2304_14463_amd.inputs import graph_from_edges
     rng = np.random.default_rng(1000 * n + 10 * C + R)
