@@ -48,9 +48,10 @@ NbLayout nb_layout(int T, int n, int m, int max_lds) {
   const int words = 5 * l.T_pad + 2 * l.bit_words + 8 * kNW + 16;
   l.adj_off = 0;
   l.bytes = 4 * words;
-  // the CSR lists both ways, if there is room: every move walks the edges of its node
+  // the CSR lists both ways, if that costs no resident workgroup (two of 16 waves fit a CU):
+  // every move walks the edges of its node
   const int with_adj = 4 * (words + 2 * (n + 1) + 2 * m);
-  if (with_adj <= max_lds) {
+  if (with_adj <= max_lds && std::min(max_lds / with_adj, 2) >= std::min(max_lds / l.bytes, 2)) {
     l.adj_off = words;
     l.bytes = with_adj;
   }
@@ -196,7 +197,8 @@ __device__ __forceinline__ void score_move(const Adj& g, int C, int sz, const Nb
 // by at most R, and when it leaves the copy ill formed the copy was shorter than that.
 template <int CT>
 __device__ __forceinline__ void score_live(const Adj& A, int C, int sz, const NbLds& L, int T, int R, int v, int i,
-                                           int field, int moved, uint32_t mine, int fixed, moc_move_score& sc) {
+                                           int field, int moved, uint32_t mine, int fixed, int in_lo, int in_hi,
+                                           int out_lo, int out_hi,                                            moc_move_score& sc) {
   const int s = (int)(mine & 0xFFFFu), e = (int)(mine >> 16);
   const int s2 = field == 0 ? moved : s, e2 = field == 0 ? e : moved;
   const bool live_new = s2 <= e2;
@@ -223,24 +225,22 @@ __device__ __forceinline__ void score_live(const Adj& A, int C, int sz, const Nb
   // Eq. (6): the old start leaves, the new one arrives
   const int start_twice = bit_at(L.occ2, s) ? 1 : 0;
   count -= start_twice;
-  if (live_new) {
-    count += s2 == s ? start_twice : (bit_at(L.occ1, s2) ? 1 : 0);
-    // Eq. (5), the copy as consumer: in-edges whose provider does not cover the start
-    for (int q = A.in_ptr[v], q1 = A.in_ptr[v + 1]; q < q1; ++q) {
-      const uint32_t* const pu = L.packed + A.in_idx[q] * C;
-      bool cov = false;
-      for (int j = 0; j < C; ++j) cov = cov || covers1(pu[j], (uint32_t)s2);
-      count += cov ? 0 : 1;
-    }
+  if (live_new) count += s2 == s ? start_twice : (bit_at(L.occ1, s2) ? 1 : 0);
+  // Eq. (5), the copy as consumer: in-edges whose provider does not cover the start
+  for (int q = in_lo, q1 = live_new ? in_hi : in_lo; q < q1; ++q) {
+    const uint32_t* const pu = L.packed + A.in_idx[q] * C;
+    bool cov = false;
+    for (int j = 0; j < C; ++j) cov = cov || covers1(pu[j], (uint32_t)s2);
+    count += cov ? 0 : 1;
   }
   // Eq. (5), node v as provider: every live copy of every consumer
-  for (int q = A.out_ptr[v], q1 = A.out_ptr[v + 1]; q < q1; ++q) {
+  for (int q = out_lo; q < out_hi; ++q) {
     const uint32_t* const pw = L.packed + A.out_idx[q] * C;
     for (int jw = 0; jw < C; ++jw) {
-      const uint32_t x = pw[jw] & 0xFFFFu;
-      if (x == 0xFFFFu) continue;
+      const uint32_t pos = pw[jw] & 0xFFFFu;
+      if (pos == 0xFFFFu) continue;
       bool cov = false;
-      for (int j = 0; j < C; ++j) cov = cov || covers1(copy_of_v(j), x);
+      for (int j = 0; j < C; ++j) cov = cov || covers1(copy_of_v(j), pos);
       count += cov ? 0 : 1;
     }
   }
@@ -252,7 +252,12 @@ __device__ __forceinline__ void score_live(const Adj& A, int C, int sz, const Nb
   else if (field == 0) { lo = min(s, s2); hi = max(s, s2) - 1; gain = s2 < s; }
   else { lo = min(e, e2) + 1; hi = max(e, e2); gain = e2 > e; }
   int top = 0;
-  for (int j = 0; j < R; ++j) top = max(top, L.profile[min(lo + j, hi)]);
+  for (int j0 = 0; j0 < R; j0 += 4) {
+    int p[4];
+#pragma unroll
+    for (int x = 0; x < 4; ++x) p[x] = L.profile[min(lo + j0 + x, hi)];
+    top = max(max(top, p[0]), max(max(p[1], p[2]), p[3]));
+  }
   const int inside = top + (gain ? sz : -sz);
   const int outside = max(lo > 0 ? L.pmax[lo - 1] : 0, hi + 1 < T ? L.smax[hi + 1] : 0);
   sc.peak = max(max(inside, 0), outside);
@@ -273,7 +278,7 @@ __device__ __forceinline__ bool better(const Best& a, const Best& b, int64_t bud
 }
 
 template <bool ADJ_LDS, int CT>
-__global__ __launch_bounds__(kNT) void neighbours_kernel(GraphView g, int64_t B, const int32_t* __restrict__ starts,
+__global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) void neighbours_kernel(GraphView g, int64_t B, const int32_t* __restrict__ starts,
                                                          const int32_t* __restrict__ ends,
                                                          const uint8_t* __restrict__ active, int R,
                                                          moc_move_score* __restrict__ out_moves,
@@ -403,11 +408,13 @@ __global__ __launch_bounds__(kNT) void neighbours_kernel(GraphView g, int64_t B,
       const int q = k * four_r + in_copy;
       const uint32_t mine = L.packed[k];
       const int sz = g.size_dur[v].x;
+      const int in_lo = A.in_ptr[v], in_hi = A.in_ptr[v + 1], out_lo = A.out_ptr[v], out_hi = A.out_ptr[v + 1];
       moc_move_score sc{-1, -1};
       if (live_of(mine)) {
         const int moved = (int)(field == 0 ? mine & 0xFFFFu : mine >> 16) + delta;
         if (moved >= 0 && moved < T)
-          score_live<CT>(A, C, sz, L, T, R, v, i, field, moved, mine, base_viol - (int)L.fold[2 * k], sc);
+          score_live<CT>(A, C, sz, L, T, R, v, i, field, moved, mine, base_viol - (int)L.fold[2 * k], in_lo, in_hi,
+                         out_lo, out_hi, sc);
       } else {   // active and ill formed (rare): from scratch
         const int s = starts[row + k], e = ends[row + k];
         const int moved = (field == 0 ? s : e) + delta;
