@@ -45,7 +45,7 @@ NbLayout nb_layout(int T, int n, int m, int max_lds) {
   l.T_pad = (T + 3) & ~3;
   l.bit_words = (T + 31) / 32;
   // profile, prefix max, suffix max, packed, f(old) + two bitmaps + scratch
-  const int words = 5 * l.T_pad + 2 * l.bit_words + 8 * kNW + 16;
+  const int words = 5 * l.T_pad + 8 + 2 * l.bit_words + 8 * kNW + 16;
   l.adj_off = 0;
   l.bytes = 4 * words;
   // the CSR lists both ways, if that costs no resident workgroup (two of 16 waves fit a CU):
@@ -191,93 +191,204 @@ __device__ __forceinline__ void score_move(const Adj& g, int C, int sz, const Nb
 }
 
 
-// One move of a live copy (v, i): field moved to `moved`, a position in [0, T).
-// `mine` is the copy before the move, `fixed` the base violation count without
-// f(old copy).  The changed positions of the profile are at most R: the move is
-// by at most R, and when it leaves the copy ill formed the copy was shorter than that.
-template <int CT>
-__device__ __forceinline__ void score_live(const Adj& A, int C, int sz, const NbLds& L, int T, int R, int v, int i,
-                                           int field, int moved, uint32_t mine, int fixed, int in_lo, int in_hi,
-                                           int out_lo, int out_hi,                                            moc_move_score& sc) {
-  const int s = (int)(mine & 0xFFFFu), e = (int)(mine >> 16);
-  const int s2 = field == 0 ? moved : s, e2 = field == 0 ? e : moved;
-  const bool live_new = s2 <= e2;
-  const uint32_t moved_copy = pack_copy(live_new, s2, e2);
-  const uint32_t* const row = L.packed + v * C;
-  uint32_t cv[CT > 0 ? CT : 1];   // the copies of v after the move
-  if constexpr (CT > 0) {
-#pragma unroll
-    for (int j = 0; j < CT; ++j) cv[j] = j == i ? moved_copy : row[j];
+// Sets of displacements as bit masks: bit d stands for the move with index d of one
+// (copy, field), d = 0..2R-1 for the displacements -R..-1, +1..+R.  32 bits serve R <= 15,
+// 64 bits any R this call accepts.
+template <bool WIDE>
+struct Bits;
+template <>
+struct Bits<false> {
+  using M = uint32_t;
+  static __device__ __forceinline__ M below(int x, int D) { return (1u << min(max(x, 0), D)) - 1u; }   // D <= 31
+  static __device__ __forceinline__ bool any(M m) { return __any(m != 0); }
+};
+template <>
+struct Bits<true> {
+  using M = uint64_t;
+  static __device__ __forceinline__ M below(int x, int D) {
+    const int c = min(x, D);
+    return c <= 0 ? 0 : ~(uint64_t)0 >> (64 - c);
   }
-  auto copy_of_v = [&](int j) -> uint32_t {
-    if constexpr (CT > 0) return cv[j];
-    else return j == i ? moved_copy : row[j];
-  };
-  int count = live_new ? 0 : 1;   // Eq. (2)/(8)
-  // Eq. (3): each live copy of v against the next live one
-  int prev_end = -1;
-  for (int j = 0; j < C; ++j) {
-    const uint32_t p = copy_of_v(j);
-    if (!live_of(p)) continue;
-    count += prev_end > (int)(p & 0xFFFFu) ? 1 : 0;
-    prev_end = (int)(p >> 16);
-  }
-  // Eq. (6): the old start leaves, the new one arrives
-  const int start_twice = bit_at(L.occ2, s) ? 1 : 0;
-  count -= start_twice;
-  if (live_new) count += s2 == s ? start_twice : (bit_at(L.occ1, s2) ? 1 : 0);
-  // Eq. (5), the copy as consumer: in-edges whose provider does not cover the start
-  for (int q = in_lo, q1 = live_new ? in_hi : in_lo; q < q1; ++q) {
-    const uint32_t* const pu = L.packed + A.in_idx[q] * C;
-    bool cov = false;
-    for (int j = 0; j < C; ++j) cov = cov || covers1(pu[j], (uint32_t)s2);
-    count += cov ? 0 : 1;
-  }
-  // Eq. (5), node v as provider: every live copy of every consumer
-  for (int q = out_lo; q < out_hi; ++q) {
-    const uint32_t* const pw = L.packed + A.out_idx[q] * C;
-    for (int jw = 0; jw < C; ++jw) {
-      const uint32_t pos = pw[jw] & 0xFFFFu;
-      if (pos == 0xFFFFu) continue;
-      bool cov = false;
-      for (int j = 0; j < C; ++j) cov = cov || covers1(copy_of_v(j), pos);
-      count += cov ? 0 : 1;
-    }
-  }
-  sc.violations = fixed + count;
-  // Eq. (4): positions gained (sign +1) or lost (sign -1)
-  int lo, hi;
-  bool gain;
-  if (!live_new) { lo = s; hi = e; gain = false; }
-  else if (field == 0) { lo = min(s, s2); hi = max(s, s2) - 1; gain = s2 < s; }
-  else { lo = min(e, e2) + 1; hi = max(e, e2); gain = e2 > e; }
-  int top = 0;
-  for (int j0 = 0; j0 < R; j0 += 4) {
-    int p[4];
-#pragma unroll
-    for (int x = 0; x < 4; ++x) p[x] = L.profile[min(lo + j0 + x, hi)];
-    top = max(max(top, p[0]), max(max(p[1], p[2]), p[3]));
-  }
-  const int inside = top + (gain ? sz : -sz);
-  const int outside = max(lo > 0 ? L.pmax[lo - 1] : 0, hi + 1 < T ? L.smax[hi + 1] : 0);
-  sc.peak = max(max(inside, 0), outside);
-}
+  static __device__ __forceinline__ bool any(M m) { return __any(m != 0); }
+};
+
+constexpr int kPlanes = 6;           // per-move counters of up to 63 as bit planes; beyond that the slow path
+constexpr int kNoCopy = 0x3FFFFFFF;  // start of a copy that does not exist
 
 struct Best {
   int viol, peak, move;   // move < 0: none
 };
 
-__device__ __forceinline__ bool better(const Best& a, const Best& b, int64_t budget) {
+// Order of the best move: (violations, max(peak, budget), peak, move index); `cap` is the
+// budget clamped to [0, 2^31 - 1], which orders peaks (never negative) the same way.
+__device__ __forceinline__ bool better(const Best& a, const Best& b, int cap) {
   if (a.move < 0) return false;
   if (b.move < 0) return true;
   if (a.viol != b.viol) return a.viol < b.viol;
-  const int64_t ma = max((int64_t)a.peak, budget), mb = max((int64_t)b.peak, budget);
+  const int ma = max(a.peak, cap), mb = max(b.peak, cap);
   if (ma != mb) return ma < mb;
   if (a.peak != b.peak) return a.peak < b.peak;
   return a.move < b.move;
 }
 
-template <bool ADJ_LDS, int CT>
+// All 2R moves of one field of a live copy (v, i), by one lane.  What a move adds to the
+// violation count is a sum of 0/1 terms, each true on an interval of the moved position:
+// the terms are built as masks over the displacements and summed in bit planes, then the
+// lane walks outwards from the old position, one step per displacement on either side,
+// keeping the maximum of the profile over the positions gained or lost so far.
+// `q0` is the index of the lane's first move, `fixed` the base count without f(old copy).
+// Returns false if a counter overflowed (the caller then scores the moves one by one).
+template <int CT, bool WIDE>
+__device__ __forceinline__ bool score_field(const Adj& A, int C, int sz, const NbLds& L, int T, int R, int v, int i,
+                                            int field, uint32_t mine, int fixed, int q0, int cap, bool want_best,
+                                            bool pairs, moc_move_score* __restrict__ dst, Best& best) {
+  using B = Bits<WIDE>;
+  using M = typename B::M;
+  const int D = 2 * R;
+  const int s = (int)(mine & 0xFFFFu), e = (int)(mine >> 16);
+  const int base = field == 0 ? s : e, first = base - R;
+  // {d : moved(d) < x}: the moved positions are first..base-1, base+1..base+R
+  auto lt = [&](int x) -> M { return B::below(x - first - (x > base ? 1 : 0), D); };
+  const M in_dom = lt(T) & ~lt(0);
+  const M live = in_dom & (field == 0 ? lt(e + 1) : ~lt(s));   // start <= end after the move
+  // Eq. (3): the live neighbours of copy i among the copies of v, and the violations
+  // between other consecutive live copies
+  const uint32_t* const row = L.packed + v * C;
+  int prev_end = -1, next_start = kNoCopy, order_others = 0;
+  {
+    int pe = -1;   // end of the last live copy on this side of copy i
+    for (int j = 0; j < C; ++j) {
+      if (j == i) { prev_end = pe; pe = -1; continue; }
+      const uint32_t p = row[j];
+      if (!live_of(p)) continue;
+      if (j > i && next_start == kNoCopy) next_start = (int)(p & 0xFFFFu);
+      order_others += pe > (int)(p & 0xFFFFu) ? 1 : 0;
+      pe = (int)(p >> 16);
+    }
+  }
+  const int start_twice = bit_at(L.occ2, s) ? 1 : 0;
+  const int if_dead = 1 + (prev_end > next_start ? 1 : 0);   // Eq. (2)/(8), Eq. (3) across the gap
+  int if_live;
+  fixed += order_others - start_twice;
+  M plane[kPlanes];
+#pragma unroll
+  for (int p = 0; p < kPlanes; ++p) plane[p] = 0;
+  M overflow = 0;
+  auto add = [&](M m) {
+    M carry = m;
+#pragma unroll
+    for (int p = 0; p < kPlanes; ++p) {
+      const M t = plane[p] & carry;
+      plane[p] ^= carry;
+      carry = t;
+      if (!B::any(carry)) break;
+    }
+    overflow |= carry;
+  };
+  const int in_lo = A.in_ptr[v], in_hi = A.in_ptr[v + 1];
+  if (field == 0) {
+    if_live = e > next_start ? 1 : 0;
+    add(live & lt(prev_end));   // Eq. (3): the previous copy ends after the new start
+    // Eq. (6): the new start is taken.  Bits of occ1 at first..base-1 and base+1..base+R
+    {
+      auto window = [&](int from) -> M {   // R bits of occ1 from position `from` (>= -R) on; positions below 0 read as 0
+        const int f0 = max(from, 0), w = min(f0 >> 5, (T - 1) >> 5), w1 = min(w + 1, (T - 1) >> 5);
+        const uint64_t two = (uint64_t)L.occ1[w] | ((uint64_t)(w1 > w ? L.occ1[w1] : 0u) << 32);
+        return (M)(((two >> (f0 & 31)) << (f0 - from)) & (((uint64_t)1 << R) - 1));
+      };
+      add(live & (window(first) | (window(base + 1) << R)));
+    }
+    // Eq. (5), the copy as consumer: in-edges whose provider does not cover the new start
+    for (int q = in_lo; q < in_hi; ++q) {
+      const uint32_t* const pu = L.packed + A.in_idx[q] * C;
+      M cov = 0;
+      for (int j = 0; j < C; ++j) {
+        const uint32_t p = pu[j];
+        cov |= lt((int)(p >> 16) + 1) & ~lt((int)(p & 0xFFFFu) + 1);   // start < moved <= end; empty for a dead copy
+      }
+      add(live & ~cov);
+    }
+  } else {
+    add(live & ~lt(next_start + 1));   // Eq. (3): the new end lies after the next copy's start
+    int uncovered = 0;                 // Eq. (5), the copy as consumer: the start stays
+    for (int q = in_lo; q < in_hi; ++q) {
+      const uint32_t* const pu = L.packed + A.in_idx[q] * C;
+      bool cov = false;
+      for (int j = 0; j < C; ++j) cov = cov || covers1(pu[j], (uint32_t)s);
+      uncovered += cov ? 0 : 1;
+    }
+    if_live = (prev_end > s ? 1 : 0) + start_twice + uncovered;
+  }
+  // Eq. (5), node v as provider: every live copy of every consumer that no other copy of v covers
+  for (int q = A.out_ptr[v], q1 = A.out_ptr[v + 1]; q < q1; ++q) {
+    const uint32_t* const pw = L.packed + A.out_idx[q] * C;
+    for (int jw = 0; jw < C; ++jw) {
+      const int x = (int)(pw[jw] & 0xFFFFu);
+      if (x == 0xFFFF) continue;
+      bool cov = false;
+      for (int j = 0; j < C; ++j) cov = cov || (j != i && covers1(row[j], (uint32_t)x));
+      if (cov) continue;
+      // the moved copy covers x: start < x <= end
+      const M mine_covers = field == 0 ? (x <= e ? live & lt(x) : (M)0) : (s < x ? live & ~lt(x) : (M)0);
+      add(in_dom & ~mine_covers);
+    }
+  }
+  if (B::any(overflow)) return false;
+  // ---- outwards from the old position: step j scores the displacements -j and +j
+  int top_down = 0, top_up = 0;   // maximum of the profile over the positions changed so far, either side
+  const int sz_down = field == 0 ? sz : -sz, sz_up = field == 0 ? -sz : sz;   // a start moved down gains positions, ...
+  auto step = [&](int j, int side) -> moc_move_score {   // side 0: displacement -j, side 1: +j
+    const int d = side == 0 ? R - j : R + j - 1;
+    const int moved = side == 0 ? base - j : base + j;
+    // the position that joins the changed window with this step, and the window [lo, hi]
+    int far, lo, hi;
+    bool joins;
+    if (field == 0) {
+      if (side == 0) { far = s - j; lo = far; hi = s - 1; joins = true; }
+      else { far = s + j - 1; lo = s; hi = min(far, e); joins = far <= e; }
+    } else {
+      if (side == 1) { far = e + j; lo = e + 1; hi = far; joins = true; }
+      else { far = e - j + 1; lo = max(far, s); hi = e; joins = far >= s; }
+    }
+    const int at = L.profile[min(max(far, 0), T - 1)];
+    int& top = side == 0 ? top_down : top_up;
+    top = joins ? max(top, at) : top;
+    moc_move_score sc{-1, -1};
+    if (moved >= 0 && moved < T) {
+      int count = 0;
+#pragma unroll
+      for (int p = 0; p < kPlanes; ++p) count |= (int)((plane[p] >> d) & 1) << p;
+      sc.violations = fixed + count + ((live >> d) & 1 ? if_live : if_dead);
+      const int outside = max(L.pmax[lo - 1], L.smax[hi + 1]);
+      sc.peak = max(max(top + (side == 0 ? sz_down : sz_up), 0), outside);
+      if (want_best) {
+        const Best cand{sc.violations, sc.peak, q0 + d};
+        if (better(cand, best, cap)) best = cand;
+      }
+    }
+    return sc;
+  };
+  if (pairs) {   // R even, dst 16-byte aligned: two scores per store
+    for (int j = 1; j < R; j += 2) {
+      const moc_move_score a0 = step(j, 0), b0 = step(j, 1), a1 = step(j + 1, 0), b1 = step(j + 1, 1);
+      if (dst) {
+        *reinterpret_cast<int4*>(dst + (R - j - 1)) = make_int4(a1.violations, a1.peak, a0.violations, a0.peak);
+        *reinterpret_cast<int4*>(dst + (R + j - 1)) = make_int4(b0.violations, b0.peak, b1.violations, b1.peak);
+      }
+    }
+  } else {
+    for (int j = 1; j <= R; ++j) {
+      const moc_move_score a0 = step(j, 0), b0 = step(j, 1);
+      if (dst) {
+        dst[R - j] = a0;
+        dst[R + j - 1] = b0;
+      }
+    }
+  }
+  return true;
+}
+
+template <bool ADJ_LDS, int CT, bool WIDE>
 __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) void neighbours_kernel(GraphView g, int64_t B, const int32_t* __restrict__ starts,
                                                          const int32_t* __restrict__ ends,
                                                          const uint8_t* __restrict__ active, int R,
@@ -286,9 +397,9 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
   extern __shared__ uint32_t nb_raw[];
   NbLds L;
   L.profile = reinterpret_cast<int32_t*>(nb_raw);
-  L.pmax = L.profile + lay.T_pad;
-  L.smax = L.pmax + lay.T_pad;
-  L.packed = reinterpret_cast<uint32_t*>(L.smax + lay.T_pad);
+  L.pmax = L.profile + lay.T_pad + 4;   // pmax[-1] = 0
+  L.smax = L.pmax + lay.T_pad;          // smax[T] = 0
+  L.packed = reinterpret_cast<uint32_t*>(L.smax + lay.T_pad + 4);
   L.fold = reinterpret_cast<uint16_t*>(L.packed + lay.T_pad);
   L.list = L.fold + 1;
   L.occ1 = reinterpret_cast<uint32_t*>(L.fold + 2 * lay.T_pad);
@@ -305,7 +416,9 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
   const int pieces = four_r <= kWave ? 1 : 2;
   const int sub = four_r <= kWave ? lane / four_r : 0;
   const int rem = four_r <= kWave ? lane - sub * four_r : lane;
-  int32_t* const counts = L.scratch + 8 * kNW;   // [0] base violations, [1] active copies, [2] inactive copies
+  int32_t* const counts = L.scratch + 8 * kNW;   // [0] base violations, [1] active copies, [2] inactive copies, [3] work drawn
+  const int cap = (int)min(max(g.budget, (int64_t)0), (int64_t)0x7FFFFFFF);
+  const bool pairs = (R & 1) == 0 && (reinterpret_cast<uintptr_t>(out_moves) & 15) == 0;   // scores stored two at a time
   Adj A{g.in_ptr, g.in_idx, g.out_ptr, g.out_idx};
   if constexpr (ADJ_LDS) {   // the adjacency lists are read by every move: keep them in LDS
     int32_t* a = reinterpret_cast<int32_t*>(nb_raw) + lay.adj_off;
@@ -321,6 +434,7 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
     for (int t = tid; t < T; t += kNT) L.profile[t] = 0;
     for (int w = tid; w < 2 * lay.bit_words; w += kNT) L.occ1[w] = 0;
     if (tid < 4) counts[tid] = 0;
+    if (tid == 0) { L.pmax[-1] = 0; L.smax[T] = 0; }
     __syncthreads();
     int viol = 0, nlive = 0;
     for (int k = tid; k < T; k += kNT) {
@@ -393,38 +507,41 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
     const int base_viol = counts[0], n_active = counts[1];
     const int base_peak = L.pmax[T - 1];
 
-    // ---- pass 2: one lane per move of an active copy
+    // ---- pass 2: one lane per (active copy, field), start moves first; the waves draw
+    // 64 of these at a time
     Best best{0, 0, -1};
-    const int groups = (n_active + per_wave - 1) / per_wave;
-    for (int it = wave; it < groups * pieces; it += kNW) {
-      const int grp = pieces == 1 ? it : it >> 1;
-      const int in_copy = pieces == 1 ? rem : rem + (it & 1) * kWave;   // field * 2R + d
-      const int entry = grp * per_wave + sub;
-      if (sub >= per_wave || entry >= n_active || in_copy >= four_r) continue;
-      const int k = L.list[2 * entry];
+    const int units = 2 * n_active;
+    for (;;) {
+      int u0 = 0;
+      if (lane == 0) u0 = atomicAdd(&counts[3], kWave);
+      u0 = __builtin_amdgcn_readfirstlane(u0);
+      if (u0 >= units) break;
+      const int u = u0 + lane;
+      if (u >= units) continue;
+      const int field = u >= n_active ? 1 : 0;
+      const int k = L.list[2 * (u - field * n_active)];
       const int v = C == 1 ? k : (int)__umulhi((uint32_t)k, c_magic), i = k - v * C;
-      const int field = in_copy >= two_r ? 1 : 0, d = in_copy - field * two_r;
-      const int delta = d < R ? d - R : d - R + 1;
-      const int q = k * four_r + in_copy;
+      const int q0 = (2 * k + field) * two_r;
       const uint32_t mine = L.packed[k];
       const int sz = g.size_dur[v].x;
-      const int in_lo = A.in_ptr[v], in_hi = A.in_ptr[v + 1], out_lo = A.out_ptr[v], out_hi = A.out_ptr[v + 1];
-      moc_move_score sc{-1, -1};
-      if (live_of(mine)) {
-        const int moved = (int)(field == 0 ? mine & 0xFFFFu : mine >> 16) + delta;
-        if (moved >= 0 && moved < T)
-          score_live<CT>(A, C, sz, L, T, R, v, i, field, moved, mine, base_viol - (int)L.fold[2 * k], in_lo, in_hi,
-                         out_lo, out_hi, sc);
-      } else {   // active and ill formed (rare): from scratch
+      moc_move_score* const dst = out_moves ? out_moves + (b * (int64_t)moves_per_cand + q0) : nullptr;
+      bool done = false;
+      if (live_of(mine))
+        done = score_field<CT, WIDE>(A, C, sz, L, T, R, v, i, field, mine, base_viol - (int)L.fold[2 * k], q0, cap,
+                                     out_best != nullptr, pairs, dst, best);
+      if (!done) {   // active and ill formed, or a node with very many edges (rare): move by move, from scratch
         const int s = starts[row + k], e = ends[row + k];
-        const int moved = (field == 0 ? s : e) + delta;
-        if (moved >= 0 && moved < T) score_move(A, C, sz, L, T, v, i, field, s, e, moved, base_viol, base_peak, sc);
+        for (int d = 0; d < two_r; ++d) {
+          const int moved = (field == 0 ? s : e) + (d < R ? d - R : d - R + 1);
+          moc_move_score sc{-1, -1};
+          if (moved >= 0 && moved < T) {
+            score_move(A, C, sz, L, T, v, i, field, s, e, moved, base_viol, base_peak, sc);
+            const Best cand{sc.violations, sc.peak, q0 + d};
+            if (better(cand, best, cap)) best = cand;
+          }
+          if (dst) dst[d] = sc;
+        }
       }
-      if (sc.violations >= 0) {
-        const Best cand{sc.violations, sc.peak, q};
-        if (better(cand, best, g.budget)) best = cand;
-      }
-      if (out_moves) out_moves[b * (int64_t)moves_per_cand + q] = sc;
     }
     // ---- the moves of inactive copies are not applicable
     if (out_moves) {
@@ -447,7 +564,7 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
         o.viol = __shfl_xor(best.viol, off);
         o.peak = __shfl_xor(best.peak, off);
         o.move = __shfl_xor(best.move, off);
-        if (better(o, best, g.budget)) best = o;
+        if (better(o, best, cap)) best = o;
       }
       if (lane == 0) {
         L.scratch[wave * 4 + 0] = best.viol;
@@ -459,7 +576,7 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
         Best all{0, 0, -1};
         for (int w = 0; w < kNW; ++w) {
           const Best o{L.scratch[w * 4], L.scratch[w * 4 + 1], L.scratch[w * 4 + 2]};
-          if (better(o, all, g.budget)) all = o;
+          if (better(o, all, cap)) all = o;
         }
         moc_best_move r;
         r.move = all.move;
@@ -476,18 +593,22 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
 using NbKernel = void (*)(GraphView, int64_t, const int32_t*, const int32_t*, const uint8_t*, int, moc_move_score*,
                           moc_best_move*, NbLayout);
 
-template <bool ADJ_LDS>
+template <bool ADJ_LDS, bool WIDE>
 NbKernel pick_copies(int C) {
   switch (C) {
-    case 1: return neighbours_kernel<ADJ_LDS, 1>;
-    case 2: return neighbours_kernel<ADJ_LDS, 2>;
-    case 3: return neighbours_kernel<ADJ_LDS, 3>;
-    case 4: return neighbours_kernel<ADJ_LDS, 4>;
-    default: return neighbours_kernel<ADJ_LDS, 0>;   // C read at run time
+    case 1: return neighbours_kernel<ADJ_LDS, 1, WIDE>;
+    case 2: return neighbours_kernel<ADJ_LDS, 2, WIDE>;
+    case 3: return neighbours_kernel<ADJ_LDS, 3, WIDE>;
+    case 4: return neighbours_kernel<ADJ_LDS, 4, WIDE>;
+    default: return neighbours_kernel<ADJ_LDS, 0, WIDE>;   // C read at run time
   }
 }
 
-NbKernel pick_kernel(bool adj_lds, int C) { return adj_lds ? pick_copies<true>(C) : pick_copies<false>(C); }
+NbKernel pick_kernel(bool adj_lds, int C, int R) {
+  const bool wide = 2 * R > 31;   // 64-bit displacement masks
+  if (adj_lds) return wide ? pick_copies<true, true>(C) : pick_copies<true, false>(C);
+  return wide ? pick_copies<false, true>(C) : pick_copies<false, false>(C);
+}
 
 }  // namespace
 
@@ -507,7 +628,7 @@ extern "C" int moc_eval_neighbours(const moc_graph* g, int64_t B, const int32_t*
   const NbLayout lay = nb_layout(g->view.T, g->view.n, g->view.m, g->max_lds);
   if (lay.bytes > g->max_lds) return MOC_EOVERFLOW;
   if ((int64_t)g->view.T * 4 * R > 0x7FFFFFFF) return MOC_EOVERFLOW;
-  auto kern = pick_kernel(lay.adj_off != 0, g->view.C);
+  auto kern = pick_kernel(lay.adj_off != 0, g->view.C, R);
   MOC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                               lay.bytes));
   int per_cu = 0;
