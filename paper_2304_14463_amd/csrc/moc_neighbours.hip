@@ -274,14 +274,14 @@ __device__ __forceinline__ bool score_field(const Adj& A, int C, int sz, const N
 #pragma unroll
   for (int p = 0; p < kPlanes; ++p) plane[p] = 0;
   M overflow = 0;
-  auto add = [&](M m) {
+  auto add = [&](M m) {   // most terms are false for every move of every lane
     M carry = m;
 #pragma unroll
     for (int p = 0; p < kPlanes; ++p) {
+      if (!B::any(carry)) break;
       const M t = plane[p] & carry;
       plane[p] ^= carry;
       carry = t;
-      if (!B::any(carry)) break;
     }
     overflow |= carry;
   };
