@@ -231,17 +231,23 @@ __device__ __forceinline__ bool better(const Best& a, const Best& b, int cap) {
   return a.move < b.move;
 }
 
-// All 2R moves of one field of a live copy (v, i), by one lane.  What a move adds to the
-// violation count is a sum of 0/1 terms, each true on an interval of the moved position:
-// the terms are built as masks over the displacements and summed in bit planes, then the
-// lane walks outwards from the old position, one step per displacement on either side,
-// keeping the maximum of the profile over the positions gained or lost so far.
-// `q0` is the index of the lane's first move, `fixed` the base count without f(old copy).
-// Returns false if a counter overflowed (the caller then scores the moves one by one).
+// What the 2R moves of one field of a live copy add to the violation count, move by move:
+// a sum of 0/1 terms, each true on an interval of the moved position.  The terms are built
+// as masks over the displacements and summed in bit planes.
+template <bool WIDE>
+struct FieldState {
+  typename Bits<WIDE>::M plane[kPlanes];   // bit d of plane p: bit p of the count of move d
+  typename Bits<WIDE>::M live;             // moves that leave the copy well formed
+  int fixed, if_live, if_dead;             // violations = fixed + (live ? if_live : if_dead) + count
+  int s, e, sz, q0;                        // the copy before the move, its size, index of its first move
+  int field;                               // 0: the start moves, 1: the end; -1: nothing to score
+};
+
+// `fixed` comes in as the base count without f(old copy).  On a counter overflow in any
+// lane the state is marked invalid (the caller then scores the moves one by one).
 template <int CT, bool WIDE>
-__device__ __forceinline__ bool score_field(const Adj& A, int C, int sz, const NbLds& L, int T, int R, int v, int i,
-                                            int field, uint32_t mine, int fixed, int q0, int cap, bool want_best,
-                                            bool pairs, moc_move_score* __restrict__ dst, Best& best) {
+__device__ __forceinline__ void build_field(const Adj& A, int C, int sz, const NbLds& L, int T, int R, int v, int i,
+                                            int field, uint32_t mine, int fixed, int q0, FieldState<WIDE>& st) {
   using B = Bits<WIDE>;
   using M = typename B::M;
   const int D = 2 * R;
@@ -333,44 +339,69 @@ __device__ __forceinline__ bool score_field(const Adj& A, int C, int sz, const N
       add(in_dom & ~mine_covers);
     }
   }
-  if (B::any(overflow)) return false;
-  // ---- outwards from the old position: step j scores the displacements -j and +j
-  int top_down = 0, top_up = 0;   // maximum of the profile over the positions changed so far, either side
-  const int sz_down = field == 0 ? sz : -sz, sz_up = field == 0 ? -sz : sz;   // a start moved down gains positions, ...
-  auto step = [&](int j, int side) -> moc_move_score {   // side 0: displacement -j, side 1: +j
-    const int d = side == 0 ? R - j : R + j - 1;
-    const int moved = side == 0 ? base - j : base + j;
-    // the position that joins the changed window with this step, and the window [lo, hi]
-    int far, lo, hi;
-    bool joins;
-    if (field == 0) {
-      if (side == 0) { far = s - j; lo = far; hi = s - 1; joins = true; }
-      else { far = s + j - 1; lo = s; hi = min(far, e); joins = far <= e; }
-    } else {
-      if (side == 1) { far = e + j; lo = e + 1; hi = far; joins = true; }
-      else { far = e - j + 1; lo = max(far, s); hi = e; joins = far >= s; }
-    }
-    const int at = L.profile[min(max(far, 0), T - 1)];
-    int& top = side == 0 ? top_down : top_up;
-    top = joins ? max(top, at) : top;
-    moc_move_score sc{-1, -1};
-    if (moved >= 0 && moved < T) {
-      int count = 0;
+  st.live = live;
+  st.fixed = fixed;
+  st.if_live = if_live;
+  st.if_dead = if_dead;
+  st.s = s;
+  st.e = e;
+  st.sz = sz;
+  st.q0 = q0;
+  st.field = B::any(overflow) ? -1 : field;
 #pragma unroll
-      for (int p = 0; p < kPlanes; ++p) count |= (int)((plane[p] >> d) & 1) << p;
-      sc.violations = fixed + count + ((live >> d) & 1 ? if_live : if_dead);
-      const int outside = max(L.pmax[lo - 1], L.smax[hi + 1]);
-      sc.peak = max(max(top + (side == 0 ? sz_down : sz_up), 0), outside);
-      if (want_best) {
-        const Best cand{sc.violations, sc.peak, q0 + d};
-        if (better(cand, best, cap)) best = cand;
-      }
-    }
-    return sc;
-  };
+  for (int p = 0; p < kPlanes; ++p) st.plane[p] = plane[p];
+}
+
+// One move of a scored field: `side` 0 is the displacement -j, 1 is +j.  `top` is the maximum
+// of the profile over the positions gained or lost on that side by the smaller displacements;
+// the step adds the position that joins the window.  A start moved down or an end moved up
+// gains positions, the other two lose them (no further than the other end of the interval;
+// re-reading that end changes no maximum).
+template <bool WIDE>
+__device__ __forceinline__ moc_move_score step_move(const FieldState<WIDE>& st, const NbLds& L, int T, int R, int j,
+                                                    int side, int& top) {
+  const int base = st.field == 0 ? st.s : st.e;
+  const int moved = side == 0 ? base - j : base + j;
+  const bool gain = st.field == side;
+  int far = gain ? moved : (side == 0 ? moved + 1 : moved - 1);
+  far = min(max(far, side == 0 && !gain ? st.s : 0), side == 1 && !gain ? st.e : T - 1);
+  top = max(top, L.profile[far]);
+  moc_move_score sc{-1, -1};
+  if (moved >= 0 && moved < T) {
+    const int d = side == 0 ? R - j : R + j - 1;
+    int count = 0;
+#pragma unroll
+    for (int p = 0; p < kPlanes; ++p) count |= (int)((st.plane[p] >> d) & 1) << p;
+    sc.violations = st.fixed + count + ((st.live >> d) & 1 ? st.if_live : st.if_dead);
+    const int lo = side == 0 ? far : (st.field == 0 ? st.s : st.e + 1);
+    const int hi = side == 1 ? far : (st.field == 0 ? st.s - 1 : st.e);
+    sc.peak = max(max(top + (gain ? st.sz : -st.sz), 0), max(L.pmax[lo - 1], L.smax[hi + 1]));
+  }
+  return sc;
+}
+
+__device__ __forceinline__ void offer(Best& best, const moc_move_score& sc, int move, int cap) {
+  if (sc.violations < 0) return;
+  const Best cand{sc.violations, sc.peak, move};
+  if (better(cand, best, cap)) best = cand;
+}
+
+// The lane walks outwards from the old position of its own field, one step per displacement
+// on either side.
+template <bool WIDE>
+__device__ __forceinline__ void walk_own(const FieldState<WIDE>& st, const NbLds& L, int T, int R, int cap,
+                                         bool want_best, bool pairs, moc_move_score* __restrict__ dst, Best& best) {
+  int top_down = 0, top_up = 0;
   if (pairs) {   // R even, dst 16-byte aligned: two scores per store
     for (int j = 1; j < R; j += 2) {
-      const moc_move_score a0 = step(j, 0), b0 = step(j, 1), a1 = step(j + 1, 0), b1 = step(j + 1, 1);
+      const moc_move_score a0 = step_move(st, L, T, R, j, 0, top_down), b0 = step_move(st, L, T, R, j, 1, top_up);
+      const moc_move_score a1 = step_move(st, L, T, R, j + 1, 0, top_down), b1 = step_move(st, L, T, R, j + 1, 1, top_up);
+      if (want_best) {
+        offer(best, a0, st.q0 + R - j, cap);
+        offer(best, b0, st.q0 + R + j - 1, cap);
+        offer(best, a1, st.q0 + R - j - 1, cap);
+        offer(best, b1, st.q0 + R + j, cap);
+      }
       if (dst) {
         *reinterpret_cast<int4*>(dst + (R - j - 1)) = make_int4(a1.violations, a1.peak, a0.violations, a0.peak);
         *reinterpret_cast<int4*>(dst + (R + j - 1)) = make_int4(b0.violations, b0.peak, b1.violations, b1.peak);
@@ -378,14 +409,17 @@ __device__ __forceinline__ bool score_field(const Adj& A, int C, int sz, const N
     }
   } else {
     for (int j = 1; j <= R; ++j) {
-      const moc_move_score a0 = step(j, 0), b0 = step(j, 1);
+      const moc_move_score a0 = step_move(st, L, T, R, j, 0, top_down), b0 = step_move(st, L, T, R, j, 1, top_up);
+      if (want_best) {
+        offer(best, a0, st.q0 + R - j, cap);
+        offer(best, b0, st.q0 + R + j - 1, cap);
+      }
       if (dst) {
         dst[R - j] = a0;
         dst[R + j - 1] = b0;
       }
     }
   }
-  return true;
 }
 
 template <bool ADJ_LDS, int CT, bool WIDE>
@@ -517,19 +551,19 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
       u0 = __builtin_amdgcn_readfirstlane(u0);
       if (u0 >= units) break;
       const int u = u0 + lane;
-      if (u >= units) continue;
+      const bool has_unit = u < units;
       const int field = u >= n_active ? 1 : 0;
-      const int k = L.list[2 * (u - field * n_active)];
+      const int k = has_unit ? L.list[2 * (u - field * n_active)] : 0;
       const int v = C == 1 ? k : (int)__umulhi((uint32_t)k, c_magic), i = k - v * C;
       const int q0 = (2 * k + field) * two_r;
-      const uint32_t mine = L.packed[k];
       const int sz = g.size_dur[v].x;
-      moc_move_score* const dst = out_moves ? out_moves + (b * (int64_t)moves_per_cand + q0) : nullptr;
-      bool done = false;
-      if (live_of(mine))
-        done = score_field<CT, WIDE>(A, C, sz, L, T, R, v, i, field, mine, base_viol - (int)L.fold[2 * k], q0, cap,
-                                     out_best != nullptr, pairs, dst, best);
-      if (!done) {   // active and ill formed, or a node with very many edges (rare): move by move, from scratch
+      FieldState<WIDE> st{};
+      st.field = -1;
+      if (has_unit && live_of(L.packed[k]))
+        build_field<CT, WIDE>(A, C, sz, L, T, R, v, i, field, L.packed[k], base_viol - (int)L.fold[2 * k], q0, st);
+      moc_move_score* const row0 = out_moves ? out_moves + b * (int64_t)moves_per_cand : nullptr;
+      if (st.field >= 0) walk_own(st, L, T, R, cap, out_best != nullptr, pairs, row0 ? row0 + q0 : nullptr, best);
+      if (has_unit && st.field < 0) {   // active and ill formed, or a node with very many edges (rare): move by move, from scratch
         const int s = starts[row + k], e = ends[row + k];
         for (int d = 0; d < two_r; ++d) {
           const int moved = (field == 0 ? s : e) + (d < R ? d - R : d - R + 1);
@@ -539,7 +573,7 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
             const Best cand{sc.violations, sc.peak, q0 + d};
             if (better(cand, best, cap)) best = cand;
           }
-          if (dst) dst[d] = sc;
+          if (row0) row0[q0 + d] = sc;
         }
       }
     }
