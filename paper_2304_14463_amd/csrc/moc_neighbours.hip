@@ -20,12 +20,12 @@
 // and peak' = max(prefix max before, suffix max after, shifted profile inside)
 // over the changed positions (at most R of them unless the copy was outside
 // the domain before the move).
-// Pass 1 stores f(old copy) per copy and lists the active copies.  Pass 2 runs
-// one lane per move of an active copy: 64 consecutive moves of the list per
-// wave, so the lanes of one copy walk the same edges together, inactive copies
-// cost nothing, and a wave writes its scores as whole 128-byte lines.  A third
-// pass fills the scores of the inactive copies (not applicable).  The adjacency
-// lists are kept in LDS when they fit beside the five T-word arrays.
+// Pass 1 counts the violations of the base and lists the active copies.  Pass 2
+// runs one lane per (active copy, field): it builds the 0/1 terms of f as bit
+// masks over the displacements, sums them in bit planes and walks outwards from
+// the old position (see build_field, walk_own).  A third pass fills the scores
+// of the inactive copies (not applicable).  The adjacency lists are kept in LDS
+// when that costs no resident workgroup.
 #include "moc_internal.h"
 
 namespace {
@@ -44,8 +44,8 @@ NbLayout nb_layout(int T, int n, int m, int max_lds) {
   NbLayout l;
   l.T_pad = (T + 3) & ~3;
   l.bit_words = (T + 31) / 32;
-  // profile, prefix max, suffix max, packed, f(old) + two bitmaps + scratch
-  const int words = 5 * l.T_pad + 8 + 2 * l.bit_words + 8 * kNW + 16;
+  // profile, prefix max, suffix max, packed, the copy lists (16 bits an entry) + two bitmaps + scratch
+  const int words = 4 * l.T_pad + l.T_pad / 2 + 8 + 2 * l.bit_words + 8 * kNW + 16;
   l.adj_off = 0;
   l.bytes = 4 * words;
   // the CSR lists both ways, if that costs no resident workgroup (two of 16 waves fit a CU):
@@ -71,8 +71,7 @@ struct NbLds {
   int32_t* pmax;
   int32_t* smax;
   uint32_t* packed;
-  uint16_t* fold;   // [2k]: f(old copy k), below 2^15 for any T this call accepts
-  uint16_t* list;   // [2j]: j-th entry of the copy lists (the other half of the same words)
+  uint16_t* list;   // active copies from the front, inactive ones from the back
   uint32_t* occ1;
   uint32_t* occ2;
   int32_t* scratch;   // 8 * kNW + 16
@@ -164,13 +163,13 @@ __device__ __forceinline__ int node_part(const Adj& g, int C, const uint32_t* __
 // at `moved`.  The general form; the kernel uses it for copies that are ill-formed before
 // the move, where the changed positions are a whole interval.
 __device__ __forceinline__ void score_move(const Adj& g, int C, int sz, const NbLds& L, int T, int v, int i,
-                                           int field, int s, int e, int moved, int base_viol, int base_peak,
-                                           moc_move_score& sc) {
+                                           int field, int s, int e, int moved, int base_rest, int base_peak,
+                                           moc_move_score& sc) {   // base_rest: the base count without f(old copy)
   const int k = v * C + i;
   const int s2 = field == 0 ? moved : s, e2 = field == 0 ? e : moved;
   const bool live_old = live_of(L.packed[k]);
   const bool live_new = (uint32_t)s2 <= (uint32_t)e2 && (uint32_t)e2 < (uint32_t)T;
-  int vv = base_viol - (int)L.fold[2 * k] + node_part(g, C, L.packed, v, i, true, live_new, s2, e2);
+  int vv = base_rest + node_part(g, C, L.packed, v, i, true, live_new, s2, e2);
   if (live_old && bit_at(L.occ2, s)) --vv;
   if (live_new) vv += (live_old && s2 == s) ? (bit_at(L.occ2, s) ? 1 : 0) : (bit_at(L.occ1, s2) ? 1 : 0);
   // peak: positions lost (sign -1) or gained (sign +1)
@@ -243,39 +242,40 @@ struct FieldState {
   int field;                               // 0: the start moves, 1: the end; -1: nothing to score
 };
 
-// `fixed` comes in as the base count without f(old copy).  On a counter overflow in any
-// lane the state is marked invalid (the caller then scores the moves one by one).
+// The 32-bit masks (R <= 15) have one bit per position first..first+2R, the copy's own
+// position (no move) included: the count at that bit is what the copy contributes now, so
+// violations of a move = base count - that + count of the move.  The 64-bit masks have one
+// bit per move (no room for the extra bit at R = 32); there the copy's present contribution
+// is computed edge by edge.  On a counter overflow in any lane the state is marked invalid
+// (the caller then scores the moves one by one).
 template <int CT, bool WIDE>
 __device__ __forceinline__ void build_field(const Adj& A, int C, int sz, const NbLds& L, int T, int R, int v, int i,
-                                            int field, uint32_t mine, int fixed, int q0, FieldState<WIDE>& st) {
+                                            int field, uint32_t mine, int base_viol, int q0, FieldState<WIDE>& st) {
   using B = Bits<WIDE>;
   using M = typename B::M;
-  const int D = 2 * R;
+  const int D = WIDE ? 2 * R : 2 * R + 1;
   const int s = (int)(mine & 0xFFFFu), e = (int)(mine >> 16);
   const int base = field == 0 ? s : e, first = base - R;
-  // {d : moved(d) < x}: the moved positions are first..base-1, base+1..base+R
-  auto lt = [&](int x) -> M { return B::below(x - first - (x > base ? 1 : 0), D); };
+  // {bits : moved < x}
+  auto lt = [&](int x) -> M {
+    if constexpr (WIDE) return B::below(x - first - (x > base ? 1 : 0), D);   // moved: first..base-1, base+1..base+R
+    else return B::below(x - first, D);                                        // moved: first..base+R
+  };
   const M in_dom = lt(T) & ~lt(0);
   const M live = in_dom & (field == 0 ? lt(e + 1) : ~lt(s));   // start <= end after the move
   // Eq. (3): the live neighbours of copy i among the copies of v, and the violations
   // between other consecutive live copies
   const uint32_t* const row = L.packed + v * C;
-  int prev_end = -1, next_start = kNoCopy, order_others = 0;
-  {
-    int pe = -1;   // end of the last live copy on this side of copy i
-    for (int j = 0; j < C; ++j) {
-      if (j == i) { prev_end = pe; pe = -1; continue; }
-      const uint32_t p = row[j];
-      if (!live_of(p)) continue;
-      if (j > i && next_start == kNoCopy) next_start = (int)(p & 0xFFFFu);
-      order_others += pe > (int)(p & 0xFFFFu) ? 1 : 0;
-      pe = (int)(p >> 16);
-    }
+  int prev_end = -1, next_start = kNoCopy;
+  for (int j = 0; j < C; ++j) {
+    const uint32_t p = row[j];
+    if (j == i || !live_of(p)) continue;
+    if (j < i) prev_end = (int)(p >> 16);
+    else if (next_start == kNoCopy) next_start = (int)(p & 0xFFFFu);
   }
   const int start_twice = bit_at(L.occ2, s) ? 1 : 0;
   const int if_dead = 1 + (prev_end > next_start ? 1 : 0);   // Eq. (2)/(8), Eq. (3) across the gap
-  int if_live;
-  fixed += order_others - start_twice;
+  int if_live;   // what a move that keeps the copy well formed adds besides the counted terms
   M plane[kPlanes];
 #pragma unroll
   for (int p = 0; p < kPlanes; ++p) plane[p] = 0;
@@ -295,14 +295,15 @@ __device__ __forceinline__ void build_field(const Adj& A, int C, int sz, const N
   if (field == 0) {
     if_live = e > next_start ? 1 : 0;
     add(live & lt(prev_end));   // Eq. (3): the previous copy ends after the new start
-    // Eq. (6): the new start is taken.  Bits of occ1 at first..base-1 and base+1..base+R
+    // Eq. (6): the new start is taken (the copy's own start is not a move)
     {
-      auto window = [&](int from) -> M {   // R bits of occ1 from position `from` (>= -R) on; positions below 0 read as 0
+      auto window = [&](int from, int bits) -> M {   // bits of occ1 from position `from` (>= -R) on; positions below 0 read as 0
         const int f0 = max(from, 0), w = min(f0 >> 5, (T - 1) >> 5), w1 = min(w + 1, (T - 1) >> 5);
         const uint64_t two = (uint64_t)L.occ1[w] | ((uint64_t)(w1 > w ? L.occ1[w1] : 0u) << 32);
-        return (M)(((two >> (f0 & 31)) << (f0 - from)) & (((uint64_t)1 << R) - 1));
+        return (M)(((two >> (f0 & 31)) << (f0 - from)) & (((uint64_t)1 << bits) - 1));
       };
-      add(live & (window(first) | (window(base + 1) << R)));
+      if constexpr (WIDE) add(live & (window(first, R) | (window(base + 1, R) << R)));
+      else add(live & window(first, D) & ~((M)1 << R));
     }
     // Eq. (5), the copy as consumer: in-edges whose provider does not cover the new start
     for (int q = in_lo; q < in_hi; ++q) {
@@ -339,6 +340,24 @@ __device__ __forceinline__ void build_field(const Adj& A, int C, int sz, const N
       add(in_dom & ~mine_covers);
     }
   }
+  // the copy's contribution now, to be replaced by the move's
+  int fixed;
+  if constexpr (WIDE) {
+    int order_others = 0, pe = -1;   // Eq. (3) between other consecutive live copies, on either side of copy i
+    for (int j = 0; j < C; ++j) {
+      if (j == i) { pe = -1; continue; }
+      const uint32_t p = row[j];
+      if (!live_of(p)) continue;
+      order_others += pe > (int)(p & 0xFFFFu) ? 1 : 0;
+      pe = (int)(p >> 16);
+    }
+    fixed = base_viol - node_part(A, C, L.packed, v, i, true, true, s, e) + order_others - start_twice;
+  } else {
+    int now = 0;   // the counted terms at the copy's own position
+#pragma unroll
+    for (int p = 0; p < kPlanes; ++p) now |= (int)((plane[p] >> R) & 1) << p;
+    fixed = base_viol - start_twice - now - (if_live - (field == 0 ? 0 : start_twice));
+  }
   st.live = live;
   st.fixed = fixed;
   st.if_live = if_live;
@@ -368,7 +387,7 @@ __device__ __forceinline__ moc_move_score step_move(const FieldState<WIDE>& st, 
   top = max(top, L.profile[far]);
   moc_move_score sc{-1, -1};
   if (moved >= 0 && moved < T) {
-    const int d = side == 0 ? R - j : R + j - 1;
+    const int d = side == 0 ? R - j : (WIDE ? R + j - 1 : R + j);   // the move's bit in the masks
     int count = 0;
 #pragma unroll
     for (int p = 0; p < kPlanes; ++p) count |= (int)((st.plane[p] >> d) & 1) << p;
@@ -434,9 +453,8 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
   L.pmax = L.profile + lay.T_pad + 4;   // pmax[-1] = 0
   L.smax = L.pmax + lay.T_pad;          // smax[T] = 0
   L.packed = reinterpret_cast<uint32_t*>(L.smax + lay.T_pad + 4);
-  L.fold = reinterpret_cast<uint16_t*>(L.packed + lay.T_pad);
-  L.list = L.fold + 1;
-  L.occ1 = reinterpret_cast<uint32_t*>(L.fold + 2 * lay.T_pad);
+  L.list = reinterpret_cast<uint16_t*>(L.packed + lay.T_pad);
+  L.occ1 = reinterpret_cast<uint32_t*>(L.list + lay.T_pad);
   L.occ2 = L.occ1 + lay.bit_words;
   L.scratch = reinterpret_cast<int32_t*>(L.occ2 + lay.bit_words);
   const int tid = threadIdx.x, lane = tid & (kWave - 1);
@@ -503,7 +521,6 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
         const int s = starts[row + k], e = ends[row + k];
         act = active[row + k] != 0;
         const bool live = live_of(L.packed[k]);
-        L.fold[2 * k] = (uint16_t)(act ? node_part(A, C, L.packed, v, i, act, live, s, e) : 0);
         // base count: each instance once -- form, the order pair that copy k opens, its inputs
         viol += (act && !live) ? 1 : 0;
         if (live) {
@@ -531,8 +548,8 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
       abase = __shfl(abase, 0);
       ibase = __shfl(ibase, 0);
       const uint64_t below = ((uint64_t)1 << lane) - 1;
-      if (act) L.list[2 * (abase + __popcll(am & below))] = (uint16_t)k;
-      else if (k < T) L.list[2 * (T - 1 - ibase - __popcll(im & below))] = (uint16_t)k;
+      if (act) L.list[abase + __popcll(am & below)] = (uint16_t)k;
+      else if (k < T) L.list[T - 1 - ibase - __popcll(im & below)] = (uint16_t)k;
     }
     int distinct = 0;
     for (int w = tid; w < lay.bit_words; w += kNT) distinct += __popc(L.occ1[w]);
@@ -553,23 +570,24 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
       const int u = u0 + lane;
       const bool has_unit = u < units;
       const int field = u >= n_active ? 1 : 0;
-      const int k = has_unit ? L.list[2 * (u - field * n_active)] : 0;
+      const int k = has_unit ? L.list[u - field * n_active] : 0;
       const int v = C == 1 ? k : (int)__umulhi((uint32_t)k, c_magic), i = k - v * C;
       const int q0 = (2 * k + field) * two_r;
       const int sz = g.size_dur[v].x;
       FieldState<WIDE> st{};
       st.field = -1;
       if (has_unit && live_of(L.packed[k]))
-        build_field<CT, WIDE>(A, C, sz, L, T, R, v, i, field, L.packed[k], base_viol - (int)L.fold[2 * k], q0, st);
+        build_field<CT, WIDE>(A, C, sz, L, T, R, v, i, field, L.packed[k], base_viol, q0, st);
       moc_move_score* const row0 = out_moves ? out_moves + b * (int64_t)moves_per_cand : nullptr;
       if (st.field >= 0) walk_own(st, L, T, R, cap, out_best != nullptr, pairs, row0 ? row0 + q0 : nullptr, best);
       if (has_unit && st.field < 0) {   // active and ill formed, or a node with very many edges (rare): move by move, from scratch
         const int s = starts[row + k], e = ends[row + k];
+        const int base_rest = base_viol - node_part(A, C, L.packed, v, i, true, live_of(L.packed[k]), s, e);
         for (int d = 0; d < two_r; ++d) {
           const int moved = (field == 0 ? s : e) + (d < R ? d - R : d - R + 1);
           moc_move_score sc{-1, -1};
           if (moved >= 0 && moved < T) {
-            score_move(A, C, sz, L, T, v, i, field, s, e, moved, base_viol, base_peak, sc);
+            score_move(A, C, sz, L, T, v, i, field, s, e, moved, base_rest, base_peak, sc);
             const Best cand{sc.violations, sc.peak, q0 + d};
             if (better(cand, best, cap)) best = cand;
           }
@@ -586,7 +604,7 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
         const int in_copy = pieces == 1 ? rem : rem + (it & 1) * kWave;
         const int entry = grp * per_wave + sub;
         if (sub >= per_wave || entry >= n_inactive || in_copy >= four_r) continue;
-        const int k = L.list[2 * (n_active + entry)];
+        const int k = L.list[n_active + entry];
         out_moves[b * (int64_t)moves_per_cand + k * four_r + in_copy] = moc_move_score{-1, -1};
       }
     }

@@ -154,7 +154,7 @@ def test_neighbours_argument_errors(moc, workloads):
     with pytest.raises(moc.MoccasinError):
         moc.moc_eval_neighbours(gh, s, e, a, 4, want_moves=False, want_best=False)
     gh.free()
-    # five T-word arrays do not fit the LDS for T = 9000
+    # 4.5 words per copy do not fit the LDS for T = 9000
     n = 9000
     g = graph_from_edges(n, [(i, i + 1) for i in range(n - 1)], np.ones(n), np.ones(n))
     gh = moc.moc_graph_upload(n, g.in_ptr, g.in_idx, g.size, g.dur, 10, 1)
