@@ -218,14 +218,13 @@ struct Best {
   int viol, peak, move;   // move < 0: none
 };
 
-// Order of the best move: (violations, max(peak, budget), peak, move index); `cap` is the
-// budget clamped to [0, 2^31 - 1], which orders peaks (never negative) the same way.
-__device__ __forceinline__ bool better(const Best& a, const Best& b, int cap) {
+// Order of the best move: (violations, max(peak, budget), peak, move index).  max(peak, budget)
+// never decreases with the peak and its ties are broken by the peak, so this is the order
+// by (violations, peak, move index).
+__device__ __forceinline__ bool better(const Best& a, const Best& b) {
   if (a.move < 0) return false;
   if (b.move < 0) return true;
   if (a.viol != b.viol) return a.viol < b.viol;
-  const int ma = max(a.peak, cap), mb = max(b.peak, cap);
-  if (ma != mb) return ma < mb;
   if (a.peak != b.peak) return a.peak < b.peak;
   return a.move < b.move;
 }
@@ -371,56 +370,58 @@ __device__ __forceinline__ void build_field(const Adj& A, int C, int sz, const N
   for (int p = 0; p < kPlanes; ++p) st.plane[p] = plane[p];
 }
 
-// One move of a scored field: `side` 0 is the displacement -j, 1 is +j.  `top` is the maximum
-// of the profile over the positions gained or lost on that side by the smaller displacements;
-// the step adds the position that joins the window.  A start moved down or an end moved up
-// gains positions, the other two lose them (no further than the other end of the interval;
-// re-reading that end changes no maximum).
-template <bool WIDE>
-__device__ __forceinline__ moc_move_score step_move(const FieldState<WIDE>& st, const NbLds& L, int T, int R, int j,
-                                                    int side, int& top) {
+// The lane walks outwards from the old position of its field, one step per displacement on
+// either side.  `top` is the maximum of the profile over the positions gained or lost so far
+// on a side; a step adds the position that joins the window.  A start moved down or an end
+// moved up gains positions, the other two lose them, no further than the other end of the
+// interval (the clamp re-reads that end, which changes no maximum).  The peak of a move is
+// max(top +- size, prefix maximum before the window, suffix maximum after it); one of the
+// two does not change along a side.  NP: bit planes in use.
+// The best move of the field is the minimum of violations << 37 | peak << 6 | index of the move
+// in the field (violations < 2^26 for any T this call accepts; a move that is not applicable
+// has violations -1, the largest key).
+template <int NP, bool WIDE>
+__device__ __forceinline__ void walk_own(const FieldState<WIDE>& st, const NbLds& L, int T, int R, bool want_best,
+                                         bool pairs, moc_move_score* __restrict__ dst, Best& best) {
   const int base = st.field == 0 ? st.s : st.e;
-  const int moved = side == 0 ? base - j : base + j;
-  const bool gain = st.field == side;
-  int far = gain ? moved : (side == 0 ? moved + 1 : moved - 1);
-  far = min(max(far, side == 0 && !gain ? st.s : 0), side == 1 && !gain ? st.e : T - 1);
-  top = max(top, L.profile[far]);
-  moc_move_score sc{-1, -1};
-  if (moved >= 0 && moved < T) {
-    const int d = side == 0 ? R - j : (WIDE ? R + j - 1 : R + j);   // the move's bit in the masks
+  const bool start_moves = st.field == 0;
+  // down: a start gains [moved, s-1], an end loses [max(moved+1, s), e]
+  const int from_down = base + (start_moves ? 0 : 1), stop_down = start_moves ? 0 : st.s;
+  const int size_down = start_moves ? st.sz : -st.sz;
+  const int after_down = L.smax[start_moves ? st.s : st.e + 1];
+  // up: a start loses [s, min(moved-1, e)], an end gains [e+1, moved]
+  const int from_up = base - (start_moves ? 1 : 0), stop_up = start_moves ? st.e : T - 1;
+  const int size_up = -size_down;
+  const int before_up = L.pmax[(start_moves ? st.s : st.e + 1) - 1];
+  const int if_delta = st.if_live - st.if_dead;
+  int top_down = 0, top_up = 0;
+  uint64_t key = ~(uint64_t)0;
+  auto score = [&](int bit, int top, int size, int outside, bool valid, int index) -> moc_move_score {
     int count = 0;
 #pragma unroll
-    for (int p = 0; p < kPlanes; ++p) count |= (int)((st.plane[p] >> d) & 1) << p;
-    sc.violations = st.fixed + count + ((st.live >> d) & 1 ? st.if_live : st.if_dead);
-    const int lo = side == 0 ? far : (st.field == 0 ? st.s : st.e + 1);
-    const int hi = side == 1 ? far : (st.field == 0 ? st.s - 1 : st.e);
-    sc.peak = max(max(top + (gain ? st.sz : -st.sz), 0), max(L.pmax[lo - 1], L.smax[hi + 1]));
-  }
-  return sc;
-}
-
-__device__ __forceinline__ void offer(Best& best, const moc_move_score& sc, int move, int cap) {
-  if (sc.violations < 0) return;
-  const Best cand{sc.violations, sc.peak, move};
-  if (better(cand, best, cap)) best = cand;
-}
-
-// The lane walks outwards from the old position of its own field, one step per displacement
-// on either side.
-template <bool WIDE>
-__device__ __forceinline__ void walk_own(const FieldState<WIDE>& st, const NbLds& L, int T, int R, int cap,
-                                         bool want_best, bool pairs, moc_move_score* __restrict__ dst, Best& best) {
-  int top_down = 0, top_up = 0;
+    for (int p = 0; p < NP; ++p) count |= (int)((st.plane[p] >> bit) & 1) << p;
+    moc_move_score sc;
+    sc.violations = valid ? st.fixed + st.if_dead + count + (int)((st.live >> bit) & 1) * if_delta : -1;
+    sc.peak = valid ? max(max(top + size, 0), outside) : -1;
+    if (want_best) {
+      const uint64_t k = ((uint64_t)(uint32_t)sc.violations << 37) | ((uint64_t)(uint32_t)sc.peak << 6) | (uint32_t)index;
+      key = k < key ? k : key;
+    }
+    return sc;
+  };
+  auto down = [&](int j) -> moc_move_score {
+    const int far = max(from_down - j, stop_down);
+    top_down = max(top_down, L.profile[far]);
+    return score(R - j, top_down, size_down, max(L.pmax[far - 1], after_down), j <= base, R - j);
+  };
+  auto up = [&](int j) -> moc_move_score {
+    const int far = min(from_up + j, stop_up);
+    top_up = max(top_up, L.profile[far]);
+    return score(WIDE ? R + j - 1 : R + j, top_up, size_up, max(before_up, L.smax[far + 1]), base + j < T, R + j - 1);
+  };
   if (pairs) {   // R even, dst 16-byte aligned: two scores per store
     for (int j = 1; j < R; j += 2) {
-      const moc_move_score a0 = step_move(st, L, T, R, j, 0, top_down), b0 = step_move(st, L, T, R, j, 1, top_up);
-      const moc_move_score a1 = step_move(st, L, T, R, j + 1, 0, top_down), b1 = step_move(st, L, T, R, j + 1, 1, top_up);
-      if (want_best) {
-        offer(best, a0, st.q0 + R - j, cap);
-        offer(best, b0, st.q0 + R + j - 1, cap);
-        offer(best, a1, st.q0 + R - j - 1, cap);
-        offer(best, b1, st.q0 + R + j, cap);
-      }
+      const moc_move_score a0 = down(j), b0 = up(j), a1 = down(j + 1), b1 = up(j + 1);
       if (dst) {
         *reinterpret_cast<int4*>(dst + (R - j - 1)) = make_int4(a1.violations, a1.peak, a0.violations, a0.peak);
         *reinterpret_cast<int4*>(dst + (R + j - 1)) = make_int4(b0.violations, b0.peak, b1.violations, b1.peak);
@@ -428,16 +429,16 @@ __device__ __forceinline__ void walk_own(const FieldState<WIDE>& st, const NbLds
     }
   } else {
     for (int j = 1; j <= R; ++j) {
-      const moc_move_score a0 = step_move(st, L, T, R, j, 0, top_down), b0 = step_move(st, L, T, R, j, 1, top_up);
-      if (want_best) {
-        offer(best, a0, st.q0 + R - j, cap);
-        offer(best, b0, st.q0 + R + j - 1, cap);
-      }
+      const moc_move_score a0 = down(j), b0 = up(j);
       if (dst) {
         dst[R - j] = a0;
         dst[R + j - 1] = b0;
       }
     }
+  }
+  if (want_best && !(key >> 63)) {
+    const Best cand{(int)(key >> 37), (int)((key >> 6) & 0x7FFFFFFFu), st.q0 + (int)(key & 63)};
+    if (better(cand, best)) best = cand;
   }
 }
 
@@ -469,7 +470,6 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
   const int sub = four_r <= kWave ? lane / four_r : 0;
   const int rem = four_r <= kWave ? lane - sub * four_r : lane;
   int32_t* const counts = L.scratch + 8 * kNW;   // [0] base violations, [1] active copies, [2] inactive copies, [3] work drawn
-  const int cap = (int)min(max(g.budget, (int64_t)0), (int64_t)0x7FFFFFFF);
   const bool pairs = (R & 1) == 0 && (reinterpret_cast<uintptr_t>(out_moves) & 15) == 0;   // scores stored two at a time
   Adj A{g.in_ptr, g.in_idx, g.out_ptr, g.out_idx};
   if constexpr (ADJ_LDS) {   // the adjacency lists are read by every move: keep them in LDS
@@ -579,7 +579,13 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
       if (has_unit && live_of(L.packed[k]))
         build_field<CT, WIDE>(A, C, sz, L, T, R, v, i, field, L.packed[k], base_viol, q0, st);
       moc_move_score* const row0 = out_moves ? out_moves + b * (int64_t)moves_per_cand : nullptr;
-      if (st.field >= 0) walk_own(st, L, T, R, cap, out_best != nullptr, pairs, row0 ? row0 + q0 : nullptr, best);
+      if (st.field >= 0) {
+        bool high = false;   // counts above 7 in some lane
+#pragma unroll
+        for (int p = 3; p < kPlanes; ++p) high = high || Bits<WIDE>::any(st.plane[p]);
+        if (high) walk_own<kPlanes, WIDE>(st, L, T, R, out_best != nullptr, pairs, row0 ? row0 + q0 : nullptr, best);
+        else walk_own<3, WIDE>(st, L, T, R, out_best != nullptr, pairs, row0 ? row0 + q0 : nullptr, best);
+      }
       if (has_unit && st.field < 0) {   // active and ill formed, or a node with very many edges (rare): move by move, from scratch
         const int s = starts[row + k], e = ends[row + k];
         const int base_rest = base_viol - node_part(A, C, L.packed, v, i, true, live_of(L.packed[k]), s, e);
@@ -589,7 +595,7 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
           if (moved >= 0 && moved < T) {
             score_move(A, C, sz, L, T, v, i, field, s, e, moved, base_rest, base_peak, sc);
             const Best cand{sc.violations, sc.peak, q0 + d};
-            if (better(cand, best, cap)) best = cand;
+            if (better(cand, best)) best = cand;
           }
           if (row0) row0[q0 + d] = sc;
         }
@@ -616,7 +622,7 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
         o.viol = __shfl_xor(best.viol, off);
         o.peak = __shfl_xor(best.peak, off);
         o.move = __shfl_xor(best.move, off);
-        if (better(o, best, cap)) best = o;
+        if (better(o, best)) best = o;
       }
       if (lane == 0) {
         L.scratch[wave * 4 + 0] = best.viol;
@@ -628,7 +634,7 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
         Best all{0, 0, -1};
         for (int w = 0; w < kNW; ++w) {
           const Best o{L.scratch[w * 4], L.scratch[w * 4 + 1], L.scratch[w * 4 + 2]};
-          if (better(o, all, cap)) all = o;
+          if (better(o, all)) all = o;
         }
         moc_best_move r;
         r.move = all.move;
