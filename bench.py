@@ -27,7 +27,7 @@ HBM_PEAK_GBS = 8000.0
 # (profiles/eval_batch_kernel_n5000_C3_B262144.md): KiB per dispatch and the factors that the same
 # counters need to reproduce a 1 GiB device copy.  Valid for the kernel sources they were taken with.
 TRAFFIC = {"workload": 4, "B": 262144, "fetch_kib": 17327700.0, "fetch_scale": 2.0, "write_kib": 20496.5,
-           "write_scale": 1.0, "sources_sha256": "75d0f43e003acddc7ee6008ca86f308c722d1b1d610ec6db45c7a0ee41992a30"}
+           "write_scale": 1.0, "sources_sha256": "0d85a5e6d844d067ba3a0738095629e84fb1858323105bd19a61956cf3fae379"}
 KERNEL_SOURCES = ("moc_eval.hip", "moc_graph.hip", "moc_internal.h")
 
 

@@ -32,17 +32,16 @@
 // unit combines the masks, counts come from popcounts or an add-with-carry per
 // lane.  Which candidate a workgroup takes next is drawn from a counter, an
 // iteration ahead (see the kernel).
-// What shaped this, measured on gfx950.  A wave issues an instruction every 8
-// clocks at best, whatever the other waves do, and with one 1024-thread
-// workgroup per compute unit (the LDS working set of a large graph allows no
-// more) only 4 waves share a SIMD: the time of a candidate is the number of
-// instructions a wave executes for it, of any kind, plus what it waits at the
-// two barriers.  LDS, per compute unit: a 64-lane 4-byte access to random
-// addresses takes about 7 clocks, read, write or atomic alike; 8-byte random
-// costs the same, 16-byte random 12.5; with the 32 lanes that LDS serves at a
-// time in distinct banks 2.8 (4.4 for 8 bytes and 16 lanes).  Hence records and
-// chunks are sized for wide accesses, nothing is read twice, and the edge list
-// is laid out for distinct banks at upload.
+// What shaped this, measured on gfx950.  A SIMD needs 4 clocks for a 64-lane
+// vector instruction, and with one 1024-thread workgroup per compute unit (the
+// LDS working set of a large graph allows no more) only 4 waves share a SIMD and
+// meet at two barriers per candidate: the vector unit is the busiest part (60 %
+// at n = 5000), scalar instructions run beside it.  Hence the scalar masks.
+// LDS, per compute unit: a 64-lane 4-byte access to random addresses takes 2.6
+// times as long as one whose 32 lanes served together fall into distinct banks,
+// read, write or atomic alike; 8-byte accesses (16 lanes at a time) 1.7 times.
+// Hence records and chunks are sized for wide accesses, nothing is read twice,
+// and the edge list is laid out for distinct banks at upload.
 // All arithmetic is integer: results do not depend on the order in which
 // lanes or workgroups run.
 #include <type_traits>
