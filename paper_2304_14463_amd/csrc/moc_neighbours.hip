@@ -396,12 +396,17 @@ __device__ __forceinline__ void walk_own(const FieldState<WIDE>& st, const NbLds
   const int if_delta = st.if_live - st.if_dead;
   int top_down = 0, top_up = 0;
   uint64_t key = ~(uint64_t)0;
+  const int if_dead = st.fixed + st.if_dead;
+  auto bit_of = [](typename Bits<WIDE>::M m, int bit) -> int {
+    if constexpr (WIDE) return (int)((m >> bit) & 1);
+    else return (int)__builtin_amdgcn_ubfe(m, (uint32_t)bit, 1u);
+  };
   auto score = [&](int bit, int top, int size, int outside, bool valid, int index) -> moc_move_score {
-    int count = 0;
+    int count = if_dead + bit_of(st.live, bit) * if_delta;
 #pragma unroll
-    for (int p = 0; p < NP; ++p) count |= (int)((st.plane[p] >> bit) & 1) << p;
+    for (int p = 0; p < NP; ++p) count += bit_of(st.plane[p], bit) << p;
     moc_move_score sc;
-    sc.violations = valid ? st.fixed + st.if_dead + count + (int)((st.live >> bit) & 1) * if_delta : -1;
+    sc.violations = valid ? count : -1;
     sc.peak = valid ? max(max(top + size, 0), outside) : -1;
     if (want_best) {
       const uint64_t k = ((uint64_t)(uint32_t)sc.violations << 37) | ((uint64_t)(uint32_t)sc.peak << 6) | (uint32_t)index;
