@@ -301,3 +301,32 @@ def test_no_remat_order_matches_liveness_simulation(workloads, cfg):
     assert r[F["feasible"]] == 0 and w.budget == (w.pct * w.no_remat_peak) // 100
     ok, peak, dur = oracle.simulate_sequence(w.graph, w.order)
     assert ok and peak == w.no_remat_peak and dur == r[F["duration"]]
+
+
+def test_best_move_order_does_not_depend_on_the_budget():
+    """The documented order of the best move is (violations, max(peak, M), peak, move index).
+    max(peak, M) never decreases with the peak and its ties are broken by the peak itself, so
+    the order is the one by (violations, peak, move index) for every budget M: the oracle's
+    choice (made with the four keys) must agree with a three-key sort of its own score table,
+    with budgets below, between and above the peaks."""
+    rng = np.random.default_rng(11)
+    n, C, R = 9, 2, 3
+    edges = sorted({(int(u), v) for v in range(1, n) for u in rng.integers(0, v, size=2)})
+    g = graph_from_edges(n, edges, rng.integers(1, 30, n), rng.integers(1, 9, n))
+    T = n * C
+    for trial in range(6):
+        s = rng.integers(0, T, T).astype(np.int32)
+        e = np.maximum(s, rng.integers(0, T, T)).astype(np.int32)
+        a = (rng.random(T) < 0.7).astype(np.uint8)
+        a[::C] = 1
+        picks = None
+        for budget in (0, 10, 40, 80, 10**9):
+            scores, best = oracle.neighbours(g, budget, C, s, e, a, R)
+            ok = scores[:, 0] >= 0
+            assert ok.any()
+            idx = np.flatnonzero(ok)
+            order = np.lexsort((idx, scores[idx, 1], scores[idx, 0]))
+            q = int(idx[order[0]])
+            assert best == (q, int(scores[q, 0]), int(scores[q, 1])), (trial, budget)
+            picks = best if picks is None else picks
+            assert best == picks   # the same move for every budget
