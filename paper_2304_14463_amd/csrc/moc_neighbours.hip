@@ -85,7 +85,6 @@ __device__ __forceinline__ uint32_t pack_copy(bool live, int s, int e) {
 __device__ __forceinline__ bool bit_at(const uint32_t* bits, int t) { return (bits[t >> 5] >> (t & 31)) & 1u; }
 
 struct AddOp { static __device__ int id() { return 0; } static __device__ int op(int a, int b) { return a + b; } };
-struct MaxOp { static __device__ int id() { return 0; } static __device__ int op(int a, int b) { return max(a, b); } };
 
 // Inclusive scan of dst[idx(0..T-1)] <- src, in place allowed; REV scans from the top.
 template <typename Op, bool REV>
@@ -111,6 +110,50 @@ __device__ void block_scan(const int32_t* src, int32_t* dst, int T, int32_t* scr
   for (int i = lo; i < hi; ++i) {
     run = Op::op(run, src[at(i)]);
     dst[at(i)] = run;
+  }
+  __syncthreads();
+}
+
+// dst_up[t] = max(src[0..t]) and dst_down[t] = max(src[t..T-1]) in one pass (src >= 0).
+__device__ void block_max_both_ways(const int32_t* src, int32_t* dst_up, int32_t* dst_down, int T, int32_t* scratch,
+                                    int tid) {
+  const int lane = tid & (kWave - 1), wave = tid / kWave;
+  const int L = (T + kNT - 1) / kNT;
+  const int lo = tid * L, hi = min(lo + L, T);
+  int up = 0, down = 0;
+  for (int i = lo; i < hi; ++i) {
+    up = max(up, src[i]);
+    down = max(down, src[T - 1 - i]);
+  }
+  int inc_up = up, inc_down = down;
+#pragma unroll
+  for (int off = 1; off < kWave; off <<= 1) {
+    const int a = __shfl_up(inc_up, off), b = __shfl_up(inc_down, off);
+    if (lane >= off) {
+      inc_up = max(inc_up, a);
+      inc_down = max(inc_down, b);
+    }
+  }
+  if (lane == kWave - 1) {
+    scratch[wave] = inc_up;
+    scratch[kNW + wave] = inc_down;
+  }
+  __syncthreads();
+  int run_up = 0, run_down = 0;
+  for (int w = 0; w < wave; ++w) {
+    run_up = max(run_up, scratch[w]);
+    run_down = max(run_down, scratch[kNW + w]);
+  }
+  const int prev_up = __shfl_up(inc_up, 1), prev_down = __shfl_up(inc_down, 1);
+  if (lane != 0) {
+    run_up = max(run_up, prev_up);
+    run_down = max(run_down, prev_down);
+  }
+  for (int i = lo; i < hi; ++i) {
+    run_up = max(run_up, src[i]);
+    dst_up[i] = run_up;
+    run_down = max(run_down, src[T - 1 - i]);
+    dst_down[T - 1 - i] = run_down;
   }
   __syncthreads();
 }
@@ -189,10 +232,10 @@ __device__ __forceinline__ void score_move(const Adj& g, int C, int sz, const Nb
   sc.peak = pk;
 }
 
-
-// Sets of displacements as bit masks: bit d stands for the move with index d of one
-// (copy, field), d = 0..2R-1 for the displacements -R..-1, +1..+R.  32 bits serve R <= 15,
-// 64 bits any R this call accepts.
+// Sets of moves of one (copy, field) as bit masks.  32 bits serve R <= 15: one bit per
+// position first..first+2R around the old one, the old position itself (no move) included.
+// 64 bits serve any R this call accepts: one bit per move, d = 0..2R-1 for the displacements
+// -R..-1, +1..+R.  below(x, D): the bits under x, clamped to the D bits in use.
 template <bool WIDE>
 struct Bits;
 template <>
@@ -262,8 +305,7 @@ __device__ __forceinline__ void build_field(const Adj& A, int C, int sz, const N
   };
   const M in_dom = lt(T) & ~lt(0);
   const M live = in_dom & (field == 0 ? lt(e + 1) : ~lt(s));   // start <= end after the move
-  // Eq. (3): the live neighbours of copy i among the copies of v, and the violations
-  // between other consecutive live copies
+  // Eq. (3): the live neighbours of copy i among the copies of v
   const uint32_t* const row = L.packed + v * C;
   int prev_end = -1, next_start = kNoCopy;
   for (int j = 0; j < C; ++j) {
@@ -493,55 +535,27 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
     if (tid < 4) counts[tid] = 0;
     if (tid == 0) { L.pmax[-1] = 0; L.smax[T] = 0; }
     __syncthreads();
+    // The active copies are listed from the front of `list`, the inactive ones from the back
+    // (whole waves, so that a ballot gives each lane its place).
     int viol = 0, nlive = 0;
-    for (int k = tid; k < T; k += kNT) {
-      const int s = starts[row + k], e = ends[row + k];
-      const bool act = active[row + k] != 0;
-      const bool live = act && (uint32_t)s <= (uint32_t)e && (uint32_t)e < (uint32_t)T;
-      const int v = C == 1 ? k : (int)__umulhi((uint32_t)k, c_magic);
-      L.packed[k] = pack_copy(live, s, e);
-      if (k == v * C && !act) ++viol;   // Eq. (7)
-      if (live) {
-        ++nlive;
-        const int sz = g.size_dur[v].x;
-        atomicAdd(&L.profile[s], sz);
-        if (e + 1 < T) atomicSub(&L.profile[e + 1], sz);
-        const uint32_t bit = 1u << (s & 31);
-        const uint32_t old = atomicOr(&L.occ1[s >> 5], bit);
-        if (old & bit) atomicOr(&L.occ2[s >> 5], bit);
-      }
-    }
-    __syncthreads();
-    block_scan<AddOp, false>(L.profile, L.profile, T, L.scratch, tid);   // Eq. (4) per position
-    block_scan<MaxOp, false>(L.profile, L.pmax, T, L.scratch, tid);
-    block_scan<MaxOp, true>(L.profile, L.smax, T, L.scratch, tid);
-
-    // ---- pass 1: f(old copy) per copy; base violation count; the lists of active copies
-    // (from the front of `list`) and of inactive ones (from the back)
     for (int k0 = wave * kWave; k0 < T; k0 += kNT) {
       const int k = k0 + lane;
       bool act = false;
       if (k < T) {
-        const int v = C == 1 ? k : (int)__umulhi((uint32_t)k, c_magic), i = k - v * C;
         const int s = starts[row + k], e = ends[row + k];
         act = active[row + k] != 0;
-        const bool live = live_of(L.packed[k]);
-        // base count: each instance once -- form, the order pair that copy k opens, its inputs
-        viol += (act && !live) ? 1 : 0;
+        const bool live = act && (uint32_t)s <= (uint32_t)e && (uint32_t)e < (uint32_t)T;
+        const int v = C == 1 ? k : (int)__umulhi((uint32_t)k, c_magic);
+        L.packed[k] = pack_copy(live, s, e);
+        if (k == v * C && !act) ++viol;   // Eq. (7)
         if (live) {
-          for (int j = i + 1; j < C; ++j) {
-            const uint32_t p = L.packed[v * C + j];
-            if (live_of(p)) {
-              viol += e > (int)(p & 0xFFFFu) ? 1 : 0;
-              break;
-            }
-          }
-          for (int q = A.in_ptr[v]; q < A.in_ptr[v + 1]; ++q) {
-            const int u = A.in_idx[q];
-            bool cov = false;
-            for (int j = 0; j < C; ++j) cov = cov || covers1(L.packed[u * C + j], (uint32_t)s);
-            viol += cov ? 0 : 1;
-          }
+          ++nlive;
+          const int sz = g.size_dur[v].x;
+          atomicAdd(&L.profile[s], sz);
+          if (e + 1 < T) atomicSub(&L.profile[e + 1], sz);
+          const uint32_t bit = 1u << (s & 31);
+          const uint32_t old = atomicOr(&L.occ1[s >> 5], bit);
+          if (old & bit) atomicOr(&L.occ2[s >> 5], bit);
         }
       }
       const uint64_t am = __ballot(act), im = __ballot(k < T && !act);
@@ -556,11 +570,41 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
       if (act) L.list[abase + __popcll(am & below)] = (uint16_t)k;
       else if (k < T) L.list[T - 1 - ibase - __popcll(im & below)] = (uint16_t)k;
     }
+    __syncthreads();
+    block_scan<AddOp, false>(L.profile, L.profile, T, L.scratch, tid);   // Eq. (4) per position
+    block_max_both_ways(L.profile, L.pmax, L.smax, T, L.scratch, tid);
+
+    // ---- pass 1: the violations of the base, each instance once: per active copy its form,
+    // the order pair it opens and its inputs
+    const int n_active = counts[1];
+    for (int j = tid; j < n_active; j += kNT) {
+      const int k = L.list[j];
+      const uint32_t mine = L.packed[k];
+      if (!live_of(mine)) {   // Eq. (2)/(8)
+        ++viol;
+        continue;
+      }
+      const int v = C == 1 ? k : (int)__umulhi((uint32_t)k, c_magic), i = k - v * C;
+      const int s = (int)(mine & 0xFFFFu), e = (int)(mine >> 16);
+      for (int jj = i + 1; jj < C; ++jj) {   // Eq. (3)
+        const uint32_t p = L.packed[v * C + jj];
+        if (live_of(p)) {
+          viol += e > (int)(p & 0xFFFFu) ? 1 : 0;
+          break;
+        }
+      }
+      for (int q = A.in_ptr[v]; q < A.in_ptr[v + 1]; ++q) {   // Eq. (5)
+        const int u = A.in_idx[q];
+        bool cov = false;
+        for (int jj = 0; jj < C; ++jj) cov = cov || covers1(L.packed[u * C + jj], (uint32_t)s);
+        viol += cov ? 0 : 1;
+      }
+    }
     int distinct = 0;
     for (int w = tid; w < lay.bit_words; w += kNT) distinct += __popc(L.occ1[w]);
     atomicAdd(&counts[0], viol + nlive - distinct);   // Eq. (6): live copies - distinct starts
     __syncthreads();
-    const int base_viol = counts[0], n_active = counts[1];
+    const int base_viol = counts[0];
     const int base_peak = L.pmax[T - 1];
 
     // ---- pass 2: one lane per (active copy, field), start moves first; the waves draw
