@@ -48,9 +48,10 @@ NbLayout nb_layout(int T, int n, int m, int max_lds) {
   const int words = 4 * l.T_pad + l.T_pad / 2 + 8 + 2 * l.bit_words + 8 * kNW + 16;
   l.adj_off = 0;
   l.bytes = 4 * words;
-  // the CSR lists both ways, if that costs no resident workgroup (two of 16 waves fit a CU):
-  // every move walks the edges of its node
-  const int with_adj = 4 * (words + 2 * (n + 1) + 2 * m);
+  // The CSR lists both ways and the sizes, which every move reads, if that costs no resident
+  // workgroup (two of 16 waves fit a CU).  (At T = 4000 it would: with them in LDS and one
+  // workgroup per CU the table of scores takes 4.2 ms instead of 3.6.)
+  const int with_adj = 4 * (words + 2 * (n + 1) + 2 * m + n);
   if (with_adj <= max_lds && std::min(max_lds / with_adj, 2) >= std::min(max_lds / l.bytes, 2)) {
     l.adj_off = words;
     l.bytes = with_adj;
@@ -64,6 +65,9 @@ struct Adj {
   const int32_t* in_idx;
   const int32_t* out_ptr;
   const int32_t* out_idx;
+  const int32_t* size;   // m_v, one word per node (LDS) or per two words (the graph's {m_v, w_v} pairs)
+  int size_stride;
+  __device__ __forceinline__ int size_of(int v) const { return size[v * size_stride]; }
 };
 
 struct NbLds {
@@ -260,6 +264,13 @@ constexpr int kNoCopy = 0x3FFFFFFF;  // start of a copy that does not exist
 struct Best {
   int viol, peak, move;   // move < 0: none
 };
+
+// Plain stores: a lane writes its row of scores in 16-byte pieces, which the L2 puts together;
+// with the non-temporal hint the table takes four times as long.
+__device__ __forceinline__ void store_score(moc_move_score* at, const moc_move_score& sc) { *at = sc; }
+__device__ __forceinline__ void store_pair(moc_move_score* at, const moc_move_score& lo, const moc_move_score& hi) {   // 16-byte aligned
+  *reinterpret_cast<int4*>(at) = make_int4(lo.violations, lo.peak, hi.violations, hi.peak);
+}
 
 // Order of the best move: (violations, max(peak, budget), peak, move index).  max(peak, budget)
 // never decreases with the peak and its ties are broken by the peak, so this is the order
@@ -470,16 +481,16 @@ __device__ __forceinline__ void walk_own(const FieldState<WIDE>& st, const NbLds
     for (int j = 1; j < R; j += 2) {
       const moc_move_score a0 = down(j), b0 = up(j), a1 = down(j + 1), b1 = up(j + 1);
       if (dst) {
-        *reinterpret_cast<int4*>(dst + (R - j - 1)) = make_int4(a1.violations, a1.peak, a0.violations, a0.peak);
-        *reinterpret_cast<int4*>(dst + (R + j - 1)) = make_int4(b0.violations, b0.peak, b1.violations, b1.peak);
+        store_pair(dst + (R - j - 1), a1, a0);
+        store_pair(dst + (R + j - 1), b0, b1);
       }
     }
   } else {
     for (int j = 1; j <= R; ++j) {
       const moc_move_score a0 = down(j), b0 = up(j);
       if (dst) {
-        dst[R - j] = a0;
-        dst[R + j - 1] = b0;
+        store_score(dst + (R - j), a0);
+        store_score(dst + (R + j - 1), b0);
       }
     }
   }
@@ -518,12 +529,14 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
   const int rem = four_r <= kWave ? lane - sub * four_r : lane;
   int32_t* const counts = L.scratch + 8 * kNW;   // [0] base violations, [1] active copies, [2] inactive copies, [3] work drawn
   const bool pairs = (R & 1) == 0 && (reinterpret_cast<uintptr_t>(out_moves) & 15) == 0;   // scores stored two at a time
-  Adj A{g.in_ptr, g.in_idx, g.out_ptr, g.out_idx};
-  if constexpr (ADJ_LDS) {   // the adjacency lists are read by every move: keep them in LDS
+  Adj A{g.in_ptr, g.in_idx, g.out_ptr, g.out_idx, reinterpret_cast<const int32_t*>(g.size_dur), 2};
+  if constexpr (ADJ_LDS) {   // the adjacency lists and sizes are read by every move: keep them in LDS
     int32_t* a = reinterpret_cast<int32_t*>(nb_raw) + lay.adj_off;
+    int32_t* const sizes = a + 2 * (g.n + 1) + 2 * g.m;
     for (int x = tid; x <= g.n; x += kNT) { a[x] = g.in_ptr[x]; a[g.n + 1 + g.m + x] = g.out_ptr[x]; }
     for (int x = tid; x < g.m; x += kNT) { a[g.n + 1 + x] = g.in_idx[x]; a[2 * (g.n + 1) + g.m + x] = g.out_idx[x]; }
-    A = Adj{a, a + g.n + 1, a + g.n + 1 + g.m, a + 2 * (g.n + 1) + g.m};
+    for (int x = tid; x < g.n; x += kNT) sizes[x] = g.size_dur[x].x;
+    A = Adj{a, a + g.n + 1, a + g.n + 1 + g.m, a + 2 * (g.n + 1) + g.m, sizes, 1};
     __syncthreads();
   }
 
@@ -550,7 +563,7 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
         if (k == v * C && !act) ++viol;   // Eq. (7)
         if (live) {
           ++nlive;
-          const int sz = g.size_dur[v].x;
+          const int sz = A.size_of(v);
           atomicAdd(&L.profile[s], sz);
           if (e + 1 < T) atomicSub(&L.profile[e + 1], sz);
           const uint32_t bit = 1u << (s & 31);
@@ -576,7 +589,7 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
 
     // ---- pass 1: the violations of the base, each instance once: per active copy its form,
     // the order pair it opens and its inputs
-    const int n_active = counts[1];
+    const int n_active = __builtin_amdgcn_readfirstlane(counts[1]);
     for (int j = tid; j < n_active; j += kNT) {
       const int k = L.list[j];
       const uint32_t mine = L.packed[k];
@@ -604,8 +617,8 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
     for (int w = tid; w < lay.bit_words; w += kNT) distinct += __popc(L.occ1[w]);
     atomicAdd(&counts[0], viol + nlive - distinct);   // Eq. (6): live copies - distinct starts
     __syncthreads();
-    const int base_viol = counts[0];
-    const int base_peak = L.pmax[T - 1];
+    const int base_viol = __builtin_amdgcn_readfirstlane(counts[0]);   // the same in every lane: scalar registers
+    const int base_peak = __builtin_amdgcn_readfirstlane(L.pmax[T - 1]);
 
     // ---- pass 2: one lane per (active copy, field), start moves first; the waves draw
     // 64 of these at a time
@@ -622,7 +635,7 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
       const int k = has_unit ? L.list[u - field * n_active] : 0;
       const int v = C == 1 ? k : (int)__umulhi((uint32_t)k, c_magic), i = k - v * C;
       const int q0 = (2 * k + field) * two_r;
-      const int sz = g.size_dur[v].x;
+      const int sz = A.size_of(v);
       FieldState<WIDE> st{};
       st.field = -1;
       if (has_unit && live_of(L.packed[k]))
@@ -646,7 +659,7 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
             const Best cand{sc.violations, sc.peak, q0 + d};
             if (better(cand, best)) best = cand;
           }
-          if (row0) row0[q0 + d] = sc;
+          if (row0) store_score(row0 + q0 + d, sc);
         }
       }
     }
@@ -660,7 +673,7 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
         const int entry = grp * per_wave + sub;
         if (sub >= per_wave || entry >= n_inactive || in_copy >= four_r) continue;
         const int k = L.list[n_active + entry];
-        out_moves[b * (int64_t)moves_per_cand + k * four_r + in_copy] = moc_move_score{-1, -1};
+        store_score(out_moves + (b * (int64_t)moves_per_cand + k * four_r + in_copy), moc_move_score{-1, -1});
       }
     }
     // ---- best move of the candidate
