@@ -267,9 +267,14 @@ struct Best {
 
 // Plain stores: a lane writes its row of scores in 16-byte pieces, which the L2 puts together;
 // with the non-temporal hint the table takes four times as long.
-__device__ __forceinline__ void store_score(moc_move_score* at, const moc_move_score& sc) { *at = sc; }
-__device__ __forceinline__ void store_pair(moc_move_score* at, const moc_move_score& lo, const moc_move_score& hi) {   // 16-byte aligned
-  *reinterpret_cast<int4*>(at) = make_int4(lo.violations, lo.peak, hi.violations, hi.peak);
+// `table` is the candidate's table (the same in every lane: a scalar base), `index` the move.
+__device__ __forceinline__ void store_score(moc_move_score* table, uint32_t index, const moc_move_score& sc) {
+  *reinterpret_cast<moc_move_score*>(reinterpret_cast<char*>(table) + (size_t)(index * 8u)) = sc;
+}
+__device__ __forceinline__ void store_pair(moc_move_score* table, uint32_t index, const moc_move_score& lo,
+                                           const moc_move_score& hi) {   // 16-byte aligned
+  *reinterpret_cast<int4*>(reinterpret_cast<char*>(table) + (size_t)(index * 8u)) =
+      make_int4(lo.violations, lo.peak, hi.violations, hi.peak);
 }
 
 // Order of the best move: (violations, max(peak, budget), peak, move index).  max(peak, budget)
@@ -435,7 +440,7 @@ __device__ __forceinline__ void build_field(const Adj& A, int C, int sz, const N
 // has violations -1, the largest key).
 template <int NP, bool WIDE>
 __device__ __forceinline__ void walk_own(const FieldState<WIDE>& st, const NbLds& L, int T, int R, bool want_best,
-                                         bool pairs, moc_move_score* __restrict__ dst, Best& best) {
+                                         bool pairs, moc_move_score* __restrict__ table, Best& best) {
   const int base = st.field == 0 ? st.s : st.e;
   const bool start_moves = st.field == 0;
   // down: a start gains [moved, s-1], an end loses [max(moved+1, s), e]
@@ -477,20 +482,20 @@ __device__ __forceinline__ void walk_own(const FieldState<WIDE>& st, const NbLds
     top_up = max(top_up, L.profile[far]);
     return score(WIDE ? R + j - 1 : R + j, top_up, size_up, max(before_up, L.smax[far + 1]), base + j < T, R + j - 1);
   };
-  if (pairs) {   // R even, dst 16-byte aligned: two scores per store
+  if (pairs) {   // R even, the table 16-byte aligned: two scores per store
     for (int j = 1; j < R; j += 2) {
       const moc_move_score a0 = down(j), b0 = up(j), a1 = down(j + 1), b1 = up(j + 1);
-      if (dst) {
-        store_pair(dst + (R - j - 1), a1, a0);
-        store_pair(dst + (R + j - 1), b0, b1);
+      if (table) {
+        store_pair(table, (uint32_t)(st.q0 + R - j - 1), a1, a0);
+        store_pair(table, (uint32_t)(st.q0 + R + j - 1), b0, b1);
       }
     }
   } else {
     for (int j = 1; j <= R; ++j) {
       const moc_move_score a0 = down(j), b0 = up(j);
-      if (dst) {
-        store_score(dst + (R - j), a0);
-        store_score(dst + (R + j - 1), b0);
+      if (table) {
+        store_score(table, (uint32_t)(st.q0 + R - j), a0);
+        store_score(table, (uint32_t)(st.q0 + R + j - 1), b0);
       }
     }
   }
@@ -542,6 +547,7 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
 
   for (int64_t b = blockIdx.x; b < B; b += gridDim.x) {
     const int64_t row = b * T;
+    moc_move_score* const row0 = out_moves ? out_moves + b * (int64_t)moves_per_cand : nullptr;   // this candidate's table
     // ---- base candidate: stage copies, scatter deltas, mark starts
     for (int t = tid; t < T; t += kNT) L.profile[t] = 0;
     for (int w = tid; w < 2 * lay.bit_words; w += kNT) L.occ1[w] = 0;
@@ -640,13 +646,12 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
       st.field = -1;
       if (has_unit && live_of(L.packed[k]))
         build_field<CT, WIDE>(A, C, sz, L, T, R, v, i, field, L.packed[k], base_viol, q0, st);
-      moc_move_score* const row0 = out_moves ? out_moves + b * (int64_t)moves_per_cand : nullptr;
       if (st.field >= 0) {
         bool high = false;   // counts above 7 in some lane
 #pragma unroll
         for (int p = 3; p < kPlanes; ++p) high = high || Bits<WIDE>::any(st.plane[p]);
-        if (high) walk_own<kPlanes, WIDE>(st, L, T, R, out_best != nullptr, pairs, row0 ? row0 + q0 : nullptr, best);
-        else walk_own<3, WIDE>(st, L, T, R, out_best != nullptr, pairs, row0 ? row0 + q0 : nullptr, best);
+        if (high) walk_own<kPlanes, WIDE>(st, L, T, R, out_best != nullptr, pairs, row0, best);
+        else walk_own<3, WIDE>(st, L, T, R, out_best != nullptr, pairs, row0, best);
       }
       if (has_unit && st.field < 0) {   // active and ill formed, or a node with very many edges (rare): move by move, from scratch
         const int s = starts[row + k], e = ends[row + k];
@@ -659,7 +664,7 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
             const Best cand{sc.violations, sc.peak, q0 + d};
             if (better(cand, best)) best = cand;
           }
-          if (row0) store_score(row0 + q0 + d, sc);
+          if (row0) store_score(row0, (uint32_t)(q0 + d), sc);
         }
       }
     }
@@ -673,7 +678,7 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
         const int entry = grp * per_wave + sub;
         if (sub >= per_wave || entry >= n_inactive || in_copy >= four_r) continue;
         const int k = L.list[n_active + entry];
-        store_score(out_moves + (b * (int64_t)moves_per_cand + k * four_r + in_copy), moc_move_score{-1, -1});
+        store_score(row0, (uint32_t)(k * four_r + in_copy), moc_move_score{-1, -1});
       }
     }
     // ---- best move of the candidate
@@ -747,7 +752,7 @@ extern "C" int moc_eval_neighbours(const moc_graph* g, int64_t B, const int32_t*
   if (g->has_self_loop) return MOC_EINVAL;
   const NbLayout lay = nb_layout(g->view.T, g->view.n, g->view.m, g->max_lds);
   if (lay.bytes > g->max_lds) return MOC_EOVERFLOW;
-  if ((int64_t)g->view.T * 4 * R > 0x7FFFFFFF) return MOC_EOVERFLOW;
+  if ((int64_t)g->view.T * 4 * R * 8 > 0xFFFFFFFFll) return MOC_EOVERFLOW;   // byte offsets in a candidate's table are 32 bits
   auto kern = pick_kernel(lay.adj_off != 0, g->view.C, R);
   MOC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                               lay.bytes));
