@@ -36,6 +36,7 @@ constexpr int kNW = kNT / kWave;
 struct NbLayout {
   int T_pad;      // T rounded up to 4
   int bit_words;  // ceil(T / 32)
+  int mask_words; // 2 * ceil(T / 64): the active flags, one bit per copy
   int adj_off;    // word offset of the graph's adjacency lists in LDS, 0 if they stay in global memory
   int bytes;
 };
@@ -44,8 +45,9 @@ NbLayout nb_layout(int T, int n, int m, int max_lds) {
   NbLayout l;
   l.T_pad = (T + 3) & ~3;
   l.bit_words = (T + 31) / 32;
+  l.mask_words = 2 * ((T + 63) / 64);
   // profile, prefix max, suffix max, packed, the copy lists (16 bits an entry) + two bitmaps + scratch
-  const int words = 4 * l.T_pad + l.T_pad / 2 + 8 + 2 * l.bit_words + 8 * kNW + 16;
+  const int words = 4 * l.T_pad + l.T_pad / 2 + 8 + 2 * l.bit_words + l.mask_words + 8 * kNW + 16;
   l.adj_off = 0;
   l.bytes = 4 * words;
   // The CSR lists both ways and the sizes, which every move reads, if that costs no resident
@@ -75,9 +77,10 @@ struct NbLds {
   int32_t* pmax;
   int32_t* smax;
   uint32_t* packed;
-  uint16_t* list;   // active copies from the front, inactive ones from the back
+  uint16_t* list;   // the active copies, in order
   uint32_t* occ1;
   uint32_t* occ2;
+  uint32_t* amask;  // bit k: copy k is active
   int32_t* scratch;   // 8 * kNW + 16
 };
 
@@ -520,7 +523,8 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
   L.list = reinterpret_cast<uint16_t*>(L.packed + lay.T_pad);
   L.occ1 = reinterpret_cast<uint32_t*>(L.list + lay.T_pad);
   L.occ2 = L.occ1 + lay.bit_words;
-  L.scratch = reinterpret_cast<int32_t*>(L.occ2 + lay.bit_words);
+  L.amask = L.occ2 + lay.bit_words;
+  L.scratch = reinterpret_cast<int32_t*>(L.amask + lay.mask_words);
   const int tid = threadIdx.x, lane = tid & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
   const int T = g.T, C = CT ? CT : g.C;
@@ -532,7 +536,7 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
   const int pieces = four_r <= kWave ? 1 : 2;
   const int sub = four_r <= kWave ? lane / four_r : 0;
   const int rem = four_r <= kWave ? lane - sub * four_r : lane;
-  int32_t* const counts = L.scratch + 8 * kNW;   // [0] base violations, [1] active copies, [2] inactive copies, [3] work drawn
+  int32_t* const counts = L.scratch + 8 * kNW;   // [0] base violations, [1] active copies, [3] work drawn
   const bool pairs = (R & 1) == 0 && (reinterpret_cast<uintptr_t>(out_moves) & 15) == 0;   // scores stored two at a time
   Adj A{g.in_ptr, g.in_idx, g.out_ptr, g.out_idx, reinterpret_cast<const int32_t*>(g.size_dur), 2};
   if constexpr (ADJ_LDS) {   // the adjacency lists and sizes are read by every move: keep them in LDS
@@ -554,8 +558,7 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
     if (tid < 4) counts[tid] = 0;
     if (tid == 0) { L.pmax[-1] = 0; L.smax[T] = 0; }
     __syncthreads();
-    // The active copies are listed from the front of `list`, the inactive ones from the back
-    // (whole waves, so that a ballot gives each lane its place).
+    // whole waves, 64 consecutive copies each: a ballot gives the active flags of the 64
     int viol = 0, nlive = 0;
     for (int k0 = wave * kWave; k0 < T; k0 += kNT) {
       const int k = k0 + lane;
@@ -577,19 +580,23 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
           if (old & bit) atomicOr(&L.occ2[s >> 5], bit);
         }
       }
-      const uint64_t am = __ballot(act), im = __ballot(k < T && !act);
-      int abase = 0, ibase = 0;
+      const uint64_t am = __ballot(act);
       if (lane == 0) {
-        abase = atomicAdd(&counts[1], __popcll(am));
-        ibase = atomicAdd(&counts[2], __popcll(im));
+        L.amask[k0 >> 5] = (uint32_t)am;
+        L.amask[(k0 >> 5) + 1] = (uint32_t)(am >> 32);
+        atomicAdd(&counts[1], __popcll(am));
       }
-      abase = __shfl(abase, 0);
-      ibase = __shfl(ibase, 0);
-      const uint64_t below = ((uint64_t)1 << lane) - 1;
-      if (act) L.list[abase + __popcll(am & below)] = (uint16_t)k;
-      else if (k < T) L.list[T - 1 - ibase - __popcll(im & below)] = (uint16_t)k;
     }
     __syncthreads();
+    // the active copies in order: those of 64 copies go behind those of the copies before
+    for (int c = wave; c < lay.mask_words / 2; c += kNW) {
+      int before = 0;
+      for (int x = lane; x < c; x += kWave) before += __popc(L.amask[2 * x]) + __popc(L.amask[2 * x + 1]);
+#pragma unroll
+      for (int off = kWave / 2; off > 0; off >>= 1) before += __shfl_xor(before, off);
+      const uint64_t am = (uint64_t)L.amask[2 * c] | ((uint64_t)L.amask[2 * c + 1] << 32);
+      if ((am >> lane) & 1) L.list[before + __popcll(am & (((uint64_t)1 << lane) - 1))] = (uint16_t)(c * kWave + lane);
+    }
     block_scan<AddOp, false>(L.profile, L.profile, T, L.scratch, tid);   // Eq. (4) per position
     block_max_both_ways(L.profile, L.pmax, L.smax, T, L.scratch, tid);
 
@@ -626,19 +633,31 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
     const int base_viol = __builtin_amdgcn_readfirstlane(counts[0]);   // the same in every lane: scalar registers
     const int base_peak = __builtin_amdgcn_readfirstlane(L.pmax[T - 1]);
 
-    // ---- pass 2: one lane per (active copy, field), start moves first; the waves draw
-    // 64 of these at a time
+    // ---- pass 2: one lane per (active copy, field); the waves draw 64 of these at a time.
+    // For the best move alone: start moves first, so that all lanes of a wave run the same
+    // field's code.  With the table of scores: both fields of 32 consecutive active copies, and
+    // the same wave then fills the rows of the inactive copies between them, so that it
+    // writes one contiguous stretch of the table (HBM takes long runs much faster than
+    // scattered 128-byte rows).
     Best best{0, 0, -1};
-    const int units = 2 * n_active;
+    const bool table = out_moves != nullptr;
+    const int draw = table ? kWave / 2 : kWave;
+    const int total = table ? max(n_active, 1) : 2 * n_active;
     for (;;) {
       int u0 = 0;
-      if (lane == 0) u0 = atomicAdd(&counts[3], kWave);
+      if (lane == 0) u0 = atomicAdd(&counts[3], draw);
       u0 = __builtin_amdgcn_readfirstlane(u0);
-      if (u0 >= units) break;
-      const int u = u0 + lane;
-      const bool has_unit = u < units;
-      const int field = u >= n_active ? 1 : 0;
-      const int k = has_unit ? L.list[u - field * n_active] : 0;
+      if (u0 >= total) break;
+      int entry, field;
+      if (table) {
+        entry = u0 + (lane & 31);
+        field = lane >> 5;
+      } else {
+        field = u0 + lane >= n_active ? 1 : 0;
+        entry = u0 + lane - field * n_active;
+      }
+      const bool has_unit = entry < n_active;
+      const int k = has_unit ? L.list[entry] : 0;
       const int v = C == 1 ? k : (int)__umulhi((uint32_t)k, c_magic), i = k - v * C;
       const int q0 = (2 * k + field) * two_r;
       const int sz = A.size_of(v);
@@ -667,18 +686,17 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
           if (row0) store_score(row0, (uint32_t)(q0 + d), sc);
         }
       }
-    }
-    // ---- the moves of inactive copies are not applicable
-    if (out_moves) {
-      const int n_inactive = T - n_active;
-      const int fill_groups = (n_inactive + per_wave - 1) / per_wave;
-      for (int it = wave; it < fill_groups * pieces; it += kNW) {
-        const int grp = pieces == 1 ? it : it >> 1;
-        const int in_copy = pieces == 1 ? rem : rem + (it & 1) * kWave;
-        const int entry = grp * per_wave + sub;
-        if (sub >= per_wave || entry >= n_inactive || in_copy >= four_r) continue;
-        const int k = L.list[n_active + entry];
-        store_score(row0, (uint32_t)(k * four_r + in_copy), moc_move_score{-1, -1});
+      if (table) {   // the moves of the inactive copies from this block's first copy to the next block's are not applicable
+        const int k_lo = u0 == 0 ? 0 : (int)L.list[u0];
+        const int k_hi = u0 + draw < n_active ? (int)L.list[u0 + draw] : T;
+        for (int kk0 = k_lo; kk0 < k_hi; kk0 += per_wave) {
+          const int kk = kk0 + sub;
+          const bool fill = sub < per_wave && kk < k_hi && !((L.amask[kk >> 5] >> (kk & 31)) & 1u);
+          for (int piece = 0; piece < pieces; ++piece) {
+            const int in_copy = rem + piece * kWave;
+            if (fill && in_copy < four_r) store_score(row0, (uint32_t)(kk * four_r + in_copy), moc_move_score{-1, -1});
+          }
+        }
       }
     }
     // ---- best move of the candidate
