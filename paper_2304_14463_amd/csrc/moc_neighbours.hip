@@ -508,7 +508,7 @@ __device__ __forceinline__ void walk_own(const FieldState<WIDE>& st, const NbLds
   }
 }
 
-template <bool ADJ_LDS, int CT, bool WIDE>
+template <bool ADJ_LDS, int CT, bool WIDE, bool TABLE>
 __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) void neighbours_kernel(GraphView g, int64_t B, const int32_t* __restrict__ starts,
                                                          const int32_t* __restrict__ ends,
                                                          const uint8_t* __restrict__ active, int R,
@@ -537,7 +537,7 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
   const int sub = four_r <= kWave ? lane / four_r : 0;
   const int rem = four_r <= kWave ? lane - sub * four_r : lane;
   int32_t* const counts = L.scratch + 8 * kNW;   // [0] base violations, [1] active copies, [3] work drawn
-  const bool pairs = (R & 1) == 0 && (reinterpret_cast<uintptr_t>(out_moves) & 15) == 0;   // scores stored two at a time
+  const bool pairs = TABLE && (R & 1) == 0 && (reinterpret_cast<uintptr_t>(out_moves) & 15) == 0;   // scores stored two at a time
   Adj A{g.in_ptr, g.in_idx, g.out_ptr, g.out_idx, reinterpret_cast<const int32_t*>(g.size_dur), 2};
   if constexpr (ADJ_LDS) {   // the adjacency lists and sizes are read by every move: keep them in LDS
     int32_t* a = reinterpret_cast<int32_t*>(nb_raw) + lay.adj_off;
@@ -551,7 +551,7 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
 
   for (int64_t b = blockIdx.x; b < B; b += gridDim.x) {
     const int64_t row = b * T;
-    moc_move_score* const row0 = out_moves ? out_moves + b * (int64_t)moves_per_cand : nullptr;   // this candidate's table
+    moc_move_score* const row0 = TABLE && out_moves ? out_moves + b * (int64_t)moves_per_cand : nullptr;   // this candidate's table
     // ---- base candidate: stage copies, scatter deltas, mark starts
     for (int t = tid; t < T; t += kNT) L.profile[t] = 0;
     for (int w = tid; w < 2 * lay.bit_words; w += kNT) L.occ1[w] = 0;
@@ -640,7 +640,11 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
     // writes one contiguous stretch of the table (HBM takes long runs much faster than
     // scattered 128-byte rows).
     Best best{0, 0, -1};
-    const bool table = out_moves != nullptr;
+    // (TABLE = false compiles the stores away: fewer registers for the best move alone.  With
+    // TABLE the pointer is still tested where it was before the kernel was specialised: the
+    // build that knows it to be set orders its waits differently and takes 3.5 ms for the table
+    // instead of 3.0.)
+    const bool table = TABLE && out_moves != nullptr;
     const int draw = table ? kWave / 2 : kWave;
     const int total = table ? max(n_active, 1) : 2 * n_active;
     for (;;) {
@@ -736,21 +740,26 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
 using NbKernel = void (*)(GraphView, int64_t, const int32_t*, const int32_t*, const uint8_t*, int, moc_move_score*,
                           moc_best_move*, NbLayout);
 
-template <bool ADJ_LDS, bool WIDE>
+template <bool ADJ_LDS, bool WIDE, bool TABLE>
 NbKernel pick_copies(int C) {
   switch (C) {
-    case 1: return neighbours_kernel<ADJ_LDS, 1, WIDE>;
-    case 2: return neighbours_kernel<ADJ_LDS, 2, WIDE>;
-    case 3: return neighbours_kernel<ADJ_LDS, 3, WIDE>;
-    case 4: return neighbours_kernel<ADJ_LDS, 4, WIDE>;
-    default: return neighbours_kernel<ADJ_LDS, 0, WIDE>;   // C read at run time
+    case 1: return neighbours_kernel<ADJ_LDS, 1, WIDE, TABLE>;
+    case 2: return neighbours_kernel<ADJ_LDS, 2, WIDE, TABLE>;
+    case 3: return neighbours_kernel<ADJ_LDS, 3, WIDE, TABLE>;
+    case 4: return neighbours_kernel<ADJ_LDS, 4, WIDE, TABLE>;
+    default: return neighbours_kernel<ADJ_LDS, 0, WIDE, TABLE>;   // C read at run time
   }
 }
 
-NbKernel pick_kernel(bool adj_lds, int C, int R) {
+template <bool ADJ_LDS, bool WIDE>
+NbKernel pick_table(int C, bool table) {
+  return table ? pick_copies<ADJ_LDS, WIDE, true>(C) : pick_copies<ADJ_LDS, WIDE, false>(C);
+}
+
+NbKernel pick_kernel(bool adj_lds, int C, int R, bool table) {
   const bool wide = 2 * R > 31;   // 64-bit displacement masks
-  if (adj_lds) return wide ? pick_copies<true, true>(C) : pick_copies<true, false>(C);
-  return wide ? pick_copies<false, true>(C) : pick_copies<false, false>(C);
+  if (adj_lds) return wide ? pick_table<true, true>(C, table) : pick_table<true, false>(C, table);
+  return wide ? pick_table<false, true>(C, table) : pick_table<false, false>(C, table);
 }
 
 }  // namespace
@@ -771,7 +780,7 @@ extern "C" int moc_eval_neighbours(const moc_graph* g, int64_t B, const int32_t*
   const NbLayout lay = nb_layout(g->view.T, g->view.n, g->view.m, g->max_lds);
   if (lay.bytes > g->max_lds) return MOC_EOVERFLOW;
   if ((int64_t)g->view.T * 4 * R * 8 > 0xFFFFFFFFll) return MOC_EOVERFLOW;   // byte offsets in a candidate's table are 32 bits
-  auto kern = pick_kernel(lay.adj_off != 0, g->view.C, R);
+  auto kern = pick_kernel(lay.adj_off != 0, g->view.C, R, out_moves != nullptr);
   MOC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                               lay.bytes));
   int per_cu = 0;
