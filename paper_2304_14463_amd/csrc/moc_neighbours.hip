@@ -536,7 +536,7 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
   const int pieces = four_r <= kWave ? 1 : 2;
   const int sub = four_r <= kWave ? lane / four_r : 0;
   const int rem = four_r <= kWave ? lane - sub * four_r : lane;
-  int32_t* const counts = L.scratch + 8 * kNW;   // [0] base violations, [1] active copies, [3] work drawn
+  int32_t* const counts = L.scratch + 8 * kNW;   // [0] base violations, [1] active copies, [2] fewest violations of a move so far, [3] work drawn
   const bool pairs = TABLE && (R & 1) == 0 && (reinterpret_cast<uintptr_t>(out_moves) & 15) == 0;   // scores stored two at a time
   Adj A{g.in_ptr, g.in_idx, g.out_ptr, g.out_idx, reinterpret_cast<const int32_t*>(g.size_dur), 2};
   if constexpr (ADJ_LDS) {   // the adjacency lists and sizes are read by every move: keep them in LDS
@@ -555,7 +555,7 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
     // ---- base candidate: stage copies, scatter deltas, mark starts
     for (int t = tid; t < T; t += kNT) L.profile[t] = 0;
     for (int w = tid; w < 2 * lay.bit_words; w += kNT) L.occ1[w] = 0;
-    if (tid < 4) counts[tid] = 0;
+    if (tid < 4) counts[tid] = tid == 2 ? 0x7FFFFFFF : 0;
     if (tid == 0) { L.pmax[-1] = 0; L.smax[T] = 0; }
     __syncthreads();
     // whole waves, 64 consecutive copies each: a ballot gives the active flags of the 64
@@ -640,6 +640,7 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
     // writes one contiguous stretch of the table (HBM takes long runs much faster than
     // scattered 128-byte rows).
     Best best{0, 0, -1};
+    int published = 0x7FFFFFFF;   // the lane's fewest violations as far as the workgroup has been told
     // (TABLE = false compiles the stores away: fewer registers for the best move alone.  With
     // TABLE the pointer is still tested where it was before the kernel was specialised: the
     // build that knows it to be set orders its waits differently and takes 3.5 ms for the table
@@ -669,12 +670,25 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
       st.field = -1;
       if (has_unit && live_of(L.packed[k]))
         build_field<CT, WIDE>(A, C, sz, L, T, R, v, i, field, L.packed[k], base_viol, q0, st);
-      if (st.field >= 0) {
+      // For the best move alone, a field none of whose moves can have as few violations as
+      // some move already scored (by any wave of the workgroup) is not walked.
+      bool walk = st.field >= 0;
+      if constexpr (!TABLE) {
+        const int least = *const_cast<volatile int32_t*>(&counts[2]);
+        walk = walk && st.fixed + min(st.if_live, st.if_dead) <= least;
+      }
+      if (walk) {
         bool high = false;   // counts above 7 in some lane
 #pragma unroll
         for (int p = 3; p < kPlanes; ++p) high = high || Bits<WIDE>::any(st.plane[p]);
         if (high) walk_own<kPlanes, WIDE>(st, L, T, R, out_best != nullptr, pairs, row0, best);
         else walk_own<3, WIDE>(st, L, T, R, out_best != nullptr, pairs, row0, best);
+        if constexpr (!TABLE) {
+          if (best.move >= 0 && best.viol < published) {
+            published = best.viol;
+            atomicMin(&counts[2], best.viol);
+          }
+        }
       }
       if (has_unit && st.field < 0) {   // active and ill formed, or a node with very many edges (rare): move by move, from scratch
         const int s = starts[row + k], e = ends[row + k];
