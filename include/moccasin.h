@@ -151,7 +151,7 @@ int moc_eval_batch(const moc_graph* g, int64_t B, const int32_t* starts, const i
  *               minimises (violations, max(peak, M), peak, q) lexicographically
  *               (max(peak, M) is the Phase-1 objective of Section 2.4)
  * At least one of out_moves / out_best must be given; both 8-byte aligned.
- * This call keeps 4.5 words per copy in LDS: T <= about 8900.  A graph with an
+ * This call keeps 4.6 words per copy in LDS: T <= about 8800.  A graph with an
  * edge (v,v) is not accepted.
  * Errors: MOC_EINVAL, MOC_EDEVICE, MOC_EOVERFLOW (T too large for this call), MOC_EHIP.
  */

@@ -46,8 +46,8 @@ NbLayout nb_layout(int T, int n, int m, int max_lds) {
   l.T_pad = (T + 3) & ~3;
   l.bit_words = (T + 31) / 32;
   l.mask_words = 2 * ((T + 63) / 64);
-  // profile, prefix max, suffix max, packed, the copy lists (16 bits an entry) + two bitmaps + scratch
-  const int words = 4 * l.T_pad + l.T_pad / 2 + 8 + 2 * l.bit_words + l.mask_words + 8 * kNW + 16;
+  // profile, prefix max, suffix max, packed, the list of active copies (16 bits an entry) + bitmaps + scratch
+  const int words = 4 * l.T_pad + l.T_pad / 2 + 8 + 2 * l.bit_words + 2 * l.mask_words + 8 * kNW + 16;
   l.adj_off = 0;
   l.bytes = 4 * words;
   // The CSR lists both ways and the sizes, which every move reads, if that costs no resident
@@ -80,7 +80,8 @@ struct NbLds {
   uint16_t* list;   // the active copies, in order
   uint32_t* occ1;
   uint32_t* occ2;
-  uint32_t* amask;  // bit k: copy k is active
+  uint32_t* involved;   // bit k: copy k takes part in a violation of Eq. (3) or (5)
+  uint32_t* amask;      // bit k: copy k is active
   int32_t* scratch;   // 8 * kNW + 16
 };
 
@@ -523,7 +524,8 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
   L.list = reinterpret_cast<uint16_t*>(L.packed + lay.T_pad);
   L.occ1 = reinterpret_cast<uint32_t*>(L.list + lay.T_pad);
   L.occ2 = L.occ1 + lay.bit_words;
-  L.amask = L.occ2 + lay.bit_words;
+  L.involved = L.occ2 + lay.bit_words;
+  L.amask = L.involved + lay.mask_words;
   L.scratch = reinterpret_cast<int32_t*>(L.amask + lay.mask_words);
   const int tid = threadIdx.x, lane = tid & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
@@ -554,7 +556,7 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
     moc_move_score* const row0 = TABLE && out_moves ? out_moves + b * (int64_t)moves_per_cand : nullptr;   // this candidate's table
     // ---- base candidate: stage copies, scatter deltas, mark starts
     for (int t = tid; t < T; t += kNT) L.profile[t] = 0;
-    for (int w = tid; w < 2 * lay.bit_words; w += kNT) L.occ1[w] = 0;
+    for (int w = tid; w < 2 * lay.bit_words + lay.mask_words; w += kNT) L.occ1[w] = 0;   // occ1, occ2, involved
     if (tid < 4) counts[tid] = tid == 2 ? 0x7FFFFFFF : 0;
     if (tid == 0) { L.pmax[-1] = 0; L.smax[T] = 0; }
     __syncthreads();
@@ -612,10 +614,16 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
       }
       const int v = C == 1 ? k : (int)__umulhi((uint32_t)k, c_magic), i = k - v * C;
       const int s = (int)(mine & 0xFFFFu), e = (int)(mine >> 16);
+      auto mark = [&](int copy) { atomicOr(&L.involved[copy >> 5], 1u << (copy & 31)); };
+      if (bit_at(L.occ2, s)) mark(k);   // Eq. (6): the start is shared
       for (int jj = i + 1; jj < C; ++jj) {   // Eq. (3)
         const uint32_t p = L.packed[v * C + jj];
         if (live_of(p)) {
-          viol += e > (int)(p & 0xFFFFu) ? 1 : 0;
+          if (e > (int)(p & 0xFFFFu)) {
+            ++viol;
+            mark(k);
+            mark(v * C + jj);
+          }
           break;
         }
       }
@@ -623,7 +631,11 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
         const int u = A.in_idx[q];
         bool cov = false;
         for (int jj = 0; jj < C; ++jj) cov = cov || covers1(L.packed[u * C + jj], (uint32_t)s);
-        viol += cov ? 0 : 1;
+        if (!cov) {   // the consumer and every copy of the provider could mend it
+          ++viol;
+          mark(k);
+          for (int jj = 0; jj < C; ++jj) mark(u * C + jj);
+        }
       }
     }
     int distinct = 0;
@@ -632,6 +644,36 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
     __syncthreads();
     const int base_viol = __builtin_amdgcn_readfirstlane(counts[0]);   // the same in every lane: scalar registers
     const int base_peak = __builtin_amdgcn_readfirstlane(L.pmax[T - 1]);
+    // For the best move alone the list is built again, the copies that take part in a violation
+    // first: their moves are the ones that can lower the count, and once one has, the others
+    // are left out wave by wave (see below).
+    int n_first = n_active;   // entries of the list's first part
+    if constexpr (!TABLE) {
+      auto chunk = [&](const uint32_t* bits, int c) { return (uint64_t)bits[2 * c] | ((uint64_t)bits[2 * c + 1] << 32); };
+      const int chunks = lay.mask_words / 2;
+      int all_first = 0;
+      for (int x = lane; x < chunks; x += kWave) all_first += __popcll(chunk(L.amask, x) & chunk(L.involved, x));
+#pragma unroll
+      for (int off = kWave / 2; off > 0; off >>= 1) all_first += __shfl_xor(all_first, off);
+      n_first = __builtin_amdgcn_readfirstlane(all_first);
+      for (int c = wave; c < chunks; c += kNW) {
+        int before_first = 0, before_rest = 0;
+        for (int x = lane; x < c; x += kWave) {
+          const uint64_t am = chunk(L.amask, x), inv = chunk(L.involved, x);
+          before_first += __popcll(am & inv);
+          before_rest += __popcll(am & ~inv);
+        }
+#pragma unroll
+        for (int off = kWave / 2; off > 0; off >>= 1) {
+          before_first += __shfl_xor(before_first, off);
+          before_rest += __shfl_xor(before_rest, off);
+        }
+        const uint64_t am = chunk(L.amask, c), inv = chunk(L.involved, c), lower = ((uint64_t)1 << lane) - 1;
+        if ((am & inv) >> lane & 1) L.list[before_first + __popcll(am & inv & lower)] = (uint16_t)(c * kWave + lane);
+        if ((am & ~inv) >> lane & 1) L.list[n_first + before_rest + __popcll(am & ~inv & lower)] = (uint16_t)(c * kWave + lane);
+      }
+      __syncthreads();
+    }
 
     // ---- pass 2: one lane per (active copy, field); the waves draw 64 of these at a time.
     // For the best move alone: start moves first, so that all lanes of a wave run the same
@@ -657,9 +699,11 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
       if (table) {
         entry = u0 + (lane & 31);
         field = lane >> 5;
-      } else {
-        field = u0 + lane >= n_active ? 1 : 0;
-        entry = u0 + lane - field * n_active;
+      } else {   // both fields of the first part of the list, then both of the rest
+        const int u = u0 + lane, part = u >= 2 * n_first ? 1 : 0;
+        const int in_part = u - part * 2 * n_first, size = part ? n_active - n_first : n_first;
+        field = in_part >= size ? 1 : 0;
+        entry = part * n_first + in_part - field * size;
       }
       const bool has_unit = entry < n_active;
       const int k = has_unit ? L.list[entry] : 0;
@@ -668,15 +712,23 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
       const int sz = A.size_of(v);
       FieldState<WIDE> st{};
       st.field = -1;
-      if (has_unit && live_of(L.packed[k]))
-        build_field<CT, WIDE>(A, C, sz, L, T, R, v, i, field, L.packed[k], base_viol, q0, st);
       // For the best move alone, a field none of whose moves can have as few violations as
-      // some move already scored (by any wave of the workgroup) is not walked.
-      bool walk = st.field >= 0;
+      // some move already scored (by any wave of the workgroup) is left out.  Before anything
+      // is computed for it: a copy that takes part in no violation now (not marked in pass 1,
+      // its start not shared) cannot get below the base's count.  After the masks are built:
+      // no move has fewer violations than the terms that do not depend on the displacement.
+      bool build = has_unit && live_of(L.packed[k]), left_out = false;
+      [[maybe_unused]] int least = 0x7FFFFFFF;
       if constexpr (!TABLE) {
-        const int least = *const_cast<volatile int32_t*>(&counts[2]);
-        walk = walk && st.fixed + min(st.if_live, st.if_dead) <= least;
+        least = *const_cast<volatile int32_t*>(&counts[2]);
+        if (build && base_viol > least && !bit_at(L.involved, k) && !bit_at(L.occ2, (int)(L.packed[k] & 0xFFFFu))) {
+          build = false;
+          left_out = true;
+        }
       }
+      if (build) build_field<CT, WIDE>(A, C, sz, L, T, R, v, i, field, L.packed[k], base_viol, q0, st);
+      bool walk = st.field >= 0;
+      if constexpr (!TABLE) walk = walk && st.fixed + min(st.if_live, st.if_dead) <= least;
       if (walk) {
         bool high = false;   // counts above 7 in some lane
 #pragma unroll
@@ -690,7 +742,7 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
           }
         }
       }
-      if (has_unit && st.field < 0) {   // active and ill formed, or a node with very many edges (rare): move by move, from scratch
+      if (has_unit && st.field < 0 && !left_out) {   // active and ill formed, or a node with very many edges (rare): move by move, from scratch
         const int s = starts[row + k], e = ends[row + k];
         const int base_rest = base_viol - node_part(A, C, L.packed, v, i, true, live_of(L.packed[k]), s, e);
         for (int d = 0; d < two_r; ++d) {
