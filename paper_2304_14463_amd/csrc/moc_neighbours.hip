@@ -20,12 +20,14 @@
 // and peak' = max(prefix max before, suffix max after, shifted profile inside)
 // over the changed positions (at most R of them unless the copy was outside
 // the domain before the move).
-// Pass 1 counts the violations of the base and lists the active copies.  Pass 2
+// The active copies are listed while the base is staged.  Pass 1 counts the
+// violations of the base and marks the copies that take part in one.  Pass 2
 // runs one lane per (active copy, field): it builds the 0/1 terms of f as bit
 // masks over the displacements, sums them in bit planes and walks outwards from
-// the old position (see build_field, walk_own).  A third pass fills the scores
-// of the inactive copies (not applicable).  The adjacency lists are kept in LDS
-// when that costs no resident workgroup.
+// the old position (see build_field, walk_own).  Two kernels: for the best move
+// alone (fields that cannot win are left out), and with the table of scores (a
+// wave writes the rows of consecutive copies, the inactive ones filled in).
+// The adjacency lists are kept in LDS when that costs no resident workgroup.
 #include "moc_internal.h"
 
 namespace {
