@@ -75,6 +75,38 @@ def test_neighbours_full_table_small_graphs(moc, n, C, R):
     gh.free()
 
 
+@pytest.mark.parametrize("consumers,C,R", [(10, 1, 4), (70, 1, 4), (40, 2, 8), (70, 2, 16)])
+def test_neighbours_hub_node(moc, consumers, C, R):
+    """One provider with many consumers: moving its copy uncovers up to `consumers` * C
+    consumer copies at once, more than the per-move counters of the fast path hold (63) in
+    the larger cases, and more than fit three bit planes in the smaller ones.  Also a base
+    with no active copy at all, and one with every copy active."""
+    from paper_2304_14463_amd.inputs import graph_from_edges
+    rng = np.random.default_rng(7 * consumers + C + R)
+    n = consumers + 2
+    edges = [(0, v) for v in range(1, consumers + 1)] + [(1, n - 1)]
+    g = graph_from_edges(n, edges, rng.integers(1, 20, n), rng.integers(1, 5, n))
+    T = n * C
+    budget = int(g.size.sum()) // 3
+    B = 4
+    s = np.zeros((B, T), np.int32); e = np.zeros((B, T), np.int32); a = np.zeros((B, T), np.uint8)
+    for b in range(2):   # node v computed at position v*C, kept to the end; b = 1: the hub is dropped early
+        for v in range(n):
+            s[b, v * C], e[b, v * C], a[b, v * C] = v * C, T - 1, 1
+    e[1, 0] = min(T - 1, 3 * C)
+    a[3, :] = 1   # every copy active, all intervals [0, 0]; b = 2: nothing active
+    gh = moc.moc_graph_upload(n, g.in_ptr, g.in_idx, g.size, g.dur, budget, C)
+    om, ob = gpu_neighbours(moc, gh, s, e, a, R)
+    _, ob2 = gpu_neighbours(moc, gh, s, e, a, R, moves=False)
+    for b in range(B):
+        scores, best = oracle.neighbours(g, budget, C, s[b], e[b], a[b], R)
+        assert (om[b]["violations"].astype(np.int64) == scores[:, 0]).all(), b
+        assert (om[b]["peak"].astype(np.int64) == scores[:, 1]).all(), b
+        assert (int(ob[b]["move"]), int(ob[b]["violations"]), int(ob[b]["peak"])) == best, b
+    assert ob2.tobytes() == ob.tobytes()
+    gh.free()
+
+
 def test_neighbours_smallest_workload_all_moves(moc, workloads):
     w = workloads(0)
     gh = upload(moc, w)
@@ -123,6 +155,11 @@ def test_neighbours_workload_sampled(moc, workloads):
             key = np.lexsort((np.arange(n_moves)[ok], p[ok], np.maximum(p[ok], w.budget), v[ok]))
             q = int(np.arange(n_moves)[ok][key[0]])
             assert (int(ob[b0 + j]["move"]), int(ob[b0 + j]["violations"]), int(ob[b0 + j]["peak"])) == (q, v[q], p[q])
+    # the kernel for the best move alone (which leaves out fields that cannot win) agrees with the
+    # kernel that writes the table, on every base
+    _, ob_alone = moc.moc_eval_neighbours(gh, ds, de, da, R, want_moves=False)
+    torch.cuda.synchronize()
+    assert moc.results_to_numpy(ob_alone, moc.BEST_MOVE_DTYPE).tobytes() == ob.tobytes()
     # apply sampled moves and evaluate them as candidates
     b = 5
     row = moc.results_to_numpy(om_t[b], moc.MOVE_SCORE_DTYPE)
