@@ -120,6 +120,20 @@ def neighbours(g, budget, C, starts, ends, active, R, moves=None, T=None):
     return scores, tuple(int(x) for x in best)
 
 
+def toggles(g, budget, C, starts, ends, active, T=None):
+    """Scores of the n*C candidates that differ from this one in one active flag, by full
+    re-evaluation: int64 [n*C][3] = (violations, peak, duration)."""
+    K = g.n * C
+    T = K if T is None else T
+    s, e, a = _cand(starts, np.int32, K), _cand(ends, np.int32, K), _cand(active, np.uint8, K)
+    assert s.shape[0] == 1
+    scores = np.zeros((K, 3), dtype=np.int64)
+    keep, ga = _graph_args(g)
+    lib().orc_toggles(*ga, ctypes.c_int64(budget), ctypes.c_int32(C), ctypes.c_int32(T),
+                      _p(s, ctypes.c_int32), _p(e, ctypes.c_int32), _p(a, ctypes.c_uint8), _p(scores, ctypes.c_int64))
+    return scores
+
+
 def simulate_sequence(g, seq):
     """Independent liveness simulation of a rematerialisation sequence.
     Returns (valid, peak, duration)."""

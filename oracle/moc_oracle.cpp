@@ -215,4 +215,26 @@ void orc_neighbours(int32_t n, const int32_t* in_ptr, const int32_t* in_idx, con
   }
 }
 
+// Scores of the K = n*C candidates that differ from the given one in one active flag
+// (starts and ends stay): scores[3k..3k+2] = (violations, peak, duration) of the candidate
+// with active[k] flipped, by full re-evaluation.  Dropping a copy or activating a spare one
+// are the moves that change the objective, Eq. (1).
+void orc_toggles(int32_t n, const int32_t* in_ptr, const int32_t* in_idx, const int32_t* size, const int32_t* dur,
+                 int64_t budget, int32_t C, int32_t T, const int32_t* starts, const int32_t* ends,
+                 const uint8_t* active, int64_t* scores) {
+  Problem p{n, in_ptr, in_idx, size, dur, budget, C, T};
+  Scratch w;
+  const int K = n * C;
+  std::vector<uint8_t> a(active, active + K);
+  int64_t res[R_FIELDS];
+  for (int k = 0; k < K; ++k) {
+    a[k] = a[k] ? 0 : 1;
+    evaluate(p, starts, ends, a.data(), w, res, nullptr);
+    a[k] = active[k];
+    scores[3 * k] = res[R_VIOLATIONS];
+    scores[3 * k + 1] = res[R_PEAK];
+    scores[3 * k + 2] = res[R_DURATION];
+  }
+}
+
 }  // extern "C"

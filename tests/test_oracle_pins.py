@@ -330,3 +330,50 @@ def test_best_move_order_does_not_depend_on_the_budget():
             assert best == (q, int(scores[q, 0]), int(scores[q, 1])), (trial, budget)
             picks = best if picks is None else picks
             assert best == picks   # the same move for every budget
+
+
+def test_toggles_on_a_chain_closed_forms():
+    """Chain 0 -> 1 -> 2 -> 3 with unit sizes, one copy per node computed in order and kept until
+    its consumer: violation-free, peak 2, duration = sum of w.  Dropping node v (the only way to
+    toggle here, C = 1) breaks Eq. (7) for v and Eq. (5) for its consumer, removes v's interval
+    from the profile and saves w_v: the closed forms below."""
+    g = graph_from_edges(4, [(0, 1), (1, 2), (2, 3)], [1, 1, 1, 1], [5, 7, 11, 13])
+    s = np.array([0, 1, 2, 3], np.int32)
+    e = np.array([1, 2, 3, 3], np.int32)
+    a = np.ones(4, np.uint8)
+    base = oracle.evaluate(g, 100, 1, s, e, a)[0]
+    assert (base[F["violations"]], base[F["peak"]], base[F["duration"]]) == (0, 2, 36)
+    t = oracle.toggles(g, 100, 1, s, e, a)
+    # node 0: first copy inactive (+1), node 1 loses its input (+1); positions 0..1 lose a unit
+    assert tuple(t[0]) == (2, 2, 31)
+    assert tuple(t[1]) == (2, 2, 29)      # peak stays 2 at position 3 ... see profile below
+    assert tuple(t[2]) == (2, 2, 25)
+    assert tuple(t[3]) == (1, 2, 23)      # the sink has no consumer: only Eq. (7)
+    # profile of the base: [1, 2, 2, 2]; without node 1 (positions 1..2): [1, 1, 1, 2] -> 2
+    # without node 3 (position 3): [1, 2, 2, 1] -> 2; without node 0 (positions 0..1): [0, 1, 2, 2] -> 2
+
+
+def test_toggles_agree_with_evaluate_and_undo():
+    """Each toggle score is what evaluate returns for the flipped candidate (the definition),
+    and toggling the same copy twice gives back the base: checked on random candidates with
+    spare copies, where activating a copy can mend or break precedence, order and start
+    constraints."""
+    rng = np.random.default_rng(5)
+    n, C = 7, 3
+    edges = sorted({(int(u), v) for v in range(1, n) for u in rng.integers(0, v, size=2)})
+    g = graph_from_edges(n, edges, rng.integers(1, 20, n), rng.integers(1, 9, n))
+    T = n * C
+    for trial in range(5):
+        s = rng.integers(-1, T + 1, T).astype(np.int32)
+        e = (s + rng.integers(-2, 6, T)).astype(np.int32)
+        a = (rng.random(T) < 0.6).astype(np.uint8)
+        base = oracle.evaluate(g, 50, C, s, e, a)[0]
+        t = oracle.toggles(g, 50, C, s, e, a)
+        for k in range(T):
+            a2 = a.copy(); a2[k] ^= 1
+            r = oracle.evaluate(g, 50, C, s, e, a2)[0]
+            assert tuple(t[k]) == (r[F["violations"]], r[F["peak"]], r[F["duration"]])
+            back = oracle.toggles(g, 50, C, s, e, a2)[k]
+            assert tuple(back) == (base[F["violations"]], base[F["peak"]], base[F["duration"]])
+            # the objective moves by the node's duration, Eq. (1)
+            assert t[k][2] - base[F["duration"]] == (1 if a2[k] else -1) * int(g.dur[k // C])
