@@ -93,6 +93,12 @@ typedef struct {
 } moc_move_score;
 
 typedef struct {
+  int32_t violations; /* as moc_result.violations */
+  int32_t peak;       /* as moc_result.peak (below 2^31 for any uploaded graph) */
+  int64_t duration;   /* as moc_result.duration: the base's, minus or plus w_v */
+} moc_toggle_score;   /* 16 bytes */
+
+typedef struct {
   int32_t move;       /* index of the best move, -1 if no move is applicable */
   int32_t violations; /* 0 when move == -1 */
   int64_t peak;       /* 0 when move == -1 */
@@ -158,6 +164,20 @@ int moc_eval_batch(const moc_graph* g, int64_t B, const int32_t* starts, const i
 int moc_eval_neighbours(const moc_graph* g, int64_t B, const int32_t* starts, const int32_t* ends,
                         const uint8_t* active, int32_t R, moc_move_score* out_moves,
                         moc_best_move* out_best, void* hip_stream);
+
+/*
+ * Score every candidate that differs from a base in one active flag.  Not part
+ * of the paper: these are the moves of a local search over the variables of
+ * Section 2.1 that change the objective, Eq. (1) -- dropping a copy saves its
+ * node's duration, activating a spare copy (at the start and end it already
+ * carries) costs it.  Entry [b][k] is what moc_eval_batch returns for base b
+ * with active[k] flipped and everything else unchanged.
+ *   out   device, moc_toggle_score [B][T], 8-byte aligned
+ * Same limits on T and on self-loops as moc_eval_neighbours.  B == 0 is a no-op.
+ * Errors: MOC_EINVAL, MOC_EDEVICE, MOC_EOVERFLOW (T too large for this call), MOC_EHIP.
+ */
+int moc_eval_toggles(const moc_graph* g, int64_t B, const int32_t* starts, const int32_t* ends,
+                     const uint8_t* active, moc_toggle_score* out, void* hip_stream);
 
 /* Release a graph (synchronises its device first).  NULL is a no-op. */
 void moc_graph_free(moc_graph* g);

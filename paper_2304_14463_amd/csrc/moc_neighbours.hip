@@ -805,6 +805,148 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
 }
 
 
+
+// ---------------------------------------------------------------------------------------------
+// moc_eval_toggles: every candidate that differs from the base in one active flag.  The base
+// is staged as above (packed intervals, profile with prefix and suffix maxima, start bitmaps);
+// the maximum of the profile over a copy's whole interval comes from maxima over blocks of 32
+// positions.  One lane per copy: violations' = violations - f(copy as it is) + f(copy with the
+// flag flipped) + what Eq. (6) and Eq. (7) see of the flip, with f = node_part; peak' from the
+// interval the copy gives up or takes; duration' = duration -+ w_v.
+struct TgLayout {
+  int T_pad, bit_words, blocks, bytes;
+};
+
+TgLayout tg_layout(int T) {
+  TgLayout l;
+  l.T_pad = (T + 3) & ~3;
+  l.bit_words = (T + 31) / 32;
+  l.blocks = (T + 31) / 32;
+  // profile, prefix max, suffix max (with sentinels), packed, block maxima, two bitmaps, scratch
+  l.bytes = 4 * (4 * l.T_pad + 8 + l.blocks + 2 * l.bit_words + 8 * kNW + 16);
+  return l;
+}
+
+__global__ __launch_bounds__(kNT) void toggles_kernel(GraphView g, int64_t B, const int32_t* __restrict__ starts,
+                                                      const int32_t* __restrict__ ends,
+                                                      const uint8_t* __restrict__ active,
+                                                      moc_toggle_score* __restrict__ out, TgLayout lay) {
+  extern __shared__ uint32_t nb_raw[];
+  NbLds L{};
+  L.profile = reinterpret_cast<int32_t*>(nb_raw);
+  L.pmax = L.profile + lay.T_pad + 4;   // pmax[-1] = 0
+  L.smax = L.pmax + lay.T_pad;          // smax[T] = 0
+  L.packed = reinterpret_cast<uint32_t*>(L.smax + lay.T_pad + 4);
+  int32_t* const block_max = reinterpret_cast<int32_t*>(L.packed + lay.T_pad);
+  L.occ1 = reinterpret_cast<uint32_t*>(block_max + lay.blocks);
+  L.occ2 = L.occ1 + lay.bit_words;
+  L.scratch = reinterpret_cast<int32_t*>(L.occ2 + lay.bit_words);
+  int32_t* const counts = L.scratch + 8 * kNW;   // [0] base violations, [1] base duration
+  const int tid = threadIdx.x;
+  const int T = g.T, C = g.C;
+  const Adj A{g.in_ptr, g.in_idx, g.out_ptr, g.out_idx, reinterpret_cast<const int32_t*>(g.size_dur), 2};
+
+  for (int64_t b = blockIdx.x; b < B; b += gridDim.x) {
+    const int64_t row = b * T;
+    // ---- the base: copies, deltas, starts
+    for (int t = tid; t < T; t += kNT) L.profile[t] = 0;
+    for (int w = tid; w < 2 * lay.bit_words; w += kNT) L.occ1[w] = 0;
+    if (tid < 2) counts[tid] = 0;
+    if (tid == 0) { L.pmax[-1] = 0; L.smax[T] = 0; }
+    __syncthreads();
+    int viol = 0, nlive = 0, dur = 0;
+    for (int k = tid; k < T; k += kNT) {
+      const int s = starts[row + k], e = ends[row + k];
+      const bool act = active[row + k] != 0;
+      const bool live = act && (uint32_t)s <= (uint32_t)e && (uint32_t)e < (uint32_t)T;
+      const int v = k / C;
+      L.packed[k] = pack_copy(live, s, e);
+      if (k == v * C && !act) ++viol;   // Eq. (7)
+      if (act) dur += g.size_dur[v].y;  // Eq. (1)
+      if (live) {
+        ++nlive;
+        const int sz = g.size_dur[v].x;
+        atomicAdd(&L.profile[s], sz);
+        if (e + 1 < T) atomicSub(&L.profile[e + 1], sz);
+        const uint32_t bit = 1u << (s & 31);
+        const uint32_t old = atomicOr(&L.occ1[s >> 5], bit);
+        if (old & bit) atomicOr(&L.occ2[s >> 5], bit);
+      }
+    }
+    __syncthreads();
+    block_scan<AddOp, false>(L.profile, L.profile, T, L.scratch, tid);   // Eq. (4) per position
+    block_max_both_ways(L.profile, L.pmax, L.smax, T, L.scratch, tid);
+    for (int x = tid; x < lay.blocks; x += kNT) {
+      int m = 0;
+      for (int t = 32 * x; t < min(32 * x + 32, T); ++t) m = max(m, L.profile[t]);
+      block_max[x] = m;
+    }
+    // ---- the violations of the base, each instance once (as pass 1 of the kernel above)
+    for (int k = tid; k < T; k += kNT) {
+      const uint32_t mine = L.packed[k];
+      if (!live_of(mine)) {
+        viol += active[row + k] != 0 ? 1 : 0;   // Eq. (2)/(8)
+        continue;
+      }
+      const int v = k / C, i = k - v * C;
+      const int s = (int)(mine & 0xFFFFu), e = (int)(mine >> 16);
+      for (int j = i + 1; j < C; ++j) {   // Eq. (3)
+        const uint32_t p = L.packed[v * C + j];
+        if (live_of(p)) {
+          viol += e > (int)(p & 0xFFFFu) ? 1 : 0;
+          break;
+        }
+      }
+      for (int q = A.in_ptr[v]; q < A.in_ptr[v + 1]; ++q) {   // Eq. (5)
+        const int u = A.in_idx[q];
+        bool cov = false;
+        for (int j = 0; j < C; ++j) cov = cov || covers1(L.packed[u * C + j], (uint32_t)s);
+        viol += cov ? 0 : 1;
+      }
+    }
+    int distinct = 0;
+    for (int w = tid; w < lay.bit_words; w += kNT) distinct += __popc(L.occ1[w]);
+    atomicAdd(&counts[0], viol + nlive - distinct);   // Eq. (6): live copies - distinct starts
+    atomicAdd(&counts[1], dur);
+    __syncthreads();
+    const int base_viol = counts[0], base_dur = counts[1], base_peak = L.pmax[T - 1];
+
+    // ---- one lane per copy
+    for (int k = tid; k < T; k += kNT) {
+      const int v = k / C, i = k - v * C;
+      const int s = starts[row + k], e = ends[row + k];
+      const bool was = active[row + k] != 0;
+      const bool well = (uint32_t)s <= (uint32_t)e && (uint32_t)e < (uint32_t)T;
+      const bool live_old = was && well, live_new = !was && well;
+      int vv = base_viol - node_part(A, C, L.packed, v, i, was, live_old, s, e) +
+               node_part(A, C, L.packed, v, i, !was, live_new, s, e);
+      if (live_old && bit_at(L.occ2, s)) --vv;   // Eq. (6): a shared start loses one of its copies
+      if (live_new && bit_at(L.occ1, s)) ++vv;   //          or a taken start gains one
+      if (i == 0) vv += was ? 1 : -1;            // Eq. (7)
+      int pk = base_peak;
+      if (well) {   // the copy's interval leaves or joins the profile
+        int top = 0;
+        if (e - s < 64) {
+          for (int t = s; t <= e; ++t) top = max(top, L.profile[t]);
+        } else {
+          const int first_block = (s + 31) >> 5, last_block = (e + 1) >> 5;   // whole blocks [first, last)
+          for (int t = s; t < 32 * first_block; ++t) top = max(top, L.profile[t]);
+          for (int x = first_block; x < last_block; ++x) top = max(top, block_max[x]);
+          for (int t = 32 * last_block; t <= e; ++t) top = max(top, L.profile[t]);
+        }
+        const int sz = g.size_dur[v].x;
+        pk = max(max(top + (was ? -sz : sz), 0), max(L.pmax[s - 1], L.smax[e + 1]));
+      }
+      moc_toggle_score sc;
+      sc.violations = vv;
+      sc.peak = pk;
+      sc.duration = (int64_t)base_dur + (was ? -g.size_dur[v].y : g.size_dur[v].y);
+      out[row + k] = sc;
+    }
+    __syncthreads();
+  }
+}
+
 using NbKernel = void (*)(GraphView, int64_t, const int32_t*, const int32_t*, const uint8_t*, int, moc_move_score*,
                           moc_best_move*, NbLayout);
 
@@ -858,6 +1000,31 @@ extern "C" int moc_eval_neighbours(const moc_graph* g, int64_t B, const int32_t*
   const unsigned grid = (unsigned)(B < resident ? B : resident);
   hipLaunchKernelGGL(kern, dim3(grid), dim3(kNT), lay.bytes, static_cast<hipStream_t>(hip_stream), g->view, B,
                      starts, ends, active, R, out_moves, out_best, lay);
+  MOC_HIP(hipGetLastError());
+  return MOC_OK;
+}
+
+extern "C" int moc_eval_toggles(const moc_graph* g, int64_t B, const int32_t* starts, const int32_t* ends,
+                                const uint8_t* active, moc_toggle_score* out, void* hip_stream) {
+  if (!g || B < 0) return MOC_EINVAL;
+  if (B == 0) return MOC_OK;
+  if (!starts || !ends || !active || !out) return MOC_EINVAL;
+  if ((((uintptr_t)starts | (uintptr_t)ends) & 3) || ((uintptr_t)out & 7)) return MOC_EINVAL;
+  int dev = -1;
+  MOC_HIP(hipGetDevice(&dev));
+  if (dev != g->device) return MOC_EDEVICE;
+  if (g->has_self_loop) return MOC_EINVAL;
+  const TgLayout lay = tg_layout(g->view.T);
+  if (lay.bytes > g->max_lds) return MOC_EOVERFLOW;
+  MOC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(toggles_kernel),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, lay.bytes));
+  int per_cu = 0;
+  MOC_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, toggles_kernel, kNT, lay.bytes));
+  if (per_cu < 1) per_cu = 1;
+  const int64_t resident = (int64_t)per_cu * g->num_cu;
+  const unsigned grid = (unsigned)(B < resident ? B : resident);
+  hipLaunchKernelGGL(toggles_kernel, dim3(grid), dim3(kNT), lay.bytes, static_cast<hipStream_t>(hip_stream), g->view,
+                     B, starts, ends, active, out, lay);
   MOC_HIP(hipGetLastError());
   return MOC_OK;
 }

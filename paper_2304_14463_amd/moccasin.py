@@ -22,8 +22,9 @@ MOC_MAX_T = 19455
 RESULT_DTYPE = np.dtype([("peak", "<i8"), ("duration", "<i8"), ("violations", "<i4"), ("feasible", "<i4")])
 MOVE_SCORE_DTYPE = np.dtype([("violations", "<i4"), ("peak", "<i4")])
 BEST_MOVE_DTYPE = np.dtype([("move", "<i4"), ("violations", "<i4"), ("peak", "<i8")])
+TOGGLE_SCORE_DTYPE = np.dtype([("violations", "<i4"), ("peak", "<i4"), ("duration", "<i8")])
 
-EXPORTS = ("moc_graph_upload", "moc_graph_info", "moc_eval_batch", "moc_eval_neighbours",
+EXPORTS = ("moc_graph_upload", "moc_graph_info", "moc_eval_batch", "moc_eval_neighbours", "moc_eval_toggles",
            "moc_graph_free", "moc_strerror", "moc_last_hip_error")
 
 
@@ -51,6 +52,8 @@ def lib():
         L.moc_eval_batch.restype = ctypes.c_int
         L.moc_eval_neighbours.argtypes = [VP, I64, VP, VP, VP, I32, VP, VP, VP]
         L.moc_eval_neighbours.restype = ctypes.c_int
+        L.moc_eval_toggles.argtypes = [VP, I64, VP, VP, VP, VP, VP]
+        L.moc_eval_toggles.restype = ctypes.c_int
         L.moc_graph_free.argtypes = [VP]
         L.moc_graph_free.restype = None
         L.moc_strerror.argtypes = [ctypes.c_int]
@@ -149,6 +152,19 @@ def moc_eval_neighbours(g: Graph, starts, ends, active, R, want_moves=True, want
         ctypes.c_void_p(out_best.data_ptr()) if out_best is not None else None, _stream_handle(stream))
     _check(code, "moc_eval_neighbours")
     return out_moves, out_best
+
+
+def moc_eval_toggles(g: Graph, starts, ends, active, out=None, stream=None):
+    """Score the B x T candidates that differ from a base in one active flag.  Returns a uint8
+    CUDA tensor [B][T][16] (moc_toggle_score)."""
+    import torch
+    B = starts.numel() // g.T if g.T else 0
+    ps, pe, pa = _cand_ptrs(g, B, starts, ends, active)
+    if out is None:
+        out = torch.empty((B, g.T, TOGGLE_SCORE_DTYPE.itemsize), dtype=torch.uint8, device=starts.device)
+    code = lib().moc_eval_toggles(g._h, B, ps, pe, pa, ctypes.c_void_p(out.data_ptr()), _stream_handle(stream))
+    _check(code, "moc_eval_toggles")
+    return out
 
 
 def results_to_numpy(out, dtype=RESULT_DTYPE):

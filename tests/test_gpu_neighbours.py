@@ -208,3 +208,64 @@ def test_neighbours_argument_errors(moc, workloads):
         moc.moc_eval_neighbours(gh, z, z, torch.ones((1, 3), dtype=torch.uint8, device="cuda"), 2)
     assert err.value.code == -1
     gh.free()
+
+
+@pytest.mark.parametrize("n,C", [(1, 1), (2, 2), (9, 2), (12, 3), (30, 4), (40, 3), (64, 2), (150, 1), (24, 5)])
+def test_toggles_small_graphs(moc, n, C):
+    """Every toggle of random candidates (wild starts and ends included), of a violation-free
+    one and of an empty one, against the oracle's full re-evaluation."""
+    from paper_2304_14463_amd.inputs import graph_from_edges
+    rng = np.random.default_rng(77 * n + C)
+    edges = set()
+    for v in range(1, n):
+        for u in rng.integers(0, v, size=rng.integers(0, 4)):
+            edges.add((int(u), v))
+    g = graph_from_edges(n, sorted(edges), rng.integers(0, 50, n), rng.integers(1, 9, n))
+    T = n * C
+    budget = int(g.size.sum()) // 2
+    B = 6
+    s, e, a = random_candidates(rng, B, T, T, wild=True)
+    s[0] = 0; e[0] = 0; a[0] = 0
+    for v in range(n):   # a topological order with every copy 0 kept to the end
+        s[0, v * C], e[0, v * C], a[0, v * C] = v, T - 1, 1
+    a[1] = 0             # nothing active
+    long = rng.integers(0, max(T // 8, 1), T)   # long intervals: the block maxima are used when T allows
+    s[2] = long; e[2] = np.minimum(T - 1, long + T // 2)
+    gh = moc.moc_graph_upload(n, g.in_ptr, g.in_idx, g.size, g.dur, budget, C)
+    ds, de, da = to_dev(s, e, a)
+    got = moc.results_to_numpy(moc.moc_eval_toggles(gh, ds, de, da), moc.TOGGLE_SCORE_DTYPE)
+    for b in range(B):
+        want = oracle.toggles(g, budget, C, s[b], e[b], a[b])
+        assert (got[b]["violations"].astype(np.int64) == want[:, 0]).all(), (n, C, b)
+        assert (got[b]["peak"].astype(np.int64) == want[:, 1]).all(), (n, C, b)
+        assert (got[b]["duration"] == want[:, 2]).all(), (n, C, b)
+    gh.free()
+
+
+def test_toggles_workload(moc, workloads):
+    """n=2000, C=2 at the full batch: sampled bases against the oracle, and sampled toggles
+    applied and evaluated with moc_eval_batch."""
+    import torch
+    from paper_2304_14463_amd.inputs import DeviceWorkload
+    w = workloads(3)
+    gh = upload(moc, w)
+    ds, de, da = DeviceWorkload(w).candidates()
+    out = moc.moc_eval_toggles(gh, ds, de, da)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(4)
+    for b in (0, w.B // 2 + 1, w.B - 1):
+        s, e, a = ds[b].cpu().numpy(), de[b].cpu().numpy(), da[b].cpu().numpy()
+        got = moc.results_to_numpy(out[b], moc.TOGGLE_SCORE_DTYPE)
+        want = oracle.toggles(w.graph, w.budget, w.C, s, e, a)
+        assert (got["violations"].astype(np.int64) == want[:, 0]).all(), b
+        assert (got["peak"].astype(np.int64) == want[:, 1]).all(), b
+        assert (got["duration"] == want[:, 2]).all(), b
+    pb, pk = rng.integers(0, w.B, 256), rng.integers(0, w.T, 256)
+    tb, tk = torch.from_numpy(pb).cuda(), torch.from_numpy(pk).cuda()
+    s = ds[tb].contiguous(); e = de[tb].contiguous(); a = da[tb].contiguous()
+    a[torch.arange(256, device="cuda"), tk] ^= 1
+    res = moc.results_to_numpy(moc.moc_eval_batch(gh, s, e, a))
+    got = moc.results_to_numpy(out[tb, tk], moc.TOGGLE_SCORE_DTYPE)
+    assert (res["violations"] == got["violations"]).all() and (res["peak"] == got["peak"]).all()
+    assert (res["duration"] == got["duration"]).all()
+    gh.free()
