@@ -146,6 +146,18 @@ def measure_neighbours(moc, steps, warmup):
         out[mode] = {"ms_per_step": ms, "moves_per_s": w.B * n_moves / (ms * 1e-3),
                      "bytes_written": (w.B * n_moves * 8 if wm else 0) + w.B * 16}
         del om, ob
+    # the moves that change the objective: one active flag flipped, B x T of them
+    ot = moc.moc_eval_toggles(gh, ds, de, da)
+    for _ in range(warmup):
+        moc.moc_eval_toggles(gh, ds, de, da, out=ot)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        moc.moc_eval_toggles(gh, ds, de, da, out=ot)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    out["toggles"] = {"ms_per_step": ms, "moves_per_s": w.B * w.T / (ms * 1e-3), "bytes_written": w.B * w.T * 16}
+    del ot
     gh.free()
     return {"workload": w.name, "n": w.n, "m": w.m, "C": w.C, "T": w.T, "B": w.B, "R": w.R,
             "moves_per_candidate": n_moves, **out}
