@@ -810,9 +810,51 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
 // moc_eval_toggles: every candidate that differs from the base in one active flag.  The base
 // is staged as above (packed intervals, profile with prefix and suffix maxima, start bitmaps);
 // the maximum of the profile over a copy's whole interval comes from maxima over blocks of 32
-// positions.  One lane per copy: violations' = violations - f(copy as it is) + f(copy with the
-// flag flipped) + what Eq. (6) and Eq. (7) see of the flip, with f = node_part; peak' from the
-// interval the copy gives up or takes; duration' = duration -+ w_v.
+// positions.  One lane per copy: violations' = violations + f(copy with the flag flipped) -
+// f(copy as it is) + what Eq. (6) and Eq. (7) see of the flip, with f = node_part (see
+// toggle_delta); peak' from the interval the copy gives up or takes; duration' = duration -+ w_v.
+// f(copy with its active flag flipped) - f(copy as it is), f = node_part, in one walk over
+// the node's edges: the flip makes a well-formed copy leave or join the live copies of v
+// (an ill-formed one only starts or stops counting as such).
+__device__ __forceinline__ int toggle_delta(const Adj& g, int C, const uint32_t* __restrict__ packed, int v, int i,
+                                            bool was, bool well, int s, int e) {
+  if (!well) return was ? -1 : 1;   // Eq. (2)/(8)
+  const int sign = was ? -1 : 1;    // the copy leaves (-1) or joins (+1)
+  // Eq. (3) among the live copies of v, with and without copy i
+  int with = 0, without = 0, end_with = -1, end_without = -1;
+  for (int j = 0; j < C; ++j) {
+    const uint32_t p = j == i ? pack_copy(true, s, e) : packed[v * C + j];
+    if (!live_of(p)) continue;
+    const int start = (int)(p & 0xFFFFu), end = (int)(p >> 16);
+    with += end_with > start ? 1 : 0;
+    end_with = end;
+    if (j != i) {
+      without += end_without > start ? 1 : 0;
+      end_without = end;
+    }
+  }
+  int delta = sign * (with - without);
+  // Eq. (5), the copy as consumer: its inputs count while it is live
+  for (int q = g.in_ptr[v]; q < g.in_ptr[v + 1]; ++q) {
+    const int u = g.in_idx[q];
+    bool cov = false;
+    for (int j = 0; j < C; ++j) cov = cov || covers1(packed[u * C + j], (uint32_t)s);
+    delta += cov ? 0 : sign;
+  }
+  // Eq. (5), node v as provider: the consumer copies that only this copy covers
+  for (int q = g.out_ptr[v]; q < g.out_ptr[v + 1]; ++q) {
+    const int w = g.out_idx[q];
+    for (int jw = 0; jw < C; ++jw) {
+      const int x = (int)(packed[w * C + jw] & 0xFFFFu);
+      if (x == 0xFFFF || !(s < x && x <= e)) continue;
+      bool others = false;
+      for (int j = 0; j < C; ++j) others = others || (j != i && covers1(packed[v * C + j], (uint32_t)x));
+      delta -= others ? 0 : sign;
+    }
+  }
+  return delta;
+}
+
 struct TgLayout {
   int T_pad, bit_words, blocks, bytes;
 };
@@ -918,8 +960,7 @@ __global__ __launch_bounds__(kNT) void toggles_kernel(GraphView g, int64_t B, co
       const bool was = active[row + k] != 0;
       const bool well = (uint32_t)s <= (uint32_t)e && (uint32_t)e < (uint32_t)T;
       const bool live_old = was && well, live_new = !was && well;
-      int vv = base_viol - node_part(A, C, L.packed, v, i, was, live_old, s, e) +
-               node_part(A, C, L.packed, v, i, !was, live_new, s, e);
+      int vv = base_viol + toggle_delta(A, C, L.packed, v, i, was, well, s, e);
       if (live_old && bit_at(L.occ2, s)) --vv;   // Eq. (6): a shared start loses one of its copies
       if (live_new && bit_at(L.occ1, s)) ++vv;   //          or a taken start gains one
       if (i == 0) vv += was ? 1 : -1;            // Eq. (7)
