@@ -856,19 +856,31 @@ __device__ __forceinline__ int toggle_delta(const Adj& g, int C, const uint32_t*
 }
 
 struct TgLayout {
-  int T_pad, bit_words, blocks, bytes;
+  int T_pad, bit_words, blocks;
+  int adj_off;   // word offset of the adjacency lists and sizes in LDS, 0 if they stay in global memory
+  int bytes;
 };
 
-TgLayout tg_layout(int T) {
+TgLayout tg_layout(int T, int n, int m, int max_lds) {
   TgLayout l;
   l.T_pad = (T + 3) & ~3;
   l.bit_words = (T + 31) / 32;
   l.blocks = (T + 31) / 32;
   // profile, prefix max, suffix max (with sentinels), packed, block maxima, two bitmaps, scratch
-  l.bytes = 4 * (4 * l.T_pad + 8 + l.blocks + 2 * l.bit_words + 8 * kNW + 16);
+  const int words = 4 * l.T_pad + 8 + l.blocks + 2 * l.bit_words + 8 * kNW + 16;
+  l.adj_off = 0;
+  l.bytes = 4 * words;
+  // A lane walks its node's edges one after the other: from LDS whenever the lists fit (the
+  // latency of global memory per edge costs more than the second workgroup per CU brings).
+  const int with_adj = 4 * (words + 2 * (n + 1) + 2 * m + n);
+  if (with_adj <= max_lds) {
+    l.adj_off = words;
+    l.bytes = with_adj;
+  }
   return l;
 }
 
+template <bool ADJ_LDS>
 __global__ __launch_bounds__(kNT) void toggles_kernel(GraphView g, int64_t B, const int32_t* __restrict__ starts,
                                                       const int32_t* __restrict__ ends,
                                                       const uint8_t* __restrict__ active,
@@ -886,7 +898,16 @@ __global__ __launch_bounds__(kNT) void toggles_kernel(GraphView g, int64_t B, co
   int32_t* const counts = L.scratch + 8 * kNW;   // [0] base violations, [1] base duration
   const int tid = threadIdx.x;
   const int T = g.T, C = g.C;
-  const Adj A{g.in_ptr, g.in_idx, g.out_ptr, g.out_idx, reinterpret_cast<const int32_t*>(g.size_dur), 2};
+  Adj A{g.in_ptr, g.in_idx, g.out_ptr, g.out_idx, reinterpret_cast<const int32_t*>(g.size_dur), 2};
+  if constexpr (ADJ_LDS) {
+    int32_t* a = reinterpret_cast<int32_t*>(nb_raw) + lay.adj_off;
+    int32_t* const sizes = a + 2 * (g.n + 1) + 2 * g.m;
+    for (int x = tid; x <= g.n; x += kNT) { a[x] = g.in_ptr[x]; a[g.n + 1 + g.m + x] = g.out_ptr[x]; }
+    for (int x = tid; x < g.m; x += kNT) { a[g.n + 1 + x] = g.in_idx[x]; a[2 * (g.n + 1) + g.m + x] = g.out_idx[x]; }
+    for (int x = tid; x < g.n; x += kNT) sizes[x] = g.size_dur[x].x;
+    A = Adj{a, a + g.n + 1, a + g.n + 1 + g.m, a + 2 * (g.n + 1) + g.m, sizes, 1};
+    __syncthreads();
+  }
 
   for (int64_t b = blockIdx.x; b < B; b += gridDim.x) {
     const int64_t row = b * T;
@@ -907,7 +928,7 @@ __global__ __launch_bounds__(kNT) void toggles_kernel(GraphView g, int64_t B, co
       if (act) dur += g.size_dur[v].y;  // Eq. (1)
       if (live) {
         ++nlive;
-        const int sz = g.size_dur[v].x;
+        const int sz = A.size_of(v);
         atomicAdd(&L.profile[s], sz);
         if (e + 1 < T) atomicSub(&L.profile[e + 1], sz);
         const uint32_t bit = 1u << (s & 31);
@@ -966,16 +987,27 @@ __global__ __launch_bounds__(kNT) void toggles_kernel(GraphView g, int64_t B, co
       if (i == 0) vv += was ? 1 : -1;            // Eq. (7)
       int pk = base_peak;
       if (well) {   // the copy's interval leaves or joins the profile
+        // eight reads in flight at a time: re-reading the last element changes no maximum
+        auto range_max = [](const int32_t* a, int from, int to) {   // max(a[from..to]), from <= to
+          int m = 0;
+          for (int t = from; t <= to; t += 8) {
+            int x[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) x[j] = a[min(t + j, to)];
+            m = max(max(max(m, x[0]), max(x[1], x[2])), max(max(x[3], x[4]), max(max(x[5], x[6]), x[7])));
+          }
+          return m;
+        };
         int top = 0;
         if (e - s < 64) {
-          for (int t = s; t <= e; ++t) top = max(top, L.profile[t]);
+          top = range_max(L.profile, s, e);
         } else {
           const int first_block = (s + 31) >> 5, last_block = (e + 1) >> 5;   // whole blocks [first, last)
-          for (int t = s; t < 32 * first_block; ++t) top = max(top, L.profile[t]);
-          for (int x = first_block; x < last_block; ++x) top = max(top, block_max[x]);
-          for (int t = 32 * last_block; t <= e; ++t) top = max(top, L.profile[t]);
+          if (s < 32 * first_block) top = range_max(L.profile, s, 32 * first_block - 1);
+          top = max(top, range_max(block_max, first_block, last_block - 1));
+          if (32 * last_block <= e) top = max(top, range_max(L.profile, 32 * last_block, e));
         }
-        const int sz = g.size_dur[v].x;
+        const int sz = A.size_of(v);
         pk = max(max(top + (was ? -sz : sz), 0), max(L.pmax[s - 1], L.smax[e + 1]));
       }
       moc_toggle_score sc;
@@ -1055,17 +1087,18 @@ extern "C" int moc_eval_toggles(const moc_graph* g, int64_t B, const int32_t* st
   MOC_HIP(hipGetDevice(&dev));
   if (dev != g->device) return MOC_EDEVICE;
   if (g->has_self_loop) return MOC_EINVAL;
-  const TgLayout lay = tg_layout(g->view.T);
+  const TgLayout lay = tg_layout(g->view.T, g->view.n, g->view.m, g->max_lds);
   if (lay.bytes > g->max_lds) return MOC_EOVERFLOW;
-  MOC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(toggles_kernel),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, lay.bytes));
+  auto kern = lay.adj_off ? toggles_kernel<true> : toggles_kernel<false>;
+  MOC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              lay.bytes));
   int per_cu = 0;
-  MOC_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, toggles_kernel, kNT, lay.bytes));
+  MOC_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, kNT, lay.bytes));
   if (per_cu < 1) per_cu = 1;
   const int64_t resident = (int64_t)per_cu * g->num_cu;
   const unsigned grid = (unsigned)(B < resident ? B : resident);
-  hipLaunchKernelGGL(toggles_kernel, dim3(grid), dim3(kNT), lay.bytes, static_cast<hipStream_t>(hip_stream), g->view,
-                     B, starts, ends, active, out, lay);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(kNT), lay.bytes, static_cast<hipStream_t>(hip_stream), g->view, B, starts,
+                     ends, active, out, lay);
   MOC_HIP(hipGetLastError());
   return MOC_OK;
 }
