@@ -200,12 +200,24 @@ def test_neighbours_argument_errors(moc, workloads):
         moc.moc_eval_neighbours(gh, z, z, torch.zeros((1, n), dtype=torch.uint8, device="cuda"), 2)
     assert err.value.code == -2
     gh.free()
+    # the toggles keep four words per copy: T = 10200 is too much for them
+    n = 10200
+    g = graph_from_edges(n, [(i, i + 1) for i in range(n - 1)], np.ones(n), np.ones(n))
+    gh = moc.moc_graph_upload(n, g.in_ptr, g.in_idx, g.size, g.dur, 10, 1)
+    z = torch.zeros((1, n), dtype=torch.int32, device="cuda")
+    with pytest.raises(moc.MoccasinError) as err:
+        moc.moc_eval_toggles(gh, z, z, torch.zeros((1, n), dtype=torch.uint8, device="cuda"))
+    assert err.value.code == -2
+    gh.free()
     # self loops are refused by this call only
     g = graph_from_edges(3, [(0, 1), (1, 1)], [1, 1, 1], [1, 1, 1])
     gh = moc.moc_graph_upload(3, g.in_ptr, g.in_idx, g.size, g.dur, 10, 1)
     z = torch.zeros((1, 3), dtype=torch.int32, device="cuda")
     with pytest.raises(moc.MoccasinError) as err:
         moc.moc_eval_neighbours(gh, z, z, torch.ones((1, 3), dtype=torch.uint8, device="cuda"), 2)
+    assert err.value.code == -1
+    with pytest.raises(moc.MoccasinError) as err:
+        moc.moc_eval_toggles(gh, z, z, torch.ones((1, 3), dtype=torch.uint8, device="cuda"))
     assert err.value.code == -1
     gh.free()
 
