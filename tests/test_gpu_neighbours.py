@@ -281,3 +281,32 @@ def test_toggles_workload(moc, workloads):
     assert (res["violations"] == got["violations"]).all() and (res["peak"] == got["peak"]).all()
     assert (res["duration"] == got["duration"]).all()
     gh.free()
+
+
+def test_toggles_adjacency_from_global_memory(moc):
+    """A graph whose adjacency lists do not fit the LDS beside the base (n = 6000, m = 12000):
+    the kernel then reads them from global memory."""
+    from paper_2304_14463_amd.inputs import graph_from_edges
+    rng = np.random.default_rng(61)
+    n, C = 6000, 1
+    edges = sorted({(int(u), v) for v in range(1, n) for u in rng.integers(max(0, v - 50), v, size=2)})
+    g = graph_from_edges(n, edges, rng.integers(1, 30, n), rng.integers(1, 9, n))
+    T = n * C
+    s = np.arange(T, dtype=np.int32)[None].repeat(2, 0)
+    last = np.arange(T, dtype=np.int32)
+    for u, v in edges:
+        last[u] = max(last[u], v)
+    e = last[None].repeat(2, 0).astype(np.int32)
+    a = np.ones((2, T), np.uint8)
+    flip = rng.random(T) < 0.2
+    a[1, flip] = 0                                     # some nodes dropped: violations to mend
+    e[1] = np.minimum(T - 1, e[1] + rng.integers(-3, 4, T)).astype(np.int32)
+    gh = moc.moc_graph_upload(n, g.in_ptr, g.in_idx, g.size, g.dur, int(g.size.sum()), C)
+    ds, de, da = to_dev(s, e, a)
+    got = moc.results_to_numpy(moc.moc_eval_toggles(gh, ds, de, da), moc.TOGGLE_SCORE_DTYPE)
+    for b in range(2):
+        want = oracle.toggles(g, int(g.size.sum()), C, s[b], e[b], a[b])
+        assert (got[b]["violations"].astype(np.int64) == want[:, 0]).all(), b
+        assert (got[b]["peak"].astype(np.int64) == want[:, 1]).all(), b
+        assert (got[b]["duration"] == want[:, 2]).all(), b
+    gh.free()
