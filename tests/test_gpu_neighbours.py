@@ -310,3 +310,37 @@ def test_toggles_adjacency_from_global_memory(moc):
         assert (got[b]["peak"].astype(np.int64) == want[:, 1]).all(), b
         assert (got[b]["duration"] == want[:, 2]).all(), b
     gh.free()
+
+
+def test_neighbours_workload_wide_radius(moc, workloads):
+    """R = 16 (64-bit displacement masks) on 512 bases of the n=2000 workload: sampled moves
+    against the oracle, the best move against the table, the two kernels against each other."""
+    import torch
+    from paper_2304_14463_amd.inputs import DeviceWorkload
+    w = workloads(3)
+    R, Bs = 16, 512
+    gh = upload(moc, w)
+    ds, de, da = DeviceWorkload(w).candidates()
+    ds, de, da = ds[:Bs].contiguous(), de[:Bs].contiguous(), da[:Bs].contiguous()
+    om_t, ob_t = moc.moc_eval_neighbours(gh, ds, de, da, R)
+    _, ob_alone = moc.moc_eval_neighbours(gh, ds, de, da, R, want_moves=False)
+    torch.cuda.synchronize()
+    ob = moc.results_to_numpy(ob_t, moc.BEST_MOVE_DTYPE)
+    assert moc.results_to_numpy(ob_alone, moc.BEST_MOVE_DTYPE).tobytes() == ob.tobytes()
+    n_moves = w.T * 4 * R
+    rng = np.random.default_rng(16)
+    for b in (0, Bs - 1):
+        s, e, a = ds[b].cpu().numpy(), de[b].cpu().numpy(), da[b].cpu().numpy()
+        row = moc.results_to_numpy(om_t[b], moc.MOVE_SCORE_DTYPE)
+        pick = np.sort(rng.choice(n_moves, 1500, replace=False))
+        scores, _ = oracle.neighbours(w.graph, w.budget, w.C, s, e, a, R, moves=pick)
+        assert (row["violations"][pick].astype(np.int64) == scores[:, 0]).all(), b
+        assert (row["peak"][pick].astype(np.int64) == scores[:, 1]).all(), b
+    for b0 in range(0, Bs, 64):
+        rows = moc.results_to_numpy(om_t[b0:b0 + 4], moc.MOVE_SCORE_DTYPE)
+        for j in range(4):
+            v, p = rows[j]["violations"].astype(np.int64), rows[j]["peak"].astype(np.int64)
+            ok = np.flatnonzero(v >= 0)
+            q = int(ok[np.lexsort((ok, p[ok], v[ok]))[0]])
+            assert (int(ob[b0 + j]["move"]), int(ob[b0 + j]["violations"]), int(ob[b0 + j]["peak"])) == (q, v[q], p[q])
+    gh.free()
