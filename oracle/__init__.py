@@ -1,5 +1,5 @@
 """ctypes front end of the CPU oracle (moc_oracle.cpp, moc_bruteforce.cpp,
-moc_exhaustive.cpp).
+moc_exhaustive.cpp, moc_decode.cpp).
 
 TEST INFRASTRUCTURE ONLY.  Imported by tests/, by the smoke check and by the
 CPU-baseline leg of the benchmark; never by the product path, and it imports
@@ -16,7 +16,7 @@ import subprocess
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SOURCES = ["moc_oracle.cpp", "moc_bruteforce.cpp", "moc_exhaustive.cpp"]
+_SOURCES = ["moc_oracle.cpp", "moc_bruteforce.cpp", "moc_exhaustive.cpp", "moc_decode.cpp"]
 _LIB_PATH = os.path.join(_HERE, "liboracle.so")
 _lib = None
 
@@ -132,6 +132,24 @@ def toggles(g, budget, C, starts, ends, active, T=None):
     lib().orc_toggles(*ga, ctypes.c_int64(budget), ctypes.c_int32(C), ctypes.c_int32(T),
                       _p(s, ctypes.c_int32), _p(e, ctypes.c_int32), _p(a, ctypes.c_uint8), _p(scores, ctypes.c_int64))
     return scores
+
+
+def decode(g, C, starts, active, T=None):
+    """Sequences the candidates stand for (active copies in start order) and their own
+    liveness footprint.  Returns (int64 [B][4] = status, length, peak, duration;
+    int32 [B][T] sequences padded with -1).  status 1 valid, 0 not a valid sequence,
+    -1 not decodable."""
+    K = g.n * C
+    T = K if T is None else T
+    s, a = _cand(starts, np.int32, K), _cand(active, np.uint8, K)
+    B = s.shape[0]
+    res = np.zeros((B, 4), dtype=np.int64)
+    seq = np.zeros((B, T), dtype=np.int32)
+    keep, ga = _graph_args(g)
+    for b in range(B):
+        lib().dec_decode(*ga, ctypes.c_int32(C), ctypes.c_int32(T), _p(s[b], ctypes.c_int32),
+                         _p(a[b], ctypes.c_uint8), _p(seq[b], ctypes.c_int32), _p(res[b], ctypes.c_int64))
+    return res, seq
 
 
 def simulate_sequence(g, seq):
