@@ -158,6 +158,27 @@ def measure_neighbours(moc, steps, warmup):
     ms = (time.perf_counter() - t0) * 1e3 / steps
     out["toggles"] = {"ms_per_step": ms, "moves_per_s": w.B * w.T / (ms * 1e-3), "bytes_written": w.B * w.T * 16}
     del ot
+    # back to sequences: every base decoded and costed, sequences written out
+    # -- of the candidates a search would decode: the violation-free bases, repeated to B rows
+    ev = moc.results_to_numpy(moc.moc_eval_batch(gh, ds, de, da))
+    clean = torch.from_numpy((ev["violations"] == 0).nonzero()[0]).cuda()
+    pick = clean[torch.arange(w.B, device="cuda") % clean.numel()]
+    ds, da = ds[pick].contiguous(), da[pick].contiguous()
+    del de
+    od, oq = moc.moc_decode_batch(gh, ds, da)
+    valid = float((moc.results_to_numpy(od, moc.DECODE_RESULT_DTYPE)["status"] == 1).mean())
+    for _ in range(warmup):
+        moc.moc_decode_batch(gh, ds, da, out=od, out_seq=oq)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        moc.moc_decode_batch(gh, ds, da, out=od, out_seq=oq)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    dec_bytes = w.B * (5 * w.T + 4 * w.T + 24)
+    out["decode"] = {"ms_per_step": ms, "candidates_per_s": w.B / (ms * 1e-3), "bytes_per_candidate": 9 * w.T + 24,
+                     "frac_valid": valid, "distinct_candidates": int(clean.numel()), "gb_per_s": dec_bytes / (ms * 1e-3) / 1e9}
+    del od, oq
     gh.free()
     return {"workload": w.name, "n": w.n, "m": w.m, "C": w.C, "T": w.T, "B": w.B, "R": w.R,
             "moves_per_candidate": n_moves, **out}

@@ -99,6 +99,13 @@ typedef struct {
 } moc_toggle_score;   /* 16 bytes */
 
 typedef struct {
+  int32_t status;     /* 1 a valid sequence, 0 decoded but not valid, -1 not decodable */
+  int32_t length;     /* number of steps = active copies; 0 when status == -1 */
+  int64_t peak;       /* the sequence's own peak footprint; 0 unless status == 1 */
+  int64_t duration;   /* summed duration of its steps; 0 unless status == 1 */
+} moc_decode_result;  /* 24 bytes */
+
+typedef struct {
   int32_t move;       /* index of the best move, -1 if no move is applicable */
   int32_t violations; /* 0 when move == -1 */
   int64_t peak;       /* 0 when move == -1 */
@@ -179,6 +186,33 @@ int moc_eval_neighbours(const moc_graph* g, int64_t B, const int32_t* starts, co
  */
 int moc_eval_toggles(const moc_graph* g, int64_t B, const int32_t* starts, const int32_t* ends,
                      const uint8_t* active, moc_toggle_score* out, void* hip_stream);
+
+/*
+ * Turn B candidates into the rematerialisation sequences they stand for and
+ * cost each sequence on its own terms (Section 2: the start of an active
+ * interval is the event at which its node is computed; Section 1, problem
+ * statement: validity, total duration and peak footprint of a sequence).
+ * Only starts and active flags are read.  The steps of a candidate are its
+ * active copies in order of their starts.  If an active copy starts outside
+ * [0, T) or two active copies share a start (Eq. (8), Eq. (6)) there is no such
+ * order: status -1.  The sequence is valid (status 1) when every node occurs
+ * and every predecessor of a step's node has been computed at an earlier step;
+ * otherwise status 0.  For a valid sequence, each use is served by the most
+ * recent earlier computation of the producer, an output is held from the step
+ * that computes it through the last step it serves (its own if none), and
+ * peak is the largest summed size held at any step.  A candidate without
+ * violations decodes to a valid sequence of the same duration whose peak is
+ * not above the candidate's (ends may keep outputs longer than needed).
+ *   out       device, moc_decode_result [B], 8-byte aligned
+ *   out_seq   device, int32 [B][T], or NULL: the node of every step in order,
+ *             then -1 up to T (all -1 when status == -1); 4-byte aligned
+ * This call keeps 2.5 words per copy in LDS: T <= about 16000.  Edges (v,v) are
+ * accepted (the first computation of such a node finds nothing to read: status
+ * 0).  B == 0 is a no-op.
+ * Errors: MOC_EINVAL, MOC_EDEVICE, MOC_EOVERFLOW (T too large for this call), MOC_EHIP.
+ */
+int moc_decode_batch(const moc_graph* g, int64_t B, const int32_t* starts, const uint8_t* active,
+                     moc_decode_result* out, int32_t* out_seq, void* hip_stream);
 
 /* Release a graph (synchronises its device first).  NULL is a no-op. */
 void moc_graph_free(moc_graph* g);

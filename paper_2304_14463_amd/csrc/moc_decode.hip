@@ -1,0 +1,241 @@
+// moc_decode_batch: from candidate assignments back to the rematerialisation sequences they
+// stand for, with each sequence's own cost (gfx950).
+//
+// Section 2 of the paper (arXiv 2304.14463): the start of an active interval is the event at
+// which its node is computed, so the active copies read in order of their starts are the
+// sequence.  Section 1 (problem statement): a sequence is valid when every node occurs and the
+// outputs of all predecessors of a node are in memory when it is computed; it costs the summed
+// duration and the peak footprint.  The footprint taken here is the sequence's own: a use is
+// served by the most recent earlier computation of the producer, an output is held from its
+// step through the last step it serves.
+//
+// One workgroup per candidate, everything in LDS.  Starts are distinct (otherwise the
+// candidate is not decodable), so sorting is a scatter by start followed by a prefix count of
+// the occupied positions; the footprint is computed over positions rather than steps -- an
+// empty position holds a subset of what the next step holds -- by the same difference array
+// and running sum as Eq. (4).
+#include "moc_internal.h"
+
+namespace {
+
+constexpr int kNT = 512;
+constexpr int kNW = kNT / kWave;
+constexpr uint32_t kNoStart = 0xFFFFu;
+
+struct DcLayout {
+  int T_pad;   // words in each of the two position arrays (>= T + 1, even)
+  int bytes;
+};
+
+DcLayout dc_layout(int T) {
+  DcLayout l;
+  l.T_pad = (T + 2) & ~1;
+  const int words = 2 * l.T_pad + l.T_pad / 2 + kNW + 8;
+  l.bytes = words * 4;
+  return l;
+}
+
+// Inclusive wave scan of one value per lane.
+__device__ __forceinline__ int wave_scan_add(int x, int lane) {
+#pragma unroll
+  for (int off = 1; off < kWave; off <<= 1) {
+    const int o = __shfl_up(x, off);
+    if (lane >= off) x += o;
+  }
+  return x;
+}
+
+// a[x] <- sum of a[0..x) for x in [0, T); returns the sum of all.  Every thread of the
+// workgroup calls it; ends with a barrier.
+__device__ int block_exclusive_sum(int32_t* a, int T, int32_t* scratch, int tid) {
+  const int lane = tid & (kWave - 1), wave = tid / kWave;
+  const int per = (T + kNT - 1) / kNT;
+  const int lo = min(tid * per, T), hi = min(lo + per, T);
+  int acc = 0;
+  for (int x = lo; x < hi; ++x) acc += a[x];
+  const int inc = wave_scan_add(acc, lane);
+  if (lane == kWave - 1) scratch[wave] = inc;
+  __syncthreads();
+  int before = 0, total = 0;
+  for (int w = 0; w < kNW; ++w) {
+    const int t = scratch[w];
+    if (w < wave) before += t;
+    total += t;
+  }
+  int run = before + inc - acc;
+  for (int x = lo; x < hi; ++x) {
+    const int t = a[x];
+    a[x] = run;
+    run += t;
+  }
+  __syncthreads();
+  return total;
+}
+
+// max over x in [0, T) of a[0] + ... + a[x] (at least 0).  Ends with a barrier.
+__device__ int block_peak_of_running_sum(const int32_t* a, int T, int32_t* scratch, int tid) {
+  const int lane = tid & (kWave - 1), wave = tid / kWave;
+  const int per = (T + kNT - 1) / kNT;
+  const int lo = min(tid * per, T), hi = min(lo + per, T);
+  int acc = 0;
+  for (int x = lo; x < hi; ++x) acc += a[x];
+  const int inc = wave_scan_add(acc, lane);
+  if (lane == kWave - 1) scratch[wave] = inc;
+  __syncthreads();
+  int run = inc - acc;
+  for (int w = 0; w < wave; ++w) run += scratch[w];
+  int best = 0;
+  for (int x = lo; x < hi; ++x) {
+    run += a[x];
+    best = max(best, run);
+  }
+#pragma unroll
+  for (int off = kWave / 2; off > 0; off >>= 1) best = max(best, __shfl_xor(best, off));
+  __syncthreads();   // every wave has read the partial sums
+  if (lane == 0) scratch[wave] = best;
+  __syncthreads();
+  for (int w = 0; w < kNW; ++w) best = max(best, scratch[w]);
+  __syncthreads();
+  return best;
+}
+
+__global__ __launch_bounds__(kNT) void decode_kernel(GraphView G, int64_t B, const int32_t* __restrict__ starts,
+                                                     const uint8_t* __restrict__ active,
+                                                     moc_decode_result* __restrict__ out, int32_t* __restrict__ out_seq,
+                                                     DcLayout lay) {
+  extern __shared__ int32_t lds[];
+  int32_t* a = lds;                 // occupancy, then step number, then memory differences, per position
+  int32_t* b = a + lay.T_pad;       // the sequence, then the last position each computation serves
+  uint16_t* st = reinterpret_cast<uint16_t*>(b + lay.T_pad);   // start of each copy, kNoStart if inactive
+  int32_t* scratch = reinterpret_cast<int32_t*>(st + lay.T_pad);
+  int32_t* flags = scratch + kNW;   // [0] not decodable, [1] not a valid sequence, [2] duration
+  const int tid = threadIdx.x, T = G.T, n = G.n, C = G.C, m = G.m;
+
+  for (int64_t cand = blockIdx.x; cand < B; cand += gridDim.x) {
+    const int32_t* s_row = starts + cand * T;
+    const uint8_t* a_row = active + cand * T;
+    int32_t* seq_row = out_seq ? out_seq + cand * T : nullptr;
+
+    for (int x = tid; x <= T; x += kNT) a[x] = 0;
+    if (tid < 4) flags[tid] = 0;
+    __syncthreads();
+
+    // scatter by start: a[x] = 1 where a computation happens
+    for (int k = tid; k < T; k += kNT) {
+      uint32_t sk = kNoStart;
+      if (a_row[k]) {
+        const int s = s_row[k];
+        if (s < 0 || s >= T) {
+          flags[0] = 1;                       // Eq. (8)
+        } else {
+          sk = (uint32_t)s;
+          if (atomicAdd(&a[s], 1) != 0) flags[0] = 1;   // Eq. (6)
+        }
+      }
+      st[k] = (uint16_t)sk;
+    }
+    __syncthreads();
+    if (flags[0]) {
+      if (seq_row)
+        for (int x = tid; x < T; x += kNT) seq_row[x] = -1;
+      if (tid == 0) out[cand] = moc_decode_result{-1, 0, 0, 0};
+      __syncthreads();
+      continue;
+    }
+
+    // step number of each occupied position
+    const int length = block_exclusive_sum(a, T, scratch, tid);
+
+    // per node: does it occur, what does it add to the duration, where do its steps go
+    int my_dur = 0;
+    for (int v = tid; v < n; v += kNT) {
+      int times = 0;
+      for (int i = 0; i < C; ++i) {
+        const uint32_t p = st[v * C + i];
+        if (p == kNoStart) continue;
+        ++times;
+        if (seq_row) b[a[p]] = v;
+      }
+      if (times == 0) flags[1] = 1;
+      my_dur += times * G.size_dur[v].y;
+    }
+    if (my_dur) atomicAdd(&flags[2], my_dur);
+    if (seq_row) {
+      for (int x = length + tid; x < T; x += kNT) b[x] = -1;
+      __syncthreads();
+      for (int x = tid; x < T; x += kNT) seq_row[x] = b[x];
+    }
+    __syncthreads();
+
+    // every computation serves at least its own step; the difference array starts at zero
+    for (int x = tid; x <= T; x += kNT) a[x] = 0;
+    for (int k = tid; k < T; k += kNT) {
+      const uint32_t p = st[k];
+      if (p != kNoStart) b[p] = (int)p;
+    }
+    __syncthreads();
+
+    // one lane per edge (u, v): each computation of v is served by the latest computation of u before it
+    for (int e = tid; e < m; e += kNT) {
+      const uint32_t pair = G.edge_pair_c[e];
+      const int uC = (int)(pair & 0xFFFFu), vC = (int)(pair >> 16);
+      for (int i = 0; i < C; ++i) {
+        const uint32_t p = st[vC + i];
+        if (p == kNoStart) continue;
+        int q = -1;
+        for (int j = 0; j < C; ++j) {
+          const uint32_t sj = st[uC + j];
+          if (sj < p) q = max(q, (int)sj);    // kNoStart is above every position
+        }
+        if (q < 0) flags[1] = 1;
+        else atomicMax(&b[q], (int)p);
+      }
+    }
+    __syncthreads();
+
+    // held from p through b[p]
+    for (int v = tid; v < n; v += kNT) {
+      const int sz = G.size_dur[v].x;
+      for (int i = 0; i < C; ++i) {
+        const uint32_t p = st[v * C + i];
+        if (p == kNoStart) continue;
+        atomicAdd(&a[p], sz);
+        atomicAdd(&a[b[p] + 1], -sz);
+      }
+    }
+    __syncthreads();
+    const int peak = block_peak_of_running_sum(a, T, scratch, tid);
+
+    if (tid == 0) {
+      const bool valid = flags[1] == 0;
+      out[cand] = moc_decode_result{valid ? 1 : 0, length, valid ? (int64_t)peak : 0, valid ? (int64_t)flags[2] : 0};
+    }
+    __syncthreads();
+  }
+}
+
+}  // namespace
+
+extern "C" int moc_decode_batch(const moc_graph* g, int64_t B, const int32_t* starts, const uint8_t* active,
+                                moc_decode_result* out, int32_t* out_seq, void* hip_stream) {
+  if (!g || B < 0) return MOC_EINVAL;
+  if (B == 0) return MOC_OK;
+  if (!starts || !active || !out) return MOC_EINVAL;
+  if (((uintptr_t)starts & 3) || ((uintptr_t)out & 7) || ((uintptr_t)out_seq & 3)) return MOC_EINVAL;
+  int dev = -1;
+  MOC_HIP(hipGetDevice(&dev));
+  if (dev != g->device) return MOC_EDEVICE;
+  const DcLayout lay = dc_layout(g->view.T);
+  if (lay.bytes > g->max_lds) return MOC_EOVERFLOW;
+  MOC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(decode_kernel),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, lay.bytes));
+  int per_cu = 0;
+  MOC_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel, kNT, lay.bytes));
+  if (per_cu < 1) per_cu = 1;
+  const int64_t resident = (int64_t)per_cu * g->num_cu;
+  const unsigned grid = (unsigned)(B < resident ? B : resident);
+  hipLaunchKernelGGL(decode_kernel, dim3(grid), dim3(kNT), lay.bytes, static_cast<hipStream_t>(hip_stream), g->view, B,
+                     starts, active, out, out_seq, lay);
+  MOC_HIP(hipGetLastError());
+  return MOC_OK;
+}

@@ -23,9 +23,10 @@ RESULT_DTYPE = np.dtype([("peak", "<i8"), ("duration", "<i8"), ("violations", "<
 MOVE_SCORE_DTYPE = np.dtype([("violations", "<i4"), ("peak", "<i4")])
 BEST_MOVE_DTYPE = np.dtype([("move", "<i4"), ("violations", "<i4"), ("peak", "<i8")])
 TOGGLE_SCORE_DTYPE = np.dtype([("violations", "<i4"), ("peak", "<i4"), ("duration", "<i8")])
+DECODE_RESULT_DTYPE = np.dtype([("status", "<i4"), ("length", "<i4"), ("peak", "<i8"), ("duration", "<i8")])
 
 EXPORTS = ("moc_graph_upload", "moc_graph_info", "moc_eval_batch", "moc_eval_neighbours", "moc_eval_toggles",
-           "moc_graph_free", "moc_strerror", "moc_last_hip_error")
+           "moc_decode_batch", "moc_graph_free", "moc_strerror", "moc_last_hip_error")
 
 
 class MoccasinError(RuntimeError):
@@ -54,6 +55,8 @@ def lib():
         L.moc_eval_neighbours.restype = ctypes.c_int
         L.moc_eval_toggles.argtypes = [VP, I64, VP, VP, VP, VP, VP]
         L.moc_eval_toggles.restype = ctypes.c_int
+        L.moc_decode_batch.argtypes = [VP, I64, VP, VP, VP, VP, VP]
+        L.moc_decode_batch.restype = ctypes.c_int
         L.moc_graph_free.argtypes = [VP]
         L.moc_graph_free.restype = None
         L.moc_strerror.argtypes = [ctypes.c_int]
@@ -165,6 +168,26 @@ def moc_eval_toggles(g: Graph, starts, ends, active, out=None, stream=None):
     code = lib().moc_eval_toggles(g._h, B, ps, pe, pa, ctypes.c_void_p(out.data_ptr()), _stream_handle(stream))
     _check(code, "moc_eval_toggles")
     return out
+
+
+def moc_decode_batch(g: Graph, starts, active, want_seq=True, out=None, out_seq=None, stream=None):
+    """Decode B candidates to their sequences.  Returns (uint8 CUDA tensor [B][24] of
+    moc_decode_result, int32 CUDA tensor [B][T] of sequences or None)."""
+    import torch
+    B = starts.numel() // g.T if g.T else 0
+    for t, dt in ((starts, torch.int32), (active, torch.uint8)):
+        if not (t.is_cuda and t.is_contiguous() and t.dtype == dt and t.numel() == B * g.T):
+            raise ValueError("candidate arrays must be contiguous CUDA tensors [B][T]: int32 starts, uint8 active")
+    if out is None:
+        out = torch.empty((B, DECODE_RESULT_DTYPE.itemsize), dtype=torch.uint8, device=starts.device)
+    if out_seq is None and want_seq:
+        out_seq = torch.empty((B, g.T), dtype=torch.int32, device=starts.device)
+    code = lib().moc_decode_batch(
+        g._h, B, ctypes.c_void_p(starts.data_ptr()), ctypes.c_void_p(active.data_ptr()),
+        ctypes.c_void_p(out.data_ptr()), ctypes.c_void_p(out_seq.data_ptr()) if out_seq is not None else None,
+        _stream_handle(stream))
+    _check(code, "moc_decode_batch")
+    return out, out_seq
 
 
 def results_to_numpy(out, dtype=RESULT_DTYPE):

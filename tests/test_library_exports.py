@@ -32,6 +32,7 @@ def test_library_exports_every_declared_symbol():
     assert lib.moc_graph_info(None, None, None, None, None) == -1
     assert lib.moc_eval_batch(None, 0, None, None, None, None, None) == -1
     assert lib.moc_eval_toggles(None, 0, None, None, None, None, None) == -1
+    assert lib.moc_decode_batch(None, 0, None, None, None, None, None) == -1
     out = ctypes.c_void_p(1)
     assert lib.moc_graph_upload(0, None, None, None, None, 0, 1, ctypes.byref(out)) == -1 and not out.value
 
@@ -40,6 +41,7 @@ def test_result_struct_layout():
     from paper_2304_14463_amd import moccasin
     assert moccasin.RESULT_DTYPE.itemsize == 24 and moccasin.MOVE_SCORE_DTYPE.itemsize == 8
     assert moccasin.BEST_MOVE_DTYPE.itemsize == 16 and moccasin.TOGGLE_SCORE_DTYPE.itemsize == 16
+    assert moccasin.DECODE_RESULT_DTYPE.itemsize == 24
 
 
 def test_device_generator_library_loads():
