@@ -30,7 +30,7 @@ struct DcLayout {
 DcLayout dc_layout(int T) {
   DcLayout l;
   l.T_pad = (T + 2) & ~1;
-  const int words = 2 * l.T_pad + l.T_pad / 2 + kNW + 8;
+  const int words = 2 * l.T_pad + l.T_pad / 2 + 2 * kNW + 8;
   l.bytes = words * 4;
   return l;
 }
@@ -45,16 +45,24 @@ __device__ __forceinline__ int wave_scan_add(int x, int lane) {
   return x;
 }
 
-// a[x] <- sum of a[0..x) for x in [0, T); returns the sum of all.  Every thread of the
-// workgroup calls it; ends with a barrier.
-__device__ int block_exclusive_sum(int32_t* a, int T, int32_t* scratch, int tid) {
+// Both scans below walk the array in rows of 64 consecutive positions, one lane per position
+// (no bank conflicts); wave w owns the rows [w * rows_per_wave, (w + 1) * rows_per_wave).
+
+// a[x] in {0, 1}: a[x] <- number of ones before x, for x in [0, T); returns the number of ones.
+// Every thread of the workgroup calls it; ends with a barrier.
+__device__ int block_rank_of_ones(int32_t* a, int T, int32_t* scratch, int tid) {
   const int lane = tid & (kWave - 1), wave = tid / kWave;
-  const int per = (T + kNT - 1) / kNT;
-  const int lo = min(tid * per, T), hi = min(lo + per, T);
-  int acc = 0;
-  for (int x = lo; x < hi; ++x) acc += a[x];
-  const int inc = wave_scan_add(acc, lane);
-  if (lane == kWave - 1) scratch[wave] = inc;
+  const int rows = (T + kWave - 1) / kWave, rows_per_wave = (rows + kNW - 1) / kNW;
+  const int r0 = min(wave * rows_per_wave, rows), r1 = min(r0 + rows_per_wave, rows);
+  int carry = 0;
+  for (int r = r0; r < r1; ++r) {
+    const int x = r * kWave + lane;
+    const bool one = x < T && a[x] != 0;
+    const uint64_t ones = __ballot(one);
+    if (x < T) a[x] = carry + __popcll(ones & ((1ull << lane) - 1));
+    carry += __popcll(ones);
+  }
+  if (lane == 0) scratch[wave] = carry;
   __syncthreads();
   int before = 0, total = 0;
   for (int w = 0; w < kNW; ++w) {
@@ -62,12 +70,11 @@ __device__ int block_exclusive_sum(int32_t* a, int T, int32_t* scratch, int tid)
     if (w < wave) before += t;
     total += t;
   }
-  int run = before + inc - acc;
-  for (int x = lo; x < hi; ++x) {
-    const int t = a[x];
-    a[x] = run;
-    run += t;
-  }
+  if (before)
+    for (int r = r0; r < r1; ++r) {
+      const int x = r * kWave + lane;
+      if (x < T) a[x] += before;
+    }
   __syncthreads();
   return total;
 }
@@ -75,40 +82,46 @@ __device__ int block_exclusive_sum(int32_t* a, int T, int32_t* scratch, int tid)
 // max over x in [0, T) of a[0] + ... + a[x] (at least 0).  Ends with a barrier.
 __device__ int block_peak_of_running_sum(const int32_t* a, int T, int32_t* scratch, int tid) {
   const int lane = tid & (kWave - 1), wave = tid / kWave;
-  const int per = (T + kNT - 1) / kNT;
-  const int lo = min(tid * per, T), hi = min(lo + per, T);
-  int acc = 0;
-  for (int x = lo; x < hi; ++x) acc += a[x];
-  const int inc = wave_scan_add(acc, lane);
-  if (lane == kWave - 1) scratch[wave] = inc;
-  __syncthreads();
-  int run = inc - acc;
-  for (int w = 0; w < wave; ++w) run += scratch[w];
-  int best = 0;
-  for (int x = lo; x < hi; ++x) {
-    run += a[x];
-    best = max(best, run);
+  const int rows = (T + kWave - 1) / kWave, rows_per_wave = (rows + kNW - 1) / kNW;
+  const int r0 = min(wave * rows_per_wave, rows), r1 = min(r0 + rows_per_wave, rows);
+  int carry = 0, top = INT32_MIN;   // sum and highest running sum of this wave's rows, from the wave's first position
+  for (int r = r0; r < r1; ++r) {
+    const int x = r * kWave + lane;
+    const int inc = wave_scan_add(x < T ? a[x] : 0, lane);
+    top = max(top, carry + inc);
+    carry += __shfl(inc, kWave - 1);
   }
 #pragma unroll
-  for (int off = kWave / 2; off > 0; off >>= 1) best = max(best, __shfl_xor(best, off));
-  __syncthreads();   // every wave has read the partial sums
-  if (lane == 0) scratch[wave] = best;
+  for (int off = kWave / 2; off > 0; off >>= 1) top = max(top, __shfl_xor(top, off));
+  if (lane == 0) {
+    scratch[wave] = carry;
+    scratch[kNW + wave] = top;
+  }
   __syncthreads();
-  for (int w = 0; w < kNW; ++w) best = max(best, scratch[w]);
+  int best = 0, before = 0;
+  for (int w = 0; w < kNW; ++w) {
+    const int t = scratch[kNW + w];
+    if (t != INT32_MIN) best = max(best, before + t);
+    before += scratch[w];
+  }
   __syncthreads();
   return best;
 }
 
-__global__ __launch_bounds__(kNT) void decode_kernel(GraphView G, int64_t B, const int32_t* __restrict__ starts,
-                                                     const uint8_t* __restrict__ active,
-                                                     moc_decode_result* __restrict__ out, int32_t* __restrict__ out_seq,
-                                                     DcLayout lay) {
+// Loops over copies, nodes and edges run the same number of rounds in every lane, kUnroll
+// items per lane and round, and read what they need from global memory at the top of a round:
+// the loads of a round are in flight together instead of one behind the other.
+constexpr int kUnroll = 4;
+
+__global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8)))
+void decode_kernel(GraphView G, int64_t B, const int32_t* __restrict__ starts, const uint8_t* __restrict__ active,
+                   moc_decode_result* __restrict__ out, int32_t* __restrict__ out_seq, DcLayout lay) {
   extern __shared__ int32_t lds[];
   int32_t* a = lds;                 // occupancy, then step number, then memory differences, per position
   int32_t* b = a + lay.T_pad;       // the sequence, then the last position each computation serves
   uint16_t* st = reinterpret_cast<uint16_t*>(b + lay.T_pad);   // start of each copy, kNoStart if inactive
   int32_t* scratch = reinterpret_cast<int32_t*>(st + lay.T_pad);
-  int32_t* flags = scratch + kNW;   // [0] not decodable, [1] not a valid sequence, [2] duration
+  int32_t* flags = scratch + 2 * kNW;   // [0] not decodable, [1] not a valid sequence, [2] duration
   const int tid = threadIdx.x, T = G.T, n = G.n, C = G.C, m = G.m;
 
   for (int64_t cand = blockIdx.x; cand < B; cand += gridDim.x) {
@@ -121,18 +134,31 @@ __global__ __launch_bounds__(kNT) void decode_kernel(GraphView G, int64_t B, con
     __syncthreads();
 
     // scatter by start: a[x] = 1 where a computation happens
-    for (int k = tid; k < T; k += kNT) {
-      uint32_t sk = kNoStart;
-      if (a_row[k]) {
-        const int s = s_row[k];
-        if (s < 0 || s >= T) {
-          flags[0] = 1;                       // Eq. (8)
-        } else {
-          sk = (uint32_t)s;
-          if (atomicAdd(&a[s], 1) != 0) flags[0] = 1;   // Eq. (6)
-        }
+    for (int round = 0; round < T; round += kUnroll * kNT) {
+      const int base = round + tid;
+      uint8_t on[kUnroll];
+      int32_t s[kUnroll];
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) {
+        const int k = base + u * kNT;
+        on[u] = k < T ? a_row[k] : (uint8_t)0;
+        s[u] = k < T ? s_row[k] : 0;
       }
-      st[k] = (uint16_t)sk;
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) {
+        const int k = base + u * kNT;
+        if (k >= T) continue;
+        uint32_t sk = kNoStart;
+        if (on[u]) {
+          if (s[u] < 0 || s[u] >= T) {
+            flags[0] = 1;                       // Eq. (8)
+          } else {
+            sk = (uint32_t)s[u];
+            if (atomicAdd(&a[s[u]], 1) != 0) flags[0] = 1;   // Eq. (6)
+          }
+        }
+        st[k] = (uint16_t)sk;
+      }
     }
     __syncthreads();
     if (flags[0]) {
@@ -144,28 +170,19 @@ __global__ __launch_bounds__(kNT) void decode_kernel(GraphView G, int64_t B, con
     }
 
     // step number of each occupied position
-    const int length = block_exclusive_sum(a, T, scratch, tid);
+    const int length = block_rank_of_ones(a, T, scratch, tid);
 
-    // per node: does it occur, what does it add to the duration, where do its steps go
-    int my_dur = 0;
-    for (int v = tid; v < n; v += kNT) {
-      int times = 0;
-      for (int i = 0; i < C; ++i) {
-        const uint32_t p = st[v * C + i];
-        if (p == kNoStart) continue;
-        ++times;
-        if (seq_row) b[a[p]] = v;
-      }
-      if (times == 0) flags[1] = 1;
-      my_dur += times * G.size_dur[v].y;
-    }
-    if (my_dur) atomicAdd(&flags[2], my_dur);
     if (seq_row) {
+      for (int v = tid; v < n; v += kNT)
+        for (int i = 0; i < C; ++i) {
+          const uint32_t p = st[v * C + i];
+          if (p != kNoStart) b[a[p]] = v;
+        }
       for (int x = length + tid; x < T; x += kNT) b[x] = -1;
       __syncthreads();
       for (int x = tid; x < T; x += kNT) seq_row[x] = b[x];
+      __syncthreads();
     }
-    __syncthreads();
 
     // every computation serves at least its own step; the difference array starts at zero
     for (int x = tid; x <= T; x += kNT) a[x] = 0;
@@ -176,33 +193,54 @@ __global__ __launch_bounds__(kNT) void decode_kernel(GraphView G, int64_t B, con
     __syncthreads();
 
     // one lane per edge (u, v): each computation of v is served by the latest computation of u before it
-    for (int e = tid; e < m; e += kNT) {
-      const uint32_t pair = G.edge_pair_c[e];
-      const int uC = (int)(pair & 0xFFFFu), vC = (int)(pair >> 16);
-      for (int i = 0; i < C; ++i) {
-        const uint32_t p = st[vC + i];
-        if (p == kNoStart) continue;
-        int q = -1;
-        for (int j = 0; j < C; ++j) {
-          const uint32_t sj = st[uC + j];
-          if (sj < p) q = max(q, (int)sj);    // kNoStart is above every position
+    for (int round = 0; round < m; round += kUnroll * kNT) {
+      const int base = round + tid;
+      uint32_t pair[kUnroll];
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) pair[u] = base + u * kNT < m ? G.edge_pair_c[base + u * kNT] : 0u;
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) {
+        if (base + u * kNT >= m) continue;
+        const int uC = (int)(pair[u] & 0xFFFFu), vC = (int)(pair[u] >> 16);
+        for (int i = 0; i < C; ++i) {
+          const uint32_t p = st[vC + i];
+          if (p == kNoStart) continue;
+          int q = -1;
+          for (int j = 0; j < C; ++j) {
+            const uint32_t sj = st[uC + j];
+            if (sj < p) q = max(q, (int)sj);    // kNoStart is above every position
+          }
+          if (q < 0) flags[1] = 1;
+          else atomicMax(&b[q], (int)p);
         }
-        if (q < 0) flags[1] = 1;
-        else atomicMax(&b[q], (int)p);
       }
     }
     __syncthreads();
 
-    // held from p through b[p]
-    for (int v = tid; v < n; v += kNT) {
-      const int sz = G.size_dur[v].x;
-      for (int i = 0; i < C; ++i) {
-        const uint32_t p = st[v * C + i];
-        if (p == kNoStart) continue;
-        atomicAdd(&a[p], sz);
-        atomicAdd(&a[b[p] + 1], -sz);
+    // per node: does it occur, what does it add to the duration; its outputs are held from p through b[p]
+    int my_dur = 0;
+    for (int round = 0; round < n; round += kUnroll * kNT) {
+      const int base = round + tid;
+      int2 sd[kUnroll];
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) sd[u] = base + u * kNT < n ? G.size_dur[base + u * kNT] : make_int2(0, 0);
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) {
+        const int v = base + u * kNT;
+        if (v >= n) continue;
+        int times = 0;
+        for (int i = 0; i < C; ++i) {
+          const uint32_t p = st[v * C + i];
+          if (p == kNoStart) continue;
+          ++times;
+          atomicAdd(&a[p], sd[u].x);
+          atomicAdd(&a[b[p] + 1], -sd[u].x);
+        }
+        if (times == 0) flags[1] = 1;
+        my_dur += times * sd[u].y;
       }
     }
+    if (my_dur) atomicAdd(&flags[2], my_dur);
     __syncthreads();
     const int peak = block_peak_of_running_sum(a, T, scratch, tid);
 
