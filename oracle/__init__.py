@@ -46,6 +46,7 @@ def lib():
         _lib.orc_result_fields.restype = ctypes.c_int
         _lib.bf_enumerate.restype = ctypes.c_int64
         _lib.bf_simulate.restype = ctypes.c_int
+        _lib.orc_cut_apply.restype = ctypes.c_int
         assert _lib.orc_result_fields() == len(FIELDS)
     return _lib
 
@@ -132,6 +133,35 @@ def toggles(g, budget, C, starts, ends, active, T=None):
     lib().orc_toggles(*ga, ctypes.c_int64(budget), ctypes.c_int32(C), ctypes.c_int32(T),
                       _p(s, ctypes.c_int32), _p(e, ctypes.c_int32), _p(a, ctypes.c_uint8), _p(scores, ctypes.c_int64))
     return scores
+
+
+def cuts(g, budget, C, starts, ends, active, T=None):
+    """Scores of the m*C cut-and-recompute moves of one candidate (in-edge x in CSR order,
+    consumer copy i; q = x*C + i) by full re-evaluation of the edited candidate:
+    int64 [m*C][3] = (violations, peak, duration), (-1, -1, 0) where not applicable."""
+    K = g.n * C
+    T = K if T is None else T
+    s, e, a = _cand(starts, np.int32, K), _cand(ends, np.int32, K), _cand(active, np.uint8, K)
+    assert s.shape[0] == 1
+    m = int(np.asarray(g.in_ptr)[-1])
+    scores = np.zeros((m * C, 3), dtype=np.int64)
+    keep, ga = _graph_args(g)
+    lib().orc_cuts(*ga, ctypes.c_int64(budget), ctypes.c_int32(C), ctypes.c_int32(T),
+                   _p(s, ctypes.c_int32), _p(e, ctypes.c_int32), _p(a, ctypes.c_uint8), _p(scores, ctypes.c_int64))
+    return scores
+
+
+def cut_apply(g, C, starts, ends, active, x, i, T=None):
+    """The candidate after the cut for in-edge x and consumer copy i: (applicable, s, e, a)."""
+    K = g.n * C
+    T = K if T is None else T
+    s, e, a = _cand(starts, np.int32, K), _cand(ends, np.int32, K), _cand(active, np.uint8, K)
+    s2, e2, a2 = np.zeros(K, np.int32), np.zeros(K, np.int32), np.zeros(K, np.uint8)
+    keep, ga = _graph_args(g)
+    ok = lib().orc_cut_apply(*ga, ctypes.c_int32(C), ctypes.c_int32(T), _p(s, ctypes.c_int32),
+                             _p(e, ctypes.c_int32), _p(a, ctypes.c_uint8), ctypes.c_int32(x), ctypes.c_int32(i),
+                             _p(s2, ctypes.c_int32), _p(e2, ctypes.c_int32), _p(a2, ctypes.c_uint8))
+    return bool(ok), s2, e2, a2
 
 
 def decode(g, C, starts, active, T=None):

@@ -237,4 +237,93 @@ void orc_toggles(int32_t n, const int32_t* in_ptr, const int32_t* in_idx, const 
   }
 }
 
+// The cut-and-recompute move for in-edge x = (u, v) (CSR order) and copy i of the consumer v,
+// applied to s, e, a in place.  Not part of the paper's text as a procedure: it is the edit that
+// turns "keep u's output until v needs it" into "recompute u just before v", the trade of
+// duration for memory the formulation exists for (Section 1; Eq. (1) against Eq. (4)).
+//   t  = start of the consumer copy, which must be live;
+//   k  = the live copy of u with s_k < t <= e_k that starts last (lowest index among equals);
+//   j  = the lowest copy of u that is not active;
+//   p  = the last position in (s_k, t) at which no live copy starts;
+//   e' = the last start, in (s_k, p), of a live copy of a consumer of u; s_k if there is none.
+// Copy k keeps [s_k, e'], copy j becomes active with [p, e_k].  Returns 0 (nothing changed) if
+// the consumer copy is not live or k, j or p does not exist.
+static int apply_cut(const Problem& p, int x, int i, int32_t* s, int32_t* e, uint8_t* a) {
+  const int C = p.C, T = p.T;
+  auto live = [&](int c) { return a[c] && s[c] >= 0 && s[c] <= e[c] && e[c] <= T - 1; };
+  int v = 0;
+  while (p.in_ptr[v + 1] <= x) ++v;
+  const int u = p.in_idx[x];
+  const int c = v * C + i;
+  if (!live(c)) return 0;
+  const int t = s[c];
+  int k = -1, j = -1;
+  for (int q = 0; q < C; ++q) {
+    const int cu = u * C + q;
+    if (live(cu) && s[cu] < t && t <= e[cu] && (k < 0 || s[cu] > s[k])) k = cu;
+    if (!a[cu] && j < 0) j = cu;
+  }
+  if (k < 0 || j < 0) return 0;
+  std::vector<char> taken(T, 0);
+  for (int q = 0; q < p.n * C; ++q)
+    if (live(q)) taken[s[q]] = 1;
+  int pos = t - 1;
+  while (pos > s[k] && taken[pos]) --pos;
+  if (pos <= s[k]) return 0;
+  int last_use = s[k];
+  for (int w = 0; w < p.n; ++w)
+    for (int y = p.in_ptr[w]; y < p.in_ptr[w + 1]; ++y)
+      if (p.in_idx[y] == u)
+        for (int q = 0; q < C; ++q) {
+          const int cw = w * C + q;
+          if (live(cw) && s[cw] > s[k] && s[cw] < pos && s[cw] > last_use) last_use = s[cw];
+        }
+  a[j] = 1;
+  s[j] = pos;
+  e[j] = e[k];
+  e[k] = last_use;
+  return 1;
+}
+
+// One cut applied to a copy of the candidate: out_s, out_e, out_a [n*C].  Returns 1 if the move
+// is applicable, 0 otherwise (outputs = inputs).
+int orc_cut_apply(int32_t n, const int32_t* in_ptr, const int32_t* in_idx, const int32_t* size, const int32_t* dur,
+                  int32_t C, int32_t T, const int32_t* starts, const int32_t* ends, const uint8_t* active,
+                  int32_t x, int32_t i, int32_t* out_s, int32_t* out_e, uint8_t* out_a) {
+  Problem p{n, in_ptr, in_idx, size, dur, 0, C, T};
+  const int K = n * C;
+  std::copy(starts, starts + K, out_s);
+  std::copy(ends, ends + K, out_e);
+  std::copy(active, active + K, out_a);
+  return apply_cut(p, x, i, out_s, out_e, out_a);
+}
+
+// Scores of all m*C cuts of one candidate: scores[3q..3q+2] = (violations, peak, duration) of
+// the edited candidate by full re-evaluation, q = x*C + i; (-1, -1, 0) where not applicable.
+void orc_cuts(int32_t n, const int32_t* in_ptr, const int32_t* in_idx, const int32_t* size, const int32_t* dur,
+              int64_t budget, int32_t C, int32_t T, const int32_t* starts, const int32_t* ends,
+              const uint8_t* active, int64_t* scores) {
+  Problem p{n, in_ptr, in_idx, size, dur, budget, C, T};
+  Scratch w;
+  const int K = n * C, m = in_ptr[n];
+  std::vector<int32_t> s(K), e(K);
+  std::vector<uint8_t> a(K);
+  int64_t res[R_FIELDS];
+  for (int x = 0; x < m; ++x)
+    for (int i = 0; i < C; ++i) {
+      std::copy(starts, starts + K, s.begin());
+      std::copy(ends, ends + K, e.begin());
+      std::copy(active, active + K, a.begin());
+      int64_t* out = scores + 3 * ((int64_t)x * C + i);
+      if (!apply_cut(p, x, i, s.data(), e.data(), a.data())) {
+        out[0] = -1; out[1] = -1; out[2] = 0;
+        continue;
+      }
+      evaluate(p, s.data(), e.data(), a.data(), w, res, nullptr);
+      out[0] = res[R_VIOLATIONS];
+      out[1] = res[R_PEAK];
+      out[2] = res[R_DURATION];
+    }
+}
+
 }  // extern "C"

@@ -1,0 +1,178 @@
+"""Pins of the oracle's cut-and-recompute move (oracle/moc_oracle.cpp, apply_cut
+and orc_cuts): keep a producer's output only as long as its earlier uses need
+it and recompute it just before a later use -- the trade of duration, Eq. (1),
+for memory, Eq. (4), that the formulation of arXiv 2304.14463 exists for.
+
+The edit is checked against the worked example of Section 2, against closed
+forms, against the sequence decoder and simulator (separate code), and by what
+must hold for any cut: memory falls by m_u exactly between the last earlier use
+and the recomputation and changes nowhere else, the duration grows by w_u, and
+no consumer of u loses its input.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2304_14463_amd.inputs import graph_from_edges
+from test_oracle_pins import worked_example
+
+F = {name: i for i, name in enumerate(oracle.FIELDS)}
+
+
+def edge_index(g, u, v):
+    """CSR index of the in-edge (u, v)."""
+    lo, hi = int(g.in_ptr[v]), int(g.in_ptr[v + 1])
+    return lo + list(g.in_idx[lo:hi]).index(u)
+
+
+def test_worked_example_is_one_cut_from_the_plain_schedule():
+    """Section 2: node 1 is kept until event 3 (its use by node 2) and computed
+    again for node 4 at the last event; the plain schedule keeps it throughout.
+    Cutting the edge 1 -> 4 gives the example's intervals, except that the second
+    interval starts at the last free event before event 10 (9; the drawing has 7)."""
+    kv, g, C, T, s, e, a = worked_example([1, 1, 1, 1], [3, 5, 7, 11])
+    plain_s, plain_e, plain_a = s.copy(), e.copy(), a.copy()
+    plain_a[1] = 0                       # no second interval of node 1 ...
+    plain_e[0] = e[1]                    # ... its first is kept to the last event
+    base = oracle.evaluate(g, 3, C, plain_s, plain_e, plain_a, T=T)[0]
+    assert base[F["violations"]] == 0 and base[F["duration"]] == 3 + 5 + 7 + 11
+    x = edge_index(g, 0, 3)
+    ok, s2, e2, a2 = oracle.cut_apply(g, C, plain_s, plain_e, plain_a, x, 0, T=T)
+    assert ok
+    assert (a2 == a).all() and (e2[a2 != 0] == e[a != 0]).all()
+    assert s2[1] == 8 and (np.delete(s2, 1)[np.delete(a2, 1) != 0] == np.delete(s, 1)[np.delete(a, 1) != 0]).all()
+    assert e2[0] + 1 == int(kv["node1.copy1"].split()[1])          # kept until event 3 (printed)
+    score = oracle.cuts(g, 3, C, plain_s, plain_e, plain_a, T=T)[x * C]
+    assert list(score) == [0, int(kv["peak.unit_sizes"]), 2 * 3 + 5 + 7 + 11]
+
+
+def test_closed_form_on_a_long_skip():
+    """Node 0 feeds node 1 and the last node of a chain.  Kept throughout, it
+    adds m_0 everywhere; cut for the last node, it is held on [0, 1] and from the
+    position before the last node only."""
+    n, C = 12, 2
+    edges = [(i, i + 1) for i in range(n - 1)] + [(0, n - 1)]
+    size = [50] + [3] * (n - 1)
+    g = graph_from_edges(n, edges, size, list(range(1, n + 1)))
+    T = n * C
+    s = np.zeros(T, np.int32); e = np.zeros(T, np.int32); a = np.zeros(T, np.uint8)
+    for v in range(n):                   # node v at position 2v (odd positions free), kept to its consumer
+        s[v * C], e[v * C], a[v * C] = 2 * v, 2 * (v + 1) if v + 1 < n else 2 * v, 1
+    e[0] = 2 * (n - 1)
+    base = oracle.evaluate(g, 10**9, C, s, e, a)[0]
+    assert base[F["violations"]] == 0 and base[F["peak"]] == 50 + 3 + 3
+    x = edge_index(g, 0, n - 1)
+    ok, s2, e2, a2 = oracle.cut_apply(g, C, s, e, a, x, 0)
+    assert ok and (s2[1], e2[1], a2[1]) == (2 * (n - 1) - 1, 2 * (n - 1), 1) and e2[0] == 2
+    score = oracle.cuts(g, 10**9, C, s, e, a)[x * C]
+    # the peak stays 50 + 3 + 3, now at the last position only (nodes 0, n-2 and n-1)
+    assert list(score) == [0, 56, base[F["duration"]] + 1]
+    _, prof0 = oracle.profile(g, 10**9, C, s, e, a)
+    _, prof1 = oracle.profile(g, 10**9, C, s2, e2, a2)
+    want = prof0.copy(); want[3:2 * (n - 1) - 1] -= 50
+    assert (prof1 == want).all() and prof1[3:2 * (n - 1) - 1].max() == 6
+    # the cut for the first consumer: recomputed at position 1, nothing gained
+    ok, s3, e3, a3 = oracle.cut_apply(g, C, s, e, a, edge_index(g, 0, 1), 0)
+    assert ok and (s3[1], e3[1], e3[0]) == (1, 2 * (n - 1), 0)
+
+
+def test_recomputation_goes_to_the_last_free_position():
+    """Node 0 feeds nodes 1..4 at positions 1, 3, 4, 5; position 2 is free.  For node 4 the
+    recomputation lands at 2 (3 and 4 are taken), behind the use by node 1 and before the uses
+    by nodes 2 and 3, which the new copy serves from then on."""
+    g = graph_from_edges(5, [(0, 1), (0, 2), (0, 3), (0, 4)], [9, 1, 1, 1, 1], [7, 1, 1, 1, 1])
+    C = 2
+    s = np.array([0, 0, 1, 0, 3, 0, 4, 0, 5, 0], np.int32)
+    e = np.array([5, 0, 1, 0, 3, 0, 4, 0, 5, 0], np.int32)
+    a = np.array([1, 0, 1, 0, 1, 0, 1, 0, 1, 0], np.uint8)
+    ok, s2, e2, a2 = oracle.cut_apply(g, C, s, e, a, edge_index(g, 0, 4), 0)
+    assert ok and (s2[0], e2[0]) == (0, 1) and (s2[1], e2[1], a2[1]) == (2, 5, 1)
+    sc = oracle.cuts(g, 100, C, s, e, a)
+    assert list(sc[edge_index(g, 0, 4) * C]) == [0, 10, 11 + 7]
+    # for node 2 (position 3) the same slot; for node 1 there is no free position in (0, 1)
+    assert list(sc[edge_index(g, 0, 2) * C]) == [0, 10, 18] and sc[edge_index(g, 0, 1) * C][0] == -1
+    # with two live copies covering the use, the one that starts last is cut
+    s[1], e[1], a[1] = 2, 5, 1           # copy 1 = [2, 5] active as well: no spare copy ...
+    assert (oracle.cuts(g, 100, C, s, e, a)[:, 0] == -1).all()
+    g3 = graph_from_edges(5, [(0, 1), (0, 2), (0, 3), (0, 4)], [9, 1, 1, 1, 1], [7, 1, 1, 1, 1])
+    s = np.array([0, 2, 0, 1, 0, 0, 3, 0, 0, 6, 0, 0, 8, 0, 0], np.int32)    # C = 3: node 0 at 0 and 2
+    e = np.array([8, 8, 0, 1, 0, 0, 3, 0, 0, 6, 0, 0, 8, 0, 0], np.int32)
+    a = np.array([1, 1, 0, 1, 0, 0, 1, 0, 0, 1, 0, 0, 1, 0, 0], np.uint8)
+    ok, s2, e2, a2 = oracle.cut_apply(g3, 3, s, e, a, edge_index(g3, 0, 4), 0)
+    assert ok and e2[0] == 8 and (s2[1], e2[1]) == (2, 6) and (s2[2], e2[2], a2[2]) == (7, 8, 1)
+    # two spare copies: the lower one is taken
+    a[1] = 0
+    ok, s2, e2, a2 = oracle.cut_apply(g3, 3, s, e, a, edge_index(g3, 0, 4), 0)
+    assert ok and (s2[0], e2[0]) == (0, 6) and (s2[1], e2[1], a2[1]) == (7, 8, 1) and a2[2] == 0
+
+
+def test_moves_that_do_not_apply():
+    g = graph_from_edges(3, [(0, 1), (0, 2), (1, 2)], [5, 1, 1], [1, 1, 1])
+    C, T = 2, 6
+    s = np.array([0, 0, 1, 0, 2, 0], np.int32); e = np.array([2, 0, 2, 0, 2, 0], np.int32)
+    a = np.array([1, 0, 1, 0, 1, 0], np.uint8)
+    sc = oracle.cuts(g, 100, C, s, e, a)
+    assert (sc == [-1, -1, 0]).all()     # positions 0, 1, 2 are all taken: no free slot before any consumer
+    # spread out: every edge has a cut for consumer copy 0, none for the inactive copy 1
+    s = np.array([0, 0, 2, 0, 4, 0], np.int32); e = np.array([4, 0, 4, 0, 4, 0], np.int32)
+    sc = oracle.cuts(g, 100, C, s, e, a)
+    assert (sc[0::2, 0] == 0).all() and (sc[1::2] == [-1, -1, 0]).all()
+    # no spare copy of the producer
+    a2 = a.copy(); a2[1] = 1; s2 = s.copy(); e2 = e.copy(); s2[1], e2[1] = 5, 5
+    sc = oracle.cuts(g, 100, C, s2, e2, a2)
+    assert (sc[[0, 2]] == [-1, -1, 0]).all() and sc[4][0] >= 0   # edges out of node 0 / the edge 1 -> 2
+    # the consumer's input is not covered by any copy of the producer: nothing to cut
+    e3 = e.copy(); e3[0] = 1
+    sc = oracle.cuts(g, 100, C, s, e3, a)
+    assert (sc[[0, 2]] == [-1, -1, 0]).all()
+    # one copy per node: never applicable
+    g1 = graph_from_edges(3, [(0, 1), (0, 2), (1, 2)], [5, 1, 1], [1, 1, 1])
+    assert (oracle.cuts(g1, 100, 1, [0, 1, 2], [2, 2, 2], [1, 1, 1]) == [-1, -1, 0]).all()
+
+
+@pytest.mark.parametrize("cfg", [0, 1])
+def test_what_every_cut_must_satisfy(workloads, cfg):
+    w = workloads(cfg)
+    g, C, T = w.graph, w.C, w.T
+    ss, ee, aa = w.candidates(0, 24)
+    ev = oracle.evaluate(g, w.budget, C, ss, ee, aa)
+    rows = [b for b in range(24) if ev[b, F["violations"]] == 0][:4] + [b for b in range(24) if ev[b, F["violations"]]][:2]
+    m = int(g.in_ptr[-1])
+    consumer = np.repeat(np.arange(g.n), np.diff(g.in_ptr))
+    applicable = improved = 0
+    for b in rows:
+        s, e, a = ss[b], ee[b], aa[b]
+        base, prof0 = oracle.profile(g, w.budget, C, s, e, a)
+        sc = oracle.cuts(g, w.budget, C, s, e, a)
+        for q in np.flatnonzero(sc[:, 0] >= 0)[::max(1, m * C // 150)]:
+            x, i = divmod(int(q), C)
+            u, v = int(g.in_idx[x]), int(consumer[x])
+            ok, s2, e2, a2 = oracle.cut_apply(g, C, s, e, a, x, i)
+            assert ok
+            changed = np.flatnonzero((s2 != s) | (e2 != e) | (a2 != a))
+            assert set(changed // C) == {u} and 1 <= changed.size <= 2
+            j = int(np.flatnonzero(a2 != a)[0])
+            k = [c for c in range(u * C, u * C + C) if a[c] and s[c] < s[v * C + i] <= e[c] and s[c] <= e[c] < T][-1:]
+            res, prof1 = oracle.profile(g, w.budget, C, s2, e2, a2)
+            assert list(res[:3]) == list(sc[q][[1, 2, 0]])
+            assert res[F["duration"]] == base[F["duration"]] + g.dur[u]
+            # memory falls by m_u strictly between the cut copy's new end and the recomputation
+            kk = int(np.flatnonzero(e2 != e)[0]) if (e2 != e).any() and a[np.flatnonzero(e2 != e)[0]] else None
+            lo = (e2[kk] if kk is not None else e[k[0]]) + 1
+            want = prof0.copy(); want[lo:s2[j]] -= g.size[u]
+            assert (prof1 == want).all()
+            assert s2[j] < s[v * C + i] and not ((a != 0) & (s == s2[j]) & (s <= e) & (e < T) & (s >= 0)).any()
+            # no consumer of u loses its input: only the recomputation's own inputs can be missing
+            assert res[F["v_prec"]] - base[F["v_prec"]] in range(0, int(g.in_ptr[u + 1] - g.in_ptr[u]) + 1)
+            assert res[F["v_start"]] == base[F["v_start"]] and res[F["v_form"]] == base[F["v_form"]]
+            applicable += 1
+            improved += int(res[F["peak"]] < base[F["peak"]])
+            if base[F["violations"]] == 0 and res[F["violations"]] == 0:
+                # the edited assignment is still a schedule: one more step, u, before v's
+                d0, seq0 = oracle.decode(g, C, s, a)
+                d1, seq1 = oracle.decode(g, C, s2, a2)
+                assert d1[0][0] == 1 and d1[0][1] == d0[0][1] + 1 and d1[0][2] <= res[F["peak"]]
+                step = int((np.sort(s[a != 0]) < s2[j]).sum())
+                assert list(seq1[0][:step]) == list(seq0[0][:step]) and seq1[0][step] == u
+                assert list(seq1[0][step + 1:d1[0][1]]) == list(seq0[0][step:d0[0][1]])
+    assert applicable > 100 and improved > 0
