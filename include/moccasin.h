@@ -98,6 +98,8 @@ typedef struct {
   int64_t duration;   /* as moc_result.duration: the base's, minus or plus w_v */
 } moc_toggle_score;   /* 16 bytes */
 
+typedef moc_toggle_score moc_cut_score; /* violations = peak = -1, duration = 0: not applicable */
+
 typedef struct {
   int32_t status;     /* 1 a valid sequence, 0 decoded but not valid, -1 not decodable */
   int32_t length;     /* number of steps = active copies; 0 when status == -1 */
@@ -186,6 +188,32 @@ int moc_eval_neighbours(const moc_graph* g, int64_t B, const int32_t* starts, co
  */
 int moc_eval_toggles(const moc_graph* g, int64_t B, const int32_t* starts, const int32_t* ends,
                      const uint8_t* active, moc_toggle_score* out, void* hip_stream);
+
+/*
+ * Score every cut-and-recompute move of B base candidates: keep a producer's
+ * output only as long as its earlier uses need it and compute it again just
+ * before a later use.  Not part of the paper as a procedure; it is the edit
+ * that trades duration, Eq. (1), for memory, Eq. (4), within the variables of
+ * Section 2.1.  Move index q = x*C + i: in-edge x = (u, v) in the order of
+ * in_idx, copy i of the consumer v.  With t the start of that copy (which must
+ * be live):
+ *   k   the live copy of u with s_k < t <= e_k that starts last (the lowest
+ *       index among equal starts),
+ *   j   the lowest copy of u that is not active,
+ *   p   the last position in (s_k, t) at which no live copy starts,
+ *   e'  the last start in (s_k, p) of a live copy of any consumer of u, s_k if
+ *       there is none;
+ * the move sets copy k to [s_k, e'] and copy j to active, [p, e_k].  It is not
+ * applicable (score -1, -1, 0) if the consumer copy is not live or k, j or p
+ * does not exist.  Otherwise entry [b][q] is what moc_eval_batch returns for
+ * the edited candidate (the duration is the base's plus w_u).
+ *   out   device, moc_cut_score [B][m*C], 8-byte aligned
+ * LDS use and limits as moc_eval_toggles.  A graph with an edge (v,v) is not
+ * accepted.  B == 0 or m == 0 is a no-op.
+ * Errors: MOC_EINVAL, MOC_EDEVICE, MOC_EOVERFLOW (T too large for this call), MOC_EHIP.
+ */
+int moc_eval_cuts(const moc_graph* g, int64_t B, const int32_t* starts, const int32_t* ends,
+                  const uint8_t* active, moc_cut_score* out, void* hip_stream);
 
 /*
  * Turn B candidates into the rematerialisation sequences they stand for and

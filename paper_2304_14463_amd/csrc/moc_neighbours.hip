@@ -855,6 +855,108 @@ __device__ __forceinline__ int toggle_delta(const Adj& g, int C, const uint32_t*
   return delta;
 }
 
+// max(a[from..to]), from <= to; eight reads in flight at a time (re-reading the last element
+// changes no maximum).
+__device__ __forceinline__ int range_max8(const int32_t* a, int from, int to) {
+  int m = 0;
+  for (int t = from; t <= to; t += 8) {
+    int x[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) x[j] = a[min(t + j, to)];
+    m = max(max(max(m, x[0]), max(x[1], x[2])), max(max(x[3], x[4]), max(max(x[5], x[6]), x[7])));
+  }
+  return m;
+}
+
+// max(profile[s..e]), s <= e, through the maxima over blocks of 32 positions for long ranges.
+__device__ __forceinline__ int interval_max(const int32_t* profile, const int32_t* block_max, int s, int e) {
+  if (e - s < 64) return range_max8(profile, s, e);
+  const int first_block = (s + 31) >> 5, last_block = (e + 1) >> 5;   // whole blocks [first, last)
+  int top = 0;
+  if (s < 32 * first_block) top = range_max8(profile, s, 32 * first_block - 1);
+  top = max(top, range_max8(block_max, first_block, last_block - 1));
+  if (32 * last_block <= e) top = max(top, range_max8(profile, 32 * last_block, e));
+  return top;
+}
+
+// The cut-and-recompute move for the in-edge (u, v) and copy i of the consumer (see
+// moc_eval_cuts in moccasin.h): copy k of u, the last-starting live copy that covers the
+// consumer's start t, keeps [s_k, last use before p]; the lowest inactive copy j of u takes
+// [p, e_k], p the last position in (s_k, t) where no live copy starts.  Only Eq. (3) among the
+// copies of u, Eq. (5) for the inputs of the new computation and Eq. (7) (when j is copy 0)
+// can change: every consumer that k covered is covered by one of the two pieces, since no
+// live consumer starts in (last use, p].  The profile loses m_u on (last use, p).
+// Returns false if the move is not applicable.
+__device__ __forceinline__ bool score_cut(const Adj& g, int C, int T, const NbLds& L, const int32_t* block_max,
+                                          const uint8_t* __restrict__ active_row, int u, int consumer_copy,
+                                          int base_viol, int base_peak, int* viol_out, int* peak_out) {
+  const uint32_t mine = L.packed[consumer_copy];
+  if (!live_of(mine)) return false;
+  const uint32_t t = mine & 0xFFFFu;
+  int k = -1, j = -1, sk = -1, ek = 0;
+  for (int q = 0; q < C; ++q) {
+    const uint32_t pu = L.packed[u * C + q];
+    if (covers1(pu, t) && (int)(pu & 0xFFFFu) > sk) {
+      k = q;
+      sk = (int)(pu & 0xFFFFu);
+      ek = (int)(pu >> 16);
+    }
+    if (j < 0 && active_row[u * C + q] == 0) j = q;
+  }
+  if (k < 0 || j < 0) return false;
+  // the last free position below t, by words of the start bitmap
+  int p = -1;
+  for (int pos = (int)t - 1; pos > sk;) {
+    const uint32_t free_bits = ~L.occ1[pos >> 5] & (0xFFFFFFFFu >> (31 - (pos & 31)));
+    if (free_bits) {
+      p = (pos & ~31) + 31 - __clz(free_bits);
+      break;
+    }
+    pos = (pos & ~31) - 1;
+  }
+  if (p <= sk) return false;
+  int last_use = sk;
+  for (int y = g.out_ptr[u]; y < g.out_ptr[u + 1]; ++y) {
+    const int w = g.out_idx[y];
+    for (int q = 0; q < C; ++q) {
+      const int x = (int)(L.packed[w * C + q] & 0xFFFFu);   // 0xFFFF (not live) is above every p
+      if (x > sk && x < p) last_use = max(last_use, x);
+    }
+  }
+  int vv = base_viol;
+  // Eq. (3) among the live copies of u, before and after
+  int before = 0, after = 0, end_before = -1, end_after = -1;
+  for (int q = 0; q < C; ++q) {
+    const uint32_t pu = L.packed[u * C + q];
+    if (live_of(pu)) {
+      before += end_before > (int)(pu & 0xFFFFu) ? 1 : 0;
+      end_before = (int)(pu >> 16);
+    }
+    const uint32_t now = q == k ? pack_copy(true, sk, last_use) : q == j ? pack_copy(true, p, ek) : pu;
+    if (live_of(now)) {
+      after += end_after > (int)(now & 0xFFFFu) ? 1 : 0;
+      end_after = (int)(now >> 16);
+    }
+  }
+  vv += after - before;
+  // Eq. (5): the inputs of the new computation at p
+  for (int y = g.in_ptr[u]; y < g.in_ptr[u + 1]; ++y) {
+    const int w = g.in_idx[y];
+    bool cov = false;
+    for (int q = 0; q < C; ++q) cov = cov || covers1(L.packed[w * C + q], (uint32_t)p);
+    vv += cov ? 0 : 1;
+  }
+  if (j == 0) --vv;   // Eq. (7)
+  int pk = base_peak;
+  if (last_use + 1 <= p - 1) {
+    const int top = interval_max(L.profile, block_max, last_use + 1, p - 1);
+    pk = max(top - g.size_of(u), max(L.pmax[last_use], L.smax[p]));
+  }
+  *viol_out = vv;
+  *peak_out = pk;
+  return true;
+}
+
 struct TgLayout {
   int T_pad, bit_words, blocks;
   int adj_off;   // word offset of the adjacency lists and sizes in LDS, 0 if they stay in global memory
@@ -880,7 +982,7 @@ TgLayout tg_layout(int T, int n, int m, int max_lds) {
   return l;
 }
 
-template <bool ADJ_LDS>
+template <bool ADJ_LDS, bool CUTS>
 __global__ __launch_bounds__(kNT) void toggles_kernel(GraphView g, int64_t B, const int32_t* __restrict__ starts,
                                                       const int32_t* __restrict__ ends,
                                                       const uint8_t* __restrict__ active,
@@ -974,6 +1076,25 @@ __global__ __launch_bounds__(kNT) void toggles_kernel(GraphView g, int64_t B, co
     __syncthreads();
     const int base_viol = counts[0], base_dur = counts[1], base_peak = L.pmax[T - 1];
 
+    if constexpr (CUTS) {
+      // ---- one lane per in-edge and copy of its consumer
+      const int64_t out_row = b * ((int64_t)g.m * C);
+      for (int q = tid; q < g.m * C; q += kNT) {
+        const int x = q / C, i = q - x * C;
+        const int u = A.in_idx[x];
+        const int consumer_copy = (int)(g.edge_pair_c[x] >> 16) + i;
+        moc_toggle_score sc{-1, -1, 0};
+        int vv, pk;
+        if (score_cut(A, C, T, L, block_max, active + row, u, consumer_copy, base_viol, base_peak, &vv, &pk)) {
+          sc.violations = vv;
+          sc.peak = pk;
+          sc.duration = (int64_t)base_dur + g.size_dur[u].y;
+        }
+        out[out_row + q] = sc;
+      }
+      __syncthreads();
+      continue;
+    }
     // ---- one lane per copy
     for (int k = tid; k < T; k += kNT) {
       const int v = k / C, i = k - v * C;
@@ -987,26 +1108,7 @@ __global__ __launch_bounds__(kNT) void toggles_kernel(GraphView g, int64_t B, co
       if (i == 0) vv += was ? 1 : -1;            // Eq. (7)
       int pk = base_peak;
       if (well) {   // the copy's interval leaves or joins the profile
-        // eight reads in flight at a time: re-reading the last element changes no maximum
-        auto range_max = [](const int32_t* a, int from, int to) {   // max(a[from..to]), from <= to
-          int m = 0;
-          for (int t = from; t <= to; t += 8) {
-            int x[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) x[j] = a[min(t + j, to)];
-            m = max(max(max(m, x[0]), max(x[1], x[2])), max(max(x[3], x[4]), max(max(x[5], x[6]), x[7])));
-          }
-          return m;
-        };
-        int top = 0;
-        if (e - s < 64) {
-          top = range_max(L.profile, s, e);
-        } else {
-          const int first_block = (s + 31) >> 5, last_block = (e + 1) >> 5;   // whole blocks [first, last)
-          if (s < 32 * first_block) top = range_max(L.profile, s, 32 * first_block - 1);
-          top = max(top, range_max(block_max, first_block, last_block - 1));
-          if (32 * last_block <= e) top = max(top, range_max(L.profile, 32 * last_block, e));
-        }
+        const int top = interval_max(L.profile, block_max, s, e);
         const int sz = A.size_of(v);
         pk = max(max(top + (was ? -sz : sz), 0), max(L.pmax[s - 1], L.smax[e + 1]));
       }
@@ -1089,7 +1191,34 @@ extern "C" int moc_eval_toggles(const moc_graph* g, int64_t B, const int32_t* st
   if (g->has_self_loop) return MOC_EINVAL;
   const TgLayout lay = tg_layout(g->view.T, g->view.n, g->view.m, g->max_lds);
   if (lay.bytes > g->max_lds) return MOC_EOVERFLOW;
-  auto kern = lay.adj_off ? toggles_kernel<true> : toggles_kernel<false>;
+  auto kern = lay.adj_off ? toggles_kernel<true, false> : toggles_kernel<false, false>;
+  MOC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              lay.bytes));
+  int per_cu = 0;
+  MOC_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, kNT, lay.bytes));
+  if (per_cu < 1) per_cu = 1;
+  const int64_t resident = (int64_t)per_cu * g->num_cu;
+  const unsigned grid = (unsigned)(B < resident ? B : resident);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(kNT), lay.bytes, static_cast<hipStream_t>(hip_stream), g->view, B, starts,
+                     ends, active, out, lay);
+  MOC_HIP(hipGetLastError());
+  return MOC_OK;
+}
+
+extern "C" int moc_eval_cuts(const moc_graph* g, int64_t B, const int32_t* starts, const int32_t* ends,
+                             const uint8_t* active, moc_cut_score* out, void* hip_stream) {
+  if (!g || B < 0) return MOC_EINVAL;
+  if (B == 0 || g->view.m == 0) return MOC_OK;
+  if (!starts || !ends || !active || !out) return MOC_EINVAL;
+  if ((((uintptr_t)starts | (uintptr_t)ends) & 3) || ((uintptr_t)out & 7)) return MOC_EINVAL;
+  int dev = -1;
+  MOC_HIP(hipGetDevice(&dev));
+  if (dev != g->device) return MOC_EDEVICE;
+  if (g->has_self_loop) return MOC_EINVAL;
+  const TgLayout lay = tg_layout(g->view.T, g->view.n, g->view.m, g->max_lds);
+  if (lay.bytes > g->max_lds) return MOC_EOVERFLOW;
+  if ((int64_t)g->view.m * g->view.C > 0x7FFFFFFFll) return MOC_EOVERFLOW;
+  auto kern = lay.adj_off ? toggles_kernel<true, true> : toggles_kernel<false, true>;
   MOC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                               lay.bytes));
   int per_cu = 0;

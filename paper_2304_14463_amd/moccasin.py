@@ -26,7 +26,7 @@ TOGGLE_SCORE_DTYPE = np.dtype([("violations", "<i4"), ("peak", "<i4"), ("duratio
 DECODE_RESULT_DTYPE = np.dtype([("status", "<i4"), ("length", "<i4"), ("peak", "<i8"), ("duration", "<i8")])
 
 EXPORTS = ("moc_graph_upload", "moc_graph_info", "moc_eval_batch", "moc_eval_neighbours", "moc_eval_toggles",
-           "moc_decode_batch", "moc_graph_free", "moc_strerror", "moc_last_hip_error")
+           "moc_eval_cuts", "moc_decode_batch", "moc_graph_free", "moc_strerror", "moc_last_hip_error")
 
 
 class MoccasinError(RuntimeError):
@@ -55,6 +55,8 @@ def lib():
         L.moc_eval_neighbours.restype = ctypes.c_int
         L.moc_eval_toggles.argtypes = [VP, I64, VP, VP, VP, VP, VP]
         L.moc_eval_toggles.restype = ctypes.c_int
+        L.moc_eval_cuts.argtypes = [VP, I64, VP, VP, VP, VP, VP]
+        L.moc_eval_cuts.restype = ctypes.c_int
         L.moc_decode_batch.argtypes = [VP, I64, VP, VP, VP, VP, VP]
         L.moc_decode_batch.restype = ctypes.c_int
         L.moc_graph_free.argtypes = [VP]
@@ -167,6 +169,19 @@ def moc_eval_toggles(g: Graph, starts, ends, active, out=None, stream=None):
         out = torch.empty((B, g.T, TOGGLE_SCORE_DTYPE.itemsize), dtype=torch.uint8, device=starts.device)
     code = lib().moc_eval_toggles(g._h, B, ps, pe, pa, ctypes.c_void_p(out.data_ptr()), _stream_handle(stream))
     _check(code, "moc_eval_toggles")
+    return out
+
+
+def moc_eval_cuts(g: Graph, starts, ends, active, out=None, stream=None):
+    """Score the B x m*C cut-and-recompute moves.  Returns a uint8 CUDA tensor [B][m*C][16]
+    (moc_cut_score = moc_toggle_score)."""
+    import torch
+    B = starts.numel() // g.T if g.T else 0
+    ps, pe, pa = _cand_ptrs(g, B, starts, ends, active)
+    if out is None:
+        out = torch.empty((B, g.m * g.C, TOGGLE_SCORE_DTYPE.itemsize), dtype=torch.uint8, device=starts.device)
+    code = lib().moc_eval_cuts(g._h, B, ps, pe, pa, ctypes.c_void_p(out.data_ptr()), _stream_handle(stream))
+    _check(code, "moc_eval_cuts")
     return out
 
 

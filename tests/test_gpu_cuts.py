@@ -1,0 +1,184 @@
+"""GPU parity of moc_eval_cuts: every cut-and-recompute move scored as the
+oracle scores it (edit the candidate, evaluate it in full), bit-exact."""
+import numpy as np
+import pytest
+
+import oracle
+from helpers import upload
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def moc():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2304_14463_amd import moccasin
+    moccasin.lib()
+    return moccasin
+
+
+def to_dev(*arrs):
+    import torch
+    return [torch.from_numpy(np.ascontiguousarray(x)).cuda() for x in arrs]
+
+
+def assert_same(got, want, what=""):
+    for i, name in enumerate(("violations", "peak", "duration")):
+        bad = np.flatnonzero(got[name].astype(np.int64) != want[:, i])
+        assert bad.size == 0, f"{what}: {name} differs at {bad[:8]}: gpu {got[name][bad[:8]]} oracle {want[bad[:8], i]}"
+
+
+def schedules(rng, g, C, B, wild):
+    """Rows in turn: a topological order spread over the positions with every output kept to
+    its last use (violation-free, plenty of cuts); the same with some copies of other nodes
+    active at random places; random intervals (wild: also outside [0, T))."""
+    n, T = g.n, g.n * C
+    out_last = np.zeros(n, int)
+    s = np.zeros((B, T), np.int32); e = np.zeros((B, T), np.int32); a = np.zeros((B, T), np.uint8)
+    for b in range(B):
+        kind = b % 3
+        if kind == 2:
+            lo, hi = (-3, T + 3) if wild else (0, T)
+            s[b] = rng.integers(lo, hi, T); e[b] = rng.integers(lo, hi, T)
+            swap = (s[b] > e[b]) & (rng.random(T) < 0.8)
+            s[b], e[b] = np.where(swap, e[b], s[b]), np.where(swap, s[b], e[b])
+            a[b] = rng.random(T) < 0.6
+            continue
+        pos = np.sort(rng.choice(T, size=n, replace=False))
+        out_last[:] = pos
+        for v in range(n):
+            for u in g.in_idx[g.in_ptr[v]:g.in_ptr[v + 1]]:
+                out_last[u] = max(out_last[u], pos[v])
+        s[b] = rng.integers(0, T, T); e[b] = rng.integers(0, T, T)    # fields of inactive copies: anything
+        s[b, ::C], e[b, ::C], a[b, ::C] = pos, out_last, 1
+        if kind == 1 and C > 1:
+            extra = rng.random(T) < 0.15
+            extra[::C] = False
+            a[b][extra] = 1
+            hi = np.maximum(s[b], e[b]); lo = np.minimum(s[b], e[b])
+            s[b][extra], e[b][extra] = lo[extra], hi[extra]
+    return s, e, a
+
+
+@pytest.mark.parametrize("n,C", [(2, 2), (5, 1), (9, 2), (17, 3), (40, 2), (64, 4), (130, 2), (257, 3), (600, 2)])
+def test_cuts_small_graphs(moc, n, C):
+    from paper_2304_14463_amd.inputs import graph_from_edges
+    rng = np.random.default_rng(53 * n + C)
+    edges = []
+    for v in range(1, n):
+        for u in rng.integers(0, v, size=rng.integers(1, 4)):
+            edges.append((int(u), v))         # duplicates stay: separate instances
+    g = graph_from_edges(n, sorted(edges), rng.integers(0, 50, n), rng.integers(1, 9, n))
+    B = 9
+    s, e, a = schedules(rng, g, C, B, wild=True)
+    budget = int(g.size.sum()) // 2
+    gh = moc.moc_graph_upload(n, g.in_ptr, g.in_idx, g.size, g.dur, budget, C)
+    ds, de, da = to_dev(s, e, a)
+    got = moc.results_to_numpy(moc.moc_eval_cuts(gh, ds, de, da), moc.TOGGLE_SCORE_DTYPE)
+    applicable = 0
+    for b in range(B):
+        want = oracle.cuts(g, budget, C, s[b], e[b], a[b])
+        assert_same(got[b], want, f"n={n} C={C} row {b}")
+        applicable += int((want[:, 0] >= 0).sum())
+    assert applicable > 0 or C == 1
+    gh.free()
+
+
+def test_cuts_hub_node(moc):
+    """One node feeds all others: long adjacency walks, uses on both sides of every cut."""
+    from paper_2304_14463_amd.inputs import graph_from_edges
+    n, C = 300, 2
+    rng = np.random.default_rng(8)
+    edges = [(0, v) for v in range(1, n)] + [(v - 1, v) for v in range(2, n)]
+    g = graph_from_edges(n, sorted(edges), rng.integers(1, 50, n), rng.integers(1, 9, n))
+    s, e, a = schedules(rng, g, C, 6, wild=False)
+    gh = moc.moc_graph_upload(n, g.in_ptr, g.in_idx, g.size, g.dur, 1000, C)
+    ds, de, da = to_dev(s, e, a)
+    got = moc.results_to_numpy(moc.moc_eval_cuts(gh, ds, de, da), moc.TOGGLE_SCORE_DTYPE)
+    for b in range(6):
+        want = oracle.cuts(g, 1000, C, s[b], e[b], a[b])
+        assert_same(got[b], want, f"hub row {b}")
+    assert (got["violations"][0] >= 0).sum() > n // 2
+    gh.free()
+
+
+def test_cuts_workload(moc, workloads):
+    """n=2000, C=2 at the full batch: sampled bases against the oracle; sampled moves applied by
+    the oracle and evaluated with moc_eval_batch; a cut never raises the peak."""
+    import torch
+    from paper_2304_14463_amd.inputs import DeviceWorkload
+    w = workloads(3)
+    gh = upload(moc, w)
+    ds, de, da = DeviceWorkload(w).candidates()
+    out = moc.moc_eval_cuts(gh, ds, de, da)
+    base = moc.results_to_numpy(moc.moc_eval_batch(gh, ds, de, da))
+    torch.cuda.synchronize()
+    for b in (0, w.B // 2 + 1, w.B - 1):
+        s, e, a = ds[b].cpu().numpy(), de[b].cpu().numpy(), da[b].cpu().numpy()
+        got = moc.results_to_numpy(out[b], moc.TOGGLE_SCORE_DTYPE)
+        assert_same(got, oracle.cuts(w.graph, w.budget, w.C, s, e, a), f"base {b}")
+    rng = np.random.default_rng(5)
+    rows, es, ee, ea, want = [], [], [], [], []
+    for b in rng.integers(0, w.B, 48):
+        got = moc.results_to_numpy(out[b], moc.TOGGLE_SCORE_DTYPE)
+        ok = np.flatnonzero(got["violations"] >= 0)
+        assert ok.size > 0
+        assert (got["peak"][ok] <= base["peak"][b]).all()
+        for q in rng.choice(ok, 4):
+            x, i = divmod(int(q), w.C)
+            s, e, a = ds[b].cpu().numpy(), de[b].cpu().numpy(), da[b].cpu().numpy()
+            applied, s2, e2, a2 = oracle.cut_apply(w.graph, w.C, s, e, a, x, i)
+            assert applied
+            es.append(s2); ee.append(e2); ea.append(a2); want.append(got[q])
+    d2 = to_dev(np.stack(es), np.stack(ee), np.stack(ea))
+    res = moc.results_to_numpy(moc.moc_eval_batch(gh, *d2))
+    want = np.array(want)
+    assert (res["violations"] == want["violations"]).all()
+    assert (res["peak"] == want["peak"]).all() and (res["duration"] == want["duration"]).all()
+    gh.free()
+
+
+def test_cuts_adjacency_from_global_memory(moc):
+    """A graph whose adjacency lists do not fit in LDS beside the working set."""
+    from paper_2304_14463_amd.inputs import graph_from_edges
+    n, C = 4300, 2
+    rng = np.random.default_rng(12)
+    edges = []
+    for v in range(1, n):
+        for u in rng.integers(max(0, v - 40), v, size=rng.integers(1, 4)):
+            edges.append((int(u), v))
+    g = graph_from_edges(n, sorted(set(edges)), rng.integers(1, 50, n), rng.integers(1, 9, n))
+    s, e, a = schedules(rng, g, C, 3, wild=False)
+    gh = moc.moc_graph_upload(n, g.in_ptr, g.in_idx, g.size, g.dur, 5000, C)
+    ds, de, da = to_dev(s, e, a)
+    got = moc.results_to_numpy(moc.moc_eval_cuts(gh, ds, de, da), moc.TOGGLE_SCORE_DTYPE)
+    for b in range(3):
+        assert_same(got[b], oracle.cuts(g, 5000, C, s[b], e[b], a[b]), f"row {b}")
+    gh.free()
+
+
+def test_cuts_rejects_bad_arguments(moc):
+    import ctypes
+    import torch
+    from paper_2304_14463_amd.inputs import graph_from_edges
+    g = graph_from_edges(3, [(0, 1), (1, 2)], [1, 1, 1], [1, 1, 1])
+    gh = moc.moc_graph_upload(3, g.in_ptr, g.in_idx, g.size, g.dur, 1, 2)
+    s = torch.zeros((2, 6), dtype=torch.int32, device="cuda")
+    a = torch.zeros((2, 6), dtype=torch.uint8, device="cuda")
+    out = torch.zeros((2, 4, 16), dtype=torch.uint8, device="cuda")
+    L = moc.lib()
+    vp = lambda t, off=0: ctypes.c_void_p(t.data_ptr() + off)
+    assert L.moc_eval_cuts(gh._h, 2, vp(s), vp(s), vp(a), None, None) == -1
+    assert L.moc_eval_cuts(gh._h, 2, None, vp(s), vp(a), vp(out), None) == -1
+    assert L.moc_eval_cuts(gh._h, 1, vp(s), vp(s), vp(a), vp(out, 4), None) == -1
+    assert L.moc_eval_cuts(gh._h, 0, None, None, None, None, None) == 0
+    gh.free()
+    gl = graph_from_edges(2, [(0, 0), (0, 1)], [1, 1], [1, 1])
+    gh = moc.moc_graph_upload(2, gl.in_ptr, gl.in_idx, gl.size, gl.dur, 1, 2)
+    assert L.moc_eval_cuts(gh._h, 1, vp(s), vp(s), vp(a), vp(out), None) == -1      # an edge (v, v)
+    gh.free()
+    g0 = graph_from_edges(2, [], [1, 1], [1, 1])                                    # no edges: nothing to do
+    gh = moc.moc_graph_upload(2, g0.in_ptr, g0.in_idx, g0.size, g0.dur, 1, 2)
+    assert L.moc_eval_cuts(gh._h, 1, vp(s), vp(s), vp(a), vp(out), None) == 0
+    gh.free()
