@@ -158,6 +158,20 @@ def measure_neighbours(moc, steps, warmup):
     ms = (time.perf_counter() - t0) * 1e3 / steps
     out["toggles"] = {"ms_per_step": ms, "moves_per_s": w.B * w.T / (ms * 1e-3), "bytes_written": w.B * w.T * 16}
     del ot
+    # the moves that trade duration for memory: one per in-edge and copy of its consumer
+    oc = moc.moc_eval_cuts(gh, ds, de, da)
+    for _ in range(warmup):
+        moc.moc_eval_cuts(gh, ds, de, da, out=oc)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        moc.moc_eval_cuts(gh, ds, de, da, out=oc)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    applicable = float((moc.results_to_numpy(oc[:64], moc.TOGGLE_SCORE_DTYPE)["violations"] >= 0).mean())
+    out["cuts"] = {"ms_per_step": ms, "moves_per_s": w.B * w.m * w.C / (ms * 1e-3),
+                   "bytes_written": w.B * w.m * w.C * 16, "frac_applicable": applicable}
+    del oc
     # back to sequences: every base decoded and costed, sequences written out
     # -- of the candidates a search would decode: the violation-free bases, repeated to B rows
     ev = moc.results_to_numpy(moc.moc_eval_batch(gh, ds, de, da))

@@ -868,13 +868,24 @@ __device__ __forceinline__ int range_max8(const int32_t* a, int from, int to) {
   return m;
 }
 
-// max(profile[s..e]), s <= e, through the maxima over blocks of 32 positions for long ranges.
-__device__ __forceinline__ int interval_max(const int32_t* profile, const int32_t* block_max, int s, int e) {
+// Maxima of the profile over blocks of 32 positions, as a table for range queries:
+// level l holds, at i, the maximum over the blocks i .. i + 2^l - 1 (level 0: the blocks).
+struct BlockMax {
+  const int32_t* level0;
+  int blocks;
+  __device__ __forceinline__ int over(int first, int last) const {   // blocks [first, last), first < last
+    const int l = 31 - __clz(last - first);
+    const int32_t* row = level0 + l * blocks;
+    return max(row[first], row[last - (1 << l)]);
+  }
+};
+
+// max(profile[s..e]), s <= e: whole blocks from the table, the rest position by position.
+__device__ __forceinline__ int interval_max(const int32_t* profile, const BlockMax& bm, int s, int e) {
   if (e - s < 64) return range_max8(profile, s, e);
-  const int first_block = (s + 31) >> 5, last_block = (e + 1) >> 5;   // whole blocks [first, last)
-  int top = 0;
-  if (s < 32 * first_block) top = range_max8(profile, s, 32 * first_block - 1);
-  top = max(top, range_max8(block_max, first_block, last_block - 1));
+  const int first_block = (s + 31) >> 5, last_block = (e + 1) >> 5;   // whole blocks [first, last): at least one
+  int top = bm.over(first_block, last_block);
+  if (s < 32 * first_block) top = max(top, range_max8(profile, s, 32 * first_block - 1));
   if (32 * last_block <= e) top = max(top, range_max8(profile, 32 * last_block, e));
   return top;
 }
@@ -887,7 +898,7 @@ __device__ __forceinline__ int interval_max(const int32_t* profile, const int32_
 // can change: every consumer that k covered is covered by one of the two pieces, since no
 // live consumer starts in (last use, p].  The profile loses m_u on (last use, p).
 // Returns false if the move is not applicable.
-__device__ __forceinline__ bool score_cut(const Adj& g, int C, int T, const NbLds& L, const int32_t* block_max,
+__device__ __forceinline__ bool score_cut(const Adj& g, int C, int T, const NbLds& L, const BlockMax& block_max,
                                           const uint8_t* __restrict__ active_row, int u, int consumer_copy,
                                           int base_viol, int base_peak, int* viol_out, int* peak_out) {
   const uint32_t mine = L.packed[consumer_copy];
@@ -959,6 +970,7 @@ __device__ __forceinline__ bool score_cut(const Adj& g, int C, int T, const NbLd
 
 struct TgLayout {
   int T_pad, bit_words, blocks;
+  int levels;    // of the table of block maxima: 2^(levels - 1) <= blocks
   int adj_off;   // word offset of the adjacency lists and sizes in LDS, 0 if they stay in global memory
   int bytes;
 };
@@ -968,8 +980,10 @@ TgLayout tg_layout(int T, int n, int m, int max_lds) {
   l.T_pad = (T + 3) & ~3;
   l.bit_words = (T + 31) / 32;
   l.blocks = (T + 31) / 32;
+  l.levels = 1;
+  while ((2 << (l.levels - 1)) <= l.blocks) ++l.levels;
   // profile, prefix max, suffix max (with sentinels), packed, block maxima, two bitmaps, scratch
-  const int words = 4 * l.T_pad + 8 + l.blocks + 2 * l.bit_words + 8 * kNW + 16;
+  const int words = 4 * l.T_pad + 8 + l.levels * l.blocks + 2 * l.bit_words + 8 * kNW + 16;
   l.adj_off = 0;
   l.bytes = 4 * words;
   // A lane walks its node's edges one after the other: from LDS whenever the lists fit (the
@@ -994,7 +1008,8 @@ __global__ __launch_bounds__(kNT) void toggles_kernel(GraphView g, int64_t B, co
   L.smax = L.pmax + lay.T_pad;          // smax[T] = 0
   L.packed = reinterpret_cast<uint32_t*>(L.smax + lay.T_pad + 4);
   int32_t* const block_max = reinterpret_cast<int32_t*>(L.packed + lay.T_pad);
-  L.occ1 = reinterpret_cast<uint32_t*>(block_max + lay.blocks);
+  L.occ1 = reinterpret_cast<uint32_t*>(block_max + lay.levels * lay.blocks);
+  const BlockMax block_table{block_max, lay.blocks};
   L.occ2 = L.occ1 + lay.bit_words;
   L.scratch = reinterpret_cast<int32_t*>(L.occ2 + lay.bit_words);
   int32_t* const counts = L.scratch + 8 * kNW;   // [0] base violations, [1] base duration
@@ -1046,6 +1061,12 @@ __global__ __launch_bounds__(kNT) void toggles_kernel(GraphView g, int64_t B, co
       for (int t = 32 * x; t < min(32 * x + 32, T); ++t) m = max(m, L.profile[t]);
       block_max[x] = m;
     }
+    for (int l = 1; l < lay.levels; ++l) {
+      __syncthreads();
+      const int half = 1 << (l - 1);
+      const int32_t* below = block_max + (l - 1) * lay.blocks;
+      for (int x = tid; x + 2 * half <= lay.blocks; x += kNT) block_max[l * lay.blocks + x] = max(below[x], below[x + half]);
+    }
     // ---- the violations of the base, each instance once (as pass 1 of the kernel above)
     for (int k = tid; k < T; k += kNT) {
       const uint32_t mine = L.packed[k];
@@ -1085,7 +1106,7 @@ __global__ __launch_bounds__(kNT) void toggles_kernel(GraphView g, int64_t B, co
         const int consumer_copy = (int)(g.edge_pair_c[x] >> 16) + i;
         moc_toggle_score sc{-1, -1, 0};
         int vv, pk;
-        if (score_cut(A, C, T, L, block_max, active + row, u, consumer_copy, base_viol, base_peak, &vv, &pk)) {
+        if (score_cut(A, C, T, L, block_table, active + row, u, consumer_copy, base_viol, base_peak, &vv, &pk)) {
           sc.violations = vv;
           sc.peak = pk;
           sc.duration = (int64_t)base_dur + g.size_dur[u].y;
@@ -1108,7 +1129,7 @@ __global__ __launch_bounds__(kNT) void toggles_kernel(GraphView g, int64_t B, co
       if (i == 0) vv += was ? 1 : -1;            // Eq. (7)
       int pk = base_peak;
       if (well) {   // the copy's interval leaves or joins the profile
-        const int top = interval_max(L.profile, block_max, s, e);
+        const int top = interval_max(L.profile, block_table, s, e);
         const int sz = A.size_of(v);
         pk = max(max(top + (was ? -sz : sz), 0), max(L.pmax[s - 1], L.smax[e + 1]));
       }
