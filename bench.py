@@ -159,19 +159,23 @@ def measure_neighbours(moc, steps, warmup):
     out["toggles"] = {"ms_per_step": ms, "moves_per_s": w.B * w.T / (ms * 1e-3), "bytes_written": w.B * w.T * 16}
     del ot
     # the moves that trade duration for memory: one per in-edge and copy of its consumer
-    oc = moc.moc_eval_cuts(gh, ds, de, da)
-    for _ in range(warmup):
-        moc.moc_eval_cuts(gh, ds, de, da, out=oc)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(steps):
-        moc.moc_eval_cuts(gh, ds, de, da, out=oc)
-    torch.cuda.synchronize()
-    ms = (time.perf_counter() - t0) * 1e3 / steps
+    oc, ob = moc.moc_eval_cuts(gh, ds, de, da, want_best=True)
+    ms_cuts = {}
+    for mode, (om, wm) in (("table_and_best", (oc, True)), ("best_only", (None, False))):
+        for _ in range(warmup):
+            moc.moc_eval_cuts(gh, ds, de, da, want_moves=wm, want_best=True, out_moves=om, out_best=ob)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            moc.moc_eval_cuts(gh, ds, de, da, want_moves=wm, want_best=True, out_moves=om, out_best=ob)
+        torch.cuda.synchronize()
+        ms_cuts[mode] = (time.perf_counter() - t0) * 1e3 / steps
+    ms = ms_cuts["table_and_best"]
     applicable = float((moc.results_to_numpy(oc[:64], moc.TOGGLE_SCORE_DTYPE)["violations"] >= 0).mean())
     out["cuts"] = {"ms_per_step": ms, "moves_per_s": w.B * w.m * w.C / (ms * 1e-3),
-                   "bytes_written": w.B * w.m * w.C * 16, "frac_applicable": applicable}
-    del oc
+                   "bytes_written": w.B * w.m * w.C * 16, "frac_applicable": applicable,
+                   "best_only_ms_per_step": ms_cuts["best_only"]}
+    del oc, ob
     # back to sequences: every base decoded and costed, sequences written out
     # -- of the candidates a search would decode: the violation-free bases, repeated to B rows
     ev = moc.results_to_numpy(moc.moc_eval_batch(gh, ds, de, da))

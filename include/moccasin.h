@@ -207,13 +207,19 @@ int moc_eval_toggles(const moc_graph* g, int64_t B, const int32_t* starts, const
  * applicable (score -1, -1, 0) if the consumer copy is not live or k, j or p
  * does not exist.  Otherwise entry [b][q] is what moc_eval_batch returns for
  * the edited candidate (the duration is the base's plus w_u).
- *   out   device, moc_cut_score [B][m*C], 8-byte aligned
+ *   out_moves   device, moc_cut_score [B][m*C], or NULL
+ *   out_best    device, moc_best_move [B], or NULL: the applicable move that
+ *               minimises (violations, peak, q) lexicographically -- the same
+ *               order as (violations, max(peak, M), peak, q); move = -1 and
+ *               zeros if none is applicable (always so when m == 0)
+ * At least one of out_moves / out_best must be given; both 8-byte aligned.
  * LDS use and limits as moc_eval_toggles.  A graph with an edge (v,v) is not
- * accepted.  B == 0 or m == 0 is a no-op.
+ * accepted.  B == 0 is a no-op.
  * Errors: MOC_EINVAL, MOC_EDEVICE, MOC_EOVERFLOW (T too large for this call), MOC_EHIP.
  */
 int moc_eval_cuts(const moc_graph* g, int64_t B, const int32_t* starts, const int32_t* ends,
-                  const uint8_t* active, moc_cut_score* out, void* hip_stream);
+                  const uint8_t* active, moc_cut_score* out_moves, moc_best_move* out_best,
+                  void* hip_stream);
 
 /*
  * Turn B candidates into the rematerialisation sequences they stand for and

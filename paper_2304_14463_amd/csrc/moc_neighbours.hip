@@ -1000,7 +1000,8 @@ template <bool ADJ_LDS, bool CUTS>
 __global__ __launch_bounds__(kNT) void toggles_kernel(GraphView g, int64_t B, const int32_t* __restrict__ starts,
                                                       const int32_t* __restrict__ ends,
                                                       const uint8_t* __restrict__ active,
-                                                      moc_toggle_score* __restrict__ out, TgLayout lay) {
+                                                      moc_toggle_score* __restrict__ out,
+                                                      moc_best_move* __restrict__ out_best, TgLayout lay) {
   extern __shared__ uint32_t nb_raw[];
   NbLds L{};
   L.profile = reinterpret_cast<int32_t*>(nb_raw);
@@ -1098,8 +1099,11 @@ __global__ __launch_bounds__(kNT) void toggles_kernel(GraphView g, int64_t B, co
     const int base_viol = counts[0], base_dur = counts[1], base_peak = L.pmax[T - 1];
 
     if constexpr (CUTS) {
-      // ---- one lane per in-edge and copy of its consumer
+      // ---- one lane per in-edge and copy of its consumer; the best move is the applicable one
+      // that minimises (violations, peak, index)
       const int64_t out_row = b * ((int64_t)g.m * C);
+      uint32_t best_viol = 0xFFFFFFFFu, best_peak = 0xFFFFFFFFu;
+      int best_q = -1;
       for (int q = tid; q < g.m * C; q += kNT) {
         const int x = q / C, i = q - x * C;
         const int u = A.in_idx[x];
@@ -1110,8 +1114,40 @@ __global__ __launch_bounds__(kNT) void toggles_kernel(GraphView g, int64_t B, co
           sc.violations = vv;
           sc.peak = pk;
           sc.duration = (int64_t)base_dur + g.size_dur[u].y;
+          if (best_q < 0 || (uint32_t)vv < best_viol || ((uint32_t)vv == best_viol && (uint32_t)pk < best_peak)) {
+            best_viol = (uint32_t)vv;   // a lane meets its moves in rising order: the first of equals stays
+            best_peak = (uint32_t)pk;
+            best_q = q;
+          }
         }
-        out[out_row + q] = sc;
+        if (out) out[out_row + q] = sc;
+      }
+      if (out_best) {
+        auto take = [&](uint32_t ov, uint32_t op, int oq) {
+          if (oq < 0) return;
+          if (best_q < 0 || ov < best_viol || (ov == best_viol && (op < best_peak || (op == best_peak && oq < best_q)))) {
+            best_viol = ov;
+            best_peak = op;
+            best_q = oq;
+          }
+        };
+#pragma unroll
+        for (int off = kWave / 2; off > 0; off >>= 1)
+          take(__shfl_xor(best_viol, off), __shfl_xor(best_peak, off), __shfl_xor(best_q, off));
+        __syncthreads();   // the scratch words below were last read by the scans of the staging
+        if ((tid & (kWave - 1)) == 0) {
+          L.scratch[3 * (tid / kWave)] = (int)best_viol;
+          L.scratch[3 * (tid / kWave) + 1] = (int)best_peak;
+          L.scratch[3 * (tid / kWave) + 2] = best_q;
+        }
+        __syncthreads();
+        if (tid == 0) {
+          best_q = -1;
+          for (int w = 0; w < kNW; ++w)
+            take((uint32_t)L.scratch[3 * w], (uint32_t)L.scratch[3 * w + 1], L.scratch[3 * w + 2]);
+          moc_best_move bm{best_q, best_q < 0 ? 0 : (int)best_viol, best_q < 0 ? 0 : (int64_t)best_peak};
+          out_best[b] = bm;
+        }
       }
       __syncthreads();
       continue;
@@ -1221,17 +1257,20 @@ extern "C" int moc_eval_toggles(const moc_graph* g, int64_t B, const int32_t* st
   const int64_t resident = (int64_t)per_cu * g->num_cu;
   const unsigned grid = (unsigned)(B < resident ? B : resident);
   hipLaunchKernelGGL(kern, dim3(grid), dim3(kNT), lay.bytes, static_cast<hipStream_t>(hip_stream), g->view, B, starts,
-                     ends, active, out, lay);
+                     ends, active, out, static_cast<moc_best_move*>(nullptr), lay);
   MOC_HIP(hipGetLastError());
   return MOC_OK;
 }
 
 extern "C" int moc_eval_cuts(const moc_graph* g, int64_t B, const int32_t* starts, const int32_t* ends,
-                             const uint8_t* active, moc_cut_score* out, void* hip_stream) {
+                             const uint8_t* active, moc_cut_score* out_moves, moc_best_move* out_best,
+                             void* hip_stream) {
   if (!g || B < 0) return MOC_EINVAL;
-  if (B == 0 || g->view.m == 0) return MOC_OK;
-  if (!starts || !ends || !active || !out) return MOC_EINVAL;
-  if ((((uintptr_t)starts | (uintptr_t)ends) & 3) || ((uintptr_t)out & 7)) return MOC_EINVAL;
+  if (!out_moves && !out_best) return MOC_EINVAL;
+  if (B == 0) return MOC_OK;
+  if (!starts || !ends || !active) return MOC_EINVAL;
+  if ((((uintptr_t)starts | (uintptr_t)ends) & 3) || ((uintptr_t)out_moves & 7) || ((uintptr_t)out_best & 7))
+    return MOC_EINVAL;
   int dev = -1;
   MOC_HIP(hipGetDevice(&dev));
   if (dev != g->device) return MOC_EDEVICE;
@@ -1248,7 +1287,7 @@ extern "C" int moc_eval_cuts(const moc_graph* g, int64_t B, const int32_t* start
   const int64_t resident = (int64_t)per_cu * g->num_cu;
   const unsigned grid = (unsigned)(B < resident ? B : resident);
   hipLaunchKernelGGL(kern, dim3(grid), dim3(kNT), lay.bytes, static_cast<hipStream_t>(hip_stream), g->view, B, starts,
-                     ends, active, out, lay);
+                     ends, active, out_moves, out_best, lay);
   MOC_HIP(hipGetLastError());
   return MOC_OK;
 }

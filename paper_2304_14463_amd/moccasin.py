@@ -55,7 +55,7 @@ def lib():
         L.moc_eval_neighbours.restype = ctypes.c_int
         L.moc_eval_toggles.argtypes = [VP, I64, VP, VP, VP, VP, VP]
         L.moc_eval_toggles.restype = ctypes.c_int
-        L.moc_eval_cuts.argtypes = [VP, I64, VP, VP, VP, VP, VP]
+        L.moc_eval_cuts.argtypes = [VP, I64, VP, VP, VP, VP, VP, VP]
         L.moc_eval_cuts.restype = ctypes.c_int
         L.moc_decode_batch.argtypes = [VP, I64, VP, VP, VP, VP, VP]
         L.moc_decode_batch.restype = ctypes.c_int
@@ -172,17 +172,22 @@ def moc_eval_toggles(g: Graph, starts, ends, active, out=None, stream=None):
     return out
 
 
-def moc_eval_cuts(g: Graph, starts, ends, active, out=None, stream=None):
-    """Score the B x m*C cut-and-recompute moves.  Returns a uint8 CUDA tensor [B][m*C][16]
-    (moc_cut_score = moc_toggle_score)."""
+def moc_eval_cuts(g: Graph, starts, ends, active, want_moves=True, want_best=False, out_moves=None, out_best=None,
+                  stream=None):
+    """Score the B x m*C cut-and-recompute moves.  Returns (uint8 CUDA tensor [B][m*C][16] of
+    moc_cut_score or None, uint8 CUDA tensor [B][16] of moc_best_move or None)."""
     import torch
     B = starts.numel() // g.T if g.T else 0
     ps, pe, pa = _cand_ptrs(g, B, starts, ends, active)
-    if out is None:
-        out = torch.empty((B, g.m * g.C, TOGGLE_SCORE_DTYPE.itemsize), dtype=torch.uint8, device=starts.device)
-    code = lib().moc_eval_cuts(g._h, B, ps, pe, pa, ctypes.c_void_p(out.data_ptr()), _stream_handle(stream))
+    if out_moves is None and want_moves:
+        out_moves = torch.empty((B, g.m * g.C, TOGGLE_SCORE_DTYPE.itemsize), dtype=torch.uint8, device=starts.device)
+    if out_best is None and want_best:
+        out_best = torch.empty((B, BEST_MOVE_DTYPE.itemsize), dtype=torch.uint8, device=starts.device)
+    code = lib().moc_eval_cuts(
+        g._h, B, ps, pe, pa, ctypes.c_void_p(out_moves.data_ptr()) if out_moves is not None else None,
+        ctypes.c_void_p(out_best.data_ptr()) if out_best is not None else None, _stream_handle(stream))
     _check(code, "moc_eval_cuts")
-    return out
+    return out_moves, out_best
 
 
 def moc_decode_batch(g: Graph, starts, active, want_seq=True, out=None, out_seq=None, stream=None):

@@ -23,6 +23,25 @@ def to_dev(*arrs):
     return [torch.from_numpy(np.ascontiguousarray(x)).cuda() for x in arrs]
 
 
+def gpu_cuts(moc, gh, ds, de, da):
+    """Table and best move of every base, and the best move from a launch that writes no table."""
+    moves, best = moc.moc_eval_cuts(gh, ds, de, da, want_moves=True, want_best=True)
+    _, alone = moc.moc_eval_cuts(gh, ds, de, da, want_moves=False, want_best=True)
+    best = moc.results_to_numpy(best, moc.BEST_MOVE_DTYPE)
+    assert (moc.results_to_numpy(alone, moc.BEST_MOVE_DTYPE) == best).all()
+    return moc.results_to_numpy(moves, moc.TOGGLE_SCORE_DTYPE), best
+
+
+def assert_best(best, want, what=""):
+    """want: the oracle's table of one base; the best move is its first minimum of (violations, peak)."""
+    ok = np.flatnonzero(want[:, 0] >= 0)
+    if ok.size == 0:
+        assert (int(best["move"]), int(best["violations"]), int(best["peak"])) == (-1, 0, 0), what
+        return
+    q = min(ok, key=lambda q: (want[q, 0], want[q, 1], q))
+    assert (int(best["move"]), int(best["violations"]), int(best["peak"])) == (q, want[q, 0], want[q, 1]), what
+
+
 def assert_same(got, want, what=""):
     for i, name in enumerate(("violations", "peak", "duration")):
         bad = np.flatnonzero(got[name].astype(np.int64) != want[:, i])
@@ -75,11 +94,12 @@ def test_cuts_small_graphs(moc, n, C):
     budget = int(g.size.sum()) // 2
     gh = moc.moc_graph_upload(n, g.in_ptr, g.in_idx, g.size, g.dur, budget, C)
     ds, de, da = to_dev(s, e, a)
-    got = moc.results_to_numpy(moc.moc_eval_cuts(gh, ds, de, da), moc.TOGGLE_SCORE_DTYPE)
+    got, best = gpu_cuts(moc, gh, ds, de, da)
     applicable = 0
     for b in range(B):
         want = oracle.cuts(g, budget, C, s[b], e[b], a[b])
         assert_same(got[b], want, f"n={n} C={C} row {b}")
+        assert_best(best[b], want, f"n={n} C={C} row {b}")
         applicable += int((want[:, 0] >= 0).sum())
     assert applicable > 0 or C == 1
     gh.free()
@@ -95,10 +115,11 @@ def test_cuts_hub_node(moc):
     s, e, a = schedules(rng, g, C, 6, wild=False)
     gh = moc.moc_graph_upload(n, g.in_ptr, g.in_idx, g.size, g.dur, 1000, C)
     ds, de, da = to_dev(s, e, a)
-    got = moc.results_to_numpy(moc.moc_eval_cuts(gh, ds, de, da), moc.TOGGLE_SCORE_DTYPE)
+    got, best = gpu_cuts(moc, gh, ds, de, da)
     for b in range(6):
         want = oracle.cuts(g, 1000, C, s[b], e[b], a[b])
         assert_same(got[b], want, f"hub row {b}")
+        assert_best(best[b], want, f"hub row {b}")
     assert (got["violations"][0] >= 0).sum() > n // 2
     gh.free()
 
@@ -111,13 +132,23 @@ def test_cuts_workload(moc, workloads):
     w = workloads(3)
     gh = upload(moc, w)
     ds, de, da = DeviceWorkload(w).candidates()
-    out = moc.moc_eval_cuts(gh, ds, de, da)
+    out, best = moc.moc_eval_cuts(gh, ds, de, da, want_best=True)
+    _, alone = moc.moc_eval_cuts(gh, ds, de, da, want_moves=False, want_best=True)
     base = moc.results_to_numpy(moc.moc_eval_batch(gh, ds, de, da))
     torch.cuda.synchronize()
+    best = moc.results_to_numpy(best, moc.BEST_MOVE_DTYPE)
+    assert (moc.results_to_numpy(alone, moc.BEST_MOVE_DTYPE) == best).all()
     for b in (0, w.B // 2 + 1, w.B - 1):
         s, e, a = ds[b].cpu().numpy(), de[b].cpu().numpy(), da[b].cpu().numpy()
         got = moc.results_to_numpy(out[b], moc.TOGGLE_SCORE_DTYPE)
-        assert_same(got, oracle.cuts(w.graph, w.budget, w.C, s, e, a), f"base {b}")
+        want = oracle.cuts(w.graph, w.budget, w.C, s, e, a)
+        assert_same(got, want, f"base {b}")
+        assert_best(best[b], want, f"base {b}")
+    # every base: the best move is the first minimum of its own table
+    for b in range(0, w.B, 97):
+        got = moc.results_to_numpy(out[b], moc.TOGGLE_SCORE_DTYPE)
+        tab = np.stack([got["violations"], got["peak"]], 1).astype(np.int64)
+        assert_best(best[b], tab, f"base {b} against its table")
     rng = np.random.default_rng(5)
     rows, es, ee, ea, want = [], [], [], [], []
     for b in rng.integers(0, w.B, 48):
@@ -152,9 +183,11 @@ def test_cuts_adjacency_from_global_memory(moc):
     s, e, a = schedules(rng, g, C, 3, wild=False)
     gh = moc.moc_graph_upload(n, g.in_ptr, g.in_idx, g.size, g.dur, 5000, C)
     ds, de, da = to_dev(s, e, a)
-    got = moc.results_to_numpy(moc.moc_eval_cuts(gh, ds, de, da), moc.TOGGLE_SCORE_DTYPE)
+    got, best = gpu_cuts(moc, gh, ds, de, da)
     for b in range(3):
-        assert_same(got[b], oracle.cuts(g, 5000, C, s[b], e[b], a[b]), f"row {b}")
+        want = oracle.cuts(g, 5000, C, s[b], e[b], a[b])
+        assert_same(got[b], want, f"row {b}")
+        assert_best(best[b], want, f"row {b}")
     gh.free()
 
 
@@ -169,16 +202,19 @@ def test_cuts_rejects_bad_arguments(moc):
     out = torch.zeros((2, 4, 16), dtype=torch.uint8, device="cuda")
     L = moc.lib()
     vp = lambda t, off=0: ctypes.c_void_p(t.data_ptr() + off)
-    assert L.moc_eval_cuts(gh._h, 2, vp(s), vp(s), vp(a), None, None) == -1
-    assert L.moc_eval_cuts(gh._h, 2, None, vp(s), vp(a), vp(out), None) == -1
-    assert L.moc_eval_cuts(gh._h, 1, vp(s), vp(s), vp(a), vp(out, 4), None) == -1
-    assert L.moc_eval_cuts(gh._h, 0, None, None, None, None, None) == 0
+    assert L.moc_eval_cuts(gh._h, 2, vp(s), vp(s), vp(a), None, None, None) == -1
+    assert L.moc_eval_cuts(gh._h, 2, None, vp(s), vp(a), vp(out), None, None) == -1
+    assert L.moc_eval_cuts(gh._h, 1, vp(s), vp(s), vp(a), vp(out, 4), None, None) == -1
+    assert L.moc_eval_cuts(gh._h, 0, None, None, None, vp(out), None, None) == 0
     gh.free()
     gl = graph_from_edges(2, [(0, 0), (0, 1)], [1, 1], [1, 1])
     gh = moc.moc_graph_upload(2, gl.in_ptr, gl.in_idx, gl.size, gl.dur, 1, 2)
-    assert L.moc_eval_cuts(gh._h, 1, vp(s), vp(s), vp(a), vp(out), None) == -1      # an edge (v, v)
+    assert L.moc_eval_cuts(gh._h, 1, vp(s), vp(s), vp(a), vp(out), None, None) == -1      # an edge (v, v)
     gh.free()
     g0 = graph_from_edges(2, [], [1, 1], [1, 1])                                    # no edges: nothing to do
     gh = moc.moc_graph_upload(2, g0.in_ptr, g0.in_idx, g0.size, g0.dur, 1, 2)
-    assert L.moc_eval_cuts(gh._h, 1, vp(s), vp(s), vp(a), vp(out), None) == 0
+    best = torch.full((1, 16), 7, dtype=torch.uint8, device="cuda")
+    assert L.moc_eval_cuts(gh._h, 1, vp(s), vp(s), vp(a), vp(out), vp(best), None) == 0
+    bm = moc.results_to_numpy(best, moc.BEST_MOVE_DTYPE)
+    assert (int(bm["move"][0]), int(bm["violations"][0]), int(bm["peak"][0])) == (-1, 0, 0)
     gh.free()
