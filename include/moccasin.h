@@ -222,6 +222,25 @@ int moc_eval_cuts(const moc_graph* g, int64_t B, const int32_t* starts, const in
                   void* hip_stream);
 
 /*
+ * Greedy descent by cut-and-recompute moves, every candidate on its own: the
+ * memory-reducing half of a local search in the spirit of Phase 1 of
+ * Section 2.4, which minimises max(peak, M).  Repeats max_steps times: find the
+ * best move as moc_eval_cuts does; if it lowers (violations, max(peak, M))
+ * lexicographically against the candidate as it stands, apply it in place.  A
+ * candidate whose best move does not improve it stays as it is from then on.
+ *   starts, ends, active   device, [B][T], edited in place
+ *   max_steps              >= 0
+ *   work_best              device, moc_best_move [B], 8-byte aligned: workspace
+ *                          (holds the last step's choice on return)
+ *   out_steps              device, int32 [B]: number of moves applied
+ * Queues 2 * max_steps + 1 kernels on the stream and returns; allocates
+ * nothing.  Limits as moc_eval_cuts; B <= 2^31 - 1.
+ * Errors: MOC_EINVAL, MOC_EDEVICE, MOC_EOVERFLOW, MOC_EHIP.
+ */
+int moc_search_cuts(const moc_graph* g, int64_t B, int32_t* starts, int32_t* ends, uint8_t* active,
+                    int32_t max_steps, moc_best_move* work_best, int32_t* out_steps, void* hip_stream);
+
+/*
  * Turn B candidates into the rematerialisation sequences they stand for and
  * cost each sequence on its own terms (Section 2: the start of an active
  * interval is the event at which its node is computed; Section 1, problem

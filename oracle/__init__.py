@@ -47,6 +47,7 @@ def lib():
         _lib.bf_enumerate.restype = ctypes.c_int64
         _lib.bf_simulate.restype = ctypes.c_int
         _lib.orc_cut_apply.restype = ctypes.c_int
+        _lib.orc_search_cuts.restype = ctypes.c_int
         assert _lib.orc_result_fields() == len(FIELDS)
     return _lib
 
@@ -162,6 +163,20 @@ def cut_apply(g, C, starts, ends, active, x, i, T=None):
                              _p(e, ctypes.c_int32), _p(a, ctypes.c_uint8), ctypes.c_int32(x), ctypes.c_int32(i),
                              _p(s2, ctypes.c_int32), _p(e2, ctypes.c_int32), _p(a2, ctypes.c_uint8))
     return bool(ok), s2, e2, a2
+
+
+def search_cuts(g, budget, C, starts, ends, active, max_steps, T=None):
+    """Greedy descent by cuts on one candidate: (steps applied, s, e, a) after up to max_steps."""
+    K = g.n * C
+    T = K if T is None else T
+    s = np.array(starts, dtype=np.int32).reshape(K).copy()
+    e = np.array(ends, dtype=np.int32).reshape(K).copy()
+    a = np.array(active, dtype=np.uint8).reshape(K).copy()
+    keep, ga = _graph_args(g)
+    steps = lib().orc_search_cuts(*ga, ctypes.c_int64(budget), ctypes.c_int32(C), ctypes.c_int32(T),
+                                  _p(s, ctypes.c_int32), _p(e, ctypes.c_int32), _p(a, ctypes.c_uint8),
+                                  ctypes.c_int32(max_steps))
+    return int(steps), s, e, a
 
 
 def decode(g, C, starts, active, T=None):

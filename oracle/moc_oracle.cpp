@@ -326,4 +326,46 @@ void orc_cuts(int32_t n, const int32_t* in_ptr, const int32_t* in_idx, const int
     }
 }
 
+// Greedy descent by cuts, one candidate, in place: up to max_steps times, score every cut by
+// full re-evaluation, take the first minimum of (violations, peak) among the applicable ones,
+// and apply it if it lowers (violations, max(peak, M)) against the candidate as it stands;
+// stop at the first step that does not.  Returns the number of cuts applied.
+int orc_search_cuts(int32_t n, const int32_t* in_ptr, const int32_t* in_idx, const int32_t* size, const int32_t* dur,
+                    int64_t budget, int32_t C, int32_t T, int32_t* starts, int32_t* ends, uint8_t* active,
+                    int32_t max_steps) {
+  Problem p{n, in_ptr, in_idx, size, dur, budget, C, T};
+  Scratch w;
+  const int K = n * C, m = in_ptr[n];
+  std::vector<int32_t> s(K), e(K);
+  std::vector<uint8_t> a(K);
+  int64_t res[R_FIELDS];
+  int applied = 0;
+  for (int step = 0; step < max_steps; ++step) {
+    evaluate(p, starts, ends, active, w, res, nullptr);
+    const int64_t now_v = res[R_VIOLATIONS], now_p = std::max(res[R_PEAK], budget);
+    int64_t best_v = 0, best_p = 0;
+    int best_x = -1, best_i = -1;
+    for (int x = 0; x < m; ++x)
+      for (int i = 0; i < C; ++i) {
+        std::copy(starts, starts + K, s.begin());
+        std::copy(ends, ends + K, e.begin());
+        std::copy(active, active + K, a.begin());
+        if (!apply_cut(p, x, i, s.data(), e.data(), a.data())) continue;
+        evaluate(p, s.data(), e.data(), a.data(), w, res, nullptr);
+        if (best_x < 0 || res[R_VIOLATIONS] < best_v || (res[R_VIOLATIONS] == best_v && res[R_PEAK] < best_p)) {
+          best_v = res[R_VIOLATIONS];
+          best_p = res[R_PEAK];
+          best_x = x;
+          best_i = i;
+        }
+      }
+    if (best_x < 0) break;
+    const int64_t then_p = std::max(best_p, budget);
+    if (!(best_v < now_v || (best_v == now_v && then_p < now_p))) break;
+    apply_cut(p, best_x, best_i, starts, ends, active);
+    ++applied;
+  }
+  return applied;
+}
+
 }  // extern "C"

@@ -898,9 +898,17 @@ __device__ __forceinline__ int interval_max(const int32_t* profile, const BlockM
 // can change: every consumer that k covered is covered by one of the two pieces, since no
 // live consumer starts in (last use, p].  The profile loses m_u on (last use, p).
 // Returns false if the move is not applicable.
-__device__ __forceinline__ bool score_cut(const Adj& g, int C, int T, const NbLds& L, const BlockMax& block_max,
-                                          const uint8_t* __restrict__ active_row, int u, int consumer_copy,
-                                          int base_viol, int base_peak, int* viol_out, int* peak_out) {
+struct Cut {
+  int k, j;        // copy of u that is cut, copy of u that becomes active
+  int sk, ek;      // interval of copy k as it stands
+  int p;           // start of the recomputation
+  int last_use;    // new end of copy k
+};
+
+// Which copies and positions the move for producer u and the given consumer copy involves;
+// false if it is not applicable.  Reads the packed copies and the start bitmap of L.
+__device__ __forceinline__ bool find_cut(const Adj& g, int C, const NbLds& L, const uint8_t* active_row, int u,
+                                         int consumer_copy, Cut* cut) {
   const uint32_t mine = L.packed[consumer_copy];
   if (!live_of(mine)) return false;
   const uint32_t t = mine & 0xFFFFu;
@@ -934,6 +942,16 @@ __device__ __forceinline__ bool score_cut(const Adj& g, int C, int T, const NbLd
       if (x > sk && x < p) last_use = max(last_use, x);
     }
   }
+  *cut = Cut{k, j, sk, ek, p, last_use};
+  return true;
+}
+
+__device__ __forceinline__ bool score_cut(const Adj& g, int C, int T, const NbLds& L, const BlockMax& block_max,
+                                          const uint8_t* __restrict__ active_row, int u, int consumer_copy,
+                                          int base_viol, int base_peak, int* viol_out, int* peak_out) {
+  Cut cut;
+  if (!find_cut(g, C, L, active_row, u, consumer_copy, &cut)) return false;
+  const int k = cut.k, j = cut.j, sk = cut.sk, ek = cut.ek, p = cut.p, last_use = cut.last_use;
   int vv = base_viol;
   // Eq. (3) among the live copies of u, before and after
   int before = 0, after = 0, end_before = -1, end_after = -1;
@@ -1001,7 +1019,8 @@ __global__ __launch_bounds__(kNT) void toggles_kernel(GraphView g, int64_t B, co
                                                       const int32_t* __restrict__ ends,
                                                       const uint8_t* __restrict__ active,
                                                       moc_toggle_score* __restrict__ out,
-                                                      moc_best_move* __restrict__ out_best, TgLayout lay) {
+                                                      moc_best_move* __restrict__ out_best, int improving,
+                                                      TgLayout lay) {
   extern __shared__ uint32_t nb_raw[];
   NbLds L{};
   L.profile = reinterpret_cast<int32_t*>(nb_raw);
@@ -1145,6 +1164,11 @@ __global__ __launch_bounds__(kNT) void toggles_kernel(GraphView g, int64_t B, co
           best_q = -1;
           for (int w = 0; w < kNW; ++w)
             take((uint32_t)L.scratch[3 * w], (uint32_t)L.scratch[3 * w + 1], L.scratch[3 * w + 2]);
+          // a descent step takes the move only if it lowers (violations, max(peak, M))
+          if (improving && best_q >= 0) {
+            const int64_t now = max((int64_t)base_peak, g.budget), then = max((int64_t)best_peak, g.budget);
+            if (!((int)best_viol < base_viol || ((int)best_viol == base_viol && then < now))) best_q = -1;
+          }
           moc_best_move bm{best_q, best_q < 0 ? 0 : (int)best_viol, best_q < 0 ? 0 : (int64_t)best_peak};
           out_best[b] = bm;
         }
@@ -1257,7 +1281,96 @@ extern "C" int moc_eval_toggles(const moc_graph* g, int64_t B, const int32_t* st
   const int64_t resident = (int64_t)per_cu * g->num_cu;
   const unsigned grid = (unsigned)(B < resident ? B : resident);
   hipLaunchKernelGGL(kern, dim3(grid), dim3(kNT), lay.bytes, static_cast<hipStream_t>(hip_stream), g->view, B, starts,
-                     ends, active, out, static_cast<moc_best_move*>(nullptr), lay);
+                     ends, active, out, static_cast<moc_best_move*>(nullptr), 0, lay);
+  MOC_HIP(hipGetLastError());
+  return MOC_OK;
+}
+
+namespace {
+
+constexpr int kApplyNT = 256;
+
+__global__ void fill_zero_kernel(int32_t* p, int64_t n) {
+  const int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0;
+}
+
+// Applies to each base the move its moc_best_move names (none if move < 0) and counts it.
+// One workgroup per base stages what find_cut reads -- packed copies and the start bitmap --
+// and one lane edits the three arrays in place.
+__global__ __launch_bounds__(kApplyNT) void apply_cuts_kernel(GraphView g, int64_t B, int32_t* starts, int32_t* ends,
+                                                              uint8_t* active, const moc_best_move* best,
+                                                              int32_t* steps) {
+  extern __shared__ uint32_t ap_raw[];
+  const int T = g.T, C = g.C, tid = threadIdx.x;
+  const int bit_words = (T + 31) / 32;
+  NbLds L{};
+  L.packed = ap_raw;
+  L.occ1 = ap_raw + T;
+  const int64_t b = blockIdx.x;
+  if (b >= B) return;
+  const int q = best[b].move;
+  if (q < 0) return;   // the same for every lane of the workgroup
+  const int64_t row = b * T;
+  for (int w = tid; w < bit_words; w += kApplyNT) L.occ1[w] = 0;
+  __syncthreads();
+  for (int k = tid; k < T; k += kApplyNT) {
+    const int s = starts[row + k], e = ends[row + k];
+    const bool live = active[row + k] != 0 && (uint32_t)s <= (uint32_t)e && (uint32_t)e < (uint32_t)T;
+    L.packed[k] = pack_copy(live, s, e);
+    if (live) atomicOr(&L.occ1[s >> 5], 1u << (s & 31));
+  }
+  __syncthreads();
+  if (tid == 0) {
+    const Adj A{g.in_ptr, g.in_idx, g.out_ptr, g.out_idx, reinterpret_cast<const int32_t*>(g.size_dur), 2};
+    const int x = q / C, i = q - x * C;
+    const int u = g.in_idx[x];
+    Cut cut;
+    if (find_cut(A, C, L, active + row, u, (int)(g.edge_pair_c[x] >> 16) + i, &cut)) {
+      ends[row + u * C + cut.k] = cut.last_use;
+      starts[row + u * C + cut.j] = cut.p;
+      ends[row + u * C + cut.j] = cut.ek;
+      active[row + u * C + cut.j] = 1;
+      steps[b] += 1;
+    }
+  }
+}
+
+}  // namespace
+
+extern "C" int moc_search_cuts(const moc_graph* g, int64_t B, int32_t* starts, int32_t* ends, uint8_t* active,
+                               int32_t max_steps, moc_best_move* work_best, int32_t* out_steps, void* hip_stream) {
+  if (!g || B < 0 || max_steps < 0) return MOC_EINVAL;
+  if (B == 0) return MOC_OK;
+  if (!starts || !ends || !active || !work_best || !out_steps) return MOC_EINVAL;
+  if ((((uintptr_t)starts | (uintptr_t)ends | (uintptr_t)out_steps) & 3) || ((uintptr_t)work_best & 7)) return MOC_EINVAL;
+  if (B > 0x7FFFFFFFll) return MOC_EINVAL;
+  int dev = -1;
+  MOC_HIP(hipGetDevice(&dev));
+  if (dev != g->device) return MOC_EDEVICE;
+  if (g->has_self_loop) return MOC_EINVAL;
+  const TgLayout lay = tg_layout(g->view.T, g->view.n, g->view.m, g->max_lds);
+  if (lay.bytes > g->max_lds) return MOC_EOVERFLOW;
+  if ((int64_t)g->view.m * g->view.C > 0x7FFFFFFFll) return MOC_EOVERFLOW;
+  auto kern = lay.adj_off ? toggles_kernel<true, true> : toggles_kernel<false, true>;
+  MOC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              lay.bytes));
+  const int apply_bytes = 4 * (g->view.T + (g->view.T + 31) / 32);
+  MOC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(apply_cuts_kernel),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, apply_bytes));
+  int per_cu = 0;
+  MOC_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, kNT, lay.bytes));
+  if (per_cu < 1) per_cu = 1;
+  const int64_t resident = (int64_t)per_cu * g->num_cu;
+  const unsigned grid = (unsigned)(B < resident ? B : resident);
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((B + 255) / 256)), dim3(256), 0, stream, out_steps, B);
+  for (int step = 0; step < max_steps; ++step) {
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kNT), lay.bytes, stream, g->view, B, starts, ends, active,
+                       static_cast<moc_toggle_score*>(nullptr), work_best, 1, lay);
+    hipLaunchKernelGGL(apply_cuts_kernel, dim3((unsigned)B), dim3(kApplyNT), apply_bytes, stream, g->view, B, starts,
+                       ends, active, work_best, out_steps);
+  }
   MOC_HIP(hipGetLastError());
   return MOC_OK;
 }
@@ -1287,7 +1400,7 @@ extern "C" int moc_eval_cuts(const moc_graph* g, int64_t B, const int32_t* start
   const int64_t resident = (int64_t)per_cu * g->num_cu;
   const unsigned grid = (unsigned)(B < resident ? B : resident);
   hipLaunchKernelGGL(kern, dim3(grid), dim3(kNT), lay.bytes, static_cast<hipStream_t>(hip_stream), g->view, B, starts,
-                     ends, active, out_moves, out_best, lay);
+                     ends, active, out_moves, out_best, 0, lay);
   MOC_HIP(hipGetLastError());
   return MOC_OK;
 }

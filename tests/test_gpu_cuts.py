@@ -218,3 +218,57 @@ def test_cuts_rejects_bad_arguments(moc):
     bm = moc.results_to_numpy(best, moc.BEST_MOVE_DTYPE)
     assert (int(bm["move"][0]), int(bm["violations"][0]), int(bm["peak"][0])) == (-1, 0, 0)
     gh.free()
+
+
+@pytest.mark.parametrize("cfg,count,steps", [(0, 48, 6), (1, 12, 20)])
+def test_search_cuts_follows_the_oracle(moc, workloads, cfg, count, steps):
+    """Greedy descent by cuts: after the same number of steps the candidates are, field by
+    field, what the oracle's descent leaves (active copies compared on all three arrays,
+    inactive ones on the flag: their starts and ends are never touched)."""
+    import torch
+    w = workloads(cfg)
+    s, e, a = w.candidates(0, count)
+    s0, e0, a0 = w.base()
+    s[0], e[0], a[0] = s0, e0, a0          # the plain schedule: violation-free, above the budget
+    gh = upload(moc, w)
+    ds, de, da = to_dev(s, e, a)
+    n_steps = moc.moc_search_cuts(gh, ds, de, da, steps).cpu().numpy()
+    gs, ge, ga = ds.cpu().numpy(), de.cpu().numpy(), da.cpu().numpy()
+    moved = 0
+    for b in range(count):
+        want_steps, ws, we, wa = oracle.search_cuts(w.graph, w.budget, w.C, s[b], e[b], a[b], steps)
+        assert n_steps[b] == want_steps, b
+        assert (ga[b] == wa).all() and (gs[b] == ws).all() and (ge[b] == we).all(), b
+        moved += want_steps
+    assert n_steps[0] > 0 and moved > count // 4
+    gh.free()
+
+
+def test_search_cuts_full_batch(moc, workloads):
+    """n=2000, C=2, all 8192 bases, 3 steps: no candidate gets worse, every applied cut adds one
+    active copy, and one candidate is followed step by step by the oracle."""
+    import torch
+    from paper_2304_14463_amd.inputs import DeviceWorkload
+    w = workloads(3)
+    gh = upload(moc, w)
+    ds, de, da = DeviceWorkload(w).candidates()
+    before = moc.results_to_numpy(moc.moc_eval_batch(gh, ds, de, da))
+    s0, e0, a0 = ds[5].cpu().numpy(), de[5].cpu().numpy(), da[5].cpu().numpy()
+    n_active = (da != 0).sum(1)
+    n_steps = moc.moc_search_cuts(gh, ds, de, da, 3)
+    after = moc.results_to_numpy(moc.moc_eval_batch(gh, ds, de, da))
+    torch.cuda.synchronize()
+    steps = n_steps.cpu().numpy()
+    assert ((da != 0).sum(1) - n_active).cpu().numpy().tolist() == steps.tolist()
+    assert steps.max() == 3 and (steps > 0).mean() > 0.5
+    key0 = np.stack([before["violations"], np.maximum(before["peak"], w.budget)], 1)
+    key1 = np.stack([after["violations"], np.maximum(after["peak"], w.budget)], 1)
+    worse = (key1[:, 0] > key0[:, 0]) | ((key1[:, 0] == key0[:, 0]) & (key1[:, 1] > key0[:, 1]))
+    assert not worse.any()
+    better = (key1[:, 0] < key0[:, 0]) | ((key1[:, 0] == key0[:, 0]) & (key1[:, 1] < key0[:, 1]))
+    assert (better == (steps > 0)).all()
+    assert (after["duration"] > before["duration"])[steps > 0].all()
+    want_steps, ws, we, wa = oracle.search_cuts(w.graph, w.budget, w.C, s0, e0, a0, 3)
+    assert steps[5] == want_steps
+    assert (da[5].cpu().numpy() == wa).all() and (ds[5].cpu().numpy() == ws).all() and (de[5].cpu().numpy() == we).all()
+    gh.free()
