@@ -176,6 +176,29 @@ def measure_neighbours(moc, steps, warmup):
                    "bytes_written": w.B * w.m * w.C * 16, "frac_applicable": applicable,
                    "best_only_ms_per_step": ms_cuts["best_only"]}
     del oc, ob
+    # greedy descent by cuts from the violation-free bases: 16 steps of score, choose, apply
+    ev0 = moc.results_to_numpy(moc.moc_eval_batch(gh, ds, de, da))
+    walkers = torch.from_numpy((ev0["violations"] == 0).nonzero()[0]).cuda()
+    walkers = walkers[torch.arange(w.B, device="cuda") % walkers.numel()]
+    ws, we, wa = ds[walkers].contiguous(), de[walkers].contiguous(), da[walkers].contiguous()
+    ev0 = moc.results_to_numpy(moc.moc_eval_batch(gh, ws, we, wa))
+    search_steps = 16
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    applied = moc.moc_search_cuts(gh, ws, we, wa, search_steps)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3
+    ev1 = moc.results_to_numpy(moc.moc_eval_batch(gh, ws, we, wa))
+    gap0 = (ev0["peak"] - w.budget).clip(min=0).astype(float)
+    gap1 = (ev1["peak"] - w.budget).clip(min=0).astype(float)
+    out["search_cuts"] = {
+        "steps": search_steps, "ms_total": ms, "ms_per_step": ms / search_steps,
+        "walkers": w.B, "mean_moves_applied": float(applied.float().mean()),
+        "violations_after": int(ev1["violations"].max()),
+        "mean_gap_to_budget_closed": float(1.0 - gap1.sum() / max(gap0.sum(), 1.0)),
+        "frac_feasible_before": float(ev0["feasible"].mean()), "frac_feasible_after": float(ev1["feasible"].mean()),
+        "mean_duration_increase_pct": float(100.0 * (ev1["duration"] / ev0["duration"] - 1.0).mean())}
+    del ws, we, wa
     # back to sequences: every base decoded and costed, sequences written out
     # -- of the candidates a search would decode: the violation-free bases, repeated to B rows
     ev = moc.results_to_numpy(moc.moc_eval_batch(gh, ds, de, da))

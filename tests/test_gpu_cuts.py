@@ -272,3 +272,27 @@ def test_search_cuts_full_batch(moc, workloads):
     assert steps[5] == want_steps
     assert (da[5].cpu().numpy() == wa).all() and (ds[5].cpu().numpy() == ws).all() and (de[5].cpu().numpy() == we).all()
     gh.free()
+
+
+def test_search_cuts_rejects_bad_arguments(moc):
+    import ctypes
+    import torch
+    from paper_2304_14463_amd.inputs import graph_from_edges
+    g = graph_from_edges(3, [(0, 1), (1, 2)], [1, 1, 1], [1, 1, 1])
+    gh = moc.moc_graph_upload(3, g.in_ptr, g.in_idx, g.size, g.dur, 1, 2)
+    s = torch.zeros((2, 6), dtype=torch.int32, device="cuda")
+    a = torch.zeros((2, 6), dtype=torch.uint8, device="cuda")
+    best = torch.zeros((2, 16), dtype=torch.uint8, device="cuda")
+    steps = torch.full((2,), 9, dtype=torch.int32, device="cuda")
+    L = moc.lib()
+    vp = lambda t, off=0: ctypes.c_void_p(t.data_ptr() + off)
+    assert L.moc_search_cuts(gh._h, 2, vp(s), vp(s), vp(a), 1, None, vp(steps), None) == -1
+    assert L.moc_search_cuts(gh._h, 2, vp(s), vp(s), vp(a), 1, vp(best), None, None) == -1
+    assert L.moc_search_cuts(gh._h, 2, vp(s), vp(s), vp(a), -1, vp(best), vp(steps), None) == -1
+    assert L.moc_search_cuts(gh._h, 2, vp(s), vp(s), vp(a), 1, vp(best, 4), vp(steps), None) == -1
+    assert L.moc_search_cuts(gh._h, 0, None, None, None, 1, None, None, None) == 0
+    assert (steps.cpu().numpy() == 9).all()                       # nothing was queued by the calls above
+    e = s.clone()
+    assert L.moc_search_cuts(gh._h, 2, vp(s), vp(e), vp(a), 0, vp(best), vp(steps), None) == 0
+    assert (steps.cpu().numpy() == 0).all()                       # no steps: the counters are cleared, nothing else
+    gh.free()
