@@ -209,8 +209,11 @@ int moc_eval_toggles(const moc_graph* g, int64_t B, const int32_t* starts, const
  * the edited candidate (the duration is the base's plus w_u).
  *   out_moves   device, moc_cut_score [B][m*C], or NULL
  *   out_best    device, moc_best_move [B], or NULL: the applicable move that
- *               minimises (violations, peak, q) lexicographically -- the same
- *               order as (violations, max(peak, M), peak, q); move = -1 and
+ *               minimises (violations, peak, n_at, q) lexicographically, n_at
+ *               being the number of positions at which the edited candidate's
+ *               memory still reaches the base's peak (0 when the peak falls):
+ *               among moves that leave the peak where it is, the one that
+ *               clears most of the positions that attain it; move = -1 and
  *               zeros if none is applicable (always so when m == 0)
  * At least one of out_moves / out_best must be given; both 8-byte aligned.
  * LDS use and limits as moc_eval_toggles.  A graph with an edge (v,v) is not
@@ -225,9 +228,11 @@ int moc_eval_cuts(const moc_graph* g, int64_t B, const int32_t* starts, const in
  * Greedy descent by cut-and-recompute moves, every candidate on its own: the
  * memory-reducing half of a local search in the spirit of Phase 1 of
  * Section 2.4, which minimises max(peak, M).  Repeats max_steps times: find the
- * best move as moc_eval_cuts does; if it lowers (violations, max(peak, M))
- * lexicographically against the candidate as it stands, apply it in place.  A
- * candidate whose best move does not improve it stays as it is from then on.
+ * best move as moc_eval_cuts does; apply it in place if it lowers
+ * (violations, max(peak, M)) lexicographically against the candidate as it
+ * stands or, with both unchanged and the peak above M, leaves fewer positions
+ * at the peak.  A candidate whose best move does neither stays as it is from
+ * then on.
  *   starts, ends, active   device, [B][T], edited in place
  *   max_steps              >= 0
  *   work_best              device, moc_best_move [B], 8-byte aligned: workspace

@@ -136,20 +136,22 @@ def toggles(g, budget, C, starts, ends, active, T=None):
     return scores
 
 
-def cuts(g, budget, C, starts, ends, active, T=None):
+def cuts(g, budget, C, starts, ends, active, T=None, with_at_peak=False):
     """Scores of the m*C cut-and-recompute moves of one candidate (in-edge x in CSR order,
     consumer copy i; q = x*C + i) by full re-evaluation of the edited candidate:
-    int64 [m*C][3] = (violations, peak, duration), (-1, -1, 0) where not applicable."""
+    int64 [m*C][3] = (violations, peak, duration), (-1, -1, 0) where not applicable.
+    with_at_peak adds a fourth column: the positions at which the edited candidate's memory
+    still reaches the peak of the candidate as given."""
     K = g.n * C
     T = K if T is None else T
     s, e, a = _cand(starts, np.int32, K), _cand(ends, np.int32, K), _cand(active, np.uint8, K)
     assert s.shape[0] == 1
     m = int(np.asarray(g.in_ptr)[-1])
-    scores = np.zeros((m * C, 3), dtype=np.int64)
+    scores = np.zeros((m * C, 4), dtype=np.int64)
     keep, ga = _graph_args(g)
     lib().orc_cuts(*ga, ctypes.c_int64(budget), ctypes.c_int32(C), ctypes.c_int32(T),
                    _p(s, ctypes.c_int32), _p(e, ctypes.c_int32), _p(a, ctypes.c_uint8), _p(scores, ctypes.c_int64))
-    return scores
+    return scores if with_at_peak else np.ascontiguousarray(scores[:, :3])
 
 
 def cut_apply(g, C, starts, ends, active, x, i, T=None):

@@ -298,8 +298,16 @@ int orc_cut_apply(int32_t n, const int32_t* in_ptr, const int32_t* in_idx, const
   return apply_cut(p, x, i, out_s, out_e, out_a);
 }
 
-// Scores of all m*C cuts of one candidate: scores[3q..3q+2] = (violations, peak, duration) of
-// the edited candidate by full re-evaluation, q = x*C + i; (-1, -1, 0) where not applicable.
+// Number of positions at which a profile reaches at least `level`.
+static int64_t positions_at(const std::vector<int64_t>& prof, int T, int64_t level) {
+  int64_t c = 0;
+  for (int t = 0; t < T; ++t) c += prof[t] >= level ? 1 : 0;
+  return c;
+}
+
+// Scores of all m*C cuts of one candidate: scores[4q..4q+3] = (violations, peak, duration,
+// positions at which the edited candidate's memory still reaches the peak of the candidate as
+// given) by full re-evaluation, q = x*C + i; (-1, -1, 0, 0) where not applicable.
 void orc_cuts(int32_t n, const int32_t* in_ptr, const int32_t* in_idx, const int32_t* size, const int32_t* dur,
               int64_t budget, int32_t C, int32_t T, const int32_t* starts, const int32_t* ends,
               const uint8_t* active, int64_t* scores) {
@@ -308,28 +316,34 @@ void orc_cuts(int32_t n, const int32_t* in_ptr, const int32_t* in_idx, const int
   const int K = n * C, m = in_ptr[n];
   std::vector<int32_t> s(K), e(K);
   std::vector<uint8_t> a(K);
+  std::vector<int64_t> prof(T);
   int64_t res[R_FIELDS];
+  evaluate(p, starts, ends, active, w, res, nullptr);
+  const int64_t base_peak = res[R_PEAK];
   for (int x = 0; x < m; ++x)
     for (int i = 0; i < C; ++i) {
       std::copy(starts, starts + K, s.begin());
       std::copy(ends, ends + K, e.begin());
       std::copy(active, active + K, a.begin());
-      int64_t* out = scores + 3 * ((int64_t)x * C + i);
+      int64_t* out = scores + 4 * ((int64_t)x * C + i);
       if (!apply_cut(p, x, i, s.data(), e.data(), a.data())) {
-        out[0] = -1; out[1] = -1; out[2] = 0;
+        out[0] = -1; out[1] = -1; out[2] = 0; out[3] = 0;
         continue;
       }
-      evaluate(p, s.data(), e.data(), a.data(), w, res, nullptr);
+      evaluate(p, s.data(), e.data(), a.data(), w, res, prof.data());
       out[0] = res[R_VIOLATIONS];
       out[1] = res[R_PEAK];
       out[2] = res[R_DURATION];
+      out[3] = positions_at(prof, T, base_peak);
     }
 }
 
 // Greedy descent by cuts, one candidate, in place: up to max_steps times, score every cut by
-// full re-evaluation, take the first minimum of (violations, peak) among the applicable ones,
-// and apply it if it lowers (violations, max(peak, M)) against the candidate as it stands;
-// stop at the first step that does not.  Returns the number of cuts applied.
+// full re-evaluation, take the first minimum of (violations, peak, positions left at the
+// present peak) among the applicable ones, and apply it if it lowers
+// (violations, max(peak, M)) against the candidate as it stands or, above the budget with both
+// unchanged, leaves fewer positions at the peak; stop at the first step that does not.
+// Returns the number of cuts applied.
 int orc_search_cuts(int32_t n, const int32_t* in_ptr, const int32_t* in_idx, const int32_t* size, const int32_t* dur,
                     int64_t budget, int32_t C, int32_t T, int32_t* starts, int32_t* ends, uint8_t* active,
                     int32_t max_steps) {
@@ -338,12 +352,14 @@ int orc_search_cuts(int32_t n, const int32_t* in_ptr, const int32_t* in_idx, con
   const int K = n * C, m = in_ptr[n];
   std::vector<int32_t> s(K), e(K);
   std::vector<uint8_t> a(K);
+  std::vector<int64_t> prof(T);
   int64_t res[R_FIELDS];
   int applied = 0;
   for (int step = 0; step < max_steps; ++step) {
-    evaluate(p, starts, ends, active, w, res, nullptr);
-    const int64_t now_v = res[R_VIOLATIONS], now_p = std::max(res[R_PEAK], budget);
-    int64_t best_v = 0, best_p = 0;
+    evaluate(p, starts, ends, active, w, res, prof.data());
+    const int64_t now_v = res[R_VIOLATIONS], now_peak = res[R_PEAK], now_p = std::max(now_peak, budget);
+    const int64_t now_at = positions_at(prof, T, now_peak);
+    int64_t best_v = 0, best_p = 0, best_at = 0;
     int best_x = -1, best_i = -1;
     for (int x = 0; x < m; ++x)
       for (int i = 0; i < C; ++i) {
@@ -351,17 +367,22 @@ int orc_search_cuts(int32_t n, const int32_t* in_ptr, const int32_t* in_idx, con
         std::copy(ends, ends + K, e.begin());
         std::copy(active, active + K, a.begin());
         if (!apply_cut(p, x, i, s.data(), e.data(), a.data())) continue;
-        evaluate(p, s.data(), e.data(), a.data(), w, res, nullptr);
-        if (best_x < 0 || res[R_VIOLATIONS] < best_v || (res[R_VIOLATIONS] == best_v && res[R_PEAK] < best_p)) {
+        evaluate(p, s.data(), e.data(), a.data(), w, res, prof.data());
+        const int64_t at = positions_at(prof, T, now_peak);
+        if (best_x < 0 || res[R_VIOLATIONS] < best_v ||
+            (res[R_VIOLATIONS] == best_v && (res[R_PEAK] < best_p || (res[R_PEAK] == best_p && at < best_at)))) {
           best_v = res[R_VIOLATIONS];
           best_p = res[R_PEAK];
+          best_at = at;
           best_x = x;
           best_i = i;
         }
       }
     if (best_x < 0) break;
     const int64_t then_p = std::max(best_p, budget);
-    if (!(best_v < now_v || (best_v == now_v && then_p < now_p))) break;
+    const bool better = best_v < now_v ||
+                        (best_v == now_v && (then_p < now_p || (then_p == now_p && now_peak > budget && best_at < now_at)));
+    if (!better) break;
     apply_cut(p, best_x, best_i, starts, ends, active);
     ++applied;
   }

@@ -898,6 +898,19 @@ __device__ __forceinline__ int interval_max(const int32_t* profile, const BlockM
 // can change: every consumer that k covered is covered by one of the two pieces, since no
 // live consumer starts in (last use, p].  The profile loses m_u on (last use, p).
 // Returns false if the move is not applicable.
+// Positions at which the base's profile reaches its peak, countable over any range.
+struct PeakCount {
+  const uint32_t* bits;
+  const int32_t* before;   // per word: such positions in the words below it
+  int total;
+  __device__ __forceinline__ int up_to(int x) const {   // in [0, x]
+    return before[x >> 5] + (int)__popc(bits[x >> 5] & (0xFFFFFFFFu >> (31 - (x & 31))));
+  }
+  __device__ __forceinline__ int within(int lo, int hi) const {   // in [lo, hi], 1 <= lo <= hi
+    return up_to(hi) - up_to(lo - 1);
+  }
+};
+
 struct Cut {
   int k, j;        // copy of u that is cut, copy of u that becomes active
   int sk, ek;      // interval of copy k as it stands
@@ -948,7 +961,8 @@ __device__ __forceinline__ bool find_cut(const Adj& g, int C, const NbLds& L, co
 
 __device__ __forceinline__ bool score_cut(const Adj& g, int C, int T, const NbLds& L, const BlockMax& block_max,
                                           const uint8_t* __restrict__ active_row, int u, int consumer_copy,
-                                          int base_viol, int base_peak, int* viol_out, int* peak_out) {
+                                          int base_viol, int base_peak, const PeakCount& at_peak, int* viol_out,
+                                          int* peak_out, int* at_peak_out) {
   Cut cut;
   if (!find_cut(g, C, L, active_row, u, consumer_copy, &cut)) return false;
   const int k = cut.k, j = cut.j, sk = cut.sk, ek = cut.ek, p = cut.p, last_use = cut.last_use;
@@ -976,13 +990,17 @@ __device__ __forceinline__ bool score_cut(const Adj& g, int C, int T, const NbLd
     vv += cov ? 0 : 1;
   }
   if (j == 0) --vv;   // Eq. (7)
-  int pk = base_peak;
+  int pk = base_peak, at = at_peak.total;
   if (last_use + 1 <= p - 1) {
     const int top = interval_max(L.profile, block_max, last_use + 1, p - 1);
-    pk = max(top - g.size_of(u), max(L.pmax[last_use], L.smax[p]));
+    const int sz = g.size_of(u);
+    pk = max(top - sz, max(L.pmax[last_use], L.smax[p]));
+    // positions still at the base's peak: those outside the range (all, if nothing is taken away)
+    at = pk < base_peak ? 0 : at - (sz > 0 ? at_peak.within(last_use + 1, p - 1) : 0);
   }
   *viol_out = vv;
   *peak_out = pk;
+  *at_peak_out = at;
   return true;
 }
 
@@ -1000,8 +1018,9 @@ TgLayout tg_layout(int T, int n, int m, int max_lds) {
   l.blocks = (T + 31) / 32;
   l.levels = 1;
   while ((2 << (l.levels - 1)) <= l.blocks) ++l.levels;
-  // profile, prefix max, suffix max (with sentinels), packed, block maxima, two bitmaps, scratch
-  const int words = 4 * l.T_pad + 8 + l.levels * l.blocks + 2 * l.bit_words + 8 * kNW + 16;
+  // profile, prefix max, suffix max (with sentinels), packed, block maxima, two start bitmaps, the
+  // bitmap of the positions at the peak with its running count per word, scratch
+  const int words = 4 * l.T_pad + 8 + l.levels * l.blocks + 4 * l.bit_words + 8 * kNW + 16;
   l.adj_off = 0;
   l.bytes = 4 * words;
   // A lane walks its node's edges one after the other: from LDS whenever the lists fit (the
@@ -1031,7 +1050,9 @@ __global__ __launch_bounds__(kNT) void toggles_kernel(GraphView g, int64_t B, co
   L.occ1 = reinterpret_cast<uint32_t*>(block_max + lay.levels * lay.blocks);
   const BlockMax block_table{block_max, lay.blocks};
   L.occ2 = L.occ1 + lay.bit_words;
-  L.scratch = reinterpret_cast<int32_t*>(L.occ2 + lay.bit_words);
+  uint32_t* const peak_bits = L.occ2 + lay.bit_words;        // bit t: the profile reaches the base's peak at t
+  int32_t* const peak_before = reinterpret_cast<int32_t*>(peak_bits + lay.bit_words);   // such positions in earlier words
+  L.scratch = reinterpret_cast<int32_t*>(peak_before + lay.bit_words);
   int32_t* const counts = L.scratch + 8 * kNW;   // [0] base violations, [1] base duration
   const int tid = threadIdx.x;
   const int T = g.T, C = g.C;
@@ -1118,56 +1139,84 @@ __global__ __launch_bounds__(kNT) void toggles_kernel(GraphView g, int64_t B, co
     const int base_viol = counts[0], base_dur = counts[1], base_peak = L.pmax[T - 1];
 
     if constexpr (CUTS) {
+      // ---- where the base is at its peak
+      for (int w = tid; w < lay.bit_words; w += kNT) {
+        uint32_t bits = 0;
+        for (int t = 32 * w; t < min(32 * w + 32, T); ++t) bits |= (L.profile[t] == base_peak ? 1u : 0u) << (t & 31);
+        peak_bits[w] = bits;
+      }
+      __syncthreads();
+      for (int w = tid; w < lay.bit_words; w += kNT) {
+        int below = 0;
+        for (int x = 0; x < w; ++x) below += __popc(peak_bits[x]);
+        peak_before[w] = below;
+      }
+      __syncthreads();
+      const PeakCount at_peak{peak_bits, peak_before,
+                              peak_before[lay.bit_words - 1] + (int)__popc(peak_bits[lay.bit_words - 1])};
       // ---- one lane per in-edge and copy of its consumer; the best move is the applicable one
-      // that minimises (violations, peak, index)
+      // that minimises (violations, peak, positions left at the base's peak, index)
       const int64_t out_row = b * ((int64_t)g.m * C);
       uint32_t best_viol = 0xFFFFFFFFu, best_peak = 0xFFFFFFFFu;
-      int best_q = -1;
+      int best_at = 0x7FFFFFFF, best_q = -1;
       for (int q = tid; q < g.m * C; q += kNT) {
         const int x = q / C, i = q - x * C;
         const int u = A.in_idx[x];
         const int consumer_copy = (int)(g.edge_pair_c[x] >> 16) + i;
         moc_toggle_score sc{-1, -1, 0};
-        int vv, pk;
-        if (score_cut(A, C, T, L, block_table, active + row, u, consumer_copy, base_viol, base_peak, &vv, &pk)) {
+        int vv, pk, at;
+        if (score_cut(A, C, T, L, block_table, active + row, u, consumer_copy, base_viol, base_peak, at_peak, &vv, &pk,
+                      &at)) {
           sc.violations = vv;
           sc.peak = pk;
           sc.duration = (int64_t)base_dur + g.size_dur[u].y;
-          if (best_q < 0 || (uint32_t)vv < best_viol || ((uint32_t)vv == best_viol && (uint32_t)pk < best_peak)) {
+          if (best_q < 0 || (uint32_t)vv < best_viol ||
+              ((uint32_t)vv == best_viol && ((uint32_t)pk < best_peak || ((uint32_t)pk == best_peak && at < best_at)))) {
             best_viol = (uint32_t)vv;   // a lane meets its moves in rising order: the first of equals stays
             best_peak = (uint32_t)pk;
+            best_at = at;
             best_q = q;
           }
         }
         if (out) out[out_row + q] = sc;
       }
       if (out_best) {
-        auto take = [&](uint32_t ov, uint32_t op, int oq) {
+        auto take = [&](uint32_t ov, uint32_t op, int oa, int oq) {
           if (oq < 0) return;
-          if (best_q < 0 || ov < best_viol || (ov == best_viol && (op < best_peak || (op == best_peak && oq < best_q)))) {
+          if (best_q < 0 || ov < best_viol ||
+              (ov == best_viol &&
+               (op < best_peak || (op == best_peak && (oa < best_at || (oa == best_at && oq < best_q)))))) {
             best_viol = ov;
             best_peak = op;
+            best_at = oa;
             best_q = oq;
           }
         };
 #pragma unroll
         for (int off = kWave / 2; off > 0; off >>= 1)
-          take(__shfl_xor(best_viol, off), __shfl_xor(best_peak, off), __shfl_xor(best_q, off));
+          take(__shfl_xor(best_viol, off), __shfl_xor(best_peak, off), __shfl_xor(best_at, off),
+               __shfl_xor(best_q, off));
         __syncthreads();   // the scratch words below were last read by the scans of the staging
         if ((tid & (kWave - 1)) == 0) {
-          L.scratch[3 * (tid / kWave)] = (int)best_viol;
-          L.scratch[3 * (tid / kWave) + 1] = (int)best_peak;
-          L.scratch[3 * (tid / kWave) + 2] = best_q;
+          L.scratch[4 * (tid / kWave)] = (int)best_viol;
+          L.scratch[4 * (tid / kWave) + 1] = (int)best_peak;
+          L.scratch[4 * (tid / kWave) + 2] = best_at;
+          L.scratch[4 * (tid / kWave) + 3] = best_q;
         }
         __syncthreads();
         if (tid == 0) {
           best_q = -1;
           for (int w = 0; w < kNW; ++w)
-            take((uint32_t)L.scratch[3 * w], (uint32_t)L.scratch[3 * w + 1], L.scratch[3 * w + 2]);
-          // a descent step takes the move only if it lowers (violations, max(peak, M))
+            take((uint32_t)L.scratch[4 * w], (uint32_t)L.scratch[4 * w + 1], L.scratch[4 * w + 2],
+                 L.scratch[4 * w + 3]);
+          // a descent step takes the move only if it lowers (violations, max(peak, M)) or, above
+          // the budget with both unchanged, leaves fewer positions at the peak
           if (improving && best_q >= 0) {
             const int64_t now = max((int64_t)base_peak, g.budget), then = max((int64_t)best_peak, g.budget);
-            if (!((int)best_viol < base_viol || ((int)best_viol == base_viol && then < now))) best_q = -1;
+            const bool better = (int)best_viol < base_viol ||
+                                ((int)best_viol == base_viol &&
+                                 (then < now || (then == now && base_peak > g.budget && best_at < at_peak.total)));
+            if (!better) best_q = -1;
           }
           moc_best_move bm{best_q, best_q < 0 ? 0 : (int)best_viol, best_q < 0 ? 0 : (int64_t)best_peak};
           out_best[b] = bm;

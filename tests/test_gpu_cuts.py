@@ -33,12 +33,13 @@ def gpu_cuts(moc, gh, ds, de, da):
 
 
 def assert_best(best, want, what=""):
-    """want: the oracle's table of one base; the best move is its first minimum of (violations, peak)."""
+    """want: the oracle's table of one base with its fourth column; the best move is the first
+    minimum of (violations, peak, positions left at the base's peak)."""
     ok = np.flatnonzero(want[:, 0] >= 0)
     if ok.size == 0:
         assert (int(best["move"]), int(best["violations"]), int(best["peak"])) == (-1, 0, 0), what
         return
-    q = min(ok, key=lambda q: (want[q, 0], want[q, 1], q))
+    q = min(ok, key=lambda q: (want[q, 0], want[q, 1], want[q, 3], q))
     assert (int(best["move"]), int(best["violations"]), int(best["peak"])) == (q, want[q, 0], want[q, 1]), what
 
 
@@ -97,7 +98,7 @@ def test_cuts_small_graphs(moc, n, C):
     got, best = gpu_cuts(moc, gh, ds, de, da)
     applicable = 0
     for b in range(B):
-        want = oracle.cuts(g, budget, C, s[b], e[b], a[b])
+        want = oracle.cuts(g, budget, C, s[b], e[b], a[b], with_at_peak=True)
         assert_same(got[b], want, f"n={n} C={C} row {b}")
         assert_best(best[b], want, f"n={n} C={C} row {b}")
         applicable += int((want[:, 0] >= 0).sum())
@@ -117,7 +118,7 @@ def test_cuts_hub_node(moc):
     ds, de, da = to_dev(s, e, a)
     got, best = gpu_cuts(moc, gh, ds, de, da)
     for b in range(6):
-        want = oracle.cuts(g, 1000, C, s[b], e[b], a[b])
+        want = oracle.cuts(g, 1000, C, s[b], e[b], a[b], with_at_peak=True)
         assert_same(got[b], want, f"hub row {b}")
         assert_best(best[b], want, f"hub row {b}")
     assert (got["violations"][0] >= 0).sum() > n // 2
@@ -141,14 +142,16 @@ def test_cuts_workload(moc, workloads):
     for b in (0, w.B // 2 + 1, w.B - 1):
         s, e, a = ds[b].cpu().numpy(), de[b].cpu().numpy(), da[b].cpu().numpy()
         got = moc.results_to_numpy(out[b], moc.TOGGLE_SCORE_DTYPE)
-        want = oracle.cuts(w.graph, w.budget, w.C, s, e, a)
+        want = oracle.cuts(w.graph, w.budget, w.C, s, e, a, with_at_peak=True)
         assert_same(got, want, f"base {b}")
         assert_best(best[b], want, f"base {b}")
-    # every base: the best move is the first minimum of its own table
+    # every base: the best move carries the least (violations, peak) of its own table
     for b in range(0, w.B, 97):
         got = moc.results_to_numpy(out[b], moc.TOGGLE_SCORE_DTYPE)
-        tab = np.stack([got["violations"], got["peak"]], 1).astype(np.int64)
-        assert_best(best[b], tab, f"base {b} against its table")
+        ok = np.flatnonzero(got["violations"] >= 0)
+        least = min((int(got["violations"][q]), int(got["peak"][q])) for q in ok)
+        q = int(best[b]["move"])
+        assert (int(best[b]["violations"]), int(best[b]["peak"])) == least == (int(got["violations"][q]), int(got["peak"][q]))
     rng = np.random.default_rng(5)
     rows, es, ee, ea, want = [], [], [], [], []
     for b in rng.integers(0, w.B, 48):
@@ -185,7 +188,7 @@ def test_cuts_adjacency_from_global_memory(moc):
     ds, de, da = to_dev(s, e, a)
     got, best = gpu_cuts(moc, gh, ds, de, da)
     for b in range(3):
-        want = oracle.cuts(g, 5000, C, s[b], e[b], a[b])
+        want = oracle.cuts(g, 5000, C, s[b], e[b], a[b], with_at_peak=True)
         assert_same(got[b], want, f"row {b}")
         assert_best(best[b], want, f"row {b}")
     gh.free()
