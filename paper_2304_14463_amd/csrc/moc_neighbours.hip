@@ -1139,19 +1139,36 @@ __global__ __launch_bounds__(kNT) void toggles_kernel(GraphView g, int64_t B, co
     const int base_viol = counts[0], base_dur = counts[1], base_peak = L.pmax[T - 1];
 
     if constexpr (CUTS) {
-      // ---- where the base is at its peak
-      for (int w = tid; w < lay.bit_words; w += kNT) {
-        uint32_t bits = 0;
-        for (int t = 32 * w; t < min(32 * w + 32, T); ++t) bits |= (L.profile[t] == base_peak ? 1u : 0u) << (t & 31);
-        peak_bits[w] = bits;
+      // ---- where the base is at its peak: a wave takes 64 positions at a time (two words of
+      // the bitmap by one ballot), then one wave turns the words' counts into running counts
+      {
+        const int lane = tid & (kWave - 1), wave = tid / kWave;
+        for (int t0 = wave * kWave; t0 < 32 * lay.bit_words; t0 += kNT) {
+          const int t = t0 + lane;
+          const uint64_t hit = __ballot(t < T && L.profile[t] == base_peak);
+          if (lane == 0) {
+            peak_bits[t0 >> 5] = (uint32_t)hit;
+            if ((t0 >> 5) + 1 < lay.bit_words) peak_bits[(t0 >> 5) + 1] = (uint32_t)(hit >> 32);
+          }
+        }
+        __syncthreads();
+        if (wave == 0) {
+          int carry = 0;
+          for (int w0 = 0; w0 < lay.bit_words; w0 += kWave) {
+            const int w = w0 + lane;
+            const int mine = w < lay.bit_words ? (int)__popc(peak_bits[w]) : 0;
+            int inc = mine;
+#pragma unroll
+            for (int off = 1; off < kWave; off <<= 1) {
+              const int o = __shfl_up(inc, off);
+              if (lane >= off) inc += o;
+            }
+            if (w < lay.bit_words) peak_before[w] = carry + inc - mine;
+            carry += __shfl(inc, kWave - 1);
+          }
+        }
+        __syncthreads();
       }
-      __syncthreads();
-      for (int w = tid; w < lay.bit_words; w += kNT) {
-        int below = 0;
-        for (int x = 0; x < w; ++x) below += __popc(peak_bits[x]);
-        peak_before[w] = below;
-      }
-      __syncthreads();
       const PeakCount at_peak{peak_bits, peak_before,
                               peak_before[lay.bit_words - 1] + (int)__popc(peak_bits[lay.bit_words - 1])};
       // ---- one lane per in-edge and copy of its consumer; the best move is the applicable one
