@@ -260,7 +260,7 @@ def cpu_baseline(w, cand, res, target_seconds=15.0):
 def main():
     args = parse()
     if args.gpus != 1:
-        sys.exit("bench.py: this build runs on one GPU only (candidates shard trivially by batch; "
+        sys.exit("bench.py: the library runs on one GPU only (candidates shard trivially by batch; "
                  "no multi-GPU path is built). Use --gpus 1.")
     import torch
     if not torch.cuda.is_available():
