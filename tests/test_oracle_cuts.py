@@ -67,7 +67,14 @@ def test_closed_form_on_a_long_skip():
     score = oracle.cuts(g, 10**9, C, s, e, a)[x * C]
     # the peak stays 50 + 3 + 3, now at the last position only (nodes 0, n-2 and n-1)
     assert list(score) == [0, 56, base[F["duration"]] + 1]
+    # the base is at its peak at every even position from 4 on (n - 2 of them: nodes 0, v-1, v);
+    # after the cut only the last of those still reaches it
+    full = oracle.cuts(g, 10**9, C, s, e, a, with_at_peak=True)
+    assert full[x * C][3] == 1 and list(full[x * C][:3]) == list(score)
+    assert full[edge_index(g, 0, 1) * C][3] == n - 2          # cut for the first consumer: nothing gained
+    assert (full[full[:, 0] < 0] == [-1, -1, 0, 0]).all()
     _, prof0 = oracle.profile(g, 10**9, C, s, e, a)
+    assert (prof0 == 56).sum() == n - 2
     _, prof1 = oracle.profile(g, 10**9, C, s2, e2, a2)
     want = prof0.copy(); want[3:2 * (n - 1) - 1] -= 50
     assert (prof1 == want).all() and prof1[3:2 * (n - 1) - 1].max() == 6
