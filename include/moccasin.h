@@ -200,7 +200,9 @@ int moc_eval_toggles(const moc_graph* g, int64_t B, const int32_t* starts, const
  *   k   the live copy of u with s_k < t <= e_k that starts last (the lowest
  *       index among equal starts),
  *   j   the lowest copy of u that is not active,
- *   p   the last position in (s_k, t) at which no live copy starts,
+ *   p   the last position in (s_k, t) at which no live copy starts and every
+ *       predecessor w of u has a live copy with s_w < p <= e_w (so that the
+ *       new computation finds its inputs, Eq. (5)),
  *   e'  the last start in (s_k, p) of a live copy of any consumer of u, s_k if
  *       there is none;
  * the move sets copy k to [s_k, e'] and copy j to active, [p, e_k].  It is not

@@ -244,7 +244,8 @@ void orc_toggles(int32_t n, const int32_t* in_ptr, const int32_t* in_idx, const 
 //   t  = start of the consumer copy, which must be live;
 //   k  = the live copy of u with s_k < t <= e_k that starts last (lowest index among equals);
 //   j  = the lowest copy of u that is not active;
-//   p  = the last position in (s_k, t) at which no live copy starts;
+//   p  = the last position in (s_k, t) at which no live copy starts and the outputs of all
+//        predecessors of u are held (Eq. (5) for the new computation);
 //   e' = the last start, in (s_k, p), of a live copy of a consumer of u; s_k if there is none.
 // Copy k keeps [s_k, e'], copy j becomes active with [p, e_k].  Returns 0 (nothing changed) if
 // the consumer copy is not live or k, j or p does not exist.
@@ -267,8 +268,19 @@ static int apply_cut(const Problem& p, int x, int i, int32_t* s, int32_t* e, uin
   std::vector<char> taken(T, 0);
   for (int q = 0; q < p.n * C; ++q)
     if (live(q)) taken[s[q]] = 1;
+  auto inputs_held = [&](int at) {   // every predecessor of u has a live copy with s < at <= e
+    for (int y = p.in_ptr[u]; y < p.in_ptr[u + 1]; ++y) {
+      bool held = false;
+      for (int q = 0; q < C; ++q) {
+        const int cw = p.in_idx[y] * C + q;
+        if (live(cw) && s[cw] < at && at <= e[cw]) held = true;
+      }
+      if (!held) return false;
+    }
+    return true;
+  };
   int pos = t - 1;
-  while (pos > s[k] && taken[pos]) --pos;
+  while (pos > s[k] && (taken[pos] || !inputs_held(pos))) --pos;
   if (pos <= s[k]) return 0;
   int last_use = s[k];
   for (int w = 0; w < p.n; ++w)

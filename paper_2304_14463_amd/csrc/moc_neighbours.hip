@@ -890,14 +890,6 @@ __device__ __forceinline__ int interval_max(const int32_t* profile, const BlockM
   return top;
 }
 
-// The cut-and-recompute move for the in-edge (u, v) and copy i of the consumer (see
-// moc_eval_cuts in moccasin.h): copy k of u, the last-starting live copy that covers the
-// consumer's start t, keeps [s_k, last use before p]; the lowest inactive copy j of u takes
-// [p, e_k], p the last position in (s_k, t) where no live copy starts.  Only Eq. (3) among the
-// copies of u, Eq. (5) for the inputs of the new computation and Eq. (7) (when j is copy 0)
-// can change: every consumer that k covered is covered by one of the two pieces, since no
-// live consumer starts in (last use, p].  The profile loses m_u on (last use, p).
-// Returns false if the move is not applicable.
 // Positions at which the base's profile reaches its peak, countable over any range.
 struct PeakCount {
   const uint32_t* bits;
@@ -911,6 +903,14 @@ struct PeakCount {
   }
 };
 
+// The cut-and-recompute move for the in-edge (u, v) and copy i of the consumer (see
+// moc_eval_cuts in moccasin.h): copy k of u, the last-starting live copy that covers the
+// consumer's start t, keeps [s_k, last use before p]; the lowest inactive copy j of u takes
+// [p, e_k], p the last position in (s_k, t) where no live copy starts and all inputs of u are
+// held.  Only Eq. (3) among the copies of u and Eq. (7) (when j is copy 0) can change: every
+// consumer that k covered is covered by one of the two pieces, since no live consumer starts
+// in (last use, p], and the new computation finds its inputs by the choice of p.  The profile
+// loses m_u on (last use, p).
 struct Cut {
   int k, j;        // copy of u that is cut, copy of u that becomes active
   int sk, ek;      // interval of copy k as it stands
@@ -936,15 +936,38 @@ __device__ __forceinline__ bool find_cut(const Adj& g, int C, const NbLds& L, co
     if (j < 0 && active_row[u * C + q] == 0) j = q;
   }
   if (k < 0 || j < 0) return false;
-  // the last free position below t, by words of the start bitmap
+  // the last position below t that is free (by words of the start bitmap) and at which every
+  // input of u is held; where an input is missing, the search resumes at the end of the
+  // nearest earlier copy of that input
   int p = -1;
-  for (int pos = (int)t - 1; pos > sk;) {
-    const uint32_t free_bits = ~L.occ1[pos >> 5] & (0xFFFFFFFFu >> (31 - (pos & 31)));
-    if (free_bits) {
-      p = (pos & ~31) + 31 - __clz(free_bits);
+  for (int hi = (int)t - 1; hi > sk;) {
+    int pos = -1;
+    for (int x = hi; x > sk;) {
+      const uint32_t free_bits = ~L.occ1[x >> 5] & (0xFFFFFFFFu >> (31 - (x & 31)));
+      if (free_bits) {
+        pos = (x & ~31) + 31 - __clz(free_bits);
+        break;
+      }
+      x = (x & ~31) - 1;
+    }
+    if (pos <= sk) return false;
+    int resume = pos;
+    for (int y = g.in_ptr[u]; y < g.in_ptr[u + 1]; ++y) {
+      const int w = g.in_idx[y];
+      bool held = false;
+      int below = -1;
+      for (int q = 0; q < C; ++q) {
+        const uint32_t pw = L.packed[w * C + q];
+        held = held || covers1(pw, (uint32_t)pos);
+        if (live_of(pw) && (int)(pw >> 16) < pos) below = max(below, (int)(pw >> 16));
+      }
+      if (!held) resume = min(resume, below);
+    }
+    if (resume == pos) {
+      p = pos;
       break;
     }
-    pos = (pos & ~31) - 1;
+    hi = resume;
   }
   if (p <= sk) return false;
   int last_use = sk;
@@ -982,13 +1005,7 @@ __device__ __forceinline__ bool score_cut(const Adj& g, int C, int T, const NbLd
     }
   }
   vv += after - before;
-  // Eq. (5): the inputs of the new computation at p
-  for (int y = g.in_ptr[u]; y < g.in_ptr[u + 1]; ++y) {
-    const int w = g.in_idx[y];
-    bool cov = false;
-    for (int q = 0; q < C; ++q) cov = cov || covers1(L.packed[w * C + q], (uint32_t)p);
-    vv += cov ? 0 : 1;
-  }
+  // Eq. (5): the inputs of the new computation are held at p by the choice of p
   if (j == 0) --vv;   // Eq. (7)
   int pk = base_peak, at = at_peak.total;
   if (last_use + 1 <= p - 1) {

@@ -1,7 +1,7 @@
 """Pins of the oracle's greedy descent by cuts (orc_search_cuts): what must hold
 of any run, whatever moves it picks -- it is a descent on
-(violations, max(peak, M)), the quantity Phase 1 of Section 2.4 of
-arXiv 2304.14463 minimises; a violation-free start stays violation-free and
+(violations, max(peak, M), positions at the peak), max(peak, M) being the
+quantity Phase 1 of Section 2.4 of arXiv 2304.14463 minimises; a violation-free start stays violation-free and
 still decodes to a valid sequence; every step is the best single cut of the
 table that orc_cuts gives for the candidate at that point."""
 import numpy as np
@@ -19,8 +19,8 @@ def test_descent_from_the_plain_schedule(workloads, cfg):
     s, e, a = (x.copy() for x in w.base())
     start = oracle.evaluate(g, w.budget, C, s, e, a)[0]
     assert start[F["violations"]] == 0 and start[F["peak"]] > w.budget
-    total, fs, fe, fa = oracle.search_cuts(g, w.budget, C, s, e, a, 50)
-    assert 0 < total < 50                                   # it stops by itself
+    total, fs, fe, fa = oracle.search_cuts(g, w.budget, C, s, e, a, 400)
+    assert 0 < total < 400                                  # it stops by itself
     prev = start
     for step in range(1, total + 2):
         # step by step: one call with max_steps = step continues the same path
@@ -30,12 +30,19 @@ def test_descent_from_the_plain_schedule(workloads, cfg):
         if step <= total:
             # the step taken is the first minimum of the table of the candidate before it
             k0, ps, pe, pa = oracle.search_cuts(g, w.budget, C, s, e, a, step - 1)
-            table = oracle.cuts(g, w.budget, C, ps, pe, pa)
+            table = oracle.cuts(g, w.budget, C, ps, pe, pa, with_at_peak=True)
             ok = np.flatnonzero(table[:, 0] >= 0)
-            q = min(ok, key=lambda q: (table[q, 0], table[q, 1], q))
-            assert list(table[q]) == [now[F["violations"]], now[F["peak"]], now[F["duration"]]]
+            q = min(ok, key=lambda q: (table[q, 0], table[q, 1], table[q, 3], q))
+            assert list(table[q][:3]) == [now[F["violations"]], now[F["peak"]], now[F["duration"]]]
             assert now[F["violations"]] == 0
-            assert max(now[F["peak"]], w.budget) < max(prev[F["peak"]], w.budget)
+            # a descent: the peak falls, or it stays and fewer positions reach it
+            _, prof_prev = oracle.profile(g, w.budget, C, ps, pe, pa)
+            _, prof_now = oracle.profile(g, w.budget, C, ts, te, ta)
+            assert prev[F["peak"]] > w.budget
+            assert now[F["peak"]] < prev[F["peak"]] or (
+                now[F["peak"]] == prev[F["peak"]] and
+                (prof_now >= prev[F["peak"]]).sum() < (prof_prev >= prev[F["peak"]]).sum())
+            assert table[q][3] == (prof_now >= prev[F["peak"]]).sum()
             assert now[F["duration"]] > prev[F["duration"]]
             assert int(ta.sum()) == int(a.sum()) + step
             d, _ = oracle.decode(g, C, ts, ta)
@@ -44,10 +51,14 @@ def test_descent_from_the_plain_schedule(workloads, cfg):
             prev = now
         else:
             assert (ts == fs).all() and (te == fe).all() and (ta == fa).all()
-    # where it stops, no single cut lowers max(peak, M) without a violation
-    table = oracle.cuts(g, w.budget, C, fs, fe, fa)
+    # where it stops, it is under the budget or no violation-free cut lowers the peak or the
+    # number of positions that reach it
+    table = oracle.cuts(g, w.budget, C, fs, fe, fa, with_at_peak=True)
     ok = table[:, 0] == 0
-    assert not (np.maximum(table[ok, 1], w.budget) < max(prev[F["peak"]], w.budget)).any()
+    _, prof = oracle.profile(g, w.budget, C, fs, fe, fa)
+    if prev[F["peak"]] > w.budget:
+        assert not (table[ok, 1] < prev[F["peak"]]).any()
+        assert not (table[ok, 3] < (prof >= prev[F["peak"]]).sum()).any()
 
 
 def test_nothing_to_do():
