@@ -182,7 +182,7 @@ int moc_eval_neighbours(const moc_graph* g, int64_t B, const int32_t* starts, co
  * carries) costs it.  Entry [b][k] is what moc_eval_batch returns for base b
  * with active[k] flipped and everything else unchanged.
  *   out   device, moc_toggle_score [B][T], 8-byte aligned
- * This call keeps 4.4 words per copy in LDS: T <= about 9300.  A graph with an
+ * This call keeps 4.7 words per copy in LDS: T <= about 8800.  A graph with an
  * edge (v,v) is not accepted.  B == 0 is a no-op.
  * Errors: MOC_EINVAL, MOC_EDEVICE, MOC_EOVERFLOW (T too large for this call), MOC_EHIP.
  */

@@ -1036,8 +1036,9 @@ TgLayout tg_layout(int T, int n, int m, int max_lds) {
   l.levels = 1;
   while ((2 << (l.levels - 1)) <= l.blocks) ++l.levels;
   // profile, prefix max, suffix max (with sentinels), packed, block maxima, two start bitmaps, the
-  // bitmap of the positions at the peak with its running count per word, scratch
-  const int words = 4 * l.T_pad + 8 + l.levels * l.blocks + 4 * l.bit_words + 8 * kNW + 16;
+  // bitmap of the positions at the peak with its running count per word, scratch, and a queue
+  // of 128 moves per wave
+  const int words = 4 * l.T_pad + 8 + l.levels * l.blocks + 4 * l.bit_words + 8 * kNW + 16 + 2 * kWave * kNW;
   l.adj_off = 0;
   l.bytes = 4 * words;
   // A lane walks its node's edges one after the other: from LDS whenever the lists fit (the
@@ -1071,6 +1072,7 @@ __global__ __launch_bounds__(kNT) void toggles_kernel(GraphView g, int64_t B, co
   int32_t* const peak_before = reinterpret_cast<int32_t*>(peak_bits + lay.bit_words);   // such positions in earlier words
   L.scratch = reinterpret_cast<int32_t*>(peak_before + lay.bit_words);
   int32_t* const counts = L.scratch + 8 * kNW;   // [0] base violations, [1] base duration
+  int32_t* const queue = counts + 16;            // 2 * kWave moves per wave (the descent's sieve)
   const int tid = threadIdx.x;
   const int T = g.T, C = g.C;
   Adj A{g.in_ptr, g.in_idx, g.out_ptr, g.out_idx, reinterpret_cast<const int32_t*>(g.size_dur), 2};
@@ -1193,7 +1195,18 @@ __global__ __launch_bounds__(kNT) void toggles_kernel(GraphView g, int64_t B, co
       const int64_t out_row = b * ((int64_t)g.m * C);
       uint32_t best_viol = 0xFFFFFFFFu, best_peak = 0xFFFFFFFFu;
       int best_at = 0x7FFFFFFF, best_q = -1;
-      for (int q = tid; q < g.m * C; q += kNT) {
+      auto take = [&](uint32_t ov, uint32_t op, int oa, int oq) {
+        if (oq < 0) return;
+        if (best_q < 0 || ov < best_viol ||
+            (ov == best_viol &&
+             (op < best_peak || (op == best_peak && (oa < best_at || (oa == best_at && oq < best_q)))))) {
+          best_viol = ov;
+          best_peak = op;
+          best_at = oa;
+          best_q = oq;
+        }
+      };
+      auto score = [&](int q) {
         const int x = q / C, i = q - x * C;
         const int u = A.in_idx[x];
         const int consumer_copy = (int)(g.edge_pair_c[x] >> 16) + i;
@@ -1204,28 +1217,51 @@ __global__ __launch_bounds__(kNT) void toggles_kernel(GraphView g, int64_t B, co
           sc.violations = vv;
           sc.peak = pk;
           sc.duration = (int64_t)base_dur + g.size_dur[u].y;
-          if (best_q < 0 || (uint32_t)vv < best_viol ||
-              ((uint32_t)vv == best_viol && ((uint32_t)pk < best_peak || ((uint32_t)pk == best_peak && at < best_at)))) {
-            best_viol = (uint32_t)vv;   // a lane meets its moves in rising order: the first of equals stays
-            best_peak = (uint32_t)pk;
-            best_at = at;
-            best_q = q;
-          }
+          take((uint32_t)vv, (uint32_t)pk, at, q);
         }
         if (out) out[out_row + q] = sc;
+      };
+      const int n_moves = g.m * C;
+      if (improving && !out && base_viol == 0) {
+        // A descent step from a candidate without violations can only take a move that lowers
+        // the peak or the number of positions reaching it: one with such a position inside
+        // (s_k, t), which contains the range the move frees.  Each wave sifts its moves by that
+        // test, keeps the survivors in a queue of its own and scores them 64 at a time.
+        const int lane = tid & (kWave - 1), wave = tid / kWave;
+        int32_t* const mine_q = queue + wave * (2 * kWave);
+        int queued = 0;
+        for (int q0 = wave * kWave; q0 < n_moves; q0 += kNT) {
+          const int q = q0 + lane;
+          bool keep = false;
+          if (q < n_moves) {
+            const int x = q / C, i = q - x * C;
+            const int u = A.in_idx[x];
+            const uint32_t consumer = L.packed[(int)(g.edge_pair_c[x] >> 16) + i];
+            if (live_of(consumer)) {
+              const uint32_t t = consumer & 0xFFFFu;
+              int sk = -1;
+              for (int c = 0; c < C; ++c) {
+                const uint32_t pu = L.packed[u * C + c];
+                if (covers1(pu, t)) sk = max(sk, (int)(pu & 0xFFFFu));
+              }
+              keep = sk >= 0 && sk + 1 <= (int)t - 1 && at_peak.within(sk + 1, (int)t - 1) > 0;
+            }
+          }
+          const uint64_t kept = __ballot(keep);
+          if (keep) mine_q[queued + __popcll(kept & ((1ull << lane) - 1))] = q;
+          queued += __popcll(kept);
+          __builtin_amdgcn_wave_barrier();
+          if (queued >= kWave) {
+            queued -= kWave;
+            score(mine_q[queued + lane]);
+            __builtin_amdgcn_wave_barrier();
+          }
+        }
+        if (lane < queued) score(mine_q[lane]);
+      } else {
+        for (int q = tid; q < n_moves; q += kNT) score(q);
       }
       if (out_best) {
-        auto take = [&](uint32_t ov, uint32_t op, int oa, int oq) {
-          if (oq < 0) return;
-          if (best_q < 0 || ov < best_viol ||
-              (ov == best_viol &&
-               (op < best_peak || (op == best_peak && (oa < best_at || (oa == best_at && oq < best_q)))))) {
-            best_viol = ov;
-            best_peak = op;
-            best_at = oa;
-            best_q = oq;
-          }
-        };
 #pragma unroll
         for (int off = kWave / 2; off > 0; off >>= 1)
           take(__shfl_xor(best_viol, off), __shfl_xor(best_peak, off), __shfl_xor(best_at, off),
