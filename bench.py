@@ -189,12 +189,15 @@ def measure_neighbours(moc, steps, warmup):
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) * 1e3
     ev1 = moc.results_to_numpy(moc.moc_eval_batch(gh, ws, we, wa))
+    # what comes out is still a schedule: decode every walker and cost the sequence on its own terms
+    cert = moc.results_to_numpy(moc.moc_decode_batch(gh, ws, wa, want_seq=False)[0], moc.DECODE_RESULT_DTYPE)
+    certified = bool(((cert["status"] == 1) & (cert["duration"] == ev1["duration"]) & (cert["peak"] <= ev1["peak"])).all())
     gap0 = (ev0["peak"] - w.budget).clip(min=0).astype(float)
     gap1 = (ev1["peak"] - w.budget).clip(min=0).astype(float)
     out["search_cuts"] = {
         "steps": search_steps, "ms_total": ms, "ms_per_step": ms / search_steps,
         "walkers": w.B, "mean_moves_applied": float(applied.float().mean()),
-        "violations_after": int(ev1["violations"].max()),
+        "violations_after": int(ev1["violations"].max()), "decoded_and_certified": certified,
         "mean_gap_to_budget_closed": float(1.0 - gap1.sum() / max(gap0.sum(), 1.0)),
         "frac_feasible_before": float(ev0["feasible"].mean()), "frac_feasible_after": float(ev1["feasible"].mean()),
         "mean_duration_increase_pct": float(100.0 * (ev1["duration"] / ev0["duration"] - 1.0).mean())}

@@ -271,6 +271,14 @@ def test_search_cuts_full_batch(moc, workloads):
     better = (key1[:, 0] < key0[:, 0]) | ((key1[:, 0] == key0[:, 0]) & (key1[:, 1] < key0[:, 1]))
     assert (better == (steps > 0)).all()
     assert (after["duration"] > before["duration"])[steps > 0].all()
+    # walkers that started without violations still stand for valid sequences, one step longer
+    # per cut, costed by the decoder at the evaluator's duration and at most its peak
+    dec = moc.results_to_numpy(moc.moc_decode_batch(gh, ds, da, want_seq=False)[0], moc.DECODE_RESULT_DTYPE)
+    clean = before["violations"] == 0
+    assert clean.sum() > 100 and (dec["status"][clean] == 1).all()
+    assert (dec["length"][clean] == (n_active.cpu().numpy() + steps)[clean]).all()
+    assert (dec["duration"][clean] == after["duration"][clean]).all()
+    assert (dec["peak"][clean] <= after["peak"][clean]).all()
     want_steps, ws, we, wa = oracle.search_cuts(w.graph, w.budget, w.C, s0, e0, a0, 3)
     assert steps[5] == want_steps
     assert (da[5].cpu().numpy() == wa).all() and (ds[5].cpu().numpy() == ws).all() and (de[5].cpu().numpy() == we).all()
