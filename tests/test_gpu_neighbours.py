@@ -200,7 +200,7 @@ def test_neighbours_argument_errors(moc, workloads):
         moc.moc_eval_neighbours(gh, z, z, torch.zeros((1, n), dtype=torch.uint8, device="cuda"), 2)
     assert err.value.code == -2
     gh.free()
-    # the toggles keep four words per copy: T = 10200 is too much for them
+    # the toggles keep 4.7 words per copy: T = 10200 is too much for them
     n = 10200
     g = graph_from_edges(n, [(i, i + 1) for i in range(n - 1)], np.ones(n), np.ones(n))
     gh = moc.moc_graph_upload(n, g.in_ptr, g.in_idx, g.size, g.dur, 10, 1)
