@@ -5,7 +5,8 @@ A step is one pass of the whole hot path (moc_eval_batch: load, structural
 checks, start collisions, memory profile, peak, precedence, objective, store)
 over one resident batch of synthetic candidates.  Default workload: the
 n=5000, C=3, B=262144 configuration (35.4 GB of candidates resident in HBM);
-the n=442 configuration is timed as well and reported under "also".
+the n=442 and n=1000 configurations are timed as well and reported under
+"also" and "also_n1000".
 
 Prints ONE JSON line.  `value` is candidates evaluated per second with inputs
 resident in HBM; `roofline` prices the evaluation kernel against the 8 TB/s
@@ -62,7 +63,7 @@ def parse():
     ap.add_argument("--workload", type=int, default=4, choices=[0, 1, 2, 3, 4])
     ap.add_argument("--batch", type=int, default=None, help="override the workload's batch size")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-also", action="store_true", help="skip the secondary (n=442) measurement")
+    ap.add_argument("--no-also", action="store_true", help="skip the secondary (n=442, n=1000) measurements")
     ap.add_argument("--no-neighbours", action="store_true", help="skip the neighbourhood (n=2000) measurement")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run one 1 GiB device copy first (reference dispatch for the HBM byte counters)")
@@ -307,6 +308,15 @@ def main():
                         "kernel_ms_avg": msk2, "kernel_ms_min": mskmin2, "achieved_GBs": gbs2,
                         "frac_of_hbm_peak": gbs2 / HBM_PEAK_GBS}
         gh2.free()
+        del cand2
+        torch.cuda.empty_cache()
+        # the smallest configuration with n >= 1000: training-shaped graph, B = 65536
+        w3, gh3, cand3, res3, info3, ms3, msk3, mskmin3, gbs3 = measure(moc, 2, max(args.steps, 50), args.warmup)
+        line["also_n1000"] = {"config": info3, "value": w3.B / (ms3 * 1e-3), "unit": "candidates/s",
+                              "ms_per_step": ms3, "kernel_ms_avg": msk3, "kernel_ms_min": mskmin3,
+                              "achieved_GBs": gbs3, "frac_of_hbm_peak": gbs3 / HBM_PEAK_GBS}
+        gh3.free()
+        del cand3
     if not args.no_neighbours:
         torch.cuda.empty_cache()
         line["neighbours"] = measure_neighbours(moc, max(3, args.steps // 4), 1)
