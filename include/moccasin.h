@@ -248,6 +248,28 @@ int moc_search_cuts(const moc_graph* g, int64_t B, int32_t* starts, int32_t* end
                     int32_t max_steps, moc_best_move* work_best, int32_t* out_steps, void* hip_stream);
 
 /*
+ * Greedy descent by single-field moves, every candidate on its own: the moves
+ * of moc_eval_neighbours, which cost no duration (they re-time computations
+ * and retentions).  Repeats max_steps times: evaluate the candidate, find its
+ * best move as moc_eval_neighbours does, and apply it in place if it lowers
+ * (violations, max(peak, M), peak) lexicographically.  A candidate whose best
+ * move does not stays as it is from then on.
+ *   starts, ends    device, [B][T], edited in place; active is only read
+ *   R               radius of the moves, 1 <= R <= 32
+ *   work_results    device, moc_result [B], 8-byte aligned: workspace
+ *   work_best       device, moc_best_move [B], 8-byte aligned: workspace
+ *   out_steps       device, int32 [B]: number of moves applied
+ * Queues 3 * max_steps + 1 kernels on the stream and returns; allocates
+ * nothing.  Limits as moc_eval_neighbours; B <= 2^31 - 1.  If a launch inside
+ * the loop is refused (more than 16 evaluations in flight on the handle), its
+ * error is returned and the steps queued so far still run.
+ * Errors: MOC_EINVAL, MOC_EDEVICE, MOC_EOVERFLOW, MOC_EHIP.
+ */
+int moc_search_moves(const moc_graph* g, int64_t B, int32_t* starts, int32_t* ends, const uint8_t* active,
+                     int32_t R, int32_t max_steps, moc_result* work_results, moc_best_move* work_best,
+                     int32_t* out_steps, void* hip_stream);
+
+/*
  * Turn B candidates into the rematerialisation sequences they stand for and
  * cost each sequence on its own terms (Section 2: the start of an active
  * interval is the event at which its node is computed; Section 1, problem

@@ -181,6 +181,29 @@ def search_cuts(g, budget, C, starts, ends, active, max_steps, T=None):
     return int(steps), s, e, a
 
 
+def search_moves(g, budget, C, starts, ends, active, R, max_steps, T=None):
+    """Greedy descent by single-field moves on one candidate, out of the oracle's own pieces:
+    at every step the best move of neighbours() is applied if it lowers
+    (violations, max(peak, M), peak) against evaluate() of the candidate as it stands.
+    Returns (steps applied, s, e)."""
+    K = g.n * C
+    T = K if T is None else T
+    s = np.array(starts, dtype=np.int32).reshape(K).copy()
+    e = np.array(ends, dtype=np.int32).reshape(K).copy()
+    a = np.array(active, dtype=np.uint8).reshape(K)
+    applied = 0
+    for _ in range(max_steps):
+        base = evaluate(g, budget, C, s, e, a, T=T)[0]
+        v0, p0 = int(base[FIELDS.index("violations")]), int(base[FIELDS.index("peak")])
+        _, (q, v1, p1) = neighbours(g, budget, C, s, e, a, R, T=T)
+        if q < 0 or not ((v1, max(p1, budget), p1) < (v0, max(p0, budget), p0)):
+            break
+        d, field, k = q % (2 * R), (q // (2 * R)) % 2, q // (4 * R)
+        (s if field == 0 else e)[k] += d - R if d < R else d - R + 1
+        applied += 1
+    return applied, s, e
+
+
 def decode(g, C, starts, active, T=None):
     """Sequences the candidates stand for (active copies in start order) and their own
     liveness footprint.  Returns (int64 [B][4] = status, length, peak, duration;

@@ -1523,3 +1523,57 @@ extern "C" int moc_eval_cuts(const moc_graph* g, int64_t B, const int32_t* start
   MOC_HIP(hipGetLastError());
   return MOC_OK;
 }
+
+namespace {
+
+// Applies to each base the single-field move its moc_best_move names if that move lowers
+// (violations, max(peak, M), peak) against the base's own result, and counts it.
+__global__ void apply_moves_kernel(int64_t B, int T, int R, int64_t budget, int32_t* starts, int32_t* ends,
+                                   const moc_best_move* best, const moc_result* base, int32_t* steps) {
+  const int64_t b = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+  if (b >= B) return;
+  const int q = best[b].move;
+  if (q < 0) return;
+  const int64_t v1 = best[b].violations, p1 = best[b].peak, v0 = base[b].violations, p0 = base[b].peak;
+  const int64_t m1 = max(p1, budget), m0 = max(p0, budget);
+  if (!(v1 < v0 || (v1 == v0 && (m1 < m0 || (m1 == m0 && p1 < p0))))) return;
+  const int d = q % (2 * R), field = (q / (2 * R)) & 1, k = q / (4 * R);
+  const int delta = d < R ? d - R : d - R + 1;
+  (field == 0 ? starts : ends)[b * T + k] += delta;
+  steps[b] += 1;
+}
+
+}  // namespace
+
+extern "C" int moc_search_moves(const moc_graph* g, int64_t B, int32_t* starts, int32_t* ends, const uint8_t* active,
+                                int32_t R, int32_t max_steps, moc_result* work_results, moc_best_move* work_best,
+                                int32_t* out_steps, void* hip_stream) {
+  if (!g || B < 0 || max_steps < 0 || R < 1 || R > 32) return MOC_EINVAL;
+  if (B == 0) return MOC_OK;
+  if (!starts || !ends || !active || !work_results || !work_best || !out_steps) return MOC_EINVAL;
+  if ((((uintptr_t)starts | (uintptr_t)ends | (uintptr_t)out_steps) & 3) ||
+      (((uintptr_t)work_best | (uintptr_t)work_results) & 7))
+    return MOC_EINVAL;
+  if (B > 0x7FFFFFFFll) return MOC_EINVAL;
+  int dev = -1;
+  MOC_HIP(hipGetDevice(&dev));
+  if (dev != g->device) return MOC_EDEVICE;
+  if (g->has_self_loop) return MOC_EINVAL;
+  const NbLayout lay = nb_layout(g->view.T, g->view.n, g->view.m, g->max_lds);
+  if (lay.bytes > g->max_lds) return MOC_EOVERFLOW;
+  if ((int64_t)g->view.T * 4 * R * 8 > 0xFFFFFFFFll) return MOC_EOVERFLOW;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const unsigned blocks = (unsigned)((B + 255) / 256);
+  hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, stream, out_steps, B);
+  for (int step = 0; step < max_steps; ++step) {
+    int rc = moc_eval_batch(g, B, starts, ends, active, work_results, hip_stream);
+    if (rc != MOC_OK) return rc;
+    rc = moc_eval_neighbours(g, B, starts, ends, active, R, nullptr, work_best, hip_stream);
+    if (rc != MOC_OK) return rc;
+    hipLaunchKernelGGL(apply_moves_kernel, dim3(blocks), dim3(256), 0, stream, B, g->view.T, (int)R, g->view.budget,
+                       starts, ends, work_best, work_results, out_steps);
+  }
+  MOC_HIP(hipGetLastError());
+  return MOC_OK;
+}
+

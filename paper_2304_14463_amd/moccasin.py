@@ -26,7 +26,7 @@ TOGGLE_SCORE_DTYPE = np.dtype([("violations", "<i4"), ("peak", "<i4"), ("duratio
 DECODE_RESULT_DTYPE = np.dtype([("status", "<i4"), ("length", "<i4"), ("peak", "<i8"), ("duration", "<i8")])
 
 EXPORTS = ("moc_graph_upload", "moc_graph_info", "moc_eval_batch", "moc_eval_neighbours", "moc_eval_toggles",
-           "moc_eval_cuts", "moc_search_cuts", "moc_decode_batch", "moc_graph_free", "moc_strerror", "moc_last_hip_error")
+           "moc_eval_cuts", "moc_search_cuts", "moc_search_moves", "moc_decode_batch", "moc_graph_free", "moc_strerror", "moc_last_hip_error")
 
 
 class MoccasinError(RuntimeError):
@@ -59,6 +59,8 @@ def lib():
         L.moc_eval_cuts.restype = ctypes.c_int
         L.moc_search_cuts.argtypes = [VP, I64, VP, VP, VP, I32, VP, VP, VP]
         L.moc_search_cuts.restype = ctypes.c_int
+        L.moc_search_moves.argtypes = [VP, I64, VP, VP, VP, I32, I32, VP, VP, VP, VP]
+        L.moc_search_moves.restype = ctypes.c_int
         L.moc_decode_batch.argtypes = [VP, I64, VP, VP, VP, VP, VP]
         L.moc_decode_batch.restype = ctypes.c_int
         L.moc_graph_free.argtypes = [VP]
@@ -205,6 +207,23 @@ def moc_search_cuts(g: Graph, starts, ends, active, max_steps, work_best=None, o
     code = lib().moc_search_cuts(g._h, B, ps, pe, pa, int(max_steps), ctypes.c_void_p(work_best.data_ptr()),
                                  ctypes.c_void_p(out_steps.data_ptr()), _stream_handle(stream))
     _check(code, "moc_search_cuts")
+    return out_steps
+
+
+def moc_search_moves(g: Graph, starts, ends, active, R, max_steps, out_steps=None, stream=None):
+    """Greedy descent by single-field start/end moves of radius R, in place.  Returns the int32
+    CUDA tensor [B] of moves applied per candidate."""
+    import torch
+    B = starts.numel() // g.T if g.T else 0
+    ps, pe, pa = _cand_ptrs(g, B, starts, ends, active)
+    work_results = torch.empty((B, RESULT_DTYPE.itemsize), dtype=torch.uint8, device=starts.device)
+    work_best = torch.empty((B, BEST_MOVE_DTYPE.itemsize), dtype=torch.uint8, device=starts.device)
+    if out_steps is None:
+        out_steps = torch.empty((B,), dtype=torch.int32, device=starts.device)
+    code = lib().moc_search_moves(g._h, B, ps, pe, pa, int(R), int(max_steps),
+                                  ctypes.c_void_p(work_results.data_ptr()), ctypes.c_void_p(work_best.data_ptr()),
+                                  ctypes.c_void_p(out_steps.data_ptr()), _stream_handle(stream))
+    _check(code, "moc_search_moves")
     return out_steps
 
 

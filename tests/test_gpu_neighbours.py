@@ -344,3 +344,71 @@ def test_neighbours_workload_wide_radius(moc, workloads):
             q = int(ok[np.lexsort((ok, p[ok], v[ok]))[0]])
             assert (int(ob[b0 + j]["move"]), int(ob[b0 + j]["violations"]), int(ob[b0 + j]["peak"])) == (q, v[q], p[q])
     gh.free()
+
+
+@pytest.mark.parametrize("cfg,count,R,steps", [(0, 40, 8, 6), (0, 12, 3, 12), (1, 3, 8, 3)])
+def test_search_moves_follows_the_oracle(moc, workloads, cfg, count, R, steps):
+    """Greedy descent by single-field moves: after the same number of steps the starts and ends
+    are what the oracle's descent (evaluate + neighbours + apply, step by step) leaves."""
+    w = workloads(cfg)
+    s, e, a = w.candidates(0, count)
+    s0, e0, a0 = w.base()
+    s[0], e[0], a[0] = s0, e0, a0
+    gh = upload(moc, w)
+    ds, de, da = to_dev(s, e, a)
+    n_steps = moc.moc_search_moves(gh, ds, de, da, R, steps).cpu().numpy()
+    gs, ge = ds.cpu().numpy(), de.cpu().numpy()
+    assert (da.cpu().numpy() == a).all()
+    for b in range(count):
+        k, ws, we = oracle.search_moves(w.graph, w.budget, w.C, s[b], e[b], a[b], R, steps)
+        assert n_steps[b] == k, b
+        assert (gs[b] == ws).all() and (ge[b] == we).all(), b
+    assert n_steps.sum() > 0
+    gh.free()
+
+
+def test_search_moves_full_batch(moc, workloads):
+    """n=2000, C=2, all 8192 bases, 4 steps of radius 8: nobody gets worse, whoever moved got
+    better in (violations, max(peak, M), peak), durations stay."""
+    import torch
+    from paper_2304_14463_amd.inputs import DeviceWorkload
+    w = workloads(3)
+    gh = upload(moc, w)
+    ds, de, da = DeviceWorkload(w).candidates()
+    before = moc.results_to_numpy(moc.moc_eval_batch(gh, ds, de, da))
+    steps = moc.moc_search_moves(gh, ds, de, da, w.R, 4).cpu().numpy()
+    after = moc.results_to_numpy(moc.moc_eval_batch(gh, ds, de, da))
+    key = lambda r: list(zip(r["violations"].tolist(), np.maximum(r["peak"], w.budget).tolist(), r["peak"].tolist()))
+    k0, k1 = key(before), key(after)
+    assert all((k1[b] < k0[b]) == (steps[b] > 0) and k1[b] <= k0[b] for b in range(w.B))
+    assert (after["duration"] == before["duration"]).all()
+    assert steps.max() == 4 and (steps > 0).mean() > 0.5
+    gh.free()
+
+
+def test_search_moves_rejects_bad_arguments(moc):
+    import ctypes
+    import torch
+    from paper_2304_14463_amd.inputs import graph_from_edges
+    g = graph_from_edges(3, [(0, 1), (1, 2)], [1, 1, 1], [1, 1, 1])
+    gh = moc.moc_graph_upload(3, g.in_ptr, g.in_idx, g.size, g.dur, 1, 2)
+    s = torch.zeros((2, 6), dtype=torch.int32, device="cuda")
+    e = torch.zeros((2, 6), dtype=torch.int32, device="cuda")
+    a = torch.zeros((2, 6), dtype=torch.uint8, device="cuda")
+    res = torch.zeros((2, 24), dtype=torch.uint8, device="cuda")
+    best = torch.zeros((2, 16), dtype=torch.uint8, device="cuda")
+    steps = torch.full((2,), 9, dtype=torch.int32, device="cuda")
+    L = moc.lib()
+    vp = lambda t, off=0: ctypes.c_void_p(t.data_ptr() + off)
+    call = lambda R, n, r, b, st: L.moc_search_moves(gh._h, 2, vp(s), vp(e), vp(a), R, n, r, b, st, None)
+    assert call(0, 1, vp(res), vp(best), vp(steps)) == -1
+    assert call(33, 1, vp(res), vp(best), vp(steps)) == -1
+    assert call(2, -1, vp(res), vp(best), vp(steps)) == -1
+    assert call(2, 1, None, vp(best), vp(steps)) == -1
+    assert call(2, 1, vp(res), None, vp(steps)) == -1
+    assert call(2, 1, vp(res), vp(best), None) == -1
+    assert call(2, 1, vp(res, 4), vp(best), vp(steps)) == -1
+    assert (steps.cpu().numpy() == 9).all()
+    assert call(2, 0, vp(res), vp(best), vp(steps)) == 0 and (steps.cpu().numpy() == 0).all()
+    assert L.moc_search_moves(gh._h, 0, None, None, None, 2, 1, None, None, None, None) == 0
+    gh.free()

@@ -35,6 +35,7 @@ def test_library_exports_every_declared_symbol():
     assert lib.moc_decode_batch(None, 0, None, None, None, None, None) == -1
     assert lib.moc_eval_cuts(None, 0, None, None, None, None, None, None) == -1
     assert lib.moc_search_cuts(None, 0, None, None, None, 1, None, None, None) == -1
+    assert lib.moc_search_moves(None, 0, None, None, None, 1, 1, None, None, None, None) == -1
     out = ctypes.c_void_p(1)
     assert lib.moc_graph_upload(0, None, None, None, None, 0, 1, ctypes.byref(out)) == -1 and not out.value
 
