@@ -202,6 +202,17 @@ def measure_neighbours(moc, steps, warmup):
         "mean_gap_to_budget_closed": float(1.0 - gap1.sum() / max(gap0.sum(), 1.0)),
         "frac_feasible_before": float(ev0["feasible"].mean()), "frac_feasible_after": float(ev1["feasible"].mean()),
         "mean_duration_increase_pct": float(100.0 * (ev1["duration"] / ev0["duration"] - 1.0).mean())}
+    # the same walkers, descent by single-field moves (no duration at stake)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    moved = moc.moc_search_moves(gh, ws, we, wa, w.R, search_steps)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3
+    ev2 = moc.results_to_numpy(moc.moc_eval_batch(gh, ws, we, wa))
+    out["search_moves"] = {"steps": search_steps, "R": w.R, "ms_total": ms, "ms_per_step": ms / search_steps,
+                           "walkers": w.B, "mean_moves_applied": float(moved.float().mean()),
+                           "violations_after": int(ev2["violations"].max()),
+                           "mean_peak_change_pct": float(100.0 * (ev2["peak"] / ev1["peak"] - 1.0).mean())}
     del ws, we, wa
     # back to sequences: every base decoded and costed, sequences written out
     # -- of the candidates a search would decode: the violation-free bases, repeated to B rows
