@@ -1,5 +1,5 @@
 """Randomised parity sweep: moc_eval_cuts (table and best move), moc_eval_toggles,
-moc_search_cuts and moc_decode_batch against the oracle on a few hundred small
+moc_search_cuts, moc_search_moves and moc_decode_batch against the oracle on a few hundred small
 random graphs with 1 to 4 copies per node, orderly and wild candidates."""
 import numpy as np
 import pytest
@@ -57,6 +57,14 @@ def test_sweep(moc, first):
             assert steps[b] == k, (seed, "search", b)
             assert (wa[b].cpu().numpy() == a2).all() and (ws[b].cpu().numpy() == s2).all(), (seed, "search", b)
             assert (we[b].cpu().numpy() == e2).all(), (seed, "search", b)
+        if n < 70:
+            R = int(rng.integers(1, 6))
+            ws, we = ds[:3].clone(), de[:3].clone()
+            steps = moc.moc_search_moves(gh, ws, we, da[:3].contiguous(), R, 3).cpu().numpy()
+            for b in range(3):
+                k, s2, e2 = oracle.search_moves(g, budget, C, s[b], e[b], a[b], R, 3)
+                assert steps[b] == k, (seed, "moves", b)
+                assert (ws[b].cpu().numpy() == s2).all() and (we[b].cpu().numpy() == e2).all(), (seed, "moves", b)
         for cs, ca in ((td.orderly_candidates(rng, g, C, 8)), (s, a)):
             want, want_seq = oracle.decode(g, C, cs, ca)
             got, seq = td.gpu_decode(moc, gh, cs, ca)
