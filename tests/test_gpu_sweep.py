@@ -1,6 +1,7 @@
-"""Randomised parity sweep: moc_eval_cuts (table and best move), moc_eval_toggles,
-moc_search_cuts, moc_search_moves and moc_decode_batch against the oracle on a few hundred small
-random graphs with 1 to 4 copies per node, orderly and wild candidates."""
+"""Randomised parity sweeps: moc_eval_batch, moc_eval_neighbours, moc_eval_cuts
+(table and best move), moc_eval_toggles, moc_search_cuts, moc_search_moves and
+moc_decode_batch against the oracle on a few hundred small random graphs with
+1 to 5 copies per node, orderly and wild candidates."""
 import numpy as np
 import pytest
 
@@ -69,4 +70,39 @@ def test_sweep(moc, first):
             want, want_seq = oracle.decode(g, C, cs, ca)
             got, seq = td.gpu_decode(moc, gh, cs, ca)
             td.assert_same(got, seq, want, want_seq, f"seed {seed} decode")
+        gh.free()
+
+
+def test_sweep_evaluator_and_neighbourhood(moc):
+    """moc_eval_batch and moc_eval_neighbours (table, best move, best move alone) on 150 random
+    graphs with 1 to 5 copies per node, random batch sizes, radii up to 32."""
+    import test_gpu_eval as te
+    import test_gpu_neighbours as tn
+    from helpers import assert_results_equal
+    from paper_2304_14463_amd.inputs import graph_from_edges
+    for seed in range(150):
+        rng = np.random.default_rng(10_000_000 + seed)
+        n = int(rng.integers(1, 90 if seed % 8 else 700))
+        C = int(rng.integers(1, 6))
+        edges = set()
+        for v in range(1, n):
+            for u in rng.integers(0, v, size=rng.integers(0, 4)):
+                edges.add((int(u), v))
+        g = graph_from_edges(n, sorted(edges), rng.integers(0, 1000, n), rng.integers(0, 50, n))
+        T, B = n * C, int(rng.integers(1, 40))
+        s, e, a = te.random_candidates(rng, B, n, C, T, wild=bool(seed % 2))
+        budget = int(g.size.sum() * rng.random())
+        gh = moc.moc_graph_upload(n, g.in_ptr, g.in_idx, g.size, g.dur, budget, C)
+        ref = oracle.evaluate(g, budget, C, s, e, a)
+        assert_results_equal(te.run_eval(moc, gh, s, e, a), ref, f"seed {seed} n={n} C={C}")
+        if n < 90:
+            R = int(rng.integers(1, 33 if seed % 5 == 0 else 9))
+            nb = min(B, 3)
+            om, ob = tn.gpu_neighbours(moc, gh, s[:nb], e[:nb], a[:nb], R)
+            _, alone = tn.gpu_neighbours(moc, gh, s[:nb], e[:nb], a[:nb], R, moves=False)
+            for b in range(nb):
+                scores, bm = oracle.neighbours(g, budget, C, s[b], e[b], a[b], R)
+                assert (om[b]["violations"] == scores[:, 0]).all() and (om[b]["peak"] == scores[:, 1]).all(), (seed, b)
+                assert (int(ob[b]["move"]), int(ob[b]["violations"]), int(ob[b]["peak"])) == bm, (seed, b)
+                assert (int(alone[b]["move"]), int(alone[b]["violations"]), int(alone[b]["peak"])) == bm, (seed, b)
         gh.free()
