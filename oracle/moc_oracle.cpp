@@ -25,9 +25,12 @@
 // hand-counted single-violation cases, closed forms, exhaustive enumeration
 // of rematerialisation sequences on tiny DAGs against an independent liveness
 // simulation (moc_bruteforce.cpp), the no-remat liveness invariant.  The
-// neighbourhood scorer is pinned by definition (full re-evaluation through
-// the pinned evaluator); the move set itself is this library's, not the
-// paper's.
+// neighbourhood scorer re-evaluates every move through the pinned evaluator;
+// its numbering of the moves, the rule for moves that do not apply and the
+// order of the best move are pinned on hand-counted cases and against
+// candidates edited by the test itself (tests/test_oracle_neighbours.py, as
+// is the descent by such moves put together in oracle/__init__.py); the move
+// set itself is this library's, not the paper's.
 #include <cstdint>
 #include <cstring>
 #include <vector>
