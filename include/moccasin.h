@@ -44,15 +44,22 @@
  * current at every later call with that graph.
  *
  * Concurrency.  A graph handle may be used from several host threads and
- * streams at once.  The handle owns 16 sets of device-side work counters,
- * which moc_eval_batch launches take in turn and leave at zero: at most 16
- * moc_eval_batch launches on one handle may be in flight on the device at the
- * same time (launches on one stream follow each other and count as one).
- * A launch that is aborted (device reset) leaves the handle unusable.
+ * streams at once.  The handle owns 16 sets of device-side work counters for
+ * moc_eval_batch; a set belongs to a stream (launches on one stream follow
+ * each other and share it), every launch leaves its set at zero.  The first 16
+ * distinct streams used with a handle get a set each; launches on any further
+ * stream are split statically over the workgroups instead, which touches no
+ * counters and gives the same results, up to a third slower on small graphs.
+ * A launch that is aborted (device reset) leaves the handle unusable: free it
+ * and upload the graph again.
  *
  * Errors.  Every function that returns int returns MOC_OK (0) or a negative
- * code; nothing is queued on the stream when an error is returned.  Contents
- * of a candidate are never an error: bad values are violations.
+ * code.  Arguments are checked before anything is queued: with MOC_EINVAL,
+ * MOC_EDEVICE or MOC_EOVERFLOW nothing has been queued on the stream.  MOC_EHIP
+ * reports a failed HIP runtime call; from the calls that queue several kernels
+ * (moc_search_cuts, moc_search_moves) the kernels queued before the failing
+ * one still run.  Contents of a candidate are never an error: bad values are
+ * violations.
  */
 #ifndef MOCCASIN_H
 #define MOCCASIN_H
@@ -260,9 +267,7 @@ int moc_search_cuts(const moc_graph* g, int64_t B, int32_t* starts, int32_t* end
  *   work_best       device, moc_best_move [B], 8-byte aligned: workspace
  *   out_steps       device, int32 [B]: number of moves applied
  * Queues 3 * max_steps + 1 kernels on the stream and returns; allocates
- * nothing.  Limits as moc_eval_neighbours; B <= 2^31 - 1.  If a launch inside
- * the loop is refused (more than 16 evaluations in flight on the handle), its
- * error is returned and the steps queued so far still run.
+ * nothing.  Limits as moc_eval_neighbours; B <= 2^31 - 1.
  * Errors: MOC_EINVAL, MOC_EDEVICE, MOC_EOVERFLOW, MOC_EHIP.
  */
 int moc_search_moves(const moc_graph* g, int64_t B, int32_t* starts, int32_t* ends, const uint8_t* active,

@@ -11,6 +11,7 @@ import glob
 import os
 import subprocess
 import sys
+import tempfile
 
 PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
@@ -25,8 +26,7 @@ HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
                "-Wall", "-Wno-unused-result"]
 
 
-def _hipcc(out, sources, extra=()):
-    cmd = ["hipcc", *HIPCC_FLAGS, *extra, "-o", out, *sources]
+def _run(cmd):
     proc = subprocess.run(cmd, capture_output=True, text=True)
     noise = "packed-fp32-ops' is not a recognized feature"
     err = "\n".join(l for l in proc.stderr.splitlines() if noise not in l)
@@ -34,6 +34,17 @@ def _hipcc(out, sources, extra=()):
         raise RuntimeError(f"hipcc failed ({' '.join(cmd)}):\n{err}")
     if err.strip():
         sys.stderr.write(err + "\n")
+
+
+def _hipcc(out, sources, extra=()):
+    """One object file per source, compiled side by side, then linked."""
+    from concurrent.futures import ThreadPoolExecutor
+    flags = [f for f in HIPCC_FLAGS if f != "-shared"]
+    with tempfile.TemporaryDirectory() as tmp:
+        objs = [os.path.join(tmp, os.path.basename(s) + ".o") for s in sources]
+        with ThreadPoolExecutor(min(len(sources), os.cpu_count() or 1, 16)) as ex:
+            list(ex.map(lambda so: _run(["hipcc", *flags, *extra, "-c", "-o", so[1], so[0]]), zip(sources, objs)))
+        _run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out, *objs])
     return out
 
 

@@ -265,11 +265,9 @@ extern "C" int moc_decode_batch(const moc_graph* g, int64_t B, const int32_t* st
   if (dev != g->device) return MOC_EDEVICE;
   const DcLayout lay = dc_layout(g->view.T);
   if (lay.bytes > g->max_lds) return MOC_EOVERFLOW;
-  MOC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(decode_kernel),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, lay.bytes));
   int per_cu = 0;
-  MOC_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel, kNT, lay.bytes));
-  if (per_cu < 1) per_cu = 1;
+  if (const int rc = moc_kernel_occupancy(g, reinterpret_cast<const void*>(decode_kernel), kNT, lay.bytes, false, &per_cu))
+    return rc;
   const int64_t resident = (int64_t)per_cu * g->num_cu;
   const unsigned grid = (unsigned)(B < resident ? B : resident);
   hipLaunchKernelGGL(decode_kernel, dim3(grid), dim3(kNT), lay.bytes, static_cast<hipStream_t>(hip_stream), g->view, B,

@@ -843,37 +843,33 @@ __global__ __launch_bounds__(NT) void eval_batch_general_kernel(GraphView g, int
 }
 
 // ------------------------------------------------------------------ host side
+// Where a launch takes its work counters from: the graph handle's set for the stream, or a set
+// the caller names (`fixed`).
+struct TicketSource {
+  uint32_t* fixed;
+};
+
 template <typename K>
 int launch_kernel(K kern, int nt, const moc_graph* g, const LdsLayout& lay, int64_t B, const int32_t* starts,
-                  const int32_t* ends, const uint8_t* active, moc_result* out, hipStream_t stream, int which) {
+                  const int32_t* ends, const uint8_t* active, moc_result* out, hipStream_t stream,
+                  const TicketSource& src) {
   if (lay.bytes > g->max_lds) return MOC_EOVERFLOW;
-  // Once per kernel and device: nothing may be placed before the dynamic LDS segment (the
-  // kernels address the node records from LDS address 0), and the kernel may use all the LDS
-  // a workgroup can have.
-  static std::atomic<uint64_t> prepared{0};   // one per instantiation, i.e. per kernel; bit = device
-  const uint64_t dev_bit = (uint64_t)1 << (g->device & 63);
-  if (!(prepared.load(std::memory_order_acquire) & dev_bit)) {
-    hipFuncAttributes attr;
-    MOC_HIP(hipFuncGetAttributes(&attr, reinterpret_cast<const void*>(kern)));
-    if (attr.sharedSizeBytes != 0) return MOC_EINVAL;
-    MOC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                g->max_lds));
-    prepared.fetch_or(dev_bit, std::memory_order_release);
-  }
-  // Workgroups of this kernel and graph that a compute unit holds: asked once per handle.
-  int per_cu = g->per_cu[which].load(std::memory_order_relaxed);
-  if (per_cu == 0) {
-    MOC_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, nt, lay.bytes));
-    if (per_cu < 1) per_cu = 1;
-    g->per_cu[which].store(per_cu, std::memory_order_relaxed);
-  }
+  // Nothing may be placed before the dynamic LDS segment: the kernels address the node
+  // records from LDS address 0.
+  int per_cu = 0;
+  const int rc = moc_kernel_occupancy(g, reinterpret_cast<const void*>(kern), nt, lay.bytes, true, &per_cu);
+  if (rc != MOC_OK) return rc;
   const int64_t resident = (int64_t)per_cu * g->num_cu;
   const unsigned grid = (unsigned)(B < resident ? B : resident);
-  // One set of counters per launch in flight (see moc_graph::tickets); about 16 workgroups share a
-  // counter.  A batch of fewer than 8 candidates per workgroup is split statically (groups = 0).
-  uint32_t* ticket = g->tickets + (size_t)(g->launch_seq.fetch_add(1u) % kTicketSlots) * kTicketSlotWords;
+  // About 16 workgroups share a counter.  A batch of fewer than 8 candidates per workgroup is
+  // split statically (groups = 0), and so is a launch for which no set of counters is free.
   int groups = grid / 16 < 1 ? 1 : grid / 16 > kTicketGroups ? kTicketGroups : (int)(grid / 16);
   if (B < (int64_t)8 * grid) groups = 0;
+  uint32_t* ticket = nullptr;
+  if (groups != 0) {
+    ticket = src.fixed ? src.fixed : moc_ticket_set(g, stream);
+    if (!ticket) groups = 0;
+  }
   hipLaunchKernelGGL(kern, dim3(grid), dim3(nt), lay.bytes, stream, g->view, B, starts, ends, active, out, lay,
                      ticket, groups);
   MOC_HIP(hipGetLastError());
@@ -882,12 +878,12 @@ int launch_kernel(K kern, int nt, const moc_graph* g, const LdsLayout& lay, int6
 
 template <int NT, int CT, int IT = kMaxIters>
 int launch_iters(int iters, const moc_graph* g, const LdsLayout& lay, int64_t B, const int32_t* s, const int32_t* e,
-                 const uint8_t* a, moc_result* out, hipStream_t st) {
+                 const uint8_t* a, moc_result* out, hipStream_t st, const TicketSource& src) {
   if constexpr (IT == 0) {
     return MOC_EINVAL;
   } else {
-    if (iters == IT) return launch_kernel(eval_batch_kernel<NT, CT, IT>, NT, g, lay, B, s, e, a, out, st, 0);
-    return launch_iters<NT, CT, IT - 1>(iters, g, lay, B, s, e, a, out, st);
+    if (iters == IT) return launch_kernel(eval_batch_kernel<NT, CT, IT>, NT, g, lay, B, s, e, a, out, st, src);
+    return launch_iters<NT, CT, IT - 1>(iters, g, lay, B, s, e, a, out, st, src);
   }
 }
 
@@ -915,19 +911,19 @@ bool fast_shape(int n, int m, int C, int nt) {
 
 template <int NT>
 int launch_nt(const moc_graph* g, int64_t B, const int32_t* s, const int32_t* e, const uint8_t* a, moc_result* out,
-              hipStream_t st, bool aligned) {
+              hipStream_t st, bool aligned, const TicketSource& src) {
   const int n = g->view.n, m = g->view.m, C = g->view.C;
   if (aligned && fast_shape(n, m, C, NT)) {
     const LdsLayout lay = fast_layout(n, m, C, NT, g->max_lds);
     const int iters = slots_per_lane(n, m, NT);
     switch (C) {
-      case 1: return launch_iters<NT, 1>(iters, g, lay, B, s, e, a, out, st);
-      case 2: return launch_iters<NT, 2>(iters, g, lay, B, s, e, a, out, st);
-      case 3: return launch_iters<NT, 3>(iters, g, lay, B, s, e, a, out, st);
-      default: return launch_iters<NT, 4>(iters, g, lay, B, s, e, a, out, st);
+      case 1: return launch_iters<NT, 1>(iters, g, lay, B, s, e, a, out, st, src);
+      case 2: return launch_iters<NT, 2>(iters, g, lay, B, s, e, a, out, st, src);
+      case 3: return launch_iters<NT, 3>(iters, g, lay, B, s, e, a, out, st, src);
+      default: return launch_iters<NT, 4>(iters, g, lay, B, s, e, a, out, st, src);
     }
   }
-  return launch_kernel(eval_batch_general_kernel<NT>, NT, g, general_layout(n, C, NT), B, s, e, a, out, st, 1);
+  return launch_kernel(eval_batch_general_kernel<NT>, NT, g, general_layout(n, C, NT), B, s, e, a, out, st, src);
 }
 
 }  // namespace
@@ -949,8 +945,10 @@ int moc_eval_lds_bytes(int n, int m, int C, int max_lds) {
   return fast > general ? fast : general;
 }
 
-extern "C" int moc_eval_batch(const moc_graph* g, int64_t B, const int32_t* starts, const int32_t* ends,
-                              const uint8_t* active, moc_result* out, void* hip_stream) {
+namespace {
+
+int eval_batch(const moc_graph* g, int64_t B, const int32_t* starts, const int32_t* ends, const uint8_t* active,
+               moc_result* out, void* hip_stream, const TicketSource& src) {
   if (!g || B < 0) return MOC_EINVAL;
   if (B == 0) return MOC_OK;
   if (!starts || !ends || !active || !out) return MOC_EINVAL;
@@ -976,13 +974,20 @@ extern "C" int moc_eval_batch(const moc_graph* g, int64_t B, const int32_t* star
     const uint8_t* a = active + at * T;
     int rc;
     switch (nt) {
-      case 64: rc = launch_nt<64>(g, count, s, e, a, out + at, st, aligned); break;
-      case 128: rc = launch_nt<128>(g, count, s, e, a, out + at, st, aligned); break;
-      case 256: rc = launch_nt<256>(g, count, s, e, a, out + at, st, aligned); break;
-      case 512: rc = launch_nt<512>(g, count, s, e, a, out + at, st, aligned); break;
-      default: rc = launch_nt<1024>(g, count, s, e, a, out + at, st, aligned); break;
+      case 64: rc = launch_nt<64>(g, count, s, e, a, out + at, st, aligned, src); break;
+      case 128: rc = launch_nt<128>(g, count, s, e, a, out + at, st, aligned, src); break;
+      case 256: rc = launch_nt<256>(g, count, s, e, a, out + at, st, aligned, src); break;
+      case 512: rc = launch_nt<512>(g, count, s, e, a, out + at, st, aligned, src); break;
+      default: rc = launch_nt<1024>(g, count, s, e, a, out + at, st, aligned, src); break;
     }
     if (rc != MOC_OK) return rc;
   }
   return MOC_OK;
+}
+
+}  // namespace
+
+extern "C" int moc_eval_batch(const moc_graph* g, int64_t B, const int32_t* starts, const int32_t* ends,
+                              const uint8_t* active, moc_result* out, void* hip_stream) {
+  return eval_batch(g, B, starts, ends, active, out, hip_stream, TicketSource{nullptr});
 }

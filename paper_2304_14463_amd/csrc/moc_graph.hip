@@ -20,6 +20,49 @@ int moc_set_hip_error(hipError_t e) {
   return MOC_EHIP;
 }
 
+uint32_t* moc_ticket_set(const moc_graph* g, hipStream_t stream) {
+  std::lock_guard<std::mutex> lock(g->mu);
+  int i = 0;
+  while (i < g->n_ticket_streams && g->ticket_stream[i] != stream) ++i;
+  if (i == g->n_ticket_streams) {
+    if (i == kTicketSlots) return nullptr;
+    g->ticket_stream[g->n_ticket_streams++] = stream;
+  }
+  return g->tickets + (size_t)i * kTicketSlotWords;
+}
+
+int moc_kernel_occupancy(const moc_graph* g, const void* kern, int nt, int lds_bytes, bool no_static_lds,
+                         int* per_cu) {
+  std::lock_guard<std::mutex> lock(g->mu);
+  for (const moc_graph::Occupancy& o : g->occupancy)
+    if (o.kern == kern && o.nt == nt && o.lds_bytes == lds_bytes) {
+      *per_cu = o.per_cu;
+      return MOC_OK;
+    }
+  // first use of this kernel on this device, by any handle
+  static std::mutex prepared_mu;
+  static std::vector<std::pair<const void*, int>> prepared;
+  {
+    std::lock_guard<std::mutex> plock(prepared_mu);
+    const std::pair<const void*, int> key(kern, g->device);
+    if (std::find(prepared.begin(), prepared.end(), key) == prepared.end()) {
+      if (no_static_lds) {
+        hipFuncAttributes attr;
+        MOC_HIP(hipFuncGetAttributes(&attr, kern));
+        if (attr.sharedSizeBytes != 0) return MOC_EINVAL;
+      }
+      MOC_HIP(hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, g->max_lds));
+      prepared.push_back(key);
+    }
+  }
+  int blocks = 0;
+  MOC_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, kern, nt, (size_t)lds_bytes));
+  if (blocks < 1) blocks = 1;
+  g->occupancy.push_back(moc_graph::Occupancy{kern, nt, lds_bytes, blocks});
+  *per_cu = blocks;
+  return MOC_OK;
+}
+
 
 // The edge list of the register-resident kernel.  Lane `tid` of a workgroup of nt threads
 // owns the entries j*nt + tid, j < edges_per_lane, and a wave fetches the records of the two

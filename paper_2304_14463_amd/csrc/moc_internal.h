@@ -5,6 +5,8 @@
 #include <stdint.h>
 
 #include <atomic>
+#include <mutex>
+#include <vector>
 
 #include "moccasin.h"
 
@@ -28,6 +30,11 @@ struct GraphView {
   int32_t n, m, C, T;
 };
 
+constexpr int kTicketSlots = 16;   // sets of work counters per graph handle = streams that get one of their own
+constexpr int kTicketGroups = 64;  // counters a launch draws candidates from (+1: workgroups that have left)
+constexpr int kTicketStride = 16;  // words from one counter to the next
+constexpr int kTicketSlotWords = (kTicketGroups + 1) * kTicketStride;
+
 struct moc_graph {
   int device;
   int num_cu;
@@ -38,20 +45,30 @@ struct moc_graph {
   int n_allocs;
   // Work counters of the evaluation kernel: kTicketSlots sets of kTicketGroups + 1 counters,
   // each counter on a 64-byte line of its own, all zero between launches (a launch leaves its
-  // set at zero when it ends).  Launches take the sets in turn, so that launches running at
-  // the same time on different streams do not share one unless more than kTicketSlots are
-  // in flight.
+  // set at zero when it ends).  A set belongs to a stream: launches on one stream follow each
+  // other, so they may share counters; launches on different streams may run at the same time
+  // and must not.  The first kTicketSlots streams seen with this handle get a set each
+  // (ticket_stream[i] owns set i); launches on further streams are split statically and touch
+  // no counters.
   uint32_t* tickets;
-  mutable std::atomic<uint32_t> launch_seq;
-  // workgroups per compute unit of the evaluation kernel this graph takes (0: not asked yet);
-  // [0] the register-resident kernel, [1] the kernel for any C
-  mutable std::atomic<int> per_cu[2];
+  mutable std::mutex mu;   // guards ticket_stream, n_ticket_streams and occupancy
+  mutable hipStream_t ticket_stream[kTicketSlots];
+  mutable int n_ticket_streams;
+  // workgroups per compute unit of (kernel, workgroup size, dynamic LDS bytes), asked once each
+  struct Occupancy { const void* kern; int nt, lds_bytes, per_cu; };
+  mutable std::vector<Occupancy> occupancy;
 };
 
-constexpr int kTicketSlots = 16;
-constexpr int kTicketGroups = 64;  // counters a launch draws candidates from (+1: workgroups that have left)
-constexpr int kTicketStride = 16;  // words from one counter to the next
-constexpr int kTicketSlotWords = (kTicketGroups + 1) * kTicketStride;
+// The set of work counters that launches of this handle on `stream` draw from, or nullptr
+// when all sets belong to other streams (the launch is then split statically).
+uint32_t* moc_ticket_set(const moc_graph* g, hipStream_t stream);
+
+// Workgroups of `kern` with nt threads and lds_bytes of dynamic LDS that a compute unit of
+// the graph's device holds (at least 1).  On the first use of a kernel on a device its
+// dynamic-LDS limit is raised to all the LDS a workgroup can have; with no_static_lds the
+// kernel must declare no static LDS (MOC_EINVAL otherwise).  Results are kept per handle.
+int moc_kernel_occupancy(const moc_graph* g, const void* kern, int nt, int lds_bytes, bool no_static_lds,
+                         int* per_cu);
 
 // Unit of the node indices in GraphView::edge_pair = words per node in the first record array
 // of the register-resident kernel: C for C <= 2 (all copies of a node in one record), 1 for

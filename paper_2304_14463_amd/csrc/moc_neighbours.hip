@@ -1366,11 +1366,8 @@ extern "C" int moc_eval_neighbours(const moc_graph* g, int64_t B, const int32_t*
   if (lay.bytes > g->max_lds) return MOC_EOVERFLOW;
   if ((int64_t)g->view.T * 4 * R * 8 > 0xFFFFFFFFll) return MOC_EOVERFLOW;   // byte offsets in a candidate's table are 32 bits
   auto kern = pick_kernel(lay.adj_off != 0, g->view.C, R, out_moves != nullptr);
-  MOC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                              lay.bytes));
   int per_cu = 0;
-  MOC_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, kNT, lay.bytes));
-  if (per_cu < 1) per_cu = 1;
+  if (const int rc = moc_kernel_occupancy(g, reinterpret_cast<const void*>(kern), kNT, lay.bytes, false, &per_cu)) return rc;
   const int64_t resident = (int64_t)per_cu * g->num_cu;
   const unsigned grid = (unsigned)(B < resident ? B : resident);
   hipLaunchKernelGGL(kern, dim3(grid), dim3(kNT), lay.bytes, static_cast<hipStream_t>(hip_stream), g->view, B,
@@ -1392,11 +1389,8 @@ extern "C" int moc_eval_toggles(const moc_graph* g, int64_t B, const int32_t* st
   const TgLayout lay = tg_layout(g->view.T, g->view.n, g->view.m, g->max_lds);
   if (lay.bytes > g->max_lds) return MOC_EOVERFLOW;
   auto kern = lay.adj_off ? toggles_kernel<true, false> : toggles_kernel<false, false>;
-  MOC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                              lay.bytes));
   int per_cu = 0;
-  MOC_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, kNT, lay.bytes));
-  if (per_cu < 1) per_cu = 1;
+  if (const int rc = moc_kernel_occupancy(g, reinterpret_cast<const void*>(kern), kNT, lay.bytes, false, &per_cu)) return rc;
   const int64_t resident = (int64_t)per_cu * g->num_cu;
   const unsigned grid = (unsigned)(B < resident ? B : resident);
   hipLaunchKernelGGL(kern, dim3(grid), dim3(kNT), lay.bytes, static_cast<hipStream_t>(hip_stream), g->view, B, starts,
@@ -1472,14 +1466,13 @@ extern "C" int moc_search_cuts(const moc_graph* g, int64_t B, int32_t* starts, i
   if (lay.bytes > g->max_lds) return MOC_EOVERFLOW;
   if ((int64_t)g->view.m * g->view.C > 0x7FFFFFFFll) return MOC_EOVERFLOW;
   auto kern = lay.adj_off ? toggles_kernel<true, true> : toggles_kernel<false, true>;
-  MOC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                              lay.bytes));
-  const int apply_bytes = 4 * (g->view.T + (g->view.T + 31) / 32);
-  MOC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(apply_cuts_kernel),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, apply_bytes));
   int per_cu = 0;
-  MOC_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, kNT, lay.bytes));
-  if (per_cu < 1) per_cu = 1;
+  if (const int rc = moc_kernel_occupancy(g, reinterpret_cast<const void*>(kern), kNT, lay.bytes, false, &per_cu)) return rc;
+  const int apply_bytes = 4 * (g->view.T + (g->view.T + 31) / 32);
+  int apply_per_cu = 0;   // not used: the call is for the kernel's LDS limit
+  if (const int rc = moc_kernel_occupancy(g, reinterpret_cast<const void*>(apply_cuts_kernel), kApplyNT, apply_bytes, false,
+                                          &apply_per_cu))
+    return rc;
   const int64_t resident = (int64_t)per_cu * g->num_cu;
   const unsigned grid = (unsigned)(B < resident ? B : resident);
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
@@ -1511,11 +1504,8 @@ extern "C" int moc_eval_cuts(const moc_graph* g, int64_t B, const int32_t* start
   if (lay.bytes > g->max_lds) return MOC_EOVERFLOW;
   if ((int64_t)g->view.m * g->view.C > 0x7FFFFFFFll) return MOC_EOVERFLOW;
   auto kern = lay.adj_off ? toggles_kernel<true, true> : toggles_kernel<false, true>;
-  MOC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                              lay.bytes));
   int per_cu = 0;
-  MOC_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, kNT, lay.bytes));
-  if (per_cu < 1) per_cu = 1;
+  if (const int rc = moc_kernel_occupancy(g, reinterpret_cast<const void*>(kern), kNT, lay.bytes, false, &per_cu)) return rc;
   const int64_t resident = (int64_t)per_cu * g->num_cu;
   const unsigned grid = (unsigned)(B < resident ? B : resident);
   hipLaunchKernelGGL(kern, dim3(grid), dim3(kNT), lay.bytes, static_cast<hipStream_t>(hip_stream), g->view, B, starts,

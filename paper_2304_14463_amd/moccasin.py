@@ -92,6 +92,15 @@ def _stream_handle(stream):
     return ctypes.c_void_p(stream.cuda_stream)
 
 
+def _on(stream):
+    """Context in which tensors are allocated for use on `stream`: a workspace that this module
+    allocates and drops while kernels queued on `stream` still use it must belong to that
+    stream for torch's allocator, or it could be handed to work on another stream too early."""
+    import contextlib
+    import torch
+    return torch.cuda.stream(stream) if stream is not None else contextlib.nullcontext()
+
+
 class Graph:
     """Handle of an uploaded problem instance (moc_graph_upload / moc_graph_free)."""
 
@@ -200,10 +209,11 @@ def moc_search_cuts(g: Graph, starts, ends, active, max_steps, work_best=None, o
     import torch
     B = starts.numel() // g.T if g.T else 0
     ps, pe, pa = _cand_ptrs(g, B, starts, ends, active)
-    if work_best is None:
-        work_best = torch.empty((B, BEST_MOVE_DTYPE.itemsize), dtype=torch.uint8, device=starts.device)
-    if out_steps is None:
-        out_steps = torch.empty((B,), dtype=torch.int32, device=starts.device)
+    with _on(stream):
+        if work_best is None:
+            work_best = torch.empty((B, BEST_MOVE_DTYPE.itemsize), dtype=torch.uint8, device=starts.device)
+        if out_steps is None:
+            out_steps = torch.empty((B,), dtype=torch.int32, device=starts.device)
     code = lib().moc_search_cuts(g._h, B, ps, pe, pa, int(max_steps), ctypes.c_void_p(work_best.data_ptr()),
                                  ctypes.c_void_p(out_steps.data_ptr()), _stream_handle(stream))
     _check(code, "moc_search_cuts")
@@ -216,10 +226,11 @@ def moc_search_moves(g: Graph, starts, ends, active, R, max_steps, out_steps=Non
     import torch
     B = starts.numel() // g.T if g.T else 0
     ps, pe, pa = _cand_ptrs(g, B, starts, ends, active)
-    work_results = torch.empty((B, RESULT_DTYPE.itemsize), dtype=torch.uint8, device=starts.device)
-    work_best = torch.empty((B, BEST_MOVE_DTYPE.itemsize), dtype=torch.uint8, device=starts.device)
-    if out_steps is None:
-        out_steps = torch.empty((B,), dtype=torch.int32, device=starts.device)
+    with _on(stream):
+        work_results = torch.empty((B, RESULT_DTYPE.itemsize), dtype=torch.uint8, device=starts.device)
+        work_best = torch.empty((B, BEST_MOVE_DTYPE.itemsize), dtype=torch.uint8, device=starts.device)
+        if out_steps is None:
+            out_steps = torch.empty((B,), dtype=torch.int32, device=starts.device)
     code = lib().moc_search_moves(g._h, B, ps, pe, pa, int(R), int(max_steps),
                                   ctypes.c_void_p(work_results.data_ptr()), ctypes.c_void_p(work_best.data_ptr()),
                                   ctypes.c_void_p(out_steps.data_ptr()), _stream_handle(stream))

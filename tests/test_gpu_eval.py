@@ -71,27 +71,40 @@ def test_eval_parity_full_batch(moc, workloads, cfg):
     torch.cuda.synchronize()
 
 
-def test_eval_parity_largest_workload_sampled(moc, workloads):
+@pytest.mark.timeout(900)
+def test_eval_parity_largest_workload_every_candidate(moc, workloads):
     """Config 4 (n=5000, C=3, T=15000) as the benchmark runs it: all 262144 candidates
-    (35.4 GB) resident in HBM, one launch.  The oracle checks sampled candidates; the
-    rest is checked through properties that hold for every candidate."""
+    (35.4 GB) resident in HBM, one launch; every one of them is compared with the oracle,
+    which takes them from the device in slices of 2.2 GB and splits a slice over the host's
+    threads."""
+    import os
     import torch
     from paper_2304_14463_amd.inputs import DeviceWorkload
     w = workloads(4)
     gh = upload(moc, w)
     ds, de, da = DeviceWorkload(w).candidates()
     gpu = moc.results_to_numpy(moc.moc_eval_batch(gh, ds, de, da))
-    rng = np.random.default_rng(4)
-    pick = np.unique(np.concatenate([[0, 1, w.B // 2 - 1, w.B // 2, w.B - 2, w.B - 1],
-                                     rng.choice(w.B, 250, replace=False)]))
-    idx = torch.from_numpy(pick).cuda()
-    s, e, a = ds[idx].cpu().numpy(), de[idx].cpu().numpy(), da[idx].cpu().numpy()
-    ref = oracle_eval_parallel(w.graph, w.budget, w.C, s, e, a)
-    assert_results_equal(gpu[pick], ref, "cfg 4")
-    assert (gpu["duration"] >= int(w.graph.dur.sum())).all()
-    assert (gpu["feasible"] == ((gpu["violations"] == 0) & (gpu["peak"] <= w.budget))).all()
-    assert (gpu["peak"] > 0).all() and (gpu["peak"] <= w.C * int(w.graph.size.sum())).all()
+    threads = min(os.cpu_count() or 8, 16)
+    step = 16384
+    n_clean = 0
+    for b0 in range(0, w.B, step):
+        s, e, a = ds[b0:b0 + step].cpu().numpy(), de[b0:b0 + step].cpu().numpy(), da[b0:b0 + step].cpu().numpy()
+        ref = oracle_eval_parallel(w.graph, w.budget, w.C, s, e, a, threads=threads)
+        assert_results_equal(gpu[b0:b0 + step], ref, f"cfg 4, candidates {b0}..")
+        n_clean += int((ref[:, F["violations"]] == 0).sum())
+        print(f"cfg 4: {b0 + len(ref)} of {w.B} candidates compared", flush=True)
+    assert 0 < n_clean < w.B
     assert (gpu["violations"][: w.B // 2] < gpu["violations"][w.B // 2:].mean()).mean() > 0.99   # type A vs type B
+    # the same batch under a budget that splits the violation-free candidates: feasible = 1 occurs
+    clean = gpu["violations"] == 0
+    mid = int(np.median(gpu["peak"][clean]))
+    gh2 = upload(moc, w, budget=mid)
+    gpu2 = moc.results_to_numpy(moc.moc_eval_batch(gh2, ds, de, da))
+    want = (clean & (gpu["peak"] <= mid)).astype(np.int32)   # gpu's peaks and counts equal the oracle's, shown above
+    assert (gpu2["feasible"] == want).all() and 0 < want.sum() < clean.sum() + 1
+    for name in ("peak", "duration", "violations"):
+        assert (gpu2[name] == gpu[name]).all(), name
+    gh2.free()
     # the same rows evaluated as a separate, smaller launch give the same bytes
     sub = moc.results_to_numpy(moc.moc_eval_batch(gh, ds[1000:1300], de[1000:1300], da[1000:1300]))
     assert sub.tobytes() == gpu[1000:1300].tobytes()
@@ -184,6 +197,61 @@ def test_eval_many_launches_one_graph(moc, n, C, B):
     torch.cuda.synchronize()
     for i, out in enumerate(outs):
         assert moc.results_to_numpy(out).tobytes() == first.tobytes(), f"launch {i} differs"
+    gh.free()
+
+
+def test_eval_streams_do_not_share_work_counters(moc):
+    """A long launch on one stream while many short ones run on another, on one graph handle:
+    a stream keeps the set of work counters it was given, so the short launches never draw
+    from the counters of the long one.  Then launches on more streams than the handle has
+    sets: those are split statically.  Every output equals the oracle's."""
+    import torch
+    from paper_2304_14463_amd.inputs import graph_from_edges
+    n, C, B, reps = 96, 3, 40000, 24
+    rng = np.random.default_rng(77)
+    edges = sorted({(int(u), v) for v in range(1, n) for u in rng.integers(0, v, size=3)})
+    g = graph_from_edges(n, edges, rng.integers(1, 100, n), rng.integers(1, 9, n))
+    T = n * C
+    s, e, a = random_candidates(rng, B, n, C, T, wild=False)
+    a.reshape(B, n, C)[:, :, 0] = 1
+    budget = int(g.size.sum()) // 3
+    gh = moc.moc_graph_upload(n, g.in_ptr, g.in_idx, g.size, g.dur, budget, C)
+    ds, de, da = to_dev(s, e, a)
+    first = moc.results_to_numpy(moc.moc_eval_batch(gh, ds, de, da))
+    assert_results_equal(first, oracle_eval_parallel(g, budget, C, s, e, a), "short batch")
+    ls, le, la = ds.repeat(reps, 1), de.repeat(reps, 1), da.repeat(reps, 1)   # the long batch: the same rows 24 times
+    torch.cuda.synchronize()
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    with torch.cuda.stream(sa):
+        long_out = moc.moc_eval_batch(gh, ls, le, la, stream=sa)
+    shorts = []
+    with torch.cuda.stream(sb):
+        for i in range(40):
+            shorts.append(moc.moc_eval_batch(gh, ds, de, da, stream=sb))
+    torch.cuda.synchronize()
+    assert moc.results_to_numpy(long_out).tobytes() == np.tile(first, reps).tobytes(), "long launch"
+    for i, out in enumerate(shorts):
+        assert moc.results_to_numpy(out).tobytes() == first.tobytes(), f"short launch {i}"
+    # the same again with the long launch issued in the middle of the short ones
+    with torch.cuda.stream(sb):
+        shorts = [moc.moc_eval_batch(gh, ds, de, da, stream=sb) for _ in range(10)]
+    with torch.cuda.stream(sa):
+        long_out = moc.moc_eval_batch(gh, ls, le, la, stream=sa)
+    with torch.cuda.stream(sb):
+        shorts += [moc.moc_eval_batch(gh, ds, de, da, stream=sb) for _ in range(30)]
+    torch.cuda.synchronize()
+    assert moc.results_to_numpy(long_out).tobytes() == np.tile(first, reps).tobytes(), "long launch, second time"
+    for i, out in enumerate(shorts):
+        assert moc.results_to_numpy(out).tobytes() == first.tobytes(), f"short launch {i}, second time"
+    # 24 more streams on the same handle: more than it has sets of counters
+    streams = [torch.cuda.Stream() for _ in range(24)]
+    outs = []
+    for st in streams:
+        with torch.cuda.stream(st):
+            outs.append(moc.moc_eval_batch(gh, ds, de, da, stream=st))
+    torch.cuda.synchronize()
+    for i, out in enumerate(outs):
+        assert moc.results_to_numpy(out).tobytes() == first.tobytes(), f"stream {i}"
     gh.free()
 
 
