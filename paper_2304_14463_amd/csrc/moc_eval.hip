@@ -843,22 +843,25 @@ __global__ __launch_bounds__(NT) void eval_batch_general_kernel(GraphView g, int
 }
 
 // ------------------------------------------------------------------ host side
-// Where a launch takes its work counters from: the graph handle's set for the stream, or a set
-// the caller names (`fixed`).
-struct TicketSource {
+// fixed: the set of work counters to use instead of the graph handle's set for the stream.
+// prepare_only: do everything a launch does on the host except the launch itself (first-use
+// set-up of the kernel and its occupancy, which the handle then remembers).
+struct LaunchOpts {
   uint32_t* fixed;
+  bool prepare_only;
 };
 
 template <typename K>
 int launch_kernel(K kern, int nt, const moc_graph* g, const LdsLayout& lay, int64_t B, const int32_t* starts,
                   const int32_t* ends, const uint8_t* active, moc_result* out, hipStream_t stream,
-                  const TicketSource& src) {
+                  const LaunchOpts& src) {
   if (lay.bytes > g->max_lds) return MOC_EOVERFLOW;
   // Nothing may be placed before the dynamic LDS segment: the kernels address the node
   // records from LDS address 0.
   int per_cu = 0;
   const int rc = moc_kernel_occupancy(g, reinterpret_cast<const void*>(kern), nt, lay.bytes, true, &per_cu);
   if (rc != MOC_OK) return rc;
+  if (src.prepare_only) return MOC_OK;
   const int64_t resident = (int64_t)per_cu * g->num_cu;
   const unsigned grid = (unsigned)(B < resident ? B : resident);
   // About 16 workgroups share a counter.  A batch of fewer than 8 candidates per workgroup is
@@ -878,7 +881,7 @@ int launch_kernel(K kern, int nt, const moc_graph* g, const LdsLayout& lay, int6
 
 template <int NT, int CT, int IT = kMaxIters>
 int launch_iters(int iters, const moc_graph* g, const LdsLayout& lay, int64_t B, const int32_t* s, const int32_t* e,
-                 const uint8_t* a, moc_result* out, hipStream_t st, const TicketSource& src) {
+                 const uint8_t* a, moc_result* out, hipStream_t st, const LaunchOpts& src) {
   if constexpr (IT == 0) {
     return MOC_EINVAL;
   } else {
@@ -911,7 +914,7 @@ bool fast_shape(int n, int m, int C, int nt) {
 
 template <int NT>
 int launch_nt(const moc_graph* g, int64_t B, const int32_t* s, const int32_t* e, const uint8_t* a, moc_result* out,
-              hipStream_t st, bool aligned, const TicketSource& src) {
+              hipStream_t st, bool aligned, const LaunchOpts& src) {
   const int n = g->view.n, m = g->view.m, C = g->view.C;
   if (aligned && fast_shape(n, m, C, NT)) {
     const LdsLayout lay = fast_layout(n, m, C, NT, g->max_lds);
@@ -947,24 +950,10 @@ int moc_eval_lds_bytes(int n, int m, int C, int max_lds) {
 
 namespace {
 
-int eval_batch(const moc_graph* g, int64_t B, const int32_t* starts, const int32_t* ends, const uint8_t* active,
-               moc_result* out, void* hip_stream, const TicketSource& src) {
-  if (!g || B < 0) return MOC_EINVAL;
-  if (B == 0) return MOC_OK;
-  if (!starts || !ends || !active || !out) return MOC_EINVAL;
-  if (((uintptr_t)starts | (uintptr_t)ends) & 3 || ((uintptr_t)out & 7)) return MOC_EINVAL;
-  int dev = -1;
-  MOC_HIP(hipGetDevice(&dev));
-  if (dev != g->device) return MOC_EDEVICE;
-  const int n = g->view.n, C = g->view.C;
-  // The register-resident kernel reads the C copies of a node as one vector: rows must be
-  // aligned to the vector (they are when the base pointers are, since a row is n vectors).
-  const uintptr_t se = (uintptr_t)starts | (uintptr_t)ends;
-  bool aligned = true;
-  if (C == 2) aligned = (se & 7) == 0 && ((uintptr_t)active & 1) == 0;
-  if (C == 4) aligned = (se & 15) == 0 && ((uintptr_t)active & 3) == 0;
-  hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  const int nt = block_threads(n, g->view.m);
+// One launch per 2^31 candidates of the kernel this graph and these arrays take.
+int dispatch(const moc_graph* g, int64_t B, const int32_t* starts, const int32_t* ends, const uint8_t* active,
+             moc_result* out, hipStream_t st, bool aligned, const LaunchOpts& src) {
+  const int nt = block_threads(g->view.n, g->view.m);
   // The kernels count candidates handed out in 32 bits: longer batches go in several launches.
   const int64_t T = g->view.T;
   for (int64_t at = 0; at < B; at += kMaxLaunch) {
@@ -985,9 +974,42 @@ int eval_batch(const moc_graph* g, int64_t B, const int32_t* starts, const int32
   return MOC_OK;
 }
 
+int check_arguments(const moc_graph* g, int64_t B, const int32_t* starts, const int32_t* ends,
+                    const uint8_t* active, moc_result* out) {
+  if (!g || B < 0) return MOC_EINVAL;
+  if (B == 0) return MOC_OK;
+  if (!starts || !ends || !active || !out) return MOC_EINVAL;
+  if (((uintptr_t)starts | (uintptr_t)ends) & 3 || ((uintptr_t)out & 7)) return MOC_EINVAL;
+  int dev = -1;
+  MOC_HIP(hipGetDevice(&dev));
+  if (dev != g->device) return MOC_EDEVICE;
+  return MOC_OK;
+}
+
+// The register-resident kernel reads the C copies of a node as one vector: rows must be
+// aligned to the vector (they are when the base pointers are, since a row is n vectors).
+bool vector_aligned(int C, const int32_t* starts, const int32_t* ends, const uint8_t* active) {
+  const uintptr_t se = (uintptr_t)starts | (uintptr_t)ends;
+  if (C == 2) return (se & 7) == 0 && ((uintptr_t)active & 1) == 0;
+  if (C == 4) return (se & 15) == 0 && ((uintptr_t)active & 3) == 0;
+  return true;
+}
+
 }  // namespace
+
+int moc_eval_prepare(const moc_graph* g) {
+  const LaunchOpts prepare{nullptr, true};
+  for (const bool aligned : {true, false}) {
+    const int rc = dispatch(g, 1, nullptr, nullptr, nullptr, nullptr, nullptr, aligned, prepare);
+    if (rc != MOC_OK) return rc;
+  }
+  return MOC_OK;
+}
 
 extern "C" int moc_eval_batch(const moc_graph* g, int64_t B, const int32_t* starts, const int32_t* ends,
                               const uint8_t* active, moc_result* out, void* hip_stream) {
-  return eval_batch(g, B, starts, ends, active, out, hip_stream, TicketSource{nullptr});
+  const int rc = check_arguments(g, B, starts, ends, active, out);
+  if (rc != MOC_OK || B == 0) return rc;
+  return dispatch(g, B, starts, ends, active, out, static_cast<hipStream_t>(hip_stream),
+                  vector_aligned(g->view.C, starts, ends, active), LaunchOpts{nullptr, false});
 }

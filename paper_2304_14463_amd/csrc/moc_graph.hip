@@ -234,6 +234,10 @@ int moc_graph_upload(int32_t n, const int32_t* in_ptr, const int32_t* in_idx, co
       rc = upload(g, zeros, &dev);
       g->tickets = const_cast<uint32_t*>(dev);
     }
+    if (rc == MOC_OK) {
+      g->occupancy.reserve(16);
+      rc = moc_eval_prepare(g);
+    }
     if (rc != MOC_OK) {
       for (int i = 0; i < g->n_allocs; ++i) (void)hipFree(g->allocs[i]);
       delete g;

@@ -84,6 +84,10 @@ int moc_eval_lds_bytes(int n, int m, int C, int max_lds);
 // edges_per_lane_used are looked at); false if the graph does not take that kernel.
 bool moc_eval_shape(int n, int m, int C, int* nt, int* edges_per_lane, int* edges_per_lane_used);
 
+// First-use set-up of the evaluation kernels this graph takes (called at upload, so that
+// moc_eval_batch finds everything in the handle).
+int moc_eval_prepare(const moc_graph* g);
+
 int moc_set_hip_error(hipError_t e);  // records e, returns MOC_EHIP
 
 #define MOC_HIP(call)                                  \
