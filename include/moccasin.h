@@ -159,6 +159,30 @@ int moc_eval_batch(const moc_graph* g, int64_t B, const int32_t* starts, const i
                    const uint8_t* active, moc_result* out, void* hip_stream);
 
 /*
+ * moc_eval_batch for callers that cannot allocate: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, same results, same kernels; the work counters of the launch are
+ * not the handle's (device memory allocated at upload) but one fixed set of
+ * 4160 bytes inside the library's device image, which each GPU the library
+ * runs on holds until the process ends.  The call queues a kernel that clears
+ * them, then the evaluation; it calls no hipMalloc, hipFree or other
+ * allocating routine (what the kernels need to know of the device was asked
+ * for when the graph was uploaded).
+ *   B   at most MOC_NOALLOC_MAX_B (one launch: the counters count candidates
+ *       in 32 bits); MOC_EOVERFLOW beyond that.  Longer batches: several calls
+ *       on one stream.
+ * All calls on a GPU share that one set of counters, whatever graph handle
+ * and stream they use: two such calls whose kernels overlap on one GPU race
+ * (candidates skipped or evaluated twice, result rows left unwritten).  Issue
+ * them on one stream, or order them with events.  They do not interfere with
+ * moc_eval_batch.
+ * Errors: MOC_EINVAL, MOC_EDEVICE, MOC_EOVERFLOW, MOC_EHIP.
+ */
+#define MOC_NOALLOC_MAX_B 2147483648ll /* 2^31 */
+int moc_eval_batch_noalloc(const moc_graph* g, int64_t B, const int32_t* starts, const int32_t* ends,
+                           const uint8_t* active, moc_result* out, void* hip_stream);
+
+/*
  * Score every single-field move of B base candidates.  Not part of the paper:
  * it is the neighbourhood a local search over the variables of Section 2.1
  * would scan.  Move index q = ((k*2 + field)*2R + d): copy k, field 0 = start,

@@ -1013,3 +1013,53 @@ extern "C" int moc_eval_batch(const moc_graph* g, int64_t B, const int32_t* star
   return dispatch(g, B, starts, ends, active, out, static_cast<hipStream_t>(hip_stream),
                   vector_aligned(g->view.C, starts, ends, active), LaunchOpts{nullptr, false});
 }
+
+// ------------------------------------------------------------------ moc_eval_batch_noalloc
+// The same evaluation with its work counters in the library's own device image instead of
+// memory allocated at upload: one set, kTicketSlotWords words, per GPU.  Host code never uses
+// the array's name as an address: the address on each device is asked for once, with that
+// device current (moc_eval_static_setup, called by moc_graph_upload), and kept.
+static __device__ __align__(256) uint32_t scratch[kTicketSlotWords];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+uint32_t* g_scratch_ptr[kMaxDevices];   // per device: where `scratch` lives there; nullptr = not asked yet
+
+__global__ void clear_counters_kernel(uint32_t* counters) {
+  for (int i = threadIdx.x; i < kTicketSlotWords; i += blockDim.x) counters[i] = 0u;
+}
+
+}  // namespace
+
+int moc_eval_static_setup(int device) {
+  if (device < 0 || device >= kMaxDevices) return MOC_EINVAL;
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (g_scratch_ptr[device]) return MOC_OK;
+  uint32_t* ptr = nullptr;
+  MOC_HIP(hipGetSymbolAddress(reinterpret_cast<void**>(&ptr), HIP_SYMBOL(scratch)));
+  if (!ptr) return MOC_EINVAL;
+  g_scratch_ptr[device] = ptr;
+  return MOC_OK;
+}
+
+extern "C" int moc_eval_batch_noalloc(const moc_graph* g, int64_t B, const int32_t* starts, const int32_t* ends,
+                                      const uint8_t* active, moc_result* out, void* hip_stream) {
+  const int rc = check_arguments(g, B, starts, ends, active, out);
+  if (rc != MOC_OK || B == 0) return rc;
+  if (B > MOC_NOALLOC_MAX_B) return MOC_EOVERFLOW;
+  uint32_t* counters;
+  {
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    counters = g_scratch_ptr[g->device];   // set when the graph was uploaded on this device
+  }
+  if (!counters) return MOC_EINVAL;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  // the array keeps what the last call left in it: start from zero (a kernel, not a memset,
+  // so that the call can be recorded into a HIP graph)
+  hipLaunchKernelGGL(clear_counters_kernel, dim3(1), dim3(256), 0, st, counters);
+  MOC_HIP(hipGetLastError());
+  return dispatch(g, B, starts, ends, active, out, st, vector_aligned(g->view.C, starts, ends, active),
+                  LaunchOpts{counters, false});
+}

@@ -238,6 +238,7 @@ int moc_graph_upload(int32_t n, const int32_t* in_ptr, const int32_t* in_idx, co
       g->occupancy.reserve(16);
       rc = moc_eval_prepare(g);
     }
+    if (rc == MOC_OK) rc = moc_eval_static_setup(g->device);
     if (rc != MOC_OK) {
       for (int i = 0; i < g->n_allocs; ++i) (void)hipFree(g->allocs[i]);
       delete g;

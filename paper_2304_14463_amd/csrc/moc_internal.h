@@ -88,6 +88,10 @@ bool moc_eval_shape(int n, int m, int C, int* nt, int* edges_per_lane, int* edge
 // moc_eval_batch finds everything in the handle).
 int moc_eval_prepare(const moc_graph* g);
 
+// Asks the current device (which must be `device`) for the address of the work counters of
+// moc_eval_batch_noalloc; once per device.
+int moc_eval_static_setup(int device);
+
 int moc_set_hip_error(hipError_t e);  // records e, returns MOC_EHIP
 
 #define MOC_HIP(call)                                  \

@@ -25,7 +25,7 @@ BEST_MOVE_DTYPE = np.dtype([("move", "<i4"), ("violations", "<i4"), ("peak", "<i
 TOGGLE_SCORE_DTYPE = np.dtype([("violations", "<i4"), ("peak", "<i4"), ("duration", "<i8")])
 DECODE_RESULT_DTYPE = np.dtype([("status", "<i4"), ("length", "<i4"), ("peak", "<i8"), ("duration", "<i8")])
 
-EXPORTS = ("moc_graph_upload", "moc_graph_info", "moc_eval_batch", "moc_eval_neighbours", "moc_eval_toggles",
+EXPORTS = ("moc_graph_upload", "moc_graph_info", "moc_eval_batch", "moc_eval_batch_noalloc", "moc_eval_neighbours", "moc_eval_toggles",
            "moc_eval_cuts", "moc_search_cuts", "moc_search_moves", "moc_decode_batch", "moc_graph_free", "moc_strerror", "moc_last_hip_error")
 
 
@@ -51,6 +51,8 @@ def lib():
         L.moc_graph_info.restype = ctypes.c_int
         L.moc_eval_batch.argtypes = [VP, I64, VP, VP, VP, VP, VP]
         L.moc_eval_batch.restype = ctypes.c_int
+        L.moc_eval_batch_noalloc.argtypes = [VP, I64, VP, VP, VP, VP, VP]
+        L.moc_eval_batch_noalloc.restype = ctypes.c_int
         L.moc_eval_neighbours.argtypes = [VP, I64, VP, VP, VP, I32, VP, VP, VP]
         L.moc_eval_neighbours.restype = ctypes.c_int
         L.moc_eval_toggles.argtypes = [VP, I64, VP, VP, VP, VP, VP]
@@ -150,6 +152,18 @@ def moc_eval_batch(g: Graph, starts, ends, active, out=None, stream=None):
         out = torch.empty((B, RESULT_DTYPE.itemsize), dtype=torch.uint8, device=starts.device)
     code = lib().moc_eval_batch(g._h, B, ps, pe, pa, ctypes.c_void_p(out.data_ptr()), _stream_handle(stream))
     _check(code, "moc_eval_batch")
+    return out
+
+
+def moc_eval_batch_noalloc(g: Graph, starts, ends, active, out, stream=None):
+    """moc_eval_batch with the work counters in the library's static device array; `out` is the
+    caller's uint8 CUDA tensor [B][24].  Nothing is allocated, here or in the library."""
+    B = starts.numel() // g.T if g.T else 0
+    ps, pe, pa = _cand_ptrs(g, B, starts, ends, active)
+    if not (out.is_cuda and out.is_contiguous() and out.numel() * out.element_size() >= B * RESULT_DTYPE.itemsize):
+        raise ValueError("out must be a contiguous CUDA tensor of at least B * 24 bytes")
+    code = lib().moc_eval_batch_noalloc(g._h, B, ps, pe, pa, ctypes.c_void_p(out.data_ptr()), _stream_handle(stream))
+    _check(code, "moc_eval_batch_noalloc")
     return out
 
 
