@@ -100,31 +100,85 @@ def time_eval(moc, gh, cand, steps, warmup):
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
     kernel_ms = [b.elapsed_time(f) for b, f in zip(begins, finishes)]
-    return wall_ms / steps, sum(kernel_ms) / len(kernel_ms), min(kernel_ms), out
+    return wall_ms / steps, KernelTimes(kernel_ms), out
 
 
-def measure(moc, cfg, steps, warmup, batch=None):
+class KernelTimes:
+    """Per-launch durations (HIP events on the launch stream around every launch)."""
+
+    def __init__(self, ms):
+        ms = sorted(ms)
+        self.avg, self.min = sum(ms) / len(ms), ms[0]
+        self.median = ms[len(ms) // 2] if len(ms) % 2 else 0.5 * (ms[len(ms) // 2 - 1] + ms[len(ms) // 2])
+
+
+def time_stream_read(cand, steps):
+    """The read-only kernel over the same three arrays: best of a few grid sizes.
+    Returns (GB/s, workgroups of 1024 threads it was best with)."""
+    import torch
+    from paper_2304_14463_amd.inputs import stream_read
+    nbytes = sum(t.numel() * t.element_size() for t in cand)
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    best = (0.0, 0)
+    for per_cu in (1, 2, 4, 8):
+        blocks = cus * per_cu
+        out = stream_read(cand, blocks)
+        torch.cuda.synchronize()
+        stream = torch.cuda.current_stream()
+        ms = []
+        for _ in range(max(3, min(steps, 10))):
+            b, f = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            b.record(stream)
+            stream_read(cand, blocks, out=out)
+            f.record(stream)
+            f.synchronize()
+            ms.append(b.elapsed_time(f))
+        gbs = nbytes / (KernelTimes(ms).median * 1e-3) / 1e9
+        if gbs > best[0]:
+            best = (gbs, blocks)
+    return best
+
+
+def measure(moc, cfg, steps, warmup, batch=None, dense=False):
     import torch
     from paper_2304_14463_amd.inputs import DeviceWorkload, make_workload
-    w = make_workload(cfg, batch)
+    w = make_workload(cfg, batch, dense=dense)
     g = w.graph
     gh = moc.moc_graph_upload(g.n, g.in_ptr, g.in_idx, g.size, g.dur, w.budget, w.C)
     cand = DeviceWorkload(w).candidates()
     torch.cuda.synchronize()
-    ms_step, ms_kernel, ms_kernel_min, out = time_eval(moc, gh, cand, steps, warmup)
+    ms_step, kt, out = time_eval(moc, gh, cand, steps, warmup)
     res = moc.results_to_numpy(out)
     bytes_per_cand = 9 * w.T + 24
+    # how many of the copies are active, and how many nodes have an active copy besides the first
+    rows = min(w.B, 4096)
+    act = (cand[2][:rows] != 0).view(rows, w.n, w.C)
     info = {
         "workload": w.name, "n": w.n, "m": w.m, "C": w.C, "T": w.T, "B": w.B,
         "budget_pct_of_no_remat_peak": w.pct, "bytes_per_candidate": bytes_per_cand,
         "frac_violation_free": float((res["violations"] == 0).mean()),
         "frac_feasible": float(res["feasible"].mean()),
+        "frac_copies_active": float(act.float().mean()),
+        "frac_nodes_with_further_copies": float(act[:, :, 1:].any(dim=2).float().mean()) if w.C > 1 else 0.0,
     }
-    gbs = w.B * bytes_per_cand / (ms_kernel * 1e-3) / 1e9
-    return w, gh, cand, res, info, ms_step, ms_kernel, ms_kernel_min, gbs
+    gbs = w.B * bytes_per_cand / (kt.avg * 1e-3) / 1e9
+    return w, gh, cand, res, info, ms_step, kt, gbs
 
 
-def measure_neighbours(moc, steps, warmup):
+def secondary(moc, cfg, steps, warmup, batch=None, dense=False):
+    """One more evaluation line: config, rate, per-launch times, fraction of the HBM peak."""
+    import torch
+    w, gh, cand, res, info, ms, kt, gbs = measure(moc, cfg, steps, warmup, batch, dense)
+    line = {"config": info, "value": w.B / (ms * 1e-3), "unit": "candidates/s", "ms_per_step": ms,
+            "kernel_ms_avg": kt.avg, "kernel_ms_median": kt.median, "kernel_ms_min": kt.min, "achieved_GBs": gbs,
+            "frac_of_hbm_peak": gbs / HBM_PEAK_GBS}
+    gh.free()
+    del cand
+    torch.cuda.empty_cache()
+    return line
+
+
+def measure_neighbours(moc, steps, warmup, with_cpu_baseline=True):
     """moc_eval_neighbours on the n=2000, C=2, R=8 workload: all 128000 moves of 8192 bases."""
     import torch
     from paper_2304_14463_amd.inputs import DeviceWorkload, make_workload
@@ -147,6 +201,8 @@ def measure_neighbours(moc, steps, warmup):
         out[mode] = {"ms_per_step": ms, "moves_per_s": w.B * n_moves / (ms * 1e-3),
                      "bytes_written": (w.B * n_moves * 8 if wm else 0) + w.B * 16}
         del om, ob
+    if with_cpu_baseline:
+        out["cpu_baseline"], out["cpu_baseline_all_cores"] = cpu_baseline_neighbours(moc, w, gh, (ds, de, da))
     # the moves that change the objective: one active flag flipped, B x T of them
     ot = moc.moc_eval_toggles(gh, ds, de, da)
     for _ in range(warmup):
@@ -272,6 +328,43 @@ def cpu_baseline(w, cand, res, target_seconds=15.0):
              "sample": f"same {count} candidates split over {cores} host threads"})
 
 
+def cpu_baseline_neighbours(moc, w, gh, cand, target_seconds=10.0):
+    """Times oracle.neighbours (full re-evaluation of every move, as it stands) on a sample of the
+    moves of the first bases: every 16th move of base 0 on one thread, then every 16th move of
+    as many bases as there are host threads, one base per thread; compared with the GPU's table."""
+    import numpy as np
+    import torch
+    import oracle
+    ds, de, da = cand
+    R = w.R
+    n_moves = w.T * 4 * R
+    cores = min(os.cpu_count() or 1, 16)
+    host = [(ds[b].cpu().numpy(), de[b].cpu().numpy(), da[b].cpu().numpy()) for b in range(cores)]
+    probe = np.arange(0, n_moves, n_moves // 64, dtype=np.int64)
+    t0 = time.perf_counter()
+    oracle.neighbours(w.graph, w.budget, w.C, *host[0], R, moves=probe)
+    per = max((time.perf_counter() - t0) / len(probe), 1e-7)
+    stride = max(1, int(n_moves * per / target_seconds))
+    pick = np.arange(0, n_moves, stride, dtype=np.int64)
+    t0 = time.perf_counter()
+    ref0, _ = oracle.neighbours(w.graph, w.budget, w.C, *host[0], R, moves=pick)
+    dt = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(cores) as ex:
+        refs = list(ex.map(lambda b: oracle.neighbours(w.graph, w.budget, w.C, *host[b], R, moves=pick)[0], range(cores)))
+    dt_all = time.perf_counter() - t0
+    om, _ = moc.moc_eval_neighbours(gh, ds[:cores], de[:cores], da[:cores], R, want_moves=True, want_best=False)
+    table = moc.results_to_numpy(om, moc.MOVE_SCORE_DTYPE)
+    ok = all((table[b]["violations"][pick] == refs[b][:, 0]).all() and (table[b]["peak"][pick] == refs[b][:, 1]).all()
+             for b in range(cores)) and (refs[0] == ref0).all()
+    del om
+    return ({"value": len(pick) / dt, "unit": "moves/s", "cores": 1, "kind": "oracle",
+             "sample": f"every {stride}th of the {n_moves} moves of base 0 ({len(pick)} moves), single-threaded "
+                       "oracle.neighbours", "matches_gpu": bool(ok)},
+            {"value": cores * len(pick) / dt_all, "unit": "moves/s", "cores": cores, "kind": "oracle",
+             "sample": f"the same {len(pick)} moves of bases 0..{cores - 1}, one base per host thread"})
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -290,8 +383,8 @@ def main():
         del src, dst
         torch.cuda.empty_cache()
 
-    w, gh, cand, res, info, ms_step, ms_kernel, ms_kernel_min, gbs = measure(
-        moc, args.workload, args.steps, args.warmup, args.batch)
+    w, gh, cand, res, info, ms_step, kt, gbs = measure(moc, args.workload, args.steps, args.warmup, args.batch)
+    read_gbs, read_blocks = time_stream_read(cand, args.steps)
     line = {
         "metric": "candidate schedules evaluated/sec",
         "value": w.B / (ms_step * 1e-3),
@@ -303,8 +396,12 @@ def main():
         "config": info,
         "roofline": {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": gbs / HBM_PEAK_GBS, "traffic": measured_traffic(args.workload, w.B),
-                     "kernel": "eval_batch_kernel", "kernel_ms_avg": ms_kernel, "kernel_ms_min": ms_kernel_min,
-                     "algorithmic_bytes_per_launch": w.B * info["bytes_per_candidate"]},
+                     "kernel": "eval_batch_kernel", "kernel_ms_avg": kt.avg, "kernel_ms_median": kt.median,
+                     "kernel_ms_min": kt.min,
+                     "algorithmic_bytes_per_launch": w.B * info["bytes_per_candidate"],
+                     # what a kernel that only reads the same three arrays reaches on this GPU
+                     "stream_read_GBs": read_gbs, "stream_read_workgroups": read_blocks,
+                     "frac_of_stream_read": gbs / read_gbs},
     }
     if not args.no_cpu_baseline:
         one, allc = cpu_baseline(w, cand, res)
@@ -314,23 +411,15 @@ def main():
     gh.free()
     torch.cuda.empty_cache()
     if not args.no_also and args.workload != 1:
-        w2, gh2, cand2, res2, info2, ms2, msk2, mskmin2, gbs2 = measure(moc, 1, max(args.steps, 50), args.warmup)
-        line["also"] = {"config": info2, "value": w2.B / (ms2 * 1e-3), "unit": "candidates/s", "ms_per_step": ms2,
-                        "kernel_ms_avg": msk2, "kernel_ms_min": mskmin2, "achieved_GBs": gbs2,
-                        "frac_of_hbm_peak": gbs2 / HBM_PEAK_GBS}
-        gh2.free()
-        del cand2
-        torch.cuda.empty_cache()
+        line["also"] = secondary(moc, 1, max(args.steps, 50), args.warmup)
         # the smallest configuration with n >= 1000: training-shaped graph, B = 65536
-        w3, gh3, cand3, res3, info3, ms3, msk3, mskmin3, gbs3 = measure(moc, 2, max(args.steps, 50), args.warmup)
-        line["also_n1000"] = {"config": info3, "value": w3.B / (ms3 * 1e-3), "unit": "candidates/s",
-                              "ms_per_step": ms3, "kernel_ms_avg": msk3, "kernel_ms_min": mskmin3,
-                              "achieved_GBs": gbs3, "frac_of_hbm_peak": gbs3 / HBM_PEAK_GBS}
-        gh3.free()
-        del cand3
+        line["also_n1000"] = secondary(moc, 2, max(args.steps, 50), args.warmup)
+        # the default workload's graph with the dense batch (nearly every copy live): how far the
+        # rate depends on the candidates having few copies beyond the first
+        line["also_dense"] = secondary(moc, args.workload, args.steps, args.warmup, batch=65536, dense=True)
     if not args.no_neighbours:
         torch.cuda.empty_cache()
-        line["neighbours"] = measure_neighbours(moc, max(3, args.steps // 4), 1)
+        line["neighbours"] = measure_neighbours(moc, max(3, args.steps // 4), 1, not args.no_cpu_baseline)
     print(json.dumps(line))
 
 

@@ -5,4 +5,4 @@ arithmetic of the evaluated method and imports neither of them.
 """
 from .graphs import Graph, graph_from_edges  # noqa: F401
 from .workloads import Workload, make_workload, workload_from_graph  # noqa: F401
-from .device import DeviceWorkload  # noqa: F401,E402
+from .device import DeviceWorkload, stream_read  # noqa: F401,E402

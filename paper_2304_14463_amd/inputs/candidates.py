@@ -21,6 +21,14 @@ order; it draws structure, it does not evaluate anything:
 * type B    : (b >= B/2) type A, then every start and end of an active copy is
               moved by U{-4..+4} with probability 1/4, clamped to [0, T).
 
+* dense     : (a batch of its own, for measuring how the evaluator's speed depends on how
+              many copies are live) every node is computed C times in a row: copy i >= 1 is
+              active with probability 7/8 and starts in the free slot pos + i; an active
+              copy is kept until the next active copy of its node starts, the last one until
+              C - 1 positions past the last consumer (so that the consumer's own later
+              copies are served too).  The first half of the batch is violation-free as it
+              stands, the second half is perturbed as type B.
+
 Every draw is hash3(seed, b, v, j) with a fixed counter j per decision, so the
 device generator (gen_candidates.hip) reproduces the same bits.
 """
@@ -86,7 +94,7 @@ def base_candidate(n, C, pos, out_ptr, cons_pos):
     return s, e, a
 
 
-def gen_candidates(seed, n, C, B_total, pos, out_ptr, cons_pos, win_hi, ncut, b0, count):
+def gen_candidates(seed, n, C, B_total, pos, out_ptr, cons_pos, win_hi, ncut, b0, count, dense=False):
     """Candidates b0 .. b0+count-1 of a batch of B_total.
 
     Returns (starts int32 [count][T], ends int32 [count][T], active uint8 [count][T]).
@@ -122,7 +130,16 @@ def gen_candidates(seed, n, C, B_total, pos, out_ptr, cons_pos, win_hi, ncut, b0
         e[:, 0] = end_default
         a[:, 0] = 1
         nc = int(ncut[v])
-        if nc >= 1:
+        if dense:
+            nxt = np.full(count, min(end_default + C - 1, T - 1), dtype=np.int64)   # end of the copy at hand
+            for i in range(C - 1, 0, -1):
+                keep = (draw(8 + i) & u64(7)) != u64(0)
+                a[:, i] = keep.astype(np.uint8)
+                s[:, i] = np.where(keep, pv + i, 0)
+                e[:, i] = np.where(keep, nxt, 0)
+                nxt = np.where(keep, pv + i, nxt)
+            e[:, 0] = nxt
+        elif nc >= 1:
             wh = int(win_hi[v])
             lo = np.zeros(count, dtype=np.int64)
             alive = np.ones(count, dtype=bool)

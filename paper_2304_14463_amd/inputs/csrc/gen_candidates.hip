@@ -22,7 +22,7 @@ __device__ __forceinline__ uint64_t mix64(uint64_t z) {
 __global__ void gen_candidates_kernel(uint64_t seed, int n, int C, int64_t B_total, const int32_t* __restrict__ pos,
                                       const int32_t* __restrict__ out_ptr, const int32_t* __restrict__ cons_pos,
                                       const int32_t* __restrict__ win_hi, const int32_t* __restrict__ ncut,
-                                      int64_t b0, int64_t count, int32_t* __restrict__ starts,
+                                      int64_t b0, int64_t count, int dense, int32_t* __restrict__ starts,
                                       int32_t* __restrict__ ends, uint8_t* __restrict__ active) {
   const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (gid >= count * n) return;
@@ -46,8 +46,17 @@ __global__ void gen_candidates_kernel(uint64_t seed, int n, int C, int64_t B_tot
   s[0] = pv; e[0] = end_default; a[0] = 1;
 
   const int nc = ncut[v], wh = win_hi[v];
+  if (dense) {   // every node computed C times in a row, each copy kept until the next one starts
+    int nxt = min(end_default + C - 1, T - 1);
+    for (int i = C - 1; i >= 1; --i) {
+      if ((draw(8 + i) & 7) == 0) continue;
+      a[i] = 1; s[i] = pv + i; e[i] = nxt;
+      nxt = pv + i;
+    }
+    e[0] = nxt;
+  }
   int lo = 0;
-  for (int i = 1; i < C && nc >= 1; ++i) {
+  for (int i = 1; i < C && nc >= 1 && !dense; ++i) {
     const int avail = nc - lo;
     const uint64_t gate = draw(2 * i), pick = draw(2 * i + 1);
     if (avail < 1 || (gate & 3) != 0) break;
@@ -75,18 +84,18 @@ __global__ void gen_candidates_kernel(uint64_t seed, int n, int C, int64_t B_tot
 }  // namespace
 
 // Fill starts/ends/active [count][n*C] (device) with candidates b0 .. b0+count-1 of a batch of
-// B_total.  Tables are device arrays as produced by inputs.candidates.candidate_tables.
+// B_total (dense != 0: the dense batch).  Tables are device arrays as produced by inputs.candidates.candidate_tables.
 // Returns the hipError_t of the launch (0 = success).
 extern "C" int mocgen_candidates(uint64_t seed, int32_t n, int32_t C, int64_t B_total, const int32_t* pos,
                                  const int32_t* out_ptr, const int32_t* cons_pos, const int32_t* win_hi,
-                                 const int32_t* ncut, int64_t b0, int64_t count, int32_t* starts, int32_t* ends,
-                                 uint8_t* active, void* hip_stream) {
+                                 const int32_t* ncut, int64_t b0, int64_t count, int32_t dense, int32_t* starts,
+                                 int32_t* ends, uint8_t* active, void* hip_stream) {
   if (count <= 0 || n <= 0) return 0;
   const int64_t threads = count * n;
   const int block = 256;
   const int64_t grid = (threads + block - 1) / block;
   if (grid > 0x7FFFFFFF) return (int)hipErrorInvalidValue;
   hipLaunchKernelGGL(gen_candidates_kernel, dim3((unsigned)grid), dim3(block), 0, static_cast<hipStream_t>(hip_stream),
-                     seed, n, C, B_total, pos, out_ptr, cons_pos, win_hi, ncut, b0, count, starts, ends, active);
+                     seed, n, C, B_total, pos, out_ptr, cons_pos, win_hi, ncut, b0, count, dense, starts, ends, active);
   return (int)hipGetLastError();
 }

@@ -18,8 +18,10 @@ def lib():
             raise FileNotFoundError(f"{LIB_PATH} is not built; run python -m paper_2304_14463_amd.build")
         L = ctypes.CDLL(LIB_PATH)
         VP, I32, I64, U64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_uint64
-        L.mocgen_candidates.argtypes = [U64, I32, I32, I64, VP, VP, VP, VP, VP, I64, I64, VP, VP, VP, VP]
+        L.mocgen_candidates.argtypes = [U64, I32, I32, I64, VP, VP, VP, VP, VP, I64, I64, I32, VP, VP, VP, VP]
         L.mocgen_candidates.restype = ctypes.c_int
+        L.mocgen_stream_read.argtypes = [VP, U64, VP, U64, VP, U64, I32, VP, VP]
+        L.mocgen_stream_read.restype = ctypes.c_int
         _lib = L
     return _lib
 
@@ -52,8 +54,26 @@ class DeviceWorkload:
             stream = torch.cuda.current_stream()
         rc = lib().mocgen_candidates(w.seed & ((1 << 64) - 1), w.n, w.C, w.B, self.pos.data_ptr(),
                                      self.out_ptr.data_ptr(), self.cons_pos.data_ptr(), self.win_hi.data_ptr(),
-                                     self.ncut.data_ptr(), b0, count, s.data_ptr(), e.data_ptr(), a.data_ptr(),
+                                     self.ncut.data_ptr(), b0, count, int(w.dense), s.data_ptr(), e.data_ptr(), a.data_ptr(),
                                      ctypes.c_void_p(stream.cuda_stream))
         if rc != 0:
             raise RuntimeError(f"mocgen_candidates: hipError {rc}")
         return s, e, a
+
+
+def stream_read(tensors, blocks, out=None, stream=None):
+    """Queues one launch that reads the three CUDA tensors once and does nothing else
+    (csrc/stream_read.hip): what a read of these bytes costs on this GPU at the least.
+    Returns the scratch tensor the kernel writes one word per thread to."""
+    import torch
+    x0, x1, x2 = tensors
+    if out is None:
+        out = torch.empty(blocks * 1024, dtype=torch.int32, device=x0.device)
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    nbytes = lambda t: t.numel() * t.element_size()
+    rc = lib().mocgen_stream_read(x0.data_ptr(), nbytes(x0), x1.data_ptr(), nbytes(x1), x2.data_ptr(), nbytes(x2),
+                                  int(blocks), out.data_ptr(), ctypes.c_void_p(stream.cuda_stream))
+    if rc != 0:
+        raise RuntimeError(f"mocgen_stream_read: hipError {rc}")
+    return out

@@ -38,6 +38,7 @@ class Workload:
     win_hi: np.ndarray
     ncut: np.ndarray
     R: int = 0  # neighbourhood radius (0: plain evaluation workload)
+    dense: bool = False  # the dense batch: nearly every copy live (see candidates.py)
 
     @property
     def n(self):
@@ -58,7 +59,7 @@ class Workload:
         if count is None:
             count = self.B - b0
         return gen_candidates(self.seed, self.n, self.C, self.B, self.pos, self.out_ptr,
-                              self.cons_pos, self.win_hi, self.ncut, b0, count)
+                              self.cons_pos, self.win_hi, self.ncut, b0, count, dense=self.dense)
 
 
 def workload_from_graph(name, seed, graph, C, B, pct, R=0, order=None):
@@ -78,8 +79,14 @@ def _layered(cfg, n, layers, dmin, dmax, skew, single_sink, target_m, size_fn, d
     return seed, G.graph_from_edges(n, edges, size, dur)
 
 
-def make_workload(cfg: int, B: int | None = None) -> Workload:
-    """cfg 0..4; B overrides the batch size (the type-A/type-B split follows B)."""
+def make_workload(cfg: int, B: int | None = None, dense: bool = False) -> Workload:
+    """cfg 0..4; B overrides the batch size (the type-A/type-B split follows B); dense: same
+    graph, order and budget with the dense candidate batch."""
+    if dense:
+        w = make_workload(cfg, B)
+        w.dense = True
+        w.name += "-dense"
+        return w
     if cfg == 0:
         seed, g = _layered(0, 50, 10, 1, 3, False, True, None,
                            lambda s, n: G.uniform_ints(s, G.S_SIZE, n, 1, 100), 50)

@@ -29,11 +29,11 @@ def run_eval(moc, gh, s, e, a):
 
 
 # ---------------------------------------------------------------- the device generator emits the host's bits
-@pytest.mark.parametrize("cfg", [0, 1, 2, 3, 4])
-def test_device_generator_matches_host(workloads, cfg):
+@pytest.mark.parametrize("cfg,dense", [(0, False), (1, False), (2, False), (3, False), (4, False), (1, True), (4, True)])
+def test_device_generator_matches_host(workloads, cfg, dense):
     import torch
-    from paper_2304_14463_amd.inputs import DeviceWorkload
-    w = workloads(cfg)
+    from paper_2304_14463_amd.inputs import DeviceWorkload, make_workload
+    w = make_workload(cfg, dense=True) if dense else workloads(cfg)
     dw = DeviceWorkload(w)
     count = min(w.B, 2048 if cfg < 4 else 256)
     for b0 in (0, w.B // 2 - count // 2, w.B - count):
@@ -111,6 +111,39 @@ def test_eval_parity_largest_workload_every_candidate(moc, workloads):
     del ds, de, da
     gh.free()
     torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("cfg,B", [(1, 4096), (2, 4096), (4, 2048)])
+def test_eval_parity_dense_batch(moc, cfg, B):
+    """The dense batch (more than 90 % of all copies live, every node computed up to C times):
+    the paths for copies beyond the first carry most of the work."""
+    from paper_2304_14463_amd.inputs import DeviceWorkload, make_workload
+    w = make_workload(cfg, B, dense=True)
+    gh = upload(moc, w)
+    ds, de, da = DeviceWorkload(w).candidates()
+    gpu = moc.results_to_numpy(moc.moc_eval_batch(gh, ds, de, da))
+    s, e, a = ds.cpu().numpy(), de.cpu().numpy(), da.cpu().numpy()
+    assert (a != 0).mean() > 0.9
+    ref = oracle_eval_parallel(w.graph, w.budget, w.C, s, e, a)
+    assert_results_equal(gpu, ref, f"cfg {cfg} dense")
+    assert (ref[: B // 2, F["violations"]] == 0).all() and (ref[B // 2:, F["violations"]] > 0).mean() > 0.9
+    gh.free()
+
+
+def test_stream_read_runs(moc):
+    """The read-only kernel the benchmark times beside the evaluator: it reads three arrays and
+    writes one word per thread; the XOR of what it wrote is the XOR of the words it read."""
+    import torch
+    from paper_2304_14463_amd.inputs import stream_read
+    g = torch.Generator(device="cuda").manual_seed(5)
+    x = [torch.randint(-2**31, 2**31 - 1, (n,), dtype=torch.int32, device="cuda", generator=g) for n in (40000, 40004, 8)]
+    out = stream_read(x, 7)
+    torch.cuda.synchronize()
+    want = 0
+    for t in x:
+        n = t.numel() // 4 * 4
+        want ^= int(np.bitwise_xor.reduce(t[:n].cpu().numpy().view(np.uint32)))
+    assert int(np.bitwise_xor.reduce(out.cpu().numpy().view(np.uint32))) == want
 
 
 # ---------------------------------------------------------------- edge cases

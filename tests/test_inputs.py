@@ -53,3 +53,25 @@ def test_candidates_are_deterministic_and_chunkable(workloads, cfg):
     assert (a.reshape(6, w.n, w.C)[:, :, 0] == 1).all()
     assert s.min() >= 0 and max(s.max(), e.max()) < w.T
     assert (s[0] != s[1]).any() or (e[0] != e[1]).any()
+
+
+@pytest.mark.parametrize("cfg", [0, 4])
+def test_dense_batch_structure(cfg):
+    """The dense batch: nearly every copy active, copies of a node in a row on the node's own
+    free slots, each kept until the next one starts."""
+    w = make_workload(cfg, 64, dense=True)
+    s, e, a = w.candidates(0, 64)
+    n, C, T = w.n, w.C, w.T
+    A = a.reshape(64, n, C) != 0
+    S, E = s.reshape(64, n, C), e.reshape(64, n, C)
+    assert A[:, :, 0].all() and 0.8 < A[:, :, 1:].mean() < 0.95
+    first = slice(0, 32)                                           # not perturbed
+    want = np.broadcast_to(w.pos[None, :, None] + np.arange(C)[None, None, :], S[first].shape)
+    assert (S[first][A[first]] == want[A[first]]).all()
+    for b in range(4):
+        for v in range(0, n, max(1, n // 50)):
+            act = [i for i in range(C) if A[b, v, i]]
+            for i, j in zip(act, act[1:]):
+                assert E[b, v, i] == S[b, v, j]
+            assert E[b, v, act[-1]] == min(T - 1, max(w.pos[v], w.cons_pos[w.out_ptr[v]:w.out_ptr[v + 1]].max(initial=0)) + C - 1)
+    assert s.min() >= 0 and max(s.max(), e.max()) < T
