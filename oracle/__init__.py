@@ -81,6 +81,21 @@ def evaluate(g, budget, C, starts, ends, active, T=None):
     return out
 
 
+def evaluate_staged(g, budget, C, index, starts, ends, active):
+    """Evaluate candidates [B][n*C] in the stage-restricted domain of Section 2.3: positions in
+    [0, n(n+1)/2), node v only at slot index[v] of a stage, first copy at slot index[v] of stage
+    index[v].  Returns int64 [B][9], columns = FIELDS."""
+    K = g.n * C
+    s, e, a = _cand(starts, np.int32, K), _cand(ends, np.int32, K), _cand(active, np.uint8, K)
+    idx = np.ascontiguousarray(index, dtype=np.int32).reshape(g.n)
+    B = s.shape[0]
+    out = np.zeros((B, len(FIELDS)), dtype=np.int64)
+    keep, ga = _graph_args(g)
+    lib().orc_eval_staged(*ga, ctypes.c_int64(budget), ctypes.c_int32(C), _p(idx, ctypes.c_int32), ctypes.c_int64(B),
+                          _p(s, ctypes.c_int32), _p(e, ctypes.c_int32), _p(a, ctypes.c_uint8), _p(out, ctypes.c_int64))
+    return out
+
+
 def profile(g, budget, C, starts, ends, active, T=None):
     """One candidate: (result row, memory in use at every position)."""
     K = g.n * C

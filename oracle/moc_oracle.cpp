@@ -62,14 +62,17 @@ inline bool well_formed(const Problem& p, int32_t s, int32_t e, uint8_t a) {
   return a != 0 && 0 <= s && s <= e && e <= p.T - 1;
 }
 
+// in_domain (may be null: every position of [0,T) is allowed): per copy, whether its start is a
+// value the variable may take at all (Section 2.3 restricts the starts to particular events).
+// A start outside its domain is treated like one outside [0,T): the copy is not usable.
 void evaluate(const Problem& p, const int32_t* s, const int32_t* e, const uint8_t* a, Scratch& w,
-              int64_t* out, int64_t* profile_out) {
+              int64_t* out, int64_t* profile_out, const char* in_domain = nullptr) {
   const int K = p.n * p.C;
   w.live.assign(K, 0);
   int64_t v_form = 0, v_first = 0, v_order = 0, v_start = 0, v_prec = 0, duration = 0;
 
   for (int k = 0; k < K; ++k) {
-    w.live[k] = well_formed(p, s[k], e[k], a[k]);
+    w.live[k] = well_formed(p, s[k], e[k], a[k]) && (!in_domain || in_domain[k]);
     if (a[k] != 0 && !w.live[k]) ++v_form;          // Eq. (2), Eq. (8)
     if (a[k] != 0) duration += p.dur[k / p.C];      // Eq. (1)
   }
@@ -157,6 +160,50 @@ void orc_profile(int32_t n, const int32_t* in_ptr, const int32_t* in_idx, const 
   Problem p{n, in_ptr, in_idx, size, dur, budget, C, T};
   Scratch w;
   evaluate(p, starts, ends, active, w, out, profile);
+}
+
+// Stage-restricted domain (Section 2.3, "Complexity Reduction by Enforcing an Initial
+// Topological Ordering").  Events are grouped into n stages, stage j (0-based) holding the
+// j + 1 positions j(j+1)/2 .. j(j+1)/2 + j, so that the domain has n(n+1)/2 positions.  With
+// index[v] = k the place of node v in the given topological order, v may be computed only at
+// event k of a stage (0-based slot k, which exists in stages j >= k), and its first interval
+// starts at slot k of stage k, the last position of that stage: a fixed value, not a variable.
+// Readings: a start that is not one of these values is outside the variable's domain, as a
+// position outside [0,T) is in the plain model: the copy counts as one violation of Eq. (8),
+// takes part in nothing else and still counts in Eq. (1).  Ends may be any position of the
+// domain.  Eq. (6) is kept as it is evaluated elsewhere (copies of one node can still share
+// an event); everything else is Eq. (1)-(8) on T = n(n+1)/2 positions.
+static int stage_of(int64_t pos) {   // the stage whose positions include pos >= 0
+  int j = 0;
+  while ((int64_t)(j + 1) * (j + 2) / 2 <= pos) ++j;
+  return j;
+}
+
+// Evaluate B candidates in the stage-restricted domain; index[v] in [0,n) is a permutation that
+// orders the nodes topologically.  starts/ends/active are [B][n*C]; out is [B][R_FIELDS].
+void orc_eval_staged(int32_t n, const int32_t* in_ptr, const int32_t* in_idx, const int32_t* size,
+                     const int32_t* dur, int64_t budget, int32_t C, const int32_t* index, int64_t B,
+                     const int32_t* starts, const int32_t* ends, const uint8_t* active, int64_t* out) {
+  const int64_t D = (int64_t)n * (n + 1) / 2;
+  Problem p{n, in_ptr, in_idx, size, dur, budget, C, (int32_t)D};
+  Scratch w;
+  const int64_t K = (int64_t)n * C;
+  std::vector<char> in_domain(K);
+  for (int64_t b = 0; b < B; ++b) {
+    const int32_t* s = starts + b * K;
+    for (int v = 0; v < n; ++v)
+      for (int i = 0; i < C; ++i) {
+        const int64_t pos = s[v * C + i];
+        bool ok = false;
+        if (pos >= 0 && pos < D) {
+          const int j = stage_of(pos);
+          const int64_t slot = pos - (int64_t)j * (j + 1) / 2;
+          ok = slot == index[v] && (i > 0 || j == index[v]);
+        }
+        in_domain[v * C + i] = ok;
+      }
+    evaluate(p, s, ends + b * K, active + b * K, w, out + b * R_FIELDS, nullptr, in_domain.data());
+  }
 }
 
 // Neighbourhood of one candidate by full re-evaluation.  Move index
