@@ -328,6 +328,58 @@ def cpu_baseline(w, cand, res, target_seconds=15.0):
              "sample": f"same {count} candidates split over {cores} host threads"})
 
 
+def measure_staged(moc, steps, warmup, with_cpu_baseline=True):
+    """moc_eval_batch_staged (stage-restricted domain of Section 2.3) on the n=1000 training-shaped
+    graph: 8192 staged candidates generated on the host, repeated to 65536 rows on the device."""
+    import numpy as np
+    import torch
+    from paper_2304_14463_amd.inputs import make_workload
+    from paper_2304_14463_amd.inputs.staged import gen_staged_candidates, staged_tables
+    w = make_workload(2)
+    g = w.graph
+    unique, reps = 8192, 8
+    tables = staged_tables(g, w.order)
+    s, e, a = gen_staged_candidates(w.seed, g, w.order, w.C, unique, 0, unique, tables)
+    gh = moc.moc_graph_upload(g.n, g.in_ptr, g.in_idx, g.size, g.dur, w.budget, w.C)
+    moc.moc_graph_set_order(gh, w.order)
+    ds, de, da = (torch.from_numpy(x).cuda().repeat(reps, 1) for x in (s, e, a))
+    B = unique * reps
+    out = moc.moc_eval_batch_staged(gh, ds, de, da)
+    for _ in range(warmup):
+        moc.moc_eval_batch_staged(gh, ds, de, da, out=out)
+    torch.cuda.synchronize()
+    stream = torch.cuda.current_stream()
+    ms = []
+    for _ in range(steps):
+        b, f = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        b.record(stream)
+        moc.moc_eval_batch_staged(gh, ds, de, da, out=out)
+        f.record(stream)
+        f.synchronize()
+        ms.append(b.elapsed_time(f))
+    kt = KernelTimes(ms)
+    res = moc.results_to_numpy(out)
+    line = {"workload": w.name + "-staged", "n": w.n, "m": w.m, "C": w.C, "positions": w.n * (w.n + 1) // 2, "B": B,
+            "distinct_candidates": unique, "kernel_ms_avg": kt.avg, "kernel_ms_median": kt.median, "kernel_ms_min": kt.min,
+            "candidates_per_s": B / (kt.median * 1e-3), "bytes_per_candidate": 9 * w.T + 24,
+            "achieved_GBs": B * (9 * w.T + 24) / (kt.median * 1e-3) / 1e9,
+            "frac_of_hbm_peak": B * (9 * w.T + 24) / (kt.median * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "frac_violation_free": float((res["violations"] == 0).mean())}
+    if with_cpu_baseline:
+        import oracle
+        count = 128
+        t0 = time.perf_counter()
+        ref = oracle.evaluate_staged(g, w.budget, w.C, tables[0], s[:count], e[:count], a[:count])
+        dt = time.perf_counter() - t0
+        ok = all((res[name][:count].astype(np.int64) == ref[:, i]).all()
+                 for i, name in enumerate(("peak", "duration", "violations", "feasible")))
+        line["cpu_baseline"] = {"value": count / dt, "unit": "candidates/s", "cores": 1, "kind": "oracle",
+                                "sample": f"first {count} candidates, single-threaded oracle.evaluate_staged",
+                                "matches_gpu": bool(ok)}
+    gh.free()
+    return line
+
+
 def cpu_baseline_neighbours(moc, w, gh, cand, target_seconds=10.0):
     """Times oracle.neighbours (full re-evaluation of every move, as it stands) on a sample of the
     moves of the first bases: every 16th move of base 0 on one thread, then every 16th move of
@@ -417,6 +469,9 @@ def main():
         # the default workload's graph with the dense batch (nearly every copy live): how far the
         # rate depends on the candidates having few copies beyond the first
         line["also_dense"] = secondary(moc, args.workload, args.steps, args.warmup, batch=65536, dense=True)
+    if not args.no_also:
+        torch.cuda.empty_cache()
+        line["staged"] = measure_staged(moc, max(5, args.steps // 2), 2, not args.no_cpu_baseline)
     if not args.no_neighbours:
         torch.cuda.empty_cache()
         line["neighbours"] = measure_neighbours(moc, max(3, args.steps // 4), 1, not args.no_cpu_baseline)

@@ -183,6 +183,44 @@ int moc_eval_batch_noalloc(const moc_graph* g, int64_t B, const int32_t* starts,
                            const uint8_t* active, moc_result* out, void* hip_stream);
 
 /*
+ * Give an uploaded graph the topological order that the stage-restricted
+ * domain of Section 2.3 is built on.
+ *   order   host, [n]: order[j] = the node with place j; a permutation of the
+ *           nodes in which every edge (u, v) has u before v
+ * May be called again with another order (synchronises the device first); not
+ * while another thread evaluates with this handle.
+ * Errors: MOC_EINVAL (not a permutation, or not topological), MOC_EDEVICE,
+ * MOC_ENOMEM, MOC_EHIP.
+ */
+int moc_graph_set_order(moc_graph* g, const int32_t* order);
+
+/*
+ * Evaluate B candidates in the stage-restricted domain (Section 2.3,
+ * "Complexity Reduction by Enforcing an Initial Topological Ordering").
+ * Positions are 0-based in [0, n(n+1)/2): stage j = 0..n-1 holds the j + 1
+ * positions j(j+1)/2 .. j(j+1)/2 + j (the paper's events, shifted by one).  A
+ * node with place k in the order of moc_graph_set_order may be computed only
+ * at slot k of a stage, i.e. at a position j(j+1)/2 + k with j >= k, and its
+ * first copy only at slot k of stage k (the paper's fixed s_v^1 = k'(k'+1)/2
+ * for the k'-th node, 1-based).  An active copy whose start is not such a
+ * position is outside its domain: like a position outside [0, T) in
+ * moc_eval_batch it counts as one violation of Eq. (8), is used by no other
+ * constraint and still counts in Eq. (1).  Ends may be any position of the
+ * domain.  Everything else, and the result, is as for moc_eval_batch with
+ * n(n+1)/2 positions in place of T; Eq. (6) is kept as it is there (here only
+ * copies of one node can share an event).
+ *   starts, ends   device, int32 [B][T] (T = n*C values per candidate)
+ *   active         device, uint8 [B][T]
+ *   out            device, moc_result [B], 8-byte aligned
+ * This call keeps 3.5 words per copy and one per node in LDS: T <= about
+ * 10000.  B == 0 is a no-op.
+ * Errors: MOC_EINVAL (also: no order set), MOC_EDEVICE, MOC_EOVERFLOW (T too
+ * large for this call), MOC_EHIP.
+ */
+int moc_eval_batch_staged(const moc_graph* g, int64_t B, const int32_t* starts, const int32_t* ends,
+                          const uint8_t* active, moc_result* out, void* hip_stream);
+
+/*
  * Score every single-field move of B base candidates.  Not part of the paper:
  * it is the neighbourhood a local search over the variables of Section 2.1
  * would scan.  Move index q = ((k*2 + field)*2R + d): copy k, field 0 = start,

@@ -251,6 +251,41 @@ int moc_graph_upload(int32_t n, const int32_t* in_ptr, const int32_t* in_idx, co
   }
 }
 
+int moc_graph_set_order(moc_graph* g, const int32_t* order) {
+  if (!g || !order) return MOC_EINVAL;
+  int dev = -1;
+  MOC_HIP(hipGetDevice(&dev));
+  if (dev != g->device) return MOC_EDEVICE;
+  const int n = g->view.n, m = g->view.m;
+  try {
+    std::vector<int32_t> place(n, -1);
+    for (int j = 0; j < n; ++j) {
+      if (order[j] < 0 || order[j] >= n || place[order[j]] >= 0) return MOC_EINVAL;   // not a permutation
+      place[order[j]] = j;
+    }
+    // topological: every edge (u, v) has u before v (the graph's arrays are read back from the device)
+    std::vector<int32_t> in_ptr(n + 1), in_idx(m);
+    MOC_HIP(hipMemcpy(in_ptr.data(), g->view.in_ptr, sizeof(int32_t) * (n + 1), hipMemcpyDeviceToHost));
+    if (m) MOC_HIP(hipMemcpy(in_idx.data(), g->view.in_idx, sizeof(int32_t) * m, hipMemcpyDeviceToHost));
+    for (int v = 0; v < n; ++v)
+      for (int q = in_ptr[v]; q < in_ptr[v + 1]; ++q)
+        if (place[in_idx[q]] >= place[v]) return MOC_EINVAL;
+    if (!g->place) {
+      void* p = nullptr;
+      const hipError_t e = hipMalloc(&p, sizeof(int32_t) * n);
+      if (e == hipErrorOutOfMemory) return MOC_ENOMEM;
+      if (e != hipSuccess) return moc_set_hip_error(e);
+      g->place = static_cast<int32_t*>(p);
+    } else {
+      MOC_HIP(hipDeviceSynchronize());   // launches that read the previous order have finished
+    }
+    MOC_HIP(hipMemcpy(g->place, place.data(), sizeof(int32_t) * n, hipMemcpyHostToDevice));
+    return MOC_OK;
+  } catch (const std::bad_alloc&) {
+    return MOC_ENOMEM;
+  }
+}
+
 int moc_graph_info(const moc_graph* g, int32_t* n, int32_t* m, int32_t* C, int32_t* T) {
   if (!g) return MOC_EINVAL;
   if (n) *n = g->view.n;
@@ -265,6 +300,7 @@ void moc_graph_free(moc_graph* g) {
   int cur = -1;
   if (hipGetDevice(&cur) == hipSuccess && cur == g->device) (void)hipDeviceSynchronize();
   for (int i = 0; i < g->n_allocs; ++i) (void)hipFree(g->allocs[i]);
+  if (g->place) (void)hipFree(g->place);
   delete g;
 }
 

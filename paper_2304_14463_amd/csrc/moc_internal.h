@@ -43,6 +43,7 @@ struct moc_graph {
   GraphView view;    // device pointers
   void* allocs[8];   // device allocations backing `view`, and `tickets`
   int n_allocs;
+  int32_t* place;    // device, [n]: place of every node in the order given to moc_graph_set_order; null before
   // Work counters of the evaluation kernel: kTicketSlots sets of kTicketGroups + 1 counters,
   // each counter on a 64-byte line of its own, all zero between launches (a launch leaves its
   // set at zero when it ends).  A set belongs to a stream: launches on one stream follow each

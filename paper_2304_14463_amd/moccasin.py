@@ -25,7 +25,7 @@ BEST_MOVE_DTYPE = np.dtype([("move", "<i4"), ("violations", "<i4"), ("peak", "<i
 TOGGLE_SCORE_DTYPE = np.dtype([("violations", "<i4"), ("peak", "<i4"), ("duration", "<i8")])
 DECODE_RESULT_DTYPE = np.dtype([("status", "<i4"), ("length", "<i4"), ("peak", "<i8"), ("duration", "<i8")])
 
-EXPORTS = ("moc_graph_upload", "moc_graph_info", "moc_eval_batch", "moc_eval_batch_noalloc", "moc_eval_neighbours", "moc_eval_toggles",
+EXPORTS = ("moc_graph_upload", "moc_graph_info", "moc_eval_batch", "moc_eval_batch_noalloc", "moc_graph_set_order", "moc_eval_batch_staged", "moc_eval_neighbours", "moc_eval_toggles",
            "moc_eval_cuts", "moc_search_cuts", "moc_search_moves", "moc_decode_batch", "moc_graph_free", "moc_strerror", "moc_last_hip_error")
 
 
@@ -53,6 +53,10 @@ def lib():
         L.moc_eval_batch.restype = ctypes.c_int
         L.moc_eval_batch_noalloc.argtypes = [VP, I64, VP, VP, VP, VP, VP]
         L.moc_eval_batch_noalloc.restype = ctypes.c_int
+        L.moc_graph_set_order.argtypes = [VP, VP]
+        L.moc_graph_set_order.restype = ctypes.c_int
+        L.moc_eval_batch_staged.argtypes = [VP, I64, VP, VP, VP, VP, VP]
+        L.moc_eval_batch_staged.restype = ctypes.c_int
         L.moc_eval_neighbours.argtypes = [VP, I64, VP, VP, VP, I32, VP, VP, VP]
         L.moc_eval_neighbours.restype = ctypes.c_int
         L.moc_eval_toggles.argtypes = [VP, I64, VP, VP, VP, VP, VP]
@@ -164,6 +168,25 @@ def moc_eval_batch_noalloc(g: Graph, starts, ends, active, out, stream=None):
         raise ValueError("out must be a contiguous CUDA tensor of at least B * 24 bytes")
     code = lib().moc_eval_batch_noalloc(g._h, B, ps, pe, pa, ctypes.c_void_p(out.data_ptr()), _stream_handle(stream))
     _check(code, "moc_eval_batch_noalloc")
+    return out
+
+
+def moc_graph_set_order(g: Graph, order):
+    """Give the graph the topological order of the stage-restricted domain (host array [n])."""
+    order = _host(order, g.n)
+    _check(lib().moc_graph_set_order(g._h, order.ctypes.data), "moc_graph_set_order")
+
+
+def moc_eval_batch_staged(g: Graph, starts, ends, active, out=None, stream=None):
+    """Evaluate B candidates in the stage-restricted domain; returns a uint8 CUDA tensor [B][24]
+    of moc_result records."""
+    import torch
+    B = starts.numel() // g.T if g.T else 0
+    ps, pe, pa = _cand_ptrs(g, B, starts, ends, active)
+    if out is None:
+        out = torch.empty((B, RESULT_DTYPE.itemsize), dtype=torch.uint8, device=starts.device)
+    code = lib().moc_eval_batch_staged(g._h, B, ps, pe, pa, ctypes.c_void_p(out.data_ptr()), _stream_handle(stream))
+    _check(code, "moc_eval_batch_staged")
     return out
 
 
