@@ -151,7 +151,7 @@ def toggles(g, budget, C, starts, ends, active, T=None):
     return scores
 
 
-def cuts(g, budget, C, starts, ends, active, T=None, with_at_peak=False):
+def cuts(g, budget, C, starts, ends, active, T=None, with_at_peak=False, mode=0):
     """Scores of the m*C cut-and-recompute moves of one candidate (in-edge x in CSR order,
     consumer copy i; q = x*C + i) by full re-evaluation of the edited candidate:
     int64 [m*C][3] = (violations, peak, duration), (-1, -1, 0) where not applicable.
@@ -165,11 +165,12 @@ def cuts(g, budget, C, starts, ends, active, T=None, with_at_peak=False):
     scores = np.zeros((m * C, 4), dtype=np.int64)
     keep, ga = _graph_args(g)
     lib().orc_cuts(*ga, ctypes.c_int64(budget), ctypes.c_int32(C), ctypes.c_int32(T),
-                   _p(s, ctypes.c_int32), _p(e, ctypes.c_int32), _p(a, ctypes.c_uint8), _p(scores, ctypes.c_int64))
+                   _p(s, ctypes.c_int32), _p(e, ctypes.c_int32), _p(a, ctypes.c_uint8), _p(scores, ctypes.c_int64),
+                   ctypes.c_int32(mode))
     return scores if with_at_peak else np.ascontiguousarray(scores[:, :3])
 
 
-def cut_apply(g, C, starts, ends, active, x, i, T=None):
+def cut_apply(g, C, starts, ends, active, x, i, T=None, mode=0):
     """The candidate after the cut for in-edge x and consumer copy i: (applicable, s, e, a)."""
     K = g.n * C
     T = K if T is None else T
@@ -178,11 +179,11 @@ def cut_apply(g, C, starts, ends, active, x, i, T=None):
     keep, ga = _graph_args(g)
     ok = lib().orc_cut_apply(*ga, ctypes.c_int32(C), ctypes.c_int32(T), _p(s, ctypes.c_int32),
                              _p(e, ctypes.c_int32), _p(a, ctypes.c_uint8), ctypes.c_int32(x), ctypes.c_int32(i),
-                             _p(s2, ctypes.c_int32), _p(e2, ctypes.c_int32), _p(a2, ctypes.c_uint8))
+                             _p(s2, ctypes.c_int32), _p(e2, ctypes.c_int32), _p(a2, ctypes.c_uint8), ctypes.c_int32(mode))
     return bool(ok), s2, e2, a2
 
 
-def search_cuts(g, budget, C, starts, ends, active, max_steps, T=None):
+def search_cuts(g, budget, C, starts, ends, active, max_steps, T=None, mode=0):
     """Greedy descent by cuts on one candidate: (steps applied, s, e, a) after up to max_steps."""
     K = g.n * C
     T = K if T is None else T
@@ -192,7 +193,7 @@ def search_cuts(g, budget, C, starts, ends, active, max_steps, T=None):
     keep, ga = _graph_args(g)
     steps = lib().orc_search_cuts(*ga, ctypes.c_int64(budget), ctypes.c_int32(C), ctypes.c_int32(T),
                                   _p(s, ctypes.c_int32), _p(e, ctypes.c_int32), _p(a, ctypes.c_uint8),
-                                  ctypes.c_int32(max_steps))
+                                  ctypes.c_int32(max_steps), ctypes.c_int32(mode))
     return int(steps), s, e, a
 
 
@@ -217,6 +218,68 @@ def search_moves(g, budget, C, starts, ends, active, R, max_steps, T=None):
         (s if field == 0 else e)[k] += d - R if d < R else d - R + 1
         applied += 1
     return applied, s, e
+
+
+def merge_candidates(C, starts, ends, active, T, K):
+    """The merge moves of one candidate, at most K of them: for every live copy, in order of its
+    index, that has an earlier live copy of the same node, the candidate in which the nearest
+    such earlier copy is kept until the later of the two ends and the copy itself is switched
+    off (the node is computed once less, Eq. (1), and its output is held across the gap instead,
+    Eq. (4)).  Returns (copy indices [count], starts, ends, active [count][n*C])."""
+    s, e, a = (np.asarray(x).reshape(-1) for x in (starts, ends, active))
+    live = (a != 0) & (s >= 0) & (s <= e) & (e <= T - 1)
+    picks, S, E, A = [], [], [], []
+    for k in range(len(s)):
+        if len(picks) == K:
+            break
+        if not live[k]:
+            continue
+        v, i = divmod(k, C)
+        prev = [v * C + j for j in range(i) if live[v * C + j]]
+        if not prev:
+            continue
+        s2, e2, a2 = s.copy(), e.copy(), a.copy()
+        e2[prev[-1]] = max(e2[prev[-1]], e2[k])
+        a2[k] = 0
+        picks.append(k)
+        S.append(s2); E.append(e2); A.append(a2)
+    n = len(s)
+    return (np.array(picks, np.int64), np.array(S, np.int32).reshape(-1, n), np.array(E, np.int32).reshape(-1, n),
+            np.array(A, np.uint8).reshape(-1, n))
+
+
+def search_merges(g, budget, C, starts, ends, active, max_steps, K, T=None):
+    """Descent by merges on one candidate (the duration-reducing half of a local search: Phase 2
+    of Section 2.4 minimises Eq. (1) subject to everything else): up to max_steps times, evaluate
+    the first K merge moves, and apply the one whose result is feasible (no violation, peak
+    within the budget) with the lowest duration, then the lowest peak, then the lowest copy
+    index; stop when none is feasible.  Returns (steps applied, s, e, a)."""
+    K_ = g.n * C
+    T = K_ if T is None else T
+    s = np.array(starts, dtype=np.int32).reshape(K_).copy()
+    e = np.array(ends, dtype=np.int32).reshape(K_).copy()
+    a = np.array(active, dtype=np.uint8).reshape(K_).copy()
+    applied = 0
+    for _ in range(max_steps):
+        picks, S, E, A = merge_candidates(C, s, e, a, T, K)
+        if len(picks) == 0:
+            break
+        res = evaluate(g, budget, C, S, E, A, T=T)
+        ok = np.flatnonzero(res[:, FIELDS.index("feasible")] == 1)
+        if ok.size == 0:
+            break
+        best = min(ok, key=lambda r: (res[r, FIELDS.index("duration")], res[r, FIELDS.index("peak")], picks[r]))
+        s, e, a = S[best].copy(), E[best].copy(), A[best].copy()
+        applied += 1
+    return applied, s, e, a
+
+
+def search_two_phase(g, budget, C, starts, ends, active, max_cuts, max_merges, K, T=None):
+    """Phase 1: descent by cuts that keep the inputs (search_cuts, mode 1) towards the budget;
+    Phase 2: descent by merges from there.  Returns (cuts applied, merges applied, s, e, a)."""
+    k1, s, e, a = search_cuts(g, budget, C, starts, ends, active, max_cuts, T=T, mode=1)
+    k2, s, e, a = search_merges(g, budget, C, s, e, a, max_merges, K, T=T)
+    return k1, k2, s, e, a
 
 
 def decode(g, C, starts, active, T=None):

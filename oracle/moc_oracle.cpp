@@ -299,7 +299,13 @@ void orc_toggles(int32_t n, const int32_t* in_ptr, const int32_t* in_idx, const 
 //   e' = the last start, in (s_k, p), of a live copy of a consumer of u; s_k if there is none.
 // Copy k keeps [s_k, e'], copy j becomes active with [p, e_k].  Returns 0 (nothing changed) if
 // the consumer copy is not live or k, j or p does not exist.
-static int apply_cut(const Problem& p, int x, int i, int32_t* s, int32_t* e, uint8_t* a) {
+// mode 1 (keep the inputs instead of looking for a place where they are held): p is the last
+// position in (s_k, t) at which no live copy starts and every predecessor w of u is either held
+// (a live copy with s_w < p <= e_w) or has a live copy that ends before p; for each predecessor
+// that is not held, its live copy with the largest end below p (the highest index among equals)
+// is kept until p.  Small inputs are then carried across the stretch on which the large output
+// is dropped.
+static int apply_cut(const Problem& p, int x, int i, int32_t* s, int32_t* e, uint8_t* a, int mode = 0) {
   const int C = p.C, T = p.T;
   auto live = [&](int c) { return a[c] && s[c] >= 0 && s[c] <= e[c] && e[c] <= T - 1; };
   int v = 0;
@@ -329,9 +335,37 @@ static int apply_cut(const Problem& p, int x, int i, int32_t* s, int32_t* e, uin
     }
     return true;
   };
+  auto held_at = [&](int w, int at) {
+    for (int q = 0; q < C; ++q) {
+      const int cw = w * C + q;
+      if (live(cw) && s[cw] < at && at <= e[cw]) return true;
+    }
+    return false;
+  };
+  auto copy_to_keep = [&](int w, int at) {   // live copy of w with the largest end below at, -1 if none
+    int best = -1;
+    for (int q = 0; q < C; ++q) {
+      const int cw = w * C + q;
+      if (live(cw) && e[cw] < at && (best < 0 || e[cw] >= e[best])) best = cw;
+    }
+    return best;
+  };
+  auto inputs_can_be_had = [&](int at) {
+    for (int y = p.in_ptr[u]; y < p.in_ptr[u + 1]; ++y)
+      if (!held_at(p.in_idx[y], at) && copy_to_keep(p.in_idx[y], at) < 0) return false;
+    return true;
+  };
   int pos = t - 1;
-  while (pos > s[k] && (taken[pos] || !inputs_held(pos))) --pos;
+  if (mode == 0)
+    while (pos > s[k] && (taken[pos] || !inputs_held(pos))) --pos;
+  else
+    while (pos > s[k] && (taken[pos] || !inputs_can_be_had(pos))) --pos;
   if (pos <= s[k]) return 0;
+  if (mode == 1)
+    for (int y = p.in_ptr[u]; y < p.in_ptr[u + 1]; ++y) {
+      const int w = p.in_idx[y];
+      if (!held_at(w, pos)) e[copy_to_keep(w, pos)] = pos;   // a predecessor listed twice is held the second time
+    }
   int last_use = s[k];
   for (int w = 0; w < p.n; ++w)
     for (int y = p.in_ptr[w]; y < p.in_ptr[w + 1]; ++y)
@@ -351,13 +385,13 @@ static int apply_cut(const Problem& p, int x, int i, int32_t* s, int32_t* e, uin
 // is applicable, 0 otherwise (outputs = inputs).
 int orc_cut_apply(int32_t n, const int32_t* in_ptr, const int32_t* in_idx, const int32_t* size, const int32_t* dur,
                   int32_t C, int32_t T, const int32_t* starts, const int32_t* ends, const uint8_t* active,
-                  int32_t x, int32_t i, int32_t* out_s, int32_t* out_e, uint8_t* out_a) {
+                  int32_t x, int32_t i, int32_t* out_s, int32_t* out_e, uint8_t* out_a, int32_t mode) {
   Problem p{n, in_ptr, in_idx, size, dur, 0, C, T};
   const int K = n * C;
   std::copy(starts, starts + K, out_s);
   std::copy(ends, ends + K, out_e);
   std::copy(active, active + K, out_a);
-  return apply_cut(p, x, i, out_s, out_e, out_a);
+  return apply_cut(p, x, i, out_s, out_e, out_a, mode);
 }
 
 // Number of positions at which a profile reaches at least `level`.
@@ -372,7 +406,7 @@ static int64_t positions_at(const std::vector<int64_t>& prof, int T, int64_t lev
 // given) by full re-evaluation, q = x*C + i; (-1, -1, 0, 0) where not applicable.
 void orc_cuts(int32_t n, const int32_t* in_ptr, const int32_t* in_idx, const int32_t* size, const int32_t* dur,
               int64_t budget, int32_t C, int32_t T, const int32_t* starts, const int32_t* ends,
-              const uint8_t* active, int64_t* scores) {
+              const uint8_t* active, int64_t* scores, int32_t mode) {
   Problem p{n, in_ptr, in_idx, size, dur, budget, C, T};
   Scratch w;
   const int K = n * C, m = in_ptr[n];
@@ -388,7 +422,7 @@ void orc_cuts(int32_t n, const int32_t* in_ptr, const int32_t* in_idx, const int
       std::copy(ends, ends + K, e.begin());
       std::copy(active, active + K, a.begin());
       int64_t* out = scores + 4 * ((int64_t)x * C + i);
-      if (!apply_cut(p, x, i, s.data(), e.data(), a.data())) {
+      if (!apply_cut(p, x, i, s.data(), e.data(), a.data(), mode)) {
         out[0] = -1; out[1] = -1; out[2] = 0; out[3] = 0;
         continue;
       }
@@ -408,7 +442,7 @@ void orc_cuts(int32_t n, const int32_t* in_ptr, const int32_t* in_idx, const int
 // Returns the number of cuts applied.
 int orc_search_cuts(int32_t n, const int32_t* in_ptr, const int32_t* in_idx, const int32_t* size, const int32_t* dur,
                     int64_t budget, int32_t C, int32_t T, int32_t* starts, int32_t* ends, uint8_t* active,
-                    int32_t max_steps) {
+                    int32_t max_steps, int32_t mode) {
   Problem p{n, in_ptr, in_idx, size, dur, budget, C, T};
   Scratch w;
   const int K = n * C, m = in_ptr[n];
@@ -428,7 +462,7 @@ int orc_search_cuts(int32_t n, const int32_t* in_ptr, const int32_t* in_idx, con
         std::copy(starts, starts + K, s.begin());
         std::copy(ends, ends + K, e.begin());
         std::copy(active, active + K, a.begin());
-        if (!apply_cut(p, x, i, s.data(), e.data(), a.data())) continue;
+        if (!apply_cut(p, x, i, s.data(), e.data(), a.data(), mode)) continue;
         evaluate(p, s.data(), e.data(), a.data(), w, res, prof.data());
         const int64_t at = positions_at(prof, T, now_peak);
         if (best_x < 0 || res[R_VIOLATIONS] < best_v ||
@@ -445,7 +479,7 @@ int orc_search_cuts(int32_t n, const int32_t* in_ptr, const int32_t* in_idx, con
     const bool better = best_v < now_v ||
                         (best_v == now_v && (then_p < now_p || (then_p == now_p && now_peak > budget && best_at < now_at)));
     if (!better) break;
-    apply_cut(p, best_x, best_i, starts, ends, active);
+    apply_cut(p, best_x, best_i, starts, ends, active, mode);
     ++applied;
   }
   return applied;
