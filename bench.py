@@ -380,6 +380,48 @@ def measure_staged(moc, steps, warmup, with_cpu_baseline=True):
     return line
 
 
+def measure_two_phase(moc, cfg, walkers, max_cuts, max_merges, K):
+    """moc_search_two_phase from the violation-free candidates of a workload: how many walkers
+    end within the budget, at what increase of the total duration over the plain schedule (the
+    paper's TDI %), and whether every result decodes to a valid sequence of that cost."""
+    import numpy as np
+    import torch
+    from paper_2304_14463_amd.inputs import DeviceWorkload, make_workload
+    w = make_workload(cfg, 4 * walkers)
+    g = w.graph
+    gh = moc.moc_graph_upload(g.n, g.in_ptr, g.in_idx, g.size, g.dur, w.budget, w.C)
+    ds, de, da = DeviceWorkload(w).candidates(0, 2 * walkers)       # the first half of a batch: no perturbed rows
+    ev = moc.results_to_numpy(moc.moc_eval_batch(gh, ds, de, da))
+    clean = torch.from_numpy((ev["violations"] == 0).nonzero()[0]).cuda()
+    pick = clean[torch.arange(walkers, device="cuda") % clean.numel()]
+    ws, we, wa = ds[pick].contiguous(), de[pick].contiguous(), da[pick].contiguous()
+    base = w.base()
+    for x, row in zip((ws, we, wa), base):
+        x[0] = torch.from_numpy(row).cuda()                          # walker 0: the plain schedule itself
+    ev0 = moc.results_to_numpy(moc.moc_eval_batch(gh, ws, we, wa))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    cuts, merges = moc.moc_search_two_phase(gh, ws, we, wa, max_cuts, max_merges, K)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3
+    ev1 = moc.results_to_numpy(moc.moc_eval_batch(gh, ws, we, wa))
+    cert = moc.results_to_numpy(moc.moc_decode_batch(gh, ws, wa, want_seq=False)[0], moc.DECODE_RESULT_DTYPE)
+    certified = bool(((cert["status"] == 1) & (cert["duration"] == ev1["duration"]) & (cert["peak"] <= ev1["peak"])).all())
+    total_w = float(g.dur.sum())
+    tdi = 100.0 * (ev1["duration"] / total_w - 1.0)
+    ok = ev1["feasible"] == 1
+    gh.free()
+    return {"workload": w.name, "n": w.n, "m": w.m, "C": w.C, "budget_pct_of_no_remat_peak": w.pct, "walkers": walkers,
+            "distinct_starts": int(clean.numel()), "max_cuts": max_cuts, "max_merges": max_merges, "K": K,
+            "ms_total": ms, "mean_cuts_applied": float(cuts.float().mean()), "mean_merges_applied": float(merges.float().mean()),
+            "frac_feasible_before": float(ev0["feasible"].mean()), "frac_feasible_after": float(ok.mean()),
+            "violations_after": int(ev1["violations"].max()), "decoded_and_certified": certified,
+            "tdi_pct_mean_of_feasible": float(tdi[ok].mean()) if ok.any() else None,
+            "tdi_pct_min_of_feasible": float(tdi[ok].min()) if ok.any() else None,
+            "tdi_pct_plain_schedule_walker": float(tdi[0]), "plain_schedule_walker_feasible": bool(ok[0]),
+            "mean_peak_pct_of_no_remat_peak_after": float(100.0 * ev1["peak"].mean() / w.no_remat_peak)}
+
+
 def cpu_baseline_neighbours(moc, w, gh, cand, target_seconds=10.0):
     """Times oracle.neighbours (full re-evaluation of every move, as it stands) on a sample of the
     moves of the first bases: every 16th move of base 0 on one thread, then every 16th move of
@@ -472,6 +514,9 @@ def main():
     if not args.no_also:
         torch.cuda.empty_cache()
         line["staged"] = measure_staged(moc, max(5, args.steps // 2), 2, not args.no_cpu_baseline)
+    if not args.no_also:
+        torch.cuda.empty_cache()
+        line["two_phase"] = [measure_two_phase(moc, 1, 1024, 64, 48, 64), measure_two_phase(moc, 2, 1024, 128, 48, 128)]
     if not args.no_neighbours:
         torch.cuda.empty_cache()
         line["neighbours"] = measure_neighbours(moc, max(3, args.steps // 4), 1, not args.no_cpu_baseline)

@@ -296,6 +296,24 @@ int moc_eval_cuts(const moc_graph* g, int64_t B, const int32_t* starts, const in
                   void* hip_stream);
 
 /*
+ * moc_eval_cuts with the other rule for where the recomputation goes: instead
+ * of waiting at a position where every input of the producer u is still held,
+ *   p   is the last position in (s_k, t) at which no live copy starts and every
+ *       predecessor w of u either is held (a live copy with s_w < p <= e_w) or
+ *       has a live copy that ends before p;
+ * and for every predecessor that is not held at p, its live copy with the
+ * largest end below p (the highest index among equals) is kept until p (its
+ * end becomes p): small inputs are carried across the stretch on which the
+ * large output is dropped.  k, j, e' and the edit of u's copies are as for
+ * moc_eval_cuts, and so are the move index, the outputs, the order of the best
+ * move, the limits and the errors.  Where all inputs are held at the last free
+ * position the two calls describe the same move.
+ */
+int moc_eval_cuts_keep(const moc_graph* g, int64_t B, const int32_t* starts, const int32_t* ends,
+                       const uint8_t* active, moc_cut_score* out_moves, moc_best_move* out_best,
+                       void* hip_stream);
+
+/*
  * Greedy descent by cut-and-recompute moves, every candidate on its own: the
  * memory-reducing half of a local search in the spirit of Phase 1 of
  * Section 2.4, which minimises max(peak, M).  Repeats max_steps times: find the
@@ -315,6 +333,38 @@ int moc_eval_cuts(const moc_graph* g, int64_t B, const int32_t* starts, const in
  */
 int moc_search_cuts(const moc_graph* g, int64_t B, int32_t* starts, int32_t* ends, uint8_t* active,
                     int32_t max_steps, moc_best_move* work_best, int32_t* out_steps, void* hip_stream);
+
+/*
+ * Local search in the two phases of Section 2.4, every candidate on its own.
+ * Phase 1 (towards the budget; the paper's Phase 1 minimises max(peak, M)):
+ * max_cuts steps as in moc_search_cuts, with the moves of moc_eval_cuts_keep.
+ * Phase 2 (the paper's Phase 2 minimises the duration, Eq. (1), from a solution
+ * within the budget): max_merges times, the merge moves of the candidate are
+ * written out as candidates of their own, evaluated by moc_eval_batch, and the
+ * best one is applied in place.  A merge move exists for every live copy c that
+ * has a live copy of its node below it (lower copy index); it switches c off
+ * and keeps the nearest such copy until the later of the two ends: the node is
+ * computed once less and its output held across the gap.  Only the first K
+ * merge moves of a candidate, in order of the copy index, are looked at in a
+ * step; the one applied is, among those whose result is feasible (no violation
+ * and peak <= M), the one with the lowest duration, then the lowest peak, then
+ * the lowest copy index.  A candidate with no feasible merge stays as it is.
+ *   starts, ends, active   device, [B][T], edited in place
+ *   K                      >= 1, merge moves per candidate and step
+ *   work_best              device, moc_best_move [B], 8-byte aligned
+ *   work_starts, work_ends device, int32 [B*K][T]      workspaces of Phase 2
+ *   work_active            device, uint8 [B*K][T]      (may be NULL when
+ *   work_list              device, int32 [B*K]          max_merges == 0)
+ *   work_results           device, moc_result [B*K], 8-byte aligned
+ *   out_cuts, out_merges   device, int32 [B]: moves applied in each phase
+ * Queues 2 * max_cuts + 4 * max_merges + 2 kernels and returns; allocates
+ * nothing.  Limits as moc_eval_cuts; B * K <= 2^31 - 1.
+ * Errors: MOC_EINVAL, MOC_EDEVICE, MOC_EOVERFLOW, MOC_EHIP.
+ */
+int moc_search_two_phase(const moc_graph* g, int64_t B, int32_t* starts, int32_t* ends, uint8_t* active,
+                         int32_t max_cuts, int32_t max_merges, int32_t K, moc_best_move* work_best,
+                         int32_t* work_starts, int32_t* work_ends, uint8_t* work_active, int32_t* work_list,
+                         moc_result* work_results, int32_t* out_cuts, int32_t* out_merges, void* hip_stream);
 
 /*
  * Greedy descent by single-field moves, every candidate on its own: the moves

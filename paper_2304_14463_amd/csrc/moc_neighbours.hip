@@ -920,8 +920,50 @@ struct Cut {
 
 // Which copies and positions the move for producer u and the given consumer copy involves;
 // false if it is not applicable.  Reads the packed copies and the start bitmap of L.
+// Is node w held at position x (a live copy with s < x <= e)?
+__device__ __forceinline__ bool held_at(int C, const uint32_t* __restrict__ packed, int w, int x) {
+  bool held = false;
+  for (int q = 0; q < C; ++q) held = held || covers1(packed[w * C + q], (uint32_t)x);
+  return held;
+}
+
+// The live copy of w with the largest end below x, the highest index among equals; -1 if none.
+__device__ __forceinline__ int copy_to_keep(int C, const uint32_t* __restrict__ packed, int w, int x, int* end_out) {
+  int best = -1, best_end = -1;
+  for (int q = 0; q < C; ++q) {
+    const uint32_t pw = packed[w * C + q];
+    if (live_of(pw) && (int)(pw >> 16) < x && (int)(pw >> 16) >= best_end) {
+      best = q;
+      best_end = (int)(pw >> 16);
+    }
+  }
+  *end_out = best_end;
+  return best;
+}
+
+// Calls f(w, q, end) for every predecessor w of u that is not held at p: q is the copy of w that
+// the move keeps until p, `end` its end as it stands.  A predecessor listed several times is
+// visited once (after the first visit it is held).
+template <typename Fn>
+__device__ __forceinline__ void for_each_kept_input(const Adj& g, int C, const uint32_t* __restrict__ packed, int u,
+                                                    int p, Fn f) {
+  const int y0 = g.in_ptr[u], y1 = g.in_ptr[u + 1];
+  for (int y = y0; y < y1; ++y) {
+    const int w = g.in_idx[y];
+    if (held_at(C, packed, w, p)) continue;
+    bool seen = false;
+    for (int z = y0; z < y; ++z) seen = seen || g.in_idx[z] == w;
+    if (seen) continue;
+    int end;
+    const int q = copy_to_keep(C, packed, w, p, &end);
+    f(w, q, end);
+  }
+}
+
+// mode 0: the recomputation waits where all inputs of u are held.  mode 1: it goes to the last free
+// position at which every input is held or has an earlier copy that can be kept until there.
 __device__ __forceinline__ bool find_cut(const Adj& g, int C, const NbLds& L, const uint8_t* active_row, int u,
-                                         int consumer_copy, Cut* cut) {
+                                         int consumer_copy, int mode, Cut* cut) {
   const uint32_t mine = L.packed[consumer_copy];
   if (!live_of(mine)) return false;
   const uint32_t t = mine & 0xFFFFu;
@@ -951,6 +993,20 @@ __device__ __forceinline__ bool find_cut(const Adj& g, int C, const NbLds& L, co
       x = (x & ~31) - 1;
     }
     if (pos <= sk) return false;
+    if (mode == 1) {
+      bool ok = true;
+      for (int y = g.in_ptr[u]; y < g.in_ptr[u + 1] && ok; ++y) {
+        const int w = g.in_idx[y];
+        int end;
+        ok = held_at(C, L.packed, w, pos) || copy_to_keep(C, L.packed, w, pos, &end) >= 0;
+      }
+      if (ok) {
+        p = pos;
+        break;
+      }
+      hi = pos - 1;
+      continue;
+    }
     int resume = pos;
     for (int y = g.in_ptr[u]; y < g.in_ptr[u + 1]; ++y) {
       const int w = g.in_idx[y];
@@ -984,10 +1040,10 @@ __device__ __forceinline__ bool find_cut(const Adj& g, int C, const NbLds& L, co
 
 __device__ __forceinline__ bool score_cut(const Adj& g, int C, int T, const NbLds& L, const BlockMax& block_max,
                                           const uint8_t* __restrict__ active_row, int u, int consumer_copy,
-                                          int base_viol, int base_peak, const PeakCount& at_peak, int* viol_out,
-                                          int* peak_out, int* at_peak_out) {
+                                          int base_viol, int base_peak, const PeakCount& at_peak, int mode,
+                                          int* viol_out, int* peak_out, int* at_peak_out) {
   Cut cut;
-  if (!find_cut(g, C, L, active_row, u, consumer_copy, &cut)) return false;
+  if (!find_cut(g, C, L, active_row, u, consumer_copy, mode, &cut)) return false;
   const int k = cut.k, j = cut.j, sk = cut.sk, ek = cut.ek, p = cut.p, last_use = cut.last_use;
   int vv = base_viol;
   // Eq. (3) among the live copies of u, before and after
@@ -1008,12 +1064,68 @@ __device__ __forceinline__ bool score_cut(const Adj& g, int C, int T, const NbLd
   // Eq. (5): the inputs of the new computation are held at p by the choice of p
   if (j == 0) --vv;   // Eq. (7)
   int pk = base_peak, at = at_peak.total;
-  if (last_use + 1 <= p - 1) {
-    const int top = interval_max(L.profile, block_max, last_use + 1, p - 1);
+  // mode 1: the inputs that are kept until p.  lo = the lowest position whose memory changes
+  int n_kept = 0, lo = last_use + 1;
+  if (mode == 1)
+    for_each_kept_input(g, C, L.packed, u, p, [&](int w, int q, int end) {
+      ++n_kept;
+      lo = min(lo, end + 1);
+      // Eq. (3): the kept copy against the next live copy of its node
+      for (int c = q + 1; c < C; ++c) {
+        const uint32_t nx = L.packed[w * C + c];
+        if (live_of(nx)) {
+          const int sn = (int)(nx & 0xFFFFu);
+          vv += (p > sn ? 1 : 0) - (end > sn ? 1 : 0);
+          break;
+        }
+      }
+      // Eq. (5): consumers of w that start in (end, p] and were not covered are covered now
+      for (int y = g.out_ptr[w]; y < g.out_ptr[w + 1]; ++y) {
+        const int x = g.out_idx[y];
+        for (int c = 0; c < C; ++c) {
+          const uint32_t px = L.packed[x * C + c];
+          const int sx = (int)(px & 0xFFFFu);   // 0xFFFF if not live: above every p
+          if (sx > end && sx <= p && !held_at(C, L.packed, w, sx)) --vv;
+        }
+      }
+    });
+  if (n_kept == 0) {
+    if (last_use + 1 <= p - 1) {
+      const int top = interval_max(L.profile, block_max, last_use + 1, p - 1);
+      const int sz = g.size_of(u);
+      pk = max(top - sz, max(L.pmax[last_use], L.smax[p]));
+      // positions still at the base's peak: those outside the range (all, if nothing is taken away)
+      at = pk < base_peak ? 0 : at - (sz > 0 ? at_peak.within(last_use + 1, p - 1) : 0);
+    }
+  } else {
+    // The memory changes on [lo, p]: -m_u on (last_use, p), +m_w on (end_w, p] for every kept
+    // input.  All these stretches end at p or just before it, so the change is a step function
+    // whose steps are at last_use + 1, at the end_w + 1 and at p: walk it step by step (the next
+    // step is found by a pass over the kept inputs; there are few of them).
     const int sz = g.size_of(u);
-    pk = max(top - sz, max(L.pmax[last_use], L.smax[p]));
-    // positions still at the base's peak: those outside the range (all, if nothing is taken away)
-    at = pk < base_peak ? 0 : at - (sz > 0 ? at_peak.within(last_use + 1, p - 1) : 0);
+    int top = max(L.pmax[lo - 1], L.smax[p + 1]);
+    int still = at_peak.total - at_peak.within(max(lo, 1), p) - (lo == 0 && bit_at(at_peak.bits, 0) ? 1 : 0);
+    for (int from = lo; from <= p;) {
+      int next = p + 1, add = 0;   // the step after `from`, and the change on [from, next)
+      if (from < last_use + 1) next = min(next, last_use + 1);
+      if (from < p) next = min(next, p);
+      for_each_kept_input(g, C, L.packed, u, p, [&](int w, int, int end) {
+        if (end + 1 > from) next = min(next, end + 1);
+        else add += g.size_of(w);
+      });
+      if (from >= last_use + 1 && from < p) add -= sz;
+      const int here = interval_max(L.profile, block_max, from, next - 1);
+      top = max(top, here + add);
+      // positions of [from, next) that reach the base's peak afterwards
+      if (add == 0) {
+        still += at_peak.within(max(from, 1), next - 1) + (from == 0 && bit_at(at_peak.bits, 0) ? 1 : 0);
+      } else if (add > 0 && here + add >= base_peak) {
+        for (int x = from; x < next; ++x) still += L.profile[x] + add >= base_peak ? 1 : 0;
+      }
+      from = next;
+    }
+    pk = top;
+    at = pk < base_peak ? 0 : still;
   }
   *viol_out = vv;
   *peak_out = pk;
@@ -1057,7 +1169,7 @@ __global__ __launch_bounds__(kNT) void toggles_kernel(GraphView g, int64_t B, co
                                                       const uint8_t* __restrict__ active,
                                                       moc_toggle_score* __restrict__ out,
                                                       moc_best_move* __restrict__ out_best, int improving,
-                                                      TgLayout lay) {
+                                                      int mode, TgLayout lay) {
   extern __shared__ uint32_t nb_raw[];
   NbLds L{};
   L.profile = reinterpret_cast<int32_t*>(nb_raw);
@@ -1212,8 +1324,8 @@ __global__ __launch_bounds__(kNT) void toggles_kernel(GraphView g, int64_t B, co
         const int consumer_copy = (int)(g.edge_pair_c[x] >> 16) + i;
         moc_toggle_score sc{-1, -1, 0};
         int vv, pk, at;
-        if (score_cut(A, C, T, L, block_table, active + row, u, consumer_copy, base_viol, base_peak, at_peak, &vv, &pk,
-                      &at)) {
+        if (score_cut(A, C, T, L, block_table, active + row, u, consumer_copy, base_viol, base_peak, at_peak, mode, &vv,
+                      &pk, &at)) {
           sc.violations = vv;
           sc.peak = pk;
           sc.duration = (int64_t)base_dur + g.size_dur[u].y;
@@ -1394,7 +1506,7 @@ extern "C" int moc_eval_toggles(const moc_graph* g, int64_t B, const int32_t* st
   const int64_t resident = (int64_t)per_cu * g->num_cu;
   const unsigned grid = (unsigned)(B < resident ? B : resident);
   hipLaunchKernelGGL(kern, dim3(grid), dim3(kNT), lay.bytes, static_cast<hipStream_t>(hip_stream), g->view, B, starts,
-                     ends, active, out, static_cast<moc_best_move*>(nullptr), 0, lay);
+                     ends, active, out, static_cast<moc_best_move*>(nullptr), 0, 0, lay);
   MOC_HIP(hipGetLastError());
   return MOC_OK;
 }
@@ -1413,7 +1525,7 @@ __global__ void fill_zero_kernel(int32_t* p, int64_t n) {
 // and one lane edits the three arrays in place.
 __global__ __launch_bounds__(kApplyNT) void apply_cuts_kernel(GraphView g, int64_t B, int32_t* starts, int32_t* ends,
                                                               uint8_t* active, const moc_best_move* best,
-                                                              int32_t* steps) {
+                                                              int32_t* steps, int mode) {
   extern __shared__ uint32_t ap_raw[];
   const int T = g.T, C = g.C, tid = threadIdx.x;
   const int bit_words = (T + 31) / 32;
@@ -1439,7 +1551,9 @@ __global__ __launch_bounds__(kApplyNT) void apply_cuts_kernel(GraphView g, int64
     const int x = q / C, i = q - x * C;
     const int u = g.in_idx[x];
     Cut cut;
-    if (find_cut(A, C, L, active + row, u, (int)(g.edge_pair_c[x] >> 16) + i, &cut)) {
+    if (find_cut(A, C, L, active + row, u, (int)(g.edge_pair_c[x] >> 16) + i, mode, &cut)) {
+      if (mode == 1)
+        for_each_kept_input(A, C, L.packed, u, cut.p, [&](int w, int q, int) { ends[row + w * C + q] = cut.p; });
       ends[row + u * C + cut.k] = cut.last_use;
       starts[row + u * C + cut.j] = cut.p;
       ends[row + u * C + cut.j] = cut.ek;
@@ -1447,6 +1561,177 @@ __global__ __launch_bounds__(kApplyNT) void apply_cuts_kernel(GraphView g, int64
       steps[b] += 1;
     }
   }
+}
+
+}  // namespace
+
+namespace {
+
+// What the launches of the cuts kernel need, worked out once per call.
+struct CutsPlan {
+  TgLayout lay;
+  void (*kern)(GraphView, int64_t, const int32_t*, const int32_t*, const uint8_t*, moc_toggle_score*, moc_best_move*,
+               int, int, TgLayout);
+  unsigned grid;
+  int apply_bytes;
+};
+
+int plan_cuts(const moc_graph* g, int64_t B, bool with_apply, CutsPlan* plan) {
+  if (g->has_self_loop) return MOC_EINVAL;
+  plan->lay = tg_layout(g->view.T, g->view.n, g->view.m, g->max_lds);
+  if (plan->lay.bytes > g->max_lds) return MOC_EOVERFLOW;
+  if ((int64_t)g->view.m * g->view.C > 0x7FFFFFFFll) return MOC_EOVERFLOW;
+  plan->kern = plan->lay.adj_off ? toggles_kernel<true, true> : toggles_kernel<false, true>;
+  int per_cu = 0;
+  if (const int rc = moc_kernel_occupancy(g, reinterpret_cast<const void*>(plan->kern), kNT, plan->lay.bytes, false, &per_cu))
+    return rc;
+  plan->apply_bytes = 4 * (g->view.T + (g->view.T + 31) / 32);
+  if (with_apply) {
+    int apply_per_cu = 0;   // not used: the call is for the kernel's LDS limit
+    if (const int rc = moc_kernel_occupancy(g, reinterpret_cast<const void*>(apply_cuts_kernel), kApplyNT,
+                                            plan->apply_bytes, false, &apply_per_cu))
+      return rc;
+  }
+  const int64_t resident = (int64_t)per_cu * g->num_cu;
+  plan->grid = (unsigned)(B < resident ? B : resident);
+  return MOC_OK;
+}
+
+// max_steps times: the best cut of every candidate that improves it, then its application.
+void queue_cut_steps(const moc_graph* g, const CutsPlan& plan, int64_t B, int32_t* starts, int32_t* ends,
+                     uint8_t* active, int max_steps, int mode, moc_best_move* work_best, int32_t* out_steps,
+                     hipStream_t stream) {
+  for (int step = 0; step < max_steps; ++step) {
+    hipLaunchKernelGGL(plan.kern, dim3(plan.grid), dim3(kNT), plan.lay.bytes, stream, g->view, B, starts, ends, active,
+                       static_cast<moc_toggle_score*>(nullptr), work_best, 1, mode, plan.lay);
+    hipLaunchKernelGGL(apply_cuts_kernel, dim3((unsigned)B), dim3(kApplyNT), plan.apply_bytes, stream, g->view, B,
+                       starts, ends, active, work_best, out_steps, mode);
+  }
+}
+
+int eval_cuts(const moc_graph* g, int64_t B, const int32_t* starts, const int32_t* ends, const uint8_t* active,
+              int mode, moc_cut_score* out_moves, moc_best_move* out_best, void* hip_stream) {
+  if (!g || B < 0) return MOC_EINVAL;
+  if (!out_moves && !out_best) return MOC_EINVAL;
+  if (B == 0) return MOC_OK;
+  if (!starts || !ends || !active) return MOC_EINVAL;
+  if ((((uintptr_t)starts | (uintptr_t)ends) & 3) || ((uintptr_t)out_moves & 7) || ((uintptr_t)out_best & 7))
+    return MOC_EINVAL;
+  int dev = -1;
+  MOC_HIP(hipGetDevice(&dev));
+  if (dev != g->device) return MOC_EDEVICE;
+  CutsPlan plan;
+  if (const int rc = plan_cuts(g, B, false, &plan)) return rc;
+  hipLaunchKernelGGL(plan.kern, dim3(plan.grid), dim3(kNT), plan.lay.bytes, static_cast<hipStream_t>(hip_stream), g->view,
+                     B, starts, ends, active, out_moves, out_best, 0, mode, plan.lay);
+  MOC_HIP(hipGetLastError());
+  return MOC_OK;
+}
+
+// ---- merges: the moves of the second phase, scored by the evaluation kernel itself
+constexpr int kMergeNT = 256;
+
+__device__ __forceinline__ bool copy_is_live(int s, int e, uint8_t a, int T) {
+  return a != 0 && (uint32_t)s <= (uint32_t)e && (uint32_t)e < (uint32_t)T;
+}
+
+// The nearest live copy of the same node below copy k (index within the row), -1 if none.
+__device__ __forceinline__ int live_copy_below(const int32_t* s, const int32_t* e, const uint8_t* a, int T, int C,
+                                               int k) {
+  const int first = k - k % C;
+  for (int c = k - 1; c >= first; --c)
+    if (copy_is_live(s[c], e[c], a[c], T)) return c;
+  return -1;
+}
+
+// One workgroup per walker: the first K copies, in index order, that are live and have a live
+// copy of their node below them, to list[walker][0..K); the rest of the list is -1.
+__global__ __launch_bounds__(kMergeNT) void list_merges_kernel(int64_t B, int T, int C, int K,
+                                                               const int32_t* __restrict__ starts,
+                                                               const int32_t* __restrict__ ends,
+                                                               const uint8_t* __restrict__ active,
+                                                               int32_t* __restrict__ list) {
+  __shared__ int wave_count[kMergeNT / kWave];
+  const int64_t b = blockIdx.x;
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  const int32_t* s = starts + b * T;
+  const int32_t* e = ends + b * T;
+  const uint8_t* a = active + b * T;
+  int32_t* out = list + b * K;
+  for (int r = tid; r < K; r += kMergeNT) out[r] = -1;
+  int found = 0;   // entries written by earlier rounds
+  for (int k0 = 0; k0 < T && found < K; k0 += kMergeNT) {
+    const int k = k0 + tid;
+    const bool mergeable = k < T && copy_is_live(s[k], e[k], a[k], T) && live_copy_below(s, e, a, T, C, k) >= 0;
+    const uint64_t hits = __ballot(mergeable);
+    __syncthreads();   // the counts of the last round have been read; the -1s above are in place
+    if (lane == 0) wave_count[wave] = __popcll(hits);
+    __syncthreads();
+    int before = found, total = found;
+    for (int w = 0; w < kMergeNT / kWave; ++w) {
+      if (w < wave) before += wave_count[w];
+      total += wave_count[w];
+    }
+    const int r = before + __popcll(hits & ((1ull << lane) - 1));
+    if (mergeable && r < K) out[r] = k;
+    found = total;
+  }
+}
+
+// One workgroup per (walker, entry of its list): the walker's row with that merge applied (the
+// copy switched off, the live copy below it kept until the later of the two ends), or the row
+// as it is where the list has no entry.
+__global__ __launch_bounds__(kMergeNT) void write_merges_kernel(int T, int C, int K, const int32_t* __restrict__ starts,
+                                                                const int32_t* __restrict__ ends,
+                                                                const uint8_t* __restrict__ active,
+                                                                const int32_t* __restrict__ list,
+                                                                int32_t* __restrict__ ws, int32_t* __restrict__ we,
+                                                                uint8_t* __restrict__ wa) {
+  const int64_t idx = blockIdx.x, b = idx / K;
+  const int32_t* s = starts + b * T;
+  const int32_t* e = ends + b * T;
+  const uint8_t* a = active + b * T;
+  const int k = list[idx];
+  int below = -1, end = 0;
+  if (k >= 0) {
+    below = live_copy_below(s, e, a, T, C, k);
+    end = max(e[below], e[k]);
+  }
+  for (int x = threadIdx.x; x < T; x += kMergeNT) {
+    ws[idx * T + x] = s[x];
+    we[idx * T + x] = x == below ? end : e[x];
+    wa[idx * T + x] = x == k ? (uint8_t)0 : a[x];
+  }
+}
+
+// One lane per walker: among the scored merges of its list those whose result is feasible, the
+// one with the lowest duration, then the lowest peak, then the lowest copy index, applied in place.
+__global__ void select_merges_kernel(int64_t B, int T, int C, int K, int32_t* starts, int32_t* ends, uint8_t* active,
+                                     const int32_t* __restrict__ list, const moc_result* __restrict__ results,
+                                     int32_t* merges) {
+  const int64_t b = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+  if (b >= B) return;
+  int best = -1;
+  int64_t best_dur = 0, best_peak = 0;
+  for (int r = 0; r < K; ++r) {
+    const int k = list[b * K + r];
+    if (k < 0) break;
+    const moc_result res = results[b * K + r];
+    if (!res.feasible) continue;
+    if (best < 0 || res.duration < best_dur || (res.duration == best_dur && res.peak < best_peak)) {
+      best = k;
+      best_dur = res.duration;
+      best_peak = res.peak;
+    }
+  }
+  if (best < 0) return;
+  int32_t* s = starts + b * T;
+  int32_t* e = ends + b * T;
+  uint8_t* a = active + b * T;
+  const int below = live_copy_below(s, e, a, T, C, best);
+  e[below] = max(e[below], e[best]);
+  a[best] = 0;
+  merges[b] += 1;
 }
 
 }  // namespace
@@ -1461,28 +1746,11 @@ extern "C" int moc_search_cuts(const moc_graph* g, int64_t B, int32_t* starts, i
   int dev = -1;
   MOC_HIP(hipGetDevice(&dev));
   if (dev != g->device) return MOC_EDEVICE;
-  if (g->has_self_loop) return MOC_EINVAL;
-  const TgLayout lay = tg_layout(g->view.T, g->view.n, g->view.m, g->max_lds);
-  if (lay.bytes > g->max_lds) return MOC_EOVERFLOW;
-  if ((int64_t)g->view.m * g->view.C > 0x7FFFFFFFll) return MOC_EOVERFLOW;
-  auto kern = lay.adj_off ? toggles_kernel<true, true> : toggles_kernel<false, true>;
-  int per_cu = 0;
-  if (const int rc = moc_kernel_occupancy(g, reinterpret_cast<const void*>(kern), kNT, lay.bytes, false, &per_cu)) return rc;
-  const int apply_bytes = 4 * (g->view.T + (g->view.T + 31) / 32);
-  int apply_per_cu = 0;   // not used: the call is for the kernel's LDS limit
-  if (const int rc = moc_kernel_occupancy(g, reinterpret_cast<const void*>(apply_cuts_kernel), kApplyNT, apply_bytes, false,
-                                          &apply_per_cu))
-    return rc;
-  const int64_t resident = (int64_t)per_cu * g->num_cu;
-  const unsigned grid = (unsigned)(B < resident ? B : resident);
+  CutsPlan plan;
+  if (const int rc = plan_cuts(g, B, true, &plan)) return rc;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((B + 255) / 256)), dim3(256), 0, stream, out_steps, B);
-  for (int step = 0; step < max_steps; ++step) {
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(kNT), lay.bytes, stream, g->view, B, starts, ends, active,
-                       static_cast<moc_toggle_score*>(nullptr), work_best, 1, lay);
-    hipLaunchKernelGGL(apply_cuts_kernel, dim3((unsigned)B), dim3(kApplyNT), apply_bytes, stream, g->view, B, starts,
-                       ends, active, work_best, out_steps);
-  }
+  queue_cut_steps(g, plan, B, starts, ends, active, max_steps, 0, work_best, out_steps, stream);
   MOC_HIP(hipGetLastError());
   return MOC_OK;
 }
@@ -1490,26 +1758,53 @@ extern "C" int moc_search_cuts(const moc_graph* g, int64_t B, int32_t* starts, i
 extern "C" int moc_eval_cuts(const moc_graph* g, int64_t B, const int32_t* starts, const int32_t* ends,
                              const uint8_t* active, moc_cut_score* out_moves, moc_best_move* out_best,
                              void* hip_stream) {
-  if (!g || B < 0) return MOC_EINVAL;
-  if (!out_moves && !out_best) return MOC_EINVAL;
+  return eval_cuts(g, B, starts, ends, active, 0, out_moves, out_best, hip_stream);
+}
+
+extern "C" int moc_eval_cuts_keep(const moc_graph* g, int64_t B, const int32_t* starts, const int32_t* ends,
+                                  const uint8_t* active, moc_cut_score* out_moves, moc_best_move* out_best,
+                                  void* hip_stream) {
+  return eval_cuts(g, B, starts, ends, active, 1, out_moves, out_best, hip_stream);
+}
+
+extern "C" int moc_search_two_phase(const moc_graph* g, int64_t B, int32_t* starts, int32_t* ends, uint8_t* active,
+                                    int32_t max_cuts, int32_t max_merges, int32_t K, moc_best_move* work_best,
+                                    int32_t* work_starts, int32_t* work_ends, uint8_t* work_active,
+                                    int32_t* work_list, moc_result* work_results, int32_t* out_cuts,
+                                    int32_t* out_merges, void* hip_stream) {
+  if (!g || B < 0 || max_cuts < 0 || max_merges < 0 || K < 1) return MOC_EINVAL;
   if (B == 0) return MOC_OK;
-  if (!starts || !ends || !active) return MOC_EINVAL;
-  if ((((uintptr_t)starts | (uintptr_t)ends) & 3) || ((uintptr_t)out_moves & 7) || ((uintptr_t)out_best & 7))
+  if (!starts || !ends || !active || !work_best || !out_cuts || !out_merges) return MOC_EINVAL;
+  if (max_merges > 0 && (!work_starts || !work_ends || !work_active || !work_list || !work_results)) return MOC_EINVAL;
+  if ((((uintptr_t)starts | (uintptr_t)ends | (uintptr_t)out_cuts | (uintptr_t)out_merges | (uintptr_t)work_list) & 3) ||
+      (((uintptr_t)work_best | (uintptr_t)work_results) & 7))
     return MOC_EINVAL;
+  if (((uintptr_t)work_starts | (uintptr_t)work_ends) & 3) return MOC_EINVAL;
+  if (B > 0x7FFFFFFFll || (int64_t)B * K > 0x7FFFFFFFll) return MOC_EINVAL;
   int dev = -1;
   MOC_HIP(hipGetDevice(&dev));
   if (dev != g->device) return MOC_EDEVICE;
-  if (g->has_self_loop) return MOC_EINVAL;
-  const TgLayout lay = tg_layout(g->view.T, g->view.n, g->view.m, g->max_lds);
-  if (lay.bytes > g->max_lds) return MOC_EOVERFLOW;
-  if ((int64_t)g->view.m * g->view.C > 0x7FFFFFFFll) return MOC_EOVERFLOW;
-  auto kern = lay.adj_off ? toggles_kernel<true, true> : toggles_kernel<false, true>;
-  int per_cu = 0;
-  if (const int rc = moc_kernel_occupancy(g, reinterpret_cast<const void*>(kern), kNT, lay.bytes, false, &per_cu)) return rc;
-  const int64_t resident = (int64_t)per_cu * g->num_cu;
-  const unsigned grid = (unsigned)(B < resident ? B : resident);
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(kNT), lay.bytes, static_cast<hipStream_t>(hip_stream), g->view, B, starts,
-                     ends, active, out_moves, out_best, 0, lay);
+  CutsPlan plan;
+  if (const int rc = plan_cuts(g, B, true, &plan)) return rc;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const unsigned blocks = (unsigned)((B + 255) / 256);
+  const int T = g->view.T, C = g->view.C;
+  hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, stream, out_cuts, B);
+  hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, stream, out_merges, B);
+  // Phase 1: towards the budget by cuts that keep the producer's inputs
+  queue_cut_steps(g, plan, B, starts, ends, active, max_cuts, 1, work_best, out_cuts, stream);
+  MOC_HIP(hipGetLastError());
+  // Phase 2: undo recomputations while the candidate stays within the budget
+  for (int step = 0; step < max_merges; ++step) {
+    hipLaunchKernelGGL(list_merges_kernel, dim3((unsigned)B), dim3(kMergeNT), 0, stream, B, T, C, (int)K, starts, ends,
+                       active, work_list);
+    hipLaunchKernelGGL(write_merges_kernel, dim3((unsigned)(B * K)), dim3(kMergeNT), 0, stream, T, C, (int)K, starts,
+                       ends, active, work_list, work_starts, work_ends, work_active);
+    MOC_HIP(hipGetLastError());
+    if (const int rc = moc_eval_batch(g, B * K, work_starts, work_ends, work_active, work_results, hip_stream)) return rc;
+    hipLaunchKernelGGL(select_merges_kernel, dim3(blocks), dim3(256), 0, stream, B, T, C, (int)K, starts, ends, active,
+                       work_list, work_results, out_merges);
+  }
   MOC_HIP(hipGetLastError());
   return MOC_OK;
 }

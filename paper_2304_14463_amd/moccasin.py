@@ -26,7 +26,7 @@ TOGGLE_SCORE_DTYPE = np.dtype([("violations", "<i4"), ("peak", "<i4"), ("duratio
 DECODE_RESULT_DTYPE = np.dtype([("status", "<i4"), ("length", "<i4"), ("peak", "<i8"), ("duration", "<i8")])
 
 EXPORTS = ("moc_graph_upload", "moc_graph_info", "moc_eval_batch", "moc_eval_batch_noalloc", "moc_graph_set_order", "moc_eval_batch_staged", "moc_eval_neighbours", "moc_eval_toggles",
-           "moc_eval_cuts", "moc_search_cuts", "moc_search_moves", "moc_decode_batch", "moc_graph_free", "moc_strerror", "moc_last_hip_error")
+           "moc_eval_cuts", "moc_eval_cuts_keep", "moc_search_cuts", "moc_search_two_phase", "moc_search_moves", "moc_decode_batch", "moc_graph_free", "moc_strerror", "moc_last_hip_error")
 
 
 class MoccasinError(RuntimeError):
@@ -63,6 +63,10 @@ def lib():
         L.moc_eval_toggles.restype = ctypes.c_int
         L.moc_eval_cuts.argtypes = [VP, I64, VP, VP, VP, VP, VP, VP]
         L.moc_eval_cuts.restype = ctypes.c_int
+        L.moc_eval_cuts_keep.argtypes = [VP, I64, VP, VP, VP, VP, VP, VP]
+        L.moc_eval_cuts_keep.restype = ctypes.c_int
+        L.moc_search_two_phase.argtypes = [VP, I64, VP, VP, VP, I32, I32, I32, VP, VP, VP, VP, VP, VP, VP, VP, VP]
+        L.moc_search_two_phase.restype = ctypes.c_int
         L.moc_search_cuts.argtypes = [VP, I64, VP, VP, VP, I32, VP, VP, VP]
         L.moc_search_cuts.restype = ctypes.c_int
         L.moc_search_moves.argtypes = [VP, I64, VP, VP, VP, I32, I32, VP, VP, VP, VP]
@@ -223,7 +227,7 @@ def moc_eval_toggles(g: Graph, starts, ends, active, out=None, stream=None):
 
 
 def moc_eval_cuts(g: Graph, starts, ends, active, want_moves=True, want_best=False, out_moves=None, out_best=None,
-                  stream=None):
+                  stream=None, keep_inputs=False):
     """Score the B x m*C cut-and-recompute moves.  Returns (uint8 CUDA tensor [B][m*C][16] of
     moc_cut_score or None, uint8 CUDA tensor [B][16] of moc_best_move or None)."""
     import torch
@@ -233,7 +237,8 @@ def moc_eval_cuts(g: Graph, starts, ends, active, want_moves=True, want_best=Fal
         out_moves = torch.empty((B, g.m * g.C, TOGGLE_SCORE_DTYPE.itemsize), dtype=torch.uint8, device=starts.device)
     if out_best is None and want_best:
         out_best = torch.empty((B, BEST_MOVE_DTYPE.itemsize), dtype=torch.uint8, device=starts.device)
-    code = lib().moc_eval_cuts(
+    call = lib().moc_eval_cuts_keep if keep_inputs else lib().moc_eval_cuts
+    code = call(
         g._h, B, ps, pe, pa, ctypes.c_void_p(out_moves.data_ptr()) if out_moves is not None else None,
         ctypes.c_void_p(out_best.data_ptr()) if out_best is not None else None, _stream_handle(stream))
     _check(code, "moc_eval_cuts")
@@ -255,6 +260,30 @@ def moc_search_cuts(g: Graph, starts, ends, active, max_steps, work_best=None, o
                                  ctypes.c_void_p(out_steps.data_ptr()), _stream_handle(stream))
     _check(code, "moc_search_cuts")
     return out_steps
+
+
+def moc_search_two_phase(g: Graph, starts, ends, active, max_cuts, max_merges, K=64, stream=None):
+    """Two-phase local search in place (cuts that keep the inputs towards the budget, then merges
+    that lower the duration).  Returns (cuts, merges): int32 CUDA tensors [B] of moves applied."""
+    import torch
+    B = starts.numel() // g.T if g.T else 0
+    ps, pe, pa = _cand_ptrs(g, B, starts, ends, active)
+    dev = starts.device
+    with _on(stream):
+        work_best = torch.empty((B, BEST_MOVE_DTYPE.itemsize), dtype=torch.uint8, device=dev)
+        rows = B * K if max_merges > 0 else 0
+        ws = torch.empty((rows, g.T), dtype=torch.int32, device=dev)
+        we = torch.empty((rows, g.T), dtype=torch.int32, device=dev)
+        wa = torch.empty((rows, g.T), dtype=torch.uint8, device=dev)
+        wl = torch.empty((rows,), dtype=torch.int32, device=dev)
+        wr = torch.empty((rows, RESULT_DTYPE.itemsize), dtype=torch.uint8, device=dev)
+        cuts = torch.empty((B,), dtype=torch.int32, device=dev)
+        merges = torch.empty((B,), dtype=torch.int32, device=dev)
+    P = lambda t: ctypes.c_void_p(t.data_ptr()) if t.numel() else None
+    code = lib().moc_search_two_phase(g._h, B, ps, pe, pa, int(max_cuts), int(max_merges), int(K), P(work_best), P(ws),
+                                      P(we), P(wa), P(wl), P(wr), P(cuts), P(merges), _stream_handle(stream))
+    _check(code, "moc_search_two_phase")
+    return cuts, merges
 
 
 def moc_search_moves(g: Graph, starts, ends, active, R, max_steps, out_steps=None, stream=None):
