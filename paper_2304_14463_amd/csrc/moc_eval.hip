@@ -591,7 +591,21 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
   }
   uint32_t drawn = 0;   // thread 0
 
+  // Workgroups that share a compute unit do not run equally fast: the issue logic prefers the
+  // oldest waves, and with four waves or fewer per workgroup many workgroups share a unit.  Each
+  // then takes the four issue priorities in turn, one candidate at a time, out of step with its
+  // neighbours, so that over a few candidates all get the same share and a batch that is split
+  // statically (a short one) does not wait for the workgroups that were dispatched last.
+  [[maybe_unused]] int turn = (int)(blockIdx.x / 256u);
   while (b < B) {
+    if constexpr (NT <= 256) {
+      switch (turn++ & 3) {
+        case 0: __builtin_amdgcn_s_setprio(0); break;
+        case 1: __builtin_amdgcn_s_setprio(1); break;
+        case 2: __builtin_amdgcn_s_setprio(2); break;
+        default: __builtin_amdgcn_s_setprio(3); break;
+      }
+    }
     int viol = wave == 0 ? n : 0;   // per wave (the same in every lane, counted on lane masks); see phase 1
     int dur = 0;               // per lane
     if (tid == 0) drawn = groups ? atomicAdd(counter, 1u) : next + 1;
