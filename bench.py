@@ -516,7 +516,8 @@ def main():
         line["staged"] = measure_staged(moc, max(5, args.steps // 2), 2, not args.no_cpu_baseline)
     if not args.no_also:
         torch.cuda.empty_cache()
-        line["two_phase"] = [measure_two_phase(moc, 1, 1024, 64, 48, 64), measure_two_phase(moc, 2, 1024, 128, 48, 128)]
+        line["two_phase"] = [measure_two_phase(moc, 1, 1024, 64, 48, 64), measure_two_phase(moc, 2, 1024, 128, 48, 128),
+                             measure_two_phase(moc, 3, 256, 640, 32, 128)]
     if not args.no_neighbours:
         torch.cuda.empty_cache()
         line["neighbours"] = measure_neighbours(moc, max(3, args.steps // 4), 1, not args.no_cpu_baseline)

@@ -21,10 +21,11 @@
 //            are fetched whole and every live copy of v is tested against the
 //            copies of u.  C >= 3: copies beyond the first are rarely live, so
 //            the first copies are kept in an array of their own (one word per
-//            node, one bit of it saying "this node needs the full test") and an
-//            edge is settled on two 4-byte reads unless one of its nodes says
-//            otherwise; those edges go to a queue per wave and take the full
-//            test afterwards, 64 per instruction.
+//            node) and an edge is settled on two 4-byte reads when the first
+//            copy of u covers the first copy of v; a node with other live
+//            copies carries a mark that makes this test fail.  The edges that
+//            are not settled go to a queue per wave and take the full test
+//            afterwards, 64 per instruction.
 //            Phase 2 touches no global memory; the loads of the workgroup's next
 //            candidate are issued in slices between its steps, so that HBM
 //            streams while the LDS work runs.
@@ -57,6 +58,7 @@ constexpr int kEdgesPerNode = 3;   // edges per lane = kEdgesPerNode * nodes per
 constexpr int kChunk = 32;         // delta positions per chunk ...
 constexpr int kChunkStride = 36;   // ... stored 36 words apart: 16 lanes x 16 bytes hit 64 distinct banks
 constexpr int64_t kMaxLaunch = (int64_t)1 << 31;   // candidates per launch
+static_assert(MOC_MAX_T < 0x8000, "bit 15 of a staged start marks nodes with other live copies (C >= 3)");
 constexpr int kQueueCap = 320;     // C >= 3: edges a wave sets aside before it has to work them off
 
 // ------------------------------------------------------------------ LDS layouts
@@ -409,6 +411,11 @@ __device__ __forceinline__ uint32_t rank_in(lanemask m, uint32_t base) {
   "v_cmp_ne_u32_sdwa %2, %5, %6 src0_sel:WORD_0 src1_sel:DWORD\n\t"               \
   "s_andn2_b64 %1, %2, %1\n\t"                                                    \
   "v_addc_co_u32 %0, vcc, 0, %0, %1"
+// the same with "live" read off the word itself: a staged copy is live iff s <= e
+#define MOC_COVER_LAST_SE                                                         \
+  "v_cmp_le_u32_sdwa %2, %5, %5 src0_sel:WORD_0 src1_sel:WORD_1\n\t"              \
+  "s_andn2_b64 %1, %2, %1\n\t"                                                    \
+  "v_addc_co_u32 %0, vcc, 0, %0, %1"
 #define MOC_COVER_REGS "+v"(viol), "=&s"(t1), "=&s"(t2), "=&s"(t3), "=&s"(c) : "v"(pv), "s"(dead)
 template <int CT>
 __device__ __forceinline__ void count_live_uncovered(int& viol, const Record<CT>& pu, uint32_t pv) {
@@ -420,15 +427,16 @@ __device__ __forceinline__ void count_live_uncovered(int& viol, const Record<CT>
   else if constexpr (CT == 2)
     asm(MOC_COVER_FIRST("%7") MOC_COVER_NEXT("%8") MOC_COVER_LAST : MOC_COVER_REGS, "v"(pu.w[0]), "v"(pu.w[1]) : "scc", "vcc");
   else if constexpr (CT == 3)
-    asm(MOC_COVER_FIRST("%7") MOC_COVER_NEXT("%8") MOC_COVER_NEXT("%9") MOC_COVER_LAST
+    asm(MOC_COVER_FIRST("%7") MOC_COVER_NEXT("%8") MOC_COVER_NEXT("%9") MOC_COVER_LAST_SE
         : MOC_COVER_REGS, "v"(pu.w[0]), "v"(pu.w[1]), "v"(pu.w[2]) : "scc", "vcc");
   else
-    asm(MOC_COVER_FIRST("%7") MOC_COVER_NEXT("%8") MOC_COVER_NEXT("%9") MOC_COVER_NEXT("%10") MOC_COVER_LAST
+    asm(MOC_COVER_FIRST("%7") MOC_COVER_NEXT("%8") MOC_COVER_NEXT("%9") MOC_COVER_NEXT("%10") MOC_COVER_LAST_SE
         : MOC_COVER_REGS, "v"(pu.w[0]), "v"(pu.w[1]), "v"(pu.w[2]), "v"(pu.w[3]) : "scc", "vcc");
 }
 #undef MOC_COVER_FIRST
 #undef MOC_COVER_NEXT
 #undef MOC_COVER_LAST
+#undef MOC_COVER_LAST_SE
 #undef MOC_COVER_REGS
 
 // C <= 2: the records of the two nodes of an edge held in a register as pair = u*C | v*C << 16
@@ -445,24 +453,23 @@ __device__ __forceinline__ void fetch_edge(uint32_t pair, Record<CT>& pv, Record
 }
 
 // Eq. (5), C >= 3, first pass over an edge pair = u | v << 16: only the first words of the
-// two nodes are fetched (pu, pv).  Bit 31 of a first word says that the node needs the full
-// test: it has other live copies, or its first copy is not live.  Where neither word has it,
-// the instance is settled here and counted (per lane) into viol; the lanes where one has are
-// returned, their edges go to the wave's queue.
+// two nodes are fetched (pu, pv).  The instance is settled, with no violation, where the first
+// copy of u covers the start of the first copy of v and v has no other live copy.  All other
+// edges are returned and go to the wave's queue for the full test: the first copy of v not
+// covered by the first copy of u (another copy of u may cover it, or it is a violation, or v's
+// first copy is not live at all), or a node with other live copies.  Such a node carries
+// bit 15 in its first word, on top of the start (positions stay below 2^15): as a consumer its
+// start then lies above every end, as a provider above every start, so the test fails by
+// itself and costs nothing extra.
 __device__ __forceinline__ lanemask check_first_copies(int& viol, uint32_t pu, uint32_t pv) {
   lanemask t1, t2, more;
-  asm("v_cmp_lt_u32_sdwa %1, %4, %5 src0_sel:WORD_0 src1_sel:WORD_0\n\t"
-      "v_cmp_ge_u32_sdwa %2, %4, %5 src0_sel:WORD_1 src1_sel:WORD_0\n\t"
-      "s_and_b64 %1, %1, %2\n\t"   // covered by the first copy of u
-      "v_cmp_gt_i32_e64 %3, 0, %4\n\t"
-      "v_cmp_gt_i32_e64 %2, 0, %5\n\t"
-      "s_or_b64 %3, %3, %2\n\t"      // one of the nodes needs the full test
-      "s_or_b64 %1, %1, %3\n\t"
-      "s_andn2_b64 %1, exec, %1\n\t"
-      "v_addc_co_u32 %0, vcc, 0, %0, %1"
-      : "+v"(viol), "=&s"(t1), "=&s"(t2), "=&s"(more)
+  asm("v_cmp_lt_u32_sdwa %0, %3, %4 src0_sel:WORD_0 src1_sel:WORD_0\n\t"
+      "v_cmp_ge_u32_sdwa %1, %3, %4 src0_sel:WORD_1 src1_sel:WORD_0\n\t"
+      "s_and_b64 %0, %0, %1\n\t"   // covered by the first copy of u
+      "s_andn2_b64 %2, exec, %0"
+      : "=&s"(t1), "=&s"(t2), "=&s"(more)
       : "v"(pu), "v"(pv)
-      : "scc", "vcc");
+      : "scc");
   return more;
 }
 
@@ -477,8 +484,8 @@ __device__ __forceinline__ void drain_queue(int& viol, const Lds& L, const uint3
     const uint32_t pair = pick(u_lt_k((uint32_t)idx, (uint32_t)count), queue[idx], dummy_pair);
     const uint32_t v = pair >> 16, u = pair & 0xFFFFu;
     Record<CT> pv, pu;
-    pv.w[0] = L.packed[v];
-    pu.w[0] = L.packed[u] & 0x7FFFFFFFu;   // only the provider's end is read from the high half
+    pv.w[0] = L.packed[v] & 0xFFFF7FFFu;   // without the mark (a dead word becomes s = 0x7FFF, e = 0: still s > e)
+    pu.w[0] = L.packed[u] & 0xFFFF7FFFu;
     if constexpr (CT == 3) {
       const uint2 rv = *reinterpret_cast<const uint2*>(L.rest + v * RS);
       const uint2 ru = *reinterpret_cast<const uint2*>(L.rest + u * RS);
@@ -660,8 +667,8 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
           } else if constexpr (CT == 2) {
             *reinterpret_cast<uint2*>(L.packed + v * 2) = make_uint2(rec.w[0], rec.w[1]);
           } else {
-            // bit 31: the edges of this node take the full test (other live copies, or no live first copy)
-            L.packed[v] = rec.w[0] | pick(others | (isn & ~live[0]), 0x80000000u);
+            // bit 15: the node has other live copies, its edges take the full test (see check_first_copies)
+            L.packed[v] = rec.w[0] | pick(others, 0x00008000u);
             if constexpr (CT == 3) *reinterpret_cast<uint2*>(L.rest + v * RS) = make_uint2(rec.w[1], rec.w[2]);
             else *reinterpret_cast<uint4*>(L.rest + v * RS) = make_uint4(rec.w[1], rec.w[2], rec.w[3], MOC_DEAD);
           }
