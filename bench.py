@@ -27,9 +27,9 @@ HBM_PEAK_GBS = 8000.0
 # HBM traffic of the evaluation kernel on the default workload, from rocprofv3 counter runs
 # (profiles/eval_batch_kernel_n5000_C3_B262144.md): KiB per dispatch and the factors that the same
 # counters need to reproduce a 1 GiB device copy.  Valid for the kernel sources they were taken with.
-TRAFFIC = {"workload": 4, "B": 262144, "fetch_kib": 17327700.0, "fetch_scale": 2.0, "write_kib": 20496.5,
-           "write_scale": 1.0, "sources_sha256": "0d85a5e6d844d067ba3a0738095629e84fb1858323105bd19a61956cf3fae379"}
-KERNEL_SOURCES = ("moc_eval.hip", "moc_graph.hip", "moc_internal.h")
+TRAFFIC = {"workload": 4, "B": 262144, "fetch_kib": 17327186.7, "fetch_scale": 2.0, "write_kib": 20496.5,
+           "write_scale": 1.0, "sources_sha256": "d53f4e8fa743f0150073dcecdd859055bdd87bc03b3e0c3cd483d80b6e4505bf"}
+KERNEL_SOURCES = ("moc_eval.hip", "moc_internal.h")
 
 
 def kernel_sources_sha256():
@@ -120,7 +120,7 @@ def time_stream_read(cand, steps):
     nbytes = sum(t.numel() * t.element_size() for t in cand)
     cus = torch.cuda.get_device_properties(0).multi_processor_count
     best = (0.0, 0)
-    for per_cu in (1, 2, 4, 8):
+    for per_cu in (1, 4, 16):
         blocks = cus * per_cu
         out = stream_read(cand, blocks)
         torch.cuda.synchronize()

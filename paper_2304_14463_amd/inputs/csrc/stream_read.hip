@@ -19,25 +19,27 @@ struct Span {
 __device__ __forceinline__ uint32_t fold(const uint4& v) { return v.x ^ v.y ^ v.z ^ v.w; }
 
 __global__ __launch_bounds__(kThreads) void stream_read_kernel(Span a, Span b, Span c, uint32_t* __restrict__ out) {
-  const uint64_t gid = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
-  const uint64_t stride = (uint64_t)gridDim.x * kThreads;
   uint32_t acc = 0;
   const Span spans[3] = {a, b, c};
 #pragma unroll
   for (int k = 0; k < 3; ++k) {
+    // every workgroup takes one contiguous stretch of the array (measured a few per cent faster
+    // than striding over it with the whole grid)
     const uint4* __restrict__ p = spans[k].p;
     const uint64_t n16 = spans[k].n16;
-    uint64_t i = gid;
-    for (; i + (kUnroll - 1) * stride < n16; i += kUnroll * stride) {
+    const uint64_t per = (n16 + gridDim.x - 1) / gridDim.x;
+    const uint64_t lo = per * blockIdx.x, hi = lo + per < n16 ? lo + per : n16;
+    uint64_t i = lo + threadIdx.x;
+    for (; i + (kUnroll - 1) * kThreads < hi; i += kUnroll * kThreads) {
       uint4 v[kUnroll];
 #pragma unroll
-      for (int j = 0; j < kUnroll; ++j) v[j] = p[i + j * stride];
+      for (int j = 0; j < kUnroll; ++j) v[j] = p[i + j * kThreads];
 #pragma unroll
       for (int j = 0; j < kUnroll; ++j) acc ^= fold(v[j]);
     }
-    for (; i < n16; i += stride) acc ^= fold(p[i]);
+    for (; i < hi; i += kThreads) acc ^= fold(p[i]);
   }
-  out[gid] = acc;
+  out[(uint64_t)blockIdx.x * kThreads + threadIdx.x] = acc;
 }
 
 }  // namespace
