@@ -66,6 +66,10 @@ __device__ __forceinline__ int wave_sum_i(int v) {
   return v;
 }
 
+// CT = C when C <= 4 (the copies of a node are then read into registers, for this candidate at
+// the top of its turn and for the workgroup's next candidate as soon as they are used), else 0
+// (any C, read where needed); U = nodes per lane, ceil(n / kNT), when CT > 0.
+template <int CT, int U>
 __global__ __launch_bounds__(kNT) void eval_staged_kernel(GraphView g, const int32_t* __restrict__ place, int64_t B,
                                                           const int32_t* __restrict__ starts,
                                                           const int32_t* __restrict__ ends,
@@ -84,6 +88,26 @@ __global__ __launch_bounds__(kNT) void eval_staged_kernel(GraphView g, const int
 
   for (int i = tid; i < kNT * lay.chunk; i += kNT) delta[i] = 0;
 
+  // registers for the copies of the lane's nodes (CT > 0)
+  constexpr int RU = CT > 0 ? U : 1, RC = CT > 0 ? CT : 1;
+  [[maybe_unused]] int rs[RU][RC], re[RU][RC];
+  [[maybe_unused]] uint8_t ra[RU][RC];
+  [[maybe_unused]] auto request = [&](int64_t cand) {
+    if constexpr (CT > 0) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int v = min(u * kNT + tid, n - 1);   // lanes past the last node re-read it
+#pragma unroll
+        for (int i = 0; i < CT; ++i) {
+          rs[u][i] = starts[cand * T + v * CT + i];
+          re[u][i] = ends[cand * T + v * CT + i];
+          ra[u][i] = active[cand * T + v * CT + i];
+        }
+      }
+    }
+  };
+  if ((int64_t)blockIdx.x < B) request(blockIdx.x);
+
   for (int64_t b = blockIdx.x; b < B; b += gridDim.x) {
     const int64_t row = b * T;
     for (int j = tid; j < n; j += kNT) cur[j] = 0;
@@ -92,39 +116,53 @@ __global__ __launch_bounds__(kNT) void eval_staged_kernel(GraphView g, const int
     // ---- per node: Eq. (1), (2), (3), (7), (8) and the domain of the starts; count the distinct
     //      usable starts per stage
     int viol = 0, dur = 0;
-    for (int v = tid; v < n; v += kNT) {
-      const int2 sd = g.size_dur[v];
-      const int k = place[v];
-      int prev_end = -1;
-      for (int i = 0; i < C; ++i) {
-        const int c = v * C + i;
-        const int s = starts[row + c], e = ends[row + c];
-        const bool act = active[row + c] != 0;
-        bool live = act && (uint32_t)s <= (uint32_t)e && (uint32_t)e < D;
-        int j = -1;
-        if (live) {
-          j = stage_of((uint32_t)s);
-          live = (uint32_t)s - (uint32_t)j * (uint32_t)(j + 1) / 2u == (uint32_t)k && (i > 0 || j == k);
+    // one copy: i-th of node v (place k, duration w); prev_end = end of the node's latest usable copy so far
+    auto copy_step = [&](int v, int k, int w, int i, int s, int e, bool act, int& prev_end) {
+      const int c = v * C + i;
+      bool live = act && (uint32_t)s <= (uint32_t)e && (uint32_t)e < D;
+      int j = -1;
+      if (live) {
+        j = stage_of((uint32_t)s);
+        live = (uint32_t)s - (uint32_t)j * (uint32_t)(j + 1) / 2u == (uint32_t)k && (i > 0 || j == k);
+      }
+      viol += (act && !live) ? 1 : 0;
+      if (i == 0) viol += act ? 0 : 1;
+      dur += act ? w : 0;
+      int code = -1;
+      if (live) {
+        viol += prev_end > s ? 1 : 0;   // Eq. (3), on the positions as given
+        prev_end = e;
+        // Eq. (6): a usable start shares its position only with copies of its own node, which
+        // sit in the same stage; the first of them stands for the position
+        bool first_here = true;
+        for (int q = 0; q < i; ++q) first_here = first_here && pj[v * C + q] >> 1 != j;
+        if (first_here) atomicAdd(&cur[j], 1);
+        else viol += 1;
+        code = j << 1 | (first_here ? 1 : 0);
+      }
+      pj[c] = live ? code : -2;   // -2 >> 1 = -1: no stage
+      pe[c] = e;
+    };
+    if constexpr (CT > 0) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int v = u * kNT + tid;
+        if (v < n) {
+          const int k = place[v], w = g.size_dur[v].y;
+          int prev_end = -1;
+#pragma unroll
+          for (int i = 0; i < CT; ++i) copy_step(v, k, w, i, rs[u][i], re[u][i], ra[u][i] != 0, prev_end);
         }
-        viol += (act && !live) ? 1 : 0;
-        if (i == 0) viol += act ? 0 : 1;
-        dur += act ? sd.y : 0;
-        int code = -1;
-        if (live) {
-          viol += prev_end > s ? 1 : 0;   // Eq. (3), on the positions as given
-          prev_end = e;
-          // Eq. (6): a usable start shares its position only with copies of its own node, which
-          // sit in the same stage; the first of them stands for the position
-          bool first_here = true;
-          for (int q = 0; q < i; ++q) first_here = first_here && pj[v * C + q] >> 1 != j;
-          if (first_here) atomicAdd(&cur[j], 1);
-          else viol += 1;
-          code = j << 1 | (first_here ? 1 : 0);
-        }
-        pj[c] = live ? code : -2;   // -2 >> 1 = -1: no stage
-        pe[c] = e;
+      }
+    } else {
+      for (int v = tid; v < n; v += kNT) {
+        const int k = place[v], w = g.size_dur[v].y;
+        int prev_end = -1;
+        for (int i = 0; i < C; ++i)
+          copy_step(v, k, w, i, starts[row + v * C + i], ends[row + v * C + i], active[row + v * C + i] != 0, prev_end);
       }
     }
+    if (b + gridDim.x < B) request(b + gridDim.x);   // the rest of this turn works from LDS
     __syncthreads();
 
     // ---- cur[j] <- number of distinct usable starts in stages 0..j (inclusive running sum)
@@ -268,13 +306,33 @@ extern "C" int moc_eval_batch_staged(const moc_graph* g, int64_t B, const int32_
   if (dev != g->device) return MOC_EDEVICE;
   const StLayout lay = st_layout(g->view.n, g->view.C);
   if (lay.bytes > g->max_lds || g->view.T >= 0xFFFF) return MOC_EOVERFLOW;
+  const int per_lane = (g->view.n + kNT - 1) / kNT, C = g->view.C;
+  auto kern = eval_staged_kernel<0, 1>;
+  if (C <= 4 && per_lane * C <= 16) {   // the copies of a lane's nodes fit its registers
+    const int u = per_lane <= 1 ? 1 : per_lane <= 2 ? 2 : per_lane <= 4 ? 4 : 8;
+    switch (C * 16 + u) {
+      case 1 * 16 + 1: kern = eval_staged_kernel<1, 1>; break;
+      case 1 * 16 + 2: kern = eval_staged_kernel<1, 2>; break;
+      case 1 * 16 + 4: kern = eval_staged_kernel<1, 4>; break;
+      case 1 * 16 + 8: kern = eval_staged_kernel<1, 8>; break;
+      case 2 * 16 + 1: kern = eval_staged_kernel<2, 1>; break;
+      case 2 * 16 + 2: kern = eval_staged_kernel<2, 2>; break;
+      case 2 * 16 + 4: kern = eval_staged_kernel<2, 4>; break;
+      case 2 * 16 + 8: kern = eval_staged_kernel<2, 8>; break;
+      case 3 * 16 + 1: kern = eval_staged_kernel<3, 1>; break;
+      case 3 * 16 + 2: kern = eval_staged_kernel<3, 2>; break;
+      case 3 * 16 + 4: kern = eval_staged_kernel<3, 4>; break;
+      case 4 * 16 + 1: kern = eval_staged_kernel<4, 1>; break;
+      case 4 * 16 + 2: kern = eval_staged_kernel<4, 2>; break;
+      case 4 * 16 + 4: kern = eval_staged_kernel<4, 4>; break;
+      default: break;
+    }
+  }
   int per_cu = 0;
-  if (const int rc = moc_kernel_occupancy(g, reinterpret_cast<const void*>(eval_staged_kernel), kNT, lay.bytes, false,
-                                          &per_cu))
-    return rc;
+  if (const int rc = moc_kernel_occupancy(g, reinterpret_cast<const void*>(kern), kNT, lay.bytes, false, &per_cu)) return rc;
   const int64_t resident = (int64_t)per_cu * g->num_cu;
   const unsigned grid = (unsigned)(B < resident ? B : resident);
-  hipLaunchKernelGGL(eval_staged_kernel, dim3(grid), dim3(kNT), lay.bytes, static_cast<hipStream_t>(hip_stream), g->view,
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(kNT), lay.bytes, static_cast<hipStream_t>(hip_stream), g->view,
                      g->place, B, starts, ends, active, out, lay);
   MOC_HIP(hipGetLastError());
   return MOC_OK;
