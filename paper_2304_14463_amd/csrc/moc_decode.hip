@@ -23,14 +23,17 @@ constexpr int kNW = kNT / kWave;
 constexpr uint32_t kNoStart = 0xFFFFu;
 
 struct DcLayout {
-  int T_pad;   // words in each of the two position arrays (>= T + 1, even)
+  int T_pad;      // words in each of the two position arrays (>= T + 1, a multiple of 4)
+  int st_words;   // words of the array of starts (16-bit entries; C = 3: 4 per node, so that a node's starts are two words)
   int bytes;
 };
 
-DcLayout dc_layout(int T) {
+DcLayout dc_layout(int n, int C) {
+  const int T = n * C;
   DcLayout l;
-  l.T_pad = (T + 2) & ~1;
-  const int words = 2 * l.T_pad + l.T_pad / 2 + 2 * kNW + 8;
+  l.T_pad = (T + 4) & ~3;   // > T, a multiple of 4
+  l.st_words = C == 3 ? 2 * n + 2 : l.T_pad / 2;
+  const int words = 2 * l.T_pad + l.st_words + 2 * kNW + 16;
   l.bytes = words * 4;
   return l;
 }
@@ -252,6 +255,261 @@ void decode_kernel(GraphView G, int64_t B, const int32_t* __restrict__ starts, c
   }
 }
 
+
+// ---- the same for C <= 4, with fewer passes (six barriers per candidate instead of twelve).
+// The copies of a node are adjacent, so a node's starts are one or two LDS words; the position
+// array holds the node computed at each position (v + 1) instead of a flag, so that the pass
+// that ranks the occupied positions can write the sequence out itself, in order, and clear the
+// array on its way; the running-sum scan at the end clears the difference array as it reads it.
+template <int CT>
+struct NodeStarts {
+  uint32_t s[CT];   // kNoStart if the copy is not computed
+};
+
+constexpr int starts_stride(int C) { return C == 3 ? 4 : C; }   // 16-bit entries per node
+
+template <int CT>
+__device__ __forceinline__ NodeStarts<CT> read_starts(const uint16_t* st, int v) {
+  NodeStarts<CT> r;
+  if constexpr (CT == 1) {
+    r.s[0] = st[v];
+  } else if constexpr (CT == 2) {
+    const uint32_t w = *reinterpret_cast<const uint32_t*>(st + 2 * v);
+    r.s[0] = w & 0xFFFFu; r.s[1] = w >> 16;
+  } else {
+    const uint2 w = *reinterpret_cast<const uint2*>(st + 4 * v);
+    r.s[0] = w.x & 0xFFFFu; r.s[1] = w.x >> 16; r.s[2] = w.y & 0xFFFFu;
+    if constexpr (CT == 4) r.s[3] = w.y >> 16;
+  }
+  return r;
+}
+
+// max over x in [0, T] of a[0] + ... + a[x] (at least 0); every a[x] is left at zero.  The entry
+// at T only ever holds releases (values <= 0), so it cannot raise the maximum.  A wave takes
+// rows of 256 positions, four per lane in one 16-byte read; `words` (a multiple of 4, > T) is
+// the length of the array.  Ends with a barrier.
+__device__ int block_peak_and_clear(int32_t* a, int words, int32_t* scratch, int tid) {
+  const int lane = tid & (kWave - 1), wave = tid / kWave;
+  const int rows = (words + 4 * kWave - 1) / (4 * kWave), rows_per_wave = (rows + kNW - 1) / kNW;
+  const int r0 = min(wave * rows_per_wave, rows), r1 = min(r0 + rows_per_wave, rows);
+  int carry = 0, top = 0;   // lane 0: sum and highest running sum of this wave's rows, from the wave's first position
+  for (int r = r0; r < r1; ++r) {
+    const int x = (r * kWave + lane) * 4;
+    int4 v = make_int4(0, 0, 0, 0);
+    if (x < words) {
+      v = *reinterpret_cast<int4*>(a + x);
+      *reinterpret_cast<int4*>(a + x) = make_int4(0, 0, 0, 0);
+    }
+    int S = v.x, P = max(S, 0);
+    S += v.y; P = max(P, S);
+    S += v.z; P = max(P, S);
+    S += v.w; P = max(P, S);
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {   // lane l absorbs lanes l+off .. l+2*off-1
+      const int S2 = __shfl_down(S, off), P2 = __shfl_down(P, off);
+      if (lane + off < kWave) {
+        P = max(P, S + P2);
+        S += S2;
+      }
+    }
+    top = max(top, carry + P);
+    carry += S;
+  }
+  if (lane == 0) {
+    scratch[wave] = carry;
+    scratch[kNW + wave] = top;
+  }
+  __syncthreads();
+  int best = 0, before = 0;
+  for (int w = 0; w < kNW; ++w) {
+    best = max(best, before + scratch[kNW + w]);
+    before += scratch[w];
+  }
+  __syncthreads();
+  return best;
+}
+
+template <int CT>
+__global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8)))
+void decode_fixed_kernel(GraphView G, int64_t B, const int32_t* __restrict__ starts, const uint8_t* __restrict__ active,
+                         moc_decode_result* __restrict__ out, int32_t* __restrict__ out_seq, DcLayout lay) {
+  extern __shared__ int32_t lds[];
+  constexpr int SS = starts_stride(CT);
+  int32_t* a = lds;                 // node computed at each position (v + 1), then memory differences
+  int32_t* b = a + lay.T_pad;       // the last position each computation serves
+  uint16_t* st = reinterpret_cast<uint16_t*>(b + lay.T_pad);   // [n][SS] start of each copy, kNoStart if not computed
+  int32_t* scratch = reinterpret_cast<int32_t*>(st) + lay.st_words;
+  int32_t* flag_words = scratch + 2 * kNW;   // two sets of [0] not decodable, [1] not a valid sequence, [2] duration
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  const int T = G.T, n = G.n, m = G.m;
+
+  for (int x = tid; x < lay.T_pad; x += kNT) a[x] = 0;
+  if (tid < 8) flag_words[tid] = 0;
+  __syncthreads();
+
+  int turn = 0;
+  for (int64_t cand = blockIdx.x; cand < B; cand += gridDim.x, turn ^= 1) {
+    const int32_t* s_row = starts + cand * T;
+    const uint8_t* a_row = active + cand * T;
+    int32_t* seq_row = out_seq ? out_seq + cand * T : nullptr;
+    int32_t* flags = flag_words + 4 * turn;
+
+    // ---- who is computed where; every computation serves at least its own step
+    for (int round = 0; round < n; round += kUnroll * kNT) {
+      int32_t s[kUnroll][CT];
+      uint8_t on[kUnroll][CT];
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) {
+        const int v = round + u * kNT + tid;
+#pragma unroll
+        for (int i = 0; i < CT; ++i) {
+          on[u][i] = v < n ? a_row[v * CT + i] : (uint8_t)0;
+          s[u][i] = v < n ? s_row[v * CT + i] : 0;
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) {
+        const int v = round + u * kNT + tid;
+        if (v >= n) continue;
+#pragma unroll
+        for (int i = 0; i < CT; ++i) {
+          uint32_t sk = kNoStart;
+          if (on[u][i]) {
+            if (s[u][i] < 0 || s[u][i] >= T) {
+              flags[0] = 1;                                        // Eq. (8)
+            } else {
+              sk = (uint32_t)s[u][i];
+              if (atomicCAS(&a[sk], 0, v + 1) != 0) flags[0] = 1;  // Eq. (6)
+              b[sk] = (int)sk;
+            }
+          }
+          st[v * SS + i] = (uint16_t)sk;
+        }
+      }
+    }
+    __syncthreads();
+    if (flags[0]) {
+      if (seq_row)
+        for (int x = tid; x < T; x += kNT) seq_row[x] = -1;
+      for (int x = tid; x <= T; x += kNT) a[x] = 0;
+      __syncthreads();
+      if (tid == 0) {
+        out[cand] = moc_decode_result{-1, 0, 0, 0};
+        flags[0] = 0;
+      }
+      __syncthreads();
+      turn ^= 1;   // the same set of flags serves the next candidate (it is clear again)
+      continue;
+    }
+    if (tid == 0) {   // the other set, for the workgroup's next candidate
+      int32_t* other = flag_words + 4 * (turn ^ 1);
+      other[0] = 0; other[1] = 0; other[2] = 0;
+    }
+
+    // ---- the sequence: occupied positions in order.  A wave owns rows of 256 positions, four per lane.
+    const int rows = (lay.T_pad + 4 * kWave - 1) / (4 * kWave), rows_per_wave = (rows + kNW - 1) / kNW;
+    const int r0 = min(wave * rows_per_wave, rows), r1 = min(r0 + rows_per_wave, rows);
+    int mine = 0;
+    for (int r = r0; r < r1; ++r) {
+      const int x = (r * kWave + lane) * 4;
+      if (x < lay.T_pad) {
+        const int4 who = *reinterpret_cast<const int4*>(a + x);
+        mine += (who.x != 0) + (who.y != 0) + (who.z != 0) + (who.w != 0);
+      }
+    }
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) mine += __shfl_xor(mine, off);
+    if (lane == 0) scratch[wave] = mine;
+    __syncthreads();
+    int before = 0, length = 0;
+    for (int w = 0; w < kNW; ++w) {
+      const int t = scratch[w];
+      if (w < wave) before += t;
+      length += t;
+    }
+    for (int r = r0; r < r1; ++r) {
+      const int x = (r * kWave + lane) * 4;
+      int4 who = make_int4(0, 0, 0, 0);
+      if (x < lay.T_pad) who = *reinterpret_cast<const int4*>(a + x);
+      const int cnt = (who.x != 0) + (who.y != 0) + (who.z != 0) + (who.w != 0);
+      const int incl = wave_scan_add(cnt, lane);
+      if (cnt) {
+        int at = before + incl - cnt;
+        if (seq_row) {
+          if (who.x) seq_row[at++] = who.x - 1;
+          if (who.y) seq_row[at++] = who.y - 1;
+          if (who.z) seq_row[at++] = who.z - 1;
+          if (who.w) seq_row[at++] = who.w - 1;
+        }
+        *reinterpret_cast<int4*>(a + x) = make_int4(0, 0, 0, 0);
+      }
+      before += __shfl(incl, kWave - 1);
+    }
+    if (seq_row)
+      for (int x = length + tid; x < T; x += kNT) seq_row[x] = -1;
+
+    // ---- one lane per edge (u, v): each computation of v is served by the latest computation of u before it
+    for (int round = 0; round < m; round += kUnroll * kNT) {
+      const int base = round + tid;
+      uint32_t pair[kUnroll];
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) pair[u] = base + u * kNT < m ? G.edge_pair_c[base + u * kNT] : 0u;
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) {
+        if (base + u * kNT >= m) continue;
+        const NodeStarts<CT> su = read_starts<CT>(st, (int)(pair[u] & 0xFFFFu) / CT);
+        const NodeStarts<CT> sv = read_starts<CT>(st, (int)(pair[u] >> 16) / CT);
+#pragma unroll
+        for (int i = 0; i < CT; ++i) {
+          const uint32_t p = sv.s[i];
+          if (p == kNoStart) continue;
+          int q = -1;
+#pragma unroll
+          for (int j = 0; j < CT; ++j)
+            if (su.s[j] < p) q = max(q, (int)su.s[j]);    // kNoStart is above every position
+          if (q < 0) flags[1] = 1;
+          else atomicMax(&b[q], (int)p);
+        }
+      }
+    }
+    __syncthreads();
+
+    // ---- per node: does it occur, what does it add to the duration; its outputs are held from p through b[p]
+    int my_dur = 0;
+    for (int round = 0; round < n; round += kUnroll * kNT) {
+      const int base = round + tid;
+      int2 sd[kUnroll];
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) sd[u] = base + u * kNT < n ? G.size_dur[base + u * kNT] : make_int2(0, 0);
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) {
+        const int v = base + u * kNT;
+        if (v >= n) continue;
+        const NodeStarts<CT> sv = read_starts<CT>(st, v);
+        int times = 0;
+#pragma unroll
+        for (int i = 0; i < CT; ++i) {
+          const uint32_t p = sv.s[i];
+          if (p == kNoStart) continue;
+          ++times;
+          atomicAdd(&a[p], sd[u].x);
+          atomicAdd(&a[b[p] + 1], -sd[u].x);
+        }
+        if (times == 0) flags[1] = 1;
+        my_dur += times * sd[u].y;
+      }
+    }
+    if (my_dur) atomicAdd(&flags[2], my_dur);
+    __syncthreads();
+    const int peak = block_peak_and_clear(a, lay.T_pad, scratch, tid);
+
+    if (tid == 0) {
+      const bool valid = flags[1] == 0;
+      out[cand] = moc_decode_result{valid ? 1 : 0, length, valid ? (int64_t)peak : 0, valid ? (int64_t)flags[2] : 0};
+    }
+  }
+}
+
 }  // namespace
 
 extern "C" int moc_decode_batch(const moc_graph* g, int64_t B, const int32_t* starts, const uint8_t* active,
@@ -263,14 +521,21 @@ extern "C" int moc_decode_batch(const moc_graph* g, int64_t B, const int32_t* st
   int dev = -1;
   MOC_HIP(hipGetDevice(&dev));
   if (dev != g->device) return MOC_EDEVICE;
-  const DcLayout lay = dc_layout(g->view.T);
+  const DcLayout lay = dc_layout(g->view.n, g->view.C);
   if (lay.bytes > g->max_lds) return MOC_EOVERFLOW;
+  auto kern = decode_kernel;
+  switch (g->view.C) {
+    case 1: kern = decode_fixed_kernel<1>; break;
+    case 2: kern = decode_fixed_kernel<2>; break;
+    case 3: kern = decode_fixed_kernel<3>; break;
+    case 4: kern = decode_fixed_kernel<4>; break;
+    default: break;
+  }
   int per_cu = 0;
-  if (const int rc = moc_kernel_occupancy(g, reinterpret_cast<const void*>(decode_kernel), kNT, lay.bytes, false, &per_cu))
-    return rc;
+  if (const int rc = moc_kernel_occupancy(g, reinterpret_cast<const void*>(kern), kNT, lay.bytes, false, &per_cu)) return rc;
   const int64_t resident = (int64_t)per_cu * g->num_cu;
   const unsigned grid = (unsigned)(B < resident ? B : resident);
-  hipLaunchKernelGGL(decode_kernel, dim3(grid), dim3(kNT), lay.bytes, static_cast<hipStream_t>(hip_stream), g->view, B,
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(kNT), lay.bytes, static_cast<hipStream_t>(hip_stream), g->view, B,
                      starts, active, out, out_seq, lay);
   MOC_HIP(hipGetLastError());
   return MOC_OK;
