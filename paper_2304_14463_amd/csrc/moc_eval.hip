@@ -21,10 +21,12 @@
 //            are fetched whole and every live copy of v is tested against the
 //            copies of u.  C >= 3: copies beyond the first are rarely live, so
 //            the first copies are kept in an array of their own (one word per
-//            node) and an edge is settled on two 4-byte reads when the first
-//            copy of u covers the first copy of v; a node with other live
-//            copies carries a mark that makes this test fail.  The edges that
-//            are not settled go to a queue per wave and take the full test
+//            node), the start of each node's first copy once more in an array
+//            of 16-bit entries that the node's in-edges read, and an edge is
+//            settled on those two reads when the first copy of u covers the
+//            first copy of v; a consumer with other live copies carries a mark
+//            in its 16-bit entry that makes this test fail.  The edges that are
+//            not settled go to a queue per wave and take the full test
 //            afterwards, 64 per instruction.
 //            Phase 2 touches no global memory; the loads of the workgroup's next
 //            candidate are issued in slices between its steps, so that HBM
@@ -58,13 +60,13 @@ constexpr int kEdgesPerNode = 3;   // edges per lane = kEdgesPerNode * nodes per
 constexpr int kChunk = 32;         // delta positions per chunk ...
 constexpr int kChunkStride = 36;   // ... stored 36 words apart: 16 lanes x 16 bytes hit 64 distinct banks
 constexpr int64_t kMaxLaunch = (int64_t)1 << 31;   // candidates per launch
-static_assert(MOC_MAX_T < 0x8000, "bit 15 of a staged start marks nodes with other live copies (C >= 3)");
+static_assert(MOC_MAX_T < 0x8000, "bit 15 of a consumer's 16-bit start marks nodes with other live copies (C >= 3)");
 constexpr int kQueueCap = 320;     // C >= 3: edges a wave sets aside before it has to work them off
 
 // ------------------------------------------------------------------ LDS layouts
 // Word offsets of the arrays inside the dynamic LDS segment, and their sizes in words.
 struct LdsLayout {
-  int packed_off, rest_off, delta_off, occ_off, red_off, queue_off;
+  int packed_off, cons_off, rest_off, delta_off, occ_off, red_off, queue_off;
   int chunk;       // general kernel: delta entries per thread (odd: conflict-free strided reads)
   int n_chunks;    // register-resident kernel: chunks of kChunk positions
   int delta_len;
@@ -78,8 +80,11 @@ struct LdsLayout {
 constexpr int round4(int x) { return (x + 3) & ~3; }
 
 // Register-resident kernel.  Node records first, at LDS address 0: with C <= 2 one record of
-// C words per node; with C >= 3 the first copy of every node (1 word), then the other copies
-// of every node (2 words for C = 3, 4 for C = 4).  Dummy nodes end the arrays: C <= 2 one
+// C words per node; with C >= 3 the first copy of every node (1 word), then 16 bits per node
+// for its role as a consumer (the start of its first copy, bit 15 set if it has other live
+// copies), then the other copies of every node (2 words for C = 3, 4 for C = 4; the three
+// arrays lie within the first 128 KB, so that a 16-bit index reaches an entry of the second).
+// Dummy nodes end the arrays: C <= 2 one
 // node n that is never live; C >= 3 a consumer n and a provider n + 1 that form a satisfied
 // edge, and a node n + 2 that is never live.  Then the delta array in padded chunks, the start bitmap, the cross-wave
 // exchange area and (C >= 3) a queue per wave, shrunk to fit when LDS is short.
@@ -91,10 +96,12 @@ LdsLayout fast_layout(int n, int m, int C, int nt, int max_lds) {
   l.delta_len = l.n_chunks * kChunkStride;
   const int first_len = round4((n + (C >= 3 ? 3 : 1)) * moc_node_stride(C));
   const int rest_len = C >= 3 ? round4((n + 3) * (C == 3 ? 2 : 4)) : 0;
-  l.packed_len = first_len + rest_len;
+  const int cons_len = C >= 3 ? round4((n + 3 + 1) / 2) : 0;   // 16 bits per node
+  l.packed_len = first_len + cons_len + rest_len;
   l.occ_words = (T + 31) / 32;
   l.packed_off = 0;
-  l.rest_off = first_len;
+  l.cons_off = first_len;
+  l.rest_off = first_len + cons_len;
   l.delta_off = l.packed_len;
   l.occ_off = l.delta_off + l.delta_len;
   l.red_off = l.occ_off + l.occ_words;
@@ -133,6 +140,7 @@ struct Lds {
   int32_t* delta;
   uint32_t* packed;
   uint32_t* rest;
+  uint16_t* cons;
   uint32_t* occ;
   int32_t* red;
   uint32_t* queue;
@@ -143,6 +151,7 @@ __device__ __forceinline__ Lds carve(uint32_t* base, const LdsLayout& lay) {
   l.delta = reinterpret_cast<int32_t*>(base + lay.delta_off);
   l.packed = base + lay.packed_off;
   l.rest = base + lay.rest_off;
+  l.cons = reinterpret_cast<uint16_t*>(base + lay.cons_off);
   l.occ = base + lay.occ_off;
   l.red = reinterpret_cast<int32_t*>(base + lay.red_off);
   l.queue = base + lay.queue_off;
@@ -325,6 +334,16 @@ __device__ __forceinline__ uint32_t addr_hi16(uint32_t p) {
   return r;
 }
 
+typedef __attribute__((address_space(3))) uint16_t lds_u16;
+__device__ __forceinline__ uint32_t lds_read_u16(uint32_t addr) { return *(const lds_u16*)(uintptr_t)addr; }
+// 2 * (high half of p): the LDS address of a 16-bit entry
+__device__ __forceinline__ uint32_t addr_hi16_half(uint32_t p) {
+  uint32_t r;
+  asm volatile("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_1"
+               : "=v"(r) : "s"(1u), "v"(p));
+  return r;
+}
+
 // The copies of a node as packed words s | e << 16 (MOC_DEAD if not live).
 template <int CT>
 struct Record {
@@ -452,15 +471,16 @@ __device__ __forceinline__ void fetch_edge(uint32_t pair, Record<CT>& pv, Record
   }
 }
 
-// Eq. (5), C >= 3, first pass over an edge pair = u | v << 16: only the first words of the
-// two nodes are fetched (pu, pv).  The instance is settled, with no violation, where the first
-// copy of u covers the start of the first copy of v and v has no other live copy.  All other
-// edges are returned and go to the wave's queue for the full test: the first copy of v not
-// covered by the first copy of u (another copy of u may cover it, or it is a violation, or v's
-// first copy is not live at all), or a node with other live copies.  Such a node carries
-// bit 15 in its first word, on top of the start (positions stay below 2^15): as a consumer its
-// start then lies above every end, as a provider above every start, so the test fails by
-// itself and costs nothing extra.
+// Eq. (5), C >= 3, first pass over an edge (u, v): the first copy of u (pu, a record word) and
+// the 16-bit entry of v as a consumer (pv) are fetched.  The instance is settled, with no
+// violation, where the first copy of u covers the start of the first copy of v and v has no
+// other live copy.  All other edges are returned and go to the wave's queue for the full test:
+// the first copy of v not covered by the first copy of u (another copy of u may cover it, or
+// it is a violation, or v's first copy is not live at all), or a consumer with other live
+// copies, each of which needs an input.  Such a consumer carries bit 15 on top of the start in
+// its entry (positions stay below 2^15): the start then lies above every end, so the test
+// fails by itself and costs nothing extra.  Whether u has other copies does not matter where
+// its first copy covers.
 __device__ __forceinline__ lanemask check_first_copies(int& viol, uint32_t pu, uint32_t pv) {
   lanemask t1, t2, more;
   asm("v_cmp_lt_u32_sdwa %0, %3, %4 src0_sel:WORD_0 src1_sel:WORD_0\n\t"
@@ -477,15 +497,15 @@ __device__ __forceinline__ lanemask check_first_copies(int& viol, uint32_t pu, u
 // for the `count` edges in the wave's queue, 64 at a time.
 template <int CT>
 __device__ __forceinline__ void drain_queue(int& viol, const Lds& L, const uint32_t* queue, int count, int lane,
-                                            uint32_t dummy_pair) {
+                                            uint32_t dummy_pair, uint32_t cons_base) {
   constexpr int RS = CT == 3 ? 2 : 4;
   for (int base = 0; base < count; base += kWave) {
     const int idx = base + lane;   // inside the queue: its capacity is a multiple of 64
     const uint32_t pair = pick(u_lt_k((uint32_t)idx, (uint32_t)count), queue[idx], dummy_pair);
-    const uint32_t v = pair >> 16, u = pair & 0xFFFFu;
+    const uint32_t v = (pair >> 16) - cons_base, u = pair & 0xFFFFu;
     Record<CT> pv, pu;
-    pv.w[0] = L.packed[v] & 0xFFFF7FFFu;   // without the mark (a dead word becomes s = 0x7FFF, e = 0: still s > e)
-    pu.w[0] = L.packed[u] & 0xFFFF7FFFu;
+    pv.w[0] = L.packed[v];
+    pu.w[0] = L.packed[u];
     if constexpr (CT == 3) {
       const uint2 rv = *reinterpret_cast<const uint2*>(L.rest + v * RS);
       const uint2 ru = *reinterpret_cast<const uint2*>(L.rest + u * RS);
@@ -521,16 +541,20 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
   uint32_t first_draw = 0;   // thread 0: the first two candidates of this workgroup, asked for before anything else
   if (tid == 0 && groups != 0) first_draw = atomicAdd(counter, 2u);
   uint32_t* const queue = L.queue + wave * lay.qcap;   // kSplit: this wave's edges set aside
+  // kSplit: the high half of an edge register is the index of the consumer's 16-bit entry, counted
+  // in 16-bit units from LDS address 0 (n + 2 * cons_off stays far below 2^16 for any T accepted)
+  const uint32_t cons_base = kSplit ? 2u * (uint32_t)lay.cons_off : 0u;
   // the pair of a node that is never live with itself: what idle lanes of the second pass look at
-  const uint32_t dummy_pair = kSplit ? (uint32_t)(n + 2) * 0x10001u : (uint32_t)(n * NS) * 0x10001u;
+  const uint32_t dummy_pair = kSplit ? (uint32_t)(n + 2) * 0x10001u + (cons_base << 16) : (uint32_t)(n * NS) * 0x10001u;
 
   for (int i = tid; i < lay.delta_len; i += NT) L.delta[i] = 0;
   for (int i = tid; i < lay.occ_words; i += NT) L.occ[i] = 0;
-  for (int i = tid; i < lay.packed_len; i += NT) L.packed[i] = MOC_DEAD;   // both record arrays, incl. the dummy nodes
+  for (int i = tid; i < lay.packed_len; i += NT) L.packed[i] = MOC_DEAD;   // the record arrays and the consumers' entries, incl. the dummy nodes
   if constexpr (kSplit) {
     __syncthreads();
     if (tid == 0) {   // the padding of the edge list is the edge (n + 1, n): start 1 inside [0, 0x7FFF]
       L.packed[n] = 1u;
+      L.cons[n] = 1;
       L.packed[n + 1] = 0x7FFF0000u;
     }
   }
@@ -540,7 +564,7 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
 #pragma unroll
   for (int j = 0; j < EPT; ++j) {
     const int e = j * NT + tid;
-    edge[j] = g.edge_pair[e];   // the list is padded with dummy edges to EPT * NT entries
+    edge[j] = g.edge_pair[e] + (cons_base << 16);   // the list is padded with dummy edges to EPT * NT entries
   }
   NodeIn<CT> in[ITERS];
   // m_v, w_v of the lane's nodes: re-read (from L2) at the start of each phase 1, behind the
@@ -667,8 +691,9 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
           } else if constexpr (CT == 2) {
             *reinterpret_cast<uint2*>(L.packed + v * 2) = make_uint2(rec.w[0], rec.w[1]);
           } else {
-            // bit 15: the node has other live copies, its edges take the full test (see check_first_copies)
-            L.packed[v] = rec.w[0] | pick(others, 0x00008000u);
+            // bit 15: the node has other live copies, its in-edges take the full test (see check_first_copies)
+            L.packed[v] = rec.w[0];
+            L.cons[v] = (uint16_t)(rec.w[0] | pick(others, 0x00008000u));
             if constexpr (CT == 3) *reinterpret_cast<uint2*>(L.rest + v * RS) = make_uint2(rec.w[1], rec.w[2]);
             else *reinterpret_cast<uint4*>(L.rest + v * RS) = make_uint4(rec.w[1], rec.w[2], rec.w[3], MOC_DEAD);
           }
@@ -753,13 +778,13 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
         }
       } else {
         if (queued > lay.qcap - kEdgesPerNode * kWave) {   // the slice might not fit: work the queue off first
-          drain_queue<CT>(eviol, L, queue, queued, lane, dummy_pair);
+          drain_queue<CT>(eviol, L, queue, queued, lane, dummy_pair, cons_base);
           queued = 0;
         }
         uint32_t pv[kEdgesPerNode], pu[kEdgesPerNode];
 #pragma unroll
         for (int j = 0; j < kEdgesPerNode; ++j) {
-          pv[j] = lds_read(addr_hi16(edge[it * kEdgesPerNode + j]));
+          pv[j] = lds_read_u16(addr_hi16_half(edge[it * kEdgesPerNode + j]));
           pu[j] = lds_read(addr_lo16(edge[it * kEdgesPerNode + j]));
         }
 #pragma unroll
@@ -770,7 +795,7 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
         }
       }
     }
-    if constexpr (kSplit) drain_queue<CT>(eviol, L, queue, queued, lane, dummy_pair);
+    if constexpr (kSplit) drain_queue<CT>(eviol, L, queue, queued, lane, dummy_pair, cons_base);
     uint32_t after_next;
     finish<NT, true>(L, g, tid, lane, wave, S, P, viol, 0, distinct - eviol, dur, out, b, drawn, &after_next);
     b = b_next;
