@@ -80,8 +80,8 @@ extern "C" {
 /* Largest T = n*C an uploaded graph may have: the per-candidate working set
  * (memory-delta array, one record of packed intervals per node, start bitmap)
  * lives in the 160 KB LDS of one compute unit.  The bound is reached with
- * C = 1; with more copies per node the records take more room (about 17500
- * for C = 3, 15600 for C = 4).  moc_graph_upload returns MOC_EOVERFLOW for a
+ * C = 1; with more copies per node the records take more room (about 16200
+ * for C = 3, 14900 for C = 4).  moc_graph_upload returns MOC_EOVERFLOW for a
  * graph that does not fit. */
 #define MOC_MAX_T 19455
 

@@ -410,6 +410,15 @@ __device__ __forceinline__ bool lanes(lanemask m) { return __builtin_amdgcn_inve
 __device__ __forceinline__ uint32_t rank_in(lanemask m, uint32_t base) {
   return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, base));
 }
+// LDS[addr] = val in the lanes of m, without a branch: a branch would end the basic block, and
+// 16-bit values that live across blocks are widened again where they are used.  LDS
+// operations of a wave complete in order, so later reads see the write; the wave's count of
+// outstanding LDS operations is only ever higher than the compiler assumes, never lower.
+__device__ __forceinline__ void lds_write_lanes(lanemask m, uint32_t addr, uint32_t val) {
+  lanemask saved;
+  asm volatile("s_and_saveexec_b64 %0, %1\n\tds_write_b32 %2, %3\n\ts_mov_b64 exec, %0"
+               : "=&s"(saved) : "s"(m), "v"(addr), "v"(val) : "memory", "scc");
+}
 
 // Eq. (5) for one copy of the consumer, packed as s | e << 16 in pv, against the CT copies of
 // the provider in pu: adds to viol the number of lanes in which the copy is live and no copy of
@@ -541,6 +550,7 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
   uint32_t first_draw = 0;   // thread 0: the first two candidates of this workgroup, asked for before anything else
   if (tid == 0 && groups != 0) first_draw = atomicAdd(counter, 2u);
   uint32_t* const queue = L.queue + wave * lay.qcap;   // kSplit: this wave's edges set aside
+  const uint32_t queue_addr = 4u * (uint32_t)(lay.queue_off + wave * lay.qcap);   // its LDS address
   // kSplit: the high half of an edge register is the index of the consumer's 16-bit entry, counted
   // in 16-bit units from LDS address 0 (n + 2 * cons_off stays far below 2^16 for any T accepted)
   const uint32_t cons_base = kSplit ? 2u * (uint32_t)lay.cons_off : 0u;
@@ -790,7 +800,8 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
 #pragma unroll
         for (int j = 0; j < kEdgesPerNode; ++j) {
           const lanemask more = check_first_copies(eviol, pu[j], pv[j]);
-          if (lanes(more)) queue[rank_in(more, (uint32_t)queued)] = edge[it * kEdgesPerNode + j];
+          const uint32_t tail = queue_addr + 4u * (uint32_t)queued;   // the same in every lane: scalar arithmetic
+          lds_write_lanes(more, tail + 4u * rank_in(more, 0u), edge[it * kEdgesPerNode + j]);
           queued += count(more);
         }
       }
