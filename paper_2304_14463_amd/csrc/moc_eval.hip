@@ -174,14 +174,41 @@ __device__ __forceinline__ int wave_sum(int v) {
          __builtin_amdgcn_readlane(v, 48);
 }
 
-// (sum, max prefix) of consecutive segments, one per lane, combined in lane order into lane 0.
+// (sum, max prefix) of consecutive segments, one per lane (max prefix >= 0 and >= sum, as a
+// running maximum that starts at 0 gives it), combined in lane order; the last lane ends with
+// the whole wave (the result stays in a vector register: scalar registers are scarce where this
+// is called).  Each lane takes in the lanes before it: inside rows of 16 by shifts of 1, 2, 4,
+// 8 (a lane with no source gets (0, 0), which changes nothing), then lane 15 of rows 0 and 2
+// goes to rows 1 and 3, then lane 31 to rows 2 and 3; lane 63 ends with the whole wave.
+template <int CTRL, int ROWS>
+__device__ __forceinline__ void absorb_earlier(int& S, int& P) {
+  const int Se = __builtin_amdgcn_update_dpp(0, S, CTRL, ROWS, 0xF, true);
+  const int Pe = __builtin_amdgcn_update_dpp(0, P, CTRL, ROWS, 0xF, true);
+  P = max(Pe, Se + P);
+  S = Se + S;
+}
+// IN_ALU: with the lane shifts of the vector ALU itself, else through the LDS crossbar, which
+// takes longer but leaves the vector ALU to the other waves.  Measured: the first is faster with
+// workgroups of up to 512 threads (n = 442: 43.9 -> 45.4 % of HBM peak, n = 1000: 57.4 -> 60.0 %),
+// the second with 1024 (n = 5000: 63.9 against 63.1 %), where the vector ALU is the busiest unit
+// and eight waves of a workgroup combine at the same time.
+template <bool IN_ALU>
 __device__ __forceinline__ void wave_combine_ordered(int lane, int& S, int& P) {
+  if constexpr (IN_ALU) {
+    absorb_earlier<0x111, 0xF>(S, P);   // row_shr:1
+    absorb_earlier<0x112, 0xF>(S, P);   // row_shr:2
+    absorb_earlier<0x114, 0xF>(S, P);   // row_shr:4
+    absorb_earlier<0x118, 0xF>(S, P);   // row_shr:8
+    absorb_earlier<0x142, 0xA>(S, P);   // row_bcast:15 into rows 1 and 3
+    absorb_earlier<0x143, 0xC>(S, P);   // row_bcast:31 into rows 2 and 3
+  } else {
 #pragma unroll
-  for (int off = 1; off < kWave; off <<= 1) {   // lane l absorbs lanes l+off .. l+2*off-1
-    const int S2 = __shfl_down(S, off), P2 = __shfl_down(P, off);
-    if (lane + off < kWave) {
-      P = max(P, S + P2);
-      S += S2;
+    for (int off = 1; off < kWave; off <<= 1) {   // lane l takes in lanes l-2*off+1 .. l-off
+      const int Se = __shfl_up(S, off), Pe = __shfl_up(P, off);
+      if (lane >= off) {
+        P = max(Pe, Se + P);
+        S = Se + S;
+      }
     }
   }
 }
@@ -220,7 +247,7 @@ __device__ __forceinline__ void finish(const Lds& L, const GraphView& g, int tid
   distinct = wave_sum(distinct);
   dur = wave_sum(dur);
   if constexpr (NW > 1) {
-    if (lane == 0) {
+    if (lane == kWave - 1) {   // the lane that holds the wave's (S, P); the sums are in every lane
       int32_t* r = L.red + wave * kRedStride;
       r[0] = S; r[1] = P; r[2] = viol + nlive - distinct; r[3] = dur;
     }
@@ -233,18 +260,13 @@ __device__ __forceinline__ void finish(const Lds& L, const GraphView& g, int tid
     P = has ? r[1] : 0;
     viol = wave_sum(has ? r[2] : 0);
     dur = wave_sum(has ? r[3] : 0);
-#pragma unroll
-    for (int off = 1; off < NW; off <<= 1) {
-      const int S2 = __shfl_down(S, off), P2 = __shfl_down(P, off);
-      P = max(P, S + P2);   // lanes >= NW hold (0, 0), the identity
-      S += S2;
-    }
+    wave_combine_ordered<(NT < 1024)>(lane, S, P);   // lanes >= NW hold (0, 0), which changes nothing
   } else {
     viol += nlive - distinct;   // Eq. (6): live copies minus distinct start positions
     __syncthreads();
     if (passed) *passed = (uint32_t)L.red[kRedPass];
   }
-  if (tid == 0) {
+  if (tid == kWave - 1) {
     moc_result res;
     res.peak = P;
     res.duration = dur;
@@ -764,7 +786,7 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
           __builtin_amdgcn_sched_barrier(0);
         }
       }
-      wave_combine_ordered(lane, S, P);
+      wave_combine_ordered<(NT < 1024)>(lane, S, P);
     }
     const int distinct = count_distinct_starts<NT>(L, lay, tid);
     // (c) edges, three per slice of the prefetch; their violations are counted per lane
@@ -881,7 +903,7 @@ __global__ __launch_bounds__(NT) void eval_batch_general_kernel(GraphView g, int
         P = max(P, S);
       }
     }
-    wave_combine_ordered(lane, S, P);
+    wave_combine_ordered<(NT < 1024)>(lane, S, P);
     const int distinct = count_distinct_starts<NT>(L, lay, tid);
     // Eq. (5): one lane per edge, every live copy of the consumer; edge_pair_c = u*C | v*C << 16
     for (int e = tid; e < g.m; e += NT) {
