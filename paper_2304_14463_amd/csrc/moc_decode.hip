@@ -38,14 +38,38 @@ DcLayout dc_layout(int n, int C) {
   return l;
 }
 
-// Inclusive wave scan of one value per lane.
-__device__ __forceinline__ int wave_scan_add(int x, int lane) {
-#pragma unroll
-  for (int off = 1; off < kWave; off <<= 1) {
-    const int o = __shfl_up(x, off);
-    if (lane >= off) x += o;
-  }
+// The value of the lane CTRL names (a lane shift of the vector ALU), 0 where that lane does not
+// exist or the row is not in ROWS.
+template <int CTRL, int ROWS>
+__device__ __forceinline__ int from_lane(int x) { return __builtin_amdgcn_update_dpp(0, x, CTRL, ROWS, 0xF, true); }
+
+// Inclusive wave scan of one value per lane: inside rows of 16 lanes by shifts of 1, 2, 4, 8,
+// then lane 15 of rows 0 and 2 is added to rows 1 and 3, then lane 31 to rows 2 and 3.
+__device__ __forceinline__ int wave_scan_add(int x, int /*lane*/) {
+  x += from_lane<0x111, 0xF>(x);   // row_shr:1
+  x += from_lane<0x112, 0xF>(x);   // row_shr:2
+  x += from_lane<0x114, 0xF>(x);   // row_shr:4
+  x += from_lane<0x118, 0xF>(x);   // row_shr:8
+  x += from_lane<0x142, 0xA>(x);   // row_bcast:15
+  x += from_lane<0x143, 0xC>(x);   // row_bcast:31
   return x;
+}
+
+// (sum, max prefix >= 0) of consecutive segments, one per lane, combined in lane order: the
+// last lane ends with the whole wave.
+template <int CTRL, int ROWS>
+__device__ __forceinline__ void absorb_earlier(int& S, int& P) {
+  const int Se = from_lane<CTRL, ROWS>(S), Pe = from_lane<CTRL, ROWS>(P);
+  P = max(Pe, Se + P);
+  S = Se + S;
+}
+__device__ __forceinline__ void wave_combine_ordered(int& S, int& P) {
+  absorb_earlier<0x111, 0xF>(S, P);
+  absorb_earlier<0x112, 0xF>(S, P);
+  absorb_earlier<0x114, 0xF>(S, P);
+  absorb_earlier<0x118, 0xF>(S, P);
+  absorb_earlier<0x142, 0xA>(S, P);
+  absorb_earlier<0x143, 0xC>(S, P);
 }
 
 // Both scans below walk the array in rows of 64 consecutive positions, one lane per position
@@ -92,7 +116,7 @@ __device__ int block_peak_of_running_sum(const int32_t* a, int T, int32_t* scrat
     const int x = r * kWave + lane;
     const int inc = wave_scan_add(x < T ? a[x] : 0, lane);
     top = max(top, carry + inc);
-    carry += __shfl(inc, kWave - 1);
+    carry += __builtin_amdgcn_readlane(inc, kWave - 1);
   }
 #pragma unroll
   for (int off = kWave / 2; off > 0; off >>= 1) top = max(top, __shfl_xor(top, off));
@@ -292,7 +316,7 @@ __device__ int block_peak_and_clear(int32_t* a, int words, int32_t* scratch, int
   const int lane = tid & (kWave - 1), wave = tid / kWave;
   const int rows = (words + 4 * kWave - 1) / (4 * kWave), rows_per_wave = (rows + kNW - 1) / kNW;
   const int r0 = min(wave * rows_per_wave, rows), r1 = min(r0 + rows_per_wave, rows);
-  int carry = 0, top = 0;   // lane 0: sum and highest running sum of this wave's rows, from the wave's first position
+  int carry = 0, top = 0;   // last lane: sum and highest running sum of this wave's rows, from the wave's first position
   for (int r = r0; r < r1; ++r) {
     const int x = (r * kWave + lane) * 4;
     int4 v = make_int4(0, 0, 0, 0);
@@ -304,18 +328,11 @@ __device__ int block_peak_and_clear(int32_t* a, int words, int32_t* scratch, int
     S += v.y; P = max(P, S);
     S += v.z; P = max(P, S);
     S += v.w; P = max(P, S);
-#pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) {   // lane l absorbs lanes l+off .. l+2*off-1
-      const int S2 = __shfl_down(S, off), P2 = __shfl_down(P, off);
-      if (lane + off < kWave) {
-        P = max(P, S + P2);
-        S += S2;
-      }
-    }
+    wave_combine_ordered(S, P);
     top = max(top, carry + P);
     carry += S;
   }
-  if (lane == 0) {
+  if (lane == kWave - 1) {   // the lane that holds the rows' combined values
     scratch[wave] = carry;
     scratch[kNW + wave] = top;
   }
@@ -417,8 +434,7 @@ void decode_fixed_kernel(GraphView G, int64_t B, const int32_t* __restrict__ sta
         mine += (who.x != 0) + (who.y != 0) + (who.z != 0) + (who.w != 0);
       }
     }
-#pragma unroll
-    for (int off = kWave / 2; off > 0; off >>= 1) mine += __shfl_xor(mine, off);
+    mine = __builtin_amdgcn_readlane(wave_scan_add(mine, lane), kWave - 1);
     if (lane == 0) scratch[wave] = mine;
     __syncthreads();
     int before = 0, length = 0;
@@ -443,7 +459,7 @@ void decode_fixed_kernel(GraphView G, int64_t B, const int32_t* __restrict__ sta
         }
         *reinterpret_cast<int4*>(a + x) = make_int4(0, 0, 0, 0);
       }
-      before += __shfl(incl, kWave - 1);
+      before += __builtin_amdgcn_readlane(incl, kWave - 1);
     }
     if (seq_row)
       for (int x = length + tid; x < T; x += kNT) seq_row[x] = -1;
