@@ -254,13 +254,25 @@ __device__ __forceinline__ void finish(const Lds& L, const GraphView& g, int tid
     __syncthreads();
     if (passed) *passed = (uint32_t)L.red[kRedPass];
     if (wave != 0) return;
-    const bool has = lane < NW;
-    const int32_t* r = L.red + (has ? lane : 0) * kRedStride;
-    S = has ? r[0] : 0;
-    P = has ? r[1] : 0;
-    viol = wave_sum(has ? r[2] : 0);
-    dur = wave_sum(has ? r[3] : 0);
-    wave_combine_ordered<(NT < 1024)>(lane, S, P);   // lanes >= NW hold (0, 0), which changes nothing
+    if constexpr (NW <= 4) {   // few waves: every lane adds them up by itself (the reads are broadcasts)
+      S = 0; P = 0; viol = 0; dur = 0;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) {
+        const int32_t* r = L.red + w * kRedStride;
+        P = max(P, S + r[1]);
+        S += r[0];
+        viol += r[2];
+        dur += r[3];
+      }
+    } else {
+      const bool has = lane < NW;
+      const int32_t* r = L.red + (has ? lane : 0) * kRedStride;
+      S = has ? r[0] : 0;
+      P = has ? r[1] : 0;
+      viol = wave_sum(has ? r[2] : 0);
+      dur = wave_sum(has ? r[3] : 0);
+      wave_combine_ordered<(NT < 1024)>(lane, S, P);   // lanes >= NW hold (0, 0), which changes nothing
+    }
   } else {
     viol += nlive - distinct;   // Eq. (6): live copies minus distinct start positions
     __syncthreads();
