@@ -57,8 +57,11 @@ constexpr int kRedStride = 8;      // ints per wave in the cross-wave exchange a
 constexpr int kRedPass = 4;        // word of that area through which thread 0 passes a value to all
 constexpr int kMaxIters = 6;       // nodes per lane the register-resident kernel is built for
 constexpr int kEdgesPerNode = 3;   // edges per lane = kEdgesPerNode * nodes per lane
-constexpr int kChunk = 32;         // delta positions per chunk ...
-constexpr int kChunkStride = 36;   // ... stored 36 words apart: 16 lanes x 16 bytes hit 64 distinct banks
+// The delta array is kept in chunks of 32 positions, one per scanning lane, stored 36 words
+// apart (16 lanes x 16 bytes then hit 64 distinct banks); workgroups of one or two waves take
+// chunks of 16 positions, 20 words apart, so that more of their lanes share the scan.
+constexpr int chunk_positions(int nt) { return nt <= 128 ? 16 : 32; }
+constexpr int chunk_stride(int nt) { return chunk_positions(nt) + 4; }
 constexpr int64_t kMaxLaunch = (int64_t)1 << 31;   // candidates per launch
 static_assert(MOC_MAX_T < 0x8000, "bit 15 of a consumer's 16-bit start marks nodes with other live copies (C >= 3)");
 constexpr int kQueueCap = 320;     // C >= 3: edges a wave sets aside before it has to work them off
@@ -68,7 +71,7 @@ constexpr int kQueueCap = 320;     // C >= 3: edges a wave sets aside before it 
 struct LdsLayout {
   int packed_off, cons_off, rest_off, delta_off, occ_off, red_off, queue_off;
   int chunk;       // general kernel: delta entries per thread (odd: conflict-free strided reads)
-  int n_chunks;    // register-resident kernel: chunks of kChunk positions
+  int n_chunks;    // register-resident kernel: chunks of chunk_positions(nt) positions
   int delta_len;
   int packed_len;  // node records (register-resident kernel, C >= 3: first copies, then the rest)
   int occ_words;   // ceil(T / 32)
@@ -92,8 +95,8 @@ LdsLayout fast_layout(int n, int m, int C, int nt, int max_lds) {
   const int T = n * C, nw = nt / kWave;
   LdsLayout l;
   l.chunk = 0;
-  l.n_chunks = (T + 1 + kChunk - 1) / kChunk;
-  l.delta_len = l.n_chunks * kChunkStride;
+  l.n_chunks = (T + 1 + chunk_positions(nt) - 1) / chunk_positions(nt);
+  l.delta_len = l.n_chunks * chunk_stride(nt);
   const int first_len = round4((n + (C >= 3 ? 3 : 1)) * moc_node_stride(C));
   const int rest_len = C >= 3 ? round4((n + 3) * (C == 3 ? 2 : 4)) : 0;
   const int cons_len = C >= 3 ? round4((n + 3 + 1) / 2) : 0;   // 16 bits per node
@@ -384,11 +387,14 @@ struct Record {
   uint32_t w[CT];
 };
 
-// position t of the delta array -> word index t + 4 * (t / 32) (chunks of 32 words, 36 apart),
-// in the two instructions it takes
+// position t of the delta array -> word index t + 4 * (t / CH) (chunks of CH words, CH + 4
+// apart), in the two instructions it takes
+template <int CH>
 __device__ __forceinline__ int delta_at(int t) {
+  static_assert(CH == 16 || CH == 32, "chunks of 16 or 32 positions");
   int idx;
-  asm("v_lshrrev_b32 %0, 5, %1\n\tv_lshl_add_u32 %0, %0, 2, %1" : "=&v"(idx) : "v"(t));
+  if constexpr (CH == 32) asm("v_lshrrev_b32 %0, 5, %1\n\tv_lshl_add_u32 %0, %0, 2, %1" : "=&v"(idx) : "v"(t));
+  else asm("v_lshrrev_b32 %0, 4, %1\n\tv_lshl_add_u32 %0, %0, 2, %1" : "=&v"(idx) : "v"(t));
   return idx;
 }
 
@@ -574,6 +580,7 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
   constexpr int NS = kSplit ? 1 : CT;       // words per node in the first array
   constexpr int RS = CT == 3 ? 2 : 4;       // kSplit: words per node in the second
   constexpr int kEarly = ITERS * 3 / 5;     // node slots re-requested during phase 1
+  constexpr int CH = chunk_positions(NT);   // delta positions per chunk
   extern __shared__ uint32_t lds_raw[];
   const Lds L = carve(lds_raw, lay);
   const int tid = threadIdx.x, lane = tid & (kWave - 1);
@@ -632,8 +639,8 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
   // Eq. (4), (6): one live copy [s, e] of a node of size m_v into the delta array (+m_v at s,
   // -m_v after e) and the bitmap of start positions
   auto scatter = [&](int s, int e, int size) {
-    atomicAdd(&L.delta[delta_at(s)], size);
-    atomicSub(&L.delta[delta_at(e + 1)], size);
+    atomicAdd(&L.delta[delta_at<CH>(s)], size);
+    atomicSub(&L.delta[delta_at<CH>(e + 1)], size);
     atomicOr(&L.occ[s >> 5], 1u << (s & 31));
   };
   request_size_dur();
@@ -777,13 +784,13 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
     // ---------------- phase 2 (LDS only), with the next candidate's loads issued in slices
     if (kEarly < ITERS) request(kEarly, next_row);
     __builtin_amdgcn_sched_barrier(0);
-    // (a) one chunk of 32 delta positions per thread
+    // (a) one chunk of CH delta positions per thread
     int S = 0, P = 0;
     if (wave * kWave < lay.n_chunks) {
       if (tid < lay.n_chunks) {
-        int4* d = reinterpret_cast<int4*>(L.delta + tid * kChunkStride);
+        int4* d = reinterpret_cast<int4*>(L.delta + tid * (CH + 4));
 #pragma unroll
-        for (int h = 0; h < kChunk / 8; ++h) {   // 8 positions at a time keeps the register count down
+        for (int h = 0; h < CH / 8; ++h) {   // 8 positions at a time keeps the register count down
           const int4 x0 = d[2 * h], x1 = d[2 * h + 1];
           d[2 * h] = make_int4(0, 0, 0, 0);
           d[2 * h + 1] = make_int4(0, 0, 0, 0);
@@ -988,18 +995,19 @@ int slots_per_lane(int n, int m, int nt) {
   return by_nodes > by_edges ? by_nodes : by_edges;
 }
 
-// Workgroup size: the smallest that leaves at most 5 node slots per lane (one wave per
+// Workgroup size: the smallest that leaves at most 5 node slots per lane and at most one delta
+// chunk per thread (one wave per
 // candidate for small graphs, up to a full 1024-thread workgroup per compute unit).
-int block_threads(int n, int m) {
+int block_threads(int n, int m, int C) {
   for (int nt = 64; nt < 1024; nt *= 2)
-    if (slots_per_lane(n, m, nt) <= 5) return nt;
+    if (slots_per_lane(n, m, nt) <= 5 && (n * C + chunk_positions(nt)) / chunk_positions(nt) <= nt) return nt;
   return 1024;
 }
 
 // The register-resident kernel applies when C <= 4, a lane's nodes and edges fit its
 // registers, and every thread has at most one delta chunk.
 bool fast_shape(int n, int m, int C, int nt) {
-  return C <= 4 && n * C >= 4 && slots_per_lane(n, m, nt) <= kMaxIters && (n * C + kChunk) / kChunk <= nt &&
+  return C <= 4 && n * C >= 4 && slots_per_lane(n, m, nt) <= kMaxIters && (n * C + chunk_positions(nt)) / chunk_positions(nt) <= nt &&
          (n + 3) * moc_node_stride(C) <= 0xFFFF;
 }
 
@@ -1025,14 +1033,14 @@ int launch_nt(const moc_graph* g, int64_t B, const int32_t* s, const int32_t* e,
 int moc_node_stride(int C) { return C == 2 ? 2 : 1; }
 
 bool moc_eval_shape(int n, int m, int C, int* nt, int* edges_per_lane, int* edges_per_lane_used) {
-  *nt = block_threads(n, m);
+  *nt = block_threads(n, m, C);
   *edges_per_lane = kEdgesPerNode * slots_per_lane(n, m, *nt);
   *edges_per_lane_used = kEdgesPerNode * ((m + kEdgesPerNode * *nt - 1) / (kEdgesPerNode * *nt));
   return fast_shape(n, m, C, *nt);
 }
 
 int moc_eval_lds_bytes(int n, int m, int C, int max_lds) {
-  const int nt = block_threads(n, m);
+  const int nt = block_threads(n, m, C);
   const int general = general_layout(n, C, nt).bytes;
   if (!fast_shape(n, m, C, nt)) return general;
   const int fast = fast_layout(n, m, C, nt, max_lds).bytes;   // misaligned candidate arrays fall back to the general kernel
@@ -1044,7 +1052,7 @@ namespace {
 // One launch per 2^31 candidates of the kernel this graph and these arrays take.
 int dispatch(const moc_graph* g, int64_t B, const int32_t* starts, const int32_t* ends, const uint8_t* active,
              moc_result* out, hipStream_t st, bool aligned, const LaunchOpts& src) {
-  const int nt = block_threads(g->view.n, g->view.m);
+  const int nt = block_threads(g->view.n, g->view.m, g->view.C);
   // The kernels count candidates handed out in 32 bits: longer batches go in several launches.
   const int64_t T = g->view.T;
   for (int64_t at = 0; at < B; at += kMaxLaunch) {
