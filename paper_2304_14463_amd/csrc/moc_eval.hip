@@ -77,6 +77,7 @@ struct LdsLayout {
   int occ_words;   // ceil(T / 32)
   int qcap;        // register-resident kernel, C >= 3: entries per wave in the queue of edges set aside
   int edge_slices; // register-resident kernel: slices of kEdgesPerNode edges per lane that hold edges
+  int edge_slots;  // ... and edges per lane that do (the last slice may hold fewer than kEdgesPerNode)
   int bytes;
 };
 
@@ -110,6 +111,7 @@ LdsLayout fast_layout(int n, int m, int C, int nt, int max_lds) {
   l.red_off = l.occ_off + l.occ_words;
   l.queue_off = l.red_off + nw * kRedStride;
   l.edge_slices = (m + kEdgesPerNode * nt - 1) / (kEdgesPerNode * nt);
+  l.edge_slots = (m + nt - 1) / nt;
   l.qcap = C >= 3 ? kQueueCap : 0;
   l.bytes = 4 * (l.queue_off + nw * l.qcap);
   while (l.bytes > max_lds && l.qcap > kEdgesPerNode * kWave) {   // a slice of edges must fit
@@ -135,6 +137,7 @@ LdsLayout general_layout(int n, int C, int nt) {
   l.queue_off = l.red_off + (nt / kWave) * kRedStride;
   l.qcap = 0;
   l.edge_slices = 0;
+  l.edge_slots = 0;
   l.bytes = 4 * l.queue_off;
   return l;
 }
@@ -819,14 +822,23 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
       // the records of the slice's edges are asked for together and looked at afterwards: one
       // LDS latency per slice, not one per edge
       if constexpr (!kSplit) {
-        Record<CT> pv[kEdgesPerNode], pu[kEdgesPerNode];
+        auto edges_of_slice = [&](auto count) {
+          constexpr int N = decltype(count)::value;
+          Record<CT> pv[N], pu[N];
 #pragma unroll
-        for (int j = 0; j < kEdgesPerNode; ++j) fetch_edge<CT>(edge[it * kEdgesPerNode + j], pv[j], pu[j]);
+          for (int j = 0; j < N; ++j) fetch_edge<CT>(edge[it * kEdgesPerNode + j], pv[j], pu[j]);
 #pragma unroll
-        for (int j = 0; j < kEdgesPerNode; ++j) {
+          for (int j = 0; j < N; ++j) {
 #pragma unroll
-          for (int i = 0; i < CT; ++i) count_live_uncovered<CT>(eviol, pu[j], pv[j].w[i]);
-        }
+            for (int i = 0; i < CT; ++i) count_live_uncovered<CT>(eviol, pu[j], pv[j].w[i]);
+          }
+        };
+        // The lane's last slice may hold edges in its first one or two entries only (padding in
+        // every lane beyond): blocks of their own, each one straight run of reads, then tests.
+        const int here = lay.edge_slots - it * kEdgesPerNode;   // > 0
+        if (it == ITERS - 1 && here == 1) edges_of_slice(std::integral_constant<int, 1>{});
+        else if (it == ITERS - 1 && here == 2) edges_of_slice(std::integral_constant<int, 2>{});
+        else edges_of_slice(std::integral_constant<int, kEdgesPerNode>{});
       } else {
         if (queued > lay.qcap - kEdgesPerNode * kWave) {   // the slice might not fit: work the queue off first
           drain_queue<CT>(eviol, L, queue, queued, lane, dummy_pair, cons_base);
@@ -1035,7 +1047,7 @@ int moc_node_stride(int C) { return C == 2 ? 2 : 1; }
 bool moc_eval_shape(int n, int m, int C, int* nt, int* edges_per_lane, int* edges_per_lane_used) {
   *nt = block_threads(n, m, C);
   *edges_per_lane = kEdgesPerNode * slots_per_lane(n, m, *nt);
-  *edges_per_lane_used = kEdgesPerNode * ((m + kEdgesPerNode * *nt - 1) / (kEdgesPerNode * *nt));
+  *edges_per_lane_used = (m + *nt - 1) / *nt;   // = LdsLayout::edge_slots
   return fast_shape(n, m, C, *nt);
 }
 
