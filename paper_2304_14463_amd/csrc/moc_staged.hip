@@ -49,14 +49,19 @@ StLayout st_layout(int n, int C) {
   return l;
 }
 
+// First position of stage j, j < 2^16 (24-bit multiply: full rate).
+__device__ __forceinline__ uint32_t stage_start(int j) { return __umul24((uint32_t)j, (uint32_t)j + 1u) >> 1; }
+
 // The stage that holds position p (0 <= p < 2^31): the largest j with j(j+1)/2 <= p.  A
-// floating-point estimate, then exact integer steps, so that the result does not depend on
-// how the square root rounds.
+// floating-point estimate, then one exact integer step each way, so that the result does not
+// depend on how the square root rounds: the estimate's error stays far below one stage (the
+// relative error of the root is a few 2^-24 and the root at most 2^17), so its floor is off by
+// one at most.
 __device__ __forceinline__ int stage_of(uint32_t p) {
   int j = (int)((__fsqrt_rn(8.0f * (float)p + 1.0f) - 1.0f) * 0.5f);
   j = max(j, 0);
-  while ((uint32_t)j * (uint32_t)(j + 1) / 2u > p) --j;
-  while ((uint32_t)(j + 1) * (uint32_t)(j + 2) / 2u <= p) ++j;
+  j -= stage_start(j) > p ? 1 : 0;
+  j += stage_start(j + 1) <= p ? 1 : 0;
   return j;
 }
 
@@ -107,6 +112,17 @@ __global__ __launch_bounds__(kNT) void eval_staged_kernel(GraphView g, const int
     }
   };
   if ((int64_t)blockIdx.x < B) request(blockIdx.x);
+  // place, m_v, w_v of the lane's nodes: the same for every candidate
+  [[maybe_unused]] int rk[RU];
+  [[maybe_unused]] int2 rsd[RU];
+  if constexpr (CT > 0) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int v = min(u * kNT + tid, n - 1);
+      rk[u] = place[v];
+      rsd[u] = g.size_dur[v];
+    }
+  }
 
   for (int64_t b = blockIdx.x; b < B; b += gridDim.x) {
     const int64_t row = b * T;
@@ -123,7 +139,7 @@ __global__ __launch_bounds__(kNT) void eval_staged_kernel(GraphView g, const int
       int j = -1;
       if (live) {
         j = stage_of((uint32_t)s);
-        live = (uint32_t)s - (uint32_t)j * (uint32_t)(j + 1) / 2u == (uint32_t)k && (i > 0 || j == k);
+        live = (uint32_t)s - stage_start(j) == (uint32_t)k && (i > 0 || j == k);
       }
       viol += (act && !live) ? 1 : 0;
       if (i == 0) viol += act ? 0 : 1;
@@ -144,14 +160,40 @@ __global__ __launch_bounds__(kNT) void eval_staged_kernel(GraphView g, const int
       pe[c] = e;
     };
     if constexpr (CT > 0) {
+      // the same per copy, on registers: the start's register takes the copy's code (stage << 1 |
+      // first at its position, -2 if not usable), which the next two phases read
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const int v = u * kNT + tid;
         if (v < n) {
-          const int k = place[v], w = g.size_dur[v].y;
+          const int k = rk[u], w = rsd[u].y;
           int prev_end = -1;
 #pragma unroll
-          for (int i = 0; i < CT; ++i) copy_step(v, k, w, i, rs[u][i], re[u][i], ra[u][i] != 0, prev_end);
+          for (int i = 0; i < CT; ++i) {
+            const int s = rs[u][i], e = re[u][i];
+            const bool act = ra[u][i] != 0;
+            bool live = act && (uint32_t)s <= (uint32_t)e && (uint32_t)e < D;
+            int j = -1;
+            if (live) {
+              j = stage_of((uint32_t)s);
+              live = (uint32_t)s - stage_start(j) == (uint32_t)k && (i > 0 || j == k);
+            }
+            viol += (act && !live) ? 1 : 0;
+            if (i == 0) viol += act ? 0 : 1;
+            dur += act ? w : 0;
+            int code = -2;
+            if (live) {
+              viol += prev_end > s ? 1 : 0;   // Eq. (3), on the positions as given
+              prev_end = e;
+              bool first_here = true;         // Eq. (6), see above
+#pragma unroll
+              for (int q = 0; q < i; ++q) first_here = first_here && rs[u][q] >> 1 != j;
+              if (first_here) atomicAdd(&cur[j], 1);
+              else viol += 1;
+              code = j << 1 | (first_here ? 1 : 0);
+            }
+            rs[u][i] = code;
+          }
         }
       }
     } else {
@@ -162,7 +204,6 @@ __global__ __launch_bounds__(kNT) void eval_staged_kernel(GraphView g, const int
           copy_step(v, k, w, i, starts[row + v * C + i], ends[row + v * C + i], active[row + v * C + i] != 0, prev_end);
       }
     }
-    if (b + gridDim.x < B) request(b + gridDim.x);   // the rest of this turn works from LDS
     __syncthreads();
 
     // ---- cur[j] <- number of distinct usable starts in stages 0..j (inclusive running sum)
@@ -191,16 +232,64 @@ __global__ __launch_bounds__(kNT) void eval_staged_kernel(GraphView g, const int
     __syncthreads();
 
     // ---- buckets: the place of every node that has a first-at-its-position start in the stage
-    for (int v = tid; v < n; v += kNT) {
-      const int k = place[v];
-      for (int i = 0; i < C; ++i) {
-        const int code = pj[v * C + i];
-        if (code >= 0 && (code & 1)) bucket[atomicAdd(&cur[code >> 1], 1)] = (uint16_t)k;
+    if constexpr (CT > 0) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        if (u * kNT + tid >= n) continue;
+#pragma unroll
+        for (int i = 0; i < CT; ++i) {
+          const int code = rs[u][i];
+          if (code >= 0 && (code & 1)) bucket[atomicAdd(&cur[code >> 1], 1)] = (uint16_t)rk[u];
+        }
+      }
+    } else {
+      for (int v = tid; v < n; v += kNT) {
+        const int k = place[v];
+        for (int i = 0; i < C; ++i) {
+          const int code = pj[v * C + i];
+          if (code >= 0 && (code & 1)) bucket[atomicAdd(&cur[code >> 1], 1)] = (uint16_t)k;
+        }
       }
     }
     __syncthreads();   // now cur[j] = end of stage j's bucket = start of stage j + 1's
 
     // ---- renumber, stage the records, scatter Eq. (4)
+    // Entries of stage j's bucket below `key` (or up to it), on top of the bucket's offset.  A
+    // bucket holds the stage's own node and the few nodes recomputed in the stage: the first two
+    // entries are read at once, a loop takes the rest.
+    [[maybe_unused]] auto rank_in_stage = [&](int j, uint32_t key, bool up_to) -> int {
+      const int lo = j ? cur[j - 1] : 0, hi = cur[j];
+      const uint32_t b0 = lo < hi ? bucket[lo] : 0xFFFFu, b1 = lo + 1 < hi ? bucket[lo + 1] : 0xFFFFu;   // places stay below 0xFFFF
+      const uint32_t bound = key + (up_to ? 1u : 0u);
+      int r = lo + (b0 < bound ? 1 : 0) + (b1 < bound ? 1 : 0);
+      for (int x = lo + 2; x < hi; ++x) r += bucket[x] < bound ? 1 : 0;
+      return r;
+    };
+    if constexpr (CT > 0) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int v = u * kNT + tid;
+        if (v >= n) continue;
+#pragma unroll
+        for (int i = 0; i < CT; ++i) {
+          const int code = rs[u][i];
+          uint32_t rec = MOC_DEAD;
+          if (code >= 0) {
+            const int cs = rank_in_stage(code >> 1, (uint32_t)rk[u], false);
+            // the last start position not after the end: all starts of earlier stages, and those of
+            // the end's stage at slots up to the end's
+            const uint32_t e = (uint32_t)re[u][i];
+            const int je = stage_of(e);
+            const int ce = rank_in_stage(je, e - stage_start(je), true) - 1;
+            rec = (uint32_t)cs | (uint32_t)ce << 16;
+            atomicAdd(&delta[cs], rsd[u].x);
+            atomicSub(&delta[ce + 1], rsd[u].x);
+          }
+          pj[v * CT + i] = (int32_t)rec;
+        }
+      }
+      if (b + gridDim.x < B) request(b + gridDim.x);   // the rest of this turn works from LDS
+    } else
     for (int v = tid; v < n; v += kNT) {
       const int2 sd = g.size_dur[v];
       const int k = place[v];
