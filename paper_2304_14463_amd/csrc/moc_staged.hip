@@ -75,7 +75,7 @@ __device__ __forceinline__ int wave_sum_i(int v) {
 // the top of its turn and for the workgroup's next candidate as soon as they are used), else 0
 // (any C, read where needed); U = nodes per lane, ceil(n / kNT), when CT > 0.
 template <int CT, int U>
-__global__ __launch_bounds__(kNT) void eval_staged_kernel(GraphView g, const int32_t* __restrict__ place, int64_t B,
+__global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) void eval_staged_kernel(GraphView g, const int32_t* __restrict__ place, int64_t B,
                                                           const int32_t* __restrict__ starts,
                                                           const int32_t* __restrict__ ends,
                                                           const uint8_t* __restrict__ active,
