@@ -82,11 +82,12 @@ def test_staged_worked_example(moc):
 
 
 @pytest.mark.parametrize("n,C", [(1, 1), (2, 2), (3, 3), (7, 1), (13, 3), (40, 4), (64, 2), (65, 3), (130, 5),
-                                 (513, 2), (700, 3), (1025, 1), (1500, 2)])
+                                 (513, 2), (700, 3), (1025, 1), (1500, 2), (4000, 2)])
 def test_staged_ragged_shapes_random_values(moc, n, C):
     """Random DAGs, a random topological order, and candidates with starts on and off their
     slots, first copies on and off their fixed start, ends anywhere, values outside the domain,
-    flags at random, several copies of a node on one event."""
+    flags at random, several copies of a node on one event, ends on the first position of a stage
+    and on the position before it (up to 8 million positions at n = 4000)."""
     from paper_2304_14463_amd.inputs import graph_from_edges
     rng = np.random.default_rng(n * 17 + C)
     edges = set()
@@ -112,7 +113,7 @@ def test_staged_ragged_shapes_random_values(moc, n, C):
     index = np.zeros(n, np.int32)
     index[order] = np.arange(n)
     D = n * (n + 1) // 2
-    B = 24
+    B = 24 if n <= 2000 else 6
     K = n * C
     s = rng.integers(-2, D + 2, size=(B, K)).astype(np.int64)
     on = rng.random((B, K)) < 0.8
@@ -122,6 +123,9 @@ def test_staged_ragged_shapes_random_values(moc, n, C):
     s = np.where(on, slot_pos, s)
     e = s + rng.integers(-1, max(2, D // 3), size=(B, K))
     e = np.where(rng.random((B, K)) < 0.1, rng.integers(-2, D + 2, size=(B, K)), e)
+    later = rng.integers(stage.reshape(B, K), n + 1)   # a stage not before the start's (n: one past the last)
+    edge_of_stage = later * (later + 1) // 2 - rng.integers(0, 2, size=(B, K))
+    e = np.where(rng.random((B, K)) < 0.2, edge_of_stage, e)
     a = ((rng.random((B, K)) < 0.7) * rng.integers(1, 256, size=(B, K))).astype(np.uint8)
     s, e = s.astype(np.int32), e.astype(np.int32)
     # row 0: the plain schedule; row 1: every copy of a node on the node's fixed start
