@@ -311,7 +311,7 @@ __device__ __forceinline__ NodeStarts<CT> read_starts(const uint16_t* st, int v)
 // max over x in [0, T] of a[0] + ... + a[x] (at least 0); every a[x] is left at zero.  The entry
 // at T only ever holds releases (values <= 0), so it cannot raise the maximum.  A wave takes
 // rows of 256 positions, four per lane in one 16-byte read; `words` (a multiple of 4, > T) is
-// the length of the array.  Ends with a barrier.
+// the length of the array.
 __device__ int block_peak_and_clear(int32_t* a, int words, int32_t* scratch, int tid) {
   const int lane = tid & (kWave - 1), wave = tid / kWave;
   const int rows = (words + 4 * kWave - 1) / (4 * kWave), rows_per_wave = (rows + kNW - 1) / kNW;
@@ -342,7 +342,8 @@ __device__ int block_peak_and_clear(int32_t* a, int words, int32_t* scratch, int
     best = max(best, before + scratch[kNW + w]);
     before += scratch[w];
   }
-  __syncthreads();
+  // No barrier here: the caller's next write to `scratch` lies behind its next barrier, and the
+  // array is clear for every wave since the barrier above.
   return best;
 }
 
