@@ -827,6 +827,7 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
           Record<CT> pv[N], pu[N];
 #pragma unroll
           for (int j = 0; j < N; ++j) fetch_edge<CT>(edge[it * kEdgesPerNode + j], pv[j], pu[j]);
+          __builtin_amdgcn_sched_barrier(0);   // all reads of the slice before its first test
 #pragma unroll
           for (int j = 0; j < N; ++j) {
 #pragma unroll
