@@ -83,12 +83,14 @@ static std::vector<uint32_t> place_edges(int n, int C, const int32_t* in_ptr, co
   const uint32_t dummy = C >= 3 ? (uint32_t)(n + 1) | ((uint32_t)n << 16) : (uint32_t)(n * ns) | ((uint32_t)(n * ns) << 16);
   std::vector<uint32_t> out((size_t)nt * edges_per_lane, dummy);
   std::vector<std::vector<uint32_t>> bucket((size_t)banks * banks);   // [bank of u][bank of v] -> pairs
+  // C >= 3: the first pass over an edge reads the consumer's 16-bit entry, two to a bank word
+  auto bank_of_consumer = [&](int v) { return C >= 3 ? (v >> 1) % banks : v % banks; };
   std::vector<int> row(banks, 0);
   size_t left = 0;
   for (int v = 0; v < n; ++v)
     for (int q = in_ptr[v]; q < in_ptr[v + 1]; ++q) {
       const int u = in_idx[q];
-      bucket[(size_t)(u % banks) * banks + v % banks].push_back((uint32_t)(u * ns) | ((uint32_t)(v * ns) << 16));
+      bucket[(size_t)(u % banks) * banks + bank_of_consumer(v)].push_back((uint32_t)(u * ns) | ((uint32_t)(v * ns) << 16));
       ++row[u % banks];
       ++left;
     }
