@@ -159,10 +159,12 @@ def random_candidates(rng, B, n, C, T, wild):
 
 
 @pytest.mark.parametrize("n,C", [(1, 1), (1, 3), (2, 2), (7, 1), (13, 3), (21, 5), (64, 2), (65, 3), (100, 7),
-                                 (341, 3), (513, 2), (1025, 1), (1031, 2), (1537, 4), (2049, 3), (3000, 6)])
+                                 (341, 3), (513, 2), (1025, 1), (1031, 2), (1537, 4), (2049, 3), (3000, 6),
+                                 (255, 4), (256, 4), (320, 4), (511, 4), (512, 4), (640, 2), (640, 3)])
 def test_eval_ragged_shapes_random_candidates(moc, n, C):
     """Shapes around every tile boundary (wave of 64 nodes, 4 copies per lane, workgroup
-    sizes, rows whose byte length is not a multiple of 16) with random DAGs and random,
+    sizes, rows whose byte length is not a multiple of 16, the sizes at which small workgroups
+    run out of delta chunks of 16 positions) with random DAGs and random,
     mostly infeasible candidates including out-of-domain positions and a > 1."""
     from paper_2304_14463_amd.inputs import graph_from_edges
     rng = np.random.default_rng(n * 131 + C)
