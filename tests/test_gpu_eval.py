@@ -202,6 +202,38 @@ def test_eval_ragged_shapes_random_candidates(moc, n, C):
 
 
 
+@pytest.mark.parametrize("n,m,C", [(64, 100, 2), (64, 250, 2), (64, 300, 1), (64, 380, 2), (128, 700, 2),
+                                   (128, 850, 1), (256, 2300, 2), (256, 2700, 2)])
+def test_eval_partial_last_slice_of_edges(moc, n, m, C):
+    """Graphs whose edge count, not their node count, sets the number of edge slices per lane,
+    with a last slice that holds edges in one, two or all three of its entries (C <= 2: the
+    kernel has a block of its own for each case)."""
+    from paper_2304_14463_amd.inputs import graph_from_edges
+    import oracle
+    rng = np.random.default_rng(n * 7 + m)
+    edges = set()
+    while len(edges) < m:
+        v = int(rng.integers(1, n))
+        edges.add((int(rng.integers(0, v)), v))
+    g = graph_from_edges(n, sorted(edges), rng.integers(1, 1000, n), rng.integers(1, 50, n))
+    T = n * C
+    B = 64
+    s, e, a = random_candidates(rng, B, n, C, T, wild=False)
+    # half of the rows close to a schedule: node v computed at v*C and kept to the end, so that
+    # most edges are satisfied and the unsatisfied ones stand out
+    base = np.repeat(np.arange(n) * C, C).astype(np.int32)
+    s[::2], e[::2] = base, T - 1
+    a[::2].reshape(-1, n, C)[:, :, 1:] = 0
+    a[::2].reshape(-1, n, C)[:, :, 0] = 1
+    s[2::4] += rng.integers(0, 3, size=s[2::4].shape).astype(np.int32) * (s[2::4] + 3 < T)
+    budget = int(g.size.sum()) // 2
+    gh = moc.moc_graph_upload(n, g.in_ptr, g.in_idx, g.size, g.dur, budget, C)
+    ref = oracle.evaluate(g, budget, C, s, e, a)
+    assert ref[0, F["violations"]] == 0 and ref[:, F["v_prec"]].max() > 0
+    assert_results_equal(run_eval(moc, gh, s, e, a), ref, f"n={n} m={m} C={C}")
+    gh.free()
+
+
 @pytest.mark.parametrize("n,C,B", [(96, 3, 40000), (200, 2, 50000), (96, 3, 3000)])
 def test_eval_many_launches_one_graph(moc, n, C, B):
     """Launches share the graph's work counters, which every launch must leave at zero: 40
