@@ -554,18 +554,25 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
   }
 
   for (int64_t b = blockIdx.x; b < B; b += gridDim.x) {
+    // what the staging below derives from the thread index is computed again for every base:
+    // kept across bases it would sit in registers that the scoring needs, or be spilled
+    int t_ = tid;
+    asm volatile("" : "+v"(t_));
+    const int lane_ = t_ & (kWave - 1);
+    const int wave_ = __builtin_amdgcn_readfirstlane(t_ / kWave);
+
     const int64_t row = b * T;
     moc_move_score* const row0 = TABLE && out_moves ? out_moves + b * (int64_t)moves_per_cand : nullptr;   // this candidate's table
     // ---- base candidate: stage copies, scatter deltas, mark starts
-    for (int t = tid; t < T; t += kNT) L.profile[t] = 0;
-    for (int w = tid; w < 2 * lay.bit_words + lay.mask_words; w += kNT) L.occ1[w] = 0;   // occ1, occ2, involved
-    if (tid < 4) counts[tid] = tid == 2 ? 0x7FFFFFFF : 0;
-    if (tid == 0) { L.pmax[-1] = 0; L.smax[T] = 0; }
+    for (int t = t_; t < T; t += kNT) L.profile[t] = 0;
+    for (int w = t_; w < 2 * lay.bit_words + lay.mask_words; w += kNT) L.occ1[w] = 0;   // occ1, occ2, involved
+    if (t_ < 4) counts[t_] = t_ == 2 ? 0x7FFFFFFF : 0;
+    if (t_ == 0) { L.pmax[-1] = 0; L.smax[T] = 0; }
     __syncthreads();
     // whole waves, 64 consecutive copies each: a ballot gives the active flags of the 64
     int viol = 0, nlive = 0;
-    for (int k0 = wave * kWave; k0 < T; k0 += kNT) {
-      const int k = k0 + lane;
+    for (int k0 = wave_ * kWave; k0 < T; k0 += kNT) {
+      const int k = k0 + lane_;
       bool act = false;
       if (k < T) {
         const int s = starts[row + k], e = ends[row + k];
@@ -585,7 +592,7 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
         }
       }
       const uint64_t am = __ballot(act);
-      if (lane == 0) {
+      if (lane_ == 0) {
         L.amask[k0 >> 5] = (uint32_t)am;
         L.amask[(k0 >> 5) + 1] = (uint32_t)(am >> 32);
         atomicAdd(&counts[1], __popcll(am));
@@ -593,21 +600,21 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
     }
     __syncthreads();
     // the active copies in order: those of 64 copies go behind those of the copies before
-    for (int c = wave; c < lay.mask_words / 2; c += kNW) {
+    for (int c = wave_; c < lay.mask_words / 2; c += kNW) {
       int before = 0;
-      for (int x = lane; x < c; x += kWave) before += __popc(L.amask[2 * x]) + __popc(L.amask[2 * x + 1]);
+      for (int x = lane_; x < c; x += kWave) before += __popc(L.amask[2 * x]) + __popc(L.amask[2 * x + 1]);
 #pragma unroll
       for (int off = kWave / 2; off > 0; off >>= 1) before += __shfl_xor(before, off);
       const uint64_t am = (uint64_t)L.amask[2 * c] | ((uint64_t)L.amask[2 * c + 1] << 32);
-      if ((am >> lane) & 1) L.list[before + __popcll(am & (((uint64_t)1 << lane) - 1))] = (uint16_t)(c * kWave + lane);
+      if ((am >> lane_) & 1) L.list[before + __popcll(am & (((uint64_t)1 << lane_) - 1))] = (uint16_t)(c * kWave + lane_);
     }
-    block_scan<AddOp, false>(L.profile, L.profile, T, L.scratch, tid);   // Eq. (4) per position
-    block_max_both_ways(L.profile, L.pmax, L.smax, T, L.scratch, tid);
+    block_scan<AddOp, false>(L.profile, L.profile, T, L.scratch, t_);   // Eq. (4) per position
+    block_max_both_ways(L.profile, L.pmax, L.smax, T, L.scratch, t_);
 
     // ---- pass 1: the violations of the base, each instance once: per active copy its form,
     // the order pair it opens and its inputs
     const int n_active = __builtin_amdgcn_readfirstlane(counts[1]);
-    for (int j = tid; j < n_active; j += kNT) {
+    for (int j = t_; j < n_active; j += kNT) {
       const int k = L.list[j];
       const uint32_t mine = L.packed[k];
       if (!live_of(mine)) {   // Eq. (2)/(8)
@@ -641,26 +648,26 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
       }
     }
     int distinct = 0;
-    for (int w = tid; w < lay.bit_words; w += kNT) distinct += __popc(L.occ1[w]);
+    for (int w = t_; w < lay.bit_words; w += kNT) distinct += __popc(L.occ1[w]);
     atomicAdd(&counts[0], viol + nlive - distinct);   // Eq. (6): live copies - distinct starts
     __syncthreads();
-    const int base_viol = __builtin_amdgcn_readfirstlane(counts[0]);   // the same in every lane: scalar registers
+    const int base_viol = __builtin_amdgcn_readfirstlane(counts[0]);   // the same in every lane_: scalar registers
     const int base_peak = __builtin_amdgcn_readfirstlane(L.pmax[T - 1]);
     // For the best move alone the list is built again, the copies that take part in a violation
     // first: their moves are the ones that can lower the count, and once one has, the others
-    // are left out wave by wave (see below).
+    // are left out wave_ by wave_ (see below).
     int n_first = n_active;   // entries of the list's first part
     if constexpr (!TABLE) {
       auto chunk = [&](const uint32_t* bits, int c) { return (uint64_t)bits[2 * c] | ((uint64_t)bits[2 * c + 1] << 32); };
       const int chunks = lay.mask_words / 2;
       int all_first = 0;
-      for (int x = lane; x < chunks; x += kWave) all_first += __popcll(chunk(L.amask, x) & chunk(L.involved, x));
+      for (int x = lane_; x < chunks; x += kWave) all_first += __popcll(chunk(L.amask, x) & chunk(L.involved, x));
 #pragma unroll
       for (int off = kWave / 2; off > 0; off >>= 1) all_first += __shfl_xor(all_first, off);
       n_first = __builtin_amdgcn_readfirstlane(all_first);
-      for (int c = wave; c < chunks; c += kNW) {
+      for (int c = wave_; c < chunks; c += kNW) {
         int before_first = 0, before_rest = 0;
-        for (int x = lane; x < c; x += kWave) {
+        for (int x = lane_; x < c; x += kWave) {
           const uint64_t am = chunk(L.amask, x), inv = chunk(L.involved, x);
           before_first += __popcll(am & inv);
           before_rest += __popcll(am & ~inv);
@@ -670,9 +677,9 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
           before_first += __shfl_xor(before_first, off);
           before_rest += __shfl_xor(before_rest, off);
         }
-        const uint64_t am = chunk(L.amask, c), inv = chunk(L.involved, c), lower = ((uint64_t)1 << lane) - 1;
-        if ((am & inv) >> lane & 1) L.list[before_first + __popcll(am & inv & lower)] = (uint16_t)(c * kWave + lane);
-        if ((am & ~inv) >> lane & 1) L.list[n_first + before_rest + __popcll(am & ~inv & lower)] = (uint16_t)(c * kWave + lane);
+        const uint64_t am = chunk(L.amask, c), inv = chunk(L.involved, c), lower = ((uint64_t)1 << lane_) - 1;
+        if ((am & inv) >> lane_ & 1) L.list[before_first + __popcll(am & inv & lower)] = (uint16_t)(c * kWave + lane_);
+        if ((am & ~inv) >> lane_ & 1) L.list[n_first + before_rest + __popcll(am & ~inv & lower)] = (uint16_t)(c * kWave + lane_);
       }
       __syncthreads();
     }
@@ -773,12 +780,16 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
     }
     // ---- best move of the candidate
     if (out_best) {
+      int own = tid;   // the lane's index, formed here: nothing of it is kept in a register across the scoring
+      asm volatile("" : "+v"(own));
+      own = (own & (kWave - 1)) << 2;
 #pragma unroll
       for (int off = kWave / 2; off > 0; off >>= 1) {
-        Best o;
-        o.viol = __shfl_xor(best.viol, off);
-        o.peak = __shfl_xor(best.peak, off);
-        o.move = __shfl_xor(best.move, off);
+        Best o;   // of lane ^ off
+        const int from = own ^ (off << 2);
+        o.viol = __builtin_amdgcn_ds_bpermute(from, best.viol);
+        o.peak = __builtin_amdgcn_ds_bpermute(from, best.peak);
+        o.move = __builtin_amdgcn_ds_bpermute(from, best.move);
         if (better(o, best)) best = o;
       }
       if (lane == 0) {
