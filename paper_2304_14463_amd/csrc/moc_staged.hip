@@ -75,7 +75,9 @@ __device__ __forceinline__ int wave_sum_i(int v) {
 // the top of its turn and for the workgroup's next candidate as soon as they are used), else 0
 // (any C, read where needed); U = nodes per lane, ceil(n / kNT), when CT > 0.
 template <int CT, int U>
-__global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) void eval_staged_kernel(GraphView g, const int32_t* __restrict__ place, int64_t B,
+// 64 registers (four workgroups per CU) where the copies of a lane's nodes are few enough to fit
+// beside the rest; otherwise as many as they take.
+__global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu((CT == 0 ? 1 : CT) * U <= 4 && U <= 2 && CT <= 3 ? 8 : 4, 8))) void eval_staged_kernel(GraphView g, const int32_t* __restrict__ place, int64_t B,
                                                           const int32_t* __restrict__ starts,
                                                           const int32_t* __restrict__ ends,
                                                           const uint8_t* __restrict__ active,
@@ -323,7 +325,9 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
     // ---- Eq. (4): peak of the running sum over the renumbered positions
     int S = 0, P = 0;
     {
-      int32_t* d = delta + tid * lay.chunk;
+      int own = tid;   // formed here: kept from the top of the kernel it is spilled, and the reload would
+      asm volatile("" : "+v"(own));   // wait for the next candidate's loads, which are in flight by now
+      int32_t* d = delta + own * lay.chunk;
       for (int x = 0; x < lay.chunk; ++x) {
         const int y = d[x];
         d[x] = 0;
