@@ -683,6 +683,14 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
   // statically (a short one) does not wait for the workgroups that were dispatched last.
   [[maybe_unused]] int turn = (int)(blockIdx.x / 256u);
   while (b < B) {
+    // Large workgroups (C >= 3 graphs): lane predicates and addresses derived from the thread
+    // index are formed where they are used.  Kept across candidates they take scalar registers
+    // that the masks of phase 1 need, and are spilled to vector lanes (two instructions to fetch
+    // one back, against one to form it again): n = 5000 63.6 -> 64.3 % of HBM peak.  The small
+    // kernels lose by it (n = 442: 50 -> 42 %) and keep them.
+    int t_ = tid;
+    if constexpr (NT >= 1024) asm volatile("" : "+v"(t_));
+    const int lane_ = t_ & (kWave - 1);
     if constexpr (NT <= 256) {
       switch (turn++ & 3) {
         case 0: __builtin_amdgcn_s_setprio(0); break;
@@ -691,9 +699,9 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
         default: __builtin_amdgcn_s_setprio(3); break;
       }
     }
-    int viol = wave == 0 ? n : 0;   // per wave (the same in every lane, counted on lane masks); see phase 1
-    int dur = 0;               // per lane
-    if (tid == 0) drawn = groups ? atomicAdd(counter, 1u) : next + 1;
+    int viol = wave == 0 ? n : 0;   // per wave (the same in every lane_, counted on lane_ masks); see phase 1
+    int dur = 0;               // per lane_
+    if (t_ == 0) drawn = groups ? atomicAdd(counter, 1u) : next + 1;
     // The workgroup's next candidate; the last one re-reads itself so that the loads below
     // need no condition.  Slot `it` is requested as soon as phase 1 has consumed the
     // registers of slot `it` (the first kEarly slots) or between the steps of phase 2 (the
@@ -704,11 +712,11 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
     // ---------------- phase 1: per node, copies in registers
 #pragma unroll
     for (int it = 0; it < ITERS; ++it) {
-      int v = it * NT + tid;
+      int v = it * NT + t_;
       asm volatile("" : "+v"(v));               // as for the edges: keep derived addresses out of registers
       if (it * NT + wave * kWave < n) {   // else: whole wave past the last node
         const NodeIn<CT>& r = in[it];
-        // Eq. (2), (7), (8), (3) on lane masks; Eq. (1) per lane
+        // Eq. (2), (7), (8), (3) on lane_ masks; Eq. (1) per lane_
         const lanemask isn = u_lt_k((uint32_t)v, (uint32_t)n);
         lanemask act[CT], live[CT];
         Record<CT> rec;
@@ -753,7 +761,7 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
           }
         }
         if (lanes(live[0])) scatter(r.s[0], r.e[0], sd[it].x);
-        // The other copies are rarely live: in round k every lane brings the k-th of its
+        // The other copies are rarely live: in round k every lane_ brings the k-th of its
         // live ones, so that a wave runs as many rounds as its busiest node has such copies
         // rather than one per copy.
         lanemask left[CT];
@@ -764,7 +772,7 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
           if (others == 0) break;
           int sx = r.s[CT - 1], ex = r.e[CT - 1];
 #pragma unroll
-          for (int i = CT - 2; i >= round; --i) {   // the first of the lane's copies that are left
+          for (int i = CT - 2; i >= round; --i) {   // the first of the lane_'s copies that are left
             sx = (int)pick(left[i], (uint32_t)r.s[i], (uint32_t)sx);
             ex = (int)pick(left[i], (uint32_t)r.e[i], (uint32_t)ex);
           }
@@ -790,8 +798,8 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
     // (a) one chunk of CH delta positions per thread
     int S = 0, P = 0;
     if (wave * kWave < lay.n_chunks) {
-      if (tid < lay.n_chunks) {
-        int4* d = reinterpret_cast<int4*>(L.delta + tid * (CH + 4));
+      if (t_ < lay.n_chunks) {
+        int4* d = reinterpret_cast<int4*>(L.delta + t_ * (CH + 4));
 #pragma unroll
         for (int h = 0; h < CH / 8; ++h) {   // 8 positions at a time keeps the register count down
           const int4 x0 = d[2 * h], x1 = d[2 * h + 1];
@@ -808,10 +816,10 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
           __builtin_amdgcn_sched_barrier(0);
         }
       }
-      wave_combine_ordered<(NT < 1024)>(lane, S, P);
+      wave_combine_ordered<(NT < 1024)>(lane_, S, P);
     }
-    const int distinct = count_distinct_starts<NT>(L, lay, tid);
-    // (c) edges, three per slice of the prefetch; their violations are counted per lane
+    const int distinct = count_distinct_starts<NT>(L, lay, t_);
+    // (c) edges, three per slice of the prefetch; their violations are counted per lane_
     int queued = 0, eviol = 0;
 #pragma unroll
     for (int it = 0; it < ITERS; ++it) {
@@ -834,15 +842,15 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
             for (int i = 0; i < CT; ++i) count_live_uncovered<CT>(eviol, pu[j], pv[j].w[i]);
           }
         };
-        // The lane's last slice may hold edges in its first one or two entries only (padding in
-        // every lane beyond): blocks of their own, each one straight run of reads, then tests.
+        // The lane_'s last slice may hold edges in its first one or two entries only (padding in
+        // every lane_ beyond): blocks of their own, each one straight run of reads, then tests.
         const int here = lay.edge_slots - it * kEdgesPerNode;   // > 0
         if (it == ITERS - 1 && here == 1) edges_of_slice(std::integral_constant<int, 1>{});
         else if (it == ITERS - 1 && here == 2) edges_of_slice(std::integral_constant<int, 2>{});
         else edges_of_slice(std::integral_constant<int, kEdgesPerNode>{});
       } else {
         if (queued > lay.qcap - kEdgesPerNode * kWave) {   // the slice might not fit: work the queue off first
-          drain_queue<CT>(eviol, L, queue, queued, lane, dummy_pair, cons_base);
+          drain_queue<CT>(eviol, L, queue, queued, lane_, dummy_pair, cons_base);
           queued = 0;
         }
         uint32_t pv[kEdgesPerNode], pu[kEdgesPerNode];
@@ -854,15 +862,15 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
 #pragma unroll
         for (int j = 0; j < kEdgesPerNode; ++j) {
           const lanemask more = check_first_copies(eviol, pu[j], pv[j]);
-          const uint32_t tail = queue_addr + 4u * (uint32_t)queued;   // the same in every lane: scalar arithmetic
+          const uint32_t tail = queue_addr + 4u * (uint32_t)queued;   // the same in every lane_: scalar arithmetic
           lds_write_lanes(more, tail + 4u * rank_in(more, 0u), edge[it * kEdgesPerNode + j]);
           queued += count(more);
         }
       }
     }
-    if constexpr (kSplit) drain_queue<CT>(eviol, L, queue, queued, lane, dummy_pair, cons_base);
+    if constexpr (kSplit) drain_queue<CT>(eviol, L, queue, queued, lane_, dummy_pair, cons_base);
     uint32_t after_next;
-    finish<NT, true>(L, g, tid, lane, wave, S, P, viol, 0, distinct - eviol, dur, out, b, drawn, &after_next);
+    finish<NT, true>(L, g, t_, lane_, wave, S, P, viol, 0, distinct - eviol, dur, out, b, drawn, &after_next);
     b = b_next;
     next = (uint32_t)__builtin_amdgcn_readfirstlane(after_next);
   }
