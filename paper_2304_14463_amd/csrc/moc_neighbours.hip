@@ -901,6 +901,24 @@ __device__ __forceinline__ int interval_max(const int32_t* profile, const BlockM
   return top;
 }
 
+// Number of x in [s, e] with profile[x] >= bound.  Whole blocks whose maximum stays below the
+// bound are passed over: few blocks come near the peak, and the ranges are long.
+__device__ __forceinline__ int count_reaching(const int32_t* profile, const BlockMax& bm, int s, int e, int bound) {
+  int cnt = 0;
+  const int first_block = (s + 31) >> 5, last_block = (e + 1) >> 5;   // whole blocks [first, last)
+  if (first_block >= last_block) {
+    for (int x = s; x <= e; ++x) cnt += profile[x] >= bound ? 1 : 0;
+    return cnt;
+  }
+  for (int x = s; x < 32 * first_block; ++x) cnt += profile[x] >= bound ? 1 : 0;
+  for (int blk = first_block; blk < last_block; ++blk) {
+    if (bm.level0[blk] < bound) continue;
+    for (int x = 32 * blk; x < 32 * blk + 32; ++x) cnt += profile[x] >= bound ? 1 : 0;
+  }
+  for (int x = 32 * last_block; x <= e; ++x) cnt += profile[x] >= bound ? 1 : 0;
+  return cnt;
+}
+
 // Positions at which the base's profile reaches its peak, countable over any range.
 struct PeakCount {
   const uint32_t* bits;
@@ -1075,10 +1093,21 @@ __device__ __forceinline__ bool score_cut(const Adj& g, int C, int T, const NbLd
   // Eq. (5): the inputs of the new computation are held at p by the choice of p
   if (j == 0) --vv;   // Eq. (7)
   int pk = base_peak, at = at_peak.total;
-  // mode 1: the inputs that are kept until p.  lo = the lowest position whose memory changes
+  // mode 1: the inputs that are kept until p.  lo = the lowest position whose memory changes.
+  // The first kKept of them are noted (end, size) for the walk below, which looks at each of them
+  // once per step: finding them again every time costs a pass over the in-edges of u with
+  // several reads per edge.
+  constexpr int kKept = 8;
+  int kept_end[kKept], kept_size[kKept];
+#pragma unroll
+  for (int s = 0; s < kKept; ++s) { kept_end[s] = 0; kept_size[s] = 0; }
   int n_kept = 0, lo = last_use + 1;
   if (mode == 1)
     for_each_kept_input(g, C, L.packed, u, p, [&](int w, int q, int end) {
+      const int m_w = g.size_of(w);
+#pragma unroll
+      for (int s = 0; s < kKept; ++s)
+        if (s == n_kept) { kept_end[s] = end; kept_size[s] = m_w; }
       ++n_kept;
       lo = min(lo, end + 1);
       // Eq. (3): the kept copy against the next live copy of its node
@@ -1090,13 +1119,14 @@ __device__ __forceinline__ bool score_cut(const Adj& g, int C, int T, const NbLd
           break;
         }
       }
-      // Eq. (5): consumers of w that start in (end, p] and were not covered are covered now
+      // Eq. (5): consumers of w that start in (end, p] are covered now.  None of them was: a copy
+      // of w that covered a position in (end, p] would end at or after p and cover p as well
+      // (w would be held there), or end in (end, p), and `end` is the largest end below p.
       for (int y = g.out_ptr[w]; y < g.out_ptr[w + 1]; ++y) {
         const int x = g.out_idx[y];
         for (int c = 0; c < C; ++c) {
-          const uint32_t px = L.packed[x * C + c];
-          const int sx = (int)(px & 0xFFFFu);   // 0xFFFF if not live: above every p
-          if (sx > end && sx <= p && !held_at(C, L.packed, w, sx)) --vv;
+          const int sx = (int)(L.packed[x * C + c] & 0xFFFFu);   // 0xFFFF if not live: above every p
+          if (sx > end && sx <= p) --vv;
         }
       }
     });
@@ -1120,10 +1150,20 @@ __device__ __forceinline__ bool score_cut(const Adj& g, int C, int T, const NbLd
       int next = p + 1, add = 0;   // the step after `from`, and the change on [from, next)
       if (from < last_use + 1) next = min(next, last_use + 1);
       if (from < p) next = min(next, p);
-      for_each_kept_input(g, C, L.packed, u, p, [&](int w, int, int end) {
-        if (end + 1 > from) next = min(next, end + 1);
-        else add += g.size_of(w);
-      });
+      if (n_kept <= kKept) {
+#pragma unroll
+        for (int s = 0; s < kKept; ++s) {
+          if (s < n_kept) {
+            if (kept_end[s] + 1 > from) next = min(next, kept_end[s] + 1);
+            else add += kept_size[s];
+          }
+        }
+      } else {
+        for_each_kept_input(g, C, L.packed, u, p, [&](int w, int, int end) {
+          if (end + 1 > from) next = min(next, end + 1);
+          else add += g.size_of(w);
+        });
+      }
       if (from >= last_use + 1 && from < p) add -= sz;
       const int here = interval_max(L.profile, block_max, from, next - 1);
       top = max(top, here + add);
@@ -1131,7 +1171,7 @@ __device__ __forceinline__ bool score_cut(const Adj& g, int C, int T, const NbLd
       if (add == 0) {
         still += at_peak.within(max(from, 1), next - 1) + (from == 0 && bit_at(at_peak.bits, 0) ? 1 : 0);
       } else if (add > 0 && here + add >= base_peak) {
-        for (int x = from; x < next; ++x) still += L.profile[x] + add >= base_peak ? 1 : 0;
+        still += count_reaching(L.profile, block_max, from, next - 1, base_peak - add);
       }
       from = next;
     }
