@@ -232,6 +232,18 @@ def measure_neighbours(moc, steps, warmup, with_cpu_baseline=True):
     out["cuts"] = {"ms_per_step": ms, "moves_per_s": w.B * w.m * w.C / (ms * 1e-3),
                    "bytes_written": w.B * w.m * w.C * 16, "frac_applicable": applicable,
                    "best_only_ms_per_step": ms_cuts["best_only"]}
+    # the cuts of the two-phase search's first phase: the producer's missing inputs are kept until the recomputation
+    keep_steps = max(1, steps // 2)
+    moc.moc_eval_cuts(gh, ds, de, da, want_moves=True, want_best=True, out_moves=oc, out_best=ob, keep_inputs=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(keep_steps):
+        moc.moc_eval_cuts(gh, ds, de, da, want_moves=True, want_best=True, out_moves=oc, out_best=ob, keep_inputs=True)
+    torch.cuda.synchronize()
+    ms_keep = (time.perf_counter() - t0) * 1e3 / keep_steps
+    out["cuts"]["keep_inputs"] = {
+        "ms_per_step": ms_keep, "moves_per_s": w.B * w.m * w.C / (ms_keep * 1e-3),
+        "frac_applicable": float((moc.results_to_numpy(oc[:64], moc.TOGGLE_SCORE_DTYPE)["violations"] >= 0).mean())}
     del oc, ob
     # greedy descent by cuts from the violation-free bases: 16 steps of score, choose, apply
     ev0 = moc.results_to_numpy(moc.moc_eval_batch(gh, ds, de, da))
