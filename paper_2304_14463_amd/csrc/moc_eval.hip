@@ -586,7 +586,7 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
   constexpr int CH = chunk_positions(NT);   // delta positions per chunk
   extern __shared__ uint32_t lds_raw[];
   const Lds L = carve(lds_raw, lay);
-  const int tid = threadIdx.x, lane = tid & (kWave - 1);
+  const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);   // the same in every lane: say so
   const int T = g.T, n = g.n;
   const uint32_t group = groups ? blockIdx.x % (uint32_t)groups : 0u;

@@ -1385,11 +1385,15 @@ __global__ __launch_bounds__(kNT) void toggles_kernel(GraphView g, int64_t B, co
         if (out) out[out_row + q] = sc;
       };
       const int n_moves = g.m * C;
-      if (improving && !out && base_viol == 0) {
-        // A descent step from a candidate without violations can only take a move that lowers
-        // the peak or the number of positions reaching it: one with such a position inside
-        // (s_k, t), which contains the range the move frees.  Each wave sifts its moves by that
-        // test, keeps the survivors in a queue of its own and scores them 64 at a time.
+      {
+        // Most moves are not applicable (the consumer's copy is not live, or no copy of the
+        // producer covers it), and scoring is long: each wave sifts its moves by that test, keeps
+        // the survivors in a queue of its own and scores them 64 at a time; the others get their
+        // "not applicable" score at once.  A descent step from a candidate without violations
+        // can, beyond that, only take a move that lowers the peak or the number of positions
+        // reaching it: one with such a position inside (s_k, t), which contains the range the
+        // move frees; the sieve then lets only those through.
+        const bool sift_peak = improving && !out && base_viol == 0;
         const int lane = tid & (kWave - 1), wave = tid / kWave;
         int32_t* const mine_q = queue + wave * (2 * kWave);
         int queued = 0;
@@ -1407,8 +1411,9 @@ __global__ __launch_bounds__(kNT) void toggles_kernel(GraphView g, int64_t B, co
                 const uint32_t pu = L.packed[u * C + c];
                 if (covers1(pu, t)) sk = max(sk, (int)(pu & 0xFFFFu));
               }
-              keep = sk >= 0 && sk + 1 <= (int)t - 1 && at_peak.within(sk + 1, (int)t - 1) > 0;
+              keep = sk >= 0 && (!sift_peak || (sk + 1 <= (int)t - 1 && at_peak.within(sk + 1, (int)t - 1) > 0));
             }
+            if (!keep && out) out[out_row + q] = moc_toggle_score{-1, -1, 0};
           }
           const uint64_t kept = __ballot(keep);
           if (keep) mine_q[queued + __popcll(kept & ((1ull << lane) - 1))] = q;
@@ -1421,8 +1426,6 @@ __global__ __launch_bounds__(kNT) void toggles_kernel(GraphView g, int64_t B, co
           }
         }
         if (lane < queued) score(mine_q[lane]);
-      } else {
-        for (int q = tid; q < n_moves; q += kNT) score(q);
       }
       if (out_best) {
 #pragma unroll
