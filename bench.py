@@ -27,8 +27,8 @@ HBM_PEAK_GBS = 8000.0
 # HBM traffic of the evaluation kernel on the default workload, from rocprofv3 counter runs
 # (profiles/eval_batch_kernel_n5000_C3_B262144.md): KiB per dispatch and the factors that the same
 # counters need to reproduce a 1 GiB device copy.  Valid for the kernel sources they were taken with.
-TRAFFIC = {"workload": 4, "B": 262144, "fetch_kib": 17326692.0, "fetch_scale": 2.0, "write_kib": 20496.5,
-           "write_scale": 1.0, "sources_sha256": "0722095a938661414eb4265c4b3c1e3be83695fb242bbedf489de8983c369f9b"}
+TRAFFIC = {"workload": 4, "B": 262144, "fetch_kib": 17326543.3, "fetch_scale": 2.0, "write_kib": 20496.5,
+           "write_scale": 1.0, "sources_sha256": "cca58c3149b95f57c59b2745060011810940a5b708be189374540c9e761c511a"}
 KERNEL_SOURCES = ("moc_eval.hip", "moc_internal.h")
 
 

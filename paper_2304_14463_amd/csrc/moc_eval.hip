@@ -621,8 +621,7 @@ __global__ __launch_bounds__(NT) void eval_batch_kernel(GraphView g, int64_t B, 
     edge[j] = g.edge_pair[e] + (cons_base << 16);   // the list is padded with dummy edges to EPT * NT entries
   }
   NodeIn<CT> in[ITERS];
-  // m_v, w_v of the lane's nodes: re-read (from L2) at the start of each phase 1, behind the
-  // candidate's own loads, rather than held in registers through phase 2 where registers are scarce
+  // m_v, w_v of the lane's nodes: the same for every candidate, read once
   int2 sd[ITERS];
   auto request_size_dur = [&]() {
 #pragma unroll
