@@ -163,7 +163,7 @@ void decode_kernel(GraphView G, int64_t B, const int32_t* __restrict__ starts, c
     // scatter by start: a[x] = 1 where a computation happens
     for (int round = 0; round < T; round += kUnroll * kNT) {
       const int base = round + tid;
-      uint8_t on[kUnroll];
+      uint32_t on[kUnroll];   // a register each: bytes packed into one register would be loaded one behind the other
       int32_t s[kUnroll];
 #pragma unroll
       for (int u = 0; u < kUnroll; ++u) {
@@ -285,6 +285,17 @@ void decode_kernel(GraphView G, int64_t B, const int32_t* __restrict__ starts, c
 // array holds the node computed at each position (v + 1) instead of a flag, so that the pass
 // that ranks the occupied positions can write the sequence out itself, in order, and clear the
 // array on its way; the running-sum scan at the end clears the difference array as it reads it.
+// The copies of a node as they lie in a candidate's row: aligned as their elements are, no more
+// (the global loads of this chip take several words at any word boundary).
+template <int CT>
+struct alignas(4) CopyStarts {
+  int32_t s[CT];
+};
+template <int CT>
+struct CopyFlags {
+  uint8_t a[CT];
+};
+
 template <int CT>
 struct NodeStarts {
   uint32_t s[CT];   // kNoStart if the copy is not computed
@@ -347,7 +358,12 @@ __device__ int block_peak_and_clear(int32_t* a, int words, int32_t* scratch, int
   return best;
 }
 
-template <int CT>
+// SMALL: the graph has at most kUnroll * kNT nodes, a lane's nodes are the same for every
+// candidate: their sizes and durations stay in registers, and the starts and flags of the
+// workgroup's next candidate are asked for while this one is still being worked on (after the
+// edge pass, whose own loads would otherwise queue behind them), so that its first phase does
+// not begin with a wait for HBM.
+template <int CT, bool SMALL>
 __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8)))
 void decode_fixed_kernel(GraphView G, int64_t B, const int32_t* __restrict__ starts, const uint8_t* __restrict__ active,
                          moc_decode_result* __restrict__ out, int32_t* __restrict__ out_seq, DcLayout lay) {
@@ -363,40 +379,66 @@ void decode_fixed_kernel(GraphView G, int64_t B, const int32_t* __restrict__ sta
 
   for (int x = tid; x < lay.T_pad; x += kNT) a[x] = 0;
   if (tid < 8) flag_words[tid] = 0;
+  if (tid < SS) st[n * SS + tid] = (uint16_t)kNoStart;   // node n: behind the last node, never computed; padding edges lead there
+  // The loads of a round of nodes are issued without conditions (lanes past the last node read
+  // it again and drop what they get) and all of them before the first is looked at; the flags
+  // take a register each.  Loads under a condition, or flags packed into the bytes of one
+  // register, end up one behind the other, each waiting for the one before.
+  struct Round {
+    int32_t s[kUnroll][CT];
+    uint32_t on[kUnroll][CT];
+  };
+  // (the candidate's rows are scalar base addresses, a lane adds a 32-bit offset)
+  auto request = [&](int64_t c, int round, int t, Round& r) {
+    const char* const s_row = reinterpret_cast<const char*>(starts + c * T);
+    const char* const a_row = reinterpret_cast<const char*>(active + c * T);
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const uint32_t off = (uint32_t)min(round + u * kNT + t, n - 1) * CT;
+      const CopyStarts<CT> sv = *reinterpret_cast<const CopyStarts<CT>*>(s_row + off * 4u);
+      const CopyFlags<CT> av = *reinterpret_cast<const CopyFlags<CT>*>(a_row + off);
+#pragma unroll
+      for (int i = 0; i < CT; ++i) {
+        r.s[u][i] = sv.s[i];
+        r.on[u][i] = av.a[i];
+      }
+    }
+  };
+  [[maybe_unused]] Round ahead;            // SMALL: the workgroup's next candidate
+  [[maybe_unused]] int2 my_sd[kUnroll];    // SMALL: m_v, w_v of the lane's nodes
+  if constexpr (SMALL) {
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) my_sd[u] = G.size_dur[min(u * kNT + tid, n - 1)];
+    request(blockIdx.x, 0, tid, ahead);   // the grid is not larger than the batch
+  }
   __syncthreads();
 
   int turn = 0;
   for (int64_t cand = blockIdx.x; cand < B; cand += gridDim.x, turn ^= 1) {
-    const int32_t* s_row = starts + cand * T;
-    const uint8_t* a_row = active + cand * T;
+    // What derives from the thread index (row bounds, LDS addresses) is formed again for every
+    // candidate: kept across candidates it takes registers that the lane's edges need.
+    int t_ = tid;
+    asm volatile("" : "+v"(t_));
+    const int lane_ = t_ & (kWave - 1);
+    const int wave_ = __builtin_amdgcn_readfirstlane(t_ / kWave);
     int32_t* seq_row = out_seq ? out_seq + cand * T : nullptr;
     int32_t* flags = flag_words + 4 * turn;
+    const int64_t after = cand + gridDim.x < B ? cand + gridDim.x : cand;   // SMALL: whose loads go out next (the last candidate asks for itself again)
 
     // ---- who is computed where; every computation serves at least its own step
-    for (int round = 0; round < n; round += kUnroll * kNT) {
-      int32_t s[kUnroll][CT];
-      uint8_t on[kUnroll][CT];
+    auto place = [&](int round, const Round& r) {
 #pragma unroll
       for (int u = 0; u < kUnroll; ++u) {
-        const int v = round + u * kNT + tid;
-#pragma unroll
-        for (int i = 0; i < CT; ++i) {
-          on[u][i] = v < n ? a_row[v * CT + i] : (uint8_t)0;
-          s[u][i] = v < n ? s_row[v * CT + i] : 0;
-        }
-      }
-#pragma unroll
-      for (int u = 0; u < kUnroll; ++u) {
-        const int v = round + u * kNT + tid;
+        const int v = round + u * kNT + t_;
         if (v >= n) continue;
 #pragma unroll
         for (int i = 0; i < CT; ++i) {
           uint32_t sk = kNoStart;
-          if (on[u][i]) {
-            if (s[u][i] < 0 || s[u][i] >= T) {
+          if (r.on[u][i]) {
+            if (r.s[u][i] < 0 || r.s[u][i] >= T) {
               flags[0] = 1;                                        // Eq. (8)
             } else {
-              sk = (uint32_t)s[u][i];
+              sk = (uint32_t)r.s[u][i];
               if (atomicCAS(&a[sk], 0, v + 1) != 0) flags[0] = 1;  // Eq. (6)
               b[sk] = (int)sk;
             }
@@ -404,14 +446,25 @@ void decode_fixed_kernel(GraphView G, int64_t B, const int32_t* __restrict__ sta
           st[v * SS + i] = (uint16_t)sk;
         }
       }
+    };
+    if constexpr (SMALL) {
+      place(0, ahead);
+    } else {
+      for (int round = 0; round < n; round += kUnroll * kNT) {
+        Round now;
+        request(cand, round, t_, now);
+        __builtin_amdgcn_sched_barrier(0);
+        place(round, now);
+      }
     }
     __syncthreads();
     if (flags[0]) {
+      if constexpr (SMALL) request(after, 0, t_, ahead);
       if (seq_row)
-        for (int x = tid; x < T; x += kNT) seq_row[x] = -1;
-      for (int x = tid; x <= T; x += kNT) a[x] = 0;
+        for (int x = t_; x < T; x += kNT) seq_row[x] = -1;
+      for (int x = t_; x <= T; x += kNT) a[x] = 0;
       __syncthreads();
-      if (tid == 0) {
+      if (t_ == 0) {
         out[cand] = moc_decode_result{-1, 0, 0, 0};
         flags[0] = 0;
       }
@@ -419,37 +472,37 @@ void decode_fixed_kernel(GraphView G, int64_t B, const int32_t* __restrict__ sta
       turn ^= 1;   // the same set of flags serves the next candidate (it is clear again)
       continue;
     }
-    if (tid == 0) {   // the other set, for the workgroup's next candidate
+    if (t_ == 0) {   // the other set, for the workgroup's next candidate
       int32_t* other = flag_words + 4 * (turn ^ 1);
       other[0] = 0; other[1] = 0; other[2] = 0;
     }
 
-    // ---- the sequence: occupied positions in order.  A wave owns rows of 256 positions, four per lane.
+    // ---- the sequence: occupied positions in order.  A wave_ owns rows of 256 positions, four per lane_.
     const int rows = (lay.T_pad + 4 * kWave - 1) / (4 * kWave), rows_per_wave = (rows + kNW - 1) / kNW;
-    const int r0 = min(wave * rows_per_wave, rows), r1 = min(r0 + rows_per_wave, rows);
+    const int r0 = min(wave_ * rows_per_wave, rows), r1 = min(r0 + rows_per_wave, rows);
     int mine = 0;
     for (int r = r0; r < r1; ++r) {
-      const int x = (r * kWave + lane) * 4;
+      const int x = (r * kWave + lane_) * 4;
       if (x < lay.T_pad) {
         const int4 who = *reinterpret_cast<const int4*>(a + x);
         mine += (who.x != 0) + (who.y != 0) + (who.z != 0) + (who.w != 0);
       }
     }
-    mine = __builtin_amdgcn_readlane(wave_scan_add(mine, lane), kWave - 1);
-    if (lane == 0) scratch[wave] = mine;
+    mine = __builtin_amdgcn_readlane(wave_scan_add(mine, lane_), kWave - 1);
+    if (lane_ == 0) scratch[wave_] = mine;
     __syncthreads();
     int before = 0, length = 0;
     for (int w = 0; w < kNW; ++w) {
       const int t = scratch[w];
-      if (w < wave) before += t;
+      if (w < wave_) before += t;
       length += t;
     }
     for (int r = r0; r < r1; ++r) {
-      const int x = (r * kWave + lane) * 4;
+      const int x = (r * kWave + lane_) * 4;
       int4 who = make_int4(0, 0, 0, 0);
       if (x < lay.T_pad) who = *reinterpret_cast<const int4*>(a + x);
       const int cnt = (who.x != 0) + (who.y != 0) + (who.z != 0) + (who.w != 0);
-      const int incl = wave_scan_add(cnt, lane);
+      const int incl = wave_scan_add(cnt, lane_);
       if (cnt) {
         int at = before + incl - cnt;
         if (seq_row) {
@@ -463,41 +516,49 @@ void decode_fixed_kernel(GraphView G, int64_t B, const int32_t* __restrict__ sta
       before += __builtin_amdgcn_readlane(incl, kWave - 1);
     }
     if (seq_row)
-      for (int x = length + tid; x < T; x += kNT) seq_row[x] = -1;
+      for (int x = length + t_; x < T; x += kNT) seq_row[x] = -1;
 
-    // ---- one lane per edge (u, v): each computation of v is served by the latest computation of u before it
+    // ---- one lane_ per edge (u, v): each computation of v is served by the latest computation of u before it
+    bool unserved = false;
+    auto serve = [&](const NodeStarts<CT>& su, const NodeStarts<CT>& sv) {
+#pragma unroll
+      for (int i = 0; i < CT; ++i) {
+        const uint32_t p = sv.s[i];
+        int q = -1;
+#pragma unroll
+        for (int j = 0; j < CT; ++j)
+          if (su.s[j] < p) q = max(q, (int)su.s[j]);    // kNoStart is above every position
+        const bool computed = p != kNoStart;
+        if (computed && q >= 0) atomicMax(&b[q], (int)p);
+        unserved = unserved || (computed && q < 0);
+      }
+    };
     for (int round = 0; round < m; round += kUnroll * kNT) {
-      const int base = round + tid;
+      const int base = round + t_;
       uint32_t pair[kUnroll];
 #pragma unroll
-      for (int u = 0; u < kUnroll; ++u) pair[u] = base + u * kNT < m ? G.edge_pair_c[base + u * kNT] : 0u;
-#pragma unroll
       for (int u = 0; u < kUnroll; ++u) {
-        if (base + u * kNT >= m) continue;
-        const NodeStarts<CT> su = read_starts<CT>(st, (int)(pair[u] & 0xFFFFu) / CT);
-        const NodeStarts<CT> sv = read_starts<CT>(st, (int)(pair[u] >> 16) / CT);
-#pragma unroll
-        for (int i = 0; i < CT; ++i) {
-          const uint32_t p = sv.s[i];
-          if (p == kNoStart) continue;
-          int q = -1;
-#pragma unroll
-          for (int j = 0; j < CT; ++j)
-            if (su.s[j] < p) q = max(q, (int)su.s[j]);    // kNoStart is above every position
-          if (q < 0) flags[1] = 1;
-          else atomicMax(&b[q], (int)p);
-        }
+        const uint32_t got = G.edge_pair_c[min(base + u * kNT, m - 1)];
+        pair[u] = base + u * kNT < m ? got : (uint32_t)T << 16;   // beyond the list: an edge into node n
       }
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u)
+        serve(read_starts<CT>(st, (int)(pair[u] & 0xFFFFu) / CT), read_starts<CT>(st, (int)(pair[u] >> 16) / CT));
     }
+    if (unserved) flags[1] = 1;
+    if constexpr (SMALL) request(after, 0, t_, ahead);
     __syncthreads();
 
     // ---- per node: does it occur, what does it add to the duration; its outputs are held from p through b[p]
     int my_dur = 0;
     for (int round = 0; round < n; round += kUnroll * kNT) {
-      const int base = round + tid;
+      const int base = round + t_;
       int2 sd[kUnroll];
 #pragma unroll
-      for (int u = 0; u < kUnroll; ++u) sd[u] = base + u * kNT < n ? G.size_dur[base + u * kNT] : make_int2(0, 0);
+      for (int u = 0; u < kUnroll; ++u) {
+        if constexpr (SMALL) sd[u] = my_sd[u];
+        else sd[u] = G.size_dur[min(base + u * kNT, n - 1)];
+      }
 #pragma unroll
       for (int u = 0; u < kUnroll; ++u) {
         const int v = base + u * kNT;
@@ -518,13 +579,18 @@ void decode_fixed_kernel(GraphView G, int64_t B, const int32_t* __restrict__ sta
     }
     if (my_dur) atomicAdd(&flags[2], my_dur);
     __syncthreads();
-    const int peak = block_peak_and_clear(a, lay.T_pad, scratch, tid);
+    const int peak = block_peak_and_clear(a, lay.T_pad, scratch, t_);
 
-    if (tid == 0) {
+    if (t_ == 0) {
       const bool valid = flags[1] == 0;
       out[cand] = moc_decode_result{valid ? 1 : 0, length, valid ? (int64_t)peak : 0, valid ? (int64_t)flags[2] : 0};
     }
   }
+}
+
+template <int CT>
+auto fixed_kernel_for(int n) {
+  return n <= kUnroll * kNT ? decode_fixed_kernel<CT, true> : decode_fixed_kernel<CT, false>;
 }
 
 }  // namespace
@@ -542,10 +608,10 @@ extern "C" int moc_decode_batch(const moc_graph* g, int64_t B, const int32_t* st
   if (lay.bytes > g->max_lds) return MOC_EOVERFLOW;
   auto kern = decode_kernel;
   switch (g->view.C) {
-    case 1: kern = decode_fixed_kernel<1>; break;
-    case 2: kern = decode_fixed_kernel<2>; break;
-    case 3: kern = decode_fixed_kernel<3>; break;
-    case 4: kern = decode_fixed_kernel<4>; break;
+    case 1: kern = fixed_kernel_for<1>(g->view.n); break;
+    case 2: kern = fixed_kernel_for<2>(g->view.n); break;
+    case 3: kern = fixed_kernel_for<3>(g->view.n); break;
+    case 4: kern = fixed_kernel_for<4>(g->view.n); break;
     default: break;
   }
   int per_cu = 0;

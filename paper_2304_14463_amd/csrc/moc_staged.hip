@@ -98,18 +98,37 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu((CT == 0 ? 
   // registers for the copies of the lane's nodes (CT > 0)
   constexpr int RU = CT > 0 ? U : 1, RC = CT > 0 ? CT : 1;
   [[maybe_unused]] int rs[RU][RC], re[RU][RC];
-  [[maybe_unused]] uint8_t ra[RU][RC];
+  // a node's flags as they lie in memory, in one register, taken apart where they are used:
+  // bytes put together in a register as they arrive make each load wait where it is issued
+  struct Flags { uint8_t a[RC]; };
+  static_assert(sizeof(Flags) <= 4, "the flags of a node fit a register");
+  [[maybe_unused]] uint32_t ra[RU];
+  // The candidate's rows are the same for all lanes (scalar registers); a lane adds a 32-bit
+  // offset that is formed here from the thread index each time.  Whole addresses per lane, kept
+  // across the loop over the candidates, would be spilled, and fetching them back here makes
+  // every load of the request wait for the one before.
+  struct alignas(4) Ints { int32_t x[RC]; };
   [[maybe_unused]] auto request = [&](int64_t cand) {
     if constexpr (CT > 0) {
+      const char* const s_row = reinterpret_cast<const char*>(starts + cand * T);
+      const char* const e_row = reinterpret_cast<const char*>(ends + cand * T);
+      const char* const a_row = reinterpret_cast<const char*>(active + cand * T);
+      int t = tid;
+      asm volatile("" : "+v"(t));
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        const int v = min(u * kNT + tid, n - 1);   // lanes past the last node re-read it
+        const uint32_t off = (uint32_t)min(u * kNT + t, n - 1) * CT;   // lanes past the last node re-read it
+        const Ints sv = *reinterpret_cast<const Ints*>(s_row + off * 4u);
+        const Ints ev = *reinterpret_cast<const Ints*>(e_row + off * 4u);
+        const Flags f = *reinterpret_cast<const Flags*>(a_row + off);
 #pragma unroll
         for (int i = 0; i < CT; ++i) {
-          rs[u][i] = starts[cand * T + v * CT + i];
-          re[u][i] = ends[cand * T + v * CT + i];
-          ra[u][i] = active[cand * T + v * CT + i];
+          rs[u][i] = sv.x[i];
+          re[u][i] = ev.x[i];
         }
+        uint32_t w = 0;
+        __builtin_memcpy(&w, &f, sizeof(Flags));
+        ra[u] = w;
       }
     }
   };
@@ -173,7 +192,7 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu((CT == 0 ? 
 #pragma unroll
           for (int i = 0; i < CT; ++i) {
             const int s = rs[u][i], e = re[u][i];
-            const bool act = ra[u][i] != 0;
+            const bool act = ((ra[u] >> (8 * i)) & 0xFFu) != 0;
             bool live = act && (uint32_t)s <= (uint32_t)e && (uint32_t)e < D;
             int j = -1;
             if (live) {
