@@ -564,6 +564,26 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
     const int64_t row = b * T;
     moc_move_score* const row0 = TABLE && out_moves ? out_moves + b * (int64_t)moves_per_cand : nullptr;   // this candidate's table
     // ---- base candidate: stage copies, scatter deltas, mark starts
+    // The candidate's first kAhead * kNT copies are asked for before the arrays are cleared, all
+    // at once and without conditions (lanes past the last copy read it again): they arrive
+    // while the workgroup clears and meets at the barrier, instead of one round of loads
+    // after the other, each waited for where it is issued.
+    constexpr int kAhead = 4;
+    int ahead_s[kAhead], ahead_e[kAhead], ahead_sz[kAhead];
+    uint32_t ahead_a[kAhead];
+    {
+      const char* const s_row = reinterpret_cast<const char*>(starts + row);
+      const char* const e_row = reinterpret_cast<const char*>(ends + row);
+      const char* const a_row = reinterpret_cast<const char*>(active + row);
+#pragma unroll
+      for (int j = 0; j < kAhead; ++j) {
+        const uint32_t k = (uint32_t)min(wave_ * kWave + j * kNT + lane_, T - 1);
+        ahead_s[j] = *reinterpret_cast<const int32_t*>(s_row + 4u * k);
+        ahead_e[j] = *reinterpret_cast<const int32_t*>(e_row + 4u * k);
+        ahead_a[j] = *reinterpret_cast<const uint8_t*>(a_row + k);
+        ahead_sz[j] = A.size_of(C == 1 ? (int)k : (int)__umulhi(k, c_magic));
+      }
+    }
     for (int t = t_; t < T; t += kNT) L.profile[t] = 0;
     for (int w = t_; w < 2 * lay.bit_words + lay.mask_words; w += kNT) L.occ1[w] = 0;   // occ1, occ2, involved
     if (t_ < 4) counts[t_] = t_ == 2 ? 0x7FFFFFFF : 0;
@@ -571,19 +591,17 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
     __syncthreads();
     // whole waves, 64 consecutive copies each: a ballot gives the active flags of the 64
     int viol = 0, nlive = 0;
-    for (int k0 = wave_ * kWave; k0 < T; k0 += kNT) {
+    auto stage = [&](int k0, int s, int e, uint32_t flag, int sz) {
       const int k = k0 + lane_;
       bool act = false;
       if (k < T) {
-        const int s = starts[row + k], e = ends[row + k];
-        act = active[row + k] != 0;
+        act = flag != 0;
         const bool live = act && (uint32_t)s <= (uint32_t)e && (uint32_t)e < (uint32_t)T;
         const int v = C == 1 ? k : (int)__umulhi((uint32_t)k, c_magic);
         L.packed[k] = pack_copy(live, s, e);
         if (k == v * C && !act) ++viol;   // Eq. (7)
         if (live) {
           ++nlive;
-          const int sz = A.size_of(v);
           atomicAdd(&L.profile[s], sz);
           if (e + 1 < T) atomicSub(&L.profile[e + 1], sz);
           const uint32_t bit = 1u << (s & 31);
@@ -597,6 +615,15 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
         L.amask[(k0 >> 5) + 1] = (uint32_t)(am >> 32);
         atomicAdd(&counts[1], __popcll(am));
       }
+    };
+#pragma unroll
+    for (int j = 0; j < kAhead; ++j) {
+      const int k0 = wave_ * kWave + j * kNT;
+      if (k0 < T) stage(k0, ahead_s[j], ahead_e[j], ahead_a[j], ahead_sz[j]);
+    }
+    for (int k0 = wave_ * kWave + kAhead * kNT; k0 < T; k0 += kNT) {
+      const int k = min(k0 + lane_, T - 1);
+      stage(k0, starts[row + k], ends[row + k], active[row + k], A.size_of(C == 1 ? k : (int)__umulhi((uint32_t)k, c_magic)));
     }
     __syncthreads();
     // the active copies in order: those of 64 copies go behind those of the copies before
@@ -780,9 +807,9 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
     }
     // ---- best move of the candidate
     if (out_best) {
-      int own = tid;   // the lane's index, formed here: nothing of it is kept in a register across the scoring
-      asm volatile("" : "+v"(own));
-      own = (own & (kWave - 1)) << 2;
+      // the lane's index, counted here from a full mask: nothing of it is kept in a register
+      // across the scoring, and the thread index need not be fetched back behind the table's stores
+      const int own = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u)) << 2;
 #pragma unroll
       for (int off = kWave / 2; off > 0; off >>= 1) {
         Best o;   // of lane ^ off
@@ -792,13 +819,13 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
         o.move = __builtin_amdgcn_ds_bpermute(from, best.move);
         if (better(o, best)) best = o;
       }
-      if (lane == 0) {
-        L.scratch[wave * 4 + 0] = best.viol;
-        L.scratch[wave * 4 + 1] = best.peak;
-        L.scratch[wave * 4 + 2] = best.move;
+      if (own == 0) {
+        L.scratch[wave_ * 4 + 0] = best.viol;
+        L.scratch[wave_ * 4 + 1] = best.peak;
+        L.scratch[wave_ * 4 + 2] = best.move;
       }
       __syncthreads();
-      if (tid == 0) {
+      if (own == 0 && wave_ == 0) {
         Best all{0, 0, -1};
         for (int w = 0; w < kNW; ++w) {
           const Best o{L.scratch[w * 4], L.scratch[w * 4 + 1], L.scratch[w * 4 + 2]};
