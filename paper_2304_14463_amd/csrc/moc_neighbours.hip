@@ -1278,31 +1278,55 @@ __global__ __launch_bounds__(kNT) void toggles_kernel(GraphView g, int64_t B, co
 
   for (int64_t b = blockIdx.x; b < B; b += gridDim.x) {
     const int64_t row = b * T;
-    // ---- the base: copies, deltas, starts
+    // ---- the base: copies, deltas, starts.  The first kAhead * kNT copies are asked for before
+    // the arrays are cleared, all at once and without conditions (as in the kernel above).
+    constexpr int kAhead = 4;
+    int ahead_s[kAhead], ahead_e[kAhead];
+    uint32_t ahead_a[kAhead];
+    int2 ahead_sd[kAhead];
+    {
+      const char* const s_row = reinterpret_cast<const char*>(starts + row);
+      const char* const e_row = reinterpret_cast<const char*>(ends + row);
+      const char* const a_row = reinterpret_cast<const char*>(active + row);
+#pragma unroll
+      for (int j = 0; j < kAhead; ++j) {
+        const uint32_t k = (uint32_t)min(j * kNT + tid, T - 1);
+        ahead_s[j] = *reinterpret_cast<const int32_t*>(s_row + 4u * k);
+        ahead_e[j] = *reinterpret_cast<const int32_t*>(e_row + 4u * k);
+        ahead_a[j] = *reinterpret_cast<const uint8_t*>(a_row + k);
+        ahead_sd[j] = g.size_dur[k / (uint32_t)C];
+      }
+    }
     for (int t = tid; t < T; t += kNT) L.profile[t] = 0;
     for (int w = tid; w < 2 * lay.bit_words; w += kNT) L.occ1[w] = 0;
     if (tid < 2) counts[tid] = 0;
     if (tid == 0) { L.pmax[-1] = 0; L.smax[T] = 0; }
     __syncthreads();
     int viol = 0, nlive = 0, dur = 0;
-    for (int k = tid; k < T; k += kNT) {
-      const int s = starts[row + k], e = ends[row + k];
-      const bool act = active[row + k] != 0;
+    auto stage = [&](int k, int s, int e, uint32_t flag, int2 sd) {
+      const bool act = flag != 0;
       const bool live = act && (uint32_t)s <= (uint32_t)e && (uint32_t)e < (uint32_t)T;
       const int v = k / C;
       L.packed[k] = pack_copy(live, s, e);
       if (k == v * C && !act) ++viol;   // Eq. (7)
-      if (act) dur += g.size_dur[v].y;  // Eq. (1)
+      if (act) dur += sd.y;             // Eq. (1)
       if (live) {
         ++nlive;
-        const int sz = A.size_of(v);
+        const int sz = sd.x;
         atomicAdd(&L.profile[s], sz);
         if (e + 1 < T) atomicSub(&L.profile[e + 1], sz);
         const uint32_t bit = 1u << (s & 31);
         const uint32_t old = atomicOr(&L.occ1[s >> 5], bit);
         if (old & bit) atomicOr(&L.occ2[s >> 5], bit);
       }
+    };
+#pragma unroll
+    for (int j = 0; j < kAhead; ++j) {
+      const int k = j * kNT + tid;
+      if (k < T) stage(k, ahead_s[j], ahead_e[j], ahead_a[j], ahead_sd[j]);
     }
+    for (int k = kAhead * kNT + tid; k < T; k += kNT)
+      stage(k, starts[row + k], ends[row + k], active[row + k], g.size_dur[k / C]);
     __syncthreads();
     block_scan<AddOp, false>(L.profile, L.profile, T, L.scratch, tid);   // Eq. (4) per position
     block_max_both_ways(L.profile, L.pmax, L.smax, T, L.scratch, tid);
