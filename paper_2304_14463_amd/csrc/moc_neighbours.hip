@@ -1288,9 +1288,11 @@ __global__ __launch_bounds__(kNT) void toggles_kernel(GraphView g, int64_t B, co
       const char* const s_row = reinterpret_cast<const char*>(starts + row);
       const char* const e_row = reinterpret_cast<const char*>(ends + row);
       const char* const a_row = reinterpret_cast<const char*>(active + row);
+      int t = tid;   // offsets formed here for every base, not kept in registers across the bases
+      asm volatile("" : "+v"(t));
 #pragma unroll
       for (int j = 0; j < kAhead; ++j) {
-        const uint32_t k = (uint32_t)min(j * kNT + tid, T - 1);
+        const uint32_t k = (uint32_t)min(j * kNT + t, T - 1);
         ahead_s[j] = *reinterpret_cast<const int32_t*>(s_row + 4u * k);
         ahead_e[j] = *reinterpret_cast<const int32_t*>(e_row + 4u * k);
         ahead_a[j] = *reinterpret_cast<const uint8_t*>(a_row + k);
