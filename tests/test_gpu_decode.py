@@ -113,6 +113,33 @@ def test_decode_small_graphs(moc, n, C):
     gh.free()
 
 
+@pytest.mark.parametrize("n,C", [(70, 1), (70, 2), (70, 3), (70, 4), (2500, 2)])
+def test_decode_rows_at_odd_addresses(moc, n, C):
+    """The kernel reads the copies of a node in one load each for starts and flags: the arrays
+    may begin at any int32 boundary (starts) and at any byte (flags)."""
+    import torch
+    from paper_2304_14463_amd.inputs import graph_from_edges
+    rng = np.random.default_rng(977 * n + C)
+    edges = set()
+    for v in range(1, n):
+        for u in rng.integers(max(0, v - 9), v, size=rng.integers(0, 3)):
+            edges.add((int(u), v))
+    g = graph_from_edges(n, sorted(edges), rng.integers(0, 50, n), rng.integers(1, 9, n))
+    T, B = n * C, 12
+    s, a = orderly_candidates(rng, g, C, B)
+    gh = moc.moc_graph_upload(n, g.in_ptr, g.in_idx, g.size, g.dur, 1, C)
+    want, want_seq = oracle.decode(g, C, s, a)
+    for shift_s, shift_a in ((1, 1), (3, 2), (2, 3)):
+        pad_s = torch.zeros(B * T + shift_s, dtype=torch.int32, device="cuda")
+        pad_a = torch.zeros(B * T + shift_a, dtype=torch.uint8, device="cuda")
+        pad_s[shift_s:] = torch.from_numpy(s.reshape(-1)).cuda()
+        pad_a[shift_a:] = torch.from_numpy(a.reshape(-1)).cuda()
+        out, seq = moc.moc_decode_batch(gh, pad_s[shift_s:], pad_a[shift_a:])
+        assert_same(moc.results_to_numpy(out, moc.DECODE_RESULT_DTYPE), seq.cpu().numpy(), want, want_seq,
+                    f"n={n} C={C} starts + {shift_s} words, flags + {shift_a} bytes")
+    gh.free()
+
+
 def test_decode_self_loop_and_duplicate_edges(moc):
     from paper_2304_14463_amd.inputs import graph_from_edges
     g = graph_from_edges(4, [(0, 1), (0, 1), (1, 1), (1, 2), (0, 3)], [3, 5, 2, 7], [1, 2, 3, 4])

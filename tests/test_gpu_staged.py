@@ -142,6 +142,14 @@ def test_staged_ragged_shapes_random_values(moc, n, C):
     assert_results_equal(gpu, ref, f"staged n={n} C={C}")
     assert ref[0, F["violations"]] == 0
     assert ref[1, F["v_start"]] == n * (C - 1)
+    # the same rows at odd addresses: the kernel reads a node's copies in one load per array
+    import torch
+    pad_s = torch.zeros(B * K + 1, dtype=torch.int32, device="cuda")
+    pad_e = torch.zeros(B * K + 3, dtype=torch.int32, device="cuda")
+    pad_a = torch.zeros(B * K + 1, dtype=torch.uint8, device="cuda")
+    pad_s[1:], pad_e[3:], pad_a[1:] = ds.reshape(-1), de.reshape(-1), da.reshape(-1)
+    gpu = moc.results_to_numpy(moc.moc_eval_batch_staged(gh, pad_s[1:], pad_e[3:], pad_a[1:]))
+    assert_results_equal(gpu, ref, f"staged n={n} C={C}, arrays at odd addresses")
     gh.free()
 
 
