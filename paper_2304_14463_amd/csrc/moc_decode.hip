@@ -374,7 +374,7 @@ void decode_fixed_kernel(GraphView G, int64_t B, const int32_t* __restrict__ sta
   uint16_t* st = reinterpret_cast<uint16_t*>(b + lay.T_pad);   // [n][SS] start of each copy, kNoStart if not computed
   int32_t* scratch = reinterpret_cast<int32_t*>(st) + lay.st_words;
   int32_t* flag_words = scratch + 2 * kNW;   // two sets of [0] not decodable, [1] not a valid sequence, [2] duration
-  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  const int tid = threadIdx.x;
   const int T = G.T, n = G.n, m = G.m;
 
   for (int x = tid; x < lay.T_pad; x += kNT) a[x] = 0;
@@ -431,20 +431,25 @@ void decode_fixed_kernel(GraphView G, int64_t B, const int32_t* __restrict__ sta
       for (int u = 0; u < kUnroll; ++u) {
         const int v = round + u * kNT + t_;
         if (v >= n) continue;
+        uint32_t where[SS];   // the node's entry of `st`, written in one piece
+#pragma unroll
+        for (int i = 0; i < SS; ++i) where[i] = kNoStart;
 #pragma unroll
         for (int i = 0; i < CT; ++i) {
-          uint32_t sk = kNoStart;
           if (r.on[u][i]) {
             if (r.s[u][i] < 0 || r.s[u][i] >= T) {
               flags[0] = 1;                                        // Eq. (8)
             } else {
-              sk = (uint32_t)r.s[u][i];
+              const uint32_t sk = (uint32_t)r.s[u][i];
+              where[i] = sk;
               if (atomicCAS(&a[sk], 0, v + 1) != 0) flags[0] = 1;  // Eq. (6)
               b[sk] = (int)sk;
             }
           }
-          st[v * SS + i] = (uint16_t)sk;
         }
+        if constexpr (SS == 1) st[v] = (uint16_t)where[0];
+        else if constexpr (SS == 2) *reinterpret_cast<uint32_t*>(st + 2 * v) = where[0] | where[1] << 16;
+        else *reinterpret_cast<uint2*>(st + 4 * v) = make_uint2(where[0] | where[1] << 16, where[2] | where[3] << 16);
       }
     };
     if constexpr (SMALL) {
@@ -533,6 +538,27 @@ void decode_fixed_kernel(GraphView G, int64_t B, const int32_t* __restrict__ sta
         unserved = unserved || (computed && q < 0);
       }
     };
+    // The same for two copies per node on the entries of `st` as they are, both copies of the
+    // consumer at once in 16-bit halves of a register.  As signed 16-bit numbers kNoStart is -1
+    // and every position is far below 2^15 (LDS bounds T), so "the latest start of the producer
+    // before p, or -1" is max over the producer's copies of (s < p ? s : -1) = s | ((p - 1 - s) >> 15),
+    // and a consumer copy that is not computed (p = -1) gets -1 by itself.
+    [[maybe_unused]] uint32_t unserved2 = 0;   // sign bits of the halves: computed and not served
+    [[maybe_unused]] auto serve2 = [&](uint32_t su, uint32_t sv) {
+      typedef short Halves __attribute__((ext_vector_type(2)));
+      const auto halves = [](uint32_t x) { return __builtin_bit_cast(Halves, x); };
+      const auto word = [](Halves x) { return __builtin_bit_cast(uint32_t, x); };
+      const Halves before = halves(sv) - Halves{1, 1};                 // p - 1, per copy of the consumer
+      const uint32_t s0 = __builtin_amdgcn_perm(su, su, 0x01000100u);   // the producer's first start in both halves
+      const uint32_t s1 = __builtin_amdgcn_perm(su, su, 0x03020302u);   // its second
+      const uint32_t c0 = s0 | word((before - halves(s0)) >> 15);
+      const uint32_t c1 = s1 | word((before - halves(s1)) >> 15);
+      const Halves q = __builtin_elementwise_max(halves(c0), halves(c1));
+      unserved2 |= word(q) & ~sv;
+      const int q0 = q.x, q1 = q.y;
+      if (q0 >= 0) atomicMax(&b[q0], (int)(sv & 0xFFFFu));
+      if (q1 >= 0) atomicMax(&b[q1], (int)(sv >> 16));
+    };
     for (int round = 0; round < m; round += kUnroll * kNT) {
       const int base = round + t_;
       uint32_t pair[kUnroll];
@@ -542,10 +568,12 @@ void decode_fixed_kernel(GraphView G, int64_t B, const int32_t* __restrict__ sta
         pair[u] = base + u * kNT < m ? got : (uint32_t)T << 16;   // beyond the list: an edge into node n
       }
 #pragma unroll
-      for (int u = 0; u < kUnroll; ++u)
-        serve(read_starts<CT>(st, (int)(pair[u] & 0xFFFFu) / CT), read_starts<CT>(st, (int)(pair[u] >> 16) / CT));
+      for (int u = 0; u < kUnroll; ++u) {
+        if constexpr (CT == 2) serve2(*reinterpret_cast<const uint32_t*>(st + (pair[u] & 0xFFFFu)), *reinterpret_cast<const uint32_t*>(st + (pair[u] >> 16)));
+        else serve(read_starts<CT>(st, (int)(pair[u] & 0xFFFFu) / CT), read_starts<CT>(st, (int)(pair[u] >> 16) / CT));
+      }
     }
-    if (unserved) flags[1] = 1;
+    if (unserved || (unserved2 & 0x80008000u)) flags[1] = 1;
     if constexpr (SMALL) request(after, 0, t_, ahead);
     __syncthreads();
 

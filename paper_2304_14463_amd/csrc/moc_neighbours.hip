@@ -530,7 +530,6 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
   L.amask = L.involved + lay.mask_words;
   L.scratch = reinterpret_cast<int32_t*>(L.amask + lay.mask_words);
   const int tid = threadIdx.x, lane = tid & (kWave - 1);
-  const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
   const int T = g.T, C = CT ? CT : g.C;
   const uint32_t c_magic = 0xFFFFFFFFu / (uint32_t)C + 1u;   // k / C = umulhi(k, c_magic) for C > 1, k < 2^16
   const int two_r = 2 * R, four_r = 4 * R;
