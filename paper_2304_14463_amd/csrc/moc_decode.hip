@@ -280,11 +280,12 @@ void decode_kernel(GraphView G, int64_t B, const int32_t* __restrict__ starts, c
 }
 
 
-// ---- the same for C <= 4, with fewer passes (six barriers per candidate instead of twelve).
+// ---- the same for C <= 4, with fewer passes (five barriers per candidate instead of twelve).
 // The copies of a node are adjacent, so a node's starts are one or two LDS words; the position
 // array holds the node computed at each position (v + 1) instead of a flag, so that the pass
 // that ranks the occupied positions can write the sequence out itself, in order, and clear the
 // array on its way; the running-sum scan at the end clears the difference array as it reads it.
+
 // The copies of a node as they lie in a candidate's row: aligned as their elements are, no more
 // (the global loads of this chip take several words at any word boundary).
 template <int CT>
@@ -416,7 +417,7 @@ void decode_fixed_kernel(GraphView G, int64_t B, const int32_t* __restrict__ sta
   int turn = 0;
   for (int64_t cand = blockIdx.x; cand < B; cand += gridDim.x, turn ^= 1) {
     // What derives from the thread index (row bounds, LDS addresses) is formed again for every
-    // candidate: kept across candidates it takes registers that the lane's edges need.
+    // candidate: kept across candidates it takes registers that the next candidate's copies need.
     int t_ = tid;
     asm volatile("" : "+v"(t_));
     const int lane_ = t_ & (kWave - 1);
