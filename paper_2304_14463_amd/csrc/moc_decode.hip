@@ -427,7 +427,11 @@ void decode_fixed_kernel(GraphView G, int64_t B, const int32_t* __restrict__ sta
     const int64_t after = cand + gridDim.x < B ? cand + gridDim.x : cand;   // SMALL: whose loads go out next (the last candidate asks for itself again)
 
     // ---- who is computed where; every computation serves at least its own step
+    // What makes the candidate undecodable is collected and reported once per round: the
+    // compare-and-swaps of a round are all under way before the first answer is looked at.
     auto place = [&](int round, const Round& r) {
+      uint32_t taken = 0;    // != 0: a position was taken already, Eq. (6)
+      bool outside = false;  // a start outside [0, T), Eq. (8)
 #pragma unroll
       for (int u = 0; u < kUnroll; ++u) {
         const int v = round + u * kNT + t_;
@@ -439,11 +443,11 @@ void decode_fixed_kernel(GraphView G, int64_t B, const int32_t* __restrict__ sta
         for (int i = 0; i < CT; ++i) {
           if (r.on[u][i]) {
             if (r.s[u][i] < 0 || r.s[u][i] >= T) {
-              flags[0] = 1;                                        // Eq. (8)
+              outside = true;
             } else {
               const uint32_t sk = (uint32_t)r.s[u][i];
               where[i] = sk;
-              if (atomicCAS(&a[sk], 0, v + 1) != 0) flags[0] = 1;  // Eq. (6)
+              taken |= (uint32_t)atomicCAS(&a[sk], 0, v + 1);   // the node there before, + 1
               b[sk] = (int)sk;
             }
           }
@@ -452,6 +456,7 @@ void decode_fixed_kernel(GraphView G, int64_t B, const int32_t* __restrict__ sta
         else if constexpr (SS == 2) *reinterpret_cast<uint32_t*>(st + 2 * v) = where[0] | where[1] << 16;
         else *reinterpret_cast<uint2*>(st + 4 * v) = make_uint2(where[0] | where[1] << 16, where[2] | where[3] << 16);
       }
+      if (outside || taken != 0) flags[0] = 1;
     };
     if constexpr (SMALL) {
       place(0, ahead);
