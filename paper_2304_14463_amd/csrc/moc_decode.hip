@@ -163,13 +163,15 @@ void decode_kernel(GraphView G, int64_t B, const int32_t* __restrict__ starts, c
     // scatter by start: a[x] = 1 where a computation happens
     for (int round = 0; round < T; round += kUnroll * kNT) {
       const int base = round + tid;
-      uint32_t on[kUnroll];   // a register each: bytes packed into one register would be loaded one behind the other
+      // loads without conditions (lanes past the last copy read it again), a register per flag:
+      // under a condition, or packed into one register, each load waits for the one before
+      uint32_t on[kUnroll];
       int32_t s[kUnroll];
 #pragma unroll
       for (int u = 0; u < kUnroll; ++u) {
-        const int k = base + u * kNT;
-        on[u] = k < T ? a_row[k] : (uint8_t)0;
-        s[u] = k < T ? s_row[k] : 0;
+        const int k = min(base + u * kNT, T - 1);
+        on[u] = a_row[k];
+        s[u] = s_row[k];
       }
 #pragma unroll
       for (int u = 0; u < kUnroll; ++u) {

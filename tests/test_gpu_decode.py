@@ -83,7 +83,7 @@ def orderly_candidates(rng, g, C, B):
 
 
 @pytest.mark.parametrize("n,C", [(1, 1), (2, 2), (5, 1), (9, 2), (17, 3), (40, 2), (64, 4), (130, 2), (257, 3),
-                                 (600, 1), (1100, 2)])
+                                 (600, 1), (1100, 2), (3, 5), (33, 5), (150, 6), (700, 5)])
 def test_decode_small_graphs(moc, n, C):
     from paper_2304_14463_amd.inputs import graph_from_edges
     rng = np.random.default_rng(31 * n + C)
@@ -113,7 +113,7 @@ def test_decode_small_graphs(moc, n, C):
     gh.free()
 
 
-@pytest.mark.parametrize("n,C", [(70, 1), (70, 2), (70, 3), (70, 4), (2500, 2)])
+@pytest.mark.parametrize("n,C", [(70, 1), (70, 2), (70, 3), (70, 4), (2500, 2), (70, 5)])
 def test_decode_rows_at_odd_addresses(moc, n, C):
     """The kernel reads the copies of a node in one load each for starts and flags: the arrays
     may begin at any int32 boundary (starts) and at any byte (flags)."""
