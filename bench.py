@@ -27,8 +27,8 @@ HBM_PEAK_GBS = 8000.0
 # HBM traffic of the evaluation kernel on the default workload, from rocprofv3 counter runs
 # (profiles/eval_batch_kernel_n5000_C3_B262144.md): KiB per dispatch and the factors that the same
 # counters need to reproduce a 1 GiB device copy.  Valid for the kernel sources they were taken with.
-TRAFFIC = {"workload": 4, "B": 262144, "fetch_kib": 17328133.0, "fetch_scale": 2.0, "write_kib": 20496.5,
-           "write_scale": 1.0, "sources_sha256": "abc0f57a0be90d7bfb0390237408df7ec1001d9490338ab1619a52aaecb1780d"}
+TRAFFIC = {"workload": 4, "B": 262144, "fetch_kib": 17327257.7, "fetch_scale": 2.0, "write_kib": 20496.5,
+           "write_scale": 1.0, "sources_sha256": "9a6d2d0cddaeda5267f32f0e1a805490aebad3e0c100055868d8f89440dd056c"}
 KERNEL_SOURCES = ("csrc/moc_eval.hip", "csrc/moc_internal.h", "build.py")   # the kernel and how it is compiled
 
 
